@@ -1,0 +1,148 @@
+/*
+ * xg2mask -- token-mask cache for grammar-constrained decoding on AMD MI355X (gfx950).
+ *
+ * C ABI of the library (libxg2mask.so).  The calls follow the statement of the problem in
+ * XGrammar-2 (arXiv 2601.04426):
+ *
+ *   compile_grammar(ebnf, vocab) -> mask_cache          section 3.4 (Earley-based adaptive token
+ *                                                       mask cache), section 3.3 (cross-grammar cache)
+ *   fill_next_token_bitmask(matchers[B], bitmask[B, ceil(V/32)])
+ *                                                       section 3.4 last paragraph and the appendix
+ *                                                       "XGrammar's Adaptive Token Mask cache
+ *                                                       Generation Algorithm" (runtime combination)
+ *   apply_token_bitmask(logits[B, V], bitmask)          section 2.1 (invalid tokens get -infinity)
+ *
+ * Conventions
+ *   - Every call returns an int32 status: XG2_OK or a negative XG2_E* code; the text of the last
+ *     error of the calling thread is returned by xg2_last_error().
+ *   - "host" pointers are ordinary CPU memory, "device" pointers are HIP device memory of the
+ *     current device.  The library never frees or keeps a caller's device buffer.
+ *   - Handles are created and destroyed by the library.  A mask cache keeps its vocabulary and
+ *     grammar alive; a matcher keeps its grammar (and cache) alive.
+ *   - Bit v%32 (least significant bit = 0) of int32 word v/32 stands for token v; 1 = allowed;
+ *     bits at or beyond V in the last word are 0.
+ *   - Device work is enqueued on the HIP stream given by the caller (a hipStream_t passed as
+ *     void*, NULL = the default stream).  xg2_compile_grammar returns after its kernels have
+ *     finished; fill and apply return as soon as their work is enqueued.
+ *   - There is no CPU fallback: without a usable HIP device every call that needs one fails
+ *     with XG2_EHIP.
+ */
+#ifndef XG2MASK_H
+#define XG2MASK_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define XG2_OK          0
+#define XG2_EINVAL     (-1)   /* bad argument, ill-formed vocabulary, unproductive grammar, ...   */
+#define XG2_EPARSE     (-2)   /* EBNF syntax error (line number in xg2_last_error())              */
+#define XG2_EREJECTED  (-3)   /* accept_token: token not allowed here; matcher state unchanged    */
+#define XG2_EOVERFLOW  (-4)   /* an internal capacity was exceeded; nothing partial is returned   */
+#define XG2_EHIP       (-5)   /* HIP runtime error or no device                                   */
+
+typedef struct xg2_vocab xg2_vocab;
+typedef struct xg2_grammar xg2_grammar;
+typedef struct xg2_pool xg2_pool;
+typedef struct xg2_mask_cache xg2_mask_cache;
+typedef struct xg2_matcher xg2_matcher;
+
+/* Counters filled by xg2_compile_grammar. */
+typedef struct xg2_compile_stats {
+    int64_t positions;        /* scannable (rule, state) positions of the grammar                 */
+    int64_t unique;           /* distinct positions after structural dedupe inside the grammar    */
+    int64_t built;            /* positions whose planes were computed by this call (pool misses)  */
+    int64_t checks;           /* built * (number of checkable tokens): logical (position, token)  */
+    int64_t executed_checks;  /* (position, token) pairs a lane actually stepped through          */
+    int64_t slow_path;        /* pairs finished by the large-capacity kernel                      */
+    int64_t n_accepted;       /* set bits over the built accepted planes                          */
+    int64_t n_uncertain;      /* set bits over the built uncertain planes                         */
+    double  host_lower_ms;    /* EBNF -> tables on the host                                       */
+    double  device_ms;        /* first table upload -> last plane written (HIP events)            */
+} xg2_compile_stats;
+
+const char* xg2_last_error(void);
+
+/* ---- vocabulary -------------------------------------------------------------------------------
+ * bytes/offsets: host CSR in token-id order, token i = bytes[offsets[i] .. offsets[i+1]).  The
+ * library copies it, sorts the tokens by bytes and (at first use on a device) lays the sorted
+ * CSR out in device memory.  eos_id is the end-of-sequence token; special_ids (host, may be
+ * NULL) are never allowed by a mask, and neither are zero-length tokens.                        */
+int32_t xg2_vocab_create(const uint8_t* bytes, const uint64_t* offsets, int32_t V, int32_t eos_id,
+                         const int32_t* special_ids, int32_t n_special, xg2_vocab** out);
+void    xg2_vocab_destroy(xg2_vocab*);
+
+/* ---- grammar (host only; no device needed) ----------------------------------------------------
+ * Lowers EBNF text (section 2.1; TagDispatch of section 3.2; repetition X{m,n} of section 3.6)
+ * to one canonical minimal byte-level automaton per rule (section 3.3) and hashes the rules
+ * (Algorithm 1; Algorithm 2 for simple reference cycles).  ebnf need not be NUL-terminated.     */
+int32_t xg2_grammar_create(const char* ebnf, size_t len, const char* root_rule, xg2_grammar** out);
+void    xg2_grammar_destroy(xg2_grammar*);
+/* JSON description of the lowered automata (rules, states, byte ranges, rule edges, hashes,
+ * positions).  Writes at most cap bytes incl. the NUL; *needed receives the full size.          */
+int32_t xg2_grammar_describe(const xg2_grammar*, char* buf, size_t cap, size_t* needed);
+int32_t xg2_grammar_num_positions(const xg2_grammar*, int32_t* out);
+
+/* ---- cross-grammar pool (section 3.3) ---------------------------------------------------------
+ * Planes of structurally identical rule positions are built once and shared by every grammar
+ * compiled with the same pool and vocabulary.  max_bytes bounds the device memory of the pool
+ * (0 = unbounded); when it would be exceeded compile fails with XG2_EOVERFLOW.                  */
+int32_t xg2_pool_create(size_t max_bytes, xg2_pool** out);
+void    xg2_pool_destroy(xg2_pool*);
+int32_t xg2_pool_stats(const xg2_pool*, int64_t* n_positions, int64_t* device_bytes);
+
+/* ---- compile_grammar(ebnf, vocab) -> mask_cache ------------------------------------------------
+ * Builds, on the device, the accepted and uncertain bit planes [W = ceil(V/32) int32 words each]
+ * of every scannable position of the grammar that the pool (nullable) does not hold yet.
+ * stats may be NULL.                                                                            */
+int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, const char* root_rule,
+                            xg2_pool* pool, void* hip_stream, xg2_mask_cache** out,
+                            xg2_compile_stats* stats);
+void    xg2_mask_cache_destroy(xg2_mask_cache*);
+int32_t xg2_mask_cache_num_positions(const xg2_mask_cache*, int32_t* out);
+/* Rule name (pointer valid while the cache lives) and canonical state of position p.            */
+int32_t xg2_mask_cache_position(const xg2_mask_cache*, int32_t p, const char** rule_name, int32_t* state);
+/* Copies the planes of position p to host arrays of W int32 words each (synchronises).          */
+int32_t xg2_mask_cache_get_planes(const xg2_mask_cache*, int32_t p, int32_t* accepted_host, int32_t* uncertain_host);
+
+/* ---- matchers (one per sequence) ---------------------------------------------------------------
+ * A matcher follows the output with an Earley parser (section 3.4, appendix on Earley parsing).
+ * xg2_matcher_create_host makes a matcher that can accept tokens and report its frontier but
+ * cannot be passed to fill (no cache).                                                          */
+int32_t xg2_matcher_create(const xg2_mask_cache*, xg2_matcher** out);
+int32_t xg2_matcher_create_host(const xg2_grammar*, const xg2_vocab*, xg2_matcher** out);
+void    xg2_matcher_destroy(xg2_matcher*);
+int32_t xg2_matcher_accept_token(xg2_matcher*, int32_t token_id);
+int32_t xg2_matcher_reset(xg2_matcher*);
+int32_t xg2_matcher_is_terminated(const xg2_matcher*, int32_t* out);
+/* Position indices of the scannable items of the current closed Earley set (at most cap are
+ * written, *n receives the count) and whether the root rule can end here.                       */
+int32_t xg2_matcher_frontier(const xg2_matcher*, int32_t* positions_host, int32_t cap, int32_t* n,
+                             int32_t* can_end);
+
+/* ---- fill_next_token_bitmask(matchers[B], bitmask[B, ceil(V/32)] int32) ------------------------
+ * For every matcher b: bitmask[b] = union of the accepted planes of its frontier, plus every
+ * token that is uncertain somewhere in the frontier and passes a re-check against the matcher's
+ * full Earley context, plus the end-of-sequence bit if the root rule can end.  A terminated
+ * matcher gets a row allowing only end-of-sequence.  matchers: host array of B handles that
+ * share one vocabulary (their caches may differ).  bitmask_dev: device, B rows of
+ * row_stride_words int32 (row_stride_words >= W).                                               */
+int32_t xg2_fill_next_token_bitmask(xg2_matcher* const* matchers, int32_t B, int32_t* bitmask_dev,
+                                    int64_t row_stride_words, void* hip_stream);
+
+/* ---- apply_token_bitmask(logits[B, V], bitmask) -------------------------------------------------
+ * In place: logits[b, v] = -infinity where bit v of bitmask row b is 0; other elements keep
+ * their bit pattern.  dtype: XG2_F32 or XG2_BF16.  logits_dev: device, B rows of
+ * row_stride_elems elements.  bitmask_dev: device, B rows of bm_row_stride_words int32.         */
+#define XG2_F32  0
+#define XG2_BF16 1
+int32_t xg2_apply_token_bitmask(void* logits_dev, int32_t dtype, int32_t B, int32_t V, int64_t row_stride_elems,
+                                const int32_t* bitmask_dev, int64_t bm_row_stride_words, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* XG2MASK_H */

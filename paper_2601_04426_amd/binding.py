@@ -1,0 +1,239 @@
+"""Thin ctypes binding over libxg2mask.so: argument marshalling only.
+
+Same names as the C ABI (include/xg2mask.h).  Device buffers are passed as integers
+(`tensor.data_ptr()`), streams as `torch.cuda.current_stream().cuda_stream`.  Nothing here
+computes a mask; if the library is missing the import fails loudly.
+"""
+from __future__ import annotations
+
+import ctypes
+import json
+import os
+from typing import List, Optional, Sequence, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libxg2mask.so")
+
+XG2_OK, XG2_EINVAL, XG2_EPARSE, XG2_EREJECTED, XG2_EOVERFLOW, XG2_EHIP = 0, -1, -2, -3, -4, -5
+XG2_F32, XG2_BF16 = 0, 1
+
+EXPORTS = [
+    "xg2_last_error", "xg2_vocab_create", "xg2_vocab_destroy", "xg2_grammar_create", "xg2_grammar_destroy",
+    "xg2_grammar_describe", "xg2_grammar_num_positions", "xg2_pool_create", "xg2_pool_destroy", "xg2_pool_stats",
+    "xg2_compile_grammar", "xg2_mask_cache_destroy", "xg2_mask_cache_num_positions", "xg2_mask_cache_position",
+    "xg2_mask_cache_get_planes", "xg2_matcher_create", "xg2_matcher_create_host", "xg2_matcher_destroy",
+    "xg2_matcher_accept_token", "xg2_matcher_reset", "xg2_matcher_is_terminated", "xg2_matcher_frontier",
+    "xg2_fill_next_token_bitmask", "xg2_apply_token_bitmask",
+]
+
+
+class Xg2Error(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"xg2 error {code}: {msg}")
+        self.code = code
+
+
+class CompileStats(ctypes.Structure):
+    _fields_ = [("positions", ctypes.c_int64), ("unique", ctypes.c_int64), ("built", ctypes.c_int64),
+                ("checks", ctypes.c_int64), ("executed_checks", ctypes.c_int64), ("slow_path", ctypes.c_int64),
+                ("n_accepted", ctypes.c_int64), ("n_uncertain", ctypes.c_int64),
+                ("host_lower_ms", ctypes.c_double), ("device_ms", ctypes.c_double)]
+
+    def as_dict(self):
+        return {k: getattr(self, k) for k, _ in self._fields_}
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2601_04426_amd.build` "
+                          "(there is no fallback implementation)")
+    L = ctypes.CDLL(LIB_PATH)
+    vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
+    pvp = ctypes.POINTER(ctypes.c_void_p)
+    L.xg2_last_error.restype = ctypes.c_char_p
+    L.xg2_vocab_create.argtypes = [vp, vp, i32, i32, vp, i32, pvp]
+    L.xg2_vocab_destroy.argtypes = [vp]
+    L.xg2_grammar_create.argtypes = [ctypes.c_char_p, sz, ctypes.c_char_p, pvp]
+    L.xg2_grammar_destroy.argtypes = [vp]
+    L.xg2_grammar_describe.argtypes = [vp, ctypes.c_char_p, sz, ctypes.POINTER(sz)]
+    L.xg2_grammar_num_positions.argtypes = [vp, ctypes.POINTER(i32)]
+    L.xg2_pool_create.argtypes = [sz, pvp]
+    L.xg2_pool_destroy.argtypes = [vp]
+    L.xg2_pool_stats.argtypes = [vp, ctypes.POINTER(i64), ctypes.POINTER(i64)]
+    L.xg2_compile_grammar.argtypes = [vp, ctypes.c_char_p, sz, ctypes.c_char_p, vp, vp, pvp, ctypes.POINTER(CompileStats)]
+    L.xg2_mask_cache_destroy.argtypes = [vp]
+    L.xg2_mask_cache_num_positions.argtypes = [vp, ctypes.POINTER(i32)]
+    L.xg2_mask_cache_position.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(i32)]
+    L.xg2_mask_cache_get_planes.argtypes = [vp, i32, vp, vp]
+    L.xg2_matcher_create.argtypes = [vp, pvp]
+    L.xg2_matcher_create_host.argtypes = [vp, vp, pvp]
+    L.xg2_matcher_destroy.argtypes = [vp]
+    L.xg2_matcher_accept_token.argtypes = [vp, i32]
+    L.xg2_matcher_reset.argtypes = [vp]
+    L.xg2_matcher_is_terminated.argtypes = [vp, ctypes.POINTER(i32)]
+    L.xg2_matcher_frontier.argtypes = [vp, vp, i32, ctypes.POINTER(i32), ctypes.POINTER(i32)]
+    L.xg2_fill_next_token_bitmask.argtypes = [vp, i32, vp, i64, vp]
+    L.xg2_apply_token_bitmask.argtypes = [vp, i32, i32, i32, i64, vp, i64, vp]
+    for name in EXPORTS:
+        if name not in ("xg2_last_error",) and not name.endswith("_destroy"):
+            getattr(L, name).restype = i32
+    return L
+
+
+lib = _load()
+
+
+def _check(code: int) -> None:
+    if code != XG2_OK:
+        raise Xg2Error(code, lib.xg2_last_error().decode("utf-8", "replace"))
+
+
+class Vocab:
+    def __init__(self, tokens: Sequence[bytes], eos_id: int, special_ids: Sequence[int] = ()):
+        blob = b"".join(tokens)
+        offs = np.zeros(len(tokens) + 1, dtype=np.uint64)
+        np.cumsum([len(t) for t in tokens], out=offs[1:])
+        buf = np.frombuffer(blob if blob else b"\0", dtype=np.uint8)
+        sp = np.array(list(special_ids), dtype=np.int32)
+        self.size = len(tokens)
+        self.words = (self.size + 31) // 32
+        self.eos_id = eos_id
+        self.h = ctypes.c_void_p()
+        _check(lib.xg2_vocab_create(buf.ctypes.data, offs.ctypes.data, len(tokens), eos_id,
+                                    sp.ctypes.data if len(sp) else None, len(sp), ctypes.byref(self.h)))
+
+    def __del__(self):
+        if getattr(self, "h", None):
+            lib.xg2_vocab_destroy(self.h)
+            self.h = None
+
+
+class Grammar:
+    """Host-only lowering of an EBNF text (no device needed)."""
+
+    def __init__(self, ebnf: str, root: str = "root"):
+        data = ebnf.encode("utf-8")
+        self.h = ctypes.c_void_p()
+        _check(lib.xg2_grammar_create(data, len(data), root.encode(), ctypes.byref(self.h)))
+
+    def describe(self) -> dict:
+        need = ctypes.c_size_t(0)
+        _check(lib.xg2_grammar_describe(self.h, None, 0, ctypes.byref(need)))
+        buf = ctypes.create_string_buffer(need.value)
+        _check(lib.xg2_grammar_describe(self.h, buf, need.value, ctypes.byref(need)))
+        return json.loads(buf.value.decode("utf-8"))
+
+    def num_positions(self) -> int:
+        n = ctypes.c_int32(0)
+        _check(lib.xg2_grammar_num_positions(self.h, ctypes.byref(n)))
+        return n.value
+
+    def __del__(self):
+        if getattr(self, "h", None):
+            lib.xg2_grammar_destroy(self.h)
+            self.h = None
+
+
+class Pool:
+    def __init__(self, max_bytes: int = 0):
+        self.h = ctypes.c_void_p()
+        _check(lib.xg2_pool_create(max_bytes, ctypes.byref(self.h)))
+
+    def stats(self) -> Tuple[int, int]:
+        n, b = ctypes.c_int64(0), ctypes.c_int64(0)
+        _check(lib.xg2_pool_stats(self.h, ctypes.byref(n), ctypes.byref(b)))
+        return n.value, b.value
+
+    def __del__(self):
+        if getattr(self, "h", None):
+            lib.xg2_pool_destroy(self.h)
+            self.h = None
+
+
+class MaskCache:
+    def __init__(self, h, vocab: Vocab, stats: CompileStats, pool: Optional[Pool]):
+        self.h, self.vocab, self.stats, self.pool = h, vocab, stats, pool
+
+    def num_positions(self) -> int:
+        n = ctypes.c_int32(0)
+        _check(lib.xg2_mask_cache_num_positions(self.h, ctypes.byref(n)))
+        return n.value
+
+    def position(self, p: int) -> Tuple[str, int]:
+        name, st = ctypes.c_char_p(), ctypes.c_int32(0)
+        _check(lib.xg2_mask_cache_position(self.h, p, ctypes.byref(name), ctypes.byref(st)))
+        return name.value.decode(), st.value
+
+    def get_planes(self, p: int) -> Tuple[np.ndarray, np.ndarray]:
+        acc = np.zeros(self.vocab.words, dtype=np.int32)
+        unc = np.zeros(self.vocab.words, dtype=np.int32)
+        _check(lib.xg2_mask_cache_get_planes(self.h, p, acc.ctypes.data, unc.ctypes.data))
+        return acc, unc
+
+    def __del__(self):
+        if getattr(self, "h", None):
+            lib.xg2_mask_cache_destroy(self.h)
+            self.h = None
+
+
+def compile_grammar(vocab: Vocab, ebnf: str, root: str = "root", pool: Optional[Pool] = None, stream: int = 0) -> MaskCache:
+    data = ebnf.encode("utf-8")
+    h = ctypes.c_void_p()
+    stats = CompileStats()
+    _check(lib.xg2_compile_grammar(vocab.h, data, len(data), root.encode(), pool.h if pool else None,
+                                   ctypes.c_void_p(stream), ctypes.byref(h), ctypes.byref(stats)))
+    return MaskCache(h, vocab, stats, pool)
+
+
+class Matcher:
+    def __init__(self, cache: Optional[MaskCache] = None, grammar: Optional[Grammar] = None, vocab: Optional[Vocab] = None):
+        self.h = ctypes.c_void_p()
+        self._keep = (cache, grammar, vocab)
+        if cache is not None:
+            _check(lib.xg2_matcher_create(cache.h, ctypes.byref(self.h)))
+        else:
+            _check(lib.xg2_matcher_create_host(grammar.h, vocab.h, ctypes.byref(self.h)))
+
+    def accept_token(self, token_id: int) -> bool:
+        code = lib.xg2_matcher_accept_token(self.h, token_id)
+        if code == XG2_EREJECTED:
+            return False
+        _check(code)
+        return True
+
+    def reset(self) -> None:
+        _check(lib.xg2_matcher_reset(self.h))
+
+    def is_terminated(self) -> bool:
+        out = ctypes.c_int32(0)
+        _check(lib.xg2_matcher_is_terminated(self.h, ctypes.byref(out)))
+        return bool(out.value)
+
+    def frontier(self) -> Tuple[List[int], bool]:
+        cap = 256
+        while True:
+            buf = np.zeros(cap, dtype=np.int32)
+            n, end = ctypes.c_int32(0), ctypes.c_int32(0)
+            _check(lib.xg2_matcher_frontier(self.h, buf.ctypes.data, cap, ctypes.byref(n), ctypes.byref(end)))
+            if n.value <= cap:
+                return list(buf[:n.value]), bool(end.value)
+            cap = n.value
+
+    def __del__(self):
+        if getattr(self, "h", None):
+            lib.xg2_matcher_destroy(self.h)
+            self.h = None
+
+
+def fill_next_token_bitmask(matchers: Sequence[Matcher], bitmask_ptr: int, row_stride_words: int, stream: int = 0) -> None:
+    arr = (ctypes.c_void_p * len(matchers))(*[m.h for m in matchers])
+    _check(lib.xg2_fill_next_token_bitmask(arr, len(matchers), ctypes.c_void_p(bitmask_ptr), row_stride_words,
+                                           ctypes.c_void_p(stream)))
+
+
+def apply_token_bitmask(logits_ptr: int, dtype: int, B: int, V: int, row_stride_elems: int, bitmask_ptr: int,
+                        bm_row_stride_words: int, stream: int = 0) -> None:
+    _check(lib.xg2_apply_token_bitmask(ctypes.c_void_p(logits_ptr), dtype, B, V, row_stride_elems,
+                                       ctypes.c_void_p(bitmask_ptr), bm_row_stride_words, ctypes.c_void_p(stream)))

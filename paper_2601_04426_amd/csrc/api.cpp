@@ -1,0 +1,708 @@
+// C ABI of libxg2mask.so (see include/xg2mask.h): argument checking, handle lifetime, host-side
+// planning of the cache build and of a fill batch, and the launches.  There is no CPU fallback for any
+// kernel: without a HIP device the device calls fail with XG2_EHIP.
+#include "../../include/xg2mask.h"
+
+#include <algorithm>
+#include <chrono>
+#include <cstring>
+#include <map>
+#include <memory>
+#include <mutex>
+#include <numeric>
+#include <string>
+#include <unordered_map>
+#include <vector>
+
+#include <hip/hip_runtime.h>
+
+#include "device.hpp"
+#include "grammar.hpp"
+#include "tables.hpp"
+
+using namespace xg2;
+
+namespace {
+
+thread_local std::string g_error;
+int32_t fail(int32_t code, const std::string& msg) { g_error = msg; return code; }
+
+struct HipError : std::runtime_error { using std::runtime_error::runtime_error; };
+#define HIP_CHECK(expr)                                                                              \
+    do {                                                                                             \
+        hipError_t e_ = (expr);                                                                      \
+        if (e_ != hipSuccess) throw HipError(std::string(#expr) + ": " + hipGetErrorString(e_));     \
+    } while (0)
+
+template <typename T>
+struct DevBuf {                                    // owning device array
+    T* p = nullptr; size_t n = 0;
+    DevBuf() = default;
+    DevBuf(const DevBuf&) = delete;
+    DevBuf& operator=(const DevBuf&) = delete;
+    ~DevBuf() { if (p) (void)hipFree(p); }
+    void alloc(size_t count) {
+        if (p) { (void)hipFree(p); p = nullptr; }
+        n = count;
+        if (count) HIP_CHECK(hipMalloc((void**)&p, count * sizeof(T)));
+    }
+    void upload(const std::vector<T>& v, hipStream_t s) {
+        alloc(std::max<size_t>(v.size(), 1));
+        if (!v.empty()) HIP_CHECK(hipMemcpyAsync(p, v.data(), v.size() * sizeof(T), hipMemcpyHostToDevice, s));
+    }
+};
+
+void require_device() {
+    int n = 0;
+    hipError_t e = hipGetDeviceCount(&n);
+    if (e != hipSuccess || n <= 0) throw HipError("no HIP device available (the mask cache runs on the GPU only)");
+}
+
+// ---- vocabulary --------------------------------------------------------------------------------------
+struct VocabImpl {
+    int32_t V = 0, eos = 0;
+    uint32_t W = 0;
+    std::vector<uint8_t> bytes;                 // id order
+    std::vector<uint64_t> offs;
+    std::vector<uint8_t> special;               // [V] 1 = never allowed by a plane (special or empty)
+    // byte-sorted layout
+    std::vector<uint32_t> perm, rank, s_off;
+    std::vector<uint8_t> s_bytes;
+    uint32_t fb_start[257];                     // first sorted rank whose first byte is >= b
+    uint32_t n_sorted = 0;
+    // device copy (made at first use)
+    std::mutex mu;
+    bool on_device = false;
+    DevBuf<uint8_t> d_bytes; DevBuf<uint32_t> d_off, d_perm, d_rank;
+    DevVocab dv{};
+
+    const uint8_t* tok(int32_t id) const { return bytes.data() + offs[(size_t)id]; }
+    size_t len(int32_t id) const { return (size_t)(offs[(size_t)id + 1] - offs[(size_t)id]); }
+
+    void ensure_device() {
+        std::lock_guard<std::mutex> lk(mu);
+        if (on_device) return;
+        require_device();
+        std::vector<uint8_t> padded = s_bytes;
+        padded.resize(s_bytes.size() + 16, 0);
+        d_bytes.upload(padded, nullptr);
+        d_off.upload(s_off, nullptr);
+        d_perm.upload(perm, nullptr);
+        d_rank.upload(rank, nullptr);
+        HIP_CHECK(hipStreamSynchronize(nullptr));
+        dv.bytes = d_bytes.p; dv.off = d_off.p; dv.perm = d_perm.p; dv.rank = d_rank.p;
+        dv.n_sorted = n_sorted; dv.V = (uint32_t)V; dv.W = W;
+        on_device = true;
+    }
+};
+
+// ---- lowered grammar ---------------------------------------------------------------------------------
+struct GrammarImpl {
+    Grammar g;
+    FlatTables ft;
+    std::vector<std::string> rule_names;
+};
+
+// ---- large-capacity scratch shared by the slow kernels (one per process; calls are serialised) --------
+struct SlowImpl {
+    std::mutex mu;
+    DevBuf<uint32_t> mem, list, count;
+    SlowScratch s{};
+    bool ready = false;
+    void ensure() {
+        if (ready) return;
+        s.n_lanes = 64 * 64;
+        s.list_cap = 1u << 20;
+        mem.alloc((size_t)s.n_lanes * kSlowSlots);
+        list.alloc((size_t)s.list_cap * 2);
+        count.alloc(2);
+        HIP_CHECK(hipMemset(count.p, 0, 2 * sizeof(uint32_t)));
+        s.mem = mem.p; s.list = list.p; s.count = count.p;
+        ready = true;
+    }
+};
+SlowImpl& slow() { static SlowImpl* s = new SlowImpl(); return *s; }
+
+// ---- cross-grammar pool -------------------------------------------------------------------------------
+struct PoolImpl {
+    size_t max_bytes = 0;
+    std::mutex mu;
+    std::shared_ptr<VocabImpl> vocab;           // bound at first use
+    struct Entry { uint64_t hash; std::string text; std::vector<uint32_t*> rows; };   // rows by canonical state id
+    std::vector<Entry> entries;
+    std::unordered_multimap<uint64_t, int> by_hash;
+    std::vector<void*> slabs;
+    uint8_t* slab_cur = nullptr; size_t slab_left = 0;
+    size_t device_bytes = 0;
+    int64_t n_rows = 0;
+    ~PoolImpl() { for (void* s : slabs) (void)hipFree(s); }
+
+    // exact interning: same hash AND same serialisation
+    int intern(uint64_t hash, const std::string& text, size_t n_states, bool shareable) {
+        if (shareable) {
+            auto range = by_hash.equal_range(hash);
+            for (auto it = range.first; it != range.second; ++it)
+                if (entries[(size_t)it->second].text == text) return it->second;
+        }
+        entries.push_back({hash, shareable ? text : std::string(), std::vector<uint32_t*>(n_states, nullptr)});
+        int id = (int)entries.size() - 1;
+        if (shareable) by_hash.emplace(hash, id);
+        return id;
+    }
+    uint32_t* alloc_row(size_t row_bytes, hipStream_t stream) {
+        if (slab_left < row_bytes) {
+            size_t want = std::max<size_t>(row_bytes * 64, (size_t)64 << 20);
+            if (max_bytes && device_bytes + want > max_bytes) want = row_bytes;
+            if (max_bytes && device_bytes + want > max_bytes) throw std::length_error("cross-grammar pool is full");
+            void* p = nullptr;
+            HIP_CHECK(hipMalloc(&p, want));
+            slabs.push_back(p);
+            HIP_CHECK(hipMemsetAsync(p, 0, want, stream));       // rows are handed out once, so they start as zeros
+            slab_cur = (uint8_t*)p; slab_left = want; device_bytes += want;
+        }
+        uint32_t* row = (uint32_t*)slab_cur;
+        slab_cur += row_bytes; slab_left -= row_bytes;
+        ++n_rows;
+        return row;
+    }
+};
+
+// ---- mask cache -----------------------------------------------------------------------------------------
+struct CacheImpl {
+    std::shared_ptr<VocabImpl> vocab;
+    std::shared_ptr<PoolImpl> pool;
+    std::shared_ptr<GrammarImpl> gram;
+    DevBuf<StateInfo> d_state; DevBuf<ByteEdge> d_bedge; DevBuf<RefEdgeP> d_redge; DevBuf<RuleInfo> d_rule;
+    DevTables dt{};
+    std::vector<uint32_t*> pos_plane;           // [positions] device address of the accepted row
+};
+
+struct MatcherImpl {
+    std::shared_ptr<CacheImpl> cache;           // null for host-only matchers
+    std::shared_ptr<GrammarImpl> gram;
+    std::shared_ptr<VocabImpl> vocab;
+    EarleyChart chart;
+    bool terminated = false;
+    MatcherImpl(std::shared_ptr<GrammarImpl> g, std::shared_ptr<VocabImpl> v) : gram(std::move(g)), vocab(std::move(v)), chart(&gram->ft) {
+        chart.start(gram->ft.root_start);
+    }
+};
+
+// ---- fill workspace: pinned staging ring + device mirror ---------------------------------------------------
+struct FillSlot {
+    uint8_t* host = nullptr; uint8_t* dev = nullptr; size_t cap = 0;
+    hipEvent_t done = nullptr; bool in_flight = false;
+};
+struct FillWorkspace {
+    std::mutex mu;
+    FillSlot slots[4];
+    int next = 0;
+    FillSlot& acquire(size_t bytes) {
+        FillSlot& s = slots[next];
+        next = (next + 1) % 4;
+        if (!s.done) HIP_CHECK(hipEventCreateWithFlags(&s.done, hipEventDisableTiming));
+        if (s.in_flight) { HIP_CHECK(hipEventSynchronize(s.done)); s.in_flight = false; }
+        if (s.cap < bytes) {
+            if (s.host) (void)hipHostFree(s.host);
+            if (s.dev) (void)hipFree(s.dev);
+            s.cap = std::max(bytes * 2, (size_t)1 << 20);
+            HIP_CHECK(hipHostMalloc((void**)&s.host, s.cap, hipHostMallocDefault));
+            HIP_CHECK(hipMalloc((void**)&s.dev, s.cap));
+        }
+        return s;
+    }
+};
+FillWorkspace& fill_ws() { static FillWorkspace* w = new FillWorkspace(); return *w; }
+
+template <typename F>
+int32_t guarded(F&& f) {
+    try { return f(); }
+    catch (const ParseError& e) { return fail(XG2_EPARSE, e.what()); }
+    catch (const GrammarError& e) { return fail(XG2_EINVAL, e.what()); }
+    catch (const HipError& e) { return fail(XG2_EHIP, e.what()); }
+    catch (const std::length_error& e) { return fail(XG2_EOVERFLOW, e.what()); }
+    catch (const std::bad_alloc&) { return fail(XG2_EOVERFLOW, "out of host memory"); }
+    catch (const std::exception& e) { return fail(XG2_EINVAL, e.what()); }
+}
+
+std::shared_ptr<GrammarImpl> make_grammar(const char* ebnf, size_t len, const char* root) {
+    if (!ebnf || !root) throw GrammarError("null grammar text or root rule");
+    auto gi = std::make_shared<GrammarImpl>();
+    gi->g = lower_grammar(std::string(ebnf, len), root);
+    if ((uint32_t)gi->g.n_states > kSidMask) throw std::length_error("grammar has too many automaton states");
+    gi->ft = flatten(gi->g);
+    for (auto& r : gi->g.rules) gi->rule_names.push_back(r.name);
+    return gi;
+}
+
+double ms_since(std::chrono::steady_clock::time_point t0) {
+    return std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
+}
+
+}  // namespace
+
+struct xg2_vocab { std::shared_ptr<VocabImpl> p; };
+struct xg2_grammar { std::shared_ptr<GrammarImpl> p; };
+struct xg2_pool { std::shared_ptr<PoolImpl> p; };
+struct xg2_mask_cache { std::shared_ptr<CacheImpl> p; };
+struct xg2_matcher { std::unique_ptr<MatcherImpl> p; };
+
+extern "C" {
+
+const char* xg2_last_error(void) { return g_error.c_str(); }
+
+int32_t xg2_vocab_create(const uint8_t* bytes, const uint64_t* offsets, int32_t V, int32_t eos_id,
+                         const int32_t* special_ids, int32_t n_special, xg2_vocab** out) {
+    return guarded([&]() -> int32_t {
+        if (!offsets || !out || V <= 0 || eos_id < 0 || eos_id >= V || n_special < 0 || (n_special > 0 && !special_ids))
+            return fail(XG2_EINVAL, "xg2_vocab_create: bad argument");
+        for (int32_t i = 0; i < V; ++i) if (offsets[i + 1] < offsets[i]) return fail(XG2_EINVAL, "xg2_vocab_create: offsets not monotone");
+        if (offsets[V] > offsets[0] && !bytes) return fail(XG2_EINVAL, "xg2_vocab_create: null bytes");
+        if (offsets[V] - offsets[0] > 0xFFFFFFF0ull) return fail(XG2_EOVERFLOW, "xg2_vocab_create: vocabulary bytes exceed 4 GiB");
+        auto v = std::make_shared<VocabImpl>();
+        v->V = V; v->eos = eos_id; v->W = ((uint32_t)V + 31) / 32;
+        v->offs.resize((size_t)V + 1);
+        for (int32_t i = 0; i <= V; ++i) v->offs[(size_t)i] = offsets[i] - offsets[0];
+        v->bytes.assign(bytes + offsets[0], bytes + offsets[V]);
+        v->special.assign((size_t)V, 0);
+        v->special[(size_t)eos_id] = 1;
+        for (int32_t k = 0; k < n_special; ++k) {
+            if (special_ids[k] < 0 || special_ids[k] >= V) return fail(XG2_EINVAL, "xg2_vocab_create: special id out of range");
+            v->special[(size_t)special_ids[k]] = 1;
+        }
+        for (int32_t i = 0; i < V; ++i) if (v->len(i) == 0) v->special[(size_t)i] = 1;
+        for (int32_t i = 0; i < V; ++i) if (!v->special[(size_t)i]) v->perm.push_back((uint32_t)i);
+        std::sort(v->perm.begin(), v->perm.end(), [&](uint32_t a, uint32_t b) {
+            size_t la = v->len((int32_t)a), lb = v->len((int32_t)b);
+            int c = std::memcmp(v->tok((int32_t)a), v->tok((int32_t)b), std::min(la, lb));
+            if (c != 0) return c < 0;
+            if (la != lb) return la < lb;
+            return a < b;
+        });
+        v->n_sorted = (uint32_t)v->perm.size();
+        v->rank.assign((size_t)V, 0xFFFFFFFFu);
+        v->s_off.push_back(0);
+        for (uint32_t r = 0; r < v->n_sorted; ++r) {
+            int32_t id = (int32_t)v->perm[r];
+            v->rank[(size_t)id] = r;
+            v->s_bytes.insert(v->s_bytes.end(), v->tok(id), v->tok(id) + v->len(id));
+            v->s_off.push_back((uint32_t)v->s_bytes.size());
+        }
+        uint32_t r = 0;
+        for (int b = 0; b <= 256; ++b) {
+            while (r < v->n_sorted && (int)v->s_bytes[v->s_off[r]] < b) ++r;
+            v->fb_start[b] = r;
+        }
+        *out = new xg2_vocab{v};
+        return XG2_OK;
+    });
+}
+void xg2_vocab_destroy(xg2_vocab* v) { delete v; }
+
+int32_t xg2_grammar_create(const char* ebnf, size_t len, const char* root_rule, xg2_grammar** out) {
+    return guarded([&]() -> int32_t {
+        if (!out) return fail(XG2_EINVAL, "xg2_grammar_create: null out");
+        *out = new xg2_grammar{make_grammar(ebnf, len, root_rule)};
+        return XG2_OK;
+    });
+}
+void xg2_grammar_destroy(xg2_grammar* g) { delete g; }
+
+int32_t xg2_grammar_describe(const xg2_grammar* g, char* buf, size_t cap, size_t* needed) {
+    return guarded([&]() -> int32_t {
+        if (!g || !needed) return fail(XG2_EINVAL, "xg2_grammar_describe: bad argument");
+        std::string s = describe_grammar(g->p->g);
+        *needed = s.size() + 1;
+        if (buf && cap) { size_t n = std::min(cap - 1, s.size()); std::memcpy(buf, s.data(), n); buf[n] = 0; }
+        return XG2_OK;
+    });
+}
+int32_t xg2_grammar_num_positions(const xg2_grammar* g, int32_t* out) {
+    if (!g || !out) return fail(XG2_EINVAL, "xg2_grammar_num_positions: bad argument");
+    *out = (int32_t)g->p->g.positions.size();
+    return XG2_OK;
+}
+
+int32_t xg2_pool_create(size_t max_bytes, xg2_pool** out) {
+    return guarded([&]() -> int32_t {
+        if (!out) return fail(XG2_EINVAL, "xg2_pool_create: null out");
+        auto p = std::make_shared<PoolImpl>();
+        p->max_bytes = max_bytes;
+        *out = new xg2_pool{p};
+        return XG2_OK;
+    });
+}
+void xg2_pool_destroy(xg2_pool* p) { delete p; }
+int32_t xg2_pool_stats(const xg2_pool* p, int64_t* n_positions, int64_t* device_bytes) {
+    if (!p) return fail(XG2_EINVAL, "xg2_pool_stats: null pool");
+    std::lock_guard<std::mutex> lk(p->p->mu);
+    if (n_positions) *n_positions = p->p->n_rows;
+    if (device_bytes) *device_bytes = (int64_t)p->p->device_bytes;
+    return XG2_OK;
+}
+
+int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, const char* root_rule, xg2_pool* pool_h,
+                            void* hip_stream, xg2_mask_cache** out, xg2_compile_stats* stats) {
+    return guarded([&]() -> int32_t {
+        if (!vocab || !out) return fail(XG2_EINVAL, "xg2_compile_grammar: bad argument");
+        hipStream_t stream = (hipStream_t)hip_stream;
+        auto t0 = std::chrono::steady_clock::now();
+        auto cache = std::make_shared<CacheImpl>();
+        cache->vocab = vocab->p;
+        cache->gram = make_grammar(ebnf, len, root_rule);
+        const Grammar& g = cache->gram->g;
+        const FlatTables& ft = cache->gram->ft;
+        VocabImpl& V = *vocab->p;
+        V.ensure_device();
+        cache->pool = pool_h ? pool_h->p : std::make_shared<PoolImpl>();
+        PoolImpl& pool = *cache->pool;
+        std::lock_guard<std::mutex> pool_lock(pool.mu);
+        if (!pool.vocab) pool.vocab = vocab->p;
+        else if (pool.vocab.get() != vocab->p.get()) return fail(XG2_EINVAL, "xg2_compile_grammar: pool is bound to another vocabulary");
+        std::lock_guard<std::mutex> slow_lock(slow().mu);
+        slow().ensure();
+        const SlowScratch S = slow().s;
+
+        // intern every rule in the pool, referenced rules first
+        std::vector<int> entry(g.rules.size(), -1);
+        std::vector<uint64_t> ref_id(g.rules.size(), 0);
+        for (const auto& comp : g.hash_order) {
+            const RuleFsm& first = g.rules[(size_t)comp[0]];
+            if (!first.shareable) {
+                for (int r : comp) entry[(size_t)r] = pool.intern(g.rules[(size_t)r].hash, "", (size_t)g.rules[(size_t)r].n_states(), false);
+            } else if (first.ring.empty()) {
+                int r = comp[0];
+                entry[(size_t)r] = pool.intern(first.hash, serialise_rule(g, r, ref_id), (size_t)first.n_states(), true);
+            } else {
+                std::vector<uint64_t> ids = ref_id;
+                for (int r : comp) ids[(size_t)r] = kInCycleRef;
+                std::map<int, std::string> local;
+                for (int r : comp) local[r] = serialise_rule(g, r, ids);
+                for (int r : comp) {
+                    std::string text = "C";
+                    for (int v : g.rules[(size_t)r].ring) { text += local[v]; text.push_back('|'); }
+                    entry[(size_t)r] = pool.intern(g.rules[(size_t)r].hash, text, (size_t)g.rules[(size_t)r].n_states(), true);
+                }
+            }
+            for (int r : comp) ref_id[(size_t)r] = (uint64_t)entry[(size_t)r] + 1;
+        }
+
+        // positions -> plane rows; rows that do not exist yet are built now
+        const size_t row_bytes = (size_t)V.W * 2 * sizeof(uint32_t);
+        std::vector<int32_t> build_pos;
+        std::vector<uint32_t*> build_rows;
+        size_t n_unique = 0;
+        {
+            std::map<std::pair<int, int>, int> seen;
+            cache->pos_plane.resize(g.positions.size());
+            for (size_t p = 0; p < g.positions.size(); ++p) {
+                const Position& ps = g.positions[p];
+                int e = entry[(size_t)ps.rule];
+                int c = g.rules[(size_t)ps.rule].canon_id[(size_t)ps.state];
+                if (seen.emplace(std::make_pair(e, c), 1).second) ++n_unique;
+                uint32_t*& row = pool.entries[(size_t)e].rows[(size_t)c];
+                if (!row) {
+                    row = pool.alloc_row(row_bytes, stream);
+                    build_pos.push_back((int32_t)p);
+                    build_rows.push_back(row);
+                }
+                cache->pos_plane[p] = row;
+            }
+        }
+        double host_ms_a = ms_since(t0);
+
+        hipEvent_t ev0, ev1;
+        HIP_CHECK(hipEventCreate(&ev0));
+        HIP_CHECK(hipEventCreate(&ev1));
+        HIP_CHECK(hipEventRecord(ev0, stream));
+        cache->d_state.upload(ft.state_info, stream);
+        cache->d_bedge.upload(ft.byte_edges, stream);
+        cache->d_redge.upload(ft.ref_edges, stream);
+        cache->d_rule.upload(ft.rule_info, stream);
+        cache->dt.state_info = reinterpret_cast<const uint4*>(cache->d_state.p);
+        cache->dt.byte_edges = reinterpret_cast<const uint2*>(cache->d_bedge.p);
+        cache->dt.ref_edges = reinterpret_cast<const uint2*>(cache->d_redge.p);
+        cache->dt.rule_info = reinterpret_cast<const uint2*>(cache->d_rule.p);
+
+        // plan: closed start set and live first-byte ranges of every position to build
+        auto t1 = std::chrono::steady_clock::now();
+        std::vector<uint32_t> seg_pos, seg_lo, seg_hi, seg_blk{0}, ctx_items, ctx_item_off{0}, ctx_wait, ctx_wait_off2;
+        int64_t executed = 0;
+        EarleyChart chart(&ft);
+        for (size_t k = 0; k < build_pos.size(); ++k) {
+            const Position& ps = g.positions[(size_t)build_pos[k]];
+            chart.start((uint32_t)ps.sid);
+            const ChartSet& s0 = chart.last();
+            bool live[257] = {false};
+            for (const ChartItem& it : s0.scan) {
+                ctx_items.push_back(pack_item(it.sid, it.origin < 0 ? kRootOrigin : 0u));
+                const StateInfo& si = ft.state_info[it.sid];
+                for (uint32_t e = 0; e < (si.counts & 0xFFFF); ++e) {
+                    const ByteEdge& be = ft.byte_edges[si.byte_off + e];
+                    for (uint32_t b = be.lohi & 0xFF; b <= ((be.lohi >> 8) & 0xFF); ++b) live[b] = true;
+                }
+            }
+            ctx_item_off.push_back((uint32_t)ctx_items.size());
+            ctx_wait_off2.push_back((uint32_t)ctx_wait.size());
+            for (const ChartItem& it : s0.wait) ctx_wait.push_back(pack_item(it.sid, it.origin < 0 ? kRootOrigin : 0u));
+            ctx_wait_off2.push_back((uint32_t)ctx_wait.size());
+            for (int b = 0; b < 256;) {
+                if (!live[b]) { ++b; continue; }
+                int e = b;
+                while (live[e + 1]) ++e;
+                uint32_t lo = V.fb_start[b], hi = V.fb_start[e + 1];
+                if (hi > lo) {
+                    seg_pos.push_back((uint32_t)k); seg_lo.push_back(lo); seg_hi.push_back(hi);
+                    seg_blk.push_back(seg_blk.back() + (hi - lo + 63) / 64);
+                    executed += hi - lo;
+                }
+                b = e + 1;
+            }
+        }
+        double host_ms_b = ms_since(t1);
+
+        DevBuf<uint32_t> d_seg_pos, d_seg_lo, d_seg_hi, d_seg_blk, d_items, d_item_off, d_wait, d_wait_off2;
+        DevBuf<uint32_t*> d_rows;
+        DevBuf<unsigned long long> d_counts;
+        d_seg_pos.upload(seg_pos, stream); d_seg_lo.upload(seg_lo, stream); d_seg_hi.upload(seg_hi, stream);
+        d_seg_blk.upload(seg_blk, stream); d_items.upload(ctx_items, stream); d_item_off.upload(ctx_item_off, stream);
+        d_wait.upload(ctx_wait, stream); d_wait_off2.upload(ctx_wait_off2, stream);
+        d_rows.upload(build_rows, stream);
+        d_counts.alloc(2);
+        HIP_CHECK(hipMemsetAsync(d_counts.p, 0, 2 * sizeof(unsigned long long), stream));
+        HIP_CHECK(hipMemsetAsync(S.count, 0, sizeof(uint32_t), stream));
+        BuildPlan P{};
+        P.seg_pos = d_seg_pos.p; P.seg_lo = d_seg_lo.p; P.seg_hi = d_seg_hi.p; P.seg_blk = d_seg_blk.p;
+        P.n_seg = (uint32_t)seg_pos.size(); P.n_blocks = seg_blk.back();
+        P.ctx_items = d_items.p; P.ctx_item_off = d_item_off.p; P.ctx_wait = d_wait.p; P.ctx_wait_off2 = d_wait_off2.p;
+        P.plane_ptr = d_rows.p;
+        if (!build_pos.empty()) {
+            launch_build(cache->dt, V.dv, P, S, stream);
+            launch_build_slow(cache->dt, V.dv, P, S, stream);
+            launch_popcount(d_rows.p, (uint32_t)build_rows.size(), V.W, d_counts.p, stream);
+        }
+        HIP_CHECK(hipEventRecord(ev1, stream));
+        uint32_t slow_counts[2] = {0, 0};
+        unsigned long long bit_counts[2] = {0, 0};
+        HIP_CHECK(hipMemcpyAsync(slow_counts, S.count, sizeof(slow_counts), hipMemcpyDeviceToHost, stream));
+        HIP_CHECK(hipMemcpyAsync(bit_counts, d_counts.p, sizeof(bit_counts), hipMemcpyDeviceToHost, stream));
+        HIP_CHECK(hipStreamSynchronize(stream));
+        HIP_CHECK(hipGetLastError());
+        float dev_ms = 0.f;
+        HIP_CHECK(hipEventElapsedTime(&dev_ms, ev0, ev1));
+        (void)hipEventDestroy(ev0); (void)hipEventDestroy(ev1);
+        if (slow_counts[1]) {
+            HIP_CHECK(hipMemset(S.count + 1, 0, sizeof(uint32_t)));
+            // rows handed out by this call hold partial results: forget them
+            for (size_t k = 0; k < build_pos.size(); ++k) {
+                const Position& ps = g.positions[(size_t)build_pos[k]];
+                pool.entries[(size_t)entry[(size_t)ps.rule]].rows[(size_t)g.rules[(size_t)ps.rule].canon_id[(size_t)ps.state]] = nullptr;
+            }
+            return fail(XG2_EOVERFLOW, "xg2_compile_grammar: Earley item sets exceeded the large-capacity limit");
+        }
+        if (stats) {
+            stats->positions = (int64_t)g.positions.size();
+            stats->unique = (int64_t)n_unique;
+            stats->built = (int64_t)build_pos.size();
+            stats->checks = (int64_t)build_pos.size() * (int64_t)V.n_sorted;
+            stats->executed_checks = executed;
+            stats->slow_path = slow_counts[0];
+            stats->n_accepted = (int64_t)bit_counts[0];
+            stats->n_uncertain = (int64_t)bit_counts[1];
+            stats->host_lower_ms = host_ms_a + host_ms_b;
+            stats->device_ms = dev_ms;
+        }
+        *out = new xg2_mask_cache{cache};
+        return XG2_OK;
+    });
+}
+void xg2_mask_cache_destroy(xg2_mask_cache* c) { delete c; }
+
+int32_t xg2_mask_cache_num_positions(const xg2_mask_cache* c, int32_t* out) {
+    if (!c || !out) return fail(XG2_EINVAL, "xg2_mask_cache_num_positions: bad argument");
+    *out = (int32_t)c->p->gram->g.positions.size();
+    return XG2_OK;
+}
+int32_t xg2_mask_cache_position(const xg2_mask_cache* c, int32_t p, const char** rule_name, int32_t* state) {
+    if (!c || p < 0 || (size_t)p >= c->p->gram->g.positions.size()) return fail(XG2_EINVAL, "xg2_mask_cache_position: bad argument");
+    const Position& ps = c->p->gram->g.positions[(size_t)p];
+    if (rule_name) *rule_name = c->p->gram->rule_names[(size_t)ps.rule].c_str();
+    if (state) *state = ps.state;
+    return XG2_OK;
+}
+int32_t xg2_mask_cache_get_planes(const xg2_mask_cache* c, int32_t p, int32_t* accepted_host, int32_t* uncertain_host) {
+    return guarded([&]() -> int32_t {
+        if (!c || p < 0 || (size_t)p >= c->p->pos_plane.size()) return fail(XG2_EINVAL, "xg2_mask_cache_get_planes: bad argument");
+        const uint32_t W = c->p->vocab->W;
+        HIP_CHECK(hipDeviceSynchronize());
+        if (accepted_host) HIP_CHECK(hipMemcpy(accepted_host, c->p->pos_plane[(size_t)p], W * sizeof(uint32_t), hipMemcpyDeviceToHost));
+        if (uncertain_host) HIP_CHECK(hipMemcpy(uncertain_host, c->p->pos_plane[(size_t)p] + W, W * sizeof(uint32_t), hipMemcpyDeviceToHost));
+        return XG2_OK;
+    });
+}
+
+int32_t xg2_matcher_create(const xg2_mask_cache* c, xg2_matcher** out) {
+    return guarded([&]() -> int32_t {
+        if (!c || !out) return fail(XG2_EINVAL, "xg2_matcher_create: bad argument");
+        auto m = std::make_unique<MatcherImpl>(c->p->gram, c->p->vocab);
+        m->cache = c->p;
+        *out = new xg2_matcher{std::move(m)};
+        return XG2_OK;
+    });
+}
+int32_t xg2_matcher_create_host(const xg2_grammar* g, const xg2_vocab* v, xg2_matcher** out) {
+    return guarded([&]() -> int32_t {
+        if (!g || !v || !out) return fail(XG2_EINVAL, "xg2_matcher_create_host: bad argument");
+        *out = new xg2_matcher{std::make_unique<MatcherImpl>(g->p, v->p)};
+        return XG2_OK;
+    });
+}
+void xg2_matcher_destroy(xg2_matcher* m) { delete m; }
+
+int32_t xg2_matcher_accept_token(xg2_matcher* m, int32_t token_id) {
+    return guarded([&]() -> int32_t {
+        if (!m) return fail(XG2_EINVAL, "xg2_matcher_accept_token: null matcher");
+        MatcherImpl& M = *m->p;
+        if (token_id < 0 || token_id >= M.vocab->V) return fail(XG2_EINVAL, "xg2_matcher_accept_token: token id out of range");
+        if (M.terminated) return fail(XG2_EINVAL, "xg2_matcher_accept_token: matcher has terminated");
+        if (token_id == M.vocab->eos) {
+            if (!M.chart.last().root_done) return fail(XG2_EREJECTED, "end of sequence is not allowed here");
+            M.terminated = true;
+            return XG2_OK;
+        }
+        if (M.vocab->special[(size_t)token_id]) return fail(XG2_EREJECTED, "special or empty tokens are never allowed");
+        if (!M.chart.advance(M.vocab->tok(token_id), M.vocab->len(token_id))) return fail(XG2_EREJECTED, "token is not allowed here");
+        return XG2_OK;
+    });
+}
+int32_t xg2_matcher_reset(xg2_matcher* m) {
+    if (!m) return fail(XG2_EINVAL, "xg2_matcher_reset: null matcher");
+    m->p->chart.start(m->p->gram->ft.root_start);
+    m->p->terminated = false;
+    return XG2_OK;
+}
+int32_t xg2_matcher_is_terminated(const xg2_matcher* m, int32_t* out) {
+    if (!m || !out) return fail(XG2_EINVAL, "xg2_matcher_is_terminated: bad argument");
+    *out = m->p->terminated ? 1 : 0;
+    return XG2_OK;
+}
+int32_t xg2_matcher_frontier(const xg2_matcher* m, int32_t* positions_host, int32_t cap, int32_t* n, int32_t* can_end) {
+    if (!m || !n || cap < 0 || (cap > 0 && !positions_host)) return fail(XG2_EINVAL, "xg2_matcher_frontier: bad argument");
+    const MatcherImpl& M = *m->p;
+    std::vector<int32_t> pos;
+    if (!M.terminated)
+        for (const ChartItem& it : M.chart.last().scan) {
+            int32_t p = M.gram->g.sid_to_pos[it.sid];
+            if (p >= 0 && std::find(pos.begin(), pos.end(), p) == pos.end()) pos.push_back(p);
+        }
+    std::sort(pos.begin(), pos.end());
+    *n = (int32_t)pos.size();
+    for (int32_t k = 0; k < std::min<int32_t>(cap, *n); ++k) positions_host[k] = pos[(size_t)k];
+    if (can_end) *can_end = (M.terminated || M.chart.last().root_done) ? 1 : 0;
+    return XG2_OK;
+}
+
+int32_t xg2_fill_next_token_bitmask(xg2_matcher* const* matchers, int32_t B, int32_t* bitmask_dev, int64_t row_stride_words,
+                                    void* hip_stream) {
+    return guarded([&]() -> int32_t {
+        if (B < 0 || (B > 0 && (!matchers || !bitmask_dev))) return fail(XG2_EINVAL, "xg2_fill_next_token_bitmask: bad argument");
+        if (B == 0) return XG2_OK;
+        hipStream_t stream = (hipStream_t)hip_stream;
+        for (int32_t b = 0; b < B; ++b) {
+            if (!matchers[b]) return fail(XG2_EINVAL, "xg2_fill_next_token_bitmask: null matcher");
+            if (!matchers[b]->p->cache) return fail(XG2_EINVAL, "xg2_fill_next_token_bitmask: host-only matcher has no mask cache");
+            if (matchers[b]->p->vocab.get() != matchers[0]->p->vocab.get())
+                return fail(XG2_EINVAL, "xg2_fill_next_token_bitmask: matchers use different vocabularies");
+        }
+        VocabImpl& V = *matchers[0]->p->vocab;
+        if (row_stride_words < (int64_t)V.W) return fail(XG2_EINVAL, "xg2_fill_next_token_bitmask: row stride smaller than ceil(V/32)");
+        V.ensure_device();
+
+        std::vector<FillRow> rows((size_t)B);
+        std::vector<uint64_t> front;
+        std::vector<uint32_t> items, wait, wait_off;
+        std::vector<DevTables> tables;
+        std::map<const CacheImpl*, uint32_t> table_idx;
+        ScanContext ctx;
+        for (int32_t b = 0; b < B; ++b) {
+            const MatcherImpl& M = *matchers[b]->p;
+            FillRow& r = rows[(size_t)b];
+            std::memset(&r, 0, sizeof(r));
+            auto ti = table_idx.find(M.cache.get());
+            if (ti == table_idx.end()) { ti = table_idx.emplace(M.cache.get(), (uint32_t)tables.size()).first; tables.push_back(M.cache->dt); }
+            r.tables_idx = ti->second;
+            r.front_off = (uint32_t)front.size();
+            r.item_off = (uint32_t)items.size();
+            r.wait_base = (uint32_t)wait.size();
+            r.waitoff_off = (uint32_t)wait_off.size();
+            if (M.terminated) { r.flags = 2; continue; }
+            r.flags = M.chart.last().root_done ? 1u : 0u;
+            if (!M.chart.context(ctx)) return fail(XG2_EOVERFLOW, "xg2_fill_next_token_bitmask: parser context too deep");
+            size_t f0 = front.size();
+            for (const ChartItem& it : M.chart.last().scan) {
+                int32_t p = M.gram->g.sid_to_pos[it.sid];
+                if (p < 0) continue;
+                uint64_t row = (uint64_t)(uintptr_t)M.cache->pos_plane[(size_t)p];
+                if (std::find(front.begin() + (long)f0, front.end(), row) == front.end()) front.push_back(row);
+            }
+            r.front_n = (uint32_t)(front.size() - f0);
+            r.item_n = (uint32_t)ctx.items.size();
+            r.H = ctx.H;
+            items.insert(items.end(), ctx.items.begin(), ctx.items.end());
+            wait.insert(wait.end(), ctx.wait.begin(), ctx.wait.end());
+            wait_off.insert(wait_off.end(), ctx.wait_off.begin(), ctx.wait_off.end());
+        }
+        auto align = [](size_t x) { return (x + 255) & ~(size_t)255; };
+        size_t o_rows = 0;
+        size_t o_front = align(o_rows + rows.size() * sizeof(FillRow));
+        size_t o_items = align(o_front + front.size() * sizeof(uint64_t));
+        size_t o_wait = align(o_items + items.size() * sizeof(uint32_t));
+        size_t o_woff = align(o_wait + wait.size() * sizeof(uint32_t));
+        size_t o_tabs = align(o_woff + wait_off.size() * sizeof(uint32_t));
+        size_t total = align(o_tabs + tables.size() * sizeof(DevTables));
+
+        std::lock_guard<std::mutex> ws_lock(fill_ws().mu);
+        std::lock_guard<std::mutex> slow_lock(slow().mu);
+        slow().ensure();
+        const SlowScratch S = slow().s;
+        FillSlot& slot = fill_ws().acquire(total);
+        std::memcpy(slot.host + o_rows, rows.data(), rows.size() * sizeof(FillRow));
+        if (!front.empty()) std::memcpy(slot.host + o_front, front.data(), front.size() * sizeof(uint64_t));
+        if (!items.empty()) std::memcpy(slot.host + o_items, items.data(), items.size() * sizeof(uint32_t));
+        if (!wait.empty()) std::memcpy(slot.host + o_wait, wait.data(), wait.size() * sizeof(uint32_t));
+        if (!wait_off.empty()) std::memcpy(slot.host + o_woff, wait_off.data(), wait_off.size() * sizeof(uint32_t));
+        std::memcpy(slot.host + o_tabs, tables.data(), tables.size() * sizeof(DevTables));
+        HIP_CHECK(hipMemcpyAsync(slot.dev, slot.host, total, hipMemcpyHostToDevice, stream));
+        FillBatch F{};
+        F.rows = reinterpret_cast<const FillRow*>(slot.dev + o_rows); F.B = (uint32_t)B;
+        F.front_planes = reinterpret_cast<const uint64_t*>(slot.dev + o_front);
+        F.ctx_items = reinterpret_cast<const uint32_t*>(slot.dev + o_items);
+        F.ctx_wait = reinterpret_cast<const uint32_t*>(slot.dev + o_wait);
+        F.ctx_wait_off = reinterpret_cast<const uint32_t*>(slot.dev + o_woff);
+        F.tables = reinterpret_cast<const DevTables*>(slot.dev + o_tabs);
+        F.eos_id = (uint32_t)V.eos;
+        HIP_CHECK(hipMemsetAsync(S.count, 0, sizeof(uint32_t), stream));
+        launch_fill(F, V.dv, bitmask_dev, row_stride_words, S, stream);
+        launch_recheck_slow(F, V.dv, bitmask_dev, row_stride_words, S, stream);
+        HIP_CHECK(hipGetLastError());
+        HIP_CHECK(hipEventRecord(slot.done, stream));
+        slot.in_flight = true;
+        return XG2_OK;
+    });
+}
+
+int32_t xg2_apply_token_bitmask(void* logits_dev, int32_t dtype, int32_t B, int32_t V, int64_t row_stride_elems,
+                                const int32_t* bitmask_dev, int64_t bm_row_stride_words, void* hip_stream) {
+    return guarded([&]() -> int32_t {
+        if (B < 0 || V < 0 || (dtype != XG2_F32 && dtype != XG2_BF16)) return fail(XG2_EINVAL, "xg2_apply_token_bitmask: bad argument");
+        if (B == 0 || V == 0) return XG2_OK;
+        if (!logits_dev || !bitmask_dev || row_stride_elems < V || bm_row_stride_words < (V + 31) / 32)
+            return fail(XG2_EINVAL, "xg2_apply_token_bitmask: null buffer or stride smaller than the row");
+        require_device();
+        launch_apply(logits_dev, dtype, B, V, row_stride_elems, bitmask_dev, bm_row_stride_words, (hipStream_t)hip_stream);
+        HIP_CHECK(hipGetLastError());
+        return XG2_OK;
+    });
+}
+
+}  // extern "C"

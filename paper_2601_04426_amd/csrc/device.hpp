@@ -1,0 +1,73 @@
+// Launchers of the gfx950 kernels.  Plain pointers and sizes only; every pointer named *_dev is
+// device memory.  All launches go to `stream`; none of them synchronises.
+#pragma once
+#include <cstdint>
+#include <hip/hip_runtime.h>
+
+namespace xg2 {
+
+struct DevTables {                       // packed grammar tables (see tables.hpp for the word layout)
+    const uint4* state_info;
+    const uint2* byte_edges;
+    const uint2* ref_edges;
+    const uint2* rule_info;
+};
+
+struct DevVocab {                        // byte-sorted vocabulary in HBM
+    const uint8_t* bytes;                // concatenated token bytes in sorted order
+    const uint32_t* off;                 // [n_sorted + 1]
+    const uint32_t* perm;                // sorted rank -> token id
+    const uint32_t* rank;                // token id -> sorted rank, 0xFFFFFFFF for tokens never checked
+    uint32_t n_sorted;                   // checkable tokens (non-special, non-empty)
+    uint32_t V, W;
+};
+
+// Work plan of one cache build: segment s covers sorted ranks [seg_lo[s], seg_hi[s]) of position
+// seg_pos[s]; seg_blk[s] = number of 64-token blocks before it (seg_blk[n_seg] = total).
+struct BuildPlan {
+    const uint32_t* seg_pos; const uint32_t* seg_lo; const uint32_t* seg_hi; const uint32_t* seg_blk;
+    uint32_t n_seg, n_blocks;
+    // closed start set of every position, as a scan context with H = 1
+    const uint32_t* ctx_items; const uint32_t* ctx_item_off;   // [n_pos + 1]
+    const uint32_t* ctx_wait; const uint32_t* ctx_wait_off2;   // [2 * n_pos]: {begin, end} into ctx_wait
+    uint32_t* const* plane_ptr;                                 // [n_pos] accepted row; uncertain row at + W words
+};
+
+struct SlowScratch {                     // large-capacity per-lane Earley scratch in device memory
+    uint32_t* mem; uint32_t n_lanes;     // mem holds n_lanes * kSlowSlots words
+    uint32_t* list; uint32_t list_cap;   // overflow work list: pairs (a, b)
+    uint32_t* count;                     // [0] = entries in list, [1] = sticky error flag
+};
+constexpr uint32_t kSlowK = 256, kSlowWM = 1024, kSlowMaxLen = 1024;
+constexpr uint32_t kSlowSlots = 2 * kSlowK + kSlowWM + kSlowMaxLen + 1;
+
+void launch_build(const DevTables& T, const DevVocab& Vd, const BuildPlan& P, const SlowScratch& S, hipStream_t stream);
+void launch_build_slow(const DevTables& T, const DevVocab& Vd, const BuildPlan& P, const SlowScratch& S, hipStream_t stream);
+void launch_popcount(const uint32_t* const* plane_ptr_dev, uint32_t n_pos, uint32_t W, unsigned long long* out2_dev, hipStream_t stream);
+
+// One row of a fill batch.
+struct FillRow {
+    uint32_t front_off, front_n;         // into front_planes
+    uint32_t item_off, item_n;           // into ctx_items
+    uint32_t wait_base;                  // into ctx_wait
+    uint32_t waitoff_off, H;             // into ctx_wait_off ([H + 1] entries, relative to wait_base)
+    uint32_t tables_idx;                 // into tables
+    uint32_t flags;                      // bit 0: root can end, bit 1: terminated
+    uint32_t pad[3];
+};
+struct FillBatch {
+    const FillRow* rows; uint32_t B;
+    const uint64_t* front_planes;        // device addresses of accepted rows (uncertain at + W words)
+    const uint32_t* ctx_items; const uint32_t* ctx_wait; const uint32_t* ctx_wait_off;
+    const DevTables* tables;
+    uint32_t eos_id;
+};
+void launch_fill(const FillBatch& F, const DevVocab& Vd, int32_t* bitmask_dev, int64_t row_stride_words,
+                 const SlowScratch& S, hipStream_t stream);
+void launch_recheck_slow(const FillBatch& F, const DevVocab& Vd, int32_t* bitmask_dev, int64_t row_stride_words,
+                         const SlowScratch& S, hipStream_t stream);
+
+void launch_apply(void* logits_dev, int32_t dtype, int32_t B, int32_t V, int64_t row_stride_elems,
+                  const int32_t* bitmask_dev, int64_t bm_row_stride_words, hipStream_t stream);
+
+}  // namespace xg2

@@ -1,0 +1,986 @@
+// EBNF -> canonical minimal per-rule automata -> structural hashes.  Host code only.
+#include "grammar.hpp"
+
+#include <algorithm>
+#include <array>
+#include <atomic>
+#include <cstring>
+#include <deque>
+#include <functional>
+#include <map>
+#include <set>
+#include <sstream>
+#include <unordered_map>
+
+namespace xg2 {
+namespace {
+
+// ------------------------------------------------------------------------------------------------
+// byte sets
+struct ByteSet {
+    uint64_t w[4] = {0, 0, 0, 0};
+    void set(int b) { w[b >> 6] |= 1ull << (b & 63); }
+    void set_range(int lo, int hi) { for (int b = lo; b <= hi; ++b) set(b); }
+    bool test(int b) const { return (w[b >> 6] >> (b & 63)) & 1ull; }
+};
+
+// ------------------------------------------------------------------------------------------------
+// syntax tree of the EBNF dialect
+enum class NK { Lit, Cls, Ref, Seq, Alt, Rep, Tag };
+struct Node {
+    NK k = NK::Seq;
+    std::vector<uint32_t> cps;                                  // Lit: code points
+    bool neg = false;                                           // Cls
+    std::vector<std::pair<uint32_t, uint32_t>> ranges;          // Cls: scalar ranges as written
+    std::string name;                                           // Ref
+    std::vector<Node> kids;                                     // Seq / Alt / Rep (one kid)
+    int m = 0, n = -1;                                          // Rep: n < 0 = unbounded
+    std::vector<std::pair<std::string, std::string>> tags;      // Tag: (tag bytes, rule name)
+    std::vector<std::string> stops;                             // Tag: stop strings (bytes)
+};
+
+void append_utf8(std::string& out, uint32_t cp) {
+    if (cp < 0x80) out.push_back((char)cp);
+    else if (cp < 0x800) { out.push_back((char)(0xC0 | (cp >> 6))); out.push_back((char)(0x80 | (cp & 63))); }
+    else if (cp < 0x10000) {
+        out.push_back((char)(0xE0 | (cp >> 12))); out.push_back((char)(0x80 | ((cp >> 6) & 63)));
+        out.push_back((char)(0x80 | (cp & 63)));
+    } else {
+        out.push_back((char)(0xF0 | (cp >> 18))); out.push_back((char)(0x80 | ((cp >> 12) & 63)));
+        out.push_back((char)(0x80 | ((cp >> 6) & 63))); out.push_back((char)(0x80 | (cp & 63)));
+    }
+}
+
+class Parser {
+  public:
+    explicit Parser(const std::string& s) : s_(s) {}
+
+    void parse(std::vector<std::string>& order, std::map<std::string, Node>& rules) {
+        while (peek() != 0) {
+            std::string nm;
+            if (!name(nm)) fail("rule name expected");
+            expect("::=");
+            skip();
+            size_t save = i_;
+            std::string head;
+            Node body;
+            if (name(head) && head == "TagDispatch" && peek() == '(') body = tagdispatch();
+            else { i_ = save; body = alternation(); }
+            if (peek() != 0 && !at_rule_head()) fail("unexpected text after rule body");
+            if (rules.count(nm)) fail("rule " + nm + " defined twice");
+            order.push_back(nm);
+            rules.emplace(nm, std::move(body));
+        }
+    }
+
+  private:
+    const std::string& s_;
+    size_t i_ = 0;
+
+    [[noreturn]] void fail(const std::string& msg) const {
+        size_t line = 1 + (size_t)std::count(s_.begin(), s_.begin() + (long)std::min(i_, s_.size()), '\n');
+        throw ParseError("line " + std::to_string(line) + ": " + msg);
+    }
+    void skip() {
+        while (i_ < s_.size()) {
+            char c = s_[i_];
+            if (c == ' ' || c == '\t' || c == '\r' || c == '\n') ++i_;
+            else if (c == '#') { while (i_ < s_.size() && s_[i_] != '\n') ++i_; }
+            else break;
+        }
+    }
+    char peek() { skip(); return i_ < s_.size() ? s_[i_] : 0; }
+    static bool name_start(char c) { return (c >= 'a' && c <= 'z') || (c >= 'A' && c <= 'Z') || c == '_'; }
+    static bool name_cont(char c) { return name_start(c) || (c >= '0' && c <= '9') || c == '.' || c == '-'; }
+    bool name(std::string& out) {
+        skip();
+        size_t j = i_;
+        if (j < s_.size() && name_start(s_[j])) {
+            ++j;
+            while (j < s_.size() && name_cont(s_[j])) ++j;
+            out = s_.substr(i_, j - i_);
+            i_ = j;
+            return true;
+        }
+        return false;
+    }
+    bool at_rule_head() {
+        size_t save = i_;
+        std::string nm;
+        bool ok = false;
+        if (name(nm)) { skip(); ok = s_.compare(i_, 3, "::=") == 0; }
+        i_ = save;
+        return ok;
+    }
+    void expect(const char* tok) {
+        skip();
+        size_t n = std::strlen(tok);
+        if (s_.compare(i_, n, tok) != 0) fail(std::string("'") + tok + "' expected");
+        i_ += n;
+    }
+    // one source character as a code point (the grammar text is UTF-8)
+    uint32_t source_char() {
+        unsigned char c = (unsigned char)s_[i_];
+        int n = c < 0x80 ? 1 : (c >> 5) == 6 ? 2 : (c >> 4) == 14 ? 3 : (c >> 3) == 30 ? 4 : 0;
+        if (n == 0 || i_ + (size_t)n > s_.size()) fail("grammar text is not valid UTF-8");
+        uint32_t cp = n == 1 ? c : (c & (0xFF >> (n + 1)));
+        for (int k = 1; k < n; ++k) {
+            unsigned char d = (unsigned char)s_[i_ + (size_t)k];
+            if ((d & 0xC0) != 0x80) fail("grammar text is not valid UTF-8");
+            cp = (cp << 6) | (d & 63);
+        }
+        i_ += (size_t)n;
+        return cp;
+    }
+    uint32_t escape(bool in_class) {
+        if (i_ >= s_.size()) fail("dangling backslash");
+        char c = s_[i_++];
+        switch (c) {
+            case '"': return 34; case '\\': return 92; case 'n': return 10; case 't': return 9;
+            case 'r': return 13; case '/': return 47; case '\'': return 39;
+            default: break;
+        }
+        if (in_class && (c == '-' || c == ']' || c == '[' || c == '^')) return (uint32_t)c;
+        int width = c == 'x' ? 2 : c == 'u' ? 4 : c == 'U' ? 8 : 0;
+        if (!width) fail(std::string("unknown escape \\") + c);
+        if (i_ + (size_t)width > s_.size()) fail("bad hex escape");
+        uint32_t cp = 0;
+        for (int k = 0; k < width; ++k) {
+            char h = s_[i_++];
+            int v = h >= '0' && h <= '9' ? h - '0' : h >= 'a' && h <= 'f' ? h - 'a' + 10 : h >= 'A' && h <= 'F' ? h - 'A' + 10 : -1;
+            if (v < 0) fail("bad hex escape");
+            cp = cp * 16 + (uint32_t)v;
+        }
+        if (cp > 0x10FFFF || (cp >= 0xD800 && cp <= 0xDFFF)) fail("escape is not a Unicode scalar value");
+        return cp;
+    }
+    std::vector<uint32_t> literal() {
+        ++i_;                                                   // opening quote
+        std::vector<uint32_t> out;
+        for (;;) {
+            if (i_ >= s_.size()) fail("unterminated literal");
+            char c = s_[i_];
+            if (c == '"') { ++i_; return out; }
+            if (c == '\\') { ++i_; out.push_back(escape(false)); }
+            else out.push_back(source_char());
+        }
+    }
+    Node char_class() {
+        ++i_;                                                   // '['
+        Node n; n.k = NK::Cls;
+        if (i_ < s_.size() && s_[i_] == '^') { n.neg = true; ++i_; }
+        auto one = [&]() -> uint32_t {
+            if (i_ >= s_.size()) fail("unterminated class");
+            if (s_[i_] == '\\') { ++i_; return escape(true); }
+            return source_char();
+        };
+        for (;;) {
+            if (i_ >= s_.size()) fail("unterminated class");
+            if (s_[i_] == ']') { ++i_; break; }
+            uint32_t lo = one(), hi = lo;
+            if (i_ + 1 < s_.size() && s_[i_] == '-' && s_[i_ + 1] != ']') {
+                ++i_;
+                hi = one();
+                if (hi < lo) fail("reversed range in class");
+            }
+            n.ranges.emplace_back(lo, hi);
+        }
+        return n;
+    }
+    int number() {
+        skip();
+        size_t j = i_;
+        long v = 0;
+        while (j < s_.size() && s_[j] >= '0' && s_[j] <= '9') { v = v * 10 + (s_[j] - '0'); if (v > 1000000) fail("repetition bound too large"); ++j; }
+        if (j == i_) fail("number expected");
+        i_ = j;
+        return (int)v;
+    }
+    Node atom() {
+        char c = peek();
+        if (c == '"') { Node n; n.k = NK::Lit; n.cps = literal(); return n; }
+        if (c == '[') return char_class();
+        if (c == '(') {
+            ++i_;
+            Node n = alternation();
+            if (peek() != ')') fail("')' expected");
+            ++i_;
+            return n;
+        }
+        Node n; n.k = NK::Ref;
+        if (!name(n.name)) fail(std::string("unexpected character '") + c + "'");
+        return n;
+    }
+    static Node rep(Node x, int m, int n) {
+        Node r; r.k = NK::Rep; r.m = m; r.n = n; r.kids.push_back(std::move(x));
+        return r;
+    }
+    Node term() {
+        Node a = atom();
+        for (;;) {
+            char c = peek();
+            if (c == '*') { ++i_; a = rep(std::move(a), 0, -1); }
+            else if (c == '+') { ++i_; a = rep(std::move(a), 1, -1); }
+            else if (c == '?') { ++i_; a = rep(std::move(a), 0, 1); }
+            else if (c == '{') {
+                ++i_;
+                int m = number(), n = m;
+                if (peek() == ',') { ++i_; n = peek() == '}' ? -1 : number(); }
+                if (peek() != '}') fail("'}' expected");
+                ++i_;
+                if (n >= 0 && n < m) fail("repetition bounds reversed");
+                a = rep(std::move(a), m, n);
+            } else return a;
+        }
+    }
+    Node sequence() {
+        Node s; s.k = NK::Seq;
+        for (;;) {
+            char c = peek();
+            if (c == 0 || c == '|' || c == ')' || at_rule_head()) break;
+            s.kids.push_back(term());
+        }
+        if (s.kids.size() == 1) { Node only = std::move(s.kids[0]); return only; }
+        return s;
+    }
+    Node alternation() {
+        Node a; a.k = NK::Alt;
+        a.kids.push_back(sequence());
+        while (peek() == '|') { ++i_; a.kids.push_back(sequence()); }
+        if (a.kids.size() == 1) { Node only = std::move(a.kids[0]); return only; }
+        return a;
+    }
+    static std::string to_bytes(const std::vector<uint32_t>& cps) {
+        std::string out;
+        for (uint32_t c : cps) append_utf8(out, c);
+        return out;
+    }
+    Node tagdispatch() {
+        Node t; t.k = NK::Tag;
+        expect("(");
+        for (;;) {
+            char c = peek();
+            if (c == '(') {
+                ++i_;
+                if (peek() != '"') fail("tag literal expected");
+                std::string tag = to_bytes(literal());
+                expect(",");
+                std::string nm;
+                if (!name(nm)) fail("rule name expected");
+                expect(")");
+                t.tags.emplace_back(tag, nm);
+            } else if (s_.compare(i_, 9, "stop_strs") == 0) {
+                i_ += 9;
+                expect("="); expect("(");
+                while (peek() == '"') { t.stops.push_back(to_bytes(literal())); if (peek() == ',') ++i_; }
+                expect(")");
+            } else fail("tag pair or stop_strs expected");
+            if (peek() == ',') { ++i_; continue; }
+            break;
+        }
+        expect(")");
+        return t;
+    }
+};
+
+// ------------------------------------------------------------------------------------------------
+// character classes: scalar ranges -> sequences of byte ranges (UTF-8, shortest form, no surrogates)
+using ScalarRanges = std::vector<std::pair<uint32_t, uint32_t>>;
+
+ScalarRanges normalise_class(bool neg, ScalarRanges rs) {
+    std::sort(rs.begin(), rs.end());
+    ScalarRanges merged;
+    for (auto& r : rs) {
+        if (!merged.empty() && r.first <= merged.back().second + 1) merged.back().second = std::max(merged.back().second, r.second);
+        else merged.push_back(r);
+    }
+    if (neg) {
+        ScalarRanges out;
+        uint32_t prev = 0;
+        for (auto& r : merged) { if (r.first > prev) out.emplace_back(prev, r.first - 1); prev = r.second + 1; }
+        if (prev <= 0x10FFFF) out.emplace_back(prev, 0x10FFFF);
+        merged.swap(out);
+    }
+    ScalarRanges fin;
+    for (auto r : merged) {
+        r.second = std::min<uint32_t>(r.second, 0x10FFFF);
+        if (r.first > r.second) continue;
+        if (r.second < 0xD800 || r.first > 0xDFFF) { fin.push_back(r); continue; }
+        if (r.first < 0xD800) fin.emplace_back(r.first, 0xD7FF);
+        if (r.second > 0xDFFF) fin.emplace_back(0xE000, r.second);
+    }
+    return fin;
+}
+
+struct ByteSeq { int n; uint8_t lo[4], hi[4]; };
+
+// [lo, hi] encodes to `len` bytes throughout; cut it until each piece is a product of byte ranges.
+void split_same_length(uint32_t lo, uint32_t hi, int len, std::vector<ByteSeq>& out) {
+    for (int i = 1; i < len; ++i) {
+        uint32_t m = (1u << (6 * i)) - 1;
+        if ((lo & ~m) != (hi & ~m)) {
+            if ((lo & m) != 0) {
+                split_same_length(lo, lo | m, len, out);
+                split_same_length((lo | m) + 1, hi, len, out);
+                return;
+            }
+            if ((hi & m) != m) {
+                split_same_length(lo, (hi & ~m) - 1, len, out);
+                split_same_length(hi & ~m, hi, len, out);
+                return;
+            }
+        }
+    }
+    std::string a, b;
+    append_utf8(a, lo);
+    append_utf8(b, hi);
+    ByteSeq s; s.n = len;
+    for (int k = 0; k < len; ++k) { s.lo[k] = (uint8_t)a[(size_t)k]; s.hi[k] = (uint8_t)b[(size_t)k]; }
+    out.push_back(s);
+}
+
+std::vector<ByteSeq> class_byte_sequences(bool neg, const ScalarRanges& written) {
+    static const uint32_t bound[5] = {0, 0x7F, 0x7FF, 0xFFFF, 0x10FFFF};
+    std::vector<ByteSeq> out;
+    for (auto r : normalise_class(neg, written))
+        for (int len = 1; len <= 4; ++len) {
+            uint32_t lo = std::max(r.first, bound[len - 1] + (len > 1 ? 1u : 0u));
+            uint32_t hi = std::min(r.second, bound[len]);
+            if (lo <= hi) split_same_length(lo, hi, len, out);
+        }
+    return out;
+}
+
+// ------------------------------------------------------------------------------------------------
+// Thompson construction over the alphabet {bytes} U {rule symbols}
+struct NEdge { int kind; ByteSet set; int rule; int dst; };   // kind 0 epsilon, 1 bytes, 2 rule symbol
+struct Nfa {
+    std::vector<std::vector<NEdge>> e;
+    int add() { e.emplace_back(); return (int)e.size() - 1; }
+    void eps(int a, int b) { e[(size_t)a].push_back({0, ByteSet(), -1, b}); }
+    void bytes(int a, const ByteSet& s, int b) { e[(size_t)a].push_back({1, s, -1, b}); }
+    void rule(int a, int r, int b) { e[(size_t)a].push_back({2, ByteSet(), r, b}); }
+};
+
+void build_nfa(const Node& nd, Nfa& nfa, int s, int e, const std::map<std::string, int>& index) {
+    switch (nd.k) {
+        case NK::Lit: {
+            std::string data;
+            for (uint32_t c : nd.cps) append_utf8(data, c);
+            int cur = s;
+            for (unsigned char b : data) { int nx = nfa.add(); ByteSet bs; bs.set(b); nfa.bytes(cur, bs, nx); cur = nx; }
+            nfa.eps(cur, e);
+            break;
+        }
+        case NK::Cls: {
+            for (const ByteSeq& q : class_byte_sequences(nd.neg, nd.ranges)) {
+                int cur = s;
+                for (int k = 0; k < q.n; ++k) {
+                    int nx = k + 1 == q.n ? e : nfa.add();
+                    ByteSet bs; bs.set_range(q.lo[k], q.hi[k]);
+                    nfa.bytes(cur, bs, nx);
+                    cur = nx;
+                }
+            }
+            break;
+        }
+        case NK::Ref: {
+            auto it = index.find(nd.name);
+            if (it == index.end()) throw GrammarError("undefined rule " + nd.name);
+            nfa.rule(s, it->second, e);
+            break;
+        }
+        case NK::Seq: {
+            int cur = s;
+            for (const Node& c : nd.kids) { int a = nfa.add(), b = nfa.add(); build_nfa(c, nfa, a, b, index); nfa.eps(cur, a); cur = b; }
+            nfa.eps(cur, e);
+            break;
+        }
+        case NK::Alt:
+            for (const Node& c : nd.kids) { int a = nfa.add(), b = nfa.add(); build_nfa(c, nfa, a, b, index); nfa.eps(s, a); nfa.eps(b, e); }
+            break;
+        case NK::Rep: {
+            const Node& x = nd.kids[0];
+            int cur = s;
+            for (int k = 0; k < nd.m; ++k) { int a = nfa.add(), b = nfa.add(); build_nfa(x, nfa, a, b, index); nfa.eps(cur, a); cur = b; }
+            if (nd.n < 0) {
+                int a = nfa.add(), b = nfa.add();
+                build_nfa(x, nfa, a, b, index);
+                nfa.eps(cur, a); nfa.eps(b, cur); nfa.eps(cur, e);
+            } else {
+                nfa.eps(cur, e);
+                for (int k = nd.m; k < nd.n; ++k) {
+                    int a = nfa.add(), b = nfa.add();
+                    build_nfa(x, nfa, a, b, index);
+                    nfa.eps(cur, a); cur = b; nfa.eps(cur, e);
+                }
+            }
+            break;
+        }
+        case NK::Tag: throw GrammarError("TagDispatch must be the whole body of a rule");
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// deterministic automaton with dense byte rows (one rule at a time, so the memory is transient)
+struct Dfa {
+    std::vector<std::array<int32_t, 256>> bt;                 // byte -> target or -1
+    std::vector<std::vector<std::pair<int, int>>> rt;         // (rule decl index, target), sorted by rule
+    std::vector<uint8_t> fin;
+    int start = 0;
+    int add(bool f) {
+        bt.emplace_back(); bt.back().fill(-1);
+        rt.emplace_back(); fin.push_back(f ? 1 : 0);
+        return (int)fin.size() - 1;
+    }
+    int n() const { return (int)fin.size(); }
+};
+
+Dfa subset_construction(const Nfa& nfa, int start, int end) {
+    std::vector<int> stamp(nfa.e.size(), -1);
+    int tick = 0;
+    auto closure = [&](std::vector<int> seed) {
+        ++tick;
+        std::vector<int> out, stack;
+        for (int q : seed) if (stamp[(size_t)q] != tick) { stamp[(size_t)q] = tick; out.push_back(q); stack.push_back(q); }
+        while (!stack.empty()) {
+            int q = stack.back(); stack.pop_back();
+            for (const NEdge& ed : nfa.e[(size_t)q])
+                if (ed.kind == 0 && stamp[(size_t)ed.dst] != tick) { stamp[(size_t)ed.dst] = tick; out.push_back(ed.dst); stack.push_back(ed.dst); }
+        }
+        std::sort(out.begin(), out.end());
+        return out;
+    };
+    Dfa d;
+    std::map<std::vector<int>, int> ids;
+    std::vector<std::vector<int>> sets;
+    auto intern = [&](std::vector<int> S) {
+        auto it = ids.find(S);
+        if (it != ids.end()) return it->second;
+        int id = d.add(std::binary_search(S.begin(), S.end(), end));
+        ids.emplace(S, id);
+        sets.push_back(std::move(S));
+        return id;
+    };
+    intern(closure({start}));
+    for (size_t cur = 0; cur < sets.size(); ++cur) {
+        std::vector<const NEdge*> bedges;
+        std::map<int, std::vector<int>> by_rule;
+        for (int q : sets[cur])
+            for (const NEdge& ed : nfa.e[(size_t)q]) {
+                if (ed.kind == 1) bedges.push_back(&ed);
+                else if (ed.kind == 2) by_rule[ed.rule].push_back(ed.dst);
+            }
+        // bytes with the same set of matching edges go to the same target
+        std::map<std::vector<int>, std::vector<int>> groups;   // edge indices -> bytes
+        for (int b = 0; b < 256; ++b) {
+            std::vector<int> hit;
+            for (size_t k = 0; k < bedges.size(); ++k) if (bedges[k]->set.test(b)) hit.push_back((int)k);
+            if (!hit.empty()) groups[hit].push_back(b);
+        }
+        for (auto& g : groups) {
+            std::vector<int> seed;
+            for (int k : g.first) seed.push_back(bedges[(size_t)k]->dst);
+            int t = intern(closure(seed));
+            for (int b : g.second) d.bt[cur][(size_t)b] = t;
+        }
+        for (auto& r : by_rule) { int t = intern(closure(r.second)); d.rt[cur].emplace_back(r.first, t); }
+    }
+    d.start = 0;
+    return d;
+}
+
+// TagDispatch (section 3.2) as an Aho-Corasick automaton: goto trie over tags and stop strings,
+// failure links, transitions completed so that every byte is free text; completing a tag leads to
+// a state whose only edge is the tag's rule and returns to the trie root; completing a stop string
+// leads to the single final exit state.  Without stop strings every dispatching state is final.
+Dfa tagdispatch_automaton(const Node& nd, const std::map<std::string, int>& index) {
+    std::vector<std::string> pats;
+    for (auto& t : nd.tags) pats.push_back(t.first);
+    for (auto& s : nd.stops) pats.push_back(s);
+    if (nd.tags.empty()) throw GrammarError("TagDispatch needs at least one tag");
+    for (size_t a = 0; a < pats.size(); ++a) {
+        if (pats[a].empty()) throw GrammarError("empty tag or stop string");
+        for (size_t b = 0; b < pats.size(); ++b)
+            if (a != b && pats[b].find(pats[a]) != std::string::npos)
+                throw GrammarError("a tag or stop string occurs inside another one");
+    }
+    struct TNode { std::map<unsigned char, int> kid; int pat = -1; int fail = 0; };
+    std::vector<TNode> trie(1);
+    for (size_t p = 0; p < pats.size(); ++p) {
+        int cur = 0;
+        for (unsigned char c : pats[p]) {
+            auto it = trie[(size_t)cur].kid.find(c);
+            if (it == trie[(size_t)cur].kid.end()) { trie.emplace_back(); int id = (int)trie.size() - 1; trie[(size_t)cur].kid[c] = id; cur = id; }
+            else cur = it->second;
+        }
+        trie[(size_t)cur].pat = (int)p;
+    }
+    // dense goto over breadth-first order, failure transitions folded in
+    std::vector<std::array<int, 256>> go(trie.size());
+    std::deque<int> bfs;
+    for (int c = 0; c < 256; ++c) {
+        auto it = trie[0].kid.find((unsigned char)c);
+        go[0][(size_t)c] = it == trie[0].kid.end() ? 0 : it->second;
+        if (it != trie[0].kid.end()) { trie[(size_t)it->second].fail = 0; bfs.push_back(it->second); }
+    }
+    while (!bfs.empty()) {
+        int u = bfs.front(); bfs.pop_front();
+        for (int c = 0; c < 256; ++c) {
+            auto it = trie[(size_t)u].kid.find((unsigned char)c);
+            if (it == trie[(size_t)u].kid.end()) go[(size_t)u][(size_t)c] = go[(size_t)trie[(size_t)u].fail][(size_t)c];
+            else {
+                int v = it->second;
+                trie[(size_t)v].fail = go[(size_t)trie[(size_t)u].fail][(size_t)c];
+                go[(size_t)u][(size_t)c] = v;
+                bfs.push_back(v);
+            }
+        }
+    }
+    Dfa d;
+    bool no_stops = nd.stops.empty();
+    std::vector<int> state_of(trie.size(), -1);
+    for (size_t u = 0; u < trie.size(); ++u) if (trie[u].pat < 0) state_of[u] = d.add(no_stops);
+    std::vector<int> after_tag(nd.tags.size());
+    for (size_t k = 0; k < nd.tags.size(); ++k) {
+        auto it = index.find(nd.tags[k].second);
+        if (it == index.end()) throw GrammarError("undefined rule " + nd.tags[k].second);
+        after_tag[k] = d.add(false);
+        d.rt[(size_t)after_tag[k]].emplace_back(it->second, state_of[0]);
+    }
+    int exit_state = no_stops ? -1 : d.add(true);
+    for (size_t u = 0; u < trie.size(); ++u) {
+        if (trie[u].pat >= 0) continue;
+        for (int c = 0; c < 256; ++c) {
+            int v = go[u][(size_t)c];
+            int p = trie[(size_t)v].pat;
+            d.bt[(size_t)state_of[u]][(size_t)c] = p < 0 ? state_of[(size_t)v] : (size_t)p < nd.tags.size() ? after_tag[(size_t)p] : exit_state;
+        }
+    }
+    d.start = state_of[0];
+    return d;
+}
+
+// Trim (reachable and able to reach a final state), Hopcroft partition refinement with bytes that
+// behave alike everywhere treated as one symbol, then canonical breadth-first renaming: out-edges
+// visited by ascending byte, then by ascending declaration index of the referenced rule.
+Dfa minimise_canonical(const Dfa& in, const std::string& rule_name) {
+    int n0 = in.n();
+    std::vector<uint8_t> reach((size_t)n0, 0), live((size_t)n0, 0);
+    std::vector<int> stack{in.start};
+    reach[(size_t)in.start] = 1;
+    std::vector<std::vector<int>> rev((size_t)n0);
+    while (!stack.empty()) {
+        int q = stack.back(); stack.pop_back();
+        auto visit = [&](int t) { if (t >= 0 && !reach[(size_t)t]) { reach[(size_t)t] = 1; stack.push_back(t); } };
+        for (int b = 0; b < 256; ++b) visit(in.bt[(size_t)q][(size_t)b]);
+        for (auto& r : in.rt[(size_t)q]) visit(r.second);
+    }
+    for (int q = 0; q < n0; ++q) {
+        if (!reach[(size_t)q]) continue;
+        int last = -1;
+        for (int b = 0; b < 256; ++b) { int t = in.bt[(size_t)q][(size_t)b]; if (t >= 0 && t != last) { rev[(size_t)t].push_back(q); last = t; } }
+        for (auto& r : in.rt[(size_t)q]) rev[(size_t)r.second].push_back(q);
+    }
+    for (int q = 0; q < n0; ++q) if (reach[(size_t)q] && in.fin[(size_t)q]) { live[(size_t)q] = 1; stack.push_back(q); }
+    while (!stack.empty()) {
+        int q = stack.back(); stack.pop_back();
+        for (int p : rev[(size_t)q]) if (!live[(size_t)p]) { live[(size_t)p] = 1; stack.push_back(p); }
+    }
+    if (!live[(size_t)in.start]) throw GrammarError("rule " + rule_name + " has an empty language");
+    std::vector<int> keep_id((size_t)n0, -1), keep;
+    for (int q = 0; q < n0; ++q) if (reach[(size_t)q] && live[(size_t)q]) { keep_id[(size_t)q] = (int)keep.size(); keep.push_back(q); }
+    int n = (int)keep.size();
+
+    // byte classes: two bytes are alike if they lead to the same target in every kept state
+    std::vector<int> bclass(256, 0);
+    int nclass = 1;
+    for (int q : keep) {
+        std::map<std::pair<int, int>, int> remap;
+        for (int b = 0; b < 256; ++b) {
+            int t = in.bt[(size_t)q][(size_t)b];
+            t = t >= 0 ? keep_id[(size_t)t] : -1;
+            auto key = std::make_pair(bclass[(size_t)b], t);
+            auto it = remap.find(key);
+            if (it == remap.end()) it = remap.emplace(key, (int)remap.size()).first;
+            bclass[(size_t)b] = it->second;
+        }
+        nclass = std::max(nclass, (int)remap.size());
+    }
+    std::vector<int> class_rep((size_t)nclass, 0);
+    for (int b = 255; b >= 0; --b) class_rep[(size_t)bclass[(size_t)b]] = b;
+    std::vector<int> rule_syms;
+    for (int q : keep) for (auto& r : in.rt[(size_t)q]) if (keep_id[(size_t)r.second] >= 0) rule_syms.push_back(r.first);
+    std::sort(rule_syms.begin(), rule_syms.end());
+    rule_syms.erase(std::unique(rule_syms.begin(), rule_syms.end()), rule_syms.end());
+    int nsym = nclass + (int)rule_syms.size();
+    std::vector<int> delta((size_t)n * (size_t)nsym, -1);
+    for (int i = 0; i < n; ++i) {
+        int q = keep[(size_t)i];
+        for (int c = 0; c < nclass; ++c) { int t = in.bt[(size_t)q][(size_t)class_rep[(size_t)c]]; delta[(size_t)i * nsym + c] = t >= 0 ? keep_id[(size_t)t] : -1; }
+        for (auto& r : in.rt[(size_t)q]) {
+            int t = keep_id[(size_t)r.second];
+            if (t < 0) continue;
+            int s = nclass + (int)(std::lower_bound(rule_syms.begin(), rule_syms.end(), r.first) - rule_syms.begin());
+            delta[(size_t)i * nsym + s] = t;
+        }
+    }
+    // inverse transitions: for target t, list of (symbol, source)
+    std::vector<std::vector<std::pair<int, int>>> inv((size_t)n);
+    for (int i = 0; i < n; ++i)
+        for (int s = 0; s < nsym; ++s) { int t = delta[(size_t)i * nsym + s]; if (t >= 0) inv[(size_t)t].emplace_back(s, i); }
+
+    std::vector<int> block_of((size_t)n);
+    std::vector<std::vector<int>> blocks;
+    {
+        std::vector<int> f, nf;
+        for (int i = 0; i < n; ++i) (in.fin[(size_t)keep[(size_t)i]] ? f : nf).push_back(i);
+        if (!f.empty()) blocks.push_back(f);
+        if (!nf.empty()) blocks.push_back(nf);
+        for (size_t b = 0; b < blocks.size(); ++b) for (int i : blocks[b]) block_of[(size_t)i] = (int)b;
+    }
+    std::deque<int> work;
+    std::vector<uint8_t> in_work(blocks.size(), 1);
+    for (size_t b = 0; b < blocks.size(); ++b) work.push_back((int)b);
+    std::vector<int> mark_count, touched;
+    std::vector<uint8_t> marked((size_t)n, 0);
+    std::vector<std::vector<int>> pre((size_t)nsym);
+    while (!work.empty()) {
+        int B = work.front(); work.pop_front();
+        in_work[(size_t)B] = 0;
+        std::vector<int> used_syms;
+        for (int t : blocks[(size_t)B])
+            for (auto& e : inv[(size_t)t]) { if (pre[(size_t)e.first].empty()) used_syms.push_back(e.first); pre[(size_t)e.first].push_back(e.second); }
+        for (int s : used_syms) {
+            std::vector<int>& X = pre[(size_t)s];
+            mark_count.assign(blocks.size(), 0);
+            touched.clear();
+            for (int q : X) { if (!marked[(size_t)q]) { marked[(size_t)q] = 1; int b = block_of[(size_t)q]; if (mark_count[(size_t)b]++ == 0) touched.push_back(b); } }
+            for (int Y : touched) {
+                if (mark_count[(size_t)Y] == (int)blocks[(size_t)Y].size()) continue;
+                std::vector<int> in_x, out_x;
+                for (int q : blocks[(size_t)Y]) (marked[(size_t)q] ? in_x : out_x).push_back(q);
+                bool new_is_in = in_x.size() <= out_x.size();
+                std::vector<int>& small = new_is_in ? in_x : out_x;
+                std::vector<int>& large = new_is_in ? out_x : in_x;
+                int nb = (int)blocks.size();
+                for (int q : small) block_of[(size_t)q] = nb;
+                blocks[(size_t)Y] = large;
+                blocks.push_back(small);
+                in_work.push_back(1);
+                work.push_back(nb);                              // Y keeps the larger half (and stays queued if it was)
+            }
+            for (int q : X) marked[(size_t)q] = 0;
+            X.clear();
+        }
+    }
+    // quotient automaton
+    int nb = (int)blocks.size();
+    Dfa quo;
+    for (int b = 0; b < nb; ++b) quo.add(in.fin[(size_t)keep[(size_t)blocks[(size_t)b][0]]]);
+    for (int b = 0; b < nb; ++b) {
+        int i = blocks[(size_t)b][0];
+        for (int c = 0; c < 256; ++c) { int t = delta[(size_t)i * nsym + bclass[(size_t)c]]; quo.bt[(size_t)b][(size_t)c] = t >= 0 ? block_of[(size_t)t] : -1; }
+        for (size_t r = 0; r < rule_syms.size(); ++r) { int t = delta[(size_t)i * nsym + nclass + (int)r]; if (t >= 0) quo.rt[(size_t)b].emplace_back(rule_syms[r], block_of[(size_t)t]); }
+    }
+    quo.start = block_of[(size_t)keep_id[(size_t)in.start]];
+    // canonical renaming
+    std::vector<int> ident((size_t)nb, -1), order{quo.start};
+    ident[(size_t)quo.start] = 0;
+    for (size_t k = 0; k < order.size(); ++k) {
+        int q = order[k];
+        auto visit = [&](int t) { if (t >= 0 && ident[(size_t)t] < 0) { ident[(size_t)t] = (int)order.size(); order.push_back(t); } };
+        for (int c = 0; c < 256; ++c) visit(quo.bt[(size_t)q][(size_t)c]);
+        for (auto& r : quo.rt[(size_t)q]) visit(r.second);
+    }
+    Dfa out;
+    for (int q : order) out.add(quo.fin[(size_t)q]);
+    for (size_t k = 0; k < order.size(); ++k) {
+        int q = order[k];
+        for (int c = 0; c < 256; ++c) { int t = quo.bt[(size_t)q][(size_t)c]; out.bt[k][(size_t)c] = t >= 0 ? ident[(size_t)t] : -1; }
+        for (auto& r : quo.rt[(size_t)q]) out.rt[k].emplace_back(r.first, ident[(size_t)r.second]);
+    }
+    out.start = 0;
+    return out;
+}
+
+// ------------------------------------------------------------------------------------------------
+// structural hashing (Algorithm 1, Algorithm 2)
+constexpr uint64_t NODE_TAG = 0xA1, RANGE_TAG = 0xB2, REF_TAG = 0xC3;
+
+void put_u64(std::string& s, uint64_t v) { for (int k = 0; k < 8; ++k) s.push_back((char)((v >> (8 * k)) & 0xFF)); }
+
+// Algorithm 1 on one rule.  ref_hash[r] = hash of referenced rule r (kInCycleRef for the unresolved
+// in-cycle reference).  Fills canon_id and redges_by_hash, returns the hash.
+uint64_t hash_one_fsm(RuleFsm& f, const std::vector<uint64_t>& ref_hash) {
+    int n = f.n_states();
+    // phase 1: out-edges sorted (ranges by (min,max); references by hash), BFS canonical ids
+    f.redges_by_hash.assign((size_t)n, {});
+    for (int s = 0; s < n; ++s) {
+        f.redges_by_hash[(size_t)s] = f.redges[(size_t)s];
+        std::stable_sort(f.redges_by_hash[(size_t)s].begin(), f.redges_by_hash[(size_t)s].end(),
+                         [&](const RefEdge& a, const RefEdge& b) { return ref_hash[(size_t)a.rule] < ref_hash[(size_t)b.rule]; });
+    }
+    f.canon_id.assign((size_t)n, -1);
+    std::vector<int> order{0};
+    f.canon_id[0] = 0;
+    for (size_t k = 0; k < order.size(); ++k) {
+        int s = order[k];
+        auto visit = [&](int t) { if (f.canon_id[(size_t)t] < 0) { f.canon_id[(size_t)t] = (int)order.size(); order.push_back(t); } };
+        for (auto& e : f.bedges[(size_t)s]) visit(e.tgt);       // already sorted by (lo, hi)
+        for (auto& e : f.redges_by_hash[(size_t)s]) visit(e.tgt);
+    }
+    // phase 2
+    uint64_t h = 0;
+    for (int s : order) {
+        h = hash_combine(hash_combine(h, NODE_TAG), f.is_final[(size_t)s]);
+        for (auto& e : f.bedges[(size_t)s])
+            h = hash_combine(hash_combine(hash_combine(hash_combine(h, RANGE_TAG), e.lo), e.hi), (uint64_t)f.canon_id[(size_t)e.tgt]);
+        for (auto& e : f.redges_by_hash[(size_t)s])
+            h = hash_combine(hash_combine(hash_combine(h, REF_TAG), ref_hash[(size_t)e.rule]), (uint64_t)f.canon_id[(size_t)e.tgt]);
+    }
+    return h;
+}
+
+std::atomic<uint64_t> g_unshareable_salt{1};
+
+void hash_rules(Grammar& g) {
+    int R = (int)g.rules.size();
+    // reference graph and its strongly connected components (Tarjan; components come out callee-first)
+    std::vector<std::vector<int>> refs((size_t)R);
+    for (int r = 0; r < R; ++r) {
+        std::set<int> s;
+        for (auto& es : g.rules[(size_t)r].redges) for (auto& e : es) s.insert(e.rule);
+        refs[(size_t)r].assign(s.begin(), s.end());
+    }
+    std::vector<int> idx((size_t)R, -1), low((size_t)R, 0), comp((size_t)R, -1), st;
+    std::vector<uint8_t> on((size_t)R, 0);
+    std::vector<std::vector<int>> comps;
+    int counter = 0;
+    std::function<void(int)> dfs = [&](int v) {
+        idx[(size_t)v] = low[(size_t)v] = counter++;
+        st.push_back(v); on[(size_t)v] = 1;
+        for (int w : refs[(size_t)v]) {
+            if (idx[(size_t)w] < 0) { dfs(w); low[(size_t)v] = std::min(low[(size_t)v], low[(size_t)w]); }
+            else if (on[(size_t)w]) low[(size_t)v] = std::min(low[(size_t)v], idx[(size_t)w]);
+        }
+        if (low[(size_t)v] == idx[(size_t)v]) {
+            comps.emplace_back();
+            for (;;) { int w = st.back(); st.pop_back(); on[(size_t)w] = 0; comp[(size_t)w] = (int)comps.size() - 1; comps.back().push_back(w); if (w == v) break; }
+        }
+    };
+    for (int r = 0; r < R; ++r) if (idx[(size_t)r] < 0) dfs(r);
+
+    std::vector<uint64_t> hash((size_t)R, 0);
+    for (auto& members : comps) {
+        int c = comp[(size_t)members[0]];
+        bool self_loop = false;
+        for (int w : refs[(size_t)members[0]]) if (w == members[0]) self_loop = true;
+        if (members.size() == 1 && !self_loop) {                 // acyclic part: bottom-up, Algorithm 1
+            RuleFsm& f = g.rules[(size_t)members[0]];
+            f.hash = hash[(size_t)members[0]] = hash_one_fsm(f, hash);
+            g.hash_order.push_back(members);
+            continue;
+        }
+        // is it a simple cycle?  every member references exactly one member, and those links form one ring
+        std::vector<int> ring;
+        bool simple = true;
+        std::map<int, int> next;
+        for (int v : members) {
+            int cnt = 0, nx = -1;
+            for (int w : refs[(size_t)v]) if (comp[(size_t)w] == c) { ++cnt; nx = w; }
+            if (cnt != 1) simple = false;
+            next[v] = nx;
+        }
+        if (simple) {
+            int v = *std::min_element(members.begin(), members.end());
+            for (size_t k = 0; k < members.size(); ++k) { ring.push_back(v); v = next[v]; }
+            std::set<int> seen(ring.begin(), ring.end());
+            if (seen.size() != members.size() || v != ring[0]) simple = false;
+        }
+        // local hashes with the shared placeholder on the unresolved in-cycle references
+        std::vector<uint64_t> with_ph = hash;
+        for (int v : members) with_ph[(size_t)v] = kInCycleRef;
+        std::map<int, uint64_t> local;
+        for (int v : members) local[v] = hash_one_fsm(g.rules[(size_t)v], with_ph);
+        g.hash_order.push_back(simple ? ring : members);
+        if (simple) {                                             // Algorithm 2
+            size_t L = ring.size();
+            for (size_t i = 0; i < L; ++i) {
+                uint64_t H = 0;
+                RuleFsm& f = g.rules[(size_t)ring[i]];
+                for (size_t j = 0; j < L; ++j) { int v = ring[(i + j) % L]; H = hash_combine(H, local[v]); f.ring.push_back(v); }
+                f.hash = hash[(size_t)ring[i]] = H;
+            }
+        } else {                                                  // not a simple cycle: never shared
+            for (int v : members) {
+                RuleFsm& f = g.rules[(size_t)v];
+                f.shareable = false;
+                f.hash = hash[(size_t)v] = hash_combine(local[v], 0xDEAD0000ull + g_unshareable_salt.fetch_add(1));
+            }
+        }
+    }
+}
+
+}  // namespace
+
+uint64_t hash_combine(uint64_t h, uint64_t v) {
+    // order-sensitive: H(H(h, a), b) != H(H(h, b), a)
+    uint64_t x = h ^ (v + 0x9E3779B97F4A7C15ull + (h << 6) + (h >> 2));
+    x ^= x >> 30; x *= 0xBF58476D1CE4E5B9ull;
+    x ^= x >> 27; x *= 0x94D049BB133111EBull;
+    x ^= x >> 31;
+    return x;
+}
+
+std::string serialise_rule(const Grammar& g, int32_t rule, const std::vector<uint64_t>& ref_id) {
+    const RuleFsm& f = g.rules[(size_t)rule];
+    int n = f.n_states();
+    std::vector<int> by_canon((size_t)n);
+    for (int s = 0; s < n; ++s) by_canon[(size_t)f.canon_id[(size_t)s]] = s;
+    std::string text;
+    for (int s : by_canon) {
+        text.push_back('N'); text.push_back((char)f.is_final[(size_t)s]);
+        for (auto& e : f.bedges[(size_t)s]) {
+            text.push_back('R'); text.push_back((char)e.lo); text.push_back((char)e.hi); put_u64(text, (uint64_t)f.canon_id[(size_t)e.tgt]);
+        }
+        for (auto& e : f.redges_by_hash[(size_t)s]) {
+            text.push_back('F'); put_u64(text, ref_id[(size_t)e.rule]); put_u64(text, (uint64_t)f.canon_id[(size_t)e.tgt]);
+        }
+    }
+    return text;
+}
+
+Grammar lower_grammar(const std::string& ebnf, const std::string& root_rule) {
+    std::vector<std::string> order;
+    std::map<std::string, Node> rules;
+    Parser(ebnf).parse(order, rules);
+    std::map<std::string, int> index;
+    for (size_t i = 0; i < order.size(); ++i) index[order[i]] = (int)i;
+    if (!index.count(root_rule)) throw GrammarError("unknown root rule " + root_rule);
+
+    // lower the rules reachable from the root
+    std::map<int, Dfa> dfas;
+    std::vector<int> todo{index[root_rule]};
+    while (!todo.empty()) {
+        int r = todo.back(); todo.pop_back();
+        if (dfas.count(r)) continue;
+        const Node& body = rules.at(order[(size_t)r]);
+        Dfa raw;
+        if (body.k == NK::Tag) raw = tagdispatch_automaton(body, index);
+        else {
+            Nfa nfa;
+            int s = nfa.add(), e = nfa.add();
+            build_nfa(body, nfa, s, e, index);
+            raw = subset_construction(nfa, s, e);
+        }
+        Dfa d = minimise_canonical(raw, order[(size_t)r]);
+        for (auto& es : d.rt) for (auto& e : es) todo.push_back(e.first);
+        dfas.emplace(r, std::move(d));
+    }
+    Grammar g;
+    std::map<int, int> remap;                                    // declaration index -> index in g.rules
+    for (auto& kv : dfas) { remap[kv.first] = (int)remap.size(); }
+    for (auto& kv : dfas) {
+        const Dfa& d = kv.second;
+        RuleFsm f;
+        f.name = order[(size_t)kv.first];
+        f.decl_index = kv.first;
+        int n = d.n();
+        f.is_final.assign(d.fin.begin(), d.fin.end());
+        f.bedges.resize((size_t)n);
+        f.redges.resize((size_t)n);
+        for (int q = 0; q < n; ++q) {
+            int b = 0;
+            while (b < 256) {
+                int t = d.bt[(size_t)q][(size_t)b];
+                int e = b;
+                while (e + 1 < 256 && d.bt[(size_t)q][(size_t)(e + 1)] == t) ++e;
+                if (t >= 0) f.bedges[(size_t)q].push_back({(uint8_t)b, (uint8_t)e, t});
+                b = e + 1;
+            }
+            for (auto& r : d.rt[(size_t)q]) f.redges[(size_t)q].push_back({remap.at(r.first), r.second});
+        }
+        g.rules.push_back(std::move(f));
+    }
+    g.root = remap.at(index[root_rule]);
+    int R = (int)g.rules.size();
+    // nullable rules (least fixed point) and productivity (every reachable rule must derive a string)
+    auto fixed_point = [&](bool want_nullable) {
+        std::vector<uint8_t> ok((size_t)R, 0);
+        for (bool changed = true; changed;) {
+            changed = false;
+            for (int r = 0; r < R; ++r) {
+                if (ok[(size_t)r]) continue;
+                const RuleFsm& f = g.rules[(size_t)r];
+                std::vector<uint8_t> seen((size_t)f.n_states(), 0);
+                std::vector<int> stack{0};
+                seen[0] = 1;
+                bool hit = false;
+                while (!stack.empty() && !hit) {
+                    int q = stack.back(); stack.pop_back();
+                    if (f.is_final[(size_t)q]) { hit = true; break; }
+                    auto visit = [&](int t) { if (!seen[(size_t)t]) { seen[(size_t)t] = 1; stack.push_back(t); } };
+                    if (!want_nullable) for (auto& e : f.bedges[(size_t)q]) visit(e.tgt);
+                    for (auto& e : f.redges[(size_t)q]) if (ok[(size_t)e.rule]) visit(e.tgt);
+                }
+                if (hit) { ok[(size_t)r] = 1; changed = true; }
+            }
+        }
+        return ok;
+    };
+    std::vector<uint8_t> nullable = fixed_point(true), productive = fixed_point(false);
+    for (int r = 0; r < R; ++r) {
+        g.rules[(size_t)r].nullable = nullable[(size_t)r];
+        if (!productive[(size_t)r]) throw GrammarError("rule " + g.rules[(size_t)r].name + " derives no string (grammar is not reduced)");
+    }
+    g.state_base.resize((size_t)R);
+    g.n_states = 0;
+    for (int r = 0; r < R; ++r) { g.state_base[(size_t)r] = g.n_states; g.n_states += g.rules[(size_t)r].n_states(); }
+    g.sid_to_pos.assign((size_t)g.n_states, -1);
+    for (int r = 0; r < R; ++r)
+        for (int q = 0; q < g.rules[(size_t)r].n_states(); ++q)
+            if (!g.rules[(size_t)r].bedges[(size_t)q].empty()) {
+                g.sid_to_pos[(size_t)g.sid(r, q)] = (int)g.positions.size();
+                g.positions.push_back({r, q, g.sid(r, q)});
+            }
+    hash_rules(g);
+    return g;
+}
+
+std::string describe_grammar(const Grammar& g) {
+    std::ostringstream o;
+    o << "{\"root\":\"" << g.rules[(size_t)g.root].name << "\",\"rules\":[";
+    for (size_t r = 0; r < g.rules.size(); ++r) {
+        const RuleFsm& f = g.rules[r];
+        if (r) o << ",";
+        o << "{\"name\":\"" << f.name << "\",\"decl_index\":" << f.decl_index << ",\"nullable\":" << (f.nullable ? "true" : "false")
+          << ",\"shareable\":" << (f.shareable ? "true" : "false") << ",\"hash\":\"" << std::hex << f.hash << std::dec << "\",\"states\":[";
+        for (int q = 0; q < f.n_states(); ++q) {
+            if (q) o << ",";
+            o << "{\"final\":" << (f.is_final[(size_t)q] ? "true" : "false") << ",\"canon\":" << f.canon_id[(size_t)q] << ",\"bytes\":[";
+            for (size_t k = 0; k < f.bedges[(size_t)q].size(); ++k) {
+                auto& e = f.bedges[(size_t)q][k];
+                if (k) o << ",";
+                o << "[" << (int)e.lo << "," << (int)e.hi << "," << e.tgt << "]";
+            }
+            o << "],\"refs\":[";
+            for (size_t k = 0; k < f.redges[(size_t)q].size(); ++k) {
+                auto& e = f.redges[(size_t)q][k];
+                if (k) o << ",";
+                o << "[\"" << g.rules[(size_t)e.rule].name << "\"," << e.tgt << "]";
+            }
+            o << "]}";
+        }
+        o << "]}";
+    }
+    o << "],\"positions\":[";
+    for (size_t p = 0; p < g.positions.size(); ++p) {
+        if (p) o << ",";
+        o << "[\"" << g.rules[(size_t)g.positions[p].rule].name << "\"," << g.positions[p].state << "]";
+    }
+    o << "]}";
+    return o.str();
+}
+
+}  // namespace xg2

@@ -1,0 +1,60 @@
+// Host-side grammar lowering: EBNF text -> one canonical minimal byte-level automaton per rule
+// (XGrammar-2 section 3.3: "structures are represented as multiple FSMs", edges are character
+// ranges or references to other FSMs), plus the structural hashes of Algorithm 1 / Algorithm 2.
+#pragma once
+#include <cstdint>
+#include <stdexcept>
+#include <string>
+#include <vector>
+
+namespace xg2 {
+
+struct ParseError : std::runtime_error { using std::runtime_error::runtime_error; };
+struct GrammarError : std::runtime_error { using std::runtime_error::runtime_error; };
+
+struct ByteRange { uint8_t lo, hi; int32_t tgt; };   // bytes lo..hi -> rule-local state tgt
+struct RefEdge { int32_t rule; int32_t tgt; };       // reference to Grammar::rules[rule] -> state tgt
+
+struct RuleFsm {
+    std::string name;
+    int32_t decl_index = 0;                           // position of the rule in the EBNF text
+    std::vector<uint8_t> is_final;                    // [n_states]
+    std::vector<std::vector<ByteRange>> bedges;       // sorted by lo; maximal runs per target
+    std::vector<std::vector<RefEdge>> redges;         // sorted by referenced rule's decl_index
+    bool nullable = false;
+    // structural hash (Algorithm 1, refined by Algorithm 2 inside simple reference cycles)
+    uint64_t hash = 0;
+    bool shareable = true;                            // false: member of a non-simple cycle, never reused
+    std::vector<int32_t> canon_id;                    // Algorithm 1 phase 1: state -> canonical id
+    std::vector<std::vector<RefEdge>> redges_by_hash; // out-references in the order Algorithm 1 sorted them
+    std::vector<int32_t> ring;                        // simple cycle through this rule, starting at it (else empty)
+    int32_t n_states() const { return (int32_t)is_final.size(); }
+};
+
+struct Position { int32_t rule, state, sid; };
+
+struct Grammar {
+    std::vector<RuleFsm> rules;                       // rules reachable from the root, in declaration order
+    int32_t root = 0;
+    std::vector<int32_t> state_base;                  // global state id = state_base[rule] + state
+    int32_t n_states = 0;
+    std::vector<Position> positions;                  // states with at least one byte edge
+    std::vector<int32_t> sid_to_pos;                  // [n_states] -> index into positions or -1
+    std::vector<std::vector<int32_t>> hash_order;     // reference-graph components, referenced rules first
+    int32_t sid(int32_t rule, int32_t state) const { return state_base[rule] + state; }
+};
+
+// Throws ParseError (syntax) or GrammarError (undefined rule, empty language, unproductive rule,
+// ill-formed TagDispatch).
+Grammar lower_grammar(const std::string& ebnf, const std::string& root_rule);
+
+std::string describe_grammar(const Grammar& g);       // JSON
+
+uint64_t hash_combine(uint64_t h, uint64_t v);        // the order-sensitive hash of Algorithms 1 and 2
+
+// Exact serialisation of one rule in Algorithm 1's canonical order; a reference to rule r is
+// written as ref_id[r].  Two rules with equal text and equal meaning of the ids are isomorphic.
+std::string serialise_rule(const Grammar& g, int32_t rule, const std::vector<uint64_t>& ref_id);
+constexpr uint64_t kInCycleRef = 0x5EEDF00DCAFEBEEFull;   // the shared placeholder X of Algorithm 2
+
+}  // namespace xg2

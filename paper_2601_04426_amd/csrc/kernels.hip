@@ -1,0 +1,443 @@
+// gfx950 (CDNA4, wave64) kernels of the token-mask cache path:
+//   k_build        classes of (position, token) pairs by a rule-scoped Earley recogniser, one lane per
+//                  token, item sets in LDS                              (XGrammar-2 section 3.4)
+//   k_build_slow   the same recogniser with large item sets in device memory, for lanes that overflowed
+//   k_fill         union of cached planes over the scannable frontier + re-check of uncertain tokens
+//                  against the full Earley context                      (section 3.4, runtime part)
+//   k_apply_*      logits of disallowed tokens := -infinity, in place    (section 2.1)
+// No MFMA: nothing here is a contraction.  All device writes are vector stores or LDS/L2 atomics.
+#include "device.hpp"
+
+namespace xg2 {
+namespace {
+
+constexpr uint32_t SID_BITS = 21;
+constexpr uint32_t SID_MASK = (1u << SID_BITS) - 1;
+constexpr uint32_t ROOT_ORIGIN = (1u << (32 - SID_BITS)) - 1;
+
+constexpr int RES_ALIVE = 1, RES_EARLY = 2, RES_OVERFLOW = 4;
+
+struct DevCtx {                      // closed item set to continue from, plus reachable waiting items
+    const uint32_t* items; uint32_t n_items;
+    const uint32_t* wait; const uint32_t* wait_off; uint32_t H;
+};
+
+// ---- per-lane item storage -------------------------------------------------------------------------
+// LDS: word (slot, lane) lives at slot * 64 + lane, so a wave touching one slot per lane hits every
+// bank once per 32 lanes whatever the slots are.
+template <int K_, int WM_>
+struct LdsStore {
+    static constexpr int K = K_, WM = WM_, MAXLEN = 16, SLOTS = 2 * K_ + WM_;
+    uint32_t* base;                  // &lds[wave_region + lane]
+    uint32_t sel = 0;
+    unsigned long long ws_lo = 0, ws_hi = 0;      // wait-list length at the start of each new set, 8 bits each
+    __device__ uint32_t get_cur(int k) const { return base[(sel * K + k) * 64]; }
+    __device__ void set_cur(int k, uint32_t v) { base[(sel * K + k) * 64] = v; }
+    __device__ uint32_t get_nxt(int k) const { return base[((sel ^ 1) * K + k) * 64]; }
+    __device__ void set_nxt(int k, uint32_t v) { base[((sel ^ 1) * K + k) * 64] = v; }
+    __device__ uint32_t get_wait(int k) const { return base[(2 * K + k) * 64]; }
+    __device__ void set_wait(int k, uint32_t v) { base[(2 * K + k) * 64] = v; }
+    __device__ void swap() { sel ^= 1; }
+    __device__ void set_wstart(int j, uint32_t v) {
+        if (j < 8) ws_lo |= (unsigned long long)v << (8 * j); else ws_hi |= (unsigned long long)v << (8 * (j - 8));
+    }
+    __device__ uint32_t get_wstart(int j) const {
+        return (uint32_t)((j < 8 ? ws_lo >> (8 * j) : ws_hi >> (8 * (j - 8))) & 0xFF);
+    }
+};
+
+// Device memory: word (slot, lane) lives at slot * n_lanes + lane (coalesced across lanes).
+struct GlobalStore {
+    static constexpr int K = kSlowK, WM = kSlowWM, MAXLEN = kSlowMaxLen;
+    uint32_t* base; size_t stride;
+    uint32_t sel = 0;
+    __device__ uint32_t get_cur(int k) const { return base[(size_t)(sel * K + k) * stride]; }
+    __device__ void set_cur(int k, uint32_t v) { base[(size_t)(sel * K + k) * stride] = v; }
+    __device__ uint32_t get_nxt(int k) const { return base[(size_t)((sel ^ 1) * K + k) * stride]; }
+    __device__ void set_nxt(int k, uint32_t v) { base[(size_t)((sel ^ 1) * K + k) * stride] = v; }
+    __device__ uint32_t get_wait(int k) const { return base[(size_t)(2 * K + k) * stride]; }
+    __device__ void set_wait(int k, uint32_t v) { base[(size_t)(2 * K + k) * stride] = v; }
+    __device__ void swap() { sel ^= 1; }
+    __device__ void set_wstart(int j, uint32_t v) { base[(size_t)(2 * K + WM + j) * stride] = v; }
+    __device__ uint32_t get_wstart(int j) const { return base[(size_t)(2 * K + WM + j) * stride]; }
+};
+
+// Put item (sid, origin) into the set under construction unless it is there.  Items whose state has a
+// byte edge (or no edge: they only ever complete) go to `nxt`, items with a rule edge to the wait list.
+// Returns false when a list is full.
+template <class S>
+__device__ __forceinline__ bool add_item(const DevTables& T, S& st, uint32_t sid, uint32_t origin, int& nn, int& nw, int wbeg) {
+    uint4 si = T.state_info[sid];
+    uint32_t nb = si.z & 0xFFFF, nr = si.z >> 16;
+    uint32_t item = sid | (origin << SID_BITS);
+    if (nb > 0 || nr == 0) {
+        for (int k = 0; k < nn; ++k) if (st.get_nxt(k) == item) return true;
+        if (nn == S::K) return false;
+        st.set_nxt(nn++, item);
+    }
+    if (nr > 0) {
+        for (int k = wbeg; k < nw; ++k) if (st.get_wait(k) == item) return true;
+        if (nw == S::WM) return false;
+        st.set_wait(nw++, item);
+    }
+    return true;
+}
+
+// Earley recognition of the n bytes at tok, continuing from context C.  New item sets are numbered
+// C.H, C.H + 1, ...  Returns RES_ALIVE if the set after the last byte is non-empty, RES_EARLY if the
+// root instance could end after some proper non-empty prefix, RES_OVERFLOW if a list filled up.
+template <class S>
+__device__ int scan_token(const DevTables& T, const DevCtx& C, const uint8_t* tok, int n, S& st) {
+    if (n > S::MAXLEN || (int)C.n_items > S::K) return RES_OVERFLOW;
+    int nc = (int)C.n_items;
+    for (int k = 0; k < nc; ++k) st.set_cur(k, C.items[k]);
+    int nw = 0;
+    int res = 0;
+    for (int i = 0; i < n; ++i) {
+        const uint32_t b = tok[i];
+        const uint32_t set_idx = C.H + (uint32_t)i;
+        int nn = 0;
+        const int wbeg = nw;
+        st.set_wstart(i, (uint32_t)nw);
+        // scanner
+        for (int k = 0; k < nc; ++k) {
+            uint32_t it = st.get_cur(k);
+            uint4 si = T.state_info[it & SID_MASK];
+            uint32_t nb = si.z & 0xFFFF;
+            for (uint32_t e = 0; e < nb; ++e) {
+                uint2 be = T.byte_edges[si.x + e];
+                if (b >= (be.x & 0xFF) && b <= ((be.x >> 8) & 0xFF)) {
+                    if (!add_item(T, st, be.y, it >> SID_BITS, nn, nw, wbeg)) return RES_OVERFLOW;
+                    break;                                   // the rule automaton is deterministic
+                }
+            }
+        }
+        // predictor and completer over the growing lists
+        bool root_now = false;
+        int pn = 0, pw = wbeg;
+        while (pn < nn || pw < nw) {
+            const bool from_nxt = pn < nn;
+            uint32_t it = from_nxt ? st.get_nxt(pn++) : st.get_wait(pw++);
+            uint32_t origin = it >> SID_BITS;
+            uint4 si = T.state_info[it & SID_MASK];
+            uint32_t nb = si.z & 0xFFFF, nr = si.z >> 16;
+            if (!from_nxt) {
+                for (uint32_t e = 0; e < nr; ++e) {
+                    uint2 re = T.ref_edges[si.y + e];
+                    uint2 ri = T.rule_info[re.x];
+                    if (!add_item(T, st, ri.x, set_idx, nn, nw, wbeg)) return RES_OVERFLOW;
+                    if (ri.y && !add_item(T, st, re.y, origin, nn, nw, wbeg)) return RES_OVERFLOW;   // nullable rule
+                }
+            }
+            const bool in_nxt = nb > 0 || nr == 0;
+            if ((si.w >> 31) && from_nxt == in_nxt) {          // final state: complete, once per item
+                uint32_t rule = si.w & 0x7FFFFFFFu;
+                if (origin == ROOT_ORIGIN) root_now = true;
+                else if (origin != set_idx) {
+                    const bool local = origin >= C.H;
+                    int lo = local ? (int)st.get_wstart((int)(origin - C.H)) : (int)C.wait_off[origin];
+                    int hi = local ? (int)st.get_wstart((int)(origin - C.H) + 1) : (int)C.wait_off[origin + 1];
+                    for (int k = lo; k < hi; ++k) {
+                        uint32_t w = local ? st.get_wait(k) : C.wait[k];
+                        uint4 wi = T.state_info[w & SID_MASK];
+                        uint32_t wr = wi.z >> 16;
+                        for (uint32_t e = 0; e < wr; ++e) {
+                            uint2 re = T.ref_edges[wi.y + e];
+                            if (re.x == rule && !add_item(T, st, re.y, w >> SID_BITS, nn, nw, wbeg)) return RES_OVERFLOW;
+                        }
+                    }
+                }
+            }
+        }
+        if (nn == 0 && nw == wbeg) return res;               // dead: nothing survives this byte
+        if (root_now && i + 1 < n) res |= RES_EARLY;
+        st.swap();
+        nc = nn;
+    }
+    return res | RES_ALIVE;
+}
+
+constexpr int BUILD_K = 12, BUILD_WM = 24;
+constexpr int BUILD_WAVES = 4;
+using BuildStore = LdsStore<BUILD_K, BUILD_WM>;
+
+__device__ __forceinline__ void push_overflow(const SlowScratch& S, uint32_t a, uint32_t b) {
+    uint32_t idx = atomicAdd(S.count, 1u);
+    if (idx < S.list_cap) { S.list[2 * idx] = a; S.list[2 * idx + 1] = b; }
+    else atomicOr(S.count + 1, 1u);
+}
+
+__device__ __forceinline__ DevCtx position_ctx(const BuildPlan& P, uint32_t p) {
+    DevCtx C;
+    C.items = P.ctx_items + P.ctx_item_off[p];
+    C.n_items = P.ctx_item_off[p + 1] - P.ctx_item_off[p];
+    C.wait = P.ctx_wait;
+    C.wait_off = P.ctx_wait_off2 + 2 * p;
+    C.H = 1;
+    return C;
+}
+
+__device__ __forceinline__ void store_class(const BuildPlan& P, uint32_t p, uint32_t W, uint32_t id, int res) {
+    uint32_t* row = P.plane_ptr[p];
+    if (res & RES_ALIVE) atomicOr(row + (id >> 5), 1u << (id & 31));
+    else if (res & RES_EARLY) atomicOr(row + W + (id >> 5), 1u << (id & 31));
+}
+
+__global__ __launch_bounds__(64 * BUILD_WAVES) void k_build(DevTables T, DevVocab Vd, BuildPlan P, SlowScratch S) {
+    __shared__ uint32_t lds[BUILD_WAVES * BuildStore::SLOTS * 64];
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint32_t blk = blockIdx.x * BUILD_WAVES + wave;
+    if (blk >= P.n_blocks) return;
+    // segment holding this block: last s with seg_blk[s] <= blk
+    uint32_t lo = 0, hi = P.n_seg;
+    while (hi - lo > 1) { uint32_t mid = (lo + hi) >> 1; if (P.seg_blk[mid] <= blk) lo = mid; else hi = mid; }
+    const uint32_t p = P.seg_pos[lo];
+    const uint32_t rank = P.seg_lo[lo] + (blk - P.seg_blk[lo]) * 64 + lane;
+    if (rank >= P.seg_hi[lo]) return;
+    const uint32_t off = Vd.off[rank];
+    const int n = (int)(Vd.off[rank + 1] - off);
+    BuildStore st;
+    st.base = lds + wave * BuildStore::SLOTS * 64 + lane;
+    DevCtx C = position_ctx(P, p);
+    int res = scan_token(T, C, Vd.bytes + off, n, st);
+    if (res & RES_OVERFLOW) { push_overflow(S, p, rank); return; }
+    store_class(P, p, Vd.W, Vd.perm[rank], res);
+}
+
+__global__ __launch_bounds__(64) void k_build_slow(DevTables T, DevVocab Vd, BuildPlan P, SlowScratch S) {
+    const uint32_t gl = blockIdx.x * 64 + threadIdx.x;
+    uint32_t count = S.count[0];
+    if (count > S.list_cap) count = S.list_cap;
+    GlobalStore st;
+    st.base = S.mem + gl;
+    st.stride = S.n_lanes;
+    for (uint32_t idx = gl; idx < count; idx += S.n_lanes) {
+        const uint32_t p = S.list[2 * idx], rank = S.list[2 * idx + 1];
+        const uint32_t off = Vd.off[rank];
+        const int n = (int)(Vd.off[rank + 1] - off);
+        st.sel = 0;
+        DevCtx C = position_ctx(P, p);
+        int res = scan_token(T, C, Vd.bytes + off, n, st);
+        if (res & RES_OVERFLOW) { atomicOr(S.count + 1, 2u); continue; }
+        store_class(P, p, Vd.W, Vd.perm[rank], res);
+    }
+}
+
+__global__ __launch_bounds__(256) void k_popcount(const uint32_t* const* plane_ptr, uint32_t n_pos, uint32_t W, unsigned long long* out2) {
+    const uint32_t p = blockIdx.x;
+    if (p >= n_pos) return;
+    const uint32_t* row = plane_ptr[p];
+    unsigned long long a = 0, u = 0;
+    for (uint32_t w = threadIdx.x; w < W; w += blockDim.x) { a += __popc(row[w]); u += __popc(row[W + w]); }
+    for (int s = 32; s > 0; s >>= 1) { a += __shfl_down(a, s); u += __shfl_down(u, s); }
+    if ((threadIdx.x & 63) == 0) { atomicAdd(out2, a); atomicAdd(out2 + 1, u); }
+}
+
+// ---- fill ------------------------------------------------------------------------------------------
+constexpr int FILL_THREADS = 128, FILL_WORDS = 128;       // one word of one row per thread
+constexpr int FILL_K = 12, FILL_WM = 24;
+using FillStore = LdsStore<FILL_K, FILL_WM>;
+
+__device__ __forceinline__ DevCtx row_ctx(const FillBatch& F, const FillRow& r) {
+    DevCtx C;
+    C.items = F.ctx_items + r.item_off;
+    C.n_items = r.item_n;
+    C.wait = F.ctx_wait + r.wait_base;
+    C.wait_off = F.ctx_wait_off + r.waitoff_off;
+    C.H = r.H;
+    return C;
+}
+
+__global__ __launch_bounds__(FILL_THREADS) void k_fill(FillBatch F, DevVocab Vd, int32_t* bitmask, long long row_stride, SlowScratch S) {
+    __shared__ uint32_t lds_store[(FILL_THREADS / 64) * FillStore::SLOTS * 64];
+    __shared__ uint32_t out_words[FILL_WORDS];
+    __shared__ uint32_t queue[FILL_WORDS * 32];
+    __shared__ uint32_t qn;
+    const uint32_t b = blockIdx.y;
+    const uint32_t w0 = blockIdx.x * FILL_WORDS;
+    const FillRow r = F.rows[b];
+    if (threadIdx.x == 0) qn = 0;
+    __syncthreads();
+    if (threadIdx.x < FILL_WORDS) {
+        const uint32_t w = w0 + threadIdx.x;
+        uint32_t acc = 0, cand = 0;
+        if (w < Vd.W) {
+            if (!(r.flags & 2u)) {
+                uint32_t unc = 0;
+                for (uint32_t k = 0; k < r.front_n; ++k) {
+                    const uint32_t* row = reinterpret_cast<const uint32_t*>(F.front_planes[r.front_off + k]);
+                    acc |= row[w];
+                    unc |= row[Vd.W + w];
+                }
+                cand = unc & ~acc;
+            }
+            if ((r.flags & 3u) && (F.eos_id >> 5) == w) acc |= 1u << (F.eos_id & 31);
+        }
+        out_words[threadIdx.x] = acc;
+        if (cand) {
+            uint32_t pos = atomicAdd(&qn, (uint32_t)__popc(cand));
+            while (cand) { uint32_t bit = __ffs(cand) - 1; cand &= cand - 1; queue[pos++] = w * 32 + bit; }
+        }
+    }
+    __syncthreads();
+    const uint32_t n_q = qn;
+    if (n_q) {
+        const DevTables T = F.tables[r.tables_idx];
+        const DevCtx C = row_ctx(F, r);
+        FillStore st;
+        st.base = lds_store + (threadIdx.x >> 6) * FillStore::SLOTS * 64 + (threadIdx.x & 63);
+        for (uint32_t q = threadIdx.x; q < n_q; q += FILL_THREADS) {
+            const uint32_t id = queue[q];
+            const uint32_t rank = Vd.rank[id];
+            if (rank >= Vd.n_sorted) continue;                   // never a checkable token
+            const uint32_t off = Vd.off[rank];
+            const int n = (int)(Vd.off[rank + 1] - off);
+            st.sel = 0; st.ws_lo = 0; st.ws_hi = 0;
+            int res = scan_token(T, C, Vd.bytes + off, n, st);
+            if (res & RES_OVERFLOW) push_overflow(S, b, id);
+            else if (res & RES_ALIVE) atomicOr(&out_words[(id >> 5) - w0], 1u << (id & 31));
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x < FILL_WORDS && w0 + threadIdx.x < Vd.W)
+        bitmask[(long long)b * row_stride + w0 + threadIdx.x] = (int32_t)out_words[threadIdx.x];
+}
+
+__global__ __launch_bounds__(64) void k_recheck_slow(FillBatch F, DevVocab Vd, int32_t* bitmask, long long row_stride, SlowScratch S) {
+    const uint32_t gl = blockIdx.x * 64 + threadIdx.x;
+    uint32_t count = S.count[0];
+    if (count > S.list_cap) count = S.list_cap;
+    GlobalStore st;
+    st.base = S.mem + gl;
+    st.stride = S.n_lanes;
+    for (uint32_t idx = gl; idx < count; idx += S.n_lanes) {
+        const uint32_t b = S.list[2 * idx], id = S.list[2 * idx + 1];
+        const FillRow r = F.rows[b];
+        const uint32_t rank = Vd.rank[id];
+        if (rank >= Vd.n_sorted) continue;
+        const uint32_t off = Vd.off[rank];
+        const int n = (int)(Vd.off[rank + 1] - off);
+        st.sel = 0;
+        int res = scan_token(F.tables[r.tables_idx], row_ctx(F, r), Vd.bytes + off, n, st);
+        if (res & RES_OVERFLOW) { atomicOr(S.count + 1, 2u); continue; }
+        if (res & RES_ALIVE) atomicOr(reinterpret_cast<uint32_t*>(bitmask) + (long long)b * row_stride + (id >> 5), 1u << (id & 31));
+    }
+}
+
+// ---- apply -----------------------------------------------------------------------------------------
+// One 16-byte vector per thread per step: 4 fp32 or 8 bf16.  A vector whose tokens are all allowed is
+// left alone (no read, no write); one whose tokens are all disallowed is overwritten without a read;
+// only mixed vectors are read, merged and written back.
+constexpr int APPLY_THREADS = 256, APPLY_VECS = 4;
+
+template <int EPV /* elements per 16-byte vector */>
+__global__ __launch_bounds__(APPLY_THREADS) void k_apply_vec(uint4* logits, long long row_stride_vecs, int n_vecs,
+                                                             const uint32_t* bitmask, long long bm_stride) {
+    const long long b = blockIdx.y;
+    uint4* row = logits + b * row_stride_vecs;
+    const uint32_t* bm = bitmask + b * bm_stride;
+    const int v0 = blockIdx.x * (APPLY_THREADS * APPLY_VECS) + threadIdx.x;
+#pragma unroll
+    for (int j = 0; j < APPLY_VECS; ++j) {
+        const int v = v0 + j * APPLY_THREADS;
+        if (v >= n_vecs) break;
+        const int e0 = v * EPV;
+        const uint32_t bits = (bm[e0 >> 5] >> (e0 & 31)) & ((1u << EPV) - 1);
+        if (bits == (1u << EPV) - 1) continue;
+        uint4 x;
+        if (EPV == 4) {
+            const uint32_t NINF = 0xFF800000u;
+            if (bits == 0) x = make_uint4(NINF, NINF, NINF, NINF);
+            else {
+                x = row[v];
+                if (!(bits & 1)) x.x = NINF;
+                if (!(bits & 2)) x.y = NINF;
+                if (!(bits & 4)) x.z = NINF;
+                if (!(bits & 8)) x.w = NINF;
+            }
+        } else {
+            const uint32_t NINF2 = 0xFF80FF80u;
+            if (bits == 0) x = make_uint4(NINF2, NINF2, NINF2, NINF2);
+            else {
+                x = row[v];
+                auto merge = [](uint32_t w, uint32_t two) {
+                    if (!(two & 1)) w = (w & 0xFFFF0000u) | 0xFF80u;
+                    if (!(two & 2)) w = (w & 0x0000FFFFu) | 0xFF800000u;
+                    return w;
+                };
+                x.x = merge(x.x, bits); x.y = merge(x.y, bits >> 2); x.z = merge(x.z, bits >> 4); x.w = merge(x.w, bits >> 6);
+            }
+        }
+        row[v] = x;
+    }
+}
+
+// Any alignment, any stride; also the tail after the last whole vector.
+template <typename E>
+__global__ __launch_bounds__(256) void k_apply_scalar(E* logits, long long row_stride, int v_begin, int V,
+                                                      const uint32_t* bitmask, long long bm_stride, E ninf) {
+    const long long b = blockIdx.y;
+    const int v = v_begin + blockIdx.x * 256 + threadIdx.x;
+    if (v >= V) return;
+    if (!((bitmask[b * bm_stride + (v >> 5)] >> (v & 31)) & 1u)) logits[b * row_stride + v] = ninf;
+}
+
+}  // namespace
+
+void launch_build(const DevTables& T, const DevVocab& Vd, const BuildPlan& P, const SlowScratch& S, hipStream_t stream) {
+    if (P.n_blocks == 0) return;
+    uint32_t grid = (P.n_blocks + BUILD_WAVES - 1) / BUILD_WAVES;
+    hipLaunchKernelGGL(k_build, dim3(grid), dim3(64 * BUILD_WAVES), 0, stream, T, Vd, P, S);
+}
+
+void launch_build_slow(const DevTables& T, const DevVocab& Vd, const BuildPlan& P, const SlowScratch& S, hipStream_t stream) {
+    hipLaunchKernelGGL(k_build_slow, dim3(S.n_lanes / 64), dim3(64), 0, stream, T, Vd, P, S);
+}
+
+void launch_popcount(const uint32_t* const* plane_ptr_dev, uint32_t n_pos, uint32_t W, unsigned long long* out2_dev, hipStream_t stream) {
+    if (n_pos == 0) return;
+    hipLaunchKernelGGL(k_popcount, dim3(n_pos), dim3(256), 0, stream, plane_ptr_dev, n_pos, W, out2_dev);
+}
+
+void launch_fill(const FillBatch& F, const DevVocab& Vd, int32_t* bitmask_dev, int64_t row_stride_words,
+                 const SlowScratch& S, hipStream_t stream) {
+    if (F.B == 0) return;
+    dim3 grid((Vd.W + FILL_WORDS - 1) / FILL_WORDS, F.B);
+    hipLaunchKernelGGL(k_fill, grid, dim3(FILL_THREADS), 0, stream, F, Vd, bitmask_dev, (long long)row_stride_words, S);
+}
+
+void launch_recheck_slow(const FillBatch& F, const DevVocab& Vd, int32_t* bitmask_dev, int64_t row_stride_words,
+                         const SlowScratch& S, hipStream_t stream) {
+    hipLaunchKernelGGL(k_recheck_slow, dim3(S.n_lanes / 64), dim3(64), 0, stream, F, Vd, bitmask_dev, (long long)row_stride_words, S);
+}
+
+void launch_apply(void* logits_dev, int32_t dtype, int32_t B, int32_t V, int64_t row_stride_elems,
+                  const int32_t* bitmask_dev, int64_t bm_row_stride_words, hipStream_t stream) {
+    if (B == 0 || V == 0) return;
+    const int esize = dtype == 0 ? 4 : 2;
+    const int epv = 16 / esize;
+    const bool aligned = (reinterpret_cast<uintptr_t>(logits_dev) % 16 == 0) && ((row_stride_elems * esize) % 16 == 0);
+    const int n_vecs = aligned ? V / epv : 0;
+    const uint32_t* bm = reinterpret_cast<const uint32_t*>(bitmask_dev);
+    if (n_vecs > 0) {
+        dim3 grid((n_vecs + APPLY_THREADS * APPLY_VECS - 1) / (APPLY_THREADS * APPLY_VECS), B);
+        if (dtype == 0)
+            hipLaunchKernelGGL(k_apply_vec<4>, grid, dim3(APPLY_THREADS), 0, stream, (uint4*)logits_dev,
+                               (long long)(row_stride_elems / 4), n_vecs, bm, (long long)bm_row_stride_words);
+        else
+            hipLaunchKernelGGL(k_apply_vec<8>, grid, dim3(APPLY_THREADS), 0, stream, (uint4*)logits_dev,
+                               (long long)(row_stride_elems / 8), n_vecs, bm, (long long)bm_row_stride_words);
+    }
+    const int v_begin = n_vecs * epv;
+    if (v_begin < V) {
+        dim3 grid((V - v_begin + 255) / 256, B);
+        if (dtype == 0)
+            hipLaunchKernelGGL(k_apply_scalar<uint32_t>, grid, dim3(256), 0, stream, (uint32_t*)logits_dev, (long long)row_stride_elems,
+                               v_begin, V, bm, (long long)bm_row_stride_words, 0xFF800000u);
+        else
+            hipLaunchKernelGGL(k_apply_scalar<uint16_t>, grid, dim3(256), 0, stream, (uint16_t*)logits_dev, (long long)row_stride_elems,
+                               v_begin, V, bm, (long long)bm_row_stride_words, (uint16_t)0xFF80);
+    }
+}
+
+}  // namespace xg2

@@ -1,0 +1,125 @@
+#include "tables.hpp"
+
+#include <algorithm>
+#include <map>
+
+namespace xg2 {
+
+FlatTables flatten(const Grammar& g) {
+    FlatTables t;
+    t.state_info.resize((size_t)g.n_states);
+    t.rule_info.resize(g.rules.size());
+    for (size_t r = 0; r < g.rules.size(); ++r) {
+        const RuleFsm& f = g.rules[r];
+        t.rule_info[r] = {(uint32_t)g.sid((int32_t)r, 0), f.nullable ? 1u : 0u};
+        for (int q = 0; q < f.n_states(); ++q) {
+            StateInfo si;
+            si.byte_off = (uint32_t)t.byte_edges.size();
+            si.ref_off = (uint32_t)t.ref_edges.size();
+            for (auto& e : f.bedges[(size_t)q]) t.byte_edges.push_back({(uint32_t)e.lo | ((uint32_t)e.hi << 8), (uint32_t)g.sid((int32_t)r, e.tgt)});
+            for (auto& e : f.redges[(size_t)q]) t.ref_edges.push_back({(uint32_t)e.rule, (uint32_t)g.sid((int32_t)r, e.tgt)});
+            si.counts = (uint32_t)f.bedges[(size_t)q].size() | ((uint32_t)f.redges[(size_t)q].size() << 16);
+            si.rule_final = (uint32_t)r | (f.is_final[(size_t)q] ? 0x80000000u : 0u);
+            t.state_info[(size_t)g.sid((int32_t)r, q)] = si;
+        }
+    }
+    t.root_start = (uint32_t)g.sid(g.root, 0);
+    return t;
+}
+
+namespace {
+inline bool has(const std::vector<ChartItem>& v, ChartItem it) {
+    for (auto& x : v) if (x.sid == it.sid && x.origin == it.origin) return true;
+    return false;
+}
+}  // namespace
+
+// Predictor and completer until nothing new.  A predicted rule that can derive the empty string
+// also advances the predicting item at once, so completions with origin == index need no lookup.
+void EarleyChart::close(ChartSet& set, int32_t index, std::vector<ChartItem>& pending) {
+    while (!pending.empty()) {
+        ChartItem it = pending.back();
+        pending.pop_back();
+        const StateInfo& si = t_->state_info[it.sid];
+        uint32_t nb = si.counts & 0xFFFF, nr = si.counts >> 16;
+        bool in_scan = nb > 0 || nr == 0, in_wait = nr > 0;
+        if (in_scan) { if (has(set.scan, it)) continue; set.scan.push_back(it); }
+        if (in_wait) { if (has(set.wait, it)) continue; set.wait.push_back(it); }
+        for (uint32_t k = 0; k < nr; ++k) {
+            const RefEdgeP& e = t_->ref_edges[si.ref_off + k];
+            pending.push_back({t_->rule_info[e.rule].start, index});
+            if (t_->rule_info[e.rule].nullable) pending.push_back({e.tgt, it.origin});
+        }
+        if (si.rule_final & 0x80000000u) {
+            uint32_t rule = si.rule_final & 0x7FFFFFFFu;
+            if (it.origin < 0) set.root_done = true;
+            else if (it.origin != index)
+                for (const ChartItem& w : chart_[(size_t)it.origin].wait) {
+                    const StateInfo& wi = t_->state_info[w.sid];
+                    for (uint32_t k = 0; k < (wi.counts >> 16); ++k) {
+                        const RefEdgeP& e = t_->ref_edges[wi.ref_off + k];
+                        if (e.rule == rule) pending.push_back({e.tgt, w.origin});
+                    }
+                }
+        }
+    }
+}
+
+void EarleyChart::start(uint32_t sid) {
+    chart_.clear();
+    chart_.emplace_back();
+    std::vector<ChartItem> pending{{sid, -1}};
+    close(chart_[0], 0, pending);
+}
+
+bool EarleyChart::advance(const uint8_t* bytes, size_t n) {
+    size_t keep = chart_.size();
+    std::vector<ChartItem> pending;
+    for (size_t i = 0; i < n; ++i) {
+        uint8_t b = bytes[i];
+        pending.clear();
+        for (const ChartItem& it : chart_.back().scan) {
+            const StateInfo& si = t_->state_info[it.sid];
+            for (uint32_t k = 0; k < (si.counts & 0xFFFF); ++k) {
+                const ByteEdge& e = t_->byte_edges[si.byte_off + k];
+                if (b >= (e.lohi & 0xFF) && b <= ((e.lohi >> 8) & 0xFF)) { pending.push_back({e.tgt, it.origin}); break; }
+            }
+        }
+        chart_.emplace_back();
+        close(chart_.back(), (int32_t)chart_.size() - 1, pending);
+        if (chart_.back().scan.empty() && chart_.back().wait.empty()) { chart_.resize(keep); return false; }
+    }
+    return true;
+}
+
+bool EarleyChart::context(ScanContext& out) const {
+    out.items.clear(); out.wait.clear(); out.wait_off.clear();
+    int32_t J = (int32_t)chart_.size() - 1;
+    // sets reachable through origins, starting from the current set
+    std::vector<int32_t> needed{J}, stack{J};
+    std::map<int32_t, uint32_t> local;
+    auto reach = [&](int32_t o) {
+        if (o >= 0 && !std::binary_search(needed.begin(), needed.end(), o)) {
+            needed.insert(std::upper_bound(needed.begin(), needed.end(), o), o);
+            stack.push_back(o);
+        }
+    };
+    for (const ChartItem& it : chart_[(size_t)J].scan) reach(it.origin);
+    while (!stack.empty()) {
+        int32_t s = stack.back(); stack.pop_back();
+        for (const ChartItem& w : chart_[(size_t)s].wait) reach(w.origin);
+    }
+    if (needed.size() > kMaxLocalSets - 64) return false;
+    for (size_t k = 0; k < needed.size(); ++k) local[needed[k]] = (uint32_t)k;
+    out.H = (uint32_t)needed.size();
+    auto loc = [&](int32_t o) { return o < 0 ? kRootOrigin : local.at(o); };
+    for (const ChartItem& it : chart_[(size_t)J].scan) out.items.push_back(pack_item(it.sid, loc(it.origin)));
+    for (size_t k = 0; k < needed.size(); ++k) {
+        out.wait_off.push_back((uint32_t)out.wait.size());
+        for (const ChartItem& w : chart_[(size_t)needed[k]].wait) out.wait.push_back(pack_item(w.sid, loc(w.origin)));
+    }
+    out.wait_off.push_back((uint32_t)out.wait.size());
+    return true;
+}
+
+}  // namespace xg2

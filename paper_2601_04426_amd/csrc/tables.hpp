@@ -1,0 +1,71 @@
+// Packed grammar tables shared by the host matcher and the device kernels (same words on both
+// sides), and the host Earley parser that follows a sequence (XGrammar-2 section 3.4 and the
+// appendix "Earley's Parsing Algorithm": predict / scan / complete over the per-rule automata).
+#pragma once
+#include <cstdint>
+#include <memory>
+#include <vector>
+
+#include "grammar.hpp"
+
+namespace xg2 {
+
+// An Earley item in 32 bits: global state id | origin << 21.  The origin is the index of the item
+// set in which the rule instance started, or kRootOrigin for the instance nobody is waiting for.
+constexpr uint32_t kSidBits = 21;
+constexpr uint32_t kSidMask = (1u << kSidBits) - 1;
+constexpr uint32_t kRootOrigin = (1u << (32 - kSidBits)) - 1;     // 2047
+constexpr uint32_t kMaxLocalSets = kRootOrigin - 1;
+inline uint32_t pack_item(uint32_t sid, uint32_t origin) { return sid | (origin << kSidBits); }
+
+struct StateInfo { uint32_t byte_off, ref_off, counts /* n_byte | n_ref << 16 */, rule_final /* rule | final << 31 */; };
+struct ByteEdge { uint32_t lohi /* lo | hi << 8 */, tgt; };
+struct RefEdgeP { uint32_t rule, tgt; };
+struct RuleInfo { uint32_t start, nullable; };
+
+struct FlatTables {
+    std::vector<StateInfo> state_info;
+    std::vector<ByteEdge> byte_edges;
+    std::vector<RefEdgeP> ref_edges;
+    std::vector<RuleInfo> rule_info;
+    uint32_t root_start = 0;
+};
+
+FlatTables flatten(const Grammar& g);
+
+// One closed Earley item set of the host parser.  `scan` holds the items whose state has a byte
+// edge or no edge at all, `wait` those whose state has a rule edge (an item can be in both).
+// Origins are chart indices; -1 marks the root instance.
+struct ChartItem { uint32_t sid; int32_t origin; };            // origin -1 = root instance
+struct ChartSet {
+    std::vector<ChartItem> scan, wait;
+    bool root_done = false;
+};
+
+// The context a kernel needs to continue parsing from a closed set: that set's scan items plus the
+// waiting items of every set reachable through origins, with set indices renumbered 0..H-1 (the
+// current set is H-1).
+struct ScanContext {
+    std::vector<uint32_t> items;       // packed (sid, local origin)
+    std::vector<uint32_t> wait;        // packed, grouped by local set
+    std::vector<uint32_t> wait_off;    // [H+1]
+    uint32_t H = 0;
+};
+
+class EarleyChart {
+  public:
+    explicit EarleyChart(const FlatTables* t) : t_(t) {}
+    void start(uint32_t sid);                        // chart = closure{(sid, root instance)}
+    bool advance(const uint8_t* bytes, size_t n);    // all or nothing: false leaves the chart unchanged
+    const ChartSet& last() const { return chart_.back(); }
+    size_t length() const { return chart_.size(); }
+    // false if more than kMaxLocalSets sets are reachable
+    bool context(ScanContext& out) const;
+
+  private:
+    const FlatTables* t_;
+    std::vector<ChartSet> chart_;
+    void close(ChartSet& set, int32_t index, std::vector<ChartItem>& pending);
+};
+
+}  // namespace xg2
