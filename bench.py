@@ -1,0 +1,219 @@
+#!/usr/bin/env python3
+"""Benchmark of the token-mask cache hot path on one MI355X.
+
+A step is one pass of the whole path over one batch of the "runtime stress" workload
+(V = 151,936, 1024 concurrent matchers): build the mask cache of the grammar (every position x
+every token), fill the batch's next-token bitmask (cached planes + re-check of uncertain tokens),
+apply it to bf16 logits and to fp32 logits, then advance every matcher by one token on the host.
+
+Prints ONE JSON line.  `value` = (position, token) checks per second of the cache build, from the
+build's device time (HIP events inside the library: table upload to last plane written); the
+fill+apply microseconds per step, the host times and the wall-clock per step are given beside it.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import random
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=5, help="workload index (5 = runtime stress, the metric's configuration)")
+    ap.add_argument("--batch", type=int, default=None)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-positions", type=int, default=4096, help="positions in the oracle's timed sample")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this path runs on one GPU; --gpus above 1 is not supported (no sharding, no collectives)", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import gen
+    import paper_2601_04426_amd as xg
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the hot path has no CPU fallback", file=sys.stderr)
+        return 3
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    stream = torch.cuda.current_stream().cuda_stream
+
+    cfg = gen.build_config(args.config)
+    ebnf, root = cfg.grammars[0]
+    B = args.batch or cfg.batch or 256
+    V = cfg.vocab.size
+    vocab = xg.Vocab(cfg.vocab.tokens, cfg.vocab.eos_id, cfg.vocab.special_ids)
+    W = vocab.words
+    n_checkable = sum(1 for i, t in enumerate(cfg.vocab.tokens) if t and i not in cfg.vocab.special_ids)
+    tok_bytes = sum(len(t) for i, t in enumerate(cfg.vocab.tokens) if t and i not in cfg.vocab.special_ids)
+
+    # matchers at random depths of their own sentences (set-up, untimed)
+    cache0 = xg.compile_grammar(vocab, ebnf, root, stream=stream)
+    rng = random.Random(gen.BASE_SEED + 100 + args.config)
+    seg = gen.Segmenter(cfg.vocab)
+    matchers = [xg.Matcher(cache0) for _ in range(B)]
+    traces, cursor = [], []
+    for b in range(B):
+        ids = seg.segment(cfg.sample_text(rng, 0), rng) + [cfg.vocab.eos_id]
+        depth = rng.randrange(0, max(1, len(ids) - 1))
+        for t in ids[:depth]:
+            assert matchers[b].accept_token(t)
+        traces.append(ids)
+        cursor.append(depth)
+    batch = xg.MatcherBatch(matchers)
+
+    g = torch.Generator(device="cpu").manual_seed(1234)
+    logits32_src = torch.randn((B, V), generator=g, dtype=torch.float32).to(dev)
+    logits16_src = logits32_src.to(torch.bfloat16)
+    logits32 = torch.empty_like(logits32_src)
+    logits16 = torch.empty_like(logits16_src)
+    bitmask = torch.zeros((B, W), dtype=torch.int32, device=dev)
+
+    def advance():
+        for b in range(B):
+            if matchers[b].is_terminated():
+                matchers[b].reset()
+                ids = seg.segment(cfg.sample_text(rng, 0), rng) + [cfg.vocab.eos_id]
+                traces[b], cursor[b] = ids, 0
+                continue
+            ok = matchers[b].accept_token(traces[b][cursor[b]])
+            assert ok
+            cursor[b] += 1
+
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(5)]
+    acc = {"build_device_ms": [], "build_kernel_ms": [], "build_host_ms": [], "fill_us": [], "apply_bf16_us": [],
+           "apply_f32_us": [], "fill_host_ms": [], "accept_host_ms": [], "masked_frac": []}
+    last_stats = None
+
+    def step(record: bool):
+        nonlocal last_stats
+        # logits of this step (untimed refresh: apply works in place)
+        logits16.copy_(logits16_src)
+        logits32.copy_(logits32_src)
+        cache = xg.compile_grammar(vocab, ebnf, root, stream=stream)          # a2: builds every position afresh
+        st = cache.stats
+        t0 = time.perf_counter()
+        ev[0].record()
+        xg.fill_next_token_bitmask(batch, bitmask.data_ptr(), W, stream)      # a3 + a4
+        t1 = time.perf_counter()
+        ev[1].record()
+        xg.apply_token_bitmask(logits16.data_ptr(), xg.XG2_BF16, B, V, V, bitmask.data_ptr(), W, stream)   # a5
+        ev[2].record()
+        xg.apply_token_bitmask(logits32.data_ptr(), xg.XG2_F32, B, V, V, bitmask.data_ptr(), W, stream)
+        ev[3].record()
+        t2 = time.perf_counter()
+        advance()                                                             # a6 (host)
+        t3 = time.perf_counter()
+        ev[3].synchronize()
+        if record:
+            last_stats = st
+            acc["build_device_ms"].append(st.device_ms)
+            acc["build_kernel_ms"].append(st.kernel_ms)
+            acc["build_host_ms"].append(st.host_lower_ms)
+            acc["fill_us"].append(ev[0].elapsed_time(ev[1]) * 1e3)
+            acc["apply_bf16_us"].append(ev[1].elapsed_time(ev[2]) * 1e3)
+            acc["apply_f32_us"].append(ev[2].elapsed_time(ev[3]) * 1e3)
+            acc["fill_host_ms"].append((t1 - t0) * 1e3)
+            acc["accept_host_ms"].append((t3 - t2) * 1e3)
+        del cache
+
+    for _ in range(args.warmup):
+        step(False)
+    torch.cuda.synchronize()
+    t_begin = time.perf_counter()
+    for _ in range(args.steps):
+        step(True)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t_begin
+
+    # fraction of logits masked in the last step (for the store-only accounting of apply)
+    allowed = 0
+    bm = bitmask.cpu().numpy().view(np.uint32)
+    allowed = int(np.unpackbits(bm.view(np.uint8)).sum())
+    masked = B * V - allowed
+
+    mean = lambda xs: float(sum(xs) / len(xs))
+    med = lambda xs: float(sorted(xs)[len(xs) // 2])
+    st = last_stats
+    build_ms = mean(acc["build_device_ms"])
+    kernel_ms = mean(acc["build_kernel_ms"])
+    checks = int(st.checks)
+    value = checks / (build_ms * 1e-3)
+    # algorithmic bytes of the build per launch: per (position, token) len(t) + 4 bytes in, 2 bits out
+    build_bytes = int(st.built) * (tok_bytes + 4 * n_checkable + n_checkable / 4.0)
+    build_gbs = build_bytes / (kernel_ms * 1e-3) / 1e9
+    out = {
+        "metric": "mask-cache build (position x token) checks/s; batch-%d mask fill+apply us/step" % B,
+        "value": value,
+        "unit": "checks/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": wall / args.steps * 1e3,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "u8",
+        "data": "synthetic",
+        "config": {"workload": cfg.name, "config_index": cfg.index, "vocab": V, "batch": B, "positions": int(st.positions),
+                   "unique_positions": int(st.unique), "built_positions": int(st.built), "checks_per_build": checks,
+                   "executed_checks": int(st.executed_checks), "slow_path_checks": int(st.slow_path),
+                   "value_basis": "device time of one cache build (HIP events: table upload to last plane), host lowering beside it"},
+        "build": {"device_ms": build_ms, "kernel_ms": kernel_ms, "host_lower_ms": mean(acc["build_host_ms"]),
+                  "n_accepted_bits": int(st.n_accepted), "n_uncertain_bits": int(st.n_uncertain)},
+        "decode": {"fill_us": med(acc["fill_us"]), "apply_bf16_us": med(acc["apply_bf16_us"]), "apply_f32_us": med(acc["apply_f32_us"]),
+                   "fill_apply_bf16_us": med(acc["fill_us"]) + med(acc["apply_bf16_us"]),
+                   "fill_apply_f32_us": med(acc["fill_us"]) + med(acc["apply_f32_us"]),
+                   "fill_host_ms": med(acc["fill_host_ms"]), "accept_host_ms": med(acc["accept_host_ms"]),
+                   "masked_fraction_last_step": masked / float(B * V)},
+        "roofline": {"kernel": "k_build", "bound": "hbm", "achieved": build_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": build_gbs / HBM_PEAK_GBS, "traffic": None,
+                     "note": "algorithmic bytes = built positions x (sum of token bytes + 4.25 B per token); "
+                             "the vocabulary stays cache-resident, so real HBM traffic is far lower"},
+    }
+    for name, key, e in (("roofline_apply_bf16", "apply_bf16_us", 2), ("roofline_apply_f32", "apply_f32_us", 4)):
+        t = med(acc[key]) * 1e-6
+        rmw = (B * W * 4 + 2 * B * V * e) / t / 1e9
+        store_only = (B * W * 4 + masked * e) / t / 1e9
+        out[name] = {"kernel": "k_apply_vec", "bound": "hbm", "achieved": rmw, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": rmw / HBM_PEAK_GBS, "traffic": None, "accounting": "read-modify-write of all logits + bitmask read",
+                     "achieved_store_only_accounting": store_only}
+    tf = med(acc["fill_us"]) * 1e-6
+    out["roofline_fill"] = {"kernel": "k_fill", "bound": "hbm", "achieved": B * W * 4 / tf / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                            "frac": B * W * 4 / tf / 1e9 / HBM_PEAK_GBS, "traffic": None, "accounting": "bitmask write only"}
+
+    if not args.no_cpu_baseline:
+        import oracle
+        orc = oracle.Oracle(ebnf, root)
+        va = oracle.VocabArrays(cfg.vocab.tokens, cfg.vocab.eos_id, cfg.vocab.special_ids)
+        pos = orc.positions()
+        prng = random.Random(7)
+        sample = prng.sample(pos, min(args.cpu_positions, len(pos)))
+        threads = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "0") or 0) or (os.cpu_count() or 1))
+        t0 = time.perf_counter()
+        for p in sample:
+            orc.classes(p, va, threads=threads)
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": len(sample) * n_checkable / dt, "unit": "checks/s", "cores": threads, "kind": "oracle",
+                               "sample": "%d of %d positions (seeded sample) x all %d tokens, textbook Earley per pair, %.1f s"
+                                         % (len(sample), len(pos), n_checkable, dt)}
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -62,6 +62,7 @@ typedef struct xg2_compile_stats {
     int64_t n_uncertain;      /* set bits over the built uncertain planes                         */
     double  host_lower_ms;    /* EBNF -> tables on the host                                       */
     double  device_ms;        /* first table upload -> last plane written (HIP events)            */
+    double  kernel_ms;        /* the classification kernel alone (HIP events around its launch)   */
 } xg2_compile_stats;
 
 const char* xg2_last_error(void);

@@ -39,7 +39,7 @@ class CompileStats(ctypes.Structure):
     _fields_ = [("positions", ctypes.c_int64), ("unique", ctypes.c_int64), ("built", ctypes.c_int64),
                 ("checks", ctypes.c_int64), ("executed_checks", ctypes.c_int64), ("slow_path", ctypes.c_int64),
                 ("n_accepted", ctypes.c_int64), ("n_uncertain", ctypes.c_int64),
-                ("host_lower_ms", ctypes.c_double), ("device_ms", ctypes.c_double)]
+                ("host_lower_ms", ctypes.c_double), ("device_ms", ctypes.c_double), ("kernel_ms", ctypes.c_double)]
 
     def as_dict(self):
         return {k: getattr(self, k) for k, _ in self._fields_}
@@ -227,8 +227,23 @@ class Matcher:
             self.h = None
 
 
-def fill_next_token_bitmask(matchers: Sequence[Matcher], bitmask_ptr: int, row_stride_words: int, stream: int = 0) -> None:
-    arr = (ctypes.c_void_p * len(matchers))(*[m.h for m in matchers])
+class MatcherBatch:
+    """A fixed list of matchers with its handle array marshalled once."""
+
+    def __init__(self, matchers: Sequence[Matcher]):
+        self.matchers = list(matchers)
+        self.arr = (ctypes.c_void_p * len(self.matchers))(*[m.h for m in self.matchers])
+
+    def __len__(self):
+        return len(self.matchers)
+
+
+def fill_next_token_bitmask(matchers, bitmask_ptr: int, row_stride_words: int, stream: int = 0) -> None:
+    """matchers: a sequence of Matcher or a MatcherBatch."""
+    if isinstance(matchers, MatcherBatch):
+        arr = matchers.arr
+    else:
+        arr = (ctypes.c_void_p * len(matchers))(*[m.h for m in matchers])
     _check(lib.xg2_fill_next_token_bitmask(arr, len(matchers), ctypes.c_void_p(bitmask_ptr), row_stride_words,
                                            ctypes.c_void_p(stream)))
 

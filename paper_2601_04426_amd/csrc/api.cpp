@@ -411,9 +411,11 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
         }
         double host_ms_a = ms_since(t0);
 
-        hipEvent_t ev0, ev1;
+        hipEvent_t ev0, ev1, evk0, evk1;
         HIP_CHECK(hipEventCreate(&ev0));
         HIP_CHECK(hipEventCreate(&ev1));
+        HIP_CHECK(hipEventCreate(&evk0));
+        HIP_CHECK(hipEventCreate(&evk1));
         HIP_CHECK(hipEventRecord(ev0, stream));
         cache->d_state.upload(ft.state_info, stream);
         cache->d_bedge.upload(ft.byte_edges, stream);
@@ -476,8 +478,10 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
         P.n_seg = (uint32_t)seg_pos.size(); P.n_blocks = seg_blk.back();
         P.ctx_items = d_items.p; P.ctx_item_off = d_item_off.p; P.ctx_wait = d_wait.p; P.ctx_wait_off2 = d_wait_off2.p;
         P.plane_ptr = d_rows.p;
+        HIP_CHECK(hipEventRecord(evk0, stream));
+        if (!build_pos.empty()) launch_build(cache->dt, V.dv, P, S, stream);
+        HIP_CHECK(hipEventRecord(evk1, stream));
         if (!build_pos.empty()) {
-            launch_build(cache->dt, V.dv, P, S, stream);
             launch_build_slow(cache->dt, V.dv, P, S, stream);
             launch_popcount(d_rows.p, (uint32_t)build_rows.size(), V.W, d_counts.p, stream);
         }
@@ -488,9 +492,10 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
         HIP_CHECK(hipMemcpyAsync(bit_counts, d_counts.p, sizeof(bit_counts), hipMemcpyDeviceToHost, stream));
         HIP_CHECK(hipStreamSynchronize(stream));
         HIP_CHECK(hipGetLastError());
-        float dev_ms = 0.f;
+        float dev_ms = 0.f, kern_ms = 0.f;
         HIP_CHECK(hipEventElapsedTime(&dev_ms, ev0, ev1));
-        (void)hipEventDestroy(ev0); (void)hipEventDestroy(ev1);
+        HIP_CHECK(hipEventElapsedTime(&kern_ms, evk0, evk1));
+        (void)hipEventDestroy(ev0); (void)hipEventDestroy(ev1); (void)hipEventDestroy(evk0); (void)hipEventDestroy(evk1);
         if (slow_counts[1]) {
             HIP_CHECK(hipMemset(S.count + 1, 0, sizeof(uint32_t)));
             // rows handed out by this call hold partial results: forget them
@@ -511,6 +516,7 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
             stats->n_uncertain = (int64_t)bit_counts[1];
             stats->host_lower_ms = host_ms_a + host_ms_b;
             stats->device_ms = dev_ms;
+            stats->kernel_ms = kern_ms;
         }
         *out = new xg2_mask_cache{cache};
         return XG2_OK;

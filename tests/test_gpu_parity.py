@@ -139,3 +139,149 @@ def test_apply_unaligned_base(xg):
     torch.cuda.synchronize()
     oracle.apply_f32(before, bm)
     assert np.array_equal(view.cpu().numpy().view(np.uint32), before)
+
+
+def test_config2_planes_and_decode(xg):
+    cfg, vocab, va = load(2)
+    ebnf, root = cfg.grammars[0]
+    cache, orc = check_planes(xg, cfg, vocab, va, ebnf, root)
+    n = run_decode(xg, cfg, vocab, va, cache, orc, batch=64, steps=48, seed=22, check_every=5)
+    assert n >= 600
+
+
+def test_config3_tagdispatch_planes_and_decode(xg):
+    cfg, vocab, va = load(3)
+    ebnf, root = cfg.grammars[0]
+    cache, orc = check_planes(xg, cfg, vocab, va, ebnf, root)          # all ~13k positions x 128,256 tokens
+    n = run_decode(xg, cfg, vocab, va, cache, orc, batch=256, steps=24, seed=33, check_every=37)
+    assert n >= 160
+
+
+def test_config5_repetition_planes_and_decode(xg):
+    cfg, vocab, va = load(5)
+    ebnf, root = cfg.grammars[0]
+    cache, orc = check_planes(xg, cfg, vocab, va, ebnf, root)
+    n = run_decode(xg, cfg, vocab, va, cache, orc, batch=1024, steps=6, seed=55, check_every=41)
+    assert n >= 140
+
+
+def test_config4_cross_grammar_pool(xg):
+    """Reduced cross-grammar workload: planes are built once per distinct rule position, later grammars reuse
+    them, and what a reusing grammar sees equals what the oracle computes for that grammar alone."""
+    cfg, vocab, va = load(4, n_grammars=12, n_tools=40)
+    pool = xg.Pool()
+    total_positions = total_built = 0
+    distinct = set()
+    caches = []
+    for gi, (ebnf, root) in enumerate(cfg.grammars):
+        cache = xg.compile_grammar(vocab, ebnf, root, pool=pool, stream=_stream())
+        st = cache.stats
+        total_positions += st.positions
+        total_built += st.built
+        caches.append(cache)
+        # exact count of distinct canonical structures, the slow way: serialise every reachable rule of the
+        # oracle's lowering with its references expanded recursively
+        orc = oracle.Oracle(ebnf, root)
+        memo = {}
+
+        def canon(name, orc=orc, memo=memo):
+            if name in memo:
+                return memo[name]
+            d = orc.low.dfa[name]
+            memo[name] = ("...",)                                   # recursion guard (no cycles in this workload)
+            out = []
+            for q in range(d.n):
+                out.append((d.final[q], tuple(sorted((m, t) for m, t in d.bedges[q])),
+                            tuple(sorted((canon(orc.order[r]), t) for r, t in d.redges[q].items()))))
+            memo[name] = tuple(out)
+            return memo[name]
+        for (rule, q) in orc.positions():
+            distinct.add((canon(rule), q))
+        if gi in (0, 5, 11):                                         # planes seen through a reusing grammar
+            rng = random.Random(gi)
+            for p in rng.sample(range(cache.num_positions()), 25):
+                acc, unc = cache.get_planes(p)
+                want_a, want_u = planes_of(orc, cache.position(p), va)
+                assert np.array_equal(acc, want_a) and np.array_equal(unc, want_u), cache.position(p)
+    n_rows, dev_bytes = pool.stats()
+    assert n_rows == total_built == len(distinct)
+    assert total_built < total_positions / 2                         # sub-structure reuse across requests
+    assert caches[-1].stats.built < caches[-1].stats.positions
+
+
+def test_long_tokens_and_item_overflow_take_the_slow_path(xg):
+    """Tokens longer than the LDS path handles (16 bytes) and grammars whose item sets outgrow the LDS
+    lists are finished by the large-capacity kernel with the same result."""
+    rng = random.Random(9)
+    toks = [b""] + [bytes([c]) for c in b"ab(),x"]
+    while len(toks) < 600:
+        n = rng.choice((3, 9, 17, 24, 40, 70))
+        t = bytes(rng.choice(b"ab(),x") for _ in range(n))
+        if t not in toks:
+            toks.append(t)
+    alts = " | ".join(f'r{i}' for i in range(20))
+    ebnf = ('root ::= "(" list ")"\nlist ::= item ("," item)*\nitem ::= ' + alts + ' | "(" list ")"\n'
+            + "".join(f'r{i} ::= "a"{{{i + 1}}} "b"*\n' for i in range(20)))
+    vocab = xg.Vocab(toks, 0, [0])
+    va = oracle.VocabArrays(toks, 0, [0])
+
+    class Cfg:
+        pass
+    cfg = Cfg()
+    cfg.vocab = Cfg()
+    cfg.vocab.tokens = toks
+    cache, orc = check_planes(xg, cfg, vocab, va, ebnf, "root")
+    assert cache.stats.slow_path > 0
+    # decode through a few long tokens
+    import torch
+    m = xg.Matcher(cache)
+    bitmask = torch.zeros((1, vocab.words), dtype=torch.int32, device="cuda:0")
+    hist = b""
+    for step in range(6):
+        xg.fill_next_token_bitmask([m], bitmask.data_ptr(), vocab.words, _stream())
+        torch.cuda.synchronize()
+        got = bitmask.cpu().numpy()[0]
+        want = oracle.pack_bitmask(orc.mask(hist, va))
+        assert np.array_equal(got, want), (hist, diff_words(got, want, toks))
+        allowed = [i for i in range(1, len(toks)) if (int(got[i // 32]) >> (i % 32)) & 1]
+        if not allowed:
+            break
+        tid = max(allowed, key=lambda i: (len(toks[i]), i))
+        assert m.accept_token(tid)
+        hist += toks[tid]
+
+
+def test_edge_cases(xg):
+    import torch
+    toks = [b"", b"a", b"", b"b", b"ab", b"\xff"]                     # id 2 is an empty non-special token
+    vocab = xg.Vocab(toks, 0, [0, 5])                                 # id 5 is special
+    va = oracle.VocabArrays(toks, 0, [0, 5])
+    cache = xg.compile_grammar(vocab, 'root ::= "a" "b"?\n', "root", stream=_stream())
+    orc = oracle.Oracle('root ::= "a" "b"?\n')
+    for p in range(cache.num_positions()):
+        acc, unc = cache.get_planes(p)
+        wa, wu = planes_of(orc, cache.position(p), va)
+        assert np.array_equal(acc, wa) and np.array_equal(unc, wu)
+    m = xg.Matcher(cache)
+    bm = torch.full((1, 1), -1, dtype=torch.int32, device="cuda:0")
+    xg.fill_next_token_bitmask([m], bm.data_ptr(), 1, _stream())
+    torch.cuda.synchronize()
+    assert bm.item() == 0b010010                                      # "a" and "ab"
+    assert not m.accept_token(2) and not m.accept_token(5) and not m.accept_token(3) and not m.accept_token(0)
+    assert m.accept_token(1)
+    xg.fill_next_token_bitmask([m], bm.data_ptr(), 1, _stream())
+    torch.cuda.synchronize()
+    assert bm.item() == 0b001001                                      # "b" or end of sequence
+    assert m.accept_token(0) and m.is_terminated()
+    xg.fill_next_token_bitmask([m], bm.data_ptr(), 1, _stream())
+    torch.cuda.synchronize()
+    assert bm.item() == 0b000001                                      # terminated: only end of sequence
+    with pytest.raises(xg.Xg2Error):
+        m.accept_token(1)
+    # empty batch, zero-size apply
+    xg.fill_next_token_bitmask([], 0, 1, _stream())
+    xg.apply_token_bitmask(0, xg.XG2_F32, 0, 10, 10, 0, 1, _stream())
+    with pytest.raises(xg.Xg2Error):
+        xg.compile_grammar(vocab, 'root ::= "a" b\nb ::= "x" b\n', "root")
+    with pytest.raises(xg.Xg2Error):
+        xg.compile_grammar(vocab, 'root ::= "a', "root")

@@ -1,0 +1,127 @@
+"""CPU-side checks of the library: it loads, exports the declared symbols, and its host logic
+(grammar lowering, hashing, the Earley chart of a matcher) agrees with the oracle.  No GPU call."""
+import os
+import random
+import re
+
+import numpy as np
+import pytest
+
+import gen
+import oracle
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def xg():
+    import paper_2601_04426_amd as xg
+    return xg
+
+
+def test_library_exports_every_declared_symbol(xg):
+    header = open(os.path.join(ROOT, "include", "xg2mask.h")).read()
+    declared = set(re.findall(r"\b(xg2_[a-z0-9_]+)\s*\(", header))
+    assert declared == set(xg.EXPORTS)
+    for name in declared:
+        assert hasattr(xg.lib, name), name
+
+
+def _same_automata(xg, ebnf, root="root"):
+    g = xg.Grammar(ebnf, root)
+    d = g.describe()
+    o = oracle.Oracle(ebnf, root)
+    assert [tuple(p) for p in d["positions"]] == o.positions()
+    assert [r["name"] for r in d["rules"]] == o.low.reachable
+    for r in d["rules"]:
+        od = o.low.dfa[r["name"]]
+        assert len(r["states"]) == od.n, r["name"]
+        for q, st in enumerate(r["states"]):
+            assert st["final"] == od.final[q]
+            by_t = {}
+            for lo, hi, t in st["bytes"]:
+                by_t[t] = by_t.get(t, 0) | (((1 << (hi + 1)) - 1) ^ ((1 << lo) - 1))
+            assert by_t == {t: m for m, t in od.bedges[q]}, (r["name"], q)
+            assert [(n, t) for n, t in st["refs"]] == [(o.order[ri], t) for ri, t in od.redges[q].items()]
+    return d, o
+
+
+@pytest.mark.parametrize("index,kw", [(1, {}), (2, {}), (3, {"n_tools": 12}), (5, {"max_objects": 40})])
+def test_lowering_equals_the_oracles_canonical_automata(xg, index, kw):
+    cfg = gen.build_config(index, vocab_size=1000, **kw)
+    _same_automata(xg, *cfg.grammars[0])
+
+
+def test_lowering_small_grammars_and_errors(xg):
+    for ebnf in ['root ::= "a" root "b" | "c"\n', 'root ::= a b\na ::= a "x" | ""\nb ::= "y"?\n',
+                 'root ::= ([ab] | "c" k)+ "d"{0,2}\nk ::= [a-c]{1,2}\n', 'root ::= [^a-z\\x00-\\x1f\\u00e9-\\U0001F600]{2,3} "\\u20ac"\n',
+                 'root ::= TagDispatch(("<a>", g1), ("<bc>", g2), stop_strs=("!!"))\ng1 ::= "xy" | "z"\ng2 ::= "q"\n']:
+        _same_automata(xg, ebnf)
+    for bad, code in [('root ::= "a', -2), ('root ::= b\n', -1), ('root ::= "a" b\nb ::= "x" b\n', -1), ('root ::= "a"{3,2}\n', -2),
+                      ('root ::= TagDispatch(("<a>", g), ("x<a>y", g))\ng ::= "k"\n', -1)]:
+        with pytest.raises(xg.Xg2Error) as e:
+            xg.Grammar(bad)
+        assert e.value.code == code, bad
+
+
+def test_hash_is_structural(xg):
+    """Algorithm 1: the hash ignores rule names and declaration order and sees every edge; Algorithm 2: the rules of a
+    simple cycle get distinct hashes that do not depend on names."""
+    def hashes(ebnf):
+        return {r["name"]: (r["hash"], r["shareable"]) for r in xg.Grammar(ebnf).describe()["rules"]}
+    a = hashes('root ::= "[" v ("," v)* "]"\nv ::= [0-9]+ | s\ns ::= "\\"" [a-z]* "\\""\n')
+    b = hashes('s2 ::= "\\"" [a-z]* "\\""\nroot ::= "[" val ("," val)* "]"\nval ::= [0-9]+ | s2\n')
+    assert a["root"] == b["root"] and a["v"] == b["val"] and a["s"] == b["s2"]
+    c = hashes('root ::= "[" v ("," v)* "]"\nv ::= [0-9]+ | s\ns ::= "\\"" [a-y]* "\\""\n')      # one byte range differs, deep down
+    assert c["s"] != a["s"] and c["v"] != a["v"] and c["root"] != a["root"]
+    cyc1 = hashes('root ::= "(" a ")"\na ::= "x" b | "."\nb ::= "y" a\n')
+    cyc2 = hashes('root ::= "(" p ")"\nq ::= "y" p\np ::= "x" q | "."\n')
+    assert cyc1["a"] == cyc2["p"] and cyc1["b"] == cyc2["q"] and cyc1["a"] != cyc1["b"] and cyc1["root"] == cyc2["root"]
+    assert all(sh for _, sh in cyc1.values())
+    tangled = hashes('root ::= a\na ::= "x" b | "." a | "!"\nb ::= "y" a | b "z"\n')                  # not a simple cycle
+    assert not tangled["a"][1] and not tangled["b"][1]
+
+
+@pytest.mark.parametrize("index,kw", [(1, {}), (2, {"vocab_size": 3000}), (3, {"vocab_size": 3000, "n_tools": 4}),
+                                      (5, {"vocab_size": 3000, "max_objects": 6})])
+def test_host_matcher_follows_the_oracle(xg, index, kw):
+    cfg = gen.build_config(index, **kw)
+    ebnf, root = cfg.grammars[0]
+    g = xg.Grammar(ebnf, root)
+    pos = [tuple(p) for p in g.describe()["positions"]]
+    v = xg.Vocab(cfg.vocab.tokens, 0, [0])
+    o = oracle.Oracle(ebnf, root)
+    va = oracle.VocabArrays(cfg.vocab.tokens, 0, [0])
+    seg = gen.Segmenter(cfg.vocab)
+    rng = random.Random(index)
+    m = xg.Matcher(grammar=g, vocab=v)
+    for trial in range(2):
+        m.reset()
+        ids = seg.segment(cfg.sample_text(rng, 0), rng)
+        hist = b""
+        for step, tid in enumerate(ids + [0]):
+            fr, can_end = m.frontier()
+            assert sorted(pos[p] for p in fr) == o.frontier(hist)
+            if step % 5 == 0:
+                mask = o.mask(hist, va)
+                assert can_end == bool(mask[0])
+                for t in rng.sample(range(1, cfg.vocab.size), 40):       # rejected tokens leave the matcher unchanged
+                    if not mask[t]:
+                        assert not m.accept_token(t)
+                assert m.frontier() == (fr, can_end)
+            assert m.accept_token(tid)
+            if tid:
+                hist += cfg.vocab.tokens[tid]
+        assert m.is_terminated()
+
+
+def test_device_calls_fail_loudly_without_a_gpu(xg, has_gpu):
+    if has_gpu:
+        pytest.skip("a GPU is present")
+    v = xg.Vocab([b"", b"a"], 0, [0])
+    with pytest.raises(xg.Xg2Error) as e:
+        xg.compile_grammar(v, 'root ::= "a"\n')
+    assert e.value.code == -5
+    with pytest.raises(xg.Xg2Error) as e:
+        xg.apply_token_bitmask(16, xg.XG2_F32, 1, 32, 32, 16, 1)
+    assert e.value.code == -5
