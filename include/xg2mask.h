@@ -50,17 +50,30 @@ typedef struct xg2_pool xg2_pool;
 typedef struct xg2_mask_cache xg2_mask_cache;
 typedef struct xg2_matcher xg2_matcher;
 
+/* Options of xg2_compile_grammar (NULL = defaults).
+ * context_depth 1: one plane pair per scannable position (rule, state), the cache of section 3.4 as it stands.
+ * context_depth 2 (default): a position of a referenced rule is cached once per distinct state the
+ *   referencing rule continues in, i.e. with one level of the reference structure built into the
+ *   plane (the context expansion that section 2.2 and section 3.3 recall); far fewer tokens stay
+ *   uncertain.  Positions of the root rule have no referencing rule and keep a plain plane.
+ * merge_equivalent (default 1): states that no string as long as the longest token can tell apart
+ *   share one plane (section 3.6: states inside a repetition differ minimally).                    */
+typedef struct xg2_compile_opts {
+    int32_t context_depth;
+    int32_t merge_equivalent;
+} xg2_compile_opts;
+
 /* Counters filled by xg2_compile_grammar. */
 typedef struct xg2_compile_stats {
     int64_t positions;        /* scannable (rule, state) positions of the grammar                 */
-    int64_t unique;           /* distinct positions after structural dedupe inside the grammar    */
-    int64_t built;            /* positions whose planes were computed by this call (pool misses)  */
-    int64_t checks;           /* built * (number of checkable tokens): logical (position, token)  */
-    int64_t executed_checks;  /* (position, token) pairs a lane actually stepped through          */
+    int64_t unique;           /* distinct planes this grammar uses (after dedupe and merging)     */
+    int64_t built;            /* planes computed by this call (pool misses)                       */
+    int64_t checks;           /* built * (number of checkable tokens): logical (plane, token)     */
+    int64_t executed_checks;  /* (plane, token) pairs a lane actually stepped through             */
     int64_t slow_path;        /* pairs finished by the large-capacity kernel                      */
     int64_t n_accepted;       /* set bits over the built accepted planes                          */
     int64_t n_uncertain;      /* set bits over the built uncertain planes                         */
-    double  host_lower_ms;    /* EBNF -> tables on the host                                       */
+    double  host_lower_ms;    /* EBNF -> tables and work plan on the host                         */
     double  device_ms;        /* first table upload -> last plane written (HIP events)            */
     double  kernel_ms;        /* the classification kernel alone (HIP events around its launch)   */
 } xg2_compile_stats;
@@ -97,17 +110,28 @@ int32_t xg2_pool_stats(const xg2_pool*, int64_t* n_positions, int64_t* device_by
 
 /* ---- compile_grammar(ebnf, vocab) -> mask_cache ------------------------------------------------
  * Builds, on the device, the accepted and uncertain bit planes [W = ceil(V/32) int32 words each]
- * of every scannable position of the grammar that the pool (nullable) does not hold yet.
- * stats may be NULL.                                                                            */
+ * of every plane of the grammar that the pool (nullable) does not hold yet.  A plane belongs to a
+ * position (rule, state), or to a position plus the state (parent rule, parent state) in which the
+ * referencing rule continues once the position's rule instance ends:
+ *   accepted  = tokens that are a prefix of a string of Suf(position) [. Suf(parent)],
+ *   uncertain = the other tokens with a proper non-empty prefix that is a whole such string.
+ * opts and stats may be NULL.                                                                    */
 int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, const char* root_rule,
-                            xg2_pool* pool, void* hip_stream, xg2_mask_cache** out,
-                            xg2_compile_stats* stats);
+                            const xg2_compile_opts* opts, xg2_pool* pool, void* hip_stream,
+                            xg2_mask_cache** out, xg2_compile_stats* stats);
 void    xg2_mask_cache_destroy(xg2_mask_cache*);
 int32_t xg2_mask_cache_num_positions(const xg2_mask_cache*, int32_t* out);
-/* Rule name (pointer valid while the cache lives) and canonical state of position p.            */
-int32_t xg2_mask_cache_position(const xg2_mask_cache*, int32_t p, const char** rule_name, int32_t* state);
-/* Copies the planes of position p to host arrays of W int32 words each (synchronises).          */
-int32_t xg2_mask_cache_get_planes(const xg2_mask_cache*, int32_t p, int32_t* accepted_host, int32_t* uncertain_host);
+int32_t xg2_mask_cache_num_planes(const xg2_mask_cache*, int32_t* out);
+/* The representative the planes of index k were built for.  Names stay valid while the cache lives;
+ * *parent_rule is NULL (and *parent_state -1) for a plane without context.                        */
+int32_t xg2_mask_cache_plane_info(const xg2_mask_cache*, int32_t k, const char** rule, int32_t* state,
+                                  const char** parent_rule, int32_t* parent_state);
+/* Index of the plane used for (rule, state) [inside (parent_rule, parent_state); parent_rule NULL =
+ * no context]; *k = -1 if the cache holds no plane for that combination.                          */
+int32_t xg2_mask_cache_find_plane(const xg2_mask_cache*, const char* rule, int32_t state,
+                                  const char* parent_rule, int32_t parent_state, int32_t* k);
+/* Copies plane k to host arrays of W int32 words each (synchronises).                              */
+int32_t xg2_mask_cache_get_planes(const xg2_mask_cache*, int32_t k, int32_t* accepted_host, int32_t* uncertain_host);
 
 /* ---- matchers (one per sequence) ---------------------------------------------------------------
  * A matcher follows the output with an Earley parser (section 3.4, appendix on Earley parsing).
@@ -119,15 +143,17 @@ void    xg2_matcher_destroy(xg2_matcher*);
 int32_t xg2_matcher_accept_token(xg2_matcher*, int32_t token_id);
 int32_t xg2_matcher_reset(xg2_matcher*);
 int32_t xg2_matcher_is_terminated(const xg2_matcher*, int32_t* out);
-/* Position indices of the scannable items of the current closed Earley set (at most cap are
- * written, *n receives the count) and whether the root rule can end here.                       */
+/* Position indices (into the grammar's position list) of the scannable items of the current
+ * closed Earley set (at most cap are written, *n receives the count) and whether the root rule
+ * can end here.                                                                                 */
 int32_t xg2_matcher_frontier(const xg2_matcher*, int32_t* positions_host, int32_t cap, int32_t* n,
                              int32_t* can_end);
 
 /* ---- fill_next_token_bitmask(matchers[B], bitmask[B, ceil(V/32)] int32) ------------------------
- * For every matcher b: bitmask[b] = union of the accepted planes of its frontier, plus every
- * token that is uncertain somewhere in the frontier and passes a re-check against the matcher's
- * full Earley context, plus the end-of-sequence bit if the root rule can end.  A terminated
+ * For every matcher b: bitmask[b] = union of the accepted planes of its frontier (each scannable
+ * item, with its referencing item at context depth 2), plus every token that is uncertain
+ * somewhere in the frontier and passes a re-check against the matcher's full Earley context, plus
+ * the end-of-sequence bit if the root rule can end.  A terminated
  * matcher gets a row allowing only end-of-sequence.  matchers: host array of B handles that
  * share one vocabulary (their caches may differ).  bitmask_dev: device, B rows of
  * row_stride_words int32 (row_stride_words >= W).                                               */

@@ -60,7 +60,7 @@ def _load():
         L.eo_productive.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
         L.eo_is_nullable.argtypes = [ctypes.c_void_p, ctypes.c_int32]
         L.eo_scan_vocab.restype = ctypes.c_int32
-        L.eo_scan_vocab.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, ctypes.c_int64,
+        L.eo_scan_vocab.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p, ctypes.c_int64,
                                     ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p,
                                     ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, ctypes.c_int32]
         L.eo_accepts.restype = ctypes.c_int32
@@ -111,7 +111,7 @@ class CGrammar:
         return bool(_load().eo_accepts(self.h, start_nt, buf.ctypes.data, len(text)))
 
     def scan_vocab(self, start_nt: int, history: bytes, blob: np.ndarray, offs: np.ndarray, threads: int = 0,
-                   want_items: bool = False):
+                   want_items: bool = False, start2_nt: int = -1):
         """-> (status, viable[V] u8, early[V] u8, items or None); status -1 dead, 1 complete, 0 otherwise."""
         V = len(offs) - 1
         viable = np.zeros(V, dtype=np.uint8)
@@ -120,7 +120,7 @@ class CGrammar:
         cap = 4096
         items = np.zeros(3 * cap, dtype=np.int32)
         n_items = ctypes.c_int32(0)
-        st = _load().eo_scan_vocab(self.h, start_nt, hist.ctypes.data, len(history), blob.ctypes.data,
+        st = _load().eo_scan_vocab(self.h, start_nt, start2_nt, hist.ctypes.data, len(history), blob.ctypes.data,
                                    offs.ctypes.data, V, viable.ctypes.data, early.ctypes.data,
                                    items.ctypes.data, cap, ctypes.byref(n_items), threads)
         it = None
@@ -194,10 +194,14 @@ class Oracle:
         return self._direct
 
     # -- cache classes of one position ------------------------------------------------------
-    def classes(self, pos: Tuple[str, int], vocab: VocabArrays, threads: int = 0) -> np.ndarray:
-        """u8[V]: ACCEPTED / UNCERTAIN / REJECTED; special and empty tokens are REJECTED."""
+    def classes(self, pos: Tuple[str, int], vocab: VocabArrays, threads: int = 0,
+                parent: Optional[Tuple[str, int]] = None) -> np.ndarray:
+        """u8[V]: ACCEPTED / UNCERTAIN / REJECTED; special and empty tokens are REJECTED.
+        With `parent` = the state the referencing rule continues in once this rule instance ends, the
+        suffix language is Suf(pos) . Suf(parent) (one level of context)."""
         start = self.fsm_bnf.names[pos]
-        st, viable, early, _ = self.cg.scan_vocab(start, b"", vocab.blob, vocab.offs, threads)
+        start2 = self.fsm_bnf.names[parent] if parent is not None else -1
+        st, viable, early, _ = self.cg.scan_vocab(start, b"", vocab.blob, vocab.offs, threads, start2_nt=start2)
         assert st >= 0
         cls = np.where(viable.astype(bool), ACCEPTED, np.where(early.astype(bool), UNCERTAIN, REJECTED)).astype(np.uint8)
         cls[vocab.special] = REJECTED

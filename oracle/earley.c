@@ -120,14 +120,14 @@ void eo_productive(void* h, uint8_t* out) {
     }
 }
 
-/* The augmented start production  S' -> start  has index g->n_prod. */
-typedef struct { const Grammar* g; int32_t start; } Ctx;
+/* The augmented start production  S' -> start  (or  S' -> start start2 ) has index g->n_prod. */
+typedef struct { const Grammar* g; int32_t start, start2; } Ctx;
 
 static inline int32_t rhs_len(const Ctx* c, int32_t prod) {
-    return prod == c->g->n_prod ? 1 : c->g->off[prod + 1] - c->g->off[prod];
+    return prod == c->g->n_prod ? (c->start2 >= 0 ? 2 : 1) : c->g->off[prod + 1] - c->g->off[prod];
 }
 static inline int32_t rhs_sym(const Ctx* c, int32_t prod, int32_t dot) {
-    return prod == c->g->n_prod ? ~c->start : c->g->syms[c->g->off[prod] + dot];
+    return prod == c->g->n_prod ? (dot == 0 ? ~c->start : ~c->start2) : c->g->syms[c->g->off[prod] + dot];
 }
 static inline int32_t prod_lhs(const Ctx* c, int32_t prod) {
     return prod == c->g->n_prod ? -1 : c->g->lhs[prod];
@@ -178,12 +178,13 @@ static void step(const Ctx* c, Set* sets, int32_t j, uint8_t byte) {
 
 static int start_complete(const Ctx* c, const Set* s) {
     for (int32_t i = 0; i < s->n; ++i)
-        if (s->it[i].prod == c->g->n_prod && s->it[i].dot == 1 && s->it[i].origin == 0) return 1;
+        if (s->it[i].prod == c->g->n_prod && s->it[i].dot == rhs_len(c, c->g->n_prod) && s->it[i].origin == 0) return 1;
     return 0;
 }
 
 /*
- * Parse `hist` (hlen bytes) from nonterminal `start`; then for every token t of the vocabulary
+ * Parse `hist` (hlen bytes) from nonterminal `start` (followed by nonterminal `start2` unless that is
+ * negative: the language is then the concatenation); then for every token t of the vocabulary
  * (CSR: blob + offs[V+1]) decide
  *     viable[t]  = 1  iff  the item set after hist.bytes(t) is non-empty
  *     early[t]   = 1  iff  for some i, 1 <= i < len(t), hist.t[0:i] is a complete sentence
@@ -192,12 +193,12 @@ static int start_complete(const Ctx* c, const Set* s) {
  * Optionally exports the items of the closed set after hist: last_items[3*k] = prod, dot, origin
  * (at most last_cap items; *last_n receives the true count).
  */
-int32_t eo_scan_vocab(void* h, int32_t start, const uint8_t* hist, int64_t hlen,
+int32_t eo_scan_vocab(void* h, int32_t start, int32_t start2, const uint8_t* hist, int64_t hlen,
                       const uint8_t* blob, const int64_t* offs, int32_t V,
                       uint8_t* viable, uint8_t* early,
                       int32_t* last_items, int32_t last_cap, int32_t* last_n, int32_t n_threads) {
     Grammar* g = (Grammar*)h;
-    Ctx c; c.g = g; c.start = start;
+    Ctx c; c.g = g; c.start = start; c.start2 = start2;
     int64_t max_tok = 0;
     for (int32_t t = 0; t < V; ++t) if (offs[t + 1] - offs[t] > max_tok) max_tok = offs[t + 1] - offs[t];
     Set* base = (Set*)malloc(sizeof(Set) * (size_t)(hlen + 1));
@@ -259,7 +260,7 @@ int32_t eo_scan_vocab(void* h, int32_t start, const uint8_t* hist, int64_t hlen,
 
 /* Does `text` belong to L(start)?  (sentence test, used by the pins) */
 int32_t eo_accepts(void* h, int32_t start, const uint8_t* text, int64_t n) {
-    return eo_scan_vocab(h, start, text, n, NULL, NULL, 0, NULL, NULL, NULL, 0, NULL, 1) == 1;
+    return eo_scan_vocab(h, start, -1, text, n, NULL, NULL, 0, NULL, NULL, NULL, 0, NULL, 1) == 1;
 }
 
 /* In-place token-bitmask application, plain loops (paper section 2.1: logits of tokens that do

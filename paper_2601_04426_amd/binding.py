@@ -22,8 +22,8 @@ XG2_F32, XG2_BF16 = 0, 1
 EXPORTS = [
     "xg2_last_error", "xg2_vocab_create", "xg2_vocab_destroy", "xg2_grammar_create", "xg2_grammar_destroy",
     "xg2_grammar_describe", "xg2_grammar_num_positions", "xg2_pool_create", "xg2_pool_destroy", "xg2_pool_stats",
-    "xg2_compile_grammar", "xg2_mask_cache_destroy", "xg2_mask_cache_num_positions", "xg2_mask_cache_position",
-    "xg2_mask_cache_get_planes", "xg2_matcher_create", "xg2_matcher_create_host", "xg2_matcher_destroy",
+    "xg2_compile_grammar", "xg2_mask_cache_destroy", "xg2_mask_cache_num_positions", "xg2_mask_cache_num_planes",
+    "xg2_mask_cache_plane_info", "xg2_mask_cache_find_plane", "xg2_mask_cache_get_planes", "xg2_matcher_create", "xg2_matcher_create_host", "xg2_matcher_destroy",
     "xg2_matcher_accept_token", "xg2_matcher_reset", "xg2_matcher_is_terminated", "xg2_matcher_frontier",
     "xg2_fill_next_token_bitmask", "xg2_apply_token_bitmask",
 ]
@@ -45,6 +45,10 @@ class CompileStats(ctypes.Structure):
         return {k: getattr(self, k) for k, _ in self._fields_}
 
 
+class CompileOpts(ctypes.Structure):
+    _fields_ = [("context_depth", ctypes.c_int32), ("merge_equivalent", ctypes.c_int32)]
+
+
 def _load() -> ctypes.CDLL:
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2601_04426_amd.build` "
@@ -62,10 +66,14 @@ def _load() -> ctypes.CDLL:
     L.xg2_pool_create.argtypes = [sz, pvp]
     L.xg2_pool_destroy.argtypes = [vp]
     L.xg2_pool_stats.argtypes = [vp, ctypes.POINTER(i64), ctypes.POINTER(i64)]
-    L.xg2_compile_grammar.argtypes = [vp, ctypes.c_char_p, sz, ctypes.c_char_p, vp, vp, pvp, ctypes.POINTER(CompileStats)]
+    L.xg2_compile_grammar.argtypes = [vp, ctypes.c_char_p, sz, ctypes.c_char_p, ctypes.POINTER(CompileOpts), vp, vp, pvp,
+                                      ctypes.POINTER(CompileStats)]
     L.xg2_mask_cache_destroy.argtypes = [vp]
     L.xg2_mask_cache_num_positions.argtypes = [vp, ctypes.POINTER(i32)]
-    L.xg2_mask_cache_position.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(i32)]
+    L.xg2_mask_cache_num_planes.argtypes = [vp, ctypes.POINTER(i32)]
+    L.xg2_mask_cache_plane_info.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(i32),
+                                            ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(i32)]
+    L.xg2_mask_cache_find_plane.argtypes = [vp, ctypes.c_char_p, i32, ctypes.c_char_p, i32, ctypes.POINTER(i32)]
     L.xg2_mask_cache_get_planes.argtypes = [vp, i32, vp, vp]
     L.xg2_matcher_create.argtypes = [vp, pvp]
     L.xg2_matcher_create_host.argtypes = [vp, vp, pvp]
@@ -161,15 +169,28 @@ class MaskCache:
         _check(lib.xg2_mask_cache_num_positions(self.h, ctypes.byref(n)))
         return n.value
 
-    def position(self, p: int) -> Tuple[str, int]:
-        name, st = ctypes.c_char_p(), ctypes.c_int32(0)
-        _check(lib.xg2_mask_cache_position(self.h, p, ctypes.byref(name), ctypes.byref(st)))
-        return name.value.decode(), st.value
+    def num_planes(self) -> int:
+        n = ctypes.c_int32(0)
+        _check(lib.xg2_mask_cache_num_planes(self.h, ctypes.byref(n)))
+        return n.value
 
-    def get_planes(self, p: int) -> Tuple[np.ndarray, np.ndarray]:
+    def plane_info(self, k: int):
+        """-> ((rule, state), parent) with parent = (rule, state) or None: the representative plane k was built for."""
+        name, st, pname, pst = ctypes.c_char_p(), ctypes.c_int32(0), ctypes.c_char_p(), ctypes.c_int32(0)
+        _check(lib.xg2_mask_cache_plane_info(self.h, k, ctypes.byref(name), ctypes.byref(st), ctypes.byref(pname), ctypes.byref(pst)))
+        parent = (pname.value.decode(), pst.value) if pname.value is not None else None
+        return (name.value.decode(), st.value), parent
+
+    def find_plane(self, pos: Tuple[str, int], parent: Optional[Tuple[str, int]] = None) -> int:
+        k = ctypes.c_int32(-1)
+        _check(lib.xg2_mask_cache_find_plane(self.h, pos[0].encode(), pos[1], parent[0].encode() if parent else None,
+                                             parent[1] if parent else -1, ctypes.byref(k)))
+        return k.value
+
+    def get_planes(self, k: int) -> Tuple[np.ndarray, np.ndarray]:
         acc = np.zeros(self.vocab.words, dtype=np.int32)
         unc = np.zeros(self.vocab.words, dtype=np.int32)
-        _check(lib.xg2_mask_cache_get_planes(self.h, p, acc.ctypes.data, unc.ctypes.data))
+        _check(lib.xg2_mask_cache_get_planes(self.h, k, acc.ctypes.data, unc.ctypes.data))
         return acc, unc
 
     def __del__(self):
@@ -178,11 +199,13 @@ class MaskCache:
             self.h = None
 
 
-def compile_grammar(vocab: Vocab, ebnf: str, root: str = "root", pool: Optional[Pool] = None, stream: int = 0) -> MaskCache:
+def compile_grammar(vocab: Vocab, ebnf: str, root: str = "root", pool: Optional[Pool] = None, stream: int = 0,
+                    context_depth: int = 2, merge_equivalent: bool = True) -> MaskCache:
     data = ebnf.encode("utf-8")
     h = ctypes.c_void_p()
     stats = CompileStats()
-    _check(lib.xg2_compile_grammar(vocab.h, data, len(data), root.encode(), pool.h if pool else None,
+    opts = CompileOpts(context_depth, 1 if merge_equivalent else 0)
+    _check(lib.xg2_compile_grammar(vocab.h, data, len(data), root.encode(), ctypes.byref(opts), pool.h if pool else None,
                                    ctypes.c_void_p(stream), ctypes.byref(h), ctypes.byref(stats)))
     return MaskCache(h, vocab, stats, pool)
 

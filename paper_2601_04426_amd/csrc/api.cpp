@@ -4,6 +4,7 @@
 #include "../../include/xg2mask.h"
 
 #include <algorithm>
+#include <array>
 #include <chrono>
 #include <cstring>
 #include <map>
@@ -70,6 +71,7 @@ struct VocabImpl {
     std::vector<uint8_t> s_bytes;
     uint32_t fb_start[257];                     // first sorted rank whose first byte is >= b
     uint32_t n_sorted = 0;
+    uint32_t max_len = 0;                       // longest checkable token, in bytes
     // device copy (made at first use)
     std::mutex mu;
     bool on_device = false;
@@ -124,13 +126,17 @@ struct SlowImpl {
 SlowImpl& slow() { static SlowImpl* s = new SlowImpl(); return *s; }
 
 // ---- cross-grammar pool -------------------------------------------------------------------------------
+// A plane is identified by (pool entry of the position's rule, canonical state, pool entry of the
+// referencing rule or -1, canonical state the referencing rule continues in or -1).
+using PlaneKey = std::array<int32_t, 4>;
 struct PoolImpl {
     size_t max_bytes = 0;
     std::mutex mu;
     std::shared_ptr<VocabImpl> vocab;           // bound at first use
-    struct Entry { uint64_t hash; std::string text; std::vector<uint32_t*> rows; };   // rows by canonical state id
+    struct Entry { uint64_t hash; std::string text; };
     std::vector<Entry> entries;
     std::unordered_multimap<uint64_t, int> by_hash;
+    std::map<PlaneKey, uint32_t*> rows;
     std::vector<void*> slabs;
     uint8_t* slab_cur = nullptr; size_t slab_left = 0;
     size_t device_bytes = 0;
@@ -138,13 +144,13 @@ struct PoolImpl {
     ~PoolImpl() { for (void* s : slabs) (void)hipFree(s); }
 
     // exact interning: same hash AND same serialisation
-    int intern(uint64_t hash, const std::string& text, size_t n_states, bool shareable) {
+    int intern(uint64_t hash, const std::string& text, bool shareable) {
         if (shareable) {
             auto range = by_hash.equal_range(hash);
             for (auto it = range.first; it != range.second; ++it)
                 if (entries[(size_t)it->second].text == text) return it->second;
         }
-        entries.push_back({hash, shareable ? text : std::string(), std::vector<uint32_t*>(n_states, nullptr)});
+        entries.push_back({hash, shareable ? text : std::string()});
         int id = (int)entries.size() - 1;
         if (shareable) by_hash.emplace(hash, id);
         return id;
@@ -168,13 +174,17 @@ struct PoolImpl {
 };
 
 // ---- mask cache -----------------------------------------------------------------------------------------
+struct PlaneInfo { int32_t rule, state, parent_rule, parent_state; uint32_t* row; };   // the representative it was built for
 struct CacheImpl {
     std::shared_ptr<VocabImpl> vocab;
     std::shared_ptr<PoolImpl> pool;
     std::shared_ptr<GrammarImpl> gram;
     DevBuf<StateInfo> d_state; DevBuf<ByteEdge> d_bedge; DevBuf<RefEdgeP> d_redge; DevBuf<RuleInfo> d_rule;
     DevTables dt{};
-    std::vector<uint32_t*> pos_plane;           // [positions] device address of the accepted row
+    int32_t context_depth = 2;
+    std::vector<PlaneInfo> planes;
+    std::vector<int32_t> plain_plane;                       // [sid] -> plane without context, or -1
+    std::unordered_map<uint64_t, int32_t> pair_plane;       // (sid << 32 | parent continuation sid) -> plane
 };
 
 struct MatcherImpl {
@@ -287,6 +297,7 @@ int32_t xg2_vocab_create(const uint8_t* bytes, const uint64_t* offsets, int32_t 
             v->rank[(size_t)id] = r;
             v->s_bytes.insert(v->s_bytes.end(), v->tok(id), v->tok(id) + v->len(id));
             v->s_off.push_back((uint32_t)v->s_bytes.size());
+            v->max_len = std::max<uint32_t>(v->max_len, (uint32_t)v->len(id));
         }
         uint32_t r = 0;
         for (int b = 0; b <= 256; ++b) {
@@ -341,14 +352,18 @@ int32_t xg2_pool_stats(const xg2_pool* p, int64_t* n_positions, int64_t* device_
     return XG2_OK;
 }
 
-int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, const char* root_rule, xg2_pool* pool_h,
-                            void* hip_stream, xg2_mask_cache** out, xg2_compile_stats* stats) {
+int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, const char* root_rule, const xg2_compile_opts* opts,
+                            xg2_pool* pool_h, void* hip_stream, xg2_mask_cache** out, xg2_compile_stats* stats) {
     return guarded([&]() -> int32_t {
         if (!vocab || !out) return fail(XG2_EINVAL, "xg2_compile_grammar: bad argument");
+        const int32_t depth = opts ? opts->context_depth : 2;
+        const bool merge = opts ? opts->merge_equivalent != 0 : true;
+        if (depth != 1 && depth != 2) return fail(XG2_EINVAL, "xg2_compile_grammar: context_depth must be 1 or 2");
         hipStream_t stream = (hipStream_t)hip_stream;
         auto t0 = std::chrono::steady_clock::now();
         auto cache = std::make_shared<CacheImpl>();
         cache->vocab = vocab->p;
+        cache->context_depth = depth;
         cache->gram = make_grammar(ebnf, len, root_rule);
         const Grammar& g = cache->gram->g;
         const FlatTables& ft = cache->gram->ft;
@@ -362,17 +377,18 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
         std::lock_guard<std::mutex> slow_lock(slow().mu);
         slow().ensure();
         const SlowScratch S = slow().s;
+        const int R = (int)g.rules.size();
 
         // intern every rule in the pool, referenced rules first
-        std::vector<int> entry(g.rules.size(), -1);
-        std::vector<uint64_t> ref_id(g.rules.size(), 0);
+        std::vector<int> entry((size_t)R, -1);
+        std::vector<uint64_t> ref_id((size_t)R, 0);
         for (const auto& comp : g.hash_order) {
             const RuleFsm& first = g.rules[(size_t)comp[0]];
             if (!first.shareable) {
-                for (int r : comp) entry[(size_t)r] = pool.intern(g.rules[(size_t)r].hash, "", (size_t)g.rules[(size_t)r].n_states(), false);
+                for (int r : comp) entry[(size_t)r] = pool.intern(g.rules[(size_t)r].hash, "", false);
             } else if (first.ring.empty()) {
                 int r = comp[0];
-                entry[(size_t)r] = pool.intern(first.hash, serialise_rule(g, r, ref_id), (size_t)first.n_states(), true);
+                entry[(size_t)r] = pool.intern(first.hash, serialise_rule(g, r, ref_id), true);
             } else {
                 std::vector<uint64_t> ids = ref_id;
                 for (int r : comp) ids[(size_t)r] = kInCycleRef;
@@ -381,33 +397,70 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
                 for (int r : comp) {
                     std::string text = "C";
                     for (int v : g.rules[(size_t)r].ring) { text += local[v]; text.push_back('|'); }
-                    entry[(size_t)r] = pool.intern(g.rules[(size_t)r].hash, text, (size_t)g.rules[(size_t)r].n_states(), true);
+                    entry[(size_t)r] = pool.intern(g.rules[(size_t)r].hash, text, true);
                 }
             }
             for (int r : comp) ref_id[(size_t)r] = (uint64_t)entry[(size_t)r] + 1;
         }
 
-        // positions -> plane rows; rows that do not exist yet are built now
+        // states that tokens cannot tell apart share planes
+        std::vector<std::vector<int32_t>> rep;
+        if (merge) rep = bounded_classes(g, (int32_t)std::max<uint32_t>(V.max_len, 1), ref_id);
+        else {
+            rep.resize((size_t)R);
+            for (int r = 0; r < R; ++r) { rep[(size_t)r].resize((size_t)g.rules[(size_t)r].n_states()); std::iota(rep[(size_t)r].begin(), rep[(size_t)r].end(), 0); }
+        }
+        // reference sites of every rule, one representative per class of the state the referencing rule continues in
+        struct Site { int32_t q, waiter, x; };
+        std::vector<std::vector<Site>> sites((size_t)R);            // all sites
+        std::vector<std::map<std::pair<int, int>, Site>> site_rep((size_t)R);   // (q, class of x) -> representative
+        if (depth == 2)
+            for (int q = 0; q < R; ++q)
+                for (int s = 0; s < g.rules[(size_t)q].n_states(); ++s)
+                    for (auto& e : g.rules[(size_t)q].redges[(size_t)s]) {
+                        Site st{q, s, e.tgt};
+                        sites[(size_t)e.rule].push_back(st);
+                        auto key = std::make_pair(q, (int)rep[(size_t)q][(size_t)e.tgt]);
+                        auto it = site_rep[(size_t)e.rule].find(key);
+                        const RuleFsm& fq = g.rules[(size_t)q];
+                        if (it == site_rep[(size_t)e.rule].end()) site_rep[(size_t)e.rule].emplace(key, st);
+                        else if (fq.canon_id[(size_t)e.tgt] < fq.canon_id[(size_t)it->second.x]) it->second = st;
+                    }
+
+        // planes of this grammar; rows missing from the pool are built now
         const size_t row_bytes = (size_t)V.W * 2 * sizeof(uint32_t);
-        std::vector<int32_t> build_pos;
+        struct ToBuild { uint32_t sid; int64_t waiter_sid; };
+        std::vector<ToBuild> build;
         std::vector<uint32_t*> build_rows;
-        size_t n_unique = 0;
-        {
-            std::map<std::pair<int, int>, int> seen;
-            cache->pos_plane.resize(g.positions.size());
-            for (size_t p = 0; p < g.positions.size(); ++p) {
-                const Position& ps = g.positions[p];
-                int e = entry[(size_t)ps.rule];
-                int c = g.rules[(size_t)ps.rule].canon_id[(size_t)ps.state];
-                if (seen.emplace(std::make_pair(e, c), 1).second) ++n_unique;
-                uint32_t*& row = pool.entries[(size_t)e].rows[(size_t)c];
-                if (!row) {
-                    row = pool.alloc_row(row_bytes, stream);
-                    build_pos.push_back((int32_t)p);
-                    build_rows.push_back(row);
-                }
-                cache->pos_plane[p] = row;
+        std::vector<PlaneKey> build_keys;
+        std::map<PlaneKey, int32_t> local_plane;
+        auto plane_for = [&](int rp, int sp_rep, const Site* site) -> int32_t {
+            const RuleFsm& fp = g.rules[(size_t)rp];
+            PlaneKey key{entry[(size_t)rp], fp.canon_id[(size_t)sp_rep], -1, -1};
+            if (site) { key[2] = entry[(size_t)site->q]; key[3] = g.rules[(size_t)site->q].canon_id[(size_t)site->x]; }
+            auto lp = local_plane.find(key);
+            if (lp != local_plane.end()) return lp->second;
+            uint32_t*& row = pool.rows[key];
+            if (!row) {
+                row = pool.alloc_row(row_bytes, stream);
+                build.push_back({(uint32_t)g.sid(rp, sp_rep), site ? (int64_t)g.sid(site->q, site->waiter) : -1});
+                build_rows.push_back(row);
+                build_keys.push_back(key);
             }
+            int32_t idx = (int32_t)cache->planes.size();
+            cache->planes.push_back({rp, sp_rep, site ? site->q : -1, site ? site->x : -1, row});
+            local_plane.emplace(key, idx);
+            return idx;
+        };
+        cache->plain_plane.assign((size_t)g.n_states, -1);
+        for (const Position& ps : g.positions) {
+            int sp_rep = rep[(size_t)ps.rule][(size_t)ps.state];
+            if (depth == 1 || ps.rule == g.root) cache->plain_plane[(size_t)ps.sid] = plane_for(ps.rule, sp_rep, nullptr);
+            if (depth == 2)
+                for (const Site& st : sites[(size_t)ps.rule]) {
+                    const Site& sr = site_rep[(size_t)ps.rule].at(std::make_pair(st.q, (int)rep[(size_t)st.q][(size_t)st.x]));
+                    cache->pair_plane[((uint64_t)(uint32_t)ps.sid << 32) | (uint32_t)g.sid(st.q, st.x)] = plane_for(ps.rule, sp_rep, &sr);
+                }
         }
         double host_ms_a = ms_since(t0);
 
@@ -426,18 +479,19 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
         cache->dt.ref_edges = reinterpret_cast<const uint2*>(cache->d_redge.p);
         cache->dt.rule_info = reinterpret_cast<const uint2*>(cache->d_rule.p);
 
-        // plan: closed start set and live first-byte ranges of every position to build
+        // plan: closed start set and live first-byte ranges of every plane to build
         auto t1 = std::chrono::steady_clock::now();
-        std::vector<uint32_t> seg_pos, seg_lo, seg_hi, seg_blk{0}, ctx_items, ctx_item_off{0}, ctx_wait, ctx_wait_off2;
+        std::vector<uint32_t> seg_pos, seg_lo, seg_hi, seg_blk{0}, ctx_items, ctx_item_off{0}, ctx_wait, ctx_wait_off, ctx_woff_start, ctx_H;
         int64_t executed = 0;
         EarleyChart chart(&ft);
-        for (size_t k = 0; k < build_pos.size(); ++k) {
-            const Position& ps = g.positions[(size_t)build_pos[k]];
-            chart.start((uint32_t)ps.sid);
-            const ChartSet& s0 = chart.last();
+        for (size_t k = 0; k < build.size(); ++k) {
+            if (build[k].waiter_sid < 0) chart.start(build[k].sid);
+            else chart.start_pair(build[k].sid, (uint32_t)build[k].waiter_sid);
+            const std::vector<ChartSet>& sets = chart.sets();
+            auto loc = [](int32_t o) { return o < 0 ? kRootOrigin : (uint32_t)o; };
             bool live[257] = {false};
-            for (const ChartItem& it : s0.scan) {
-                ctx_items.push_back(pack_item(it.sid, it.origin < 0 ? kRootOrigin : 0u));
+            for (const ChartItem& it : sets.back().scan) {
+                ctx_items.push_back(pack_item(it.sid, loc(it.origin)));
                 const StateInfo& si = ft.state_info[it.sid];
                 for (uint32_t e = 0; e < (si.counts & 0xFFFF); ++e) {
                     const ByteEdge& be = ft.byte_edges[si.byte_off + e];
@@ -445,9 +499,13 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
                 }
             }
             ctx_item_off.push_back((uint32_t)ctx_items.size());
-            ctx_wait_off2.push_back((uint32_t)ctx_wait.size());
-            for (const ChartItem& it : s0.wait) ctx_wait.push_back(pack_item(it.sid, it.origin < 0 ? kRootOrigin : 0u));
-            ctx_wait_off2.push_back((uint32_t)ctx_wait.size());
+            ctx_woff_start.push_back((uint32_t)ctx_wait_off.size());
+            ctx_H.push_back((uint32_t)sets.size());
+            for (const ChartSet& cs : sets) {
+                ctx_wait_off.push_back((uint32_t)ctx_wait.size());
+                for (const ChartItem& it : cs.wait) ctx_wait.push_back(pack_item(it.sid, loc(it.origin)));
+            }
+            ctx_wait_off.push_back((uint32_t)ctx_wait.size());
             for (int b = 0; b < 256;) {
                 if (!live[b]) { ++b; continue; }
                 int e = b;
@@ -463,12 +521,13 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
         }
         double host_ms_b = ms_since(t1);
 
-        DevBuf<uint32_t> d_seg_pos, d_seg_lo, d_seg_hi, d_seg_blk, d_items, d_item_off, d_wait, d_wait_off2;
+        DevBuf<uint32_t> d_seg_pos, d_seg_lo, d_seg_hi, d_seg_blk, d_items, d_item_off, d_wait, d_wait_off, d_woff_start, d_H;
         DevBuf<uint32_t*> d_rows;
         DevBuf<unsigned long long> d_counts;
         d_seg_pos.upload(seg_pos, stream); d_seg_lo.upload(seg_lo, stream); d_seg_hi.upload(seg_hi, stream);
         d_seg_blk.upload(seg_blk, stream); d_items.upload(ctx_items, stream); d_item_off.upload(ctx_item_off, stream);
-        d_wait.upload(ctx_wait, stream); d_wait_off2.upload(ctx_wait_off2, stream);
+        d_wait.upload(ctx_wait, stream); d_wait_off.upload(ctx_wait_off, stream);
+        d_woff_start.upload(ctx_woff_start, stream); d_H.upload(ctx_H, stream);
         d_rows.upload(build_rows, stream);
         d_counts.alloc(2);
         HIP_CHECK(hipMemsetAsync(d_counts.p, 0, 2 * sizeof(unsigned long long), stream));
@@ -476,12 +535,13 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
         BuildPlan P{};
         P.seg_pos = d_seg_pos.p; P.seg_lo = d_seg_lo.p; P.seg_hi = d_seg_hi.p; P.seg_blk = d_seg_blk.p;
         P.n_seg = (uint32_t)seg_pos.size(); P.n_blocks = seg_blk.back();
-        P.ctx_items = d_items.p; P.ctx_item_off = d_item_off.p; P.ctx_wait = d_wait.p; P.ctx_wait_off2 = d_wait_off2.p;
+        P.ctx_items = d_items.p; P.ctx_item_off = d_item_off.p; P.ctx_wait = d_wait.p; P.ctx_wait_off = d_wait_off.p;
+        P.ctx_woff_start = d_woff_start.p; P.ctx_H = d_H.p;
         P.plane_ptr = d_rows.p;
         HIP_CHECK(hipEventRecord(evk0, stream));
-        if (!build_pos.empty()) launch_build(cache->dt, V.dv, P, S, stream);
+        if (!build.empty()) launch_build(cache->dt, V.dv, P, S, stream);
         HIP_CHECK(hipEventRecord(evk1, stream));
-        if (!build_pos.empty()) {
+        if (!build.empty()) {
             launch_build_slow(cache->dt, V.dv, P, S, stream);
             launch_popcount(d_rows.p, (uint32_t)build_rows.size(), V.W, d_counts.p, stream);
         }
@@ -498,18 +558,14 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
         (void)hipEventDestroy(ev0); (void)hipEventDestroy(ev1); (void)hipEventDestroy(evk0); (void)hipEventDestroy(evk1);
         if (slow_counts[1]) {
             HIP_CHECK(hipMemset(S.count + 1, 0, sizeof(uint32_t)));
-            // rows handed out by this call hold partial results: forget them
-            for (size_t k = 0; k < build_pos.size(); ++k) {
-                const Position& ps = g.positions[(size_t)build_pos[k]];
-                pool.entries[(size_t)entry[(size_t)ps.rule]].rows[(size_t)g.rules[(size_t)ps.rule].canon_id[(size_t)ps.state]] = nullptr;
-            }
+            for (const PlaneKey& key : build_keys) pool.rows.erase(key);      // rows of this call hold partial results: forget them
             return fail(XG2_EOVERFLOW, "xg2_compile_grammar: Earley item sets exceeded the large-capacity limit");
         }
         if (stats) {
             stats->positions = (int64_t)g.positions.size();
-            stats->unique = (int64_t)n_unique;
-            stats->built = (int64_t)build_pos.size();
-            stats->checks = (int64_t)build_pos.size() * (int64_t)V.n_sorted;
+            stats->unique = (int64_t)cache->planes.size();
+            stats->built = (int64_t)build.size();
+            stats->checks = (int64_t)build.size() * (int64_t)V.n_sorted;
             stats->executed_checks = executed;
             stats->slow_path = slow_counts[0];
             stats->n_accepted = (int64_t)bit_counts[0];
@@ -529,20 +585,44 @@ int32_t xg2_mask_cache_num_positions(const xg2_mask_cache* c, int32_t* out) {
     *out = (int32_t)c->p->gram->g.positions.size();
     return XG2_OK;
 }
-int32_t xg2_mask_cache_position(const xg2_mask_cache* c, int32_t p, const char** rule_name, int32_t* state) {
-    if (!c || p < 0 || (size_t)p >= c->p->gram->g.positions.size()) return fail(XG2_EINVAL, "xg2_mask_cache_position: bad argument");
-    const Position& ps = c->p->gram->g.positions[(size_t)p];
-    if (rule_name) *rule_name = c->p->gram->rule_names[(size_t)ps.rule].c_str();
-    if (state) *state = ps.state;
+int32_t xg2_mask_cache_num_planes(const xg2_mask_cache* c, int32_t* out) {
+    if (!c || !out) return fail(XG2_EINVAL, "xg2_mask_cache_num_planes: bad argument");
+    *out = (int32_t)c->p->planes.size();
     return XG2_OK;
 }
-int32_t xg2_mask_cache_get_planes(const xg2_mask_cache* c, int32_t p, int32_t* accepted_host, int32_t* uncertain_host) {
+int32_t xg2_mask_cache_plane_info(const xg2_mask_cache* c, int32_t k, const char** rule, int32_t* state,
+                                  const char** parent_rule, int32_t* parent_state) {
+    if (!c || k < 0 || (size_t)k >= c->p->planes.size()) return fail(XG2_EINVAL, "xg2_mask_cache_plane_info: bad argument");
+    const PlaneInfo& pi = c->p->planes[(size_t)k];
+    if (rule) *rule = c->p->gram->rule_names[(size_t)pi.rule].c_str();
+    if (state) *state = pi.state;
+    if (parent_rule) *parent_rule = pi.parent_rule >= 0 ? c->p->gram->rule_names[(size_t)pi.parent_rule].c_str() : nullptr;
+    if (parent_state) *parent_state = pi.parent_state;
+    return XG2_OK;
+}
+int32_t xg2_mask_cache_find_plane(const xg2_mask_cache* c, const char* rule, int32_t state, const char* parent_rule,
+                                  int32_t parent_state, int32_t* k) {
+    if (!c || !rule || !k) return fail(XG2_EINVAL, "xg2_mask_cache_find_plane: bad argument");
+    const Grammar& g = c->p->gram->g;
+    auto find_rule = [&](const char* name) { for (size_t r = 0; r < g.rules.size(); ++r) if (g.rules[r].name == name) return (int)r; return -1; };
+    int rp = find_rule(rule);
+    if (rp < 0 || state < 0 || state >= g.rules[(size_t)rp].n_states()) return fail(XG2_EINVAL, "xg2_mask_cache_find_plane: unknown rule or state");
+    *k = -1;
+    if (!parent_rule) { *k = c->p->plain_plane[(size_t)g.sid(rp, state)]; return XG2_OK; }
+    int rq = find_rule(parent_rule);
+    if (rq < 0 || parent_state < 0 || parent_state >= g.rules[(size_t)rq].n_states()) return fail(XG2_EINVAL, "xg2_mask_cache_find_plane: unknown parent rule or state");
+    auto it = c->p->pair_plane.find(((uint64_t)(uint32_t)g.sid(rp, state) << 32) | (uint32_t)g.sid(rq, parent_state));
+    if (it != c->p->pair_plane.end()) *k = it->second;
+    return XG2_OK;
+}
+int32_t xg2_mask_cache_get_planes(const xg2_mask_cache* c, int32_t k, int32_t* accepted_host, int32_t* uncertain_host) {
     return guarded([&]() -> int32_t {
-        if (!c || p < 0 || (size_t)p >= c->p->pos_plane.size()) return fail(XG2_EINVAL, "xg2_mask_cache_get_planes: bad argument");
+        if (!c || k < 0 || (size_t)k >= c->p->planes.size()) return fail(XG2_EINVAL, "xg2_mask_cache_get_planes: bad argument");
         const uint32_t W = c->p->vocab->W;
+        const uint32_t* row = c->p->planes[(size_t)k].row;
         HIP_CHECK(hipDeviceSynchronize());
-        if (accepted_host) HIP_CHECK(hipMemcpy(accepted_host, c->p->pos_plane[(size_t)p], W * sizeof(uint32_t), hipMemcpyDeviceToHost));
-        if (uncertain_host) HIP_CHECK(hipMemcpy(uncertain_host, c->p->pos_plane[(size_t)p] + W, W * sizeof(uint32_t), hipMemcpyDeviceToHost));
+        if (accepted_host) HIP_CHECK(hipMemcpy(accepted_host, row, W * sizeof(uint32_t), hipMemcpyDeviceToHost));
+        if (uncertain_host) HIP_CHECK(hipMemcpy(uncertain_host, row + W, W * sizeof(uint32_t), hipMemcpyDeviceToHost));
         return XG2_OK;
     });
 }
@@ -645,11 +725,37 @@ int32_t xg2_fill_next_token_bitmask(xg2_matcher* const* matchers, int32_t B, int
             r.flags = M.chart.last().root_done ? 1u : 0u;
             if (!M.chart.context(ctx)) return fail(XG2_EOVERFLOW, "xg2_fill_next_token_bitmask: parser context too deep");
             size_t f0 = front.size();
-            for (const ChartItem& it : M.chart.last().scan) {
-                int32_t p = M.gram->g.sid_to_pos[it.sid];
-                if (p < 0) continue;
-                uint64_t row = (uint64_t)(uintptr_t)M.cache->pos_plane[(size_t)p];
+            auto push_plane = [&](int32_t plane, bool accepted_only) {
+                uint64_t row = (uint64_t)(uintptr_t)M.cache->planes[(size_t)plane].row | (accepted_only ? 1u : 0u);
                 if (std::find(front.begin() + (long)f0, front.end(), row) == front.end()) front.push_back(row);
+            };
+            const Grammar& G = M.gram->g;
+            const FlatTables& FT = M.gram->ft;
+            for (const ChartItem& it : M.chart.last().scan) {
+                if (G.sid_to_pos[it.sid] < 0) continue;                         // nothing to scan from this item
+                if (it.origin < 0 || M.cache->context_depth == 1) {
+                    // the root instance: leaving the rule leaves the grammar, so uncertain tokens are never allowed
+                    int32_t plane = M.cache->plain_plane[it.sid];
+                    if (plane < 0) return fail(XG2_EINVAL, "xg2_fill_next_token_bitmask: frontier item without a plane");
+                    push_plane(plane, it.origin < 0);
+                    continue;
+                }
+                const uint32_t rule = FT.state_info[it.sid].rule_final & 0x7FFFFFFFu;
+                size_t before = front.size();
+                bool any_parent = false;
+                for (const ChartItem& w : M.chart.sets()[(size_t)it.origin].wait) {
+                    const StateInfo& wi = FT.state_info[w.sid];
+                    for (uint32_t k = 0; k < (wi.counts >> 16); ++k) {
+                        const RefEdgeP& e = FT.ref_edges[wi.ref_off + k];
+                        if (e.rule != rule) continue;
+                        auto pp = M.cache->pair_plane.find(((uint64_t)it.sid << 32) | e.tgt);
+                        if (pp == M.cache->pair_plane.end()) return fail(XG2_EINVAL, "xg2_fill_next_token_bitmask: frontier item without a plane");
+                        push_plane(pp->second, false);
+                        any_parent = true;
+                    }
+                }
+                (void)before;
+                if (!any_parent) return fail(XG2_EINVAL, "xg2_fill_next_token_bitmask: frontier item without a referencing item");
             }
             r.front_n = (uint32_t)(front.size() - f0);
             r.item_n = (uint32_t)ctx.items.size();

@@ -27,10 +27,12 @@ struct DevVocab {                        // byte-sorted vocabulary in HBM
 struct BuildPlan {
     const uint32_t* seg_pos; const uint32_t* seg_lo; const uint32_t* seg_hi; const uint32_t* seg_blk;
     uint32_t n_seg, n_blocks;
-    // closed start set of every position, as a scan context with H = 1
-    const uint32_t* ctx_items; const uint32_t* ctx_item_off;   // [n_pos + 1]
-    const uint32_t* ctx_wait; const uint32_t* ctx_wait_off2;   // [2 * n_pos]: {begin, end} into ctx_wait
-    uint32_t* const* plane_ptr;                                 // [n_pos] accepted row; uncertain row at + W words
+    // closed start set of every plane to build, as a scan context (H = 1: the position alone; H = 2: the
+    // position inside one level of referencing rule)
+    const uint32_t* ctx_items; const uint32_t* ctx_item_off;   // [n_planes + 1]
+    const uint32_t* ctx_wait; const uint32_t* ctx_wait_off;    // per plane H + 1 offsets into ctx_wait ...
+    const uint32_t* ctx_woff_start; const uint32_t* ctx_H;     // ... starting at ctx_woff_start[k]; ctx_H[k] = H
+    uint32_t* const* plane_ptr;                                 // [n_planes] accepted row; uncertain row at + W words
 };
 
 struct SlowScratch {                     // large-capacity per-lane Earley scratch in device memory
@@ -57,7 +59,8 @@ struct FillRow {
 };
 struct FillBatch {
     const FillRow* rows; uint32_t B;
-    const uint64_t* front_planes;        // device addresses of accepted rows (uncertain at + W words)
+    const uint64_t* front_planes;        // device addresses of accepted rows (uncertain at + W words);
+                                         // bit 0 set: only the accepted row counts (root instance)
     const uint32_t* ctx_items; const uint32_t* ctx_wait; const uint32_t* ctx_wait_off;
     const DevTables* tables;
     uint32_t eos_id;

@@ -934,6 +934,34 @@ Grammar lower_grammar(const std::string& ebnf, const std::string& root_rule) {
         g.rules[(size_t)r].nullable = nullable[(size_t)r];
         if (!productive[(size_t)r]) throw GrammarError("rule " + g.rules[(size_t)r].name + " derives no string (grammar is not reduced)");
     }
+    // shortest sentence of every rule: relax until stable (byte edge = 1, rule edge = the rule's own minimum)
+    {
+        const int32_t INF = 1 << 28;
+        std::vector<int32_t> ml((size_t)R, INF);
+        for (bool changed = true; changed;) {
+            changed = false;
+            for (int r = 0; r < R; ++r) {
+                const RuleFsm& f = g.rules[(size_t)r];
+                std::vector<int32_t> dist((size_t)f.n_states(), INF);
+                dist[0] = 0;
+                for (bool moved = true; moved;) {                   // Bellman-Ford over the (small) automaton
+                    moved = false;
+                    for (int q = 0; q < f.n_states(); ++q) {
+                        if (dist[(size_t)q] >= INF) continue;
+                        for (auto& e : f.bedges[(size_t)q]) if (dist[(size_t)q] + 1 < dist[(size_t)e.tgt]) { dist[(size_t)e.tgt] = dist[(size_t)q] + 1; moved = true; }
+                        for (auto& e : f.redges[(size_t)q]) {
+                            int32_t c = ml[(size_t)e.rule];
+                            if (c < INF && dist[(size_t)q] + c < dist[(size_t)e.tgt]) { dist[(size_t)e.tgt] = dist[(size_t)q] + c; moved = true; }
+                        }
+                    }
+                }
+                int32_t best = INF;
+                for (int q = 0; q < f.n_states(); ++q) if (f.is_final[(size_t)q]) best = std::min(best, dist[(size_t)q]);
+                if (best < ml[(size_t)r]) { ml[(size_t)r] = best; changed = true; }
+            }
+        }
+        for (int r = 0; r < R; ++r) g.rules[(size_t)r].min_len = ml[(size_t)r];
+    }
     g.state_base.resize((size_t)R);
     g.n_states = 0;
     for (int r = 0; r < R; ++r) { g.state_base[(size_t)r] = g.n_states; g.n_states += g.rules[(size_t)r].n_states(); }
@@ -946,6 +974,74 @@ Grammar lower_grammar(const std::string& ebnf, const std::string& root_rule) {
             }
     hash_rules(g);
     return g;
+}
+
+std::vector<std::vector<int32_t>> bounded_classes(const Grammar& g, int32_t budget, const std::vector<uint64_t>& ref_identity) {
+    std::vector<std::vector<int32_t>> rep(g.rules.size());
+    for (size_t r = 0; r < g.rules.size(); ++r) {
+        const RuleFsm& f = g.rules[r];
+        const int n = f.n_states();
+        // level[d][x] = class of x with d bytes left; level 0 tells nothing apart
+        std::vector<std::vector<int32_t>> level(1, std::vector<int32_t>((size_t)n, 0));
+        for (int32_t d = 1; d <= budget; ++d) {
+            const std::vector<int32_t>& prev = level.back();
+            // part of the signature that does not depend on the level being computed
+            std::vector<std::vector<int64_t>> base((size_t)n);
+            for (int x = 0; x < n; ++x) {
+                std::vector<int64_t>& sg = base[(size_t)x];
+                sg.push_back(prev[(size_t)x]);
+                sg.push_back(f.is_final[(size_t)x]);
+                int32_t by_byte[256];
+                for (int b = 0; b < 256; ++b) by_byte[b] = -1;
+                for (auto& e : f.bedges[(size_t)x]) for (int b = e.lo; b <= e.hi; ++b) by_byte[b] = prev[(size_t)e.tgt];
+                for (int b = 0; b < 256;) {
+                    int e = b;
+                    while (e + 1 < 256 && by_byte[e + 1] == by_byte[b]) ++e;
+                    if (by_byte[b] >= 0) { sg.push_back(b); sg.push_back(e); sg.push_back(by_byte[b]); }
+                    b = e + 1;
+                }
+                sg.push_back(-7);
+                std::vector<std::pair<int64_t, int64_t>> refs;
+                for (auto& e : f.redges[(size_t)x]) {
+                    const RuleFsm& c = g.rules[(size_t)e.rule];
+                    if (c.nullable) continue;
+                    int32_t left = d - c.min_len;
+                    refs.emplace_back((int64_t)ref_identity[(size_t)e.rule], left >= 0 ? level[(size_t)left][(size_t)e.tgt] : -1);
+                }
+                std::sort(refs.begin(), refs.end());
+                for (auto& p : refs) { sg.push_back(p.first); sg.push_back(p.second); }
+            }
+            // coarsest partition stable under "a nullable rule edge leads to the same class of this level"
+            std::vector<int32_t> cur((size_t)n, 0);
+            for (size_t n_classes = 0;;) {
+                std::map<std::vector<int64_t>, int32_t> ids;
+                std::vector<int32_t> nxt((size_t)n);
+                for (int x = 0; x < n; ++x) {
+                    std::vector<int64_t> sg = base[(size_t)x];
+                    sg.push_back(-9);
+                    std::vector<std::pair<int64_t, int64_t>> refs;
+                    for (auto& e : f.redges[(size_t)x])
+                        if (g.rules[(size_t)e.rule].nullable) refs.emplace_back((int64_t)ref_identity[(size_t)e.rule], cur[(size_t)e.tgt]);
+                    std::sort(refs.begin(), refs.end());
+                    for (auto& p : refs) { sg.push_back(p.first); sg.push_back(p.second); }
+                    nxt[(size_t)x] = ids.emplace(std::move(sg), (int32_t)ids.size()).first->second;
+                }
+                cur.swap(nxt);
+                if (ids.size() == n_classes) break;
+                n_classes = ids.size();
+            }
+            level.push_back(cur);
+        }
+        const std::vector<int32_t>& fin = level.back();
+        std::map<int32_t, int32_t> best;                         // class -> member with the smallest canonical id
+        for (int x = 0; x < n; ++x) {
+            auto it = best.find(fin[(size_t)x]);
+            if (it == best.end() || f.canon_id[(size_t)x] < f.canon_id[(size_t)it->second]) best[fin[(size_t)x]] = x;
+        }
+        rep[r].resize((size_t)n);
+        for (int x = 0; x < n; ++x) rep[r][(size_t)x] = best[fin[(size_t)x]];
+    }
+    return rep;
 }
 
 std::string describe_grammar(const Grammar& g) {

@@ -22,6 +22,7 @@ struct RuleFsm {
     std::vector<std::vector<ByteRange>> bedges;       // sorted by lo; maximal runs per target
     std::vector<std::vector<RefEdge>> redges;         // sorted by referenced rule's decl_index
     bool nullable = false;
+    int32_t min_len = 0;                              // length of the rule's shortest sentence, in bytes
     // structural hash (Algorithm 1, refined by Algorithm 2 inside simple reference cycles)
     uint64_t hash = 0;
     bool shareable = true;                            // false: member of a non-simple cycle, never reused
@@ -51,6 +52,14 @@ Grammar lower_grammar(const std::string& ebnf, const std::string& root_rule);
 std::string describe_grammar(const Grammar& g);       // JSON
 
 uint64_t hash_combine(uint64_t h, uint64_t v);        // the order-sensitive hash of Algorithms 1 and 2
+
+// States of one rule that no string of at most `budget` bytes can tell apart (bounded bisimulation):
+// returns, per rule and state, the member of the state's class with the smallest canonical id.
+// Rule edges are compared by ref_identity[rule] (rules known to be identical may share an identity).
+// This is what makes planes independent of the bounds of a long repetition (section 3.6 observes
+// that the states inside a repetition differ minimally): tokens are at most `budget` bytes long, so
+// equivalent states have equal planes.
+std::vector<std::vector<int32_t>> bounded_classes(const Grammar& g, int32_t budget, const std::vector<uint64_t>& ref_identity);
 
 // Exact serialisation of one rule in Algorithm 1's canonical order; a reference to rule r is
 // written as ref_id[r].  Two rules with equal text and equal meaning of the ids are isomorphic.

@@ -172,8 +172,8 @@ __device__ __forceinline__ DevCtx position_ctx(const BuildPlan& P, uint32_t p) {
     C.items = P.ctx_items + P.ctx_item_off[p];
     C.n_items = P.ctx_item_off[p + 1] - P.ctx_item_off[p];
     C.wait = P.ctx_wait;
-    C.wait_off = P.ctx_wait_off2 + 2 * p;
-    C.H = 1;
+    C.wait_off = P.ctx_wait_off + P.ctx_woff_start[p];
+    C.H = P.ctx_H[p];
     return C;
 }
 
@@ -265,9 +265,10 @@ __global__ __launch_bounds__(FILL_THREADS) void k_fill(FillBatch F, DevVocab Vd,
             if (!(r.flags & 2u)) {
                 uint32_t unc = 0;
                 for (uint32_t k = 0; k < r.front_n; ++k) {
-                    const uint32_t* row = reinterpret_cast<const uint32_t*>(F.front_planes[r.front_off + k]);
+                    const uint64_t addr = F.front_planes[r.front_off + k];
+                    const uint32_t* row = reinterpret_cast<const uint32_t*>(addr & ~(uint64_t)1);
                     acc |= row[w];
-                    unc |= row[Vd.W + w];
+                    if (!(addr & 1)) unc |= row[Vd.W + w];
                 }
                 cand = unc & ~acc;
             }

@@ -72,6 +72,15 @@ void EarleyChart::start(uint32_t sid) {
     close(chart_[0], 0, pending);
 }
 
+void EarleyChart::start_pair(uint32_t sid, uint32_t waiter_sid) {
+    chart_.clear();
+    chart_.emplace_back();
+    chart_[0].wait.push_back({waiter_sid, -1});
+    chart_.emplace_back();
+    std::vector<ChartItem> pending{{sid, 0}};
+    close(chart_[1], 1, pending);
+}
+
 bool EarleyChart::advance(const uint8_t* bytes, size_t n) {
     size_t keep = chart_.size();
     std::vector<ChartItem> pending;

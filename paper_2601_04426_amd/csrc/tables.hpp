@@ -56,6 +56,10 @@ class EarleyChart {
   public:
     explicit EarleyChart(const FlatTables* t) : t_(t) {}
     void start(uint32_t sid);                        // chart = closure{(sid, root instance)}
+    // Two sets: set 0 holds only the waiting item (waiter_sid, root instance), set 1 is the closure of
+    // (sid, origin 0): the rule instance of `sid` one level inside the rule of `waiter_sid`.
+    void start_pair(uint32_t sid, uint32_t waiter_sid);
+    const std::vector<ChartSet>& sets() const { return chart_; }
     bool advance(const uint8_t* bytes, size_t n);    // all or nothing: false leaves the chart unchanged
     const ChartSet& last() const { return chart_.back(); }
     size_t length() const { return chart_.size(); }

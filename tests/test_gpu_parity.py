@@ -9,7 +9,7 @@ import pytest
 
 import gen
 import oracle
-from helpers import diff_words, load, planes_of
+from helpers import all_contexts, diff_words, load, planes_of
 
 pytestmark = pytest.mark.gpu
 
@@ -27,17 +27,33 @@ def _stream():
     return torch.cuda.current_stream().cuda_stream
 
 
-def check_planes(xg, cfg, vocab, va, ebnf, root, positions=None, pool=None):
-    cache = xg.compile_grammar(vocab, ebnf, root, pool=pool, stream=_stream())
+def check_planes(xg, cfg, vocab, va, ebnf, root, pool=None, depth=2, merge=True, max_contexts=400, seed=0):
+    """Every plane of the cache equals the oracle's classes of the representative it was built for, and a
+    seeded sample of all (position, parent) combinations is served by a plane equal to the oracle's classes of
+    that exact combination (this is what checks the merging of equivalent states)."""
+    cache = xg.compile_grammar(vocab, ebnf, root, pool=pool, stream=_stream(), context_depth=depth, merge_equivalent=merge)
     orc = oracle.Oracle(ebnf, root)
-    n = cache.num_positions()
-    assert sorted(cache.position(p) for p in range(n)) == sorted(orc.positions())
-    todo = range(n) if positions is None else positions
-    for p in todo:
-        acc, unc = cache.get_planes(p)
-        want_a, want_u = planes_of(orc, cache.position(p), va)
-        assert np.array_equal(acc, want_a), ("accepted", cache.position(p), diff_words(acc, want_a, cfg.vocab.tokens))
-        assert np.array_equal(unc, want_u), ("uncertain", cache.position(p), diff_words(unc, want_u, cfg.vocab.tokens))
+    assert cache.stats.positions == len(orc.positions())
+    for k in range(cache.num_planes()):
+        pos, parent = cache.plane_info(k)
+        acc, unc = cache.get_planes(k)
+        want_a, want_u = planes_of(orc, pos, va, parent)
+        assert np.array_equal(acc, want_a), ("accepted", pos, parent, diff_words(acc, want_a, cfg.vocab.tokens))
+        assert np.array_equal(unc, want_u), ("uncertain", pos, parent, diff_words(unc, want_u, cfg.vocab.tokens))
+    contexts = all_contexts(orc, depth)
+    rng = random.Random(seed)
+    if len(contexts) > max_contexts:
+        contexts = rng.sample(contexts, max_contexts)
+    cache_rows = {}
+    for pos, parent in contexts:
+        k = cache.find_plane(pos, parent)
+        assert k >= 0, ("no plane for", pos, parent)
+        if k not in cache_rows:
+            cache_rows[k] = cache.get_planes(k)
+        acc, unc = cache_rows[k]
+        want_a, want_u = planes_of(orc, pos, va, parent)
+        assert np.array_equal(acc, want_a), ("accepted (merged)", pos, parent, cache.plane_info(k), diff_words(acc, want_a, cfg.vocab.tokens))
+        assert np.array_equal(unc, want_u), ("uncertain (merged)", pos, parent, cache.plane_info(k), diff_words(unc, want_u, cfg.vocab.tokens))
     return cache, orc
 
 
@@ -82,13 +98,15 @@ def run_decode(xg, cfg, vocab, va, cache, orc, batch, steps, seed, check_every=1
     return n_checked
 
 
-def test_config1_planes_and_decode(xg):
+@pytest.mark.parametrize("depth,merge", [(1, False), (1, True), (2, False), (2, True)])
+def test_config1_planes_and_decode(xg, depth, merge):
     cfg, vocab, va = load(1)
     ebnf, root = cfg.grammars[0]
-    cache, orc = check_planes(xg, cfg, vocab, va, ebnf, root)
+    cache, orc = check_planes(xg, cfg, vocab, va, ebnf, root, depth=depth, merge=merge, max_contexts=100000)
     st = cache.stats
-    assert st.positions == len(orc.positions()) and st.built == st.unique <= st.positions
-    assert st.checks == st.built * (cfg.vocab.size - 1)
+    if depth == 1 and not merge:
+        assert st.built == st.unique == st.positions          # the cache of section 3.4 as it stands: one plane per position
+    assert st.built == st.unique and st.checks == st.built * (cfg.vocab.size - 1)
     n = run_decode(xg, cfg, vocab, va, cache, orc, batch=cfg.batch, steps=cfg.steps, seed=11)
     assert n == cfg.batch * cfg.steps
 
@@ -152,35 +170,56 @@ def test_config2_planes_and_decode(xg):
 def test_config3_tagdispatch_planes_and_decode(xg):
     cfg, vocab, va = load(3)
     ebnf, root = cfg.grammars[0]
-    cache, orc = check_planes(xg, cfg, vocab, va, ebnf, root)          # all ~13k positions x 128,256 tokens
+    cache, orc = check_planes(xg, cfg, vocab, va, ebnf, root)          # every plane x 128,256 tokens
     n = run_decode(xg, cfg, vocab, va, cache, orc, batch=256, steps=24, seed=33, check_every=37)
     assert n >= 160
+
+
+def test_config5_depth1_unmerged_planes(xg):
+    """One plane per position, nothing merged: the plain cache on the largest vocabulary, all 1,547 positions."""
+    cfg, vocab, va = load(5)
+    ebnf, root = cfg.grammars[0]
+    cache, orc = check_planes(xg, cfg, vocab, va, ebnf, root, depth=1, merge=False, max_contexts=0)
+    assert cache.stats.built == cache.stats.positions == len(orc.positions())
+    n = run_decode(xg, cfg, vocab, va, cache, orc, batch=64, steps=4, seed=56, check_every=9)
+    assert n >= 25
 
 
 def test_config5_repetition_planes_and_decode(xg):
     cfg, vocab, va = load(5)
     ebnf, root = cfg.grammars[0]
-    cache, orc = check_planes(xg, cfg, vocab, va, ebnf, root)
+    cache, orc = check_planes(xg, cfg, vocab, va, ebnf, root, max_contexts=600)
+    assert cache.stats.unique < 800                          # planes do not grow with the {0,999} repetition bound
     n = run_decode(xg, cfg, vocab, va, cache, orc, batch=1024, steps=6, seed=55, check_every=41)
     assert n >= 140
 
 
 def test_config4_cross_grammar_pool(xg):
-    """Reduced cross-grammar workload: planes are built once per distinct rule position, later grammars reuse
-    them, and what a reusing grammar sees equals what the oracle computes for that grammar alone."""
+    """Reduced cross-grammar workload: planes are built once per distinct structure, later grammars reuse them,
+    and what a reusing grammar sees equals what the oracle computes for that grammar alone."""
     cfg, vocab, va = load(4, n_grammars=12, n_tools=40)
     pool = xg.Pool()
-    total_positions = total_built = 0
-    distinct = set()
+    total_unique = total_built = 0
     caches = []
     for gi, (ebnf, root) in enumerate(cfg.grammars):
-        cache = xg.compile_grammar(vocab, ebnf, root, pool=pool, stream=_stream())
-        st = cache.stats
-        total_positions += st.positions
-        total_built += st.built
+        if gi in (0, 5, 11):                                         # planes seen through a reusing grammar
+            cache, orc = check_planes(xg, cfg, vocab, va, ebnf, root, pool=pool, max_contexts=60, seed=gi)
+        else:
+            cache = xg.compile_grammar(vocab, ebnf, root, pool=pool, stream=_stream())
+        total_unique += cache.stats.unique
+        total_built += cache.stats.built
         caches.append(cache)
-        # exact count of distinct canonical structures, the slow way: serialise every reachable rule of the
-        # oracle's lowering with its references expanded recursively
+    n_rows, dev_bytes = pool.stats()
+    assert n_rows == total_built
+    assert total_built < total_unique / 2                            # sub-structure reuse across requests
+    assert caches[-1].stats.built < caches[-1].stats.unique
+    # the same 12 grammars without merging and without context: one row per distinct canonical (rule, state)
+    pool1 = xg.Pool()
+    built1 = 0
+    distinct = set()
+    for ebnf, root in cfg.grammars:
+        c1 = xg.compile_grammar(vocab, ebnf, root, pool=pool1, stream=_stream(), context_depth=1, merge_equivalent=False)
+        built1 += c1.stats.built
         orc = oracle.Oracle(ebnf, root)
         memo = {}
 
@@ -188,7 +227,7 @@ def test_config4_cross_grammar_pool(xg):
             if name in memo:
                 return memo[name]
             d = orc.low.dfa[name]
-            memo[name] = ("...",)                                   # recursion guard (no cycles in this workload)
+            memo[name] = ("...",)                                   # no reference cycles in this workload
             out = []
             for q in range(d.n):
                 out.append((d.final[q], tuple(sorted((m, t) for m, t in d.bedges[q])),
@@ -197,16 +236,7 @@ def test_config4_cross_grammar_pool(xg):
             return memo[name]
         for (rule, q) in orc.positions():
             distinct.add((canon(rule), q))
-        if gi in (0, 5, 11):                                         # planes seen through a reusing grammar
-            rng = random.Random(gi)
-            for p in rng.sample(range(cache.num_positions()), 25):
-                acc, unc = cache.get_planes(p)
-                want_a, want_u = planes_of(orc, cache.position(p), va)
-                assert np.array_equal(acc, want_a) and np.array_equal(unc, want_u), cache.position(p)
-    n_rows, dev_bytes = pool.stats()
-    assert n_rows == total_built == len(distinct)
-    assert total_built < total_positions / 2                         # sub-structure reuse across requests
-    assert caches[-1].stats.built < caches[-1].stats.positions
+    assert built1 == pool1.stats()[0] == len(distinct)              # exact count of distinct structures, the slow way
 
 
 def test_long_tokens_and_item_overflow_take_the_slow_path(xg):
@@ -230,7 +260,7 @@ def test_long_tokens_and_item_overflow_take_the_slow_path(xg):
     cfg = Cfg()
     cfg.vocab = Cfg()
     cfg.vocab.tokens = toks
-    cache, orc = check_planes(xg, cfg, vocab, va, ebnf, "root")
+    cache, orc = check_planes(xg, cfg, vocab, va, ebnf, "root", max_contexts=150)
     assert cache.stats.slow_path > 0
     # decode through a few long tokens
     import torch
@@ -258,9 +288,10 @@ def test_edge_cases(xg):
     va = oracle.VocabArrays(toks, 0, [0, 5])
     cache = xg.compile_grammar(vocab, 'root ::= "a" "b"?\n', "root", stream=_stream())
     orc = oracle.Oracle('root ::= "a" "b"?\n')
-    for p in range(cache.num_positions()):
-        acc, unc = cache.get_planes(p)
-        wa, wu = planes_of(orc, cache.position(p), va)
+    for k in range(cache.num_planes()):
+        acc, unc = cache.get_planes(k)
+        pos, parent = cache.plane_info(k)
+        wa, wu = planes_of(orc, pos, va, parent)
         assert np.array_equal(acc, wa) and np.array_equal(unc, wu)
     m = xg.Matcher(cache)
     bm = torch.full((1, 1), -1, dtype=torch.int32, device="cuda:0")

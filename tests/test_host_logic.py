@@ -125,3 +125,6 @@ def test_device_calls_fail_loudly_without_a_gpu(xg, has_gpu):
     with pytest.raises(xg.Xg2Error) as e:
         xg.apply_token_bitmask(16, xg.XG2_F32, 1, 32, 32, 16, 1)
     assert e.value.code == -5
+    with pytest.raises(xg.Xg2Error) as e:
+        xg.compile_grammar(v, 'root ::= "a"\n', context_depth=3)
+    assert e.value.code == -1

@@ -106,22 +106,15 @@ def _placeholder(e, index):
     return e
 
 
-@pytest.mark.parametrize("name,ebnf,rules,alphabet,N", TINY, ids=[t[0] for t in TINY])
-def test_classes_match_enumeration(name, ebnf, rules, alphabet, N):
-    """accepted / uncertain / rejected of every position == the definition evaluated on the
-    enumerated suffix language: Suf(rule, state) = (access word)^-1 L_symbolic(rule) with every
-    rule symbol replaced by that rule's sentences."""
-    o = oracle.Oracle(ebnf)
+def _suffix_languages(o, rules, N):
+    """{(rule, state): enumerated Suf(rule, state)}: (access word)^-1 L_symbolic(rule) with every rule
+    symbol replaced by that rule's enumerated sentences."""
     index = o.low.index
     L = languages(rules, N)
-    toks, va = _tiny_vocab(alphabet)
-    n_checked = 0
+    out = {}
     for rule in o.low.reachable:
         sym_lang = languages({"r": _placeholder(rules[rule], index)}, N)["r"]
-        words = _access_words(o.low.dfa[rule])
-        for q, w in words.items():
-            if not o.low.dfa[rule].bedges[q]:
-                continue
+        for q, w in _access_words(o.low.dfa[rule]).items():
             suf = set()
             for s in sym_lang:
                 if not s.startswith(w):
@@ -131,21 +124,59 @@ def test_classes_match_enumeration(name, ebnf, rules, alphabet, N):
                     nxt = L[o.order[c - 0xF0]] if c >= 0xF0 else {bytes([c])}
                     cur = {x + y for x in cur for y in nxt if len(x) + len(y) <= N}
                 suf |= cur
-            pre = prefixes(suf)
-            got = o.classes((rule, q), va)
-            assert got[0] == oracle.REJECTED
-            for i, t in enumerate(toks):
-                if not i:
-                    continue
-                if t in pre:
-                    want = oracle.ACCEPTED
-                elif any(t[:k] in suf for k in range(1, len(t))):
-                    want = oracle.UNCERTAIN
-                else:
-                    want = oracle.REJECTED
-                assert got[i] == want, (rule, q, w, t)
-                n_checked += 1
-    assert n_checked >= 14
+            out[(rule, q)] = suf
+    return out
+
+
+def _classes_by_definition(suf, toks):
+    pre = prefixes(suf)
+    want = [oracle.REJECTED]
+    for t in toks[1:]:
+        if t in pre:
+            want.append(oracle.ACCEPTED)
+        elif any(t[:k] in suf for k in range(1, len(t))):
+            want.append(oracle.UNCERTAIN)
+        else:
+            want.append(oracle.REJECTED)
+    return want
+
+
+@pytest.mark.parametrize("name,ebnf,rules,alphabet,N", TINY, ids=[t[0] for t in TINY])
+def test_classes_match_enumeration(name, ebnf, rules, alphabet, N):
+    """accepted / uncertain / rejected of every position == the definition evaluated on the
+    enumerated suffix language."""
+    o = oracle.Oracle(ebnf)
+    sufs = _suffix_languages(o, rules, N)
+    toks, va = _tiny_vocab(alphabet)
+    n_checked = 0
+    for pos in o.positions():
+        got = o.classes(pos, va)
+        assert list(got) == _classes_by_definition(sufs[pos], toks), pos
+        n_checked += 1
+    assert n_checked >= 2
+
+
+@pytest.mark.parametrize("name,ebnf,rules,alphabet,N", TINY, ids=[t[0] for t in TINY])
+def test_classes_with_one_level_of_context_match_enumeration(name, ebnf, rules, alphabet, N):
+    """With a parent state x (where the referencing rule continues), the suffix language is the
+    concatenation Suf(position) . Suf(x); classes follow the same definition on it."""
+    o = oracle.Oracle(ebnf)
+    sufs = _suffix_languages(o, rules, N)
+    toks, va = _tiny_vocab(alphabet)
+    n_checked = 0
+    for parent_rule in o.low.reachable:
+        d = o.low.dfa[parent_rule]
+        for q in range(d.n):
+            for r, x in d.redges[q].items():
+                child = o.order[r]
+                for pos in o.positions():
+                    if pos[0] != child:
+                        continue
+                    cat = {a + b for a in sufs[pos] for b in sufs[(parent_rule, x)] if len(a) + len(b) <= N}
+                    got = o.classes(pos, va, parent=(parent_rule, x))
+                    assert list(got) == _classes_by_definition(cat, toks), (pos, parent_rule, x)
+                    n_checked += 1
+    assert n_checked >= 1
 
 
 def test_number_grammar_equals_python_regex():
