@@ -60,7 +60,7 @@ def _load():
         L.eo_productive.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
         L.eo_is_nullable.argtypes = [ctypes.c_void_p, ctypes.c_int32]
         L.eo_scan_vocab.restype = ctypes.c_int32
-        L.eo_scan_vocab.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p, ctypes.c_int64,
+        L.eo_scan_vocab.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p, ctypes.c_int64,
                                     ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p,
                                     ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, ctypes.c_int32]
         L.eo_accepts.restype = ctypes.c_int32
@@ -111,7 +111,7 @@ class CGrammar:
         return bool(_load().eo_accepts(self.h, start_nt, buf.ctypes.data, len(text)))
 
     def scan_vocab(self, start_nt: int, history: bytes, blob: np.ndarray, offs: np.ndarray, threads: int = 0,
-                   want_items: bool = False, start2_nt: int = -1):
+                   want_items: bool = False, start2_nt: int = -1, follow_nt: int = -1):
         """-> (status, viable[V] u8, early[V] u8, items or None); status -1 dead, 1 complete, 0 otherwise."""
         V = len(offs) - 1
         viable = np.zeros(V, dtype=np.uint8)
@@ -120,7 +120,7 @@ class CGrammar:
         cap = 4096
         items = np.zeros(3 * cap, dtype=np.int32)
         n_items = ctypes.c_int32(0)
-        st = _load().eo_scan_vocab(self.h, start_nt, start2_nt, hist.ctypes.data, len(history), blob.ctypes.data,
+        st = _load().eo_scan_vocab(self.h, start_nt, start2_nt, follow_nt, hist.ctypes.data, len(history), blob.ctypes.data,
                                    offs.ctypes.data, V, viable.ctypes.data, early.ctypes.data,
                                    items.ctypes.data, cap, ctypes.byref(n_items), threads)
         it = None
@@ -155,6 +155,7 @@ class Oracle:
         self.root = root
         self.low = _fsm.Lowered(self.order, self.rules, root)
         self.fsm_bnf = _bnf.fsm_bnf(self.low)
+        _bnf.add_follow(self.fsm_bnf, self.low)
         self.cg = CGrammar(self.fsm_bnf)
         self.root_nt = self.fsm_bnf.names[(root, 0)]
         self._nt_key = {v: k for k, v in self.fsm_bnf.names.items()}
@@ -195,13 +196,19 @@ class Oracle:
 
     # -- cache classes of one position ------------------------------------------------------
     def classes(self, pos: Tuple[str, int], vocab: VocabArrays, threads: int = 0,
-                parent: Optional[Tuple[str, int]] = None) -> np.ndarray:
+                parent: Optional[Tuple[str, int]] = None, follow: bool = False) -> np.ndarray:
         """u8[V]: ACCEPTED / UNCERTAIN / REJECTED; special and empty tokens are REJECTED.
         With `parent` = the state the referencing rule continues in once this rule instance ends, the
-        suffix language is Suf(pos) . Suf(parent) (one level of context)."""
+        suffix language is Suf(pos) . Suf(parent) (one level of context).
+        With `follow`, a token that leaves the (outermost) rule after t[0:i] stays uncertain only if the
+        rest t[i:] is a viable prefix of what can follow that rule somewhere in the grammar (the follow
+        language: the union over the rule's reference sites of Suf(site) . follow(site's rule); the root
+        rule may also be followed by nothing); otherwise no context can accept it and it is REJECTED."""
         start = self.fsm_bnf.names[pos]
         start2 = self.fsm_bnf.names[parent] if parent is not None else -1
-        st, viable, early, _ = self.cg.scan_vocab(start, b"", vocab.blob, vocab.offs, threads, start2_nt=start2)
+        outer = parent[0] if parent is not None else pos[0]
+        fnt = self.fsm_bnf.names[("follow", outer)] if follow else -1
+        st, viable, early, _ = self.cg.scan_vocab(start, b"", vocab.blob, vocab.offs, threads, start2_nt=start2, follow_nt=fnt)
         assert st >= 0
         cls = np.where(viable.astype(bool), ACCEPTED, np.where(early.astype(bool), UNCERTAIN, REJECTED)).astype(np.uint8)
         cls[vocab.special] = REJECTED

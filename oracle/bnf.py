@@ -66,6 +66,24 @@ def fsm_bnf(low: F.Lowered) -> BNF:
     return b
 
 
+def add_follow(b: BNF, low: F.Lowered) -> None:
+    """Follow languages as extra nonterminals ("follow", R): whatever can come after an instance of rule R
+    in a sentential form of the root.  follow(R) -> N(Q, x) follow(Q) for every edge  s --R--> x  of a
+    rule Q;  follow(root) -> empty  as well."""
+    for nm in low.reachable:
+        b.nt(("follow", nm))
+    b.add(b.nt(("follow", low.root)), [])
+    for q_rule in low.reachable:
+        d = low.dfa[q_rule]
+        seen = set()
+        for q in range(d.n):
+            for r, x in d.redges[q].items():
+                if (r, x) in seen:
+                    continue
+                seen.add((r, x))
+                b.add(b.nt(("follow", low.order[r])), [~b.nt((q_rule, x)), ~b.nt(("follow", q_rule))])
+
+
 def direct_bnf(order: List[str], rules: Dict[str, tuple], root: str) -> BNF:
     b = BNF()
     index = {nm: i for i, nm in enumerate(order)}

@@ -188,12 +188,26 @@ static int start_complete(const Ctx* c, const Set* s) {
  * (CSR: blob + offs[V+1]) decide
  *     viable[t]  = 1  iff  the item set after hist.bytes(t) is non-empty
  *     early[t]   = 1  iff  for some i, 1 <= i < len(t), hist.t[0:i] is a complete sentence
+ * If follow >= 0, early[t] additionally requires that the rest of the token, t[i:], is a viable prefix
+ * of the language of nonterminal `follow` (what may come after the start symbols in some context).
  * Zero-length tokens get 0 / 0.  Returns -1 if hist itself is not a viable prefix, else
  * 1 if hist is a complete sentence, else 0.
  * Optionally exports the items of the closed set after hist: last_items[3*k] = prod, dot, origin
  * (at most last_cap items; *last_n receives the true count).
  */
-int32_t eo_scan_vocab(void* h, int32_t start, int32_t start2, const uint8_t* hist, int64_t hlen,
+static int viable_from(const Grammar* g, int32_t nt, const uint8_t* text, int64_t n, Set* scratch) {
+    Ctx c; c.g = g; c.start = nt; c.start2 = -1;
+    scratch[0].n = 0;
+    set_add(&scratch[0], g->n_prod, 0, 0);
+    closure(&c, scratch, 0);
+    for (int64_t j = 0; j < n; ++j) {
+        step(&c, scratch, (int32_t)j, text[j]);
+        if (scratch[j + 1].n == 0) return 0;
+    }
+    return 1;
+}
+
+int32_t eo_scan_vocab(void* h, int32_t start, int32_t start2, int32_t follow, const uint8_t* hist, int64_t hlen,
                       const uint8_t* blob, const int64_t* offs, int32_t V,
                       uint8_t* viable, uint8_t* early,
                       int32_t* last_items, int32_t last_cap, int32_t* last_n, int32_t n_threads) {
@@ -230,6 +244,8 @@ int32_t eo_scan_vocab(void* h, int32_t start, int32_t start2, const uint8_t* his
                 Set* sets = (Set*)malloc(sizeof(Set) * (size_t)(hlen + max_tok + 2));
                 for (int64_t j = 0; j <= hlen; ++j) sets[j] = base[j];       /* shared, read-only */
                 for (int64_t j = hlen + 1; j <= hlen + max_tok + 1; ++j) set_init(&sets[j]);
+                Set* fsets = (Set*)malloc(sizeof(Set) * (size_t)(max_tok + 2));
+                for (int64_t j = 0; j <= max_tok + 1; ++j) set_init(&fsets[j]);
 #ifdef _OPENMP
 #pragma omp for schedule(dynamic, 256)
 #endif
@@ -242,13 +258,18 @@ int32_t eo_scan_vocab(void* h, int32_t start, int32_t start2, const uint8_t* his
                         for (int64_t i = 0; i < n; ++i) {
                             step(&c, sets, (int32_t)(hlen + i), b[i]);
                             if (sets[hlen + i + 1].n == 0) { ok = 0; break; }
-                            if (i + 1 < n && start_complete(&c, &sets[hlen + i + 1])) ear = 1;
+                            if (i + 1 < n && start_complete(&c, &sets[hlen + i + 1])) {
+                                if (follow < 0) ear = 1;
+                                else if (!ear && viable_from(g, follow, b + i + 1, n - i - 1, fsets)) ear = 1;
+                            }
                         }
                     }
                     viable[t] = ok;
                     if (early) early[t] = ear;
                 }
                 for (int64_t j = hlen + 1; j <= hlen + max_tok + 1; ++j) set_free(&sets[j]);
+                for (int64_t j = 0; j <= max_tok + 1; ++j) set_free(&fsets[j]);
+                free(fsets);
                 free(sets);
             }
         }
@@ -260,7 +281,7 @@ int32_t eo_scan_vocab(void* h, int32_t start, int32_t start2, const uint8_t* his
 
 /* Does `text` belong to L(start)?  (sentence test, used by the pins) */
 int32_t eo_accepts(void* h, int32_t start, const uint8_t* text, int64_t n) {
-    return eo_scan_vocab(h, start, -1, text, n, NULL, NULL, 0, NULL, NULL, NULL, 0, NULL, 1) == 1;
+    return eo_scan_vocab(h, start, -1, -1, text, n, NULL, NULL, 0, NULL, NULL, NULL, 0, NULL, 1) == 1;
 }
 
 /* In-place token-bitmask application, plain loops (paper section 2.1: logits of tokens that do

@@ -50,6 +50,12 @@ class CompileOpts(ctypes.Structure):
 
 
 def _load() -> ctypes.CDLL:
+    try:
+        # PyTorch wheels ship their own HIP runtime; load it first so that the process has one runtime,
+        # whichever of the two is imported first.
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2601_04426_amd.build` "
                           "(there is no fallback implementation)")

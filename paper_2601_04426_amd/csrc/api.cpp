@@ -207,6 +207,11 @@ struct FillWorkspace {
     std::mutex mu;
     FillSlot slots[4];
     int next = 0;
+    DevBuf<uint32_t> cand_words, work_list, work_count;
+    void ensure_scratch(size_t words) {
+        if (cand_words.n < words) { cand_words.alloc(words * 5 / 4); work_list.alloc(words * 5 / 4); }
+        if (!work_count.p) work_count.alloc(1);
+    }
     FillSlot& acquire(size_t bytes) {
         FillSlot& s = slots[next];
         next = (next + 1) % 4;
@@ -793,6 +798,10 @@ int32_t xg2_fill_next_token_bitmask(xg2_matcher* const* matchers, int32_t B, int
         F.ctx_wait_off = reinterpret_cast<const uint32_t*>(slot.dev + o_woff);
         F.tables = reinterpret_cast<const DevTables*>(slot.dev + o_tabs);
         F.eos_id = (uint32_t)V.eos;
+        fill_ws().ensure_scratch((size_t)B * V.W);
+        F.cand_words = fill_ws().cand_words.p; F.work_list = fill_ws().work_list.p; F.work_count = fill_ws().work_count.p;
+        F.recheck_blocks = 1024;
+        HIP_CHECK(hipMemsetAsync(F.work_count, 0, sizeof(uint32_t), stream));
         HIP_CHECK(hipMemsetAsync(S.count, 0, sizeof(uint32_t), stream));
         launch_fill(F, V.dv, bitmask_dev, row_stride_words, S, stream);
         launch_recheck_slow(F, V.dv, bitmask_dev, row_stride_words, S, stream);

@@ -64,6 +64,11 @@ struct FillBatch {
     const uint32_t* ctx_items; const uint32_t* ctx_wait; const uint32_t* ctx_wait_off;
     const DevTables* tables;
     uint32_t eos_id;
+    // re-check scratch: candidate bits of every mask word, indices of the non-zero ones, their count
+    uint32_t* cand_words;                // [B * W]
+    uint32_t* work_list;                 // [B * W]
+    uint32_t* work_count;                // [1], zeroed before the launch
+    uint32_t recheck_blocks;             // grid of the re-check kernel
 };
 void launch_fill(const FillBatch& F, const DevVocab& Vd, int32_t* bitmask_dev, int64_t row_stride_words,
                  const SlowScratch& S, hipStream_t stream);

@@ -234,8 +234,15 @@ __global__ __launch_bounds__(256) void k_popcount(const uint32_t* const* plane_p
 }
 
 // ---- fill ------------------------------------------------------------------------------------------
-constexpr int FILL_THREADS = 128, FILL_WORDS = 128;       // one word of one row per thread
+// k_fill_or: pure streaming.  Thread = one mask word of one row: OR of the accepted planes of the row's
+// frontier, plus the end-of-sequence bit; uncertain-and-not-accepted bits go to a scratch word and the
+// word's index to a global work list (one atomic per non-zero word; the list can hold every word).
+// k_recheck: each wave takes 64 listed words, spreads their set bits densely over its lanes and runs the
+// Earley routine from the row's context; survivors are OR-ed into the bitmask.
+constexpr int FILL_THREADS = 256;
 constexpr int FILL_K = 12, FILL_WM = 24;
+constexpr int RECHECK_WAVES = 4;
+constexpr uint32_t RECHECK_CHUNK = 16;                    // listed words per wave per round (few, so that many waves share the work)
 using FillStore = LdsStore<FILL_K, FILL_WM>;
 
 __device__ __forceinline__ DevCtx row_ctx(const FillBatch& F, const FillRow& r) {
@@ -248,60 +255,83 @@ __device__ __forceinline__ DevCtx row_ctx(const FillBatch& F, const FillRow& r) 
     return C;
 }
 
-__global__ __launch_bounds__(FILL_THREADS) void k_fill(FillBatch F, DevVocab Vd, int32_t* bitmask, long long row_stride, SlowScratch S) {
-    __shared__ uint32_t lds_store[(FILL_THREADS / 64) * FillStore::SLOTS * 64];
-    __shared__ uint32_t out_words[FILL_WORDS];
-    __shared__ uint32_t queue[FILL_WORDS * 32];
-    __shared__ uint32_t qn;
+__global__ __launch_bounds__(FILL_THREADS) void k_fill_or(FillBatch F, DevVocab Vd, int32_t* bitmask, long long row_stride) {
     const uint32_t b = blockIdx.y;
-    const uint32_t w0 = blockIdx.x * FILL_WORDS;
-    const FillRow r = F.rows[b];
-    if (threadIdx.x == 0) qn = 0;
-    __syncthreads();
-    if (threadIdx.x < FILL_WORDS) {
-        const uint32_t w = w0 + threadIdx.x;
-        uint32_t acc = 0, cand = 0;
-        if (w < Vd.W) {
-            if (!(r.flags & 2u)) {
-                uint32_t unc = 0;
-                for (uint32_t k = 0; k < r.front_n; ++k) {
-                    const uint64_t addr = F.front_planes[r.front_off + k];
-                    const uint32_t* row = reinterpret_cast<const uint32_t*>(addr & ~(uint64_t)1);
-                    acc |= row[w];
-                    if (!(addr & 1)) unc |= row[Vd.W + w];
-                }
-                cand = unc & ~acc;
-            }
-            if ((r.flags & 3u) && (F.eos_id >> 5) == w) acc |= 1u << (F.eos_id & 31);
+    const uint32_t w_raw = blockIdx.x * FILL_THREADS + threadIdx.x;
+    const bool in_row = w_raw < Vd.W;
+    const uint32_t w = in_row ? w_raw : Vd.W - 1;                 // lanes past the row redo its last word (same value)
+    const uint32_t front_off = F.rows[b].front_off, front_n = F.rows[b].front_n, flags = F.rows[b].flags;
+    uint32_t acc = 0, unc = 0;
+    if (!(flags & 2u))
+        for (uint32_t k = 0; k < front_n; ++k) {
+            const uint64_t addr = F.front_planes[front_off + k];
+            const uint32_t* row = reinterpret_cast<const uint32_t*>(addr & ~(uint64_t)1);
+            acc |= row[w];
+            if (!(addr & 1)) unc |= row[Vd.W + w];
         }
-        out_words[threadIdx.x] = acc;
+    const uint32_t cand = in_row ? (unc & ~acc) : 0u;
+    if ((flags & 3u) && (F.eos_id >> 5) == w) acc |= 1u << (F.eos_id & 31);
+    if (in_row) bitmask[(long long)b * row_stride + w] = (int32_t)acc;
+    // one atomic per wave: lanes with candidates take consecutive slots of the work list
+    const unsigned long long has = __ballot(cand != 0);
+    if (has) {
+        const uint32_t lane = threadIdx.x & 63;
+        const uint32_t leader = (uint32_t)__ffsll((long long)has) - 1;
+        uint32_t base = 0;
+        if (lane == leader) base = atomicAdd(F.work_count, (uint32_t)__popcll(has));
+        base = __shfl(base, (int)leader);
         if (cand) {
-            uint32_t pos = atomicAdd(&qn, (uint32_t)__popc(cand));
-            while (cand) { uint32_t bit = __ffs(cand) - 1; cand &= cand - 1; queue[pos++] = w * 32 + bit; }
+            const uint32_t idx = b * Vd.W + w;
+            F.cand_words[idx] = cand;
+            F.work_list[base + (uint32_t)__popcll(has & ((1ull << lane) - 1))] = idx;
         }
     }
-    __syncthreads();
-    const uint32_t n_q = qn;
-    if (n_q) {
-        const DevTables T = F.tables[r.tables_idx];
-        const DevCtx C = row_ctx(F, r);
-        FillStore st;
-        st.base = lds_store + (threadIdx.x >> 6) * FillStore::SLOTS * 64 + (threadIdx.x & 63);
-        for (uint32_t q = threadIdx.x; q < n_q; q += FILL_THREADS) {
-            const uint32_t id = queue[q];
-            const uint32_t rank = Vd.rank[id];
-            if (rank >= Vd.n_sorted) continue;                   // never a checkable token
-            const uint32_t off = Vd.off[rank];
-            const int n = (int)(Vd.off[rank + 1] - off);
-            st.sel = 0; st.ws_lo = 0; st.ws_hi = 0;
-            int res = scan_token(T, C, Vd.bytes + off, n, st);
-            if (res & RES_OVERFLOW) push_overflow(S, b, id);
-            else if (res & RES_ALIVE) atomicOr(&out_words[(id >> 5) - w0], 1u << (id & 31));
+}
+
+__global__ __launch_bounds__(64 * RECHECK_WAVES) void k_recheck(FillBatch F, DevVocab Vd, int32_t* bitmask, long long row_stride, SlowScratch S) {
+    __shared__ uint32_t lds_store[RECHECK_WAVES * FillStore::SLOTS * 64];
+    __shared__ uint32_t sh_prefix[RECHECK_WAVES][64], sh_cand[RECHECK_WAVES][64], sh_idx[RECHECK_WAVES][64];
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint32_t n_waves = gridDim.x * RECHECK_WAVES;
+    const uint32_t count = *F.work_count;
+    FillStore st;
+    st.base = lds_store + wave * FillStore::SLOTS * 64 + lane;
+    for (uint32_t base = (blockIdx.x * RECHECK_WAVES + wave) * RECHECK_CHUNK; base < count; base += n_waves * RECHECK_CHUNK) {
+        // RECHECK_CHUNK listed words, one per lane; inclusive prefix sum of their candidate counts
+        uint32_t idx = 0, cand = 0;
+        if (lane < RECHECK_CHUNK && base + lane < count) { idx = F.work_list[base + lane]; cand = F.cand_words[idx]; }
+        uint32_t incl = (uint32_t)__popc(cand);
+        for (int d = 1; d < 64; d <<= 1) { uint32_t up = __shfl_up(incl, d); if ((int)lane >= d) incl += up; }
+        __builtin_amdgcn_wave_barrier();                           // lanes of the previous round are done reading
+        sh_prefix[wave][lane] = incl; sh_cand[wave][lane] = cand; sh_idx[wave][lane] = idx;
+        __builtin_amdgcn_wave_barrier();                           // one wave: LDS operations complete in order
+        const uint32_t total = __shfl(incl, 63);
+        for (uint32_t t0 = 0; t0 < total; t0 += 64) {
+            const uint32_t my = t0 + lane;
+            if (my < total) {
+                // entry j = first lane whose inclusive prefix exceeds `my`
+                uint32_t lo = 0, hi = 63;
+                while (lo < hi) { uint32_t mid = (lo + hi) >> 1; if (sh_prefix[wave][mid] > my) hi = mid; else lo = mid + 1; }
+                uint32_t c = sh_cand[wave][lo];
+                uint32_t k = my - (sh_prefix[wave][lo] - (uint32_t)__popc(c));
+                while (k--) c &= c - 1;                            // drop the k lowest set bits
+                const uint32_t bit = __ffs(c) - 1;
+                const uint32_t widx = sh_idx[wave][lo];
+                const uint32_t b = widx / Vd.W, w = widx - b * Vd.W;
+                const uint32_t id = w * 32 + bit;
+                const uint32_t rank = Vd.rank[id];
+                if (rank < Vd.n_sorted) {
+                    const FillRow r = F.rows[b];
+                    const uint32_t off = Vd.off[rank];
+                    const int n = (int)(Vd.off[rank + 1] - off);
+                    st.sel = 0; st.ws_lo = 0; st.ws_hi = 0;
+                    int res = scan_token(F.tables[r.tables_idx], row_ctx(F, r), Vd.bytes + off, n, st);
+                    if (res & RES_OVERFLOW) push_overflow(S, b, id);
+                    else if (res & RES_ALIVE) atomicOr(reinterpret_cast<uint32_t*>(bitmask) + (long long)b * row_stride + w, 1u << bit);
+                }
+            }
         }
-        __syncthreads();
     }
-    if (threadIdx.x < FILL_WORDS && w0 + threadIdx.x < Vd.W)
-        bitmask[(long long)b * row_stride + w0 + threadIdx.x] = (int32_t)out_words[threadIdx.x];
 }
 
 __global__ __launch_bounds__(64) void k_recheck_slow(FillBatch F, DevVocab Vd, int32_t* bitmask, long long row_stride, SlowScratch S) {
@@ -403,8 +433,10 @@ void launch_popcount(const uint32_t* const* plane_ptr_dev, uint32_t n_pos, uint3
 void launch_fill(const FillBatch& F, const DevVocab& Vd, int32_t* bitmask_dev, int64_t row_stride_words,
                  const SlowScratch& S, hipStream_t stream) {
     if (F.B == 0) return;
-    dim3 grid((Vd.W + FILL_WORDS - 1) / FILL_WORDS, F.B);
-    hipLaunchKernelGGL(k_fill, grid, dim3(FILL_THREADS), 0, stream, F, Vd, bitmask_dev, (long long)row_stride_words, S);
+    dim3 grid((Vd.W + FILL_THREADS - 1) / FILL_THREADS, F.B);
+    hipLaunchKernelGGL(k_fill_or, grid, dim3(FILL_THREADS), 0, stream, F, Vd, bitmask_dev, (long long)row_stride_words);
+    hipLaunchKernelGGL(k_recheck, dim3(F.recheck_blocks), dim3(64 * RECHECK_WAVES), 0, stream, F, Vd, bitmask_dev,
+                       (long long)row_stride_words, S);
 }
 
 void launch_recheck_slow(const FillBatch& F, const DevVocab& Vd, int32_t* bitmask_dev, int64_t row_stride_words,

@@ -179,6 +179,57 @@ def test_classes_with_one_level_of_context_match_enumeration(name, ebnf, rules, 
     assert n_checked >= 1
 
 
+@pytest.mark.parametrize("name,ebnf,rules,alphabet,N", TINY, ids=[t[0] for t in TINY])
+def test_follow_filtered_classes_match_enumeration(name, ebnf, rules, alphabet, N):
+    """With the follow filter a token that leaves the outermost rule after t[0:i] stays uncertain only if
+    t[i:] is a prefix of an enumerated follow string of that rule; follow strings are enumerated as the least
+    fixed point of  follow(R) = U over sites  Suf(site) . follow(site's rule),  follow(root) containing ''."""
+    o = oracle.Oracle(ebnf)
+    sufs = _suffix_languages(o, rules, N)
+    toks, va = _tiny_vocab(alphabet)
+    follow = {r: set() for r in o.low.reachable}
+    follow[o.root].add(b"")
+    while True:
+        grew = False
+        for q_rule in o.low.reachable:
+            d = o.low.dfa[q_rule]
+            for q in range(d.n):
+                for r, x in d.redges[q].items():
+                    add = {a + b for a in sufs[(q_rule, x)] for b in follow[q_rule] if len(a) + len(b) <= N}
+                    if not add <= follow[o.order[r]]:
+                        follow[o.order[r]] |= add
+                        grew = True
+        if not grew:
+            break
+
+    def want(lang, outer):
+        pre, fpre = prefixes(lang), prefixes(follow[outer])
+        out = [oracle.REJECTED]
+        for t in toks[1:]:
+            if t in pre:
+                out.append(oracle.ACCEPTED)
+            elif any(t[:k] in lang and t[k:] in fpre for k in range(1, len(t))):
+                out.append(oracle.UNCERTAIN)
+            else:
+                out.append(oracle.REJECTED)
+        return out
+    n_moved = 0
+    for pos in o.positions():
+        got = list(o.classes(pos, va, follow=True))
+        assert got == want(sufs[pos], pos[0]), pos
+        n_moved += sum(1 for a, b in zip(got, o.classes(pos, va)) if a != b)
+    for parent_rule in o.low.reachable:
+        d = o.low.dfa[parent_rule]
+        for q in range(d.n):
+            for r, x in d.redges[q].items():
+                for pos in o.positions():
+                    if pos[0] == o.order[r]:
+                        cat = {a + b for a in sufs[pos] for b in sufs[(parent_rule, x)] if len(a) + len(b) <= N}
+                        assert list(o.classes(pos, va, parent=(parent_rule, x), follow=True)) == want(cat, parent_rule), (pos, parent_rule, x)
+    if name in ("list", "repeat"):
+        assert n_moved > 0                     # the filter does reject something on these grammars
+
+
 def test_number_grammar_equals_python_regex():
     """A grammar without rule references is a regular expression: compare with `re`."""
     o = oracle.Oracle('root ::= "-"? ("0" | [1-9] [0-9]*) ("." [0-9]+)? ([eE] [+\\-]? [0-9]+)?\n')
