@@ -57,10 +57,16 @@ typedef struct xg2_matcher xg2_matcher;
  *   plane (the context expansion that section 2.2 and section 3.3 recall); far fewer tokens stay
  *   uncertain.  Positions of the root rule have no referencing rule and keep a plain plane.
  * merge_equivalent (default 1): states that no string as long as the longest token can tell apart
- *   share one plane (section 3.6: states inside a repetition differ minimally).                    */
+ *   share one plane (section 3.6: states inside a repetition differ minimally).
+ * follow_filter (default 1): a token that leaves the plane's (outermost) rule before its last byte
+ *   stays uncertain only if the rest of the token is a viable prefix of what can follow that rule
+ *   at some reference site of the grammar; otherwise it is rejected at build time (sections 2.2 and
+ *   3.3: the reference structure / lookahead is used to reject context-dependent tokens).  Planes
+ *   built with the filter are shared between grammars only where the follow sets agree.          */
 typedef struct xg2_compile_opts {
     int32_t context_depth;
     int32_t merge_equivalent;
+    int32_t follow_filter;
 } xg2_compile_opts;
 
 /* Counters filled by xg2_compile_grammar. */
@@ -114,7 +120,8 @@ int32_t xg2_pool_stats(const xg2_pool*, int64_t* n_positions, int64_t* device_by
  * position (rule, state), or to a position plus the state (parent rule, parent state) in which the
  * referencing rule continues once the position's rule instance ends:
  *   accepted  = tokens that are a prefix of a string of Suf(position) [. Suf(parent)],
- *   uncertain = the other tokens with a proper non-empty prefix that is a whole such string.
+ *   uncertain = the other tokens with a proper non-empty prefix that is a whole such string
+ *               (and, with follow_filter, a rest that some reference site can continue).
  * opts and stats may be NULL.                                                                    */
 int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, const char* root_rule,
                             const xg2_compile_opts* opts, xg2_pool* pool, void* hip_stream,

@@ -46,7 +46,7 @@ class CompileStats(ctypes.Structure):
 
 
 class CompileOpts(ctypes.Structure):
-    _fields_ = [("context_depth", ctypes.c_int32), ("merge_equivalent", ctypes.c_int32)]
+    _fields_ = [("context_depth", ctypes.c_int32), ("merge_equivalent", ctypes.c_int32), ("follow_filter", ctypes.c_int32)]
 
 
 def _load() -> ctypes.CDLL:
@@ -206,11 +206,11 @@ class MaskCache:
 
 
 def compile_grammar(vocab: Vocab, ebnf: str, root: str = "root", pool: Optional[Pool] = None, stream: int = 0,
-                    context_depth: int = 2, merge_equivalent: bool = True) -> MaskCache:
+                    context_depth: int = 2, merge_equivalent: bool = True, follow_filter: bool = True) -> MaskCache:
     data = ebnf.encode("utf-8")
     h = ctypes.c_void_p()
     stats = CompileStats()
-    opts = CompileOpts(context_depth, 1 if merge_equivalent else 0)
+    opts = CompileOpts(context_depth, 1 if merge_equivalent else 0, 1 if follow_filter else 0)
     _check(lib.xg2_compile_grammar(vocab.h, data, len(data), root.encode(), ctypes.byref(opts), pool.h if pool else None,
                                    ctypes.c_void_p(stream), ctypes.byref(h), ctypes.byref(stats)))
     return MaskCache(h, vocab, stats, pool)

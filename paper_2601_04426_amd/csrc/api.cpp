@@ -128,7 +128,7 @@ SlowImpl& slow() { static SlowImpl* s = new SlowImpl(); return *s; }
 // ---- cross-grammar pool -------------------------------------------------------------------------------
 // A plane is identified by (pool entry of the position's rule, canonical state, pool entry of the
 // referencing rule or -1, canonical state the referencing rule continues in or -1).
-using PlaneKey = std::array<int32_t, 4>;
+using PlaneKey = std::array<int64_t, 5>;   // the fifth word: follow signature of the outermost rule (0 = unfiltered)
 struct PoolImpl {
     size_t max_bytes = 0;
     std::mutex mu;
@@ -180,6 +180,7 @@ struct CacheImpl {
     std::shared_ptr<PoolImpl> pool;
     std::shared_ptr<GrammarImpl> gram;
     DevBuf<StateInfo> d_state; DevBuf<ByteEdge> d_bedge; DevBuf<RefEdgeP> d_redge; DevBuf<RuleInfo> d_rule;
+    DevBuf<uint32_t> d_site_off, d_site_tgt;
     DevTables dt{};
     int32_t context_depth = 2;
     std::vector<PlaneInfo> planes;
@@ -363,6 +364,7 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
         if (!vocab || !out) return fail(XG2_EINVAL, "xg2_compile_grammar: bad argument");
         const int32_t depth = opts ? opts->context_depth : 2;
         const bool merge = opts ? opts->merge_equivalent != 0 : true;
+        const bool follow = opts ? opts->follow_filter != 0 : true;
         if (depth != 1 && depth != 2) return fail(XG2_EINVAL, "xg2_compile_grammar: context_depth must be 1 or 2");
         hipStream_t stream = (hipStream_t)hip_stream;
         auto t0 = std::chrono::steady_clock::now();
@@ -409,12 +411,15 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
         }
 
         // states that tokens cannot tell apart share planes
-        std::vector<std::vector<int32_t>> rep;
-        if (merge) rep = bounded_classes(g, (int32_t)std::max<uint32_t>(V.max_len, 1), ref_id);
+        std::vector<std::vector<int32_t>> rep, classes;
+        if (merge || follow) classes = bounded_classes(g, (int32_t)std::max<uint32_t>(V.max_len, 1), ref_id);
+        if (merge) rep = classes;
         else {
             rep.resize((size_t)R);
             for (int r = 0; r < R; ++r) { rep[(size_t)r].resize((size_t)g.rules[(size_t)r].n_states()); std::iota(rep[(size_t)r].begin(), rep[(size_t)r].end(), 0); }
         }
+        std::vector<uint64_t> follow_sig;
+        if (follow) follow_sig = follow_signatures(g, (int32_t)std::max<uint32_t>(V.max_len, 1));
         // reference sites of every rule, one representative per class of the state the referencing rule continues in
         struct Site { int32_t q, waiter, x; };
         std::vector<std::vector<Site>> sites((size_t)R);            // all sites
@@ -441,8 +446,9 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
         std::map<PlaneKey, int32_t> local_plane;
         auto plane_for = [&](int rp, int sp_rep, const Site* site) -> int32_t {
             const RuleFsm& fp = g.rules[(size_t)rp];
-            PlaneKey key{entry[(size_t)rp], fp.canon_id[(size_t)sp_rep], -1, -1};
+            PlaneKey key{entry[(size_t)rp], fp.canon_id[(size_t)sp_rep], -1, -1, 0};
             if (site) { key[2] = entry[(size_t)site->q]; key[3] = g.rules[(size_t)site->q].canon_id[(size_t)site->x]; }
+            if (follow) key[4] = (int64_t)(follow_sig[(size_t)(site ? site->q : rp)] | 1);
             auto lp = local_plane.find(key);
             if (lp != local_plane.end()) return lp->second;
             uint32_t*& row = pool.rows[key];
@@ -483,6 +489,25 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
         cache->dt.byte_edges = reinterpret_cast<const uint2*>(cache->d_bedge.p);
         cache->dt.ref_edges = reinterpret_cast<const uint2*>(cache->d_redge.p);
         cache->dt.rule_info = reinterpret_cast<const uint2*>(cache->d_rule.p);
+        // per rule, the states referencing rules continue in: one per class of indistinguishable states
+        std::vector<uint32_t> site_off{0}, site_tgt;
+        if (follow) {
+            std::vector<std::vector<uint32_t>> by_rule((size_t)R);
+            for (int q = 0; q < R; ++q)
+                for (int s = 0; s < g.rules[(size_t)q].n_states(); ++s)
+                    for (auto& e : g.rules[(size_t)q].redges[(size_t)s])
+                        by_rule[(size_t)e.rule].push_back((uint32_t)g.sid(q, classes[(size_t)q][(size_t)e.tgt]));
+            for (auto& v : by_rule) {
+                std::sort(v.begin(), v.end());
+                v.erase(std::unique(v.begin(), v.end()), v.end());
+                site_tgt.insert(site_tgt.end(), v.begin(), v.end());
+                site_off.push_back((uint32_t)site_tgt.size());
+            }
+        } else site_off.assign((size_t)R + 1, 0);
+        cache->d_site_off.upload(site_off, stream);
+        cache->d_site_tgt.upload(site_tgt, stream);
+        cache->dt.site_off = cache->d_site_off.p;
+        cache->dt.site_tgt = cache->d_site_tgt.p;
 
         // plan: closed start set and live first-byte ranges of every plane to build
         auto t1 = std::chrono::steady_clock::now();
@@ -543,6 +568,7 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
         P.ctx_items = d_items.p; P.ctx_item_off = d_item_off.p; P.ctx_wait = d_wait.p; P.ctx_wait_off = d_wait_off.p;
         P.ctx_woff_start = d_woff_start.p; P.ctx_H = d_H.p;
         P.plane_ptr = d_rows.p;
+        P.follow_filter = follow ? 1u : 0u;
         HIP_CHECK(hipEventRecord(evk0, stream));
         if (!build.empty()) launch_build(cache->dt, V.dv, P, S, stream);
         HIP_CHECK(hipEventRecord(evk1, stream));

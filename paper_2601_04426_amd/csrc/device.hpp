@@ -11,6 +11,8 @@ struct DevTables {                       // packed grammar tables (see tables.hp
     const uint2* byte_edges;
     const uint2* ref_edges;
     const uint2* rule_info;
+    const uint32_t* site_off;            // per rule: states in which referencing rules continue (CSR)
+    const uint32_t* site_tgt;
 };
 
 struct DevVocab {                        // byte-sorted vocabulary in HBM
@@ -33,6 +35,7 @@ struct BuildPlan {
     const uint32_t* ctx_wait; const uint32_t* ctx_wait_off;    // per plane H + 1 offsets into ctx_wait ...
     const uint32_t* ctx_woff_start; const uint32_t* ctx_H;     // ... starting at ctx_woff_start[k]; ctx_H[k] = H
     uint32_t* const* plane_ptr;                                 // [n_planes] accepted row; uncertain row at + W words
+    uint32_t follow_filter;                                     // drop uncertain tokens that no reference site can continue
 };
 
 struct SlowScratch {                     // large-capacity per-lane Earley scratch in device memory

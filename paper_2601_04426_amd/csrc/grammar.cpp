@@ -1044,6 +1044,101 @@ std::vector<std::vector<int32_t>> bounded_classes(const Grammar& g, int32_t budg
     return rep;
 }
 
+std::vector<uint64_t> follow_signatures(const Grammar& g, int32_t budget) {
+    const int R = (int)g.rules.size();
+    const int32_t INF = 1 << 28;
+    // shortest completion of every state, in bytes
+    std::vector<std::vector<int32_t>> min_suf((size_t)R);
+    for (int r = 0; r < R; ++r) {
+        const RuleFsm& f = g.rules[(size_t)r];
+        std::vector<int32_t>& d = min_suf[(size_t)r];
+        d.assign((size_t)f.n_states(), INF);
+        for (int q = 0; q < f.n_states(); ++q) if (f.is_final[(size_t)q]) d[(size_t)q] = 0;
+        for (bool moved = true; moved;) {
+            moved = false;
+            for (int q = 0; q < f.n_states(); ++q) {
+                for (auto& e : f.bedges[(size_t)q]) if (d[(size_t)e.tgt] + 1 < d[(size_t)q]) { d[(size_t)q] = d[(size_t)e.tgt] + 1; moved = true; }
+                for (auto& e : f.redges[(size_t)q]) {
+                    int32_t c = d[(size_t)e.tgt] + g.rules[(size_t)e.rule].min_len;
+                    if (c < d[(size_t)q]) { d[(size_t)q] = c; moved = true; }
+                }
+            }
+        }
+    }
+    // unfold[d][sid]: structural hash of the state's behaviour on at most d bytes
+    std::vector<std::vector<uint64_t>> unfold((size_t)budget + 1, std::vector<uint64_t>((size_t)g.n_states, 0));
+    for (int r = 0; r < R; ++r) {
+        const RuleFsm& f = g.rules[(size_t)r];
+        const int n = f.n_states();
+        // order in which nullable rule edges are resolved (targets first); states on a cycle of such edges are salted
+        std::vector<int> indeg((size_t)n, 0), order;
+        std::vector<std::vector<int>> preds((size_t)n);
+        for (int x = 0; x < n; ++x)
+            for (auto& e : f.redges[(size_t)x]) if (g.rules[(size_t)e.rule].nullable) { ++indeg[(size_t)x]; preds[(size_t)e.tgt].push_back(x); }
+        for (int x = 0; x < n; ++x) if (indeg[(size_t)x] == 0) order.push_back(x);
+        for (size_t k = 0; k < order.size(); ++k) for (int p : preds[(size_t)order[k]]) if (--indeg[(size_t)p] == 0) order.push_back(p);
+        std::vector<uint8_t> cyclic((size_t)n, 1);
+        for (int x : order) cyclic[(size_t)x] = 0;
+        for (int32_t d = 1; d <= budget; ++d) {
+            for (int x = 0; x < n; ++x) if (cyclic[(size_t)x]) unfold[(size_t)d][(size_t)g.sid(r, x)] = hash_combine(0xC1C1ull, g_unshareable_salt.fetch_add(1));
+            for (int x : order) {
+                uint64_t h = hash_combine(0x51ull, f.is_final[(size_t)x]);
+                uint64_t by_byte[256];
+                bool has[256];
+                for (int b = 0; b < 256; ++b) { by_byte[b] = 0; has[b] = false; }
+                for (auto& e : f.bedges[(size_t)x]) for (int b = e.lo; b <= e.hi; ++b) { by_byte[b] = unfold[(size_t)d - 1][(size_t)g.sid(r, e.tgt)]; has[b] = true; }
+                for (int b = 0; b < 256;) {
+                    int e = b;
+                    while (e + 1 < 256 && has[e + 1] == has[b] && by_byte[e + 1] == by_byte[b]) ++e;
+                    if (has[b]) h = hash_combine(hash_combine(hash_combine(h, (uint64_t)b), (uint64_t)e), by_byte[b]);
+                    b = e + 1;
+                }
+                std::vector<std::pair<uint64_t, uint64_t>> refs;
+                for (auto& e : f.redges[(size_t)x]) {
+                    const RuleFsm& c = g.rules[(size_t)e.rule];
+                    int32_t left = c.nullable ? d : d - c.min_len;
+                    refs.emplace_back(c.hash, left >= 0 ? unfold[(size_t)left][(size_t)g.sid(r, e.tgt)] : 0x7777ull);
+                }
+                std::sort(refs.begin(), refs.end());
+                for (auto& p : refs) h = hash_combine(hash_combine(hash_combine(h, 0xEFull), p.first), p.second);
+                unfold[(size_t)d][(size_t)g.sid(r, x)] = h;
+            }
+        }
+    }
+    // reference sites of every rule
+    struct Site { int q, x; };
+    std::vector<std::vector<Site>> sites((size_t)R);
+    for (int q = 0; q < R; ++q)
+        for (int s = 0; s < g.rules[(size_t)q].n_states(); ++s)
+            for (auto& e : g.rules[(size_t)q].redges[(size_t)s]) sites[(size_t)e.rule].push_back({q, e.tgt});
+    std::map<std::pair<int, int>, uint64_t> memo;
+    std::set<std::pair<int, int>> open;
+    std::function<uint64_t(int, int)> sig = [&](int rule, int d) -> uint64_t {
+        auto key = std::make_pair(rule, d);
+        auto it = memo.find(key);
+        if (it != memo.end()) return it->second;
+        if (!open.insert(key).second) return hash_combine(0xCCCCull, g_unshareable_salt.fetch_add(1));   // cycle through rule ends
+        std::vector<uint64_t> parts;
+        if (rule == g.root) parts.push_back(0xE0Full);                      // the input may end here
+        for (const Site& st : sites[(size_t)rule]) {
+            uint64_t h = unfold[(size_t)d][(size_t)g.sid(st.q, st.x)];
+            int32_t left = d - min_suf[(size_t)st.q][(size_t)st.x];
+            if (left > 0 || (left == 0 && d > 0 && min_suf[(size_t)st.q][(size_t)st.x] == 0)) h = hash_combine(h, sig(st.q, left));
+            parts.push_back(h);
+        }
+        std::sort(parts.begin(), parts.end());
+        parts.erase(std::unique(parts.begin(), parts.end()), parts.end());
+        uint64_t h = 0xF011ull;
+        for (uint64_t p : parts) h = hash_combine(h, p);
+        open.erase(key);
+        memo[key] = h;
+        return h;
+    };
+    std::vector<uint64_t> out((size_t)R);
+    for (int r = 0; r < R; ++r) out[(size_t)r] = sig(r, budget);
+    return out;
+}
+
 std::string describe_grammar(const Grammar& g) {
     std::ostringstream o;
     o << "{\"root\":\"" << g.rules[(size_t)g.root].name << "\",\"rules\":[";

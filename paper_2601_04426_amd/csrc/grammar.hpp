@@ -61,6 +61,15 @@ uint64_t hash_combine(uint64_t h, uint64_t v);        // the order-sensitive has
 // equivalent states have equal planes.
 std::vector<std::vector<int32_t>> bounded_classes(const Grammar& g, int32_t budget, const std::vector<uint64_t>& ref_identity);
 
+// Per rule, a 64-bit signature of everything that can follow an instance of the rule within `budget`
+// bytes in this grammar: the set of states referencing rules continue in (as structural hashes of their
+// unfolding to the bytes that are left), recursively through rules that can end within the budget, and
+// whether the input may end (root rule).  Two rules with equal signatures reject the same uncertain
+// tokens by context expansion (section 2.2), so filtered planes can be shared across grammars
+// (section 3.3: reuse needs matching lookahead).  Rules on a reference cycle through rule ends, or behind
+// a cycle of nullable rule edges, get a process-unique signature (never shared, always sound).
+std::vector<uint64_t> follow_signatures(const Grammar& g, int32_t budget);
+
 // Exact serialisation of one rule in Algorithm 1's canonical order; a reference to rule r is
 // written as ref_id[r].  Two rules with equal text and equal meaning of the ids are isomorphic.
 std::string serialise_rule(const Grammar& g, int32_t rule, const std::vector<uint64_t>& ref_id);

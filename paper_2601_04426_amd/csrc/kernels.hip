@@ -86,7 +86,10 @@ __device__ __forceinline__ bool add_item(const DevTables& T, S& st, uint32_t sid
 // Earley recognition of the n bytes at tok, continuing from context C.  New item sets are numbered
 // C.H, C.H + 1, ...  Returns RES_ALIVE if the set after the last byte is non-empty, RES_EARLY if the
 // root instance could end after some proper non-empty prefix, RES_OVERFLOW if a list filled up.
-template <class S>
+// With FOLLOW, the end of the root instance is not the end of the parse: every state in which a rule
+// referencing the ended rule continues (anywhere in the grammar) goes on as a new root instance, i.e.
+// the rest of the token is matched against everything that can follow in some context.
+template <class S, bool FOLLOW = false>
 __device__ int scan_token(const DevTables& T, const DevCtx& C, const uint8_t* tok, int n, S& st) {
     if (n > S::MAXLEN || (int)C.n_items > S::K) return RES_OVERFLOW;
     int nc = (int)C.n_items;
@@ -132,8 +135,12 @@ __device__ int scan_token(const DevTables& T, const DevCtx& C, const uint8_t* to
             const bool in_nxt = nb > 0 || nr == 0;
             if ((si.w >> 31) && from_nxt == in_nxt) {          // final state: complete, once per item
                 uint32_t rule = si.w & 0x7FFFFFFFu;
-                if (origin == ROOT_ORIGIN) root_now = true;
-                else if (origin != set_idx) {
+                if (origin == ROOT_ORIGIN) {
+                    root_now = true;
+                    if (FOLLOW)
+                        for (uint32_t k = T.site_off[rule]; k < T.site_off[rule + 1]; ++k)
+                            if (!add_item(T, st, T.site_tgt[k], ROOT_ORIGIN, nn, nw, wbeg)) return RES_OVERFLOW;
+                } else if (origin != set_idx) {
                     const bool local = origin >= C.H;
                     int lo = local ? (int)st.get_wstart((int)(origin - C.H)) : (int)C.wait_off[origin];
                     int hi = local ? (int)st.get_wstart((int)(origin - C.H) + 1) : (int)C.wait_off[origin + 1];
@@ -200,6 +207,13 @@ __global__ __launch_bounds__(64 * BUILD_WAVES) void k_build(DevTables T, DevVoca
     st.base = lds + wave * BuildStore::SLOTS * 64 + lane;
     DevCtx C = position_ctx(P, p);
     int res = scan_token(T, C, Vd.bytes + off, n, st);
+    if (P.follow_filter && !(res & (RES_ALIVE | RES_OVERFLOW)) && (res & RES_EARLY)) {
+        // leaves the rule early: keep it uncertain only if some context can take the rest of the token
+        st.sel = 0; st.ws_lo = 0; st.ws_hi = 0;
+        int res2 = scan_token<BuildStore, true>(T, C, Vd.bytes + off, n, st);
+        if (res2 & RES_OVERFLOW) res = RES_OVERFLOW;
+        else if (!(res2 & RES_ALIVE)) res = 0;
+    }
     if (res & RES_OVERFLOW) { push_overflow(S, p, rank); return; }
     store_class(P, p, Vd.W, Vd.perm[rank], res);
 }
@@ -218,6 +232,12 @@ __global__ __launch_bounds__(64) void k_build_slow(DevTables T, DevVocab Vd, Bui
         st.sel = 0;
         DevCtx C = position_ctx(P, p);
         int res = scan_token(T, C, Vd.bytes + off, n, st);
+        if (P.follow_filter && !(res & (RES_ALIVE | RES_OVERFLOW)) && (res & RES_EARLY)) {
+            st.sel = 0;
+            int res2 = scan_token<GlobalStore, true>(T, C, Vd.bytes + off, n, st);
+            if (res2 & RES_OVERFLOW) res = RES_OVERFLOW;
+            else if (!(res2 & RES_ALIVE)) res = 0;
+        }
         if (res & RES_OVERFLOW) { atomicOr(S.count + 1, 2u); continue; }
         store_class(P, p, Vd.W, Vd.perm[rank], res);
     }

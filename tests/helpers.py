@@ -7,8 +7,8 @@ import gen
 import oracle
 
 
-def planes_of(orc: oracle.Oracle, pos, va, parent=None, threads: int = 0):
-    cls = orc.classes(pos, va, threads=threads, parent=parent)
+def planes_of(orc: oracle.Oracle, pos, va, parent=None, follow=False, threads: int = 0):
+    cls = orc.classes(pos, va, threads=threads, parent=parent, follow=follow)
     return oracle.pack_bitmask(cls == oracle.ACCEPTED), oracle.pack_bitmask(cls == oracle.UNCERTAIN)
 
 

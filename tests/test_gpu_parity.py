@@ -27,17 +27,18 @@ def _stream():
     return torch.cuda.current_stream().cuda_stream
 
 
-def check_planes(xg, cfg, vocab, va, ebnf, root, pool=None, depth=2, merge=True, max_contexts=400, seed=0):
+def check_planes(xg, cfg, vocab, va, ebnf, root, pool=None, depth=2, merge=True, follow=True, max_contexts=400, seed=0):
     """Every plane of the cache equals the oracle's classes of the representative it was built for, and a
     seeded sample of all (position, parent) combinations is served by a plane equal to the oracle's classes of
     that exact combination (this is what checks the merging of equivalent states)."""
-    cache = xg.compile_grammar(vocab, ebnf, root, pool=pool, stream=_stream(), context_depth=depth, merge_equivalent=merge)
+    cache = xg.compile_grammar(vocab, ebnf, root, pool=pool, stream=_stream(), context_depth=depth, merge_equivalent=merge,
+                               follow_filter=follow)
     orc = oracle.Oracle(ebnf, root)
     assert cache.stats.positions == len(orc.positions())
     for k in range(cache.num_planes()):
         pos, parent = cache.plane_info(k)
         acc, unc = cache.get_planes(k)
-        want_a, want_u = planes_of(orc, pos, va, parent)
+        want_a, want_u = planes_of(orc, pos, va, parent, follow)
         assert np.array_equal(acc, want_a), ("accepted", pos, parent, diff_words(acc, want_a, cfg.vocab.tokens))
         assert np.array_equal(unc, want_u), ("uncertain", pos, parent, diff_words(unc, want_u, cfg.vocab.tokens))
     contexts = all_contexts(orc, depth)
@@ -51,7 +52,7 @@ def check_planes(xg, cfg, vocab, va, ebnf, root, pool=None, depth=2, merge=True,
         if k not in cache_rows:
             cache_rows[k] = cache.get_planes(k)
         acc, unc = cache_rows[k]
-        want_a, want_u = planes_of(orc, pos, va, parent)
+        want_a, want_u = planes_of(orc, pos, va, parent, follow)
         assert np.array_equal(acc, want_a), ("accepted (merged)", pos, parent, cache.plane_info(k), diff_words(acc, want_a, cfg.vocab.tokens))
         assert np.array_equal(unc, want_u), ("uncertain (merged)", pos, parent, cache.plane_info(k), diff_words(unc, want_u, cfg.vocab.tokens))
     return cache, orc
@@ -98,11 +99,12 @@ def run_decode(xg, cfg, vocab, va, cache, orc, batch, steps, seed, check_every=1
     return n_checked
 
 
-@pytest.mark.parametrize("depth,merge", [(1, False), (1, True), (2, False), (2, True)])
-def test_config1_planes_and_decode(xg, depth, merge):
+@pytest.mark.parametrize("depth,merge,follow", [(1, False, False), (1, True, False), (2, False, False), (2, True, False),
+                                                (1, False, True), (2, True, True)])
+def test_config1_planes_and_decode(xg, depth, merge, follow):
     cfg, vocab, va = load(1)
     ebnf, root = cfg.grammars[0]
-    cache, orc = check_planes(xg, cfg, vocab, va, ebnf, root, depth=depth, merge=merge, max_contexts=100000)
+    cache, orc = check_planes(xg, cfg, vocab, va, ebnf, root, depth=depth, merge=merge, follow=follow, max_contexts=100000)
     st = cache.stats
     if depth == 1 and not merge:
         assert st.built == st.unique == st.positions          # the cache of section 3.4 as it stands: one plane per position
@@ -179,7 +181,7 @@ def test_config5_depth1_unmerged_planes(xg):
     """One plane per position, nothing merged: the plain cache on the largest vocabulary, all 1,547 positions."""
     cfg, vocab, va = load(5)
     ebnf, root = cfg.grammars[0]
-    cache, orc = check_planes(xg, cfg, vocab, va, ebnf, root, depth=1, merge=False, max_contexts=0)
+    cache, orc = check_planes(xg, cfg, vocab, va, ebnf, root, depth=1, merge=False, follow=False, max_contexts=0)
     assert cache.stats.built == cache.stats.positions == len(orc.positions())
     n = run_decode(xg, cfg, vocab, va, cache, orc, batch=64, steps=4, seed=56, check_every=9)
     assert n >= 25
@@ -218,7 +220,8 @@ def test_config4_cross_grammar_pool(xg):
     built1 = 0
     distinct = set()
     for ebnf, root in cfg.grammars:
-        c1 = xg.compile_grammar(vocab, ebnf, root, pool=pool1, stream=_stream(), context_depth=1, merge_equivalent=False)
+        c1 = xg.compile_grammar(vocab, ebnf, root, pool=pool1, stream=_stream(), context_depth=1, merge_equivalent=False,
+                                follow_filter=False)
         built1 += c1.stats.built
         orc = oracle.Oracle(ebnf, root)
         memo = {}
@@ -291,7 +294,7 @@ def test_edge_cases(xg):
     for k in range(cache.num_planes()):
         acc, unc = cache.get_planes(k)
         pos, parent = cache.plane_info(k)
-        wa, wu = planes_of(orc, pos, va, parent)
+        wa, wu = planes_of(orc, pos, va, parent, True)
         assert np.array_equal(acc, wa) and np.array_equal(unc, wu)
     m = xg.Matcher(cache)
     bm = torch.full((1, 1), -1, dtype=torch.int32, device="cuda:0")
