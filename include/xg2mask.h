@@ -167,6 +167,10 @@ int32_t xg2_matcher_frontier(const xg2_matcher*, int32_t* positions_host, int32_
 int32_t xg2_fill_next_token_bitmask(xg2_matcher* const* matchers, int32_t B, int32_t* bitmask_dev,
                                     int64_t row_stride_words, void* hip_stream);
 
+/* Measurement aid: device time in microseconds of the work the latest fill call of this process enqueued
+ * (context upload, plane union, re-check), from HIP events on its stream.  Waits for that work.   */
+int32_t xg2_fill_last_device_us(float* out);
+
 /* ---- apply_token_bitmask(logits[B, V], bitmask) -------------------------------------------------
  * In place: logits[b, v] = -infinity where bit v of bitmask row b is 0; other elements keep
  * their bit pattern.  dtype: XG2_F32 or XG2_BF16.  logits_dev: device, B rows of

@@ -25,7 +25,7 @@ EXPORTS = [
     "xg2_compile_grammar", "xg2_mask_cache_destroy", "xg2_mask_cache_num_positions", "xg2_mask_cache_num_planes",
     "xg2_mask_cache_plane_info", "xg2_mask_cache_find_plane", "xg2_mask_cache_get_planes", "xg2_matcher_create", "xg2_matcher_create_host", "xg2_matcher_destroy",
     "xg2_matcher_accept_token", "xg2_matcher_reset", "xg2_matcher_is_terminated", "xg2_matcher_frontier",
-    "xg2_fill_next_token_bitmask", "xg2_apply_token_bitmask",
+    "xg2_fill_next_token_bitmask", "xg2_fill_last_device_us", "xg2_apply_token_bitmask",
 ]
 
 
@@ -57,7 +57,7 @@ def _load() -> ctypes.CDLL:
     except ImportError:
         pass
     if not os.path.exists(LIB_PATH):
-        raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2601_04426_amd.build` "
+        raise ImportError(f"{LIB_PATH} is missing: build it with `python paper_2601_04426_amd/build.py` "
                           "(there is no fallback implementation)")
     L = ctypes.CDLL(LIB_PATH)
     vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
@@ -89,6 +89,7 @@ def _load() -> ctypes.CDLL:
     L.xg2_matcher_is_terminated.argtypes = [vp, ctypes.POINTER(i32)]
     L.xg2_matcher_frontier.argtypes = [vp, vp, i32, ctypes.POINTER(i32), ctypes.POINTER(i32)]
     L.xg2_fill_next_token_bitmask.argtypes = [vp, i32, vp, i64, vp]
+    L.xg2_fill_last_device_us.argtypes = [ctypes.POINTER(ctypes.c_float)]
     L.xg2_apply_token_bitmask.argtypes = [vp, i32, i32, i32, i64, vp, i64, vp]
     for name in EXPORTS:
         if name not in ("xg2_last_error",) and not name.endswith("_destroy"):
@@ -275,6 +276,12 @@ def fill_next_token_bitmask(matchers, bitmask_ptr: int, row_stride_words: int, s
         arr = (ctypes.c_void_p * len(matchers))(*[m.h for m in matchers])
     _check(lib.xg2_fill_next_token_bitmask(arr, len(matchers), ctypes.c_void_p(bitmask_ptr), row_stride_words,
                                            ctypes.c_void_p(stream)))
+
+
+def fill_last_device_us() -> float:
+    out = ctypes.c_float(0)
+    _check(lib.xg2_fill_last_device_us(ctypes.byref(out)))
+    return out.value
 
 
 def apply_token_bitmask(logits_ptr: int, dtype: int, B: int, V: int, row_stride_elems: int, bitmask_ptr: int,

@@ -53,6 +53,33 @@ struct DevBuf {                                    // owning device array
     }
 };
 
+// Several host arrays laid out back to back (256-byte aligned) in one pinned buffer, moved to the device
+// with one copy.
+struct Packer {
+    struct Seg { const void* src; size_t bytes, off; };
+    std::vector<Seg> segs;
+    size_t total = 0;
+    uint8_t* host = nullptr;
+    uint8_t* dev = nullptr;
+    bool own_dev = true;
+    template <typename T> size_t add(const std::vector<T>& v) {
+        size_t off = total;
+        segs.push_back({v.data(), v.size() * sizeof(T), off});
+        total = (total + v.size() * sizeof(T) + 255) & ~(size_t)255;
+        return off;
+    }
+    void stage() {
+        size_t n = std::max<size_t>(total, 256);
+        HIP_CHECK(hipHostMalloc((void**)&host, n, hipHostMallocDefault));
+        HIP_CHECK(hipMalloc((void**)&dev, n));
+        for (const Seg& s : segs) if (s.bytes) std::memcpy(host + s.off, s.src, s.bytes);
+    }
+    void copy(hipStream_t stream) { if (total) HIP_CHECK(hipMemcpyAsync(dev, host, total, hipMemcpyHostToDevice, stream)); }
+    template <typename T> T* at(size_t off) const { return reinterpret_cast<T*>(dev + off); }
+    uint8_t* release_dev() { own_dev = false; return dev; }
+    ~Packer() { if (host) (void)hipHostFree(host); if (dev && own_dev) (void)hipFree(dev); }
+};
+
 void require_device() {
     int n = 0;
     hipError_t e = hipGetDeviceCount(&n);
@@ -179,8 +206,8 @@ struct CacheImpl {
     std::shared_ptr<VocabImpl> vocab;
     std::shared_ptr<PoolImpl> pool;
     std::shared_ptr<GrammarImpl> gram;
-    DevBuf<StateInfo> d_state; DevBuf<ByteEdge> d_bedge; DevBuf<RefEdgeP> d_redge; DevBuf<RuleInfo> d_rule;
-    DevBuf<uint32_t> d_site_off, d_site_tgt;
+    uint8_t* d_tables = nullptr;                            // one device block holding all packed tables
+    ~CacheImpl() { if (d_tables) (void)hipFree(d_tables); }
     DevTables dt{};
     int32_t context_depth = 2;
     std::vector<PlaneInfo> planes;
@@ -209,7 +236,10 @@ struct FillWorkspace {
     FillSlot slots[4];
     int next = 0;
     DevBuf<uint32_t> cand_words, work_list, work_count;
+    hipEvent_t t_begin = nullptr, t_end = nullptr;          // around the device work of the latest fill
+    bool timed = false;
     void ensure_scratch(size_t words) {
+        if (!t_begin) { HIP_CHECK(hipEventCreate(&t_begin)); HIP_CHECK(hipEventCreate(&t_end)); }
         if (cand_words.n < words) { cand_words.alloc(words * 5 / 4); work_list.alloc(words * 5 / 4); }
         if (!work_count.p) work_count.alloc(1);
     }
@@ -475,20 +505,6 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
         }
         double host_ms_a = ms_since(t0);
 
-        hipEvent_t ev0, ev1, evk0, evk1;
-        HIP_CHECK(hipEventCreate(&ev0));
-        HIP_CHECK(hipEventCreate(&ev1));
-        HIP_CHECK(hipEventCreate(&evk0));
-        HIP_CHECK(hipEventCreate(&evk1));
-        HIP_CHECK(hipEventRecord(ev0, stream));
-        cache->d_state.upload(ft.state_info, stream);
-        cache->d_bedge.upload(ft.byte_edges, stream);
-        cache->d_redge.upload(ft.ref_edges, stream);
-        cache->d_rule.upload(ft.rule_info, stream);
-        cache->dt.state_info = reinterpret_cast<const uint4*>(cache->d_state.p);
-        cache->dt.byte_edges = reinterpret_cast<const uint2*>(cache->d_bedge.p);
-        cache->dt.ref_edges = reinterpret_cast<const uint2*>(cache->d_redge.p);
-        cache->dt.rule_info = reinterpret_cast<const uint2*>(cache->d_rule.p);
         // per rule, the states referencing rules continue in: one per class of indistinguishable states
         std::vector<uint32_t> site_off{0}, site_tgt;
         if (follow) {
@@ -504,10 +520,6 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
                 site_off.push_back((uint32_t)site_tgt.size());
             }
         } else site_off.assign((size_t)R + 1, 0);
-        cache->d_site_off.upload(site_off, stream);
-        cache->d_site_tgt.upload(site_tgt, stream);
-        cache->dt.site_off = cache->d_site_off.p;
-        cache->dt.site_tgt = cache->d_site_tgt.p;
 
         // plan: closed start set and live first-byte ranges of every plane to build
         auto t1 = std::chrono::steady_clock::now();
@@ -549,32 +561,54 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
                 b = e + 1;
             }
         }
+
+        // everything the device needs goes up in two copies: the tables (kept with the cache) and the plan
+        Packer tab, plan;
+        const size_t o_state = tab.add(ft.state_info), o_bedge = tab.add(ft.byte_edges), o_redge = tab.add(ft.ref_edges),
+                     o_rule = tab.add(ft.rule_info), o_soff = tab.add(site_off), o_stgt = tab.add(site_tgt);
+        const size_t o_seg_pos = plan.add(seg_pos), o_seg_lo = plan.add(seg_lo), o_seg_hi = plan.add(seg_hi), o_seg_blk = plan.add(seg_blk),
+                     o_items = plan.add(ctx_items), o_item_off = plan.add(ctx_item_off), o_wait = plan.add(ctx_wait),
+                     o_wait_off = plan.add(ctx_wait_off), o_woff_start = plan.add(ctx_woff_start), o_H = plan.add(ctx_H),
+                     o_rows = plan.add(build_rows);
+        tab.stage();
+        plan.stage();
+        DevBuf<unsigned long long> d_counts;
+        d_counts.alloc(2);
         double host_ms_b = ms_since(t1);
 
-        DevBuf<uint32_t> d_seg_pos, d_seg_lo, d_seg_hi, d_seg_blk, d_items, d_item_off, d_wait, d_wait_off, d_woff_start, d_H;
-        DevBuf<uint32_t*> d_rows;
-        DevBuf<unsigned long long> d_counts;
-        d_seg_pos.upload(seg_pos, stream); d_seg_lo.upload(seg_lo, stream); d_seg_hi.upload(seg_hi, stream);
-        d_seg_blk.upload(seg_blk, stream); d_items.upload(ctx_items, stream); d_item_off.upload(ctx_item_off, stream);
-        d_wait.upload(ctx_wait, stream); d_wait_off.upload(ctx_wait_off, stream);
-        d_woff_start.upload(ctx_woff_start, stream); d_H.upload(ctx_H, stream);
-        d_rows.upload(build_rows, stream);
-        d_counts.alloc(2);
+        hipEvent_t ev0, ev1, evk0, evk1;
+        HIP_CHECK(hipEventCreate(&ev0));
+        HIP_CHECK(hipEventCreate(&ev1));
+        HIP_CHECK(hipEventCreate(&evk0));
+        HIP_CHECK(hipEventCreate(&evk1));
+        HIP_CHECK(hipEventRecord(ev0, stream));
+        tab.copy(stream);
+        plan.copy(stream);
+        cache->d_tables = tab.release_dev();
+        cache->dt.state_info = tab.at<const uint4>(o_state);
+        cache->dt.byte_edges = tab.at<const uint2>(o_bedge);
+        cache->dt.ref_edges = tab.at<const uint2>(o_redge);
+        cache->dt.rule_info = tab.at<const uint2>(o_rule);
+        cache->dt.site_off = tab.at<const uint32_t>(o_soff);
+        cache->dt.site_tgt = tab.at<const uint32_t>(o_stgt);
         HIP_CHECK(hipMemsetAsync(d_counts.p, 0, 2 * sizeof(unsigned long long), stream));
         HIP_CHECK(hipMemsetAsync(S.count, 0, sizeof(uint32_t), stream));
         BuildPlan P{};
-        P.seg_pos = d_seg_pos.p; P.seg_lo = d_seg_lo.p; P.seg_hi = d_seg_hi.p; P.seg_blk = d_seg_blk.p;
+        P.seg_pos = plan.at<const uint32_t>(o_seg_pos); P.seg_lo = plan.at<const uint32_t>(o_seg_lo);
+        P.seg_hi = plan.at<const uint32_t>(o_seg_hi); P.seg_blk = plan.at<const uint32_t>(o_seg_blk);
         P.n_seg = (uint32_t)seg_pos.size(); P.n_blocks = seg_blk.back();
-        P.ctx_items = d_items.p; P.ctx_item_off = d_item_off.p; P.ctx_wait = d_wait.p; P.ctx_wait_off = d_wait_off.p;
-        P.ctx_woff_start = d_woff_start.p; P.ctx_H = d_H.p;
-        P.plane_ptr = d_rows.p;
+        P.ctx_items = plan.at<const uint32_t>(o_items); P.ctx_item_off = plan.at<const uint32_t>(o_item_off);
+        P.ctx_wait = plan.at<const uint32_t>(o_wait); P.ctx_wait_off = plan.at<const uint32_t>(o_wait_off);
+        P.ctx_woff_start = plan.at<const uint32_t>(o_woff_start); P.ctx_H = plan.at<const uint32_t>(o_H);
+        P.plane_ptr = plan.at<uint32_t*>(o_rows);
         P.follow_filter = follow ? 1u : 0u;
+        uint32_t* const* d_rows_p = plan.at<uint32_t*>(o_rows);
         HIP_CHECK(hipEventRecord(evk0, stream));
         if (!build.empty()) launch_build(cache->dt, V.dv, P, S, stream);
         HIP_CHECK(hipEventRecord(evk1, stream));
         if (!build.empty()) {
             launch_build_slow(cache->dt, V.dv, P, S, stream);
-            launch_popcount(d_rows.p, (uint32_t)build_rows.size(), V.W, d_counts.p, stream);
+            launch_popcount(d_rows_p, (uint32_t)build_rows.size(), V.W, d_counts.p, stream);
         }
         HIP_CHECK(hipEventRecord(ev1, stream));
         uint32_t slow_counts[2] = {0, 0};
@@ -815,6 +849,8 @@ int32_t xg2_fill_next_token_bitmask(xg2_matcher* const* matchers, int32_t B, int
         if (!wait.empty()) std::memcpy(slot.host + o_wait, wait.data(), wait.size() * sizeof(uint32_t));
         if (!wait_off.empty()) std::memcpy(slot.host + o_woff, wait_off.data(), wait_off.size() * sizeof(uint32_t));
         std::memcpy(slot.host + o_tabs, tables.data(), tables.size() * sizeof(DevTables));
+        fill_ws().ensure_scratch((size_t)B * V.W);
+        HIP_CHECK(hipEventRecord(fill_ws().t_begin, stream));
         HIP_CHECK(hipMemcpyAsync(slot.dev, slot.host, total, hipMemcpyHostToDevice, stream));
         FillBatch F{};
         F.rows = reinterpret_cast<const FillRow*>(slot.dev + o_rows); F.B = (uint32_t)B;
@@ -832,8 +868,23 @@ int32_t xg2_fill_next_token_bitmask(xg2_matcher* const* matchers, int32_t B, int
         launch_fill(F, V.dv, bitmask_dev, row_stride_words, S, stream);
         launch_recheck_slow(F, V.dv, bitmask_dev, row_stride_words, S, stream);
         HIP_CHECK(hipGetLastError());
+        HIP_CHECK(hipEventRecord(fill_ws().t_end, stream));
+        fill_ws().timed = true;
         HIP_CHECK(hipEventRecord(slot.done, stream));
         slot.in_flight = true;
+        return XG2_OK;
+    });
+}
+
+int32_t xg2_fill_last_device_us(float* out) {
+    return guarded([&]() -> int32_t {
+        if (!out) return fail(XG2_EINVAL, "xg2_fill_last_device_us: null out");
+        std::lock_guard<std::mutex> ws_lock(fill_ws().mu);
+        if (!fill_ws().timed) return fail(XG2_EINVAL, "xg2_fill_last_device_us: no fill call yet");
+        HIP_CHECK(hipEventSynchronize(fill_ws().t_end));
+        float ms = 0.f;
+        HIP_CHECK(hipEventElapsedTime(&ms, fill_ws().t_begin, fill_ws().t_end));
+        *out = ms * 1e3f;
         return XG2_OK;
     });
 }
