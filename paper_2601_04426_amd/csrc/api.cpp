@@ -113,7 +113,7 @@ struct VocabImpl {
         if (on_device) return;
         require_device();
         std::vector<uint8_t> padded = s_bytes;
-        padded.resize(s_bytes.size() + 16, 0);
+        padded.resize(s_bytes.size() + 32, 0);
         d_bytes.upload(padded, nullptr);
         d_off.upload(s_off, nullptr);
         d_perm.upload(perm, nullptr);
@@ -319,10 +319,15 @@ int32_t xg2_vocab_create(const uint8_t* bytes, const uint64_t* offsets, int32_t 
         for (int32_t i = 0; i < V; ++i) if (v->len(i) == 0) v->special[(size_t)i] = 1;
         for (int32_t i = 0; i < V; ++i) if (!v->special[(size_t)i]) v->perm.push_back((uint32_t)i);
         std::sort(v->perm.begin(), v->perm.end(), [&](uint32_t a, uint32_t b) {
+            // by first byte (whole ranges of it are skipped per plane), then by length (a wavefront's 64 lanes
+            // run as long as its longest token), then by bytes (neighbours share prefixes)
             size_t la = v->len((int32_t)a), lb = v->len((int32_t)b);
-            int c = std::memcmp(v->tok((int32_t)a), v->tok((int32_t)b), std::min(la, lb));
-            if (c != 0) return c < 0;
+            const uint8_t* ta = v->tok((int32_t)a);
+            const uint8_t* tb = v->tok((int32_t)b);
+            if (ta[0] != tb[0]) return ta[0] < tb[0];
             if (la != lb) return la < lb;
+            int c = std::memcmp(ta, tb, la);
+            if (c != 0) return c < 0;
             return a < b;
         });
         v->n_sorted = (uint32_t)v->perm.size();
@@ -512,7 +517,7 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
             for (int q = 0; q < R; ++q)
                 for (int s = 0; s < g.rules[(size_t)q].n_states(); ++s)
                     for (auto& e : g.rules[(size_t)q].redges[(size_t)s])
-                        by_rule[(size_t)e.rule].push_back((uint32_t)g.sid(q, classes[(size_t)q][(size_t)e.tgt]));
+                        by_rule[(size_t)e.rule].push_back(ft.ref((uint32_t)g.sid(q, classes[(size_t)q][(size_t)e.tgt])));
             for (auto& v : by_rule) {
                 std::sort(v.begin(), v.end());
                 v.erase(std::unique(v.begin(), v.end()), v.end());
@@ -533,7 +538,7 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
             auto loc = [](int32_t o) { return o < 0 ? kRootOrigin : (uint32_t)o; };
             bool live[257] = {false};
             for (const ChartItem& it : sets.back().scan) {
-                ctx_items.push_back(pack_item(it.sid, loc(it.origin)));
+                ctx_items.push_back(pack_item(ft.ref(it.sid), loc(it.origin)));
                 const StateInfo& si = ft.state_info[it.sid];
                 for (uint32_t e = 0; e < (si.counts & 0xFFFF); ++e) {
                     const ByteEdge& be = ft.byte_edges[si.byte_off + e];
@@ -545,7 +550,7 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
             ctx_H.push_back((uint32_t)sets.size());
             for (const ChartSet& cs : sets) {
                 ctx_wait_off.push_back((uint32_t)ctx_wait.size());
-                for (const ChartItem& it : cs.wait) ctx_wait.push_back(pack_item(it.sid, loc(it.origin)));
+                for (const ChartItem& it : cs.wait) ctx_wait.push_back(pack_item(ft.ref(it.sid), loc(it.origin)));
             }
             ctx_wait_off.push_back((uint32_t)ctx_wait.size());
             for (int b = 0; b < 256;) {
@@ -564,8 +569,9 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
 
         // everything the device needs goes up in two copies: the tables (kept with the cache) and the plan
         Packer tab, plan;
-        const size_t o_state = tab.add(ft.state_info), o_bedge = tab.add(ft.byte_edges), o_redge = tab.add(ft.ref_edges),
-                     o_rule = tab.add(ft.rule_info), o_soff = tab.add(site_off), o_stgt = tab.add(site_tgt);
+        const size_t o_state = tab.add(ft.state_info), o_redge = tab.add(ft.dev_ref_edges), o_rule = tab.add(ft.dev_rule_info),
+                     o_soff = tab.add(site_off), o_stgt = tab.add(site_tgt), o_trans = tab.add(ft.trans),
+                     o_cls = tab.add(ft.byte_class_words);
         const size_t o_seg_pos = plan.add(seg_pos), o_seg_lo = plan.add(seg_lo), o_seg_hi = plan.add(seg_hi), o_seg_blk = plan.add(seg_blk),
                      o_items = plan.add(ctx_items), o_item_off = plan.add(ctx_item_off), o_wait = plan.add(ctx_wait),
                      o_wait_off = plan.add(ctx_wait_off), o_woff_start = plan.add(ctx_woff_start), o_H = plan.add(ctx_H),
@@ -586,7 +592,9 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
         plan.copy(stream);
         cache->d_tables = tab.release_dev();
         cache->dt.state_info = tab.at<const uint4>(o_state);
-        cache->dt.byte_edges = tab.at<const uint2>(o_bedge);
+        cache->dt.trans = tab.at<const uint32_t>(o_trans);
+        cache->dt.byte_class_words = tab.at<const uint32_t>(o_cls);
+        cache->dt.n_classes = ft.n_classes;
         cache->dt.ref_edges = tab.at<const uint2>(o_redge);
         cache->dt.rule_info = tab.at<const uint2>(o_rule);
         cache->dt.site_off = tab.at<const uint32_t>(o_soff);

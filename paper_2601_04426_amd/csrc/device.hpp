@@ -7,10 +7,12 @@
 namespace xg2 {
 
 struct DevTables {                       // packed grammar tables (see tables.hpp for the word layout)
-    const uint4* state_info;
-    const uint2* byte_edges;
-    const uint2* ref_edges;
-    const uint2* rule_info;
+    const uint4* state_info;             // loaded only for states with rule edges or final states
+    const uint2* ref_edges;              // {rule, state reference of the target}
+    const uint2* rule_info;              // {state reference of the start state, nullable}
+    const uint32_t* trans;               // [n_states * n_classes] state reference of the byte target or 0xFFFFFFFF
+    const uint32_t* byte_class_words;    // [64] byte -> class, four per word
+    uint32_t n_classes;
     const uint32_t* site_off;            // per rule: states in which referencing rules continue (CSR)
     const uint32_t* site_tgt;
 };

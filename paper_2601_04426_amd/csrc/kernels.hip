@@ -11,9 +11,13 @@
 namespace xg2 {
 namespace {
 
-constexpr uint32_t SID_BITS = 21;
-constexpr uint32_t SID_MASK = (1u << SID_BITS) - 1;
-constexpr uint32_t ROOT_ORIGIN = (1u << (32 - SID_BITS)) - 1;
+// A state reference is 21 bits: state id (18) | has byte edge | has rule edge | final; an item is a state
+// reference with the origin (item-set index, 2047 = root instance) in the upper 11 bits.
+constexpr uint32_t SID_MASK = (1u << 18) - 1;
+constexpr uint32_t F_BYTE = 1u << 18, F_REF = 1u << 19, F_FINAL = 1u << 20;
+constexpr uint32_t REF_BITS = 21;
+constexpr uint32_t ROOT_ORIGIN = (1u << (32 - REF_BITS)) - 1;
+constexpr uint32_t NO_TARGET = 0xFFFFFFFFu;
 
 constexpr int RES_ALIVE = 1, RES_EARLY = 2, RES_OVERFLOW = 4;
 
@@ -38,6 +42,7 @@ struct LdsStore {
     __device__ uint32_t get_wait(int k) const { return base[(2 * K + k) * 64]; }
     __device__ void set_wait(int k, uint32_t v) { base[(2 * K + k) * 64] = v; }
     __device__ void swap() { sel ^= 1; }
+    __device__ void reset() { sel = 0; ws_lo = 0; ws_hi = 0; }
     __device__ void set_wstart(int j, uint32_t v) {
         if (j < 8) ws_lo |= (unsigned long long)v << (8 * j); else ws_hi |= (unsigned long long)v << (8 * (j - 8));
     }
@@ -58,24 +63,23 @@ struct GlobalStore {
     __device__ uint32_t get_wait(int k) const { return base[(size_t)(2 * K + k) * stride]; }
     __device__ void set_wait(int k, uint32_t v) { base[(size_t)(2 * K + k) * stride] = v; }
     __device__ void swap() { sel ^= 1; }
+    __device__ void reset() { sel = 0; }
     __device__ void set_wstart(int j, uint32_t v) { base[(size_t)(2 * K + WM + j) * stride] = v; }
     __device__ uint32_t get_wstart(int j) const { return base[(size_t)(2 * K + WM + j) * stride]; }
 };
 
-// Put item (sid, origin) into the set under construction unless it is there.  Items whose state has a
-// byte edge (or no edge: they only ever complete) go to `nxt`, items with a rule edge to the wait list.
-// Returns false when a list is full.
+// Put item (state reference, origin) into the set under construction unless it is there.  Items whose state
+// has a byte edge (or no edge: they only ever complete) go to `nxt`, items with a rule edge to the wait
+// list.  No memory is read: the flags travel with the state reference.  Returns false when a list is full.
 template <class S>
-__device__ __forceinline__ bool add_item(const DevTables& T, S& st, uint32_t sid, uint32_t origin, int& nn, int& nw, int wbeg) {
-    uint4 si = T.state_info[sid];
-    uint32_t nb = si.z & 0xFFFF, nr = si.z >> 16;
-    uint32_t item = sid | (origin << SID_BITS);
-    if (nb > 0 || nr == 0) {
+__device__ __forceinline__ bool add_item(S& st, uint32_t ref, uint32_t origin, int& nn, int& nw, int wbeg) {
+    const uint32_t item = ref | (origin << REF_BITS);
+    if ((ref & F_BYTE) || !(ref & F_REF)) {
         for (int k = 0; k < nn; ++k) if (st.get_nxt(k) == item) return true;
         if (nn == S::K) return false;
         st.set_nxt(nn++, item);
     }
-    if (nr > 0) {
+    if (ref & F_REF) {
         for (int k = wbeg; k < nw; ++k) if (st.get_wait(k) == item) return true;
         if (nw == S::WM) return false;
         st.set_wait(nw++, item);
@@ -89,68 +93,68 @@ __device__ __forceinline__ bool add_item(const DevTables& T, S& st, uint32_t sid
 // With FOLLOW, the end of the root instance is not the end of the parse: every state in which a rule
 // referencing the ended rule continues (anywhere in the grammar) goes on as a new root instance, i.e.
 // the rest of the token is matched against everything that can follow in some context.
+// cls_words: the byte -> class table (64 words), in LDS or device memory.
 template <class S, bool FOLLOW = false>
-__device__ int scan_token(const DevTables& T, const DevCtx& C, const uint8_t* tok, int n, S& st) {
+__device__ int scan_token(const DevTables& T, const uint32_t* cls_words, const DevCtx& C, const uint8_t* tok, int n, S& st) {
     if (n > S::MAXLEN || (int)C.n_items > S::K) return RES_OVERFLOW;
     int nc = (int)C.n_items;
     for (int k = 0; k < nc; ++k) st.set_cur(k, C.items[k]);
     int nw = 0;
     int res = 0;
+    uint32_t b_next = n > 0 ? tok[0] : 0;
     for (int i = 0; i < n; ++i) {
-        const uint32_t b = tok[i];
+        const uint32_t b = b_next;
+        if (i + 1 < n) b_next = tok[i + 1];                     // in flight while this byte is processed
+        const uint32_t cls = (cls_words[b >> 2] >> ((b & 3) * 8)) & 0xFF;
         const uint32_t set_idx = C.H + (uint32_t)i;
         int nn = 0;
         const int wbeg = nw;
         st.set_wstart(i, (uint32_t)nw);
-        // scanner
+        // scanner: one table word per scannable item
         for (int k = 0; k < nc; ++k) {
-            uint32_t it = st.get_cur(k);
-            uint4 si = T.state_info[it & SID_MASK];
-            uint32_t nb = si.z & 0xFFFF;
-            for (uint32_t e = 0; e < nb; ++e) {
-                uint2 be = T.byte_edges[si.x + e];
-                if (b >= (be.x & 0xFF) && b <= ((be.x >> 8) & 0xFF)) {
-                    if (!add_item(T, st, be.y, it >> SID_BITS, nn, nw, wbeg)) return RES_OVERFLOW;
-                    break;                                   // the rule automaton is deterministic
-                }
-            }
+            const uint32_t it = st.get_cur(k);
+            if (!(it & F_BYTE)) continue;
+            const uint32_t tgt = T.trans[(it & SID_MASK) * T.n_classes + cls];
+            if (tgt != NO_TARGET && !add_item(st, tgt, it >> REF_BITS, nn, nw, wbeg)) return RES_OVERFLOW;
         }
         // predictor and completer over the growing lists
         bool root_now = false;
         int pn = 0, pw = wbeg;
         while (pn < nn || pw < nw) {
             const bool from_nxt = pn < nn;
-            uint32_t it = from_nxt ? st.get_nxt(pn++) : st.get_wait(pw++);
-            uint32_t origin = it >> SID_BITS;
-            uint4 si = T.state_info[it & SID_MASK];
-            uint32_t nb = si.z & 0xFFFF, nr = si.z >> 16;
+            const uint32_t it = from_nxt ? st.get_nxt(pn++) : st.get_wait(pw++);
+            const uint32_t origin = it >> REF_BITS;
+            const bool in_nxt = (it & F_BYTE) || !(it & F_REF);
+            const bool complete = (it & F_FINAL) && from_nxt == in_nxt;      // once per item
+            if (from_nxt && !complete) continue;                 // plain scannable item: nothing to do
+            const uint4 si = T.state_info[it & SID_MASK];
             if (!from_nxt) {
+                const uint32_t nr = si.z >> 16;
                 for (uint32_t e = 0; e < nr; ++e) {
-                    uint2 re = T.ref_edges[si.y + e];
-                    uint2 ri = T.rule_info[re.x];
-                    if (!add_item(T, st, ri.x, set_idx, nn, nw, wbeg)) return RES_OVERFLOW;
-                    if (ri.y && !add_item(T, st, re.y, origin, nn, nw, wbeg)) return RES_OVERFLOW;   // nullable rule
+                    const uint2 re = T.ref_edges[si.y + e];
+                    const uint2 ri = T.rule_info[re.x];
+                    if (!add_item(st, ri.x, set_idx, nn, nw, wbeg)) return RES_OVERFLOW;
+                    if (ri.y && !add_item(st, re.y, origin, nn, nw, wbeg)) return RES_OVERFLOW;   // nullable rule
                 }
             }
-            const bool in_nxt = nb > 0 || nr == 0;
-            if ((si.w >> 31) && from_nxt == in_nxt) {          // final state: complete, once per item
-                uint32_t rule = si.w & 0x7FFFFFFFu;
+            if (complete) {
+                const uint32_t rule = si.w & 0x7FFFFFFFu;
                 if (origin == ROOT_ORIGIN) {
                     root_now = true;
                     if (FOLLOW)
                         for (uint32_t k = T.site_off[rule]; k < T.site_off[rule + 1]; ++k)
-                            if (!add_item(T, st, T.site_tgt[k], ROOT_ORIGIN, nn, nw, wbeg)) return RES_OVERFLOW;
+                            if (!add_item(st, T.site_tgt[k], ROOT_ORIGIN, nn, nw, wbeg)) return RES_OVERFLOW;
                 } else if (origin != set_idx) {
                     const bool local = origin >= C.H;
-                    int lo = local ? (int)st.get_wstart((int)(origin - C.H)) : (int)C.wait_off[origin];
-                    int hi = local ? (int)st.get_wstart((int)(origin - C.H) + 1) : (int)C.wait_off[origin + 1];
+                    const int lo = local ? (int)st.get_wstart((int)(origin - C.H)) : (int)C.wait_off[origin];
+                    const int hi = local ? (int)st.get_wstart((int)(origin - C.H) + 1) : (int)C.wait_off[origin + 1];
                     for (int k = lo; k < hi; ++k) {
-                        uint32_t w = local ? st.get_wait(k) : C.wait[k];
-                        uint4 wi = T.state_info[w & SID_MASK];
-                        uint32_t wr = wi.z >> 16;
+                        const uint32_t w = local ? st.get_wait(k) : C.wait[k];
+                        const uint4 wi = T.state_info[w & SID_MASK];
+                        const uint32_t wr = wi.z >> 16;
                         for (uint32_t e = 0; e < wr; ++e) {
-                            uint2 re = T.ref_edges[wi.y + e];
-                            if (re.x == rule && !add_item(T, st, re.y, w >> SID_BITS, nn, nw, wbeg)) return RES_OVERFLOW;
+                            const uint2 re = T.ref_edges[wi.y + e];
+                            if (re.x == rule && !add_item(st, re.y, w >> REF_BITS, nn, nw, wbeg)) return RES_OVERFLOW;
                         }
                     }
                 }
@@ -164,7 +168,7 @@ __device__ int scan_token(const DevTables& T, const DevCtx& C, const uint8_t* to
     return res | RES_ALIVE;
 }
 
-constexpr int BUILD_K = 12, BUILD_WM = 24;
+constexpr int BUILD_K = 8, BUILD_WM = 12;
 constexpr int BUILD_WAVES = 4;
 using BuildStore = LdsStore<BUILD_K, BUILD_WM>;
 
@@ -192,6 +196,9 @@ __device__ __forceinline__ void store_class(const BuildPlan& P, uint32_t p, uint
 
 __global__ __launch_bounds__(64 * BUILD_WAVES) void k_build(DevTables T, DevVocab Vd, BuildPlan P, SlowScratch S) {
     __shared__ uint32_t lds[BUILD_WAVES * BuildStore::SLOTS * 64];
+    __shared__ uint32_t cls_words[64];
+    if (threadIdx.x < 64) cls_words[threadIdx.x] = T.byte_class_words[threadIdx.x];
+    __syncthreads();
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const uint32_t blk = blockIdx.x * BUILD_WAVES + wave;
     if (blk >= P.n_blocks) return;
@@ -206,11 +213,11 @@ __global__ __launch_bounds__(64 * BUILD_WAVES) void k_build(DevTables T, DevVoca
     BuildStore st;
     st.base = lds + wave * BuildStore::SLOTS * 64 + lane;
     DevCtx C = position_ctx(P, p);
-    int res = scan_token(T, C, Vd.bytes + off, n, st);
+    int res = scan_token(T, cls_words, C, Vd.bytes + off, n, st);
     if (P.follow_filter && !(res & (RES_ALIVE | RES_OVERFLOW)) && (res & RES_EARLY)) {
         // leaves the rule early: keep it uncertain only if some context can take the rest of the token
-        st.sel = 0; st.ws_lo = 0; st.ws_hi = 0;
-        int res2 = scan_token<BuildStore, true>(T, C, Vd.bytes + off, n, st);
+        st.reset();
+        int res2 = scan_token<BuildStore, true>(T, cls_words, C, Vd.bytes + off, n, st);
         if (res2 & RES_OVERFLOW) res = RES_OVERFLOW;
         else if (!(res2 & RES_ALIVE)) res = 0;
     }
@@ -229,12 +236,12 @@ __global__ __launch_bounds__(64) void k_build_slow(DevTables T, DevVocab Vd, Bui
         const uint32_t p = S.list[2 * idx], rank = S.list[2 * idx + 1];
         const uint32_t off = Vd.off[rank];
         const int n = (int)(Vd.off[rank + 1] - off);
-        st.sel = 0;
+        st.reset();
         DevCtx C = position_ctx(P, p);
-        int res = scan_token(T, C, Vd.bytes + off, n, st);
+        int res = scan_token(T, T.byte_class_words, C, Vd.bytes + off, n, st);
         if (P.follow_filter && !(res & (RES_ALIVE | RES_OVERFLOW)) && (res & RES_EARLY)) {
-            st.sel = 0;
-            int res2 = scan_token<GlobalStore, true>(T, C, Vd.bytes + off, n, st);
+            st.reset();
+            int res2 = scan_token<GlobalStore, true>(T, T.byte_class_words, C, Vd.bytes + off, n, st);
             if (res2 & RES_OVERFLOW) res = RES_OVERFLOW;
             else if (!(res2 & RES_ALIVE)) res = 0;
         }
@@ -260,7 +267,7 @@ __global__ __launch_bounds__(256) void k_popcount(const uint32_t* const* plane_p
 // k_recheck: each wave takes 64 listed words, spreads their set bits densely over its lanes and runs the
 // Earley routine from the row's context; survivors are OR-ed into the bitmask.
 constexpr int FILL_THREADS = 256;
-constexpr int FILL_K = 12, FILL_WM = 24;
+constexpr int FILL_K = 8, FILL_WM = 12;
 constexpr int RECHECK_WAVES = 4;
 constexpr uint32_t RECHECK_CHUNK = 16;                    // listed words per wave per round (few, so that many waves share the work)
 using FillStore = LdsStore<FILL_K, FILL_WM>;
@@ -344,8 +351,9 @@ __global__ __launch_bounds__(64 * RECHECK_WAVES) void k_recheck(FillBatch F, Dev
                     const FillRow r = F.rows[b];
                     const uint32_t off = Vd.off[rank];
                     const int n = (int)(Vd.off[rank + 1] - off);
-                    st.sel = 0; st.ws_lo = 0; st.ws_hi = 0;
-                    int res = scan_token(F.tables[r.tables_idx], row_ctx(F, r), Vd.bytes + off, n, st);
+                    st.reset();
+                    const DevTables T = F.tables[r.tables_idx];
+                    int res = scan_token(T, T.byte_class_words, row_ctx(F, r), Vd.bytes + off, n, st);
                     if (res & RES_OVERFLOW) push_overflow(S, b, id);
                     else if (res & RES_ALIVE) atomicOr(reinterpret_cast<uint32_t*>(bitmask) + (long long)b * row_stride + w, 1u << bit);
                 }
@@ -368,8 +376,9 @@ __global__ __launch_bounds__(64) void k_recheck_slow(FillBatch F, DevVocab Vd, i
         if (rank >= Vd.n_sorted) continue;
         const uint32_t off = Vd.off[rank];
         const int n = (int)(Vd.off[rank + 1] - off);
-        st.sel = 0;
-        int res = scan_token(F.tables[r.tables_idx], row_ctx(F, r), Vd.bytes + off, n, st);
+        st.reset();
+        const DevTables T = F.tables[r.tables_idx];
+        int res = scan_token(T, T.byte_class_words, row_ctx(F, r), Vd.bytes + off, n, st);
         if (res & RES_OVERFLOW) { atomicOr(S.count + 1, 2u); continue; }
         if (res & RES_ALIVE) atomicOr(reinterpret_cast<uint32_t*>(bitmask) + (long long)b * row_stride + (id >> 5), 1u << (id & 31));
     }

@@ -2,6 +2,7 @@
 
 #include <algorithm>
 #include <map>
+#include <stdexcept>
 
 namespace xg2 {
 
@@ -24,6 +25,35 @@ FlatTables flatten(const Grammar& g) {
         }
     }
     t.root_start = (uint32_t)g.sid(g.root, 0);
+    for (const RefEdgeP& e : t.ref_edges) t.dev_ref_edges.push_back({e.rule, t.ref(e.tgt)});
+    for (const RuleInfo& ri : t.rule_info) t.dev_rule_info.push_back({t.ref(ri.start), ri.nullable});
+    // byte classes: refine by (class so far, target) state after state
+    const size_t n = t.state_info.size();
+    std::vector<uint32_t> cls(256, 0);
+    std::vector<int64_t> row(256);
+    for (size_t sid = 0; sid < n; ++sid) {
+        const StateInfo& si = t.state_info[sid];
+        if (!(si.counts & 0xFFFF)) continue;
+        std::fill(row.begin(), row.end(), -1);
+        for (uint32_t k = 0; k < (si.counts & 0xFFFF); ++k) {
+            const ByteEdge& e = t.byte_edges[si.byte_off + k];
+            for (uint32_t b = e.lohi & 0xFF; b <= ((e.lohi >> 8) & 0xFF); ++b) row[b] = e.tgt;
+        }
+        std::map<std::pair<uint32_t, int64_t>, uint32_t> remap;
+        for (int b = 0; b < 256; ++b) cls[(size_t)b] = remap.emplace(std::make_pair(cls[(size_t)b], row[(size_t)b]), (uint32_t)remap.size()).first->second;
+    }
+    t.n_classes = *std::max_element(cls.begin(), cls.end()) + 1;
+    if (t.n_classes > 256) throw std::logic_error("more byte classes than bytes");
+    t.byte_class_words.assign(64, 0);
+    for (int b = 0; b < 256; ++b) t.byte_class_words[(size_t)b >> 2] |= cls[(size_t)b] << ((b & 3) * 8);
+    t.trans.assign(n * t.n_classes, kNoTarget);
+    for (size_t sid = 0; sid < n; ++sid) {
+        const StateInfo& si = t.state_info[sid];
+        for (uint32_t k = 0; k < (si.counts & 0xFFFF); ++k) {
+            const ByteEdge& e = t.byte_edges[si.byte_off + k];
+            for (uint32_t b = e.lohi & 0xFF; b <= ((e.lohi >> 8) & 0xFF); ++b) t.trans[sid * t.n_classes + cls[b]] = t.ref(e.tgt);
+        }
+    }
     return t;
 }
 
@@ -122,10 +152,10 @@ bool EarleyChart::context(ScanContext& out) const {
     for (size_t k = 0; k < needed.size(); ++k) local[needed[k]] = (uint32_t)k;
     out.H = (uint32_t)needed.size();
     auto loc = [&](int32_t o) { return o < 0 ? kRootOrigin : local.at(o); };
-    for (const ChartItem& it : chart_[(size_t)J].scan) out.items.push_back(pack_item(it.sid, loc(it.origin)));
+    for (const ChartItem& it : chart_[(size_t)J].scan) out.items.push_back(pack_item(t_->ref(it.sid), loc(it.origin)));
     for (size_t k = 0; k < needed.size(); ++k) {
         out.wait_off.push_back((uint32_t)out.wait.size());
-        for (const ChartItem& w : chart_[(size_t)needed[k]].wait) out.wait.push_back(pack_item(w.sid, loc(w.origin)));
+        for (const ChartItem& w : chart_[(size_t)needed[k]].wait) out.wait.push_back(pack_item(t_->ref(w.sid), loc(w.origin)));
     }
     out.wait_off.push_back((uint32_t)out.wait.size());
     return true;

@@ -10,13 +10,17 @@
 
 namespace xg2 {
 
-// An Earley item in 32 bits: global state id | origin << 21.  The origin is the index of the item
-// set in which the rule instance started, or kRootOrigin for the instance nobody is waiting for.
-constexpr uint32_t kSidBits = 21;
+// A state reference in 21 bits: global state id (18 bits) | has-byte-edge << 18 | has-rule-edge << 19 |
+// final << 20, so that a kernel knows what to do with a state without loading anything.
+// An Earley item in 32 bits: state reference | origin << 21.  The origin is the index of the item set in
+// which the rule instance started, or kRootOrigin for the instance nobody is waiting for.
+constexpr uint32_t kSidBits = 18;
 constexpr uint32_t kSidMask = (1u << kSidBits) - 1;
-constexpr uint32_t kRootOrigin = (1u << (32 - kSidBits)) - 1;     // 2047
+constexpr uint32_t kRefBits = 21;
+constexpr uint32_t kHasByte = 1u << 18, kHasRef = 1u << 19, kFinal = 1u << 20;
+constexpr uint32_t kRootOrigin = (1u << (32 - kRefBits)) - 1;     // 2047
 constexpr uint32_t kMaxLocalSets = kRootOrigin - 1;
-inline uint32_t pack_item(uint32_t sid, uint32_t origin) { return sid | (origin << kSidBits); }
+inline uint32_t pack_item(uint32_t state_ref, uint32_t origin) { return state_ref | (origin << kRefBits); }
 
 struct StateInfo { uint32_t byte_off, ref_off, counts /* n_byte | n_ref << 16 */, rule_final /* rule | final << 31 */; };
 struct ByteEdge { uint32_t lohi /* lo | hi << 8 */, tgt; };
@@ -29,7 +33,20 @@ struct FlatTables {
     std::vector<RefEdgeP> ref_edges;
     std::vector<RuleInfo> rule_info;
     uint32_t root_start = 0;
+    // device-side forms: every stored state is a state reference (id | flags)
+    std::vector<RefEdgeP> dev_ref_edges;
+    std::vector<RuleInfo> dev_rule_info;
+    // dense byte transitions: bytes that lead to the same state from every state form one class;
+    // trans[sid * n_classes + class] = state reference of the target or kNoTarget
+    std::vector<uint32_t> byte_class_words;      // 64 words: class of byte b = byte (b & 3) of word b >> 2
+    uint32_t n_classes = 0;
+    std::vector<uint32_t> trans;
+    uint32_t ref(uint32_t sid) const {
+        const StateInfo& si = state_info[sid];
+        return sid | ((si.counts & 0xFFFF) ? kHasByte : 0u) | ((si.counts >> 16) ? kHasRef : 0u) | ((si.rule_final >> 31) ? kFinal : 0u);
+    }
 };
+constexpr uint32_t kNoTarget = 0xFFFFFFFFu;
 
 FlatTables flatten(const Grammar& g);
 
