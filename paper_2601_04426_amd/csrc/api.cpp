@@ -102,7 +102,7 @@ struct VocabImpl {
     // device copy (made at first use)
     std::mutex mu;
     bool on_device = false;
-    DevBuf<uint8_t> d_bytes; DevBuf<uint32_t> d_off, d_perm, d_rank;
+    DevBuf<uint8_t> d_bytes; DevBuf<uint32_t> d_off, d_perm, d_rank; DevBuf<uint4> d_tok16;
     DevVocab dv{};
 
     const uint8_t* tok(int32_t id) const { return bytes.data() + offs[(size_t)id]; }
@@ -118,7 +118,12 @@ struct VocabImpl {
         d_off.upload(s_off, nullptr);
         d_perm.upload(perm, nullptr);
         d_rank.upload(rank, nullptr);
+        std::vector<uint4> tok16(n_sorted, make_uint4(0, 0, 0, 0));
+        for (uint32_t r = 0; r < n_sorted; ++r)
+            std::memcpy(&tok16[r], s_bytes.data() + s_off[r], std::min<size_t>(16, s_off[r + 1] - s_off[r]));
+        d_tok16.upload(tok16, nullptr);
         HIP_CHECK(hipStreamSynchronize(nullptr));
+        dv.tok16 = d_tok16.p;
         dv.bytes = d_bytes.p; dv.off = d_off.p; dv.perm = d_perm.p; dv.rank = d_rank.p;
         dv.n_sorted = n_sorted; dv.V = (uint32_t)V; dv.W = W;
         on_device = true;
@@ -528,7 +533,8 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
 
         // plan: closed start set and live first-byte ranges of every plane to build
         auto t1 = std::chrono::steady_clock::now();
-        std::vector<uint32_t> seg_pos, seg_lo, seg_hi, seg_blk{0}, ctx_items, ctx_item_off{0}, ctx_wait, ctx_wait_off, ctx_woff_start, ctx_H;
+        std::vector<uint32_t> ctx_items, ctx_wait, ctx_wait_off;
+        std::vector<uint4> chunks, plane_ctx;
         int64_t executed = 0;
         EarleyChart chart(&ft);
         for (size_t k = 0; k < build.size(); ++k) {
@@ -537,6 +543,7 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
             const std::vector<ChartSet>& sets = chart.sets();
             auto loc = [](int32_t o) { return o < 0 ? kRootOrigin : (uint32_t)o; };
             bool live[257] = {false};
+            const uint32_t item0 = (uint32_t)ctx_items.size();
             for (const ChartItem& it : sets.back().scan) {
                 ctx_items.push_back(pack_item(ft.ref(it.sid), loc(it.origin)));
                 const StateInfo& si = ft.state_info[it.sid];
@@ -545,9 +552,7 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
                     for (uint32_t b = be.lohi & 0xFF; b <= ((be.lohi >> 8) & 0xFF); ++b) live[b] = true;
                 }
             }
-            ctx_item_off.push_back((uint32_t)ctx_items.size());
-            ctx_woff_start.push_back((uint32_t)ctx_wait_off.size());
-            ctx_H.push_back((uint32_t)sets.size());
+            plane_ctx.push_back(make_uint4(item0, (uint32_t)ctx_items.size() - item0, (uint32_t)ctx_wait_off.size(), (uint32_t)sets.size()));
             for (const ChartSet& cs : sets) {
                 ctx_wait_off.push_back((uint32_t)ctx_wait.size());
                 for (const ChartItem& it : cs.wait) ctx_wait.push_back(pack_item(ft.ref(it.sid), loc(it.origin)));
@@ -558,11 +563,8 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
                 int e = b;
                 while (live[e + 1]) ++e;
                 uint32_t lo = V.fb_start[b], hi = V.fb_start[e + 1];
-                if (hi > lo) {
-                    seg_pos.push_back((uint32_t)k); seg_lo.push_back(lo); seg_hi.push_back(hi);
-                    seg_blk.push_back(seg_blk.back() + (hi - lo + 63) / 64);
-                    executed += hi - lo;
-                }
+                for (uint32_t c = lo; c < hi; c += kBuildChunk) chunks.push_back(make_uint4((uint32_t)k, c, std::min(hi, c + kBuildChunk), 0));
+                executed += hi - lo;
                 b = e + 1;
             }
         }
@@ -572,10 +574,8 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
         const size_t o_state = tab.add(ft.state_info), o_redge = tab.add(ft.dev_ref_edges), o_rule = tab.add(ft.dev_rule_info),
                      o_soff = tab.add(site_off), o_stgt = tab.add(site_tgt), o_trans = tab.add(ft.trans),
                      o_cls = tab.add(ft.byte_class_words);
-        const size_t o_seg_pos = plan.add(seg_pos), o_seg_lo = plan.add(seg_lo), o_seg_hi = plan.add(seg_hi), o_seg_blk = plan.add(seg_blk),
-                     o_items = plan.add(ctx_items), o_item_off = plan.add(ctx_item_off), o_wait = plan.add(ctx_wait),
-                     o_wait_off = plan.add(ctx_wait_off), o_woff_start = plan.add(ctx_woff_start), o_H = plan.add(ctx_H),
-                     o_rows = plan.add(build_rows);
+        const size_t o_chunks = plan.add(chunks), o_pctx = plan.add(plane_ctx), o_items = plan.add(ctx_items), o_wait = plan.add(ctx_wait),
+                     o_wait_off = plan.add(ctx_wait_off), o_rows = plan.add(build_rows);
         tab.stage();
         plan.stage();
         DevBuf<unsigned long long> d_counts;
@@ -602,12 +602,10 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
         HIP_CHECK(hipMemsetAsync(d_counts.p, 0, 2 * sizeof(unsigned long long), stream));
         HIP_CHECK(hipMemsetAsync(S.count, 0, sizeof(uint32_t), stream));
         BuildPlan P{};
-        P.seg_pos = plan.at<const uint32_t>(o_seg_pos); P.seg_lo = plan.at<const uint32_t>(o_seg_lo);
-        P.seg_hi = plan.at<const uint32_t>(o_seg_hi); P.seg_blk = plan.at<const uint32_t>(o_seg_blk);
-        P.n_seg = (uint32_t)seg_pos.size(); P.n_blocks = seg_blk.back();
-        P.ctx_items = plan.at<const uint32_t>(o_items); P.ctx_item_off = plan.at<const uint32_t>(o_item_off);
+        P.chunk = plan.at<const uint4>(o_chunks); P.n_chunks = (uint32_t)chunks.size();
+        P.plane_ctx = plan.at<const uint4>(o_pctx);
+        P.ctx_items = plan.at<const uint32_t>(o_items);
         P.ctx_wait = plan.at<const uint32_t>(o_wait); P.ctx_wait_off = plan.at<const uint32_t>(o_wait_off);
-        P.ctx_woff_start = plan.at<const uint32_t>(o_woff_start); P.ctx_H = plan.at<const uint32_t>(o_H);
         P.plane_ptr = plan.at<uint32_t*>(o_rows);
         P.follow_filter = follow ? 1u : 0u;
         uint32_t* const* d_rows_p = plan.at<uint32_t*>(o_rows);

@@ -20,22 +20,24 @@ struct DevTables {                       // packed grammar tables (see tables.hp
 struct DevVocab {                        // byte-sorted vocabulary in HBM
     const uint8_t* bytes;                // concatenated token bytes in sorted order
     const uint32_t* off;                 // [n_sorted + 1]
+    const uint4* tok16;                  // [n_sorted] first 16 bytes of each token, zero padded: one coalesced load
+                                         // instead of sixteen byte loads for the tokens the LDS path handles
     const uint32_t* perm;                // sorted rank -> token id
     const uint32_t* rank;                // token id -> sorted rank, 0xFFFFFFFF for tokens never checked
     uint32_t n_sorted;                   // checkable tokens (non-special, non-empty)
     uint32_t V, W;
 };
 
-// Work plan of one cache build: segment s covers sorted ranks [seg_lo[s], seg_hi[s]) of position
-// seg_pos[s]; seg_blk[s] = number of 64-token blocks before it (seg_blk[n_seg] = total).
+// Work plan of one cache build.  Chunk c covers sorted ranks [chunk[c].y, chunk[c].z) of plane chunk[c].x
+// (at most kBuildChunk tokens, all with a first byte the plane's start set can read); one workgroup per
+// chunk.  plane_ctx[k] = {first item, number of items, first wait offset, H} describes the closed start
+// set of plane k as a scan context (H = 1: the position alone; H = 2: the position inside one level of
+// referencing rule).
+constexpr uint32_t kBuildChunk = 1024;
 struct BuildPlan {
-    const uint32_t* seg_pos; const uint32_t* seg_lo; const uint32_t* seg_hi; const uint32_t* seg_blk;
-    uint32_t n_seg, n_blocks;
-    // closed start set of every plane to build, as a scan context (H = 1: the position alone; H = 2: the
-    // position inside one level of referencing rule)
-    const uint32_t* ctx_items; const uint32_t* ctx_item_off;   // [n_planes + 1]
-    const uint32_t* ctx_wait; const uint32_t* ctx_wait_off;    // per plane H + 1 offsets into ctx_wait ...
-    const uint32_t* ctx_woff_start; const uint32_t* ctx_H;     // ... starting at ctx_woff_start[k]; ctx_H[k] = H
+    const uint4* chunk; uint32_t n_chunks;
+    const uint4* plane_ctx;                                     // [n_planes]
+    const uint32_t* ctx_items; const uint32_t* ctx_wait; const uint32_t* ctx_wait_off;
     uint32_t* const* plane_ptr;                                 // [n_planes] accepted row; uncertain row at + W words
     uint32_t follow_filter;                                     // drop uncertain tokens that no reference site can continue
 };

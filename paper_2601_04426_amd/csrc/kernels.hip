@@ -26,25 +26,44 @@ struct DevCtx {                      // closed item set to continue from, plus r
     const uint32_t* wait; const uint32_t* wait_off; uint32_t H;
 };
 
+// ---- token bytes, consumed front to back: in registers (at most 16) or in device memory ----------------
+struct RegBytes {
+    uint4 v;                                                    // a 128-bit shift register: no indexed access, no spill
+    __device__ uint32_t next() {
+        const uint32_t b = v.x & 0xFF;
+        v.x = __builtin_amdgcn_alignbit(v.y, v.x, 8);
+        v.y = __builtin_amdgcn_alignbit(v.z, v.y, 8);
+        v.z = __builtin_amdgcn_alignbit(v.w, v.z, 8);
+        v.w >>= 8;
+        return b;
+    }
+};
+struct MemBytes {
+    const uint8_t* p;
+    __device__ uint32_t next() { return *p++; }
+};
+
 // ---- per-lane item storage -------------------------------------------------------------------------
 // LDS: word (slot, lane) lives at slot * 64 + lane, so a wave touching one slot per lane hits every
 // bank once per 32 lanes whatever the slots are.
 template <int K_, int WM_>
 struct LdsStore {
     static constexpr int K = K_, WM = WM_, MAXLEN = 16, SLOTS = 2 * K_ + WM_;
-    uint32_t* base;                  // &lds[wave_region + lane]
-    uint32_t sel = 0;
-    unsigned long long ws_lo = 0, ws_hi = 0;      // wait-list length at the start of each new set, 8 bits each
-    __device__ uint32_t get_cur(int k) const { return base[(sel * K + k) * 64]; }
-    __device__ void set_cur(int k, uint32_t v) { base[(sel * K + k) * 64] = v; }
-    __device__ uint32_t get_nxt(int k) const { return base[((sel ^ 1) * K + k) * 64]; }
-    __device__ void set_nxt(int k, uint32_t v) { base[((sel ^ 1) * K + k) * 64] = v; }
-    __device__ uint32_t get_wait(int k) const { return base[(2 * K + k) * 64]; }
-    __device__ void set_wait(int k, uint32_t v) { base[(2 * K + k) * 64] = v; }
-    __device__ void swap() { sel ^= 1; }
-    __device__ void reset() { sel = 0; ws_lo = 0; ws_hi = 0; }
+    uint32_t* cur; uint32_t* nxt; uint32_t* wait;  // this lane's column of the two item lists and the wait list
+    unsigned long long ws_lo = 0, ws_hi = 0;        // wait-list length at the start of each new set, 8 bits each
+    __device__ void init(uint32_t* base) { cur = base; nxt = base + K * 64; wait = base + 2 * K * 64; }
+    __device__ uint32_t get_cur(int k) const { return cur[k * 64]; }
+    __device__ void set_cur(int k, uint32_t v) { cur[k * 64] = v; }
+    __device__ uint32_t get_nxt(int k) const { return nxt[k * 64]; }
+    __device__ void set_nxt(int k, uint32_t v) { nxt[k * 64] = v; }
+    __device__ uint32_t get_wait(int k) const { return wait[k * 64]; }
+    __device__ void set_wait(int k, uint32_t v) { wait[k * 64] = v; }
+    __device__ void swap() { uint32_t* t = cur; cur = nxt; nxt = t; }
+    __device__ void reset() { ws_lo = 0; ws_hi = 0; }
     __device__ void set_wstart(int j, uint32_t v) {
-        if (j < 8) ws_lo |= (unsigned long long)v << (8 * j); else ws_hi |= (unsigned long long)v << (8 * (j - 8));
+        const int sh = 8 * (j & 7);
+        unsigned long long& w = j < 8 ? ws_lo : ws_hi;
+        w = (w & ~(0xFFull << sh)) | ((unsigned long long)v << sh);
     }
     __device__ uint32_t get_wstart(int j) const {
         return (uint32_t)((j < 8 ? ws_lo >> (8 * j) : ws_hi >> (8 * (j - 8))) & 0xFF);
@@ -54,18 +73,20 @@ struct LdsStore {
 // Device memory: word (slot, lane) lives at slot * n_lanes + lane (coalesced across lanes).
 struct GlobalStore {
     static constexpr int K = kSlowK, WM = kSlowWM, MAXLEN = kSlowMaxLen;
-    uint32_t* base; size_t stride;
-    uint32_t sel = 0;
-    __device__ uint32_t get_cur(int k) const { return base[(size_t)(sel * K + k) * stride]; }
-    __device__ void set_cur(int k, uint32_t v) { base[(size_t)(sel * K + k) * stride] = v; }
-    __device__ uint32_t get_nxt(int k) const { return base[(size_t)((sel ^ 1) * K + k) * stride]; }
-    __device__ void set_nxt(int k, uint32_t v) { base[(size_t)((sel ^ 1) * K + k) * stride] = v; }
-    __device__ uint32_t get_wait(int k) const { return base[(size_t)(2 * K + k) * stride]; }
-    __device__ void set_wait(int k, uint32_t v) { base[(size_t)(2 * K + k) * stride] = v; }
-    __device__ void swap() { sel ^= 1; }
-    __device__ void reset() { sel = 0; }
-    __device__ void set_wstart(int j, uint32_t v) { base[(size_t)(2 * K + WM + j) * stride] = v; }
-    __device__ uint32_t get_wstart(int j) const { return base[(size_t)(2 * K + WM + j) * stride]; }
+    uint32_t* cur; uint32_t* nxt; uint32_t* wait; uint32_t* ws; size_t stride;
+    __device__ void init(uint32_t* base, size_t n_lanes) {
+        stride = n_lanes; cur = base; nxt = base + (size_t)K * stride; wait = base + (size_t)2 * K * stride; ws = base + (size_t)(2 * K + WM) * stride;
+    }
+    __device__ uint32_t get_cur(int k) const { return cur[(size_t)k * stride]; }
+    __device__ void set_cur(int k, uint32_t v) { cur[(size_t)k * stride] = v; }
+    __device__ uint32_t get_nxt(int k) const { return nxt[(size_t)k * stride]; }
+    __device__ void set_nxt(int k, uint32_t v) { nxt[(size_t)k * stride] = v; }
+    __device__ uint32_t get_wait(int k) const { return wait[(size_t)k * stride]; }
+    __device__ void set_wait(int k, uint32_t v) { wait[(size_t)k * stride] = v; }
+    __device__ void swap() { uint32_t* t = cur; cur = nxt; nxt = t; }
+    __device__ void reset() {}
+    __device__ void set_wstart(int j, uint32_t v) { ws[(size_t)j * stride] = v; }
+    __device__ uint32_t get_wstart(int j) const { return ws[(size_t)j * stride]; }
 };
 
 // Put item (state reference, origin) into the set under construction unless it is there.  Items whose state
@@ -94,30 +115,52 @@ __device__ __forceinline__ bool add_item(S& st, uint32_t ref, uint32_t origin, i
 // referencing the ended rule continues (anywhere in the grammar) goes on as a new root instance, i.e.
 // the rest of the token is matched against everything that can follow in some context.
 // cls_words: the byte -> class table (64 words), in LDS or device memory.
-template <class S, bool FOLLOW = false>
-__device__ int scan_token(const DevTables& T, const uint32_t* cls_words, const DevCtx& C, const uint8_t* tok, int n, S& st) {
+//
+// While the item set is a single item whose state has byte edges only (not final, no rule edge) the
+// recogniser is a plain automaton walk: the item stays in a register and a byte costs one table load.
+// The lists in `st` are used from the first state that predicts or completes, and left again when the
+// set shrinks back to one such item (older waiting items stay where they are).
+template <class S, bool FOLLOW = false, class BYTES = RegBytes>
+__device__ int scan_token(const DevTables& T, const uint32_t* cls_words, const DevCtx& C, BYTES tok, int n, S& st) {
     if (n > S::MAXLEN || (int)C.n_items > S::K) return RES_OVERFLOW;
     int nc = (int)C.n_items;
-    for (int k = 0; k < nc; ++k) st.set_cur(k, C.items[k]);
+    uint32_t one = nc == 1 ? C.items[0] : 0u;
+    bool single = nc == 1 && (one & (F_BYTE | F_REF | F_FINAL)) == F_BYTE;
+    if (!single) for (int k = 0; k < nc; ++k) st.set_cur(k, C.items[k]);
     int nw = 0;
     int res = 0;
-    uint32_t b_next = n > 0 ? tok[0] : 0;
-    for (int i = 0; i < n; ++i) {
-        const uint32_t b = b_next;
-        if (i + 1 < n) b_next = tok[i + 1];                     // in flight while this byte is processed
-        const uint32_t cls = (cls_words[b >> 2] >> ((b & 3) * 8)) & 0xFF;
-        const uint32_t set_idx = C.H + (uint32_t)i;
+    int i = 0;
+    for (;;) {
+        // ---- automaton walk: one item, in a register; a byte costs one table load ----------------
+        uint32_t pending = NO_TARGET;
+        while (single && i < n) {
+            const uint32_t b = tok.next();
+            const uint32_t cls = (cls_words[b >> 2] >> ((b & 3) * 8)) & 0xFF;
+            const uint32_t tgt = T.trans[(one & SID_MASK) * T.n_classes + cls];
+            if (tgt == NO_TARGET) return res;                    // dead
+            if (tgt & (F_REF | F_FINAL)) { pending = tgt; single = false; break; }   // this state predicts or completes
+            one = tgt | (one & ~((1u << REF_BITS) - 1));
+            ++i;
+        }
+        if (i >= n) break;
+        // ---- one general step for byte i ---------------------------------------------------------
+        st.set_wstart(i, (uint32_t)nw);
         int nn = 0;
         const int wbeg = nw;
-        st.set_wstart(i, (uint32_t)nw);
-        // scanner: one table word per scannable item
-        for (int k = 0; k < nc; ++k) {
-            const uint32_t it = st.get_cur(k);
-            if (!(it & F_BYTE)) continue;
-            const uint32_t tgt = T.trans[(it & SID_MASK) * T.n_classes + cls];
-            if (tgt != NO_TARGET && !add_item(st, tgt, it >> REF_BITS, nn, nw, wbeg)) return RES_OVERFLOW;
+        if (pending != NO_TARGET) {
+            if (!add_item(st, pending, one >> REF_BITS, nn, nw, wbeg)) return RES_OVERFLOW;
+        } else {
+            const uint32_t b = tok.next();
+            const uint32_t cls = (cls_words[b >> 2] >> ((b & 3) * 8)) & 0xFF;
+            for (int k = 0; k < nc; ++k) {                       // scanner: one table word per scannable item
+                const uint32_t it = st.get_cur(k);
+                if (!(it & F_BYTE)) continue;
+                const uint32_t tgt = T.trans[(it & SID_MASK) * T.n_classes + cls];
+                if (tgt != NO_TARGET && !add_item(st, tgt, it >> REF_BITS, nn, nw, wbeg)) return RES_OVERFLOW;
+            }
         }
         // predictor and completer over the growing lists
+        const uint32_t set_idx = C.H + (uint32_t)i;
         bool root_now = false;
         int pn = 0, pw = wbeg;
         while (pn < nn || pw < nw) {
@@ -164,12 +207,25 @@ __device__ int scan_token(const DevTables& T, const uint32_t* cls_words, const D
         if (root_now && i + 1 < n) res |= RES_EARLY;
         st.swap();
         nc = nn;
+        ++i;
+        if (i < n) st.set_wstart(i, (uint32_t)nw);             // sets made by the automaton walk add no waiting items
+        if (nc == 1) {                                           // back to the register walk?
+            one = st.get_cur(0);
+            single = (one & (F_BYTE | F_REF | F_FINAL)) == F_BYTE;
+        }
     }
     return res | RES_ALIVE;
 }
 
-constexpr int BUILD_K = 8, BUILD_WM = 12;
-constexpr int BUILD_WAVES = 4;
+#ifndef XG2_BUILD_K
+#define XG2_BUILD_K 6
+#define XG2_BUILD_WM 10
+#endif
+#ifndef XG2_BUILD_WAVES
+#define XG2_BUILD_WAVES 4
+#endif
+constexpr int BUILD_K = XG2_BUILD_K, BUILD_WM = XG2_BUILD_WM;   // item-list capacities of the LDS path (tuning knobs)
+constexpr int BUILD_WAVES = XG2_BUILD_WAVES;
 using BuildStore = LdsStore<BUILD_K, BUILD_WM>;
 
 __device__ __forceinline__ void push_overflow(const SlowScratch& S, uint32_t a, uint32_t b) {
@@ -179,12 +235,13 @@ __device__ __forceinline__ void push_overflow(const SlowScratch& S, uint32_t a, 
 }
 
 __device__ __forceinline__ DevCtx position_ctx(const BuildPlan& P, uint32_t p) {
+    const uint4 d = P.plane_ctx[p];
     DevCtx C;
-    C.items = P.ctx_items + P.ctx_item_off[p];
-    C.n_items = P.ctx_item_off[p + 1] - P.ctx_item_off[p];
+    C.items = P.ctx_items + d.x;
+    C.n_items = d.y;
     C.wait = P.ctx_wait;
-    C.wait_off = P.ctx_wait_off + P.ctx_woff_start[p];
-    C.H = P.ctx_H[p];
+    C.wait_off = P.ctx_wait_off + d.z;
+    C.H = d.w;
     return C;
 }
 
@@ -200,29 +257,27 @@ __global__ __launch_bounds__(64 * BUILD_WAVES) void k_build(DevTables T, DevVoca
     if (threadIdx.x < 64) cls_words[threadIdx.x] = T.byte_class_words[threadIdx.x];
     __syncthreads();
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const uint32_t blk = blockIdx.x * BUILD_WAVES + wave;
-    if (blk >= P.n_blocks) return;
-    // segment holding this block: last s with seg_blk[s] <= blk
-    uint32_t lo = 0, hi = P.n_seg;
-    while (hi - lo > 1) { uint32_t mid = (lo + hi) >> 1; if (P.seg_blk[mid] <= blk) lo = mid; else hi = mid; }
-    const uint32_t p = P.seg_pos[lo];
-    const uint32_t rank = P.seg_lo[lo] + (blk - P.seg_blk[lo]) * 64 + lane;
-    if (rank >= P.seg_hi[lo]) return;
-    const uint32_t off = Vd.off[rank];
-    const int n = (int)(Vd.off[rank + 1] - off);
+    const uint4 chunk = P.chunk[blockIdx.x];                    // one descriptor per workgroup
+    const uint32_t p = chunk.x;
+    const DevCtx C = position_ctx(P, p);
     BuildStore st;
-    st.base = lds + wave * BuildStore::SLOTS * 64 + lane;
-    DevCtx C = position_ctx(P, p);
-    int res = scan_token(T, cls_words, C, Vd.bytes + off, n, st);
-    if (P.follow_filter && !(res & (RES_ALIVE | RES_OVERFLOW)) && (res & RES_EARLY)) {
-        // leaves the rule early: keep it uncertain only if some context can take the rest of the token
+    st.init(lds + wave * BuildStore::SLOTS * 64 + lane);
+    for (uint32_t rank = chunk.y + wave * 64 + lane; rank < chunk.z; rank += 64 * BUILD_WAVES) {
+        const int n = (int)(Vd.off[rank + 1] - Vd.off[rank]);
+        RegBytes tok;
+        tok.v = Vd.tok16[rank];
         st.reset();
-        int res2 = scan_token<BuildStore, true>(T, cls_words, C, Vd.bytes + off, n, st);
-        if (res2 & RES_OVERFLOW) res = RES_OVERFLOW;
-        else if (!(res2 & RES_ALIVE)) res = 0;
+        int res = scan_token(T, cls_words, C, tok, n, st);
+        if (P.follow_filter && !(res & (RES_ALIVE | RES_OVERFLOW)) && (res & RES_EARLY)) {
+            // leaves the rule early: keep it uncertain only if some context can take the rest of the token
+            st.reset();
+            int res2 = scan_token<BuildStore, true>(T, cls_words, C, tok, n, st);
+            if (res2 & RES_OVERFLOW) res = RES_OVERFLOW;
+            else if (!(res2 & RES_ALIVE)) res = 0;
+        }
+        if (res & RES_OVERFLOW) push_overflow(S, p, rank);
+        else store_class(P, p, Vd.W, Vd.perm[rank], res);
     }
-    if (res & RES_OVERFLOW) { push_overflow(S, p, rank); return; }
-    store_class(P, p, Vd.W, Vd.perm[rank], res);
 }
 
 __global__ __launch_bounds__(64) void k_build_slow(DevTables T, DevVocab Vd, BuildPlan P, SlowScratch S) {
@@ -230,18 +285,18 @@ __global__ __launch_bounds__(64) void k_build_slow(DevTables T, DevVocab Vd, Bui
     uint32_t count = S.count[0];
     if (count > S.list_cap) count = S.list_cap;
     GlobalStore st;
-    st.base = S.mem + gl;
-    st.stride = S.n_lanes;
+    st.init(S.mem + gl, S.n_lanes);
     for (uint32_t idx = gl; idx < count; idx += S.n_lanes) {
         const uint32_t p = S.list[2 * idx], rank = S.list[2 * idx + 1];
         const uint32_t off = Vd.off[rank];
         const int n = (int)(Vd.off[rank + 1] - off);
         st.reset();
         DevCtx C = position_ctx(P, p);
-        int res = scan_token(T, T.byte_class_words, C, Vd.bytes + off, n, st);
+        MemBytes tok{Vd.bytes + off};
+        int res = scan_token<GlobalStore, false, MemBytes>(T, T.byte_class_words, C, tok, n, st);
         if (P.follow_filter && !(res & (RES_ALIVE | RES_OVERFLOW)) && (res & RES_EARLY)) {
             st.reset();
-            int res2 = scan_token<GlobalStore, true>(T, T.byte_class_words, C, Vd.bytes + off, n, st);
+            int res2 = scan_token<GlobalStore, true, MemBytes>(T, T.byte_class_words, C, tok, n, st);
             if (res2 & RES_OVERFLOW) res = RES_OVERFLOW;
             else if (!(res2 & RES_ALIVE)) res = 0;
         }
@@ -322,7 +377,7 @@ __global__ __launch_bounds__(64 * RECHECK_WAVES) void k_recheck(FillBatch F, Dev
     const uint32_t n_waves = gridDim.x * RECHECK_WAVES;
     const uint32_t count = *F.work_count;
     FillStore st;
-    st.base = lds_store + wave * FillStore::SLOTS * 64 + lane;
+    st.init(lds_store + wave * FillStore::SLOTS * 64 + lane);
     for (uint32_t base = (blockIdx.x * RECHECK_WAVES + wave) * RECHECK_CHUNK; base < count; base += n_waves * RECHECK_CHUNK) {
         // RECHECK_CHUNK listed words, one per lane; inclusive prefix sum of their candidate counts
         uint32_t idx = 0, cand = 0;
@@ -349,11 +404,12 @@ __global__ __launch_bounds__(64 * RECHECK_WAVES) void k_recheck(FillBatch F, Dev
                 const uint32_t rank = Vd.rank[id];
                 if (rank < Vd.n_sorted) {
                     const FillRow r = F.rows[b];
-                    const uint32_t off = Vd.off[rank];
-                    const int n = (int)(Vd.off[rank + 1] - off);
+                    const int n = (int)(Vd.off[rank + 1] - Vd.off[rank]);
+                    RegBytes tok;
+                    tok.v = Vd.tok16[rank];
                     st.reset();
                     const DevTables T = F.tables[r.tables_idx];
-                    int res = scan_token(T, T.byte_class_words, row_ctx(F, r), Vd.bytes + off, n, st);
+                    int res = scan_token(T, T.byte_class_words, row_ctx(F, r), tok, n, st);
                     if (res & RES_OVERFLOW) push_overflow(S, b, id);
                     else if (res & RES_ALIVE) atomicOr(reinterpret_cast<uint32_t*>(bitmask) + (long long)b * row_stride + w, 1u << bit);
                 }
@@ -367,8 +423,7 @@ __global__ __launch_bounds__(64) void k_recheck_slow(FillBatch F, DevVocab Vd, i
     uint32_t count = S.count[0];
     if (count > S.list_cap) count = S.list_cap;
     GlobalStore st;
-    st.base = S.mem + gl;
-    st.stride = S.n_lanes;
+    st.init(S.mem + gl, S.n_lanes);
     for (uint32_t idx = gl; idx < count; idx += S.n_lanes) {
         const uint32_t b = S.list[2 * idx], id = S.list[2 * idx + 1];
         const FillRow r = F.rows[b];
@@ -378,7 +433,8 @@ __global__ __launch_bounds__(64) void k_recheck_slow(FillBatch F, DevVocab Vd, i
         const int n = (int)(Vd.off[rank + 1] - off);
         st.reset();
         const DevTables T = F.tables[r.tables_idx];
-        int res = scan_token(T, T.byte_class_words, row_ctx(F, r), Vd.bytes + off, n, st);
+        MemBytes tok{Vd.bytes + off};
+        int res = scan_token<GlobalStore, false, MemBytes>(T, T.byte_class_words, row_ctx(F, r), tok, n, st);
         if (res & RES_OVERFLOW) { atomicOr(S.count + 1, 2u); continue; }
         if (res & RES_ALIVE) atomicOr(reinterpret_cast<uint32_t*>(bitmask) + (long long)b * row_stride + (id >> 5), 1u << (id & 31));
     }
@@ -445,9 +501,8 @@ __global__ __launch_bounds__(256) void k_apply_scalar(E* logits, long long row_s
 }  // namespace
 
 void launch_build(const DevTables& T, const DevVocab& Vd, const BuildPlan& P, const SlowScratch& S, hipStream_t stream) {
-    if (P.n_blocks == 0) return;
-    uint32_t grid = (P.n_blocks + BUILD_WAVES - 1) / BUILD_WAVES;
-    hipLaunchKernelGGL(k_build, dim3(grid), dim3(64 * BUILD_WAVES), 0, stream, T, Vd, P, S);
+    if (P.n_chunks == 0) return;
+    hipLaunchKernelGGL(k_build, dim3(P.n_chunks), dim3(64 * BUILD_WAVES), 0, stream, T, Vd, P, S);
 }
 
 void launch_build_slow(const DevTables& T, const DevVocab& Vd, const BuildPlan& P, const SlowScratch& S, hipStream_t stream) {
