@@ -13,6 +13,7 @@
 #include <numeric>
 #include <string>
 #include <unordered_map>
+#include <unordered_set>
 #include <vector>
 
 #include <hip/hip_runtime.h>
@@ -169,6 +170,7 @@ struct PoolImpl {
     std::vector<Entry> entries;
     std::unordered_multimap<uint64_t, int> by_hash;
     std::map<PlaneKey, uint32_t*> rows;
+    std::unordered_set<const uint32_t*> no_uncertain;      // rows whose uncertain plane is all zero (need not be read)
     std::vector<void*> slabs;
     uint8_t* slab_cur = nullptr; size_t slab_left = 0;
     size_t device_bytes = 0;
@@ -206,7 +208,7 @@ struct PoolImpl {
 };
 
 // ---- mask cache -----------------------------------------------------------------------------------------
-struct PlaneInfo { int32_t rule, state, parent_rule, parent_state; uint32_t* row; };   // the representative it was built for
+struct PlaneInfo { int32_t rule, state, parent_rule, parent_state; uint32_t* row; bool no_uncertain; };   // the representative it was built for
 struct CacheImpl {
     std::shared_ptr<VocabImpl> vocab;
     std::shared_ptr<PoolImpl> pool;
@@ -499,7 +501,7 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
                 build_keys.push_back(key);
             }
             int32_t idx = (int32_t)cache->planes.size();
-            cache->planes.push_back({rp, sp_rep, site ? site->q : -1, site ? site->x : -1, row});
+            cache->planes.push_back({rp, sp_rep, site ? site->q : -1, site ? site->x : -1, row, false});
             local_plane.emplace(key, idx);
             return idx;
         };
@@ -580,6 +582,8 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
         plan.stage();
         DevBuf<unsigned long long> d_counts;
         d_counts.alloc(2);
+        DevBuf<uint32_t> d_unc;
+        d_unc.alloc(std::max<size_t>(build_rows.size(), 1));
         double host_ms_b = ms_since(t1);
 
         hipEvent_t ev0, ev1, evk0, evk1;
@@ -600,6 +604,7 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
         cache->dt.site_off = tab.at<const uint32_t>(o_soff);
         cache->dt.site_tgt = tab.at<const uint32_t>(o_stgt);
         HIP_CHECK(hipMemsetAsync(d_counts.p, 0, 2 * sizeof(unsigned long long), stream));
+        HIP_CHECK(hipMemsetAsync(d_unc.p, 0, std::max<size_t>(build_rows.size(), 1) * sizeof(uint32_t), stream));
         HIP_CHECK(hipMemsetAsync(S.count, 0, sizeof(uint32_t), stream));
         BuildPlan P{};
         P.chunk = plan.at<const uint4>(o_chunks); P.n_chunks = (uint32_t)chunks.size();
@@ -614,13 +619,15 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
         HIP_CHECK(hipEventRecord(evk1, stream));
         if (!build.empty()) {
             launch_build_slow(cache->dt, V.dv, P, S, stream);
-            launch_popcount(d_rows_p, (uint32_t)build_rows.size(), V.W, d_counts.p, stream);
+            launch_popcount(d_rows_p, (uint32_t)build_rows.size(), V.W, d_counts.p, d_unc.p, stream);
         }
         HIP_CHECK(hipEventRecord(ev1, stream));
         uint32_t slow_counts[2] = {0, 0};
         unsigned long long bit_counts[2] = {0, 0};
         HIP_CHECK(hipMemcpyAsync(slow_counts, S.count, sizeof(slow_counts), hipMemcpyDeviceToHost, stream));
         HIP_CHECK(hipMemcpyAsync(bit_counts, d_counts.p, sizeof(bit_counts), hipMemcpyDeviceToHost, stream));
+        std::vector<uint32_t> unc_counts(build_rows.size(), 0);
+        if (!build_rows.empty()) HIP_CHECK(hipMemcpyAsync(unc_counts.data(), d_unc.p, build_rows.size() * sizeof(uint32_t), hipMemcpyDeviceToHost, stream));
         HIP_CHECK(hipStreamSynchronize(stream));
         HIP_CHECK(hipGetLastError());
         float dev_ms = 0.f, kern_ms = 0.f;
@@ -632,6 +639,8 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
             for (const PlaneKey& key : build_keys) pool.rows.erase(key);      // rows of this call hold partial results: forget them
             return fail(XG2_EOVERFLOW, "xg2_compile_grammar: Earley item sets exceeded the large-capacity limit");
         }
+        for (size_t k = 0; k < build_rows.size(); ++k) if (!unc_counts[k]) pool.no_uncertain.insert(build_rows[k]);
+        for (PlaneInfo& pi : cache->planes) pi.no_uncertain = pool.no_uncertain.count(pi.row) != 0;
         if (stats) {
             stats->positions = (int64_t)g.positions.size();
             stats->unique = (int64_t)cache->planes.size();
@@ -797,7 +806,8 @@ int32_t xg2_fill_next_token_bitmask(xg2_matcher* const* matchers, int32_t B, int
             if (!M.chart.context(ctx)) return fail(XG2_EOVERFLOW, "xg2_fill_next_token_bitmask: parser context too deep");
             size_t f0 = front.size();
             auto push_plane = [&](int32_t plane, bool accepted_only) {
-                uint64_t row = (uint64_t)(uintptr_t)M.cache->planes[(size_t)plane].row | (accepted_only ? 1u : 0u);
+                const PlaneInfo& pi = M.cache->planes[(size_t)plane];
+                uint64_t row = (uint64_t)(uintptr_t)pi.row | ((accepted_only || pi.no_uncertain) ? 1u : 0u);
                 if (std::find(front.begin() + (long)f0, front.end(), row) == front.end()) front.push_back(row);
             };
             const Grammar& G = M.gram->g;

@@ -52,7 +52,8 @@ constexpr uint32_t kSlowSlots = 2 * kSlowK + kSlowWM + kSlowMaxLen + 1;
 
 void launch_build(const DevTables& T, const DevVocab& Vd, const BuildPlan& P, const SlowScratch& S, hipStream_t stream);
 void launch_build_slow(const DevTables& T, const DevVocab& Vd, const BuildPlan& P, const SlowScratch& S, hipStream_t stream);
-void launch_popcount(const uint32_t* const* plane_ptr_dev, uint32_t n_pos, uint32_t W, unsigned long long* out2_dev, hipStream_t stream);
+void launch_popcount(const uint32_t* const* plane_ptr_dev, uint32_t n_pos, uint32_t W, unsigned long long* out2_dev,
+                     uint32_t* unc_out_dev, hipStream_t stream);
 
 // One row of a fill batch.
 struct FillRow {

@@ -305,14 +305,16 @@ __global__ __launch_bounds__(64) void k_build_slow(DevTables T, DevVocab Vd, Bui
     }
 }
 
-__global__ __launch_bounds__(256) void k_popcount(const uint32_t* const* plane_ptr, uint32_t n_pos, uint32_t W, unsigned long long* out2) {
+// Set bits of the freshly built planes: totals in out2[0..1], per-plane uncertain count in unc_out (zeroed before).
+__global__ __launch_bounds__(256) void k_popcount(const uint32_t* const* plane_ptr, uint32_t n_pos, uint32_t W, unsigned long long* out2,
+                                                  uint32_t* unc_out) {
     const uint32_t p = blockIdx.x;
     if (p >= n_pos) return;
     const uint32_t* row = plane_ptr[p];
     unsigned long long a = 0, u = 0;
     for (uint32_t w = threadIdx.x; w < W; w += blockDim.x) { a += __popc(row[w]); u += __popc(row[W + w]); }
     for (int s = 32; s > 0; s >>= 1) { a += __shfl_down(a, s); u += __shfl_down(u, s); }
-    if ((threadIdx.x & 63) == 0) { atomicAdd(out2, a); atomicAdd(out2 + 1, u); }
+    if ((threadIdx.x & 63) == 0) { atomicAdd(out2, a); atomicAdd(out2 + 1, u); if (u) atomicAdd(unc_out + p, (uint32_t)u); }
 }
 
 // ---- fill ------------------------------------------------------------------------------------------
@@ -509,9 +511,10 @@ void launch_build_slow(const DevTables& T, const DevVocab& Vd, const BuildPlan& 
     hipLaunchKernelGGL(k_build_slow, dim3(S.n_lanes / 64), dim3(64), 0, stream, T, Vd, P, S);
 }
 
-void launch_popcount(const uint32_t* const* plane_ptr_dev, uint32_t n_pos, uint32_t W, unsigned long long* out2_dev, hipStream_t stream) {
+void launch_popcount(const uint32_t* const* plane_ptr_dev, uint32_t n_pos, uint32_t W, unsigned long long* out2_dev,
+                     uint32_t* unc_out_dev, hipStream_t stream) {
     if (n_pos == 0) return;
-    hipLaunchKernelGGL(k_popcount, dim3(n_pos), dim3(256), 0, stream, plane_ptr_dev, n_pos, W, out2_dev);
+    hipLaunchKernelGGL(k_popcount, dim3(n_pos), dim3(256), 0, stream, plane_ptr_dev, n_pos, W, out2_dev, unc_out_dev);
 }
 
 void launch_fill(const FillBatch& F, const DevVocab& Vd, int32_t* bitmask_dev, int64_t row_stride_words,
