@@ -556,10 +556,10 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
             }
             plane_ctx.push_back(make_uint4(item0, (uint32_t)ctx_items.size() - item0, (uint32_t)ctx_wait_off.size(), (uint32_t)sets.size()));
             for (const ChartSet& cs : sets) {
-                ctx_wait_off.push_back((uint32_t)ctx_wait.size());
-                for (const ChartItem& it : cs.wait) ctx_wait.push_back(pack_item(ft.ref(it.sid), loc(it.origin)));
+                ctx_wait_off.push_back((uint32_t)(ctx_wait.size() / 2));
+                for (const ChartItem& it : cs.wait) chart.push_triples(it, loc(it.origin), ctx_wait);
             }
-            ctx_wait_off.push_back((uint32_t)ctx_wait.size());
+            ctx_wait_off.push_back((uint32_t)(ctx_wait.size() / 2));
             for (int b = 0; b < 256;) {
                 if (!live[b]) { ++b; continue; }
                 int e = b;
@@ -573,7 +573,7 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
 
         // everything the device needs goes up in two copies: the tables (kept with the cache) and the plan
         Packer tab, plan;
-        const size_t o_state = tab.add(ft.state_info), o_redge = tab.add(ft.dev_ref_edges), o_rule = tab.add(ft.dev_rule_info),
+        const size_t o_state = tab.add(ft.dev_state), o_exp = tab.add(ft.exp_list),
                      o_soff = tab.add(site_off), o_stgt = tab.add(site_tgt), o_trans = tab.add(ft.trans),
                      o_cls = tab.add(ft.byte_class_words);
         const size_t o_chunks = plan.add(chunks), o_pctx = plan.add(plane_ctx), o_items = plan.add(ctx_items), o_wait = plan.add(ctx_wait),
@@ -595,12 +595,11 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
         tab.copy(stream);
         plan.copy(stream);
         cache->d_tables = tab.release_dev();
-        cache->dt.state_info = tab.at<const uint4>(o_state);
+        cache->dt.state = tab.at<const uint4>(o_state);
+        cache->dt.exp_list = tab.at<const uint32_t>(o_exp);
         cache->dt.trans = tab.at<const uint32_t>(o_trans);
         cache->dt.byte_class_words = tab.at<const uint32_t>(o_cls);
         cache->dt.n_classes = ft.n_classes;
-        cache->dt.ref_edges = tab.at<const uint2>(o_redge);
-        cache->dt.rule_info = tab.at<const uint2>(o_rule);
         cache->dt.site_off = tab.at<const uint32_t>(o_soff);
         cache->dt.site_tgt = tab.at<const uint32_t>(o_stgt);
         HIP_CHECK(hipMemsetAsync(d_counts.p, 0, 2 * sizeof(unsigned long long), stream));
@@ -610,7 +609,7 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
         P.chunk = plan.at<const uint4>(o_chunks); P.n_chunks = (uint32_t)chunks.size();
         P.plane_ctx = plan.at<const uint4>(o_pctx);
         P.ctx_items = plan.at<const uint32_t>(o_items);
-        P.ctx_wait = plan.at<const uint32_t>(o_wait); P.ctx_wait_off = plan.at<const uint32_t>(o_wait_off);
+        P.ctx_wait = plan.at<const uint2>(o_wait); P.ctx_wait_off = plan.at<const uint32_t>(o_wait_off);
         P.plane_ptr = plan.at<uint32_t*>(o_rows);
         P.follow_filter = follow ? 1u : 0u;
         uint32_t* const* d_rows_p = plan.at<uint32_t*>(o_rows);
@@ -799,7 +798,7 @@ int32_t xg2_fill_next_token_bitmask(xg2_matcher* const* matchers, int32_t B, int
             r.tables_idx = ti->second;
             r.front_off = (uint32_t)front.size();
             r.item_off = (uint32_t)items.size();
-            r.wait_base = (uint32_t)wait.size();
+            r.wait_base = (uint32_t)(wait.size() / 2);
             r.waitoff_off = (uint32_t)wait_off.size();
             if (M.terminated) { r.flags = 2; continue; }
             r.flags = M.chart.last().root_done ? 1u : 0u;
@@ -872,7 +871,7 @@ int32_t xg2_fill_next_token_bitmask(xg2_matcher* const* matchers, int32_t B, int
         F.rows = reinterpret_cast<const FillRow*>(slot.dev + o_rows); F.B = (uint32_t)B;
         F.front_planes = reinterpret_cast<const uint64_t*>(slot.dev + o_front);
         F.ctx_items = reinterpret_cast<const uint32_t*>(slot.dev + o_items);
-        F.ctx_wait = reinterpret_cast<const uint32_t*>(slot.dev + o_wait);
+        F.ctx_wait = reinterpret_cast<const uint2*>(slot.dev + o_wait);
         F.ctx_wait_off = reinterpret_cast<const uint32_t*>(slot.dev + o_woff);
         F.tables = reinterpret_cast<const DevTables*>(slot.dev + o_tabs);
         F.eos_id = (uint32_t)V.eos;

@@ -7,9 +7,9 @@
 namespace xg2 {
 
 struct DevTables {                       // packed grammar tables (see tables.hpp for the word layout)
-    const uint4* state_info;             // loaded only for states with rule edges or final states
-    const uint2* ref_edges;              // {rule, state reference of the target}
-    const uint2* rule_info;              // {state reference of the start state, nullable}
+    const uint4* state;                  // {rule, expansion offset, n_items, n_triples}: loaded only for states with
+                                         // rule edges (what entering them adds) and for completing items (their rule)
+    const uint32_t* exp_list;            // expansions: item words, then {rule, target} pairs
     const uint32_t* trans;               // [n_states * n_classes] state reference of the byte target or 0xFFFFFFFF
     const uint32_t* byte_class_words;    // [64] byte -> class, four per word
     uint32_t n_classes;
@@ -32,12 +32,13 @@ struct DevVocab {                        // byte-sorted vocabulary in HBM
 // (at most kBuildChunk tokens, all with a first byte the plane's start set can read); one workgroup per
 // chunk.  plane_ctx[k] = {first item, number of items, first wait offset, H} describes the closed start
 // set of plane k as a scan context (H = 1: the position alone; H = 2: the position inside one level of
-// referencing rule).
+// referencing rule).  ctx_wait holds, set after set, what the waiting items wait for as pairs
+// {rule, state reference of the target | origin << 21}; ctx_wait_off counts pairs.
 constexpr uint32_t kBuildChunk = 1024;
 struct BuildPlan {
     const uint4* chunk; uint32_t n_chunks;
     const uint4* plane_ctx;                                     // [n_planes]
-    const uint32_t* ctx_items; const uint32_t* ctx_wait; const uint32_t* ctx_wait_off;
+    const uint32_t* ctx_items; const uint2* ctx_wait; const uint32_t* ctx_wait_off;
     uint32_t* const* plane_ptr;                                 // [n_planes] accepted row; uncertain row at + W words
     uint32_t follow_filter;                                     // drop uncertain tokens that no reference site can continue
 };
@@ -48,7 +49,7 @@ struct SlowScratch {                     // large-capacity per-lane Earley scrat
     uint32_t* count;                     // [0] = entries in list, [1] = sticky error flag
 };
 constexpr uint32_t kSlowK = 256, kSlowWM = 1024, kSlowMaxLen = 1024;
-constexpr uint32_t kSlowSlots = 2 * kSlowK + kSlowWM + kSlowMaxLen + 1;
+constexpr uint32_t kSlowSlots = 2 * kSlowK + 2 * kSlowWM + kSlowMaxLen + 1;
 
 void launch_build(const DevTables& T, const DevVocab& Vd, const BuildPlan& P, const SlowScratch& S, hipStream_t stream);
 void launch_build_slow(const DevTables& T, const DevVocab& Vd, const BuildPlan& P, const SlowScratch& S, hipStream_t stream);
@@ -59,7 +60,7 @@ void launch_popcount(const uint32_t* const* plane_ptr_dev, uint32_t n_pos, uint3
 struct FillRow {
     uint32_t front_off, front_n;         // into front_planes
     uint32_t item_off, item_n;           // into ctx_items
-    uint32_t wait_base;                  // into ctx_wait
+    uint32_t wait_base;                  // into ctx_wait (pairs)
     uint32_t waitoff_off, H;             // into ctx_wait_off ([H + 1] entries, relative to wait_base)
     uint32_t tables_idx;                 // into tables
     uint32_t flags;                      // bit 0: root can end, bit 1: terminated
@@ -69,7 +70,7 @@ struct FillBatch {
     const FillRow* rows; uint32_t B;
     const uint64_t* front_planes;        // device addresses of accepted rows (uncertain at + W words);
                                          // bit 0 set: only the accepted row counts (root instance)
-    const uint32_t* ctx_items; const uint32_t* ctx_wait; const uint32_t* ctx_wait_off;
+    const uint32_t* ctx_items; const uint2* ctx_wait; const uint32_t* ctx_wait_off;
     const DevTables* tables;
     uint32_t eos_id;
     // re-check scratch: candidate bits of every mask word, indices of the non-zero ones, their count

@@ -1,0 +1,193 @@
+// The rule-scoped Earley recogniser the kernels run per lane (XGrammar-2 section 3.4 and the appendix on
+// Earley parsing: scanner, predictor, completer over the per-rule automata), written once so that the same
+// source also compiles for the host, where a test steps it against the host parser.  It only reads the
+// packed tables and the caller's per-lane item store; it allocates nothing and every loop is bounded by a
+// list capacity or by the token length.
+#pragma once
+#include "device.hpp"
+
+namespace xg2 {
+namespace core {
+
+#if defined(__HIP_DEVICE_COMPILE__)
+__device__ __forceinline__ uint32_t funnel_shift(uint32_t hi, uint32_t lo, uint32_t s) { return __builtin_amdgcn_alignbit(hi, lo, s); }
+#else
+__device__ __forceinline__ uint32_t funnel_shift(uint32_t hi, uint32_t lo, uint32_t s) { return (uint32_t)(((((unsigned long long)hi) << 32) | lo) >> s); }
+#endif
+
+// A state reference is 21 bits: state id (18) | has byte edge | has rule edge | final; an item is a state
+// reference with the origin (item-set index, 2047 = root instance) in the upper 11 bits.
+constexpr uint32_t SID_MASK = (1u << 18) - 1;
+constexpr uint32_t F_BYTE = 1u << 18, F_REF = 1u << 19, F_FINAL = 1u << 20;
+constexpr uint32_t REF_BITS = 21;
+constexpr uint32_t ROOT_ORIGIN = (1u << (32 - REF_BITS)) - 1;
+constexpr uint32_t NO_TARGET = 0xFFFFFFFFu;
+
+constexpr int RES_ALIVE = 1, RES_EARLY = 2, RES_OVERFLOW = 4;
+
+struct DevCtx {                      // closed item set to continue from, plus what older sets wait for
+    const uint32_t* items; uint32_t n_items;
+    const uint2* wait; const uint32_t* wait_off; uint32_t H;    // pairs {rule, target | origin << 21} per set
+};
+
+// ---- token bytes, consumed front to back: in registers (at most 16) or in device memory ----------------
+struct RegBytes {
+    uint4 v;                                                    // a 128-bit shift register: no indexed access, no spill
+    __device__ uint32_t next() {
+        const uint32_t b = v.x & 0xFF;
+        v.x = funnel_shift(v.y, v.x, 8);
+        v.y = funnel_shift(v.z, v.y, 8);
+        v.z = funnel_shift(v.w, v.z, 8);
+        v.w >>= 8;
+        return b;
+    }
+};
+struct MemBytes {
+    const uint8_t* p;
+    __device__ uint32_t next() { return *p++; }
+};
+
+// Entering state `ref` with origin `origin` while set `set_idx` is under construction.  The item itself goes
+// to `nxt` if its state can scan or complete (or has no edge at all); if it is there already nothing more
+// happens.  A state with rule edges brings its expansion: every item that prediction, and advancing over
+// rules that derive the empty string, add (already followed to the end on the host, so nothing added here
+// needs expanding again) and one wait entry {rule, target | origin} per rule edge involved.  The flags
+// travel with the state reference; memory is read only for expansions.  Returns false when a list is full.
+constexpr uint32_t REF_MASK = (1u << REF_BITS) - 1;
+constexpr uint32_t EXP_CURRENT = 1u << REF_BITS;
+
+template <class S>
+__device__ __forceinline__ bool add_nxt(S& st, uint32_t item, int& nn, bool& fresh) {
+    fresh = false;
+    for (int k = 0; k < nn; ++k) if (st.get_nxt(k) == item) return true;
+    if (nn == S::K) return false;
+    st.set_nxt(nn++, item);
+    fresh = true;
+    return true;
+}
+
+template <class S>
+__device__ __forceinline__ bool add_wait(S& st, uint32_t rule, uint32_t tgt, int& nw, int wbeg) {
+    for (int k = wbeg; k < nw; ++k) if (st.wait_tgt(k) == tgt && st.wait_rule(k) == rule) return true;
+    if (nw == S::WM) return false;
+    st.set_wait(nw++, rule, tgt);
+    return true;
+}
+
+template <class S>
+__device__ __forceinline__ bool enter(const DevTables& T, S& st, uint32_t ref, uint32_t origin, uint32_t set_idx, int& nn, int& nw, int wbeg) {
+    bool fresh;
+    if ((ref & (F_BYTE | F_FINAL)) || !(ref & F_REF)) {
+        if (!add_nxt(st, ref | (origin << REF_BITS), nn, fresh)) return false;
+        if (!fresh) return true;
+    }
+    if (ref & F_REF) {
+        const uint4 d = T.state[ref & SID_MASK];
+        const uint32_t* e = T.exp_list + d.y;
+        for (uint32_t k = 0; k < d.z; ++k) {
+            const uint32_t w = e[k];
+            if (!add_nxt(st, (w & REF_MASK) | (((w & EXP_CURRENT) ? set_idx : origin) << REF_BITS), nn, fresh)) return false;
+        }
+        e += d.z;
+        for (uint32_t k = 0; k < d.w; ++k) {
+            const uint32_t w = e[2 * k + 1];
+            if (!add_wait(st, e[2 * k], (w & REF_MASK) | (((w & EXP_CURRENT) ? set_idx : origin) << REF_BITS), nw, wbeg)) return false;
+        }
+    }
+    return true;
+}
+
+// Earley recognition of the n bytes at tok, continuing from context C.  New item sets are numbered
+// C.H, C.H + 1, ...  Returns RES_ALIVE if the set after the last byte is non-empty, RES_EARLY if the
+// root instance could end after some proper non-empty prefix, RES_OVERFLOW if a list filled up.
+// With FOLLOW, the end of the root instance is not the end of the parse: every state in which a rule
+// referencing the ended rule continues (anywhere in the grammar) goes on as a new root instance, i.e.
+// the rest of the token is matched against everything that can follow in some context.
+// cls_words: the byte -> class table (64 words), in LDS or device memory.
+//
+// While the item set is a single item whose state has byte edges only (not final, no rule edge) the
+// recogniser is a plain automaton walk: the item stays in a register and a byte costs one table load.
+// The lists in `st` are used from the first state that predicts or completes, and left again when the
+// set shrinks back to one such item (older wait entries stay where they are).
+template <class S, bool FOLLOW = false, class BYTES = RegBytes>
+__device__ int scan_token(const DevTables& T, const uint32_t* cls_words, const DevCtx& C, BYTES tok, int n, S& st) {
+    if (n > S::MAXLEN || (int)C.n_items > S::K) return RES_OVERFLOW;
+    int nc = (int)C.n_items;
+    uint32_t one = nc == 1 ? C.items[0] : 0u;
+    bool single = nc == 1 && (one & (F_BYTE | F_REF | F_FINAL)) == F_BYTE;
+    if (!single) for (int k = 0; k < nc; ++k) st.set_cur(k, C.items[k]);
+    int nw = 0;
+    int res = 0;
+    int i = 0;
+    for (;;) {
+        // ---- automaton walk: one item, in a register; a byte costs one table load ----------------
+        uint32_t pending = NO_TARGET;
+        while (single && i < n) {
+            const uint32_t b = tok.next();
+            const uint32_t cls = (cls_words[b >> 2] >> ((b & 3) * 8)) & 0xFF;
+            const uint32_t tgt = T.trans[(one & SID_MASK) * T.n_classes + cls];
+            if (tgt == NO_TARGET) return res;                    // dead
+            if (tgt & (F_REF | F_FINAL)) { pending = tgt; single = false; break; }   // this state predicts or completes
+            one = tgt | (one & ~REF_MASK);
+            ++i;
+        }
+        if (i >= n) break;
+        // ---- one general step for byte i ---------------------------------------------------------
+        st.set_wstart(i, (uint32_t)nw);
+        int nn = 0;
+        const int wbeg = nw;
+        const uint32_t set_idx = C.H + (uint32_t)i;
+        if (pending != NO_TARGET) {
+            if (!enter(T, st, pending, one >> REF_BITS, set_idx, nn, nw, wbeg)) return RES_OVERFLOW;
+        } else {
+            const uint32_t b = tok.next();
+            const uint32_t cls = (cls_words[b >> 2] >> ((b & 3) * 8)) & 0xFF;
+            for (int k = 0; k < nc; ++k) {                       // scanner: one table word per scannable item
+                const uint32_t it = st.get_cur(k);
+                if (!(it & F_BYTE)) continue;
+                const uint32_t tgt = T.trans[(it & SID_MASK) * T.n_classes + cls];
+                if (tgt != NO_TARGET && !enter(T, st, tgt, it >> REF_BITS, set_idx, nn, nw, wbeg)) return RES_OVERFLOW;
+            }
+        }
+        // completer over the growing item list (prediction happened on entering)
+        bool root_now = false;
+        for (int pn = 0; pn < nn; ++pn) {
+            const uint32_t it = st.get_nxt(pn);
+            const uint32_t origin = it >> REF_BITS;
+            if (!(it & F_FINAL) || origin == set_idx) continue;  // rules that derive the empty string were advanced over on entering
+            if (origin == ROOT_ORIGIN) {
+                root_now = true;
+                if (FOLLOW) {
+                    const uint32_t rule = T.state[it & SID_MASK].x;
+                    for (uint32_t k = T.site_off[rule]; k < T.site_off[rule + 1]; ++k)
+                        if (!enter(T, st, T.site_tgt[k], ROOT_ORIGIN, set_idx, nn, nw, wbeg)) return RES_OVERFLOW;
+                }
+                continue;
+            }
+            const uint32_t rule = T.state[it & SID_MASK].x;
+            const bool local = origin >= C.H;
+            const int lo = local ? (int)st.get_wstart((int)(origin - C.H)) : (int)C.wait_off[origin];
+            const int hi = local ? (int)st.get_wstart((int)(origin - C.H) + 1) : (int)C.wait_off[origin + 1];
+            for (int k = lo; k < hi; ++k) {
+                uint32_t wr, wt;
+                if (local) { wr = st.wait_rule(k); wt = st.wait_tgt(k); }
+                else { const uint2 w = C.wait[k]; wr = w.x; wt = w.y; }
+                if (wr == rule && !enter(T, st, wt & REF_MASK, wt >> REF_BITS, set_idx, nn, nw, wbeg)) return RES_OVERFLOW;
+            }
+        }
+        if (nn == 0 && nw == wbeg) return res;               // dead: nothing survives this byte
+        if (root_now && i + 1 < n) res |= RES_EARLY;
+        st.swap();
+        nc = nn;
+        ++i;
+        if (i < n) st.set_wstart(i, (uint32_t)nw);             // sets made by the automaton walk add no wait entries
+        if (nc == 1) {                                           // back to the register walk?
+            one = st.get_cur(0);
+            single = (one & (F_BYTE | F_REF | F_FINAL)) == F_BYTE;
+        }
+    }
+    return res | RES_ALIVE;
+}
+
+}  // namespace core
+}  // namespace xg2

@@ -7,57 +7,29 @@
 //   k_apply_*      logits of disallowed tokens := -infinity, in place    (section 2.1)
 // No MFMA: nothing here is a contraction.  All device writes are vector stores or LDS/L2 atomics.
 #include "device.hpp"
+#include "earley_core.hpp"
 
 namespace xg2 {
 namespace {
 
-// A state reference is 21 bits: state id (18) | has byte edge | has rule edge | final; an item is a state
-// reference with the origin (item-set index, 2047 = root instance) in the upper 11 bits.
-constexpr uint32_t SID_MASK = (1u << 18) - 1;
-constexpr uint32_t F_BYTE = 1u << 18, F_REF = 1u << 19, F_FINAL = 1u << 20;
-constexpr uint32_t REF_BITS = 21;
-constexpr uint32_t ROOT_ORIGIN = (1u << (32 - REF_BITS)) - 1;
-constexpr uint32_t NO_TARGET = 0xFFFFFFFFu;
-
-constexpr int RES_ALIVE = 1, RES_EARLY = 2, RES_OVERFLOW = 4;
-
-struct DevCtx {                      // closed item set to continue from, plus reachable waiting items
-    const uint32_t* items; uint32_t n_items;
-    const uint32_t* wait; const uint32_t* wait_off; uint32_t H;
-};
-
-// ---- token bytes, consumed front to back: in registers (at most 16) or in device memory ----------------
-struct RegBytes {
-    uint4 v;                                                    // a 128-bit shift register: no indexed access, no spill
-    __device__ uint32_t next() {
-        const uint32_t b = v.x & 0xFF;
-        v.x = __builtin_amdgcn_alignbit(v.y, v.x, 8);
-        v.y = __builtin_amdgcn_alignbit(v.z, v.y, 8);
-        v.z = __builtin_amdgcn_alignbit(v.w, v.z, 8);
-        v.w >>= 8;
-        return b;
-    }
-};
-struct MemBytes {
-    const uint8_t* p;
-    __device__ uint32_t next() { return *p++; }
-};
+using namespace core;
 
 // ---- per-lane item storage -------------------------------------------------------------------------
 // LDS: word (slot, lane) lives at slot * 64 + lane, so a wave touching one slot per lane hits every
 // bank once per 32 lanes whatever the slots are.
 template <int K_, int WM_>
 struct LdsStore {
-    static constexpr int K = K_, WM = WM_, MAXLEN = 16, SLOTS = 2 * K_ + WM_;
-    uint32_t* cur; uint32_t* nxt; uint32_t* wait;  // this lane's column of the two item lists and the wait list
+    static constexpr int K = K_, WM = WM_, MAXLEN = 16, SLOTS = 2 * K_ + 2 * WM_;
+    uint32_t* cur; uint32_t* nxt; uint32_t* wait;  // this lane's column of the two item lists and the wait list (two words an entry)
     unsigned long long ws_lo = 0, ws_hi = 0;        // wait-list length at the start of each new set, 8 bits each
     __device__ void init(uint32_t* base) { cur = base; nxt = base + K * 64; wait = base + 2 * K * 64; }
     __device__ uint32_t get_cur(int k) const { return cur[k * 64]; }
     __device__ void set_cur(int k, uint32_t v) { cur[k * 64] = v; }
     __device__ uint32_t get_nxt(int k) const { return nxt[k * 64]; }
     __device__ void set_nxt(int k, uint32_t v) { nxt[k * 64] = v; }
-    __device__ uint32_t get_wait(int k) const { return wait[k * 64]; }
-    __device__ void set_wait(int k, uint32_t v) { wait[k * 64] = v; }
+    __device__ uint32_t wait_rule(int k) const { return wait[k * 128]; }
+    __device__ uint32_t wait_tgt(int k) const { return wait[k * 128 + 64]; }
+    __device__ void set_wait(int k, uint32_t rule, uint32_t tgt) { wait[k * 128] = rule; wait[k * 128 + 64] = tgt; }
     __device__ void swap() { uint32_t* t = cur; cur = nxt; nxt = t; }
     __device__ void reset() { ws_lo = 0; ws_hi = 0; }
     __device__ void set_wstart(int j, uint32_t v) {
@@ -75,147 +47,20 @@ struct GlobalStore {
     static constexpr int K = kSlowK, WM = kSlowWM, MAXLEN = kSlowMaxLen;
     uint32_t* cur; uint32_t* nxt; uint32_t* wait; uint32_t* ws; size_t stride;
     __device__ void init(uint32_t* base, size_t n_lanes) {
-        stride = n_lanes; cur = base; nxt = base + (size_t)K * stride; wait = base + (size_t)2 * K * stride; ws = base + (size_t)(2 * K + WM) * stride;
+        stride = n_lanes; cur = base; nxt = base + (size_t)K * stride; wait = base + (size_t)2 * K * stride; ws = base + (size_t)(2 * K + 2 * WM) * stride;
     }
     __device__ uint32_t get_cur(int k) const { return cur[(size_t)k * stride]; }
     __device__ void set_cur(int k, uint32_t v) { cur[(size_t)k * stride] = v; }
     __device__ uint32_t get_nxt(int k) const { return nxt[(size_t)k * stride]; }
     __device__ void set_nxt(int k, uint32_t v) { nxt[(size_t)k * stride] = v; }
-    __device__ uint32_t get_wait(int k) const { return wait[(size_t)k * stride]; }
-    __device__ void set_wait(int k, uint32_t v) { wait[(size_t)k * stride] = v; }
+    __device__ uint32_t wait_rule(int k) const { return wait[(size_t)(2 * k) * stride]; }
+    __device__ uint32_t wait_tgt(int k) const { return wait[(size_t)(2 * k + 1) * stride]; }
+    __device__ void set_wait(int k, uint32_t rule, uint32_t tgt) { wait[(size_t)(2 * k) * stride] = rule; wait[(size_t)(2 * k + 1) * stride] = tgt; }
     __device__ void swap() { uint32_t* t = cur; cur = nxt; nxt = t; }
     __device__ void reset() {}
     __device__ void set_wstart(int j, uint32_t v) { ws[(size_t)j * stride] = v; }
     __device__ uint32_t get_wstart(int j) const { return ws[(size_t)j * stride]; }
 };
-
-// Put item (state reference, origin) into the set under construction unless it is there.  Items whose state
-// has a byte edge (or no edge: they only ever complete) go to `nxt`, items with a rule edge to the wait
-// list.  No memory is read: the flags travel with the state reference.  Returns false when a list is full.
-template <class S>
-__device__ __forceinline__ bool add_item(S& st, uint32_t ref, uint32_t origin, int& nn, int& nw, int wbeg) {
-    const uint32_t item = ref | (origin << REF_BITS);
-    if ((ref & F_BYTE) || !(ref & F_REF)) {
-        for (int k = 0; k < nn; ++k) if (st.get_nxt(k) == item) return true;
-        if (nn == S::K) return false;
-        st.set_nxt(nn++, item);
-    }
-    if (ref & F_REF) {
-        for (int k = wbeg; k < nw; ++k) if (st.get_wait(k) == item) return true;
-        if (nw == S::WM) return false;
-        st.set_wait(nw++, item);
-    }
-    return true;
-}
-
-// Earley recognition of the n bytes at tok, continuing from context C.  New item sets are numbered
-// C.H, C.H + 1, ...  Returns RES_ALIVE if the set after the last byte is non-empty, RES_EARLY if the
-// root instance could end after some proper non-empty prefix, RES_OVERFLOW if a list filled up.
-// With FOLLOW, the end of the root instance is not the end of the parse: every state in which a rule
-// referencing the ended rule continues (anywhere in the grammar) goes on as a new root instance, i.e.
-// the rest of the token is matched against everything that can follow in some context.
-// cls_words: the byte -> class table (64 words), in LDS or device memory.
-//
-// While the item set is a single item whose state has byte edges only (not final, no rule edge) the
-// recogniser is a plain automaton walk: the item stays in a register and a byte costs one table load.
-// The lists in `st` are used from the first state that predicts or completes, and left again when the
-// set shrinks back to one such item (older waiting items stay where they are).
-template <class S, bool FOLLOW = false, class BYTES = RegBytes>
-__device__ int scan_token(const DevTables& T, const uint32_t* cls_words, const DevCtx& C, BYTES tok, int n, S& st) {
-    if (n > S::MAXLEN || (int)C.n_items > S::K) return RES_OVERFLOW;
-    int nc = (int)C.n_items;
-    uint32_t one = nc == 1 ? C.items[0] : 0u;
-    bool single = nc == 1 && (one & (F_BYTE | F_REF | F_FINAL)) == F_BYTE;
-    if (!single) for (int k = 0; k < nc; ++k) st.set_cur(k, C.items[k]);
-    int nw = 0;
-    int res = 0;
-    int i = 0;
-    for (;;) {
-        // ---- automaton walk: one item, in a register; a byte costs one table load ----------------
-        uint32_t pending = NO_TARGET;
-        while (single && i < n) {
-            const uint32_t b = tok.next();
-            const uint32_t cls = (cls_words[b >> 2] >> ((b & 3) * 8)) & 0xFF;
-            const uint32_t tgt = T.trans[(one & SID_MASK) * T.n_classes + cls];
-            if (tgt == NO_TARGET) return res;                    // dead
-            if (tgt & (F_REF | F_FINAL)) { pending = tgt; single = false; break; }   // this state predicts or completes
-            one = tgt | (one & ~((1u << REF_BITS) - 1));
-            ++i;
-        }
-        if (i >= n) break;
-        // ---- one general step for byte i ---------------------------------------------------------
-        st.set_wstart(i, (uint32_t)nw);
-        int nn = 0;
-        const int wbeg = nw;
-        if (pending != NO_TARGET) {
-            if (!add_item(st, pending, one >> REF_BITS, nn, nw, wbeg)) return RES_OVERFLOW;
-        } else {
-            const uint32_t b = tok.next();
-            const uint32_t cls = (cls_words[b >> 2] >> ((b & 3) * 8)) & 0xFF;
-            for (int k = 0; k < nc; ++k) {                       // scanner: one table word per scannable item
-                const uint32_t it = st.get_cur(k);
-                if (!(it & F_BYTE)) continue;
-                const uint32_t tgt = T.trans[(it & SID_MASK) * T.n_classes + cls];
-                if (tgt != NO_TARGET && !add_item(st, tgt, it >> REF_BITS, nn, nw, wbeg)) return RES_OVERFLOW;
-            }
-        }
-        // predictor and completer over the growing lists
-        const uint32_t set_idx = C.H + (uint32_t)i;
-        bool root_now = false;
-        int pn = 0, pw = wbeg;
-        while (pn < nn || pw < nw) {
-            const bool from_nxt = pn < nn;
-            const uint32_t it = from_nxt ? st.get_nxt(pn++) : st.get_wait(pw++);
-            const uint32_t origin = it >> REF_BITS;
-            const bool in_nxt = (it & F_BYTE) || !(it & F_REF);
-            const bool complete = (it & F_FINAL) && from_nxt == in_nxt;      // once per item
-            if (from_nxt && !complete) continue;                 // plain scannable item: nothing to do
-            const uint4 si = T.state_info[it & SID_MASK];
-            if (!from_nxt) {
-                const uint32_t nr = si.z >> 16;
-                for (uint32_t e = 0; e < nr; ++e) {
-                    const uint2 re = T.ref_edges[si.y + e];
-                    const uint2 ri = T.rule_info[re.x];
-                    if (!add_item(st, ri.x, set_idx, nn, nw, wbeg)) return RES_OVERFLOW;
-                    if (ri.y && !add_item(st, re.y, origin, nn, nw, wbeg)) return RES_OVERFLOW;   // nullable rule
-                }
-            }
-            if (complete) {
-                const uint32_t rule = si.w & 0x7FFFFFFFu;
-                if (origin == ROOT_ORIGIN) {
-                    root_now = true;
-                    if (FOLLOW)
-                        for (uint32_t k = T.site_off[rule]; k < T.site_off[rule + 1]; ++k)
-                            if (!add_item(st, T.site_tgt[k], ROOT_ORIGIN, nn, nw, wbeg)) return RES_OVERFLOW;
-                } else if (origin != set_idx) {
-                    const bool local = origin >= C.H;
-                    const int lo = local ? (int)st.get_wstart((int)(origin - C.H)) : (int)C.wait_off[origin];
-                    const int hi = local ? (int)st.get_wstart((int)(origin - C.H) + 1) : (int)C.wait_off[origin + 1];
-                    for (int k = lo; k < hi; ++k) {
-                        const uint32_t w = local ? st.get_wait(k) : C.wait[k];
-                        const uint4 wi = T.state_info[w & SID_MASK];
-                        const uint32_t wr = wi.z >> 16;
-                        for (uint32_t e = 0; e < wr; ++e) {
-                            const uint2 re = T.ref_edges[wi.y + e];
-                            if (re.x == rule && !add_item(st, re.y, w >> REF_BITS, nn, nw, wbeg)) return RES_OVERFLOW;
-                        }
-                    }
-                }
-            }
-        }
-        if (nn == 0 && nw == wbeg) return res;               // dead: nothing survives this byte
-        if (root_now && i + 1 < n) res |= RES_EARLY;
-        st.swap();
-        nc = nn;
-        ++i;
-        if (i < n) st.set_wstart(i, (uint32_t)nw);             // sets made by the automaton walk add no waiting items
-        if (nc == 1) {                                           // back to the register walk?
-            one = st.get_cur(0);
-            single = (one & (F_BYTE | F_REF | F_FINAL)) == F_BYTE;
-        }
-    }
-    return res | RES_ALIVE;
-}
 
 #ifndef XG2_BUILD_K
 #define XG2_BUILD_K 6

@@ -25,8 +25,43 @@ FlatTables flatten(const Grammar& g) {
         }
     }
     t.root_start = (uint32_t)g.sid(g.root, 0);
-    for (const RefEdgeP& e : t.ref_edges) t.dev_ref_edges.push_back({e.rule, t.ref(e.tgt)});
-    for (const RuleInfo& ri : t.rule_info) t.dev_rule_info.push_back({t.ref(ri.start), ri.nullable});
+    // expansions: closure of prediction and of advancing over empty-deriving rules, per state with rule edges
+    t.dev_state.resize(t.state_info.size());
+    {
+        std::vector<std::pair<uint32_t, uint32_t>> queue;            // (state, 1 = origin is the set being built)
+        std::vector<uint32_t> items, triples;
+        for (size_t sid = 0; sid < t.state_info.size(); ++sid) {
+            const StateInfo& s0 = t.state_info[sid];
+            DevState ds{s0.rule_final & 0x7FFFFFFFu, (uint32_t)t.exp_list.size(), 0, 0};
+            if (s0.counts >> 16) {
+                queue.assign(1, {(uint32_t)sid, 0u});
+                items.clear(); triples.clear();
+                auto enqueue = [&](uint32_t u, uint32_t cur) {
+                    for (auto& q : queue) if (q.first == u && q.second == cur) return;
+                    queue.emplace_back(u, cur);
+                };
+                for (size_t qi = 0; qi < queue.size(); ++qi) {
+                    const uint32_t u = queue[qi].first, cur = queue[qi].second;
+                    const StateInfo& su = t.state_info[u];
+                    const uint32_t nb = su.counts & 0xFFFF, nr = su.counts >> 16;
+                    const bool listed = nb > 0 || (su.rule_final >> 31) || nr == 0;   // scannable or completing
+                    if (qi > 0 && listed) items.push_back(t.ref(u) | (cur ? kExpCurrent : 0u));
+                    for (uint32_t k = 0; k < nr; ++k) {
+                        const RefEdgeP& e = t.ref_edges[su.ref_off + k];
+                        triples.push_back(e.rule);
+                        triples.push_back(t.ref(e.tgt) | (cur ? kExpCurrent : 0u));
+                        enqueue(t.rule_info[e.rule].start, 1u);
+                        if (t.rule_info[e.rule].nullable) enqueue(e.tgt, cur);
+                    }
+                }
+                ds.n_items = (uint32_t)items.size();
+                ds.n_triples = (uint32_t)(triples.size() / 2);
+                t.exp_list.insert(t.exp_list.end(), items.begin(), items.end());
+                t.exp_list.insert(t.exp_list.end(), triples.begin(), triples.end());
+            }
+            t.dev_state[sid] = ds;
+        }
+    }
     // byte classes: refine by (class so far, target) state after state
     const size_t n = t.state_info.size();
     std::vector<uint32_t> cls(256, 0);
@@ -154,11 +189,20 @@ bool EarleyChart::context(ScanContext& out) const {
     auto loc = [&](int32_t o) { return o < 0 ? kRootOrigin : local.at(o); };
     for (const ChartItem& it : chart_[(size_t)J].scan) out.items.push_back(pack_item(t_->ref(it.sid), loc(it.origin)));
     for (size_t k = 0; k < needed.size(); ++k) {
-        out.wait_off.push_back((uint32_t)out.wait.size());
-        for (const ChartItem& w : chart_[(size_t)needed[k]].wait) out.wait.push_back(pack_item(t_->ref(w.sid), loc(w.origin)));
+        out.wait_off.push_back((uint32_t)(out.wait.size() / 2));
+        for (const ChartItem& w : chart_[(size_t)needed[k]].wait) push_triples(w, loc(w.origin), out.wait);
     }
-    out.wait_off.push_back((uint32_t)out.wait.size());
+    out.wait_off.push_back((uint32_t)(out.wait.size() / 2));
     return true;
+}
+
+void EarleyChart::push_triples(const ChartItem& w, uint32_t local_origin, std::vector<uint32_t>& out) const {
+    const StateInfo& wi = t_->state_info[w.sid];
+    for (uint32_t k = 0; k < (wi.counts >> 16); ++k) {
+        const RefEdgeP& e = t_->ref_edges[wi.ref_off + k];
+        out.push_back(e.rule);
+        out.push_back(pack_item(t_->ref(e.tgt), local_origin));
+    }
 }
 
 }  // namespace xg2

@@ -26,6 +26,8 @@ struct StateInfo { uint32_t byte_off, ref_off, counts /* n_byte | n_ref << 16 */
 struct ByteEdge { uint32_t lohi /* lo | hi << 8 */, tgt; };
 struct RefEdgeP { uint32_t rule, tgt; };
 struct RuleInfo { uint32_t start, nullable; };
+struct DevState { uint32_t rule, exp_off, n_items, n_triples; };
+constexpr uint32_t kExpCurrent = 1u << kRefBits;
 
 struct FlatTables {
     std::vector<StateInfo> state_info;
@@ -33,9 +35,15 @@ struct FlatTables {
     std::vector<RefEdgeP> ref_edges;
     std::vector<RuleInfo> rule_info;
     uint32_t root_start = 0;
-    // device-side forms: every stored state is a state reference (id | flags)
-    std::vector<RefEdgeP> dev_ref_edges;
-    std::vector<RuleInfo> dev_rule_info;
+    // device-side forms: every stored state is a state reference (id | flags).
+    // dev_state[sid] = {rule, offset into exp_list, n_items, n_triples}.  The expansion of a state with rule
+    // edges lists everything that entering it adds to an Earley set besides the item itself, predictions and
+    // advances over rules that derive the empty string followed to the end: first n_items item words
+    // (state reference | kExpCurrent if the origin is the set being built, else the origin of the entering
+    // item), then n_triples pairs {rule, state reference [| kExpCurrent]}: "when `rule`, started in this
+    // set, completes, continue in that state".
+    std::vector<DevState> dev_state;
+    std::vector<uint32_t> exp_list;
     // dense byte transitions: bytes that lead to the same state from every state form one class;
     // trans[sid * n_classes + class] = state reference of the target or kNoTarget
     std::vector<uint32_t> byte_class_words;      // 64 words: class of byte b = byte (b & 3) of word b >> 2
@@ -59,13 +67,14 @@ struct ChartSet {
     bool root_done = false;
 };
 
-// The context a kernel needs to continue parsing from a closed set: that set's scan items plus the
-// waiting items of every set reachable through origins, with set indices renumbered 0..H-1 (the
-// current set is H-1).
+// The context a kernel needs to continue parsing from a closed set: that set's scan items plus, for every
+// set reachable through origins, what its waiting items wait for, with set indices renumbered 0..H-1 (the
+// current set is H-1).  A waiting item with rule edge (rule -> target) gives the triple
+// {rule, state reference of the target | local origin << 21}, two words.
 struct ScanContext {
-    std::vector<uint32_t> items;       // packed (sid, local origin)
-    std::vector<uint32_t> wait;        // packed, grouped by local set
-    std::vector<uint32_t> wait_off;    // [H+1]
+    std::vector<uint32_t> items;       // packed (state reference, local origin)
+    std::vector<uint32_t> wait;        // triples, two words each, grouped by local set
+    std::vector<uint32_t> wait_off;    // [H+1], in triples
     uint32_t H = 0;
 };
 
@@ -77,11 +86,14 @@ class EarleyChart {
     // (sid, origin 0): the rule instance of `sid` one level inside the rule of `waiter_sid`.
     void start_pair(uint32_t sid, uint32_t waiter_sid);
     const std::vector<ChartSet>& sets() const { return chart_; }
+    const FlatTables* tables() const { return t_; }
     bool advance(const uint8_t* bytes, size_t n);    // all or nothing: false leaves the chart unchanged
     const ChartSet& last() const { return chart_.back(); }
     size_t length() const { return chart_.size(); }
     // false if more than kMaxLocalSets sets are reachable
     bool context(ScanContext& out) const;
+    // appends the triples of waiting item `w` (origin already renumbered) to `out`
+    void push_triples(const ChartItem& w, uint32_t local_origin, std::vector<uint32_t>& out) const;
 
   private:
     const FlatTables* t_;

@@ -1,0 +1,145 @@
+// Test helper (CPU only): steps the recogniser core that the kernels run per lane, compiled for the host,
+// against the host Earley parser of the library, for every plane context of a grammar and a list of tokens.
+// Built by tests/test_host_logic.py with g++; it is not part of the library.
+#include <cstdint>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "../../paper_2601_04426_amd/csrc/earley_core.hpp"
+#include "../../paper_2601_04426_amd/csrc/grammar.hpp"
+#include "../../paper_2601_04426_amd/csrc/tables.hpp"
+
+using namespace xg2;
+using namespace xg2::core;
+
+namespace {
+
+template <int K_, int WM_, int MAXLEN_>
+struct HostStore {
+    static constexpr int K = K_, WM = WM_, MAXLEN = MAXLEN_;
+    std::vector<uint32_t> a, b, w, ws;
+    uint32_t* cur; uint32_t* nxt;
+    HostStore() : a(K_), b(K_), w(2 * WM_), ws(MAXLEN_ + 1) { cur = a.data(); nxt = b.data(); }
+    uint32_t get_cur(int k) const { return cur[k]; }
+    void set_cur(int k, uint32_t v) { cur[k] = v; }
+    uint32_t get_nxt(int k) const { return nxt[k]; }
+    void set_nxt(int k, uint32_t v) { nxt[k] = v; }
+    uint32_t wait_rule(int k) const { return w[2 * (size_t)k]; }
+    uint32_t wait_tgt(int k) const { return w[2 * (size_t)k + 1]; }
+    void set_wait(int k, uint32_t r, uint32_t t) { w[2 * (size_t)k] = r; w[2 * (size_t)k + 1] = t; }
+    void swap() { std::swap(cur, nxt); }
+    void reset() {}
+    void set_wstart(int j, uint32_t v) { ws.at((size_t)j) = v; }
+    uint32_t get_wstart(int j) const { return ws.at((size_t)j); }
+};
+
+struct Ctx {
+    std::vector<uint32_t> items, wait, wait_off;
+    uint32_t H = 0;
+};
+
+Ctx ctx_of(const EarleyChart& chart, bool renumber) {
+    Ctx c;
+    if (renumber) {
+        ScanContext sc;
+        if (!chart.context(sc)) throw std::runtime_error("context too deep");
+        c.items = sc.items; c.wait = sc.wait; c.wait_off = sc.wait_off; c.H = sc.H;
+        return c;
+    }
+    // the way the build plans a plane: every set of the chart, in order
+    const auto& sets = chart.sets();
+    auto loc = [](int32_t o) { return o < 0 ? kRootOrigin : (uint32_t)o; };
+    for (const ChartItem& it : sets.back().scan) c.items.push_back(pack_item(chart.tables()->ref(it.sid), loc(it.origin)));
+    for (const ChartSet& cs : sets) {
+        c.wait_off.push_back((uint32_t)(c.wait.size() / 2));
+        for (const ChartItem& it : cs.wait) chart.push_triples(it, loc(it.origin), c.wait);
+    }
+    c.wait_off.push_back((uint32_t)(c.wait.size() / 2));
+    c.H = (uint32_t)sets.size();
+    return c;
+}
+
+// what the host parser says about token t from the chart's current state: bit 0 alive, bit 1 early
+int host_result(EarleyChart chart, const uint8_t* t, size_t n) {
+    int res = 0;
+    for (size_t i = 0; i < n; ++i) {
+        if (!chart.advance(t + i, 1)) return res;
+        if (chart.last().root_done && i + 1 < n) res |= RES_EARLY;
+    }
+    return res | RES_ALIVE;
+}
+
+template <class S>
+int core_result(const FlatTables& ft, const DevTables& T, const Ctx& c, const uint8_t* t, size_t n) {
+    DevCtx C;
+    C.items = c.items.data(); C.n_items = (uint32_t)c.items.size();
+    C.wait = reinterpret_cast<const uint2*>(c.wait.data()); C.wait_off = c.wait_off.data(); C.H = c.H;
+    S st;
+    MemBytes tok{t};
+    return scan_token<S, false, MemBytes>(T, ft.byte_class_words.data(), C, tok, (int)n, st);
+}
+
+}  // namespace
+
+// Returns the number of (context, token) pairs checked, or -(1 + index of the first mismatch) with a
+// description in msg.  Contexts: every position alone; every position inside every state that references
+// its rule; and the states along `sentence` (renumbered contexts, as fill builds them).
+extern "C" long long xg2hc_check(const char* ebnf, size_t len, const char* root, const uint8_t* bytes, const uint64_t* offs, int n_tok,
+                                 const uint8_t* sentence, size_t sentence_len, int max_contexts, char* msg, size_t msg_cap,
+                                 long long* n_small_overflow) {
+    try {
+        Grammar g = lower_grammar(std::string(ebnf, len), root);
+        FlatTables ft = flatten(g);
+        DevTables T{};
+        T.state = reinterpret_cast<const uint4*>(ft.dev_state.data());
+        T.exp_list = ft.exp_list.data();
+        T.trans = ft.trans.data();
+        T.byte_class_words = ft.byte_class_words.data();
+        T.n_classes = ft.n_classes;
+        long long checked = 0, small_over = 0;
+        int n_ctx = 0;
+        auto run = [&](const EarleyChart& chart, bool renumber, const std::string& what) -> bool {
+            Ctx c = ctx_of(chart, renumber);
+            for (int k = 0; k < n_tok; ++k) {
+                const uint8_t* t = bytes + offs[k];
+                size_t n = (size_t)(offs[k + 1] - offs[k]);
+                if (n == 0) continue;
+                int want = host_result(chart, t, n);
+                int got = n <= 16 ? core_result<HostStore<6, 10, 16>>(ft, T, c, t, n) : RES_OVERFLOW;
+                if (got & RES_OVERFLOW) { ++small_over; got = core_result<HostStore<256, 1024, 1024>>(ft, T, c, t, n); }
+                ++checked;
+                if (got != want) {
+                    snprintf(msg, msg_cap, "%s token %d: host parser %d, recogniser core %d", what.c_str(), k, want, got);
+                    return false;
+                }
+            }
+            return true;
+        };
+        EarleyChart chart(&ft);
+        for (const Position& ps : g.positions) {
+            if (n_ctx++ >= max_contexts) break;
+            chart.start((uint32_t)ps.sid);
+            if (!run(chart, false, "position " + std::to_string(ps.sid))) return -checked - 1;
+            for (size_t w = 0; w < ft.state_info.size(); ++w) {
+                const StateInfo& wi = ft.state_info[w];
+                bool refs = false;
+                for (uint32_t e = 0; e < (wi.counts >> 16); ++e) refs |= ft.ref_edges[wi.ref_off + e].rule == (uint32_t)ps.rule;
+                if (!refs) continue;
+                if (n_ctx++ >= max_contexts) break;
+                chart.start_pair((uint32_t)ps.sid, (uint32_t)w);
+                if (!run(chart, false, "position " + std::to_string(ps.sid) + " inside state " + std::to_string(w))) return -checked - 1;
+            }
+        }
+        chart.start(ft.root_start);
+        for (size_t i = 0; i <= sentence_len; ++i) {
+            if (!run(chart, true, "after " + std::to_string(i) + " sentence bytes")) return -checked - 1;
+            if (i < sentence_len && !chart.advance(sentence + i, 1)) { snprintf(msg, msg_cap, "sentence rejected at byte %zu", i); return -checked - 1; }
+        }
+        if (n_small_overflow) *n_small_overflow = small_over;
+        return checked;
+    } catch (const std::exception& e) {
+        snprintf(msg, msg_cap, "exception: %s", e.what());
+        return -1;
+    }
+}

@@ -1,0 +1,91 @@
+"""The per-lane recogniser of the kernels, compiled for the host, against the library's host Earley parser.
+
+The kernels' scanner / predictor / completer (XGrammar-2 section 3.4 and the appendix on Earley parsing)
+lives in `csrc/earley_core.hpp` and compiles for the host as well.  `tests/hostcheck/hostcheck.cpp` steps
+it, with the small item-list capacities of the LDS path and with the large ones of the device-memory
+path, over every plane context of a grammar (a position alone, a position inside each state that
+references its rule) and over the renumbered contexts along a sentence, and compares "alive after the last
+byte" and "the outermost rule could end earlier" with the host parser, which `test_host_logic.py` ties to
+the oracle.  No GPU is involved; the GPU parity tests compare the kernels themselves with the oracle.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import random
+import subprocess
+
+import pytest
+
+import gen
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(HERE)
+PKG = os.path.join(ROOT, "paper_2601_04426_amd")
+SRC = os.path.join(HERE, "hostcheck", "hostcheck.cpp")
+OUT = os.path.join(HERE, "hostcheck", "libhostcheck.so")
+
+
+@pytest.fixture(scope="module")
+def hostcheck():
+    lib = os.path.join(PKG, "libxg2mask.so")
+    if not os.path.exists(lib):
+        pytest.fail("libxg2mask.so is not built (run __graft_entry__.build())")
+    deps = [SRC, lib] + [os.path.join(PKG, "csrc", f) for f in ("earley_core.hpp", "device.hpp", "tables.hpp", "grammar.hpp")]
+    if not os.path.exists(OUT) or any(os.path.getmtime(d) > os.path.getmtime(OUT) for d in deps):
+        cmd = ["g++", "-O2", "-std=c++17", "-fPIC", "-shared", "-I/opt/rocm/include", "-D__HIP_PLATFORM_AMD__",
+               "-o", OUT, SRC, lib, "-Wl,-rpath," + PKG]
+        res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+        assert res.returncode == 0, res.stdout
+    h = ctypes.CDLL(OUT)
+    h.xg2hc_check.restype = ctypes.c_longlong
+    return h
+
+
+def run_check(h, ebnf, root, tokens, sentence, max_contexts):
+    blob = b"".join(tokens)
+    offs = [0]
+    for t in tokens:
+        offs.append(offs[-1] + len(t))
+    offs_c = (ctypes.c_uint64 * len(offs))(*offs)
+    msg = ctypes.create_string_buffer(512)
+    small = ctypes.c_longlong(0)
+    e = ebnf.encode()
+    n = h.xg2hc_check(e, ctypes.c_size_t(len(e)), root.encode(), blob, offs_c, len(tokens), sentence,
+                      ctypes.c_size_t(len(sentence)), max_contexts, msg, ctypes.c_size_t(512), ctypes.byref(small))
+    assert n > 0, msg.value.decode()
+    return n, small.value
+
+
+TINY = [
+    ('root ::= "a" root "b" | ""', "root", [b"a", b"b", b"ab", b"aab", b"abb", b"aabb", b"ba", b"aaabbb", b"bb"], b"aaabbb"),
+    ('root ::= root "x" | ""', "root", [b"x", b"xx", b"xxxxxxxxxxxxxxxxx", b"y", b"xy"], b"xxxx"),
+    ('root ::= a b c\na ::= "p"?\nb ::= a a | "q"\nc ::= [0-9]* a', "root", [b"p", b"q", b"pp", b"ppp", b"pq", b"q1", b"pp12p", b"1", b"12p", b"pppp", b"qpp"], b"pq12p"),
+    ('root ::= (item ",")* item\nitem ::= "[" root "]" | [a-c]{1,3}', "root",
+     [b"a", b"ab", b"abc", b"abca", b"[", b"]", b",", b"[a", b"a]", b"a,b", b"[[a],b]", b"],[", b"a],", b"]]", b",,", b"[[[[[[[[[[[[[[[["], b"[[a,bc],abc,[c]]"),
+    ('root ::= TagDispatch(("<t>", body), ("<u>", num), stop_strs=("END",))\nbody ::= [a-z]+ "</t>"\nnum ::= [0-9]{1,3} ";"', "root",
+     [b"<", b"<t", b"<t>", b"t>ab", b"x<t>ab</t>y", b"<u>12;", b"<u>1234", b"EN", b"END", b"ENDx", b"<t>a</t>END", b">", b"</t>", b"9;<"], b"zz<t>abc</t>q<u>7;END"),
+]
+
+
+@pytest.mark.parametrize("case", range(len(TINY)))
+def test_core_matches_host_parser_on_tiny_grammars(hostcheck, case):
+    ebnf, root, tokens, sentence = TINY[case]
+    singles = [bytes([b]) for b in set(b"".join(tokens))]
+    n, _ = run_check(hostcheck, ebnf, root, tokens + singles, sentence, 100000)
+    assert n >= len(tokens)
+
+
+@pytest.mark.parametrize("index,n_tokens,max_contexts", [(1, 2048, 100000), (2, 800, 150), (5, 800, 150), (3, 500, 100)])
+def test_core_matches_host_parser_on_workloads(hostcheck, index, n_tokens, max_contexts):
+    cfg = gen.build_config(index, n_tools=4) if index == 3 else gen.build_config(index)
+    ebnf, root = cfg.grammars[0]
+    rng = random.Random(1000 + index)
+    tokens = [t for i, t in enumerate(cfg.vocab.tokens) if t and i not in cfg.vocab.special_ids]
+    sample = rng.sample(tokens, min(n_tokens, len(tokens)))
+    text = cfg.sample_text(rng, 0)
+    sentence = (text if isinstance(text, bytes) else text.encode())[:200]
+    n, small = run_check(hostcheck, ebnf, root, sample, sentence, max_contexts)
+    assert n >= len(sample) * 10
+    # the capacities of the LDS path are meant to cover these workloads without the device-memory path
+    assert small <= n // 100
