@@ -555,6 +555,9 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
                 }
             }
             plane_ctx.push_back(make_uint4(item0, (uint32_t)ctx_items.size() - item0, (uint32_t)ctx_wait_off.size(), (uint32_t)sets.size()));
+            // a start set that is one item with byte edges only is walked as a plain automaton; the others need the
+            // Earley steps from the first byte on and go first, so that the long workgroups do not end the launch
+            const uint32_t heavy = (ctx_items.size() - item0 == 1 && (ctx_items[item0] & (kHasByte | kHasRef | kFinal)) == kHasByte) ? 0u : 1u;
             for (const ChartSet& cs : sets) {
                 ctx_wait_off.push_back((uint32_t)(ctx_wait.size() / 2));
                 for (const ChartItem& it : cs.wait) chart.push_triples(it, loc(it.origin), ctx_wait);
@@ -565,12 +568,13 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
                 int e = b;
                 while (live[e + 1]) ++e;
                 uint32_t lo = V.fb_start[b], hi = V.fb_start[e + 1];
-                for (uint32_t c = lo; c < hi; c += kBuildChunk) chunks.push_back(make_uint4((uint32_t)k, c, std::min(hi, c + kBuildChunk), 0));
+                for (uint32_t c = lo; c < hi; c += kBuildChunk) chunks.push_back(make_uint4((uint32_t)k, c, std::min(hi, c + kBuildChunk), heavy));
                 executed += hi - lo;
                 b = e + 1;
             }
         }
 
+        std::stable_sort(chunks.begin(), chunks.end(), [](const uint4& a, const uint4& b) { return a.w > b.w; });
         // everything the device needs goes up in two copies: the tables (kept with the cache) and the plan
         Packer tab, plan;
         const size_t o_state = tab.add(ft.dev_state), o_exp = tab.add(ft.exp_list),

@@ -34,7 +34,10 @@ struct DevVocab {                        // byte-sorted vocabulary in HBM
 // set of plane k as a scan context (H = 1: the position alone; H = 2: the position inside one level of
 // referencing rule).  ctx_wait holds, set after set, what the waiting items wait for as pairs
 // {rule, state reference of the target | origin << 21}; ctx_wait_off counts pairs.
-constexpr uint32_t kBuildChunk = 1024;
+#ifndef XG2_BUILD_CHUNK
+#define XG2_BUILD_CHUNK 512
+#endif
+constexpr uint32_t kBuildChunk = XG2_BUILD_CHUNK;
 struct BuildPlan {
     const uint4* chunk; uint32_t n_chunks;
     const uint4* plane_ctx;                                     // [n_planes]

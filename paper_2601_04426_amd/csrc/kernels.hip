@@ -96,32 +96,88 @@ __device__ __forceinline__ void store_class(const BuildPlan& P, uint32_t p, uint
     else if (res & RES_EARLY) atomicOr(row + W + (id >> 5), 1u << (id & 31));
 }
 
+// One workgroup per chunk of sorted ranks of one plane, in two phases.
+// Phase 1 (only when the plane's start set is a single item whose state has byte edges only): every lane
+// walks its token through the automaton, one table load per byte.  A token that dies is rejected, one that
+// reaches its end is accepted; one that reaches a state which predicts or completes is put on the
+// workgroup's deferred list.  Phase 2: the waves take the deferred tokens (or, for the other planes, all
+// tokens of the chunk) 64 at a time and run the Earley recogniser on them, so that its long divergent
+// steps run on full waves instead of on the few lanes of each wave that need them.
 __global__ __launch_bounds__(64 * BUILD_WAVES) void k_build(DevTables T, DevVocab Vd, BuildPlan P, SlowScratch S) {
     __shared__ uint32_t lds[BUILD_WAVES * BuildStore::SLOTS * 64];
     __shared__ uint32_t cls_words[64];
+    __shared__ uint32_t deferred[kBuildChunk];
+    __shared__ uint32_t n_deferred, n_taken;
     if (threadIdx.x < 64) cls_words[threadIdx.x] = T.byte_class_words[threadIdx.x];
+    if (threadIdx.x == 0) { n_deferred = 0; n_taken = 0; }
     __syncthreads();
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const uint4 chunk = P.chunk[blockIdx.x];                    // one descriptor per workgroup
     const uint32_t p = chunk.x;
     const DevCtx C = position_ctx(P, p);
+    const uint32_t item0 = C.items[0];
+    const bool walkable = C.n_items == 1 && (item0 & (F_BYTE | F_REF | F_FINAL)) == F_BYTE;   // same for the whole workgroup
+    uint32_t n_work = chunk.z - chunk.y;
+    if (walkable) {
+        for (uint32_t rank0 = chunk.y + wave * 64; rank0 < chunk.z; rank0 += 64 * BUILD_WAVES) {
+            const uint32_t rank = rank0 + lane;
+            bool defer = false;
+            if (rank < chunk.z) {
+                const int n = (int)(Vd.off[rank + 1] - Vd.off[rank]);
+                if (n > BuildStore::MAXLEN) defer = true;           // phase 2 hands it to the large-capacity kernel
+                else {
+                    RegBytes tok;
+                    tok.v = Vd.tok16[rank];
+                    uint32_t sid = item0 & SID_MASK;
+                    bool dead = false;
+                    for (int i = 0; i < n; ++i) {
+                        const uint32_t b = tok.next();
+                        const uint32_t cls = (cls_words[b >> 2] >> ((b & 3) * 8)) & 0xFF;
+                        const uint32_t tgt = T.trans[sid * T.n_classes + cls];
+                        if (tgt == NO_TARGET) { dead = true; break; }
+                        if (tgt & (F_REF | F_FINAL)) { defer = true; break; }
+                        sid = tgt & SID_MASK;
+                    }
+                    if (!dead && !defer) store_class(P, p, Vd.W, Vd.perm[rank], RES_ALIVE);
+                }
+            }
+            const unsigned long long m = __ballot(defer);
+            if (m) {                                                // one LDS atomic per wave
+                const uint32_t leader = (uint32_t)__ffsll((long long)m) - 1;
+                uint32_t base = 0;
+                if (lane == leader) base = atomicAdd(&n_deferred, (uint32_t)__popcll(m));
+                base = __shfl(base, (int)leader);
+                if (defer) deferred[base + (uint32_t)__popcll(m & ((1ull << lane) - 1))] = rank;
+            }
+        }
+        __syncthreads();
+        n_work = n_deferred;
+    }
     BuildStore st;
     st.init(lds + wave * BuildStore::SLOTS * 64 + lane);
-    for (uint32_t rank = chunk.y + wave * 64 + lane; rank < chunk.z; rank += 64 * BUILD_WAVES) {
-        const int n = (int)(Vd.off[rank + 1] - Vd.off[rank]);
-        RegBytes tok;
-        tok.v = Vd.tok16[rank];
-        st.reset();
-        int res = scan_token(T, cls_words, C, tok, n, st);
-        if (P.follow_filter && !(res & (RES_ALIVE | RES_OVERFLOW)) && (res & RES_EARLY)) {
-            // leaves the rule early: keep it uncertain only if some context can take the rest of the token
+    for (;;) {
+        uint32_t batch = 0;
+        if (lane == 0) batch = atomicAdd(&n_taken, 1u);
+        batch = __builtin_amdgcn_readfirstlane(batch);
+        if (batch * 64 >= n_work) break;                            // the counter only grows: every wave gets here
+        const uint32_t idx = batch * 64 + lane;
+        if (idx < n_work) {
+            const uint32_t rank = walkable ? deferred[idx] : chunk.y + idx;
+            const int n = (int)(Vd.off[rank + 1] - Vd.off[rank]);
+            RegBytes tok;
+            tok.v = Vd.tok16[rank];
             st.reset();
-            int res2 = scan_token<BuildStore, true>(T, cls_words, C, tok, n, st);
-            if (res2 & RES_OVERFLOW) res = RES_OVERFLOW;
-            else if (!(res2 & RES_ALIVE)) res = 0;
+            int res = scan_token(T, cls_words, C, tok, n, st);
+            if (P.follow_filter && !(res & (RES_ALIVE | RES_OVERFLOW)) && (res & RES_EARLY)) {
+                // leaves the rule early: keep it uncertain only if some context can take the rest of the token
+                st.reset();
+                int res2 = scan_token<BuildStore, true>(T, cls_words, C, tok, n, st);
+                if (res2 & RES_OVERFLOW) res = RES_OVERFLOW;
+                else if (!(res2 & RES_ALIVE)) res = 0;
+            }
+            if (res & RES_OVERFLOW) push_overflow(S, p, rank);
+            else store_class(P, p, Vd.W, Vd.perm[rank], res);
         }
-        if (res & RES_OVERFLOW) push_overflow(S, p, rank);
-        else store_class(P, p, Vd.W, Vd.perm[rank], res);
     }
 }
 

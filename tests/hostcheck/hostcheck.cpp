@@ -10,6 +10,10 @@
 #include "../../paper_2601_04426_amd/csrc/grammar.hpp"
 #include "../../paper_2601_04426_amd/csrc/tables.hpp"
 
+#ifndef HC_K
+#define HC_K 6      // capacities of the LDS path of the build kernel
+#define HC_WM 10
+#endif
 using namespace xg2;
 using namespace xg2::core;
 
@@ -106,7 +110,7 @@ extern "C" long long xg2hc_check(const char* ebnf, size_t len, const char* root,
                 size_t n = (size_t)(offs[k + 1] - offs[k]);
                 if (n == 0) continue;
                 int want = host_result(chart, t, n);
-                int got = n <= 16 ? core_result<HostStore<6, 10, 16>>(ft, T, c, t, n) : RES_OVERFLOW;
+                int got = n <= 16 ? core_result<HostStore<HC_K, HC_WM, 16>>(ft, T, c, t, n) : RES_OVERFLOW;
                 if (got & RES_OVERFLOW) { ++small_over; got = core_result<HostStore<256, 1024, 1024>>(ft, T, c, t, n); }
                 ++checked;
                 if (got != want) {
