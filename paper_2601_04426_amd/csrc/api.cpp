@@ -575,19 +575,16 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
         }
 
         std::stable_sort(chunks.begin(), chunks.end(), [](const uint4& a, const uint4& b) { return a.w > b.w; });
-        // everything the device needs goes up in two copies: the tables (kept with the cache) and the plan
-        Packer tab, plan;
+        // everything the device needs goes up in one copy and stays with the cache: the tables, the plan, and a
+        // few zeroed words (bit counts, uncertain bits per built plane)
+        std::vector<uint32_t> zeros(8 + build_rows.size(), 0u);
+        Packer tab;
         const size_t o_state = tab.add(ft.dev_state), o_exp = tab.add(ft.exp_list),
                      o_soff = tab.add(site_off), o_stgt = tab.add(site_tgt), o_trans = tab.add(ft.trans),
                      o_cls = tab.add(ft.byte_class_words);
-        const size_t o_chunks = plan.add(chunks), o_pctx = plan.add(plane_ctx), o_items = plan.add(ctx_items), o_wait = plan.add(ctx_wait),
-                     o_wait_off = plan.add(ctx_wait_off), o_rows = plan.add(build_rows);
+        const size_t o_chunks = tab.add(chunks), o_pctx = tab.add(plane_ctx), o_items = tab.add(ctx_items), o_wait = tab.add(ctx_wait),
+                     o_wait_off = tab.add(ctx_wait_off), o_rows = tab.add(build_rows), o_zero = tab.add(zeros);
         tab.stage();
-        plan.stage();
-        DevBuf<unsigned long long> d_counts;
-        d_counts.alloc(2);
-        DevBuf<uint32_t> d_unc;
-        d_unc.alloc(std::max<size_t>(build_rows.size(), 1));
         double host_ms_b = ms_since(t1);
 
         hipEvent_t ev0, ev1, evk0, evk1;
@@ -597,7 +594,6 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
         HIP_CHECK(hipEventCreate(&evk1));
         HIP_CHECK(hipEventRecord(ev0, stream));
         tab.copy(stream);
-        plan.copy(stream);
         cache->d_tables = tab.release_dev();
         cache->dt.state = tab.at<const uint4>(o_state);
         cache->dt.exp_list = tab.at<const uint32_t>(o_exp);
@@ -606,31 +602,31 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
         cache->dt.n_classes = ft.n_classes;
         cache->dt.site_off = tab.at<const uint32_t>(o_soff);
         cache->dt.site_tgt = tab.at<const uint32_t>(o_stgt);
-        HIP_CHECK(hipMemsetAsync(d_counts.p, 0, 2 * sizeof(unsigned long long), stream));
-        HIP_CHECK(hipMemsetAsync(d_unc.p, 0, std::max<size_t>(build_rows.size(), 1) * sizeof(uint32_t), stream));
+        unsigned long long* d_counts = tab.at<unsigned long long>(o_zero);
+        uint32_t* d_unc = tab.at<uint32_t>(o_zero) + 8;
         HIP_CHECK(hipMemsetAsync(S.count, 0, sizeof(uint32_t), stream));
         BuildPlan P{};
-        P.chunk = plan.at<const uint4>(o_chunks); P.n_chunks = (uint32_t)chunks.size();
-        P.plane_ctx = plan.at<const uint4>(o_pctx);
-        P.ctx_items = plan.at<const uint32_t>(o_items);
-        P.ctx_wait = plan.at<const uint2>(o_wait); P.ctx_wait_off = plan.at<const uint32_t>(o_wait_off);
-        P.plane_ptr = plan.at<uint32_t*>(o_rows);
+        P.chunk = tab.at<const uint4>(o_chunks); P.n_chunks = (uint32_t)chunks.size();
+        P.plane_ctx = tab.at<const uint4>(o_pctx);
+        P.ctx_items = tab.at<const uint32_t>(o_items);
+        P.ctx_wait = tab.at<const uint2>(o_wait); P.ctx_wait_off = tab.at<const uint32_t>(o_wait_off);
+        P.plane_ptr = tab.at<uint32_t*>(o_rows);
         P.follow_filter = follow ? 1u : 0u;
-        uint32_t* const* d_rows_p = plan.at<uint32_t*>(o_rows);
+        uint32_t* const* d_rows_p = tab.at<uint32_t*>(o_rows);
         HIP_CHECK(hipEventRecord(evk0, stream));
         if (!build.empty()) launch_build(cache->dt, V.dv, P, S, stream);
         HIP_CHECK(hipEventRecord(evk1, stream));
         if (!build.empty()) {
             launch_build_slow(cache->dt, V.dv, P, S, stream);
-            launch_popcount(d_rows_p, (uint32_t)build_rows.size(), V.W, d_counts.p, d_unc.p, stream);
+            launch_popcount(d_rows_p, (uint32_t)build_rows.size(), V.W, d_counts, d_unc, stream);
         }
         HIP_CHECK(hipEventRecord(ev1, stream));
         uint32_t slow_counts[2] = {0, 0};
         unsigned long long bit_counts[2] = {0, 0};
         HIP_CHECK(hipMemcpyAsync(slow_counts, S.count, sizeof(slow_counts), hipMemcpyDeviceToHost, stream));
-        HIP_CHECK(hipMemcpyAsync(bit_counts, d_counts.p, sizeof(bit_counts), hipMemcpyDeviceToHost, stream));
+        HIP_CHECK(hipMemcpyAsync(bit_counts, d_counts, sizeof(bit_counts), hipMemcpyDeviceToHost, stream));
         std::vector<uint32_t> unc_counts(build_rows.size(), 0);
-        if (!build_rows.empty()) HIP_CHECK(hipMemcpyAsync(unc_counts.data(), d_unc.p, build_rows.size() * sizeof(uint32_t), hipMemcpyDeviceToHost, stream));
+        if (!build_rows.empty()) HIP_CHECK(hipMemcpyAsync(unc_counts.data(), d_unc, build_rows.size() * sizeof(uint32_t), hipMemcpyDeviceToHost, stream));
         HIP_CHECK(hipStreamSynchronize(stream));
         HIP_CHECK(hipGetLastError());
         float dev_ms = 0.f, kern_ms = 0.f;

@@ -29,13 +29,13 @@ struct DevVocab {                        // byte-sorted vocabulary in HBM
 };
 
 // Work plan of one cache build.  Chunk c covers sorted ranks [chunk[c].y, chunk[c].z) of plane chunk[c].x
-// (at most kBuildChunk tokens, all with a first byte the plane's start set can read); one workgroup per
-// chunk.  plane_ctx[k] = {first item, number of items, first wait offset, H} describes the closed start
+// (at most kBuildChunk tokens, all with a first byte the plane's start set can read); the workgroups of a
+// persistent grid take chunks round-robin.  plane_ctx[k] = {first item, number of items, first wait offset, H} describes the closed start
 // set of plane k as a scan context (H = 1: the position alone; H = 2: the position inside one level of
 // referencing rule).  ctx_wait holds, set after set, what the waiting items wait for as pairs
 // {rule, state reference of the target | origin << 21}; ctx_wait_off counts pairs.
 #ifndef XG2_BUILD_CHUNK
-#define XG2_BUILD_CHUNK 512
+#define XG2_BUILD_CHUNK 256
 #endif
 constexpr uint32_t kBuildChunk = XG2_BUILD_CHUNK;
 struct BuildPlan {

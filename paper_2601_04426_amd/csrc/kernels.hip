@@ -6,6 +6,8 @@
 //                  against the full Earley context                      (section 3.4, runtime part)
 //   k_apply_*      logits of disallowed tokens := -infinity, in place    (section 2.1)
 // No MFMA: nothing here is a contraction.  All device writes are vector stores or LDS/L2 atomics.
+#include <algorithm>
+
 #include "device.hpp"
 #include "earley_core.hpp"
 
@@ -66,11 +68,7 @@ struct GlobalStore {
 #define XG2_BUILD_K 6
 #define XG2_BUILD_WM 10
 #endif
-#ifndef XG2_BUILD_WAVES
-#define XG2_BUILD_WAVES 4
-#endif
 constexpr int BUILD_K = XG2_BUILD_K, BUILD_WM = XG2_BUILD_WM;   // item-list capacities of the LDS path (tuning knobs)
-constexpr int BUILD_WAVES = XG2_BUILD_WAVES;
 using BuildStore = LdsStore<BUILD_K, BUILD_WM>;
 
 __device__ __forceinline__ void push_overflow(const SlowScratch& S, uint32_t a, uint32_t b) {
@@ -96,89 +94,113 @@ __device__ __forceinline__ void store_class(const BuildPlan& P, uint32_t p, uint
     else if (res & RES_EARLY) atomicOr(row + W + (id >> 5), 1u << (id & 31));
 }
 
-// One workgroup per chunk of sorted ranks of one plane, in two phases.
+// A persistent grid of single-wave workgroups: workgroup g handles chunks g, g + grid, g + 2 grid, ...
+// (sorted ranks of one plane each; the host puts the long ones first), each in phases, so that the long
+// divergent steps of the recogniser run on full waves instead of on the few lanes that need them.
 // Phase 1 (only when the plane's start set is a single item whose state has byte edges only): every lane
 // walks its token through the automaton, one table load per byte.  A token that dies is rejected, one that
-// reaches its end is accepted; one that reaches a state which predicts or completes is put on the
-// workgroup's deferred list.  Phase 2: the waves take the deferred tokens (or, for the other planes, all
-// tokens of the chunk) 64 at a time and run the Earley recogniser on them, so that its long divergent
-// steps run on full waves instead of on the few lanes of each wave that need them.
-__global__ __launch_bounds__(64 * BUILD_WAVES) void k_build(DevTables T, DevVocab Vd, BuildPlan P, SlowScratch S) {
-    __shared__ uint32_t lds[BUILD_WAVES * BuildStore::SLOTS * 64];
+// reaches its end is accepted; one that reaches a state which predicts or completes goes on the deferred
+// list.  Phase 2: the deferred tokens (for the other planes: all tokens of the chunk), 64 at a time,
+// through the Earley recogniser.  Tokens that leave the outermost rule early and then die need the second,
+// follow-language run; they are collected across chunks as (plane, rank) pairs and run 64 at a time too.
+__device__ __forceinline__ void follow_batch(const DevTables& T, const DevVocab& Vd, const BuildPlan& P, const SlowScratch& S,
+                                             const uint32_t* cls_words, const uint32_t* f_plane, const uint32_t* f_rank,
+                                             uint32_t first, uint32_t count, uint32_t lane, BuildStore& st) {
+    if (lane < count) {
+        const uint32_t p = f_plane[first + lane], rank = f_rank[first + lane];
+        const DevCtx C = position_ctx(P, p);
+        const int n = (int)(Vd.off[rank + 1] - Vd.off[rank]);
+        RegBytes tok;
+        tok.v = Vd.tok16[rank];
+        st.reset();
+        const int res = scan_token<BuildStore, true>(T, cls_words, C, tok, n, st);
+        if (res & RES_OVERFLOW) push_overflow(S, p, rank);
+        else if (res & RES_ALIVE) store_class(P, p, Vd.W, Vd.perm[rank], RES_EARLY);   // some context can take the rest: uncertain
+    }
+}
+
+__global__ __launch_bounds__(64) void k_build(DevTables T, DevVocab Vd, BuildPlan P, SlowScratch S) {
+    __shared__ uint32_t lds[BuildStore::SLOTS * 64];
     __shared__ uint32_t cls_words[64];
     __shared__ uint32_t deferred[kBuildChunk];
-    __shared__ uint32_t n_deferred, n_taken;
-    if (threadIdx.x < 64) cls_words[threadIdx.x] = T.byte_class_words[threadIdx.x];
-    if (threadIdx.x == 0) { n_deferred = 0; n_taken = 0; }
-    __syncthreads();
-    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const uint4 chunk = P.chunk[blockIdx.x];                    // one descriptor per workgroup
-    const uint32_t p = chunk.x;
-    const DevCtx C = position_ctx(P, p);
-    const uint32_t item0 = C.items[0];
-    const bool walkable = C.n_items == 1 && (item0 & (F_BYTE | F_REF | F_FINAL)) == F_BYTE;   // same for the whole workgroup
-    uint32_t n_work = chunk.z - chunk.y;
-    if (walkable) {
-        for (uint32_t rank0 = chunk.y + wave * 64; rank0 < chunk.z; rank0 += 64 * BUILD_WAVES) {
-            const uint32_t rank = rank0 + lane;
-            bool defer = false;
-            if (rank < chunk.z) {
-                const int n = (int)(Vd.off[rank + 1] - Vd.off[rank]);
-                if (n > BuildStore::MAXLEN) defer = true;           // phase 2 hands it to the large-capacity kernel
-                else {
-                    RegBytes tok;
-                    tok.v = Vd.tok16[rank];
-                    uint32_t sid = item0 & SID_MASK;
-                    bool dead = false;
-                    for (int i = 0; i < n; ++i) {
-                        const uint32_t b = tok.next();
-                        const uint32_t cls = (cls_words[b >> 2] >> ((b & 3) * 8)) & 0xFF;
-                        const uint32_t tgt = T.trans[sid * T.n_classes + cls];
-                        if (tgt == NO_TARGET) { dead = true; break; }
-                        if (tgt & (F_REF | F_FINAL)) { defer = true; break; }
-                        sid = tgt & SID_MASK;
+    __shared__ uint32_t f_plane[128], f_rank[128];
+    const uint32_t lane = threadIdx.x;
+    cls_words[lane] = T.byte_class_words[lane];
+    BuildStore st;
+    st.init(lds + lane);
+    uint32_t n_follow = 0;                                          // same in every lane
+    for (uint32_t chunk_idx = blockIdx.x; chunk_idx < P.n_chunks; chunk_idx += gridDim.x) {
+        __syncthreads();                                            // one wave: orders the LDS traffic of the phases
+        const uint4 chunk = P.chunk[chunk_idx];
+        const uint32_t p = chunk.x;
+        const DevCtx C = position_ctx(P, p);
+        const uint32_t item0 = C.items[0];
+        const bool walkable = C.n_items == 1 && (item0 & (F_BYTE | F_REF | F_FINAL)) == F_BYTE;   // same for the whole chunk
+        uint32_t n_work = chunk.z - chunk.y;
+        if (walkable) {
+            n_work = 0;
+            for (uint32_t rank0 = chunk.y; rank0 < chunk.z; rank0 += 64) {
+                const uint32_t rank = rank0 + lane;
+                bool defer = false;
+                if (rank < chunk.z) {
+                    const int n = (int)(Vd.off[rank + 1] - Vd.off[rank]);
+                    if (n > BuildStore::MAXLEN) defer = true;       // phase 2 hands it to the large-capacity kernel
+                    else {
+                        RegBytes tok;
+                        tok.v = Vd.tok16[rank];
+                        uint32_t sid = item0 & SID_MASK;
+                        bool dead = false;
+                        for (int i = 0; i < n; ++i) {
+                            const uint32_t b = tok.next();
+                            const uint32_t cls = (cls_words[b >> 2] >> ((b & 3) * 8)) & 0xFF;
+                            const uint32_t tgt = T.trans[sid * T.n_classes + cls];
+                            if (tgt == NO_TARGET) { dead = true; break; }
+                            if (tgt & (F_REF | F_FINAL)) { defer = true; break; }
+                            sid = tgt & SID_MASK;
+                        }
+                        if (!dead && !defer) store_class(P, p, Vd.W, Vd.perm[rank], RES_ALIVE);
                     }
-                    if (!dead && !defer) store_class(P, p, Vd.W, Vd.perm[rank], RES_ALIVE);
+                }
+                const unsigned long long m = __ballot(defer);
+                if (defer) deferred[n_work + (uint32_t)__popcll(m & ((1ull << lane) - 1))] = rank;
+                n_work += (uint32_t)__popcll(m);
+            }
+            __syncthreads();
+        }
+        for (uint32_t base = 0; base < n_work; base += 64) {
+            const uint32_t idx = base + lane;
+            bool again = false;
+            uint32_t rank = 0;
+            if (idx < n_work) {
+                rank = walkable ? deferred[idx] : chunk.y + idx;
+                const int n = (int)(Vd.off[rank + 1] - Vd.off[rank]);
+                RegBytes tok;
+                tok.v = Vd.tok16[rank];
+                st.reset();
+                const int res = scan_token(T, cls_words, C, tok, n, st);
+                // leaves the rule early and dies: it stays uncertain only if some context can take the rest of the token
+                again = P.follow_filter && !(res & (RES_ALIVE | RES_OVERFLOW)) && (res & RES_EARLY);
+                if (res & RES_OVERFLOW) push_overflow(S, p, rank);
+                else if (!again) store_class(P, p, Vd.W, Vd.perm[rank], res);
+            }
+            const unsigned long long m = __ballot(again);
+            if (m) {
+                if (again) {
+                    const uint32_t at = n_follow + (uint32_t)__popcll(m & ((1ull << lane) - 1));
+                    f_plane[at] = p; f_rank[at] = rank;
+                }
+                n_follow += (uint32_t)__popcll(m);
+                __syncthreads();
+                if (n_follow >= 64) {
+                    n_follow -= 64;
+                    follow_batch(T, Vd, P, S, cls_words, f_plane, f_rank, n_follow, 64, lane, st);
+                    __syncthreads();
                 }
             }
-            const unsigned long long m = __ballot(defer);
-            if (m) {                                                // one LDS atomic per wave
-                const uint32_t leader = (uint32_t)__ffsll((long long)m) - 1;
-                uint32_t base = 0;
-                if (lane == leader) base = atomicAdd(&n_deferred, (uint32_t)__popcll(m));
-                base = __shfl(base, (int)leader);
-                if (defer) deferred[base + (uint32_t)__popcll(m & ((1ull << lane) - 1))] = rank;
-            }
-        }
-        __syncthreads();
-        n_work = n_deferred;
-    }
-    BuildStore st;
-    st.init(lds + wave * BuildStore::SLOTS * 64 + lane);
-    for (;;) {
-        uint32_t batch = 0;
-        if (lane == 0) batch = atomicAdd(&n_taken, 1u);
-        batch = __builtin_amdgcn_readfirstlane(batch);
-        if (batch * 64 >= n_work) break;                            // the counter only grows: every wave gets here
-        const uint32_t idx = batch * 64 + lane;
-        if (idx < n_work) {
-            const uint32_t rank = walkable ? deferred[idx] : chunk.y + idx;
-            const int n = (int)(Vd.off[rank + 1] - Vd.off[rank]);
-            RegBytes tok;
-            tok.v = Vd.tok16[rank];
-            st.reset();
-            int res = scan_token(T, cls_words, C, tok, n, st);
-            if (P.follow_filter && !(res & (RES_ALIVE | RES_OVERFLOW)) && (res & RES_EARLY)) {
-                // leaves the rule early: keep it uncertain only if some context can take the rest of the token
-                st.reset();
-                int res2 = scan_token<BuildStore, true>(T, cls_words, C, tok, n, st);
-                if (res2 & RES_OVERFLOW) res = RES_OVERFLOW;
-                else if (!(res2 & RES_ALIVE)) res = 0;
-            }
-            if (res & RES_OVERFLOW) push_overflow(S, p, rank);
-            else store_class(P, p, Vd.W, Vd.perm[rank], res);
         }
     }
+    __syncthreads();
+    if (n_follow) follow_batch(T, Vd, P, S, cls_words, f_plane, f_rank, 0, n_follow, lane, st);
 }
 
 __global__ __launch_bounds__(64) void k_build_slow(DevTables T, DevVocab Vd, BuildPlan P, SlowScratch S) {
@@ -405,7 +427,14 @@ __global__ __launch_bounds__(256) void k_apply_scalar(E* logits, long long row_s
 
 void launch_build(const DevTables& T, const DevVocab& Vd, const BuildPlan& P, const SlowScratch& S, hipStream_t stream) {
     if (P.n_chunks == 0) return;
-    hipLaunchKernelGGL(k_build, dim3(P.n_chunks), dim3(64 * BUILD_WAVES), 0, stream, T, Vd, P, S);
+    // as many single-wave workgroups as the device can hold at once at full occupancy (32 waves per compute unit)
+    static const uint32_t resident = [] {
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+            cus = 256;
+        return (uint32_t)cus * 32u;
+    }();
+    hipLaunchKernelGGL(k_build, dim3(std::min(P.n_chunks, resident)), dim3(64), 0, stream, T, Vd, P, S);
 }
 
 void launch_build_slow(const DevTables& T, const DevVocab& Vd, const BuildPlan& P, const SlowScratch& S, hipStream_t stream) {
