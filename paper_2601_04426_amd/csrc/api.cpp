@@ -242,13 +242,12 @@ struct FillWorkspace {
     std::mutex mu;
     FillSlot slots[4];
     int next = 0;
-    DevBuf<uint32_t> cand_words, work_list, work_count;
+    DevBuf<uint32_t> cand_words, work_list;
     hipEvent_t t_begin = nullptr, t_end = nullptr;          // around the device work of the latest fill
     bool timed = false;
     void ensure_scratch(size_t words) {
         if (!t_begin) { HIP_CHECK(hipEventCreate(&t_begin)); HIP_CHECK(hipEventCreate(&t_end)); }
         if (cand_words.n < words) { cand_words.alloc(words * 5 / 4); work_list.alloc(words * 5 / 4); }
-        if (!work_count.p) work_count.alloc(1);
     }
     FillSlot& acquire(size_t bytes) {
         FillSlot& s = slots[next];
@@ -425,7 +424,7 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
         else if (pool.vocab.get() != vocab->p.get()) return fail(XG2_EINVAL, "xg2_compile_grammar: pool is bound to another vocabulary");
         std::lock_guard<std::mutex> slow_lock(slow().mu);
         slow().ensure();
-        const SlowScratch S = slow().s;
+        SlowScratch S = slow().s;
         const int R = (int)g.rules.size();
 
         // intern every rule in the pool, referenced rules first
@@ -604,7 +603,7 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
         cache->dt.site_tgt = tab.at<const uint32_t>(o_stgt);
         unsigned long long* d_counts = tab.at<unsigned long long>(o_zero);
         uint32_t* d_unc = tab.at<uint32_t>(o_zero) + 8;
-        HIP_CHECK(hipMemsetAsync(S.count, 0, sizeof(uint32_t), stream));
+        S.count = tab.at<uint32_t>(o_zero) + 4;                   // this call's own overflow counter and flag, zero on arrival
         BuildPlan P{};
         P.chunk = tab.at<const uint4>(o_chunks); P.n_chunks = (uint32_t)chunks.size();
         P.plane_ctx = tab.at<const uint4>(o_pctx);
@@ -616,11 +615,9 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
         HIP_CHECK(hipEventRecord(evk0, stream));
         if (!build.empty()) launch_build(cache->dt, V.dv, P, S, stream);
         HIP_CHECK(hipEventRecord(evk1, stream));
-        if (!build.empty()) {
-            launch_build_slow(cache->dt, V.dv, P, S, stream);
-            launch_popcount(d_rows_p, (uint32_t)build_rows.size(), V.W, d_counts, d_unc, stream);
-        }
-        HIP_CHECK(hipEventRecord(ev1, stream));
+        if (!build.empty()) launch_build_slow(cache->dt, V.dv, P, S, stream);
+        HIP_CHECK(hipEventRecord(ev1, stream));                          // every plane is written
+        if (!build.empty()) launch_popcount(d_rows_p, (uint32_t)build_rows.size(), V.W, d_counts, d_unc, stream);   // statistics
         uint32_t slow_counts[2] = {0, 0};
         unsigned long long bit_counts[2] = {0, 0};
         HIP_CHECK(hipMemcpyAsync(slow_counts, S.count, sizeof(slow_counts), hipMemcpyDeviceToHost, stream));
@@ -634,7 +631,6 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
         HIP_CHECK(hipEventElapsedTime(&kern_ms, evk0, evk1));
         (void)hipEventDestroy(ev0); (void)hipEventDestroy(ev1); (void)hipEventDestroy(evk0); (void)hipEventDestroy(evk1);
         if (slow_counts[1]) {
-            HIP_CHECK(hipMemset(S.count + 1, 0, sizeof(uint32_t)));
             for (const PlaneKey& key : build_keys) pool.rows.erase(key);      // rows of this call hold partial results: forget them
             return fail(XG2_EOVERFLOW, "xg2_compile_grammar: Earley item sets exceeded the large-capacity limit");
         }
@@ -851,12 +847,13 @@ int32_t xg2_fill_next_token_bitmask(xg2_matcher* const* matchers, int32_t B, int
         size_t o_wait = align(o_items + items.size() * sizeof(uint32_t));
         size_t o_woff = align(o_wait + wait.size() * sizeof(uint32_t));
         size_t o_tabs = align(o_woff + wait_off.size() * sizeof(uint32_t));
-        size_t total = align(o_tabs + tables.size() * sizeof(DevTables));
+        size_t o_zero = align(o_tabs + tables.size() * sizeof(DevTables));      // work-list length; overflow-list length and flag
+        size_t total = align(o_zero + 4 * sizeof(uint32_t));
 
         std::lock_guard<std::mutex> ws_lock(fill_ws().mu);
         std::lock_guard<std::mutex> slow_lock(slow().mu);
         slow().ensure();
-        const SlowScratch S = slow().s;
+        SlowScratch S = slow().s;
         FillSlot& slot = fill_ws().acquire(total);
         std::memcpy(slot.host + o_rows, rows.data(), rows.size() * sizeof(FillRow));
         if (!front.empty()) std::memcpy(slot.host + o_front, front.data(), front.size() * sizeof(uint64_t));
@@ -864,6 +861,7 @@ int32_t xg2_fill_next_token_bitmask(xg2_matcher* const* matchers, int32_t B, int
         if (!wait.empty()) std::memcpy(slot.host + o_wait, wait.data(), wait.size() * sizeof(uint32_t));
         if (!wait_off.empty()) std::memcpy(slot.host + o_woff, wait_off.data(), wait_off.size() * sizeof(uint32_t));
         std::memcpy(slot.host + o_tabs, tables.data(), tables.size() * sizeof(DevTables));
+        std::memset(slot.host + o_zero, 0, 4 * sizeof(uint32_t));
         fill_ws().ensure_scratch((size_t)B * V.W);
         HIP_CHECK(hipEventRecord(fill_ws().t_begin, stream));
         HIP_CHECK(hipMemcpyAsync(slot.dev, slot.host, total, hipMemcpyHostToDevice, stream));
@@ -876,10 +874,10 @@ int32_t xg2_fill_next_token_bitmask(xg2_matcher* const* matchers, int32_t B, int
         F.tables = reinterpret_cast<const DevTables*>(slot.dev + o_tabs);
         F.eos_id = (uint32_t)V.eos;
         fill_ws().ensure_scratch((size_t)B * V.W);
-        F.cand_words = fill_ws().cand_words.p; F.work_list = fill_ws().work_list.p; F.work_count = fill_ws().work_count.p;
+        F.cand_words = fill_ws().cand_words.p; F.work_list = fill_ws().work_list.p;
+        F.work_count = reinterpret_cast<uint32_t*>(slot.dev + o_zero);      // zero on arrival, like this call's overflow counter
+        S.count = reinterpret_cast<uint32_t*>(slot.dev + o_zero) + 2;
         F.recheck_blocks = 1024;
-        HIP_CHECK(hipMemsetAsync(F.work_count, 0, sizeof(uint32_t), stream));
-        HIP_CHECK(hipMemsetAsync(S.count, 0, sizeof(uint32_t), stream));
         launch_fill(F, V.dv, bitmask_dev, row_stride_words, S, stream);
         launch_recheck_slow(F, V.dv, bitmask_dev, row_stride_words, S, stream);
         HIP_CHECK(hipGetLastError());

@@ -241,9 +241,9 @@ __global__ __launch_bounds__(256) void k_popcount(const uint32_t* const* plane_p
 }
 
 // ---- fill ------------------------------------------------------------------------------------------
-// k_fill_or: pure streaming.  Thread = one mask word of one row: OR of the accepted planes of the row's
+// k_fill_or: pure streaming.  Workgroup = one row; per mask word the OR of the accepted planes of the row's
 // frontier, plus the end-of-sequence bit; uncertain-and-not-accepted bits go to a scratch word and the
-// word's index to a global work list (one atomic per non-zero word; the list can hold every word).
+// word's index to a global work list (one atomic per wave with candidates; the list can hold every word).
 // k_recheck: each wave takes 64 listed words, spreads their set bits densely over its lanes and runs the
 // Earley routine from the row's context; survivors are OR-ed into the bitmask.
 constexpr int FILL_THREADS = 256;
@@ -262,24 +262,8 @@ __device__ __forceinline__ DevCtx row_ctx(const FillBatch& F, const FillRow& r) 
     return C;
 }
 
-__global__ __launch_bounds__(FILL_THREADS) void k_fill_or(FillBatch F, DevVocab Vd, int32_t* bitmask, long long row_stride) {
-    const uint32_t b = blockIdx.y;
-    const uint32_t w_raw = blockIdx.x * FILL_THREADS + threadIdx.x;
-    const bool in_row = w_raw < Vd.W;
-    const uint32_t w = in_row ? w_raw : Vd.W - 1;                 // lanes past the row redo its last word (same value)
-    const uint32_t front_off = F.rows[b].front_off, front_n = F.rows[b].front_n, flags = F.rows[b].flags;
-    uint32_t acc = 0, unc = 0;
-    if (!(flags & 2u))
-        for (uint32_t k = 0; k < front_n; ++k) {
-            const uint64_t addr = F.front_planes[front_off + k];
-            const uint32_t* row = reinterpret_cast<const uint32_t*>(addr & ~(uint64_t)1);
-            acc |= row[w];
-            if (!(addr & 1)) unc |= row[Vd.W + w];
-        }
-    const uint32_t cand = in_row ? (unc & ~acc) : 0u;
-    if ((flags & 3u) && (F.eos_id >> 5) == w) acc |= 1u << (F.eos_id & 31);
-    if (in_row) bitmask[(long long)b * row_stride + w] = (int32_t)acc;
-    // one atomic per wave: lanes with candidates take consecutive slots of the work list
+// Candidate words of one mask word position, appended to the work list with one atomic per wave.
+__device__ __forceinline__ void list_candidates(const FillBatch& F, uint32_t cand, uint32_t idx) {
     const unsigned long long has = __ballot(cand != 0);
     if (has) {
         const uint32_t lane = threadIdx.x & 63;
@@ -288,9 +272,53 @@ __global__ __launch_bounds__(FILL_THREADS) void k_fill_or(FillBatch F, DevVocab 
         if (lane == leader) base = atomicAdd(F.work_count, (uint32_t)__popcll(has));
         base = __shfl(base, (int)leader);
         if (cand) {
-            const uint32_t idx = b * Vd.W + w;
             F.cand_words[idx] = cand;
             F.work_list[base + (uint32_t)__popcll(has & ((1ull << lane) - 1))] = idx;
+        }
+    }
+}
+
+// One workgroup per row; a thread handles WORDS consecutive mask words per step (4: 16-byte loads and
+// stores, needs W % 4 == 0 and a 16-byte aligned bitmask row; 1: any layout).
+template <int WORDS>
+__global__ __launch_bounds__(FILL_THREADS) void k_fill_or(FillBatch F, DevVocab Vd, int32_t* bitmask, long long row_stride) {
+    const uint32_t b = blockIdx.x;
+    const uint32_t front_off = F.rows[b].front_off, front_n = F.rows[b].front_n, flags = F.rows[b].flags;
+    const uint32_t eos_word = F.eos_id >> 5, eos_bit = 1u << (F.eos_id & 31);
+    uint32_t* out = reinterpret_cast<uint32_t*>(bitmask) + (long long)b * row_stride;
+    const uint32_t n_steps = (Vd.W / WORDS + FILL_THREADS - 1) / FILL_THREADS;        // same for every thread: the ballots see whole waves
+    for (uint32_t step = 0; step < n_steps; ++step) {
+        const uint32_t v = step * FILL_THREADS + threadIdx.x;
+        const bool in_row = v < Vd.W / WORDS;
+        uint32_t acc[WORDS], unc[WORDS];
+#pragma unroll
+        for (int c = 0; c < WORDS; ++c) { acc[c] = 0; unc[c] = 0; }
+        if (in_row && !(flags & 2u))
+            for (uint32_t k = 0; k < front_n; ++k) {
+                const uint64_t addr = F.front_planes[front_off + k];
+                const uint32_t* row = reinterpret_cast<const uint32_t*>(addr & ~(uint64_t)1);
+                if (WORDS == 4) {
+                    const uint4 a = reinterpret_cast<const uint4*>(row)[v];
+                    acc[0] |= a.x; acc[1 % WORDS] |= a.y; acc[2 % WORDS] |= a.z; acc[3 % WORDS] |= a.w;
+                    if (!(addr & 1)) {
+                        const uint4 u = reinterpret_cast<const uint4*>(row + Vd.W)[v];
+                        unc[0] |= u.x; unc[1 % WORDS] |= u.y; unc[2 % WORDS] |= u.z; unc[3 % WORDS] |= u.w;
+                    }
+                } else {
+                    acc[0] |= row[v];
+                    if (!(addr & 1)) unc[0] |= row[Vd.W + v];
+                }
+            }
+#pragma unroll
+        for (int c = 0; c < WORDS; ++c) {
+            const uint32_t w = v * WORDS + c;
+            const uint32_t cand = in_row ? (unc[c] & ~acc[c]) : 0u;
+            if ((flags & 3u) && eos_word == w) acc[c] |= eos_bit;
+            list_candidates(F, cand, b * Vd.W + w);
+        }
+        if (in_row) {
+            if (WORDS == 4) reinterpret_cast<uint4*>(out)[v] = make_uint4(acc[0], acc[1 % WORDS], acc[2 % WORDS], acc[3 % WORDS]);
+            else out[v] = acc[0];
         }
     }
 }
@@ -450,8 +478,9 @@ void launch_popcount(const uint32_t* const* plane_ptr_dev, uint32_t n_pos, uint3
 void launch_fill(const FillBatch& F, const DevVocab& Vd, int32_t* bitmask_dev, int64_t row_stride_words,
                  const SlowScratch& S, hipStream_t stream) {
     if (F.B == 0) return;
-    dim3 grid((Vd.W + FILL_THREADS - 1) / FILL_THREADS, F.B);
-    hipLaunchKernelGGL(k_fill_or, grid, dim3(FILL_THREADS), 0, stream, F, Vd, bitmask_dev, (long long)row_stride_words);
+    const bool wide = Vd.W % 4 == 0 && row_stride_words % 4 == 0 && ((uintptr_t)bitmask_dev & 15) == 0;   // plane rows are 16-byte aligned when W % 4 == 0
+    if (wide) hipLaunchKernelGGL(k_fill_or<4>, dim3(F.B), dim3(FILL_THREADS), 0, stream, F, Vd, bitmask_dev, (long long)row_stride_words);
+    else hipLaunchKernelGGL(k_fill_or<1>, dim3(F.B), dim3(FILL_THREADS), 0, stream, F, Vd, bitmask_dev, (long long)row_stride_words);
     hipLaunchKernelGGL(k_recheck, dim3(F.recheck_blocks), dim3(64 * RECHECK_WAVES), 0, stream, F, Vd, bitmask_dev,
                        (long long)row_stride_words, S);
 }
