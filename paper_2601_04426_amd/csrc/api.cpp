@@ -242,10 +242,11 @@ struct FillWorkspace {
     std::mutex mu;
     FillSlot slots[4];
     int next = 0;
-    DevBuf<uint32_t> cand_words, work_list;
+    DevBuf<uint32_t> cand_words, work_list, row_count;
     hipEvent_t t_begin = nullptr, t_end = nullptr;          // around the device work of the latest fill
     bool timed = false;
-    void ensure_scratch(size_t words) {
+    void ensure_scratch(size_t words, size_t rows) {
+        if (row_count.n < rows) row_count.alloc(rows * 2);
         if (!t_begin) { HIP_CHECK(hipEventCreate(&t_begin)); HIP_CHECK(hipEventCreate(&t_end)); }
         if (cand_words.n < words) { cand_words.alloc(words * 5 / 4); work_list.alloc(words * 5 / 4); }
     }
@@ -575,8 +576,8 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
 
         std::stable_sort(chunks.begin(), chunks.end(), [](const uint4& a, const uint4& b) { return a.w > b.w; });
         // everything the device needs goes up in one copy and stays with the cache: the tables, the plan, and a
-        // few zeroed words (bit counts, uncertain bits per built plane)
-        std::vector<uint32_t> zeros(8 + build_rows.size(), 0u);
+        // few zeroed words (overflow counter and flag, bit counts per built plane)
+        std::vector<uint32_t> zeros(8 + 2 * build_rows.size(), 0u);
         Packer tab;
         const size_t o_state = tab.add(ft.dev_state), o_exp = tab.add(ft.exp_list),
                      o_soff = tab.add(site_off), o_stgt = tab.add(site_tgt), o_trans = tab.add(ft.trans),
@@ -601,8 +602,7 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
         cache->dt.n_classes = ft.n_classes;
         cache->dt.site_off = tab.at<const uint32_t>(o_soff);
         cache->dt.site_tgt = tab.at<const uint32_t>(o_stgt);
-        unsigned long long* d_counts = tab.at<unsigned long long>(o_zero);
-        uint32_t* d_unc = tab.at<uint32_t>(o_zero) + 8;
+        uint32_t* d_counts = tab.at<uint32_t>(o_zero) + 8;
         S.count = tab.at<uint32_t>(o_zero) + 4;                   // this call's own overflow counter and flag, zero on arrival
         BuildPlan P{};
         P.chunk = tab.at<const uint4>(o_chunks); P.n_chunks = (uint32_t)chunks.size();
@@ -617,13 +617,12 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
         HIP_CHECK(hipEventRecord(evk1, stream));
         if (!build.empty()) launch_build_slow(cache->dt, V.dv, P, S, stream);
         HIP_CHECK(hipEventRecord(ev1, stream));                          // every plane is written
-        if (!build.empty()) launch_popcount(d_rows_p, (uint32_t)build_rows.size(), V.W, d_counts, d_unc, stream);   // statistics
+        if (!build.empty()) launch_popcount(d_rows_p, (uint32_t)build_rows.size(), V.W, d_counts, stream);   // statistics
         uint32_t slow_counts[2] = {0, 0};
         unsigned long long bit_counts[2] = {0, 0};
+        std::vector<uint32_t> plane_counts(2 * build_rows.size(), 0);
         HIP_CHECK(hipMemcpyAsync(slow_counts, S.count, sizeof(slow_counts), hipMemcpyDeviceToHost, stream));
-        HIP_CHECK(hipMemcpyAsync(bit_counts, d_counts, sizeof(bit_counts), hipMemcpyDeviceToHost, stream));
-        std::vector<uint32_t> unc_counts(build_rows.size(), 0);
-        if (!build_rows.empty()) HIP_CHECK(hipMemcpyAsync(unc_counts.data(), d_unc, build_rows.size() * sizeof(uint32_t), hipMemcpyDeviceToHost, stream));
+        if (!build_rows.empty()) HIP_CHECK(hipMemcpyAsync(plane_counts.data(), d_counts, plane_counts.size() * sizeof(uint32_t), hipMemcpyDeviceToHost, stream));
         HIP_CHECK(hipStreamSynchronize(stream));
         HIP_CHECK(hipGetLastError());
         float dev_ms = 0.f, kern_ms = 0.f;
@@ -634,7 +633,10 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
             for (const PlaneKey& key : build_keys) pool.rows.erase(key);      // rows of this call hold partial results: forget them
             return fail(XG2_EOVERFLOW, "xg2_compile_grammar: Earley item sets exceeded the large-capacity limit");
         }
-        for (size_t k = 0; k < build_rows.size(); ++k) if (!unc_counts[k]) pool.no_uncertain.insert(build_rows[k]);
+        for (size_t k = 0; k < build_rows.size(); ++k) {
+            bit_counts[0] += plane_counts[2 * k]; bit_counts[1] += plane_counts[2 * k + 1];
+            if (!plane_counts[2 * k + 1]) pool.no_uncertain.insert(build_rows[k]);
+        }
         for (PlaneInfo& pi : cache->planes) pi.no_uncertain = pool.no_uncertain.count(pi.row) != 0;
         if (stats) {
             stats->positions = (int64_t)g.positions.size();
@@ -847,7 +849,7 @@ int32_t xg2_fill_next_token_bitmask(xg2_matcher* const* matchers, int32_t B, int
         size_t o_wait = align(o_items + items.size() * sizeof(uint32_t));
         size_t o_woff = align(o_wait + wait.size() * sizeof(uint32_t));
         size_t o_tabs = align(o_woff + wait_off.size() * sizeof(uint32_t));
-        size_t o_zero = align(o_tabs + tables.size() * sizeof(DevTables));      // work-list length; overflow-list length and flag
+        size_t o_zero = align(o_tabs + tables.size() * sizeof(DevTables));      // overflow-list length and flag
         size_t total = align(o_zero + 4 * sizeof(uint32_t));
 
         std::lock_guard<std::mutex> ws_lock(fill_ws().mu);
@@ -862,7 +864,7 @@ int32_t xg2_fill_next_token_bitmask(xg2_matcher* const* matchers, int32_t B, int
         if (!wait_off.empty()) std::memcpy(slot.host + o_woff, wait_off.data(), wait_off.size() * sizeof(uint32_t));
         std::memcpy(slot.host + o_tabs, tables.data(), tables.size() * sizeof(DevTables));
         std::memset(slot.host + o_zero, 0, 4 * sizeof(uint32_t));
-        fill_ws().ensure_scratch((size_t)B * V.W);
+        fill_ws().ensure_scratch((size_t)B * V.W, (size_t)B);
         HIP_CHECK(hipEventRecord(fill_ws().t_begin, stream));
         HIP_CHECK(hipMemcpyAsync(slot.dev, slot.host, total, hipMemcpyHostToDevice, stream));
         FillBatch F{};
@@ -873,11 +875,10 @@ int32_t xg2_fill_next_token_bitmask(xg2_matcher* const* matchers, int32_t B, int
         F.ctx_wait_off = reinterpret_cast<const uint32_t*>(slot.dev + o_woff);
         F.tables = reinterpret_cast<const DevTables*>(slot.dev + o_tabs);
         F.eos_id = (uint32_t)V.eos;
-        fill_ws().ensure_scratch((size_t)B * V.W);
+        fill_ws().ensure_scratch((size_t)B * V.W, (size_t)B);
         F.cand_words = fill_ws().cand_words.p; F.work_list = fill_ws().work_list.p;
-        F.work_count = reinterpret_cast<uint32_t*>(slot.dev + o_zero);      // zero on arrival, like this call's overflow counter
-        S.count = reinterpret_cast<uint32_t*>(slot.dev + o_zero) + 2;
-        F.recheck_blocks = 1024;
+        F.row_count = fill_ws().row_count.p;
+        S.count = reinterpret_cast<uint32_t*>(slot.dev + o_zero);          // this call's overflow counter and flag, zero on arrival
         launch_fill(F, V.dv, bitmask_dev, row_stride_words, S, stream);
         launch_recheck_slow(F, V.dv, bitmask_dev, row_stride_words, S, stream);
         HIP_CHECK(hipGetLastError());

@@ -56,8 +56,8 @@ constexpr uint32_t kSlowSlots = 2 * kSlowK + 2 * kSlowWM + kSlowMaxLen + 1;
 
 void launch_build(const DevTables& T, const DevVocab& Vd, const BuildPlan& P, const SlowScratch& S, hipStream_t stream);
 void launch_build_slow(const DevTables& T, const DevVocab& Vd, const BuildPlan& P, const SlowScratch& S, hipStream_t stream);
-void launch_popcount(const uint32_t* const* plane_ptr_dev, uint32_t n_pos, uint32_t W, unsigned long long* out2_dev,
-                     uint32_t* unc_out_dev, hipStream_t stream);
+// counts_dev[2p], counts_dev[2p + 1] = set bits of the accepted and of the uncertain row of plane p
+void launch_popcount(const uint32_t* const* plane_ptr_dev, uint32_t n_pos, uint32_t W, uint32_t* counts_dev, hipStream_t stream);
 
 // One row of a fill batch.
 struct FillRow {
@@ -76,11 +76,10 @@ struct FillBatch {
     const uint32_t* ctx_items; const uint2* ctx_wait; const uint32_t* ctx_wait_off;
     const DevTables* tables;
     uint32_t eos_id;
-    // re-check scratch: candidate bits of every mask word, indices of the non-zero ones, their count
+    // re-check scratch: candidate bits of every mask word; per row, the indices of the non-zero ones and their count
     uint32_t* cand_words;                // [B * W]
-    uint32_t* work_list;                 // [B * W]
-    uint32_t* work_count;                // [1], zeroed before the launch
-    uint32_t recheck_blocks;             // grid of the re-check kernel
+    uint32_t* work_list;                 // [B * W], row b's list starts at b * W
+    uint32_t* row_count;                 // [B], written by the union kernel
 };
 void launch_fill(const FillBatch& F, const DevVocab& Vd, int32_t* bitmask_dev, int64_t row_stride_words,
                  const SlowScratch& S, hipStream_t stream);

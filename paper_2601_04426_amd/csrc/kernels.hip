@@ -228,16 +228,21 @@ __global__ __launch_bounds__(64) void k_build_slow(DevTables T, DevVocab Vd, Bui
     }
 }
 
-// Set bits of the freshly built planes: totals in out2[0..1], per-plane uncertain count in unc_out (zeroed before).
-__global__ __launch_bounds__(256) void k_popcount(const uint32_t* const* plane_ptr, uint32_t n_pos, uint32_t W, unsigned long long* out2,
-                                                  uint32_t* unc_out) {
+// Set bits of the freshly built planes: counts[2p] = accepted, counts[2p + 1] = uncertain bits of plane p.
+__global__ __launch_bounds__(256) void k_popcount(const uint32_t* const* plane_ptr, uint32_t n_pos, uint32_t W, uint32_t* counts) {
+    __shared__ uint32_t part[2][4];
     const uint32_t p = blockIdx.x;
     if (p >= n_pos) return;
     const uint32_t* row = plane_ptr[p];
-    unsigned long long a = 0, u = 0;
+    uint32_t a = 0, u = 0;
     for (uint32_t w = threadIdx.x; w < W; w += blockDim.x) { a += __popc(row[w]); u += __popc(row[W + w]); }
     for (int s = 32; s > 0; s >>= 1) { a += __shfl_down(a, s); u += __shfl_down(u, s); }
-    if ((threadIdx.x & 63) == 0) { atomicAdd(out2, a); atomicAdd(out2 + 1, u); if (u) atomicAdd(unc_out + p, (uint32_t)u); }
+    if ((threadIdx.x & 63) == 0) { part[0][threadIdx.x >> 6] = a; part[1][threadIdx.x >> 6] = u; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        counts[2 * p] = part[0][0] + part[0][1] + part[0][2] + part[0][3];
+        counts[2 * p + 1] = part[1][0] + part[1][1] + part[1][2] + part[1][3];
+    }
 }
 
 // ---- fill ------------------------------------------------------------------------------------------
@@ -262,18 +267,19 @@ __device__ __forceinline__ DevCtx row_ctx(const FillBatch& F, const FillRow& r) 
     return C;
 }
 
-// Candidate words of one mask word position, appended to the work list with one atomic per wave.
-__device__ __forceinline__ void list_candidates(const FillBatch& F, uint32_t cand, uint32_t idx) {
+// Candidate bits of one mask word of row b go to the scratch word; the word's index goes to the row's own
+// work list (one LDS atomic per wave with candidates: no atomics on device memory).
+__device__ __forceinline__ void list_candidates(const FillBatch& F, uint32_t* n_listed, uint32_t cand, uint32_t row_base, uint32_t w) {
     const unsigned long long has = __ballot(cand != 0);
     if (has) {
         const uint32_t lane = threadIdx.x & 63;
         const uint32_t leader = (uint32_t)__ffsll((long long)has) - 1;
         uint32_t base = 0;
-        if (lane == leader) base = atomicAdd(F.work_count, (uint32_t)__popcll(has));
+        if (lane == leader) base = atomicAdd(n_listed, (uint32_t)__popcll(has));
         base = __shfl(base, (int)leader);
         if (cand) {
-            F.cand_words[idx] = cand;
-            F.work_list[base + (uint32_t)__popcll(has & ((1ull << lane) - 1))] = idx;
+            F.cand_words[row_base + w] = cand;
+            F.work_list[row_base + base + (uint32_t)__popcll(has & ((1ull << lane) - 1))] = w;
         }
     }
 }
@@ -282,7 +288,10 @@ __device__ __forceinline__ void list_candidates(const FillBatch& F, uint32_t can
 // stores, needs W % 4 == 0 and a 16-byte aligned bitmask row; 1: any layout).
 template <int WORDS>
 __global__ __launch_bounds__(FILL_THREADS) void k_fill_or(FillBatch F, DevVocab Vd, int32_t* bitmask, long long row_stride) {
+    __shared__ uint32_t n_listed;
     const uint32_t b = blockIdx.x;
+    if (threadIdx.x == 0) n_listed = 0;
+    __syncthreads();
     const uint32_t front_off = F.rows[b].front_off, front_n = F.rows[b].front_n, flags = F.rows[b].flags;
     const uint32_t eos_word = F.eos_id >> 5, eos_bit = 1u << (F.eos_id & 31);
     uint32_t* out = reinterpret_cast<uint32_t*>(bitmask) + (long long)b * row_stride;
@@ -314,27 +323,32 @@ __global__ __launch_bounds__(FILL_THREADS) void k_fill_or(FillBatch F, DevVocab 
             const uint32_t w = v * WORDS + c;
             const uint32_t cand = in_row ? (unc[c] & ~acc[c]) : 0u;
             if ((flags & 3u) && eos_word == w) acc[c] |= eos_bit;
-            list_candidates(F, cand, b * Vd.W + w);
+            list_candidates(F, &n_listed, cand, b * Vd.W, w);
         }
         if (in_row) {
             if (WORDS == 4) reinterpret_cast<uint4*>(out)[v] = make_uint4(acc[0], acc[1 % WORDS], acc[2 % WORDS], acc[3 % WORDS]);
             else out[v] = acc[0];
         }
     }
+    __syncthreads();
+    if (threadIdx.x == 0) F.row_count[b] = n_listed;                  // every row writes its count: nothing to clear beforehand
 }
 
 __global__ __launch_bounds__(64 * RECHECK_WAVES) void k_recheck(FillBatch F, DevVocab Vd, int32_t* bitmask, long long row_stride, SlowScratch S) {
     __shared__ uint32_t lds_store[RECHECK_WAVES * FillStore::SLOTS * 64];
     __shared__ uint32_t sh_prefix[RECHECK_WAVES][64], sh_cand[RECHECK_WAVES][64], sh_idx[RECHECK_WAVES][64];
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const uint32_t n_waves = gridDim.x * RECHECK_WAVES;
-    const uint32_t count = *F.work_count;
+    const uint32_t b = blockIdx.x;                                  // one workgroup per row
+    const uint32_t count = F.row_count[b];
+    if (count == 0) return;
+    const uint32_t* list = F.work_list + b * Vd.W;
+    const uint32_t* cands = F.cand_words + b * Vd.W;
     FillStore st;
     st.init(lds_store + wave * FillStore::SLOTS * 64 + lane);
-    for (uint32_t base = (blockIdx.x * RECHECK_WAVES + wave) * RECHECK_CHUNK; base < count; base += n_waves * RECHECK_CHUNK) {
+    for (uint32_t base = wave * RECHECK_CHUNK; base < count; base += RECHECK_WAVES * RECHECK_CHUNK) {
         // RECHECK_CHUNK listed words, one per lane; inclusive prefix sum of their candidate counts
         uint32_t idx = 0, cand = 0;
-        if (lane < RECHECK_CHUNK && base + lane < count) { idx = F.work_list[base + lane]; cand = F.cand_words[idx]; }
+        if (lane < RECHECK_CHUNK && base + lane < count) { idx = list[base + lane]; cand = cands[idx]; }
         uint32_t incl = (uint32_t)__popc(cand);
         for (int d = 1; d < 64; d <<= 1) { uint32_t up = __shfl_up(incl, d); if ((int)lane >= d) incl += up; }
         __builtin_amdgcn_wave_barrier();                           // lanes of the previous round are done reading
@@ -351,8 +365,7 @@ __global__ __launch_bounds__(64 * RECHECK_WAVES) void k_recheck(FillBatch F, Dev
                 uint32_t k = my - (sh_prefix[wave][lo] - (uint32_t)__popc(c));
                 while (k--) c &= c - 1;                            // drop the k lowest set bits
                 const uint32_t bit = __ffs(c) - 1;
-                const uint32_t widx = sh_idx[wave][lo];
-                const uint32_t b = widx / Vd.W, w = widx - b * Vd.W;
+                const uint32_t w = sh_idx[wave][lo];
                 const uint32_t id = w * 32 + bit;
                 const uint32_t rank = Vd.rank[id];
                 if (rank < Vd.n_sorted) {
@@ -469,10 +482,9 @@ void launch_build_slow(const DevTables& T, const DevVocab& Vd, const BuildPlan& 
     hipLaunchKernelGGL(k_build_slow, dim3(S.n_lanes / 64), dim3(64), 0, stream, T, Vd, P, S);
 }
 
-void launch_popcount(const uint32_t* const* plane_ptr_dev, uint32_t n_pos, uint32_t W, unsigned long long* out2_dev,
-                     uint32_t* unc_out_dev, hipStream_t stream) {
+void launch_popcount(const uint32_t* const* plane_ptr_dev, uint32_t n_pos, uint32_t W, uint32_t* counts_dev, hipStream_t stream) {
     if (n_pos == 0) return;
-    hipLaunchKernelGGL(k_popcount, dim3(n_pos), dim3(256), 0, stream, plane_ptr_dev, n_pos, W, out2_dev, unc_out_dev);
+    hipLaunchKernelGGL(k_popcount, dim3(n_pos), dim3(256), 0, stream, plane_ptr_dev, n_pos, W, counts_dev);
 }
 
 void launch_fill(const FillBatch& F, const DevVocab& Vd, int32_t* bitmask_dev, int64_t row_stride_words,
@@ -481,7 +493,7 @@ void launch_fill(const FillBatch& F, const DevVocab& Vd, int32_t* bitmask_dev, i
     const bool wide = Vd.W % 4 == 0 && row_stride_words % 4 == 0 && ((uintptr_t)bitmask_dev & 15) == 0;   // plane rows are 16-byte aligned when W % 4 == 0
     if (wide) hipLaunchKernelGGL(k_fill_or<4>, dim3(F.B), dim3(FILL_THREADS), 0, stream, F, Vd, bitmask_dev, (long long)row_stride_words);
     else hipLaunchKernelGGL(k_fill_or<1>, dim3(F.B), dim3(FILL_THREADS), 0, stream, F, Vd, bitmask_dev, (long long)row_stride_words);
-    hipLaunchKernelGGL(k_recheck, dim3(F.recheck_blocks), dim3(64 * RECHECK_WAVES), 0, stream, F, Vd, bitmask_dev,
+    hipLaunchKernelGGL(k_recheck, dim3(F.B), dim3(64 * RECHECK_WAVES), 0, stream, F, Vd, bitmask_dev,
                        (long long)row_stride_words, S);
 }
 
