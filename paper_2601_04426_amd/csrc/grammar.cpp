@@ -472,17 +472,39 @@ Dfa subset_construction(const Nfa& nfa, int start, int end) {
                 else if (ed.kind == 2) by_rule[ed.rule].push_back(ed.dst);
             }
         // bytes with the same set of matching edges go to the same target
-        std::map<std::vector<int>, std::vector<int>> groups;   // edge indices -> bytes
-        for (int b = 0; b < 256; ++b) {
-            std::vector<int> hit;
-            for (size_t k = 0; k < bedges.size(); ++k) if (bedges[k]->set.test(b)) hit.push_back((int)k);
-            if (!hit.empty()) groups[hit].push_back(b);
-        }
-        for (auto& g : groups) {
-            std::vector<int> seed;
-            for (int k : g.first) seed.push_back(bedges[(size_t)k]->dst);
-            int t = intern(closure(seed));
-            for (int b : g.second) d.bt[cur][(size_t)b] = t;
+        if (bedges.size() <= 64) {
+            // the set of matching edges as a bit mask per byte; equal masks are grouped by a linear search over
+            // the few distinct masks of one state
+            uint64_t masks[256];
+            for (int b = 0; b < 256; ++b) masks[b] = 0;
+            for (size_t k = 0; k < bedges.size(); ++k)
+                for (int b = 0; b < 256; ++b) if (bedges[k]->set.test(b)) masks[b] |= 1ull << k;
+            std::vector<std::pair<uint64_t, int>> seen;             // mask -> target
+            for (int b = 0; b < 256; ++b) {
+                if (!masks[b]) continue;
+                int t = -1;
+                for (auto& sm : seen) if (sm.first == masks[b]) { t = sm.second; break; }
+                if (t < 0) {
+                    std::vector<int> seed;
+                    for (size_t k = 0; k < bedges.size(); ++k) if ((masks[b] >> k) & 1) seed.push_back(bedges[k]->dst);
+                    t = intern(closure(seed));
+                    seen.emplace_back(masks[b], t);
+                }
+                d.bt[cur][(size_t)b] = t;
+            }
+        } else {
+            std::map<std::vector<int>, std::vector<int>> groups;   // edge indices -> bytes
+            for (int b = 0; b < 256; ++b) {
+                std::vector<int> hit;
+                for (size_t k = 0; k < bedges.size(); ++k) if (bedges[k]->set.test(b)) hit.push_back((int)k);
+                if (!hit.empty()) groups[hit].push_back(b);
+            }
+            for (auto& g : groups) {
+                std::vector<int> seed;
+                for (int k : g.first) seed.push_back(bedges[(size_t)k]->dst);
+                int t = intern(closure(seed));
+                for (int b : g.second) d.bt[cur][(size_t)b] = t;
+            }
         }
         for (auto& r : by_rule) { int t = intern(closure(r.second)); d.rt[cur].emplace_back(r.first, t); }
     }
@@ -595,17 +617,22 @@ Dfa minimise_canonical(const Dfa& in, const std::string& rule_name) {
     // byte classes: two bytes are alike if they lead to the same target in every kept state
     std::vector<int> bclass(256, 0);
     int nclass = 1;
-    for (int q : keep) {
-        std::map<std::pair<int, int>, int> remap;
-        for (int b = 0; b < 256; ++b) {
-            int t = in.bt[(size_t)q][(size_t)b];
-            t = t >= 0 ? keep_id[(size_t)t] : -1;
-            auto key = std::make_pair(bclass[(size_t)b], t);
-            auto it = remap.find(key);
-            if (it == remap.end()) it = remap.emplace(key, (int)remap.size()).first;
-            bclass[(size_t)b] = it->second;
+    {
+        struct Split { int old_class, target, new_class; };
+        std::vector<Split> splits;                                  // few per state: searched linearly
+        for (int q : keep) {
+            splits.clear();
+            for (int b = 0; b < 256; ++b) {
+                int t = in.bt[(size_t)q][(size_t)b];
+                t = t >= 0 ? keep_id[(size_t)t] : -1;
+                const int oc = bclass[(size_t)b];
+                int nc = -1;
+                for (const Split& sp : splits) if (sp.old_class == oc && sp.target == t) { nc = sp.new_class; break; }
+                if (nc < 0) { nc = (int)splits.size(); splits.push_back({oc, t, nc}); }
+                bclass[(size_t)b] = nc;
+            }
+            nclass = std::max(nclass, (int)splits.size());
         }
-        nclass = std::max(nclass, (int)remap.size());
     }
     std::vector<int> class_rep((size_t)nclass, 0);
     for (int b = 255; b >= 0; --b) class_rep[(size_t)bclass[(size_t)b]] = b;
@@ -653,7 +680,7 @@ Dfa minimise_canonical(const Dfa& in, const std::string& rule_name) {
             for (auto& e : inv[(size_t)t]) { if (pre[(size_t)e.first].empty()) used_syms.push_back(e.first); pre[(size_t)e.first].push_back(e.second); }
         for (int s : used_syms) {
             std::vector<int>& X = pre[(size_t)s];
-            mark_count.assign(blocks.size(), 0);
+            mark_count.resize(blocks.size(), 0);                  // all zero here: the touched entries are cleared below
             touched.clear();
             for (int q : X) { if (!marked[(size_t)q]) { marked[(size_t)q] = 1; int b = block_of[(size_t)q]; if (mark_count[(size_t)b]++ == 0) touched.push_back(b); } }
             for (int Y : touched) {
@@ -670,35 +697,31 @@ Dfa minimise_canonical(const Dfa& in, const std::string& rule_name) {
                 in_work.push_back(1);
                 work.push_back(nb);                              // Y keeps the larger half (and stays queued if it was)
             }
+            for (int Y : touched) mark_count[(size_t)Y] = 0;
             for (int q : X) marked[(size_t)q] = 0;
             X.clear();
         }
     }
-    // quotient automaton
+    // quotient automaton, renamed breadth-first on the way: out-edges by ascending byte, then by rule
     int nb = (int)blocks.size();
-    Dfa quo;
-    for (int b = 0; b < nb; ++b) quo.add(in.fin[(size_t)keep[(size_t)blocks[(size_t)b][0]]]);
-    for (int b = 0; b < nb; ++b) {
-        int i = blocks[(size_t)b][0];
-        for (int c = 0; c < 256; ++c) { int t = delta[(size_t)i * nsym + bclass[(size_t)c]]; quo.bt[(size_t)b][(size_t)c] = t >= 0 ? block_of[(size_t)t] : -1; }
-        for (size_t r = 0; r < rule_syms.size(); ++r) { int t = delta[(size_t)i * nsym + nclass + (int)r]; if (t >= 0) quo.rt[(size_t)b].emplace_back(rule_syms[r], block_of[(size_t)t]); }
-    }
-    quo.start = block_of[(size_t)keep_id[(size_t)in.start]];
-    // canonical renaming
-    std::vector<int> ident((size_t)nb, -1), order{quo.start};
-    ident[(size_t)quo.start] = 0;
+    const int start_block = block_of[(size_t)keep_id[(size_t)in.start]];
+    auto byte_target = [&](int b, int c) { int t = delta[(size_t)blocks[(size_t)b][0] * nsym + bclass[(size_t)c]]; return t >= 0 ? block_of[(size_t)t] : -1; };
+    auto rule_target = [&](int b, size_t r) { int t = delta[(size_t)blocks[(size_t)b][0] * nsym + nclass + (int)r]; return t >= 0 ? block_of[(size_t)t] : -1; };
+    std::vector<int> ident((size_t)nb, -1), order{start_block};
+    ident[(size_t)start_block] = 0;
     for (size_t k = 0; k < order.size(); ++k) {
         int q = order[k];
         auto visit = [&](int t) { if (t >= 0 && ident[(size_t)t] < 0) { ident[(size_t)t] = (int)order.size(); order.push_back(t); } };
-        for (int c = 0; c < 256; ++c) visit(quo.bt[(size_t)q][(size_t)c]);
-        for (auto& r : quo.rt[(size_t)q]) visit(r.second);
+        int last = -2;
+        for (int c = 0; c < 256; ++c) { int t = byte_target(q, c); if (t != last) { visit(t); last = t; } }
+        for (size_t r = 0; r < rule_syms.size(); ++r) visit(rule_target(q, r));
     }
     Dfa out;
-    for (int q : order) out.add(quo.fin[(size_t)q]);
+    for (int q : order) out.add(in.fin[(size_t)keep[(size_t)blocks[(size_t)q][0]]]);
     for (size_t k = 0; k < order.size(); ++k) {
         int q = order[k];
-        for (int c = 0; c < 256; ++c) { int t = quo.bt[(size_t)q][(size_t)c]; out.bt[k][(size_t)c] = t >= 0 ? ident[(size_t)t] : -1; }
-        for (auto& r : quo.rt[(size_t)q]) out.rt[k].emplace_back(r.first, ident[(size_t)r.second]);
+        for (int c = 0; c < 256; ++c) { int t = byte_target(q, c); out.bt[k][(size_t)c] = t >= 0 ? ident[(size_t)t] : -1; }
+        for (size_t r = 0; r < rule_syms.size(); ++r) { int t = rule_target(q, r); if (t >= 0) out.rt[k].emplace_back(rule_syms[r], ident[(size_t)t]); }
     }
     out.start = 0;
     return out;

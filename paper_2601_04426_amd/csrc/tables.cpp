@@ -66,6 +66,8 @@ FlatTables flatten(const Grammar& g) {
     const size_t n = t.state_info.size();
     std::vector<uint32_t> cls(256, 0);
     std::vector<int64_t> row(256);
+    struct Split { uint32_t old_class; int64_t target; uint32_t new_class; };
+    std::vector<Split> splits;
     for (size_t sid = 0; sid < n; ++sid) {
         const StateInfo& si = t.state_info[sid];
         if (!(si.counts & 0xFFFF)) continue;
@@ -74,8 +76,15 @@ FlatTables flatten(const Grammar& g) {
             const ByteEdge& e = t.byte_edges[si.byte_off + k];
             for (uint32_t b = e.lohi & 0xFF; b <= ((e.lohi >> 8) & 0xFF); ++b) row[b] = e.tgt;
         }
-        std::map<std::pair<uint32_t, int64_t>, uint32_t> remap;
-        for (int b = 0; b < 256; ++b) cls[(size_t)b] = remap.emplace(std::make_pair(cls[(size_t)b], row[(size_t)b]), (uint32_t)remap.size()).first->second;
+        splits.clear();                                             // few per state: searched linearly
+        for (int b = 0; b < 256; ++b) {
+            const uint32_t oc = cls[(size_t)b];
+            const int64_t tg = row[(size_t)b];
+            int nc = -1;
+            for (const Split& sp : splits) if (sp.old_class == oc && sp.target == tg) { nc = (int)sp.new_class; break; }
+            if (nc < 0) { nc = (int)splits.size(); splits.push_back({oc, tg, (uint32_t)nc}); }
+            cls[(size_t)b] = (uint32_t)nc;
+        }
     }
     t.n_classes = *std::max_element(cls.begin(), cls.end()) + 1;
     if (t.n_classes > 256) throw std::logic_error("more byte classes than bytes");
