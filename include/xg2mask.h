@@ -148,6 +148,11 @@ int32_t xg2_matcher_create(const xg2_mask_cache*, xg2_matcher** out);
 int32_t xg2_matcher_create_host(const xg2_grammar*, const xg2_vocab*, xg2_matcher** out);
 void    xg2_matcher_destroy(xg2_matcher*);
 int32_t xg2_matcher_accept_token(xg2_matcher*, int32_t token_id);
+/* One token for each of B matchers (the sampled tokens of a decoding step; section 3.4: the parser traces
+ * the output).  token_ids[b] < 0 skips matcher b.  status_host[b] receives what xg2_matcher_accept_token
+ * would have returned for matcher b; the call itself fails only on bad arguments.  The matchers must be
+ * distinct; several host threads share the work.                                                    */
+int32_t xg2_matcher_accept_tokens(xg2_matcher* const* matchers, const int32_t* token_ids, int32_t B, int32_t* status_host);
 int32_t xg2_matcher_reset(xg2_matcher*);
 int32_t xg2_matcher_is_terminated(const xg2_matcher*, int32_t* out);
 /* Position indices (into the grammar's position list) of the scannable items of the current

@@ -24,7 +24,7 @@ EXPORTS = [
     "xg2_grammar_describe", "xg2_grammar_num_positions", "xg2_pool_create", "xg2_pool_destroy", "xg2_pool_stats",
     "xg2_compile_grammar", "xg2_mask_cache_destroy", "xg2_mask_cache_num_positions", "xg2_mask_cache_num_planes",
     "xg2_mask_cache_plane_info", "xg2_mask_cache_find_plane", "xg2_mask_cache_get_planes", "xg2_matcher_create", "xg2_matcher_create_host", "xg2_matcher_destroy",
-    "xg2_matcher_accept_token", "xg2_matcher_reset", "xg2_matcher_is_terminated", "xg2_matcher_frontier",
+    "xg2_matcher_accept_token", "xg2_matcher_accept_tokens", "xg2_matcher_reset", "xg2_matcher_is_terminated", "xg2_matcher_frontier",
     "xg2_fill_next_token_bitmask", "xg2_fill_last_device_us", "xg2_apply_token_bitmask",
 ]
 
@@ -85,6 +85,7 @@ def _load() -> ctypes.CDLL:
     L.xg2_matcher_create_host.argtypes = [vp, vp, pvp]
     L.xg2_matcher_destroy.argtypes = [vp]
     L.xg2_matcher_accept_token.argtypes = [vp, i32]
+    L.xg2_matcher_accept_tokens.argtypes = [vp, vp, i32, vp]
     L.xg2_matcher_reset.argtypes = [vp]
     L.xg2_matcher_is_terminated.argtypes = [vp, ctypes.POINTER(i32)]
     L.xg2_matcher_frontier.argtypes = [vp, vp, i32, ctypes.POINTER(i32), ctypes.POINTER(i32)]
@@ -266,6 +267,15 @@ class MatcherBatch:
 
     def __len__(self):
         return len(self.matchers)
+
+    def accept_tokens(self, token_ids) -> np.ndarray:
+        """One token per matcher (negative = skip); returns the int32 status of every matcher."""
+        ids = np.ascontiguousarray(token_ids, dtype=np.int32)
+        if ids.shape != (len(self.matchers),):
+            raise ValueError("one token id per matcher expected")
+        status = np.zeros(len(self.matchers), dtype=np.int32)
+        _check(lib.xg2_matcher_accept_tokens(self.arr, ids.ctypes.data, len(self.matchers), status.ctypes.data))
+        return status
 
 
 def fill_next_token_bitmask(matchers, bitmask_ptr: int, row_stride_words: int, stream: int = 0) -> None:

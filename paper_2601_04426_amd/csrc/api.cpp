@@ -12,6 +12,7 @@
 #include <mutex>
 #include <numeric>
 #include <string>
+#include <thread>
 #include <unordered_map>
 #include <unordered_set>
 #include <vector>
@@ -737,6 +738,21 @@ int32_t xg2_matcher_accept_token(xg2_matcher* m, int32_t token_id) {
         if (!M.chart.advance(M.vocab->tok(token_id), M.vocab->len(token_id))) return fail(XG2_EREJECTED, "token is not allowed here");
         return XG2_OK;
     });
+}
+int32_t xg2_matcher_accept_tokens(xg2_matcher* const* matchers, const int32_t* token_ids, int32_t B, int32_t* status_host) {
+    if (B < 0 || (B > 0 && (!matchers || !token_ids || !status_host))) return fail(XG2_EINVAL, "xg2_matcher_accept_tokens: bad argument");
+    for (int32_t b = 0; b < B; ++b) if (!matchers[b]) return fail(XG2_EINVAL, "xg2_matcher_accept_tokens: null matcher");
+    // matchers are independent: a few host threads each take a contiguous share (a handle listed twice would race)
+    const int32_t n_threads = std::max<int32_t>(1, std::min<int32_t>({(int32_t)std::thread::hardware_concurrency(), 8, B / 64}));
+    auto work = [&](int32_t lo, int32_t hi) {
+        for (int32_t b = lo; b < hi; ++b) status_host[b] = token_ids[b] < 0 ? XG2_OK : xg2_matcher_accept_token(matchers[b], token_ids[b]);
+    };
+    if (n_threads == 1) { work(0, B); return XG2_OK; }
+    std::vector<std::thread> pool;
+    const int32_t share = (B + n_threads - 1) / n_threads;
+    for (int32_t t = 0; t < n_threads; ++t) pool.emplace_back(work, std::min(B, t * share), std::min(B, (t + 1) * share));
+    for (std::thread& th : pool) th.join();
+    return XG2_OK;
 }
 int32_t xg2_matcher_reset(xg2_matcher* m) {
     if (!m) return fail(XG2_EINVAL, "xg2_matcher_reset: null matcher");

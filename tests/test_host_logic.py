@@ -115,6 +115,38 @@ def test_host_matcher_follows_the_oracle(xg, index, kw):
         assert m.is_terminated()
 
 
+def test_batched_accept_equals_one_by_one(xg):
+    """xg2_matcher_accept_tokens: same statuses and same matcher states as one call per matcher, threads or not."""
+    cfg = gen.build_config(1)
+    ebnf, root = cfg.grammars[0]
+    g = xg.Grammar(ebnf, root)
+    v = xg.Vocab(cfg.vocab.tokens, 0, [0])
+    seg = gen.Segmenter(cfg.vocab)
+    rng = random.Random(77)
+    B = 200                                                       # enough for several host threads
+    single = [xg.Matcher(grammar=g, vocab=v) for _ in range(B)]
+    batched = [xg.Matcher(grammar=g, vocab=v) for _ in range(B)]
+    batch = xg.MatcherBatch(batched)
+    traces = [seg.segment(cfg.sample_text(rng, 0), rng) + [0] for _ in range(B)]
+    for step in range(12):
+        ids = []
+        for b in range(B):
+            r = rng.random()
+            if r < 0.1:
+                ids.append(-1)                                    # skipped
+            elif r < 0.3:
+                ids.append(rng.randrange(1, cfg.vocab.size))      # mostly rejected
+            else:
+                ids.append(traces[b][min(step, len(traces[b]) - 1)])
+        status = batch.accept_tokens(ids)
+        for b in range(B):
+            want = 0 if ids[b] < 0 else xg.lib.xg2_matcher_accept_token(single[b].h, ids[b])
+            assert status[b] == want, (step, b, ids[b])
+            assert batched[b].is_terminated() == single[b].is_terminated()
+            if not single[b].is_terminated():
+                assert batched[b].frontier() == single[b].frontier()
+
+
 def test_device_calls_fail_loudly_without_a_gpu(xg, has_gpu):
     if has_gpu:
         pytest.skip("a GPU is present")
