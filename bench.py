@@ -120,7 +120,9 @@ def main() -> int:
         # one batched accept for the whole batch; matchers that ended restart on a fresh sentence
         for b in range(B):
             next_ids[b] = traces[b][cursor[b]] if cursor[b] < len(traces[b]) else -1
+        tc = time.perf_counter()
         status = batch.accept_tokens(next_ids)
+        acc["accept_call_ms"].append((time.perf_counter() - tc) * 1e3)
         assert not status.any(), "a trace token was rejected"
         for b in range(B):
             cursor[b] += 1
@@ -131,7 +133,7 @@ def main() -> int:
 
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(5)]
     acc = {"build_device_ms": [], "build_kernel_ms": [], "build_host_ms": [], "fill_us": [], "apply_bf16_us": [],
-           "apply_f32_us": [], "fill_device_us": [], "fill_host_ms": [], "accept_host_ms": [], "masked_frac": []}
+           "apply_f32_us": [], "fill_device_us": [], "fill_host_ms": [], "accept_host_ms": [], "accept_call_ms": [], "masked_frac": []}
     last_stats = None
 
     def step(record: bool):
@@ -219,6 +221,7 @@ def main() -> int:
                    "fill_apply_f32_us": med(acc["fill_device_us"]) + med(acc["apply_f32_us"]),
                    "fill_call_us_incl_host_prep": med(acc["fill_us"]),
                    "fill_host_ms": med(acc["fill_host_ms"]), "accept_host_ms": med(acc["accept_host_ms"]),
+                   "accept_call_ms": med(acc["accept_call_ms"][-args.steps:]),
                    "masked_fraction_last_step": masked / float(B * V)},
         "roofline": {"kernel": "k_build", "bound": "hbm", "achieved": build_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": build_gbs / HBM_PEAK_GBS, "traffic": measured_traffic("k_build", default_workload),
@@ -238,6 +241,26 @@ def main() -> int:
     out["roofline_fill"] = {"kernel": "k_fill_or + k_recheck", "bound": "hbm", "achieved": B * W * 4 / tf / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                             "frac": B * W * 4 / tf / 1e9 / HBM_PEAK_GBS, "traffic": measured_traffic("k_fill_or", default_workload),
                             "accounting": "bitmask write only, over the whole device time of fill (upload, union, re-check)"}
+
+    # just-in-time compilation (section 3.5), beside the main figures: nothing built at compile time, planes built by the
+    # fill calls that first reach them; per-step latency of fill (host + device, synchronised) over fresh sentences
+    jit_cache = xg.compile_grammar(vocab, ebnf, root, stream=stream, jit=True, jit_prebuild=0)
+    jm = [xg.Matcher(jit_cache) for _ in range(B)]
+    jbatch = xg.MatcherBatch(jm)
+    jtr = [seg.segment(cfg.sample_text(rng, 0), rng) + [cfg.vocab.eos_id] for _ in range(B)]
+    jlat = []
+    for stp in range(32):
+        torch.cuda.synchronize()
+        tj = time.perf_counter()
+        xg.fill_next_token_bitmask(jbatch, bitmask.data_ptr(), W, stream)
+        torch.cuda.synchronize()
+        jlat.append((time.perf_counter() - tj) * 1e3)
+        jbatch.accept_tokens([t[stp] if stp < len(t) else -1 for t in jtr])
+    jbuilt, jlaunches, jms = jit_cache.jit_stats()
+    out["jit"] = {"compile_device_ms": jit_cache.stats.device_ms, "planes_total": jit_cache.num_planes(), "planes_built_after_32_steps": jbuilt,
+                  "build_launches_in_fill": jlaunches, "build_device_ms_in_fill": jms,
+                  "fill_step_ms_mean": mean(jlat), "fill_step_ms_max": max(jlat), "fill_step_ms_median": med(jlat)}
+    del jm, jbatch, jit_cache
 
     if not args.no_cpu_baseline:
         import oracle

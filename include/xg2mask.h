@@ -62,11 +62,17 @@ typedef struct xg2_matcher xg2_matcher;
  *   stays uncertain only if the rest of the token is a viable prefix of what can follow that rule
  *   at some reference site of the grammar; otherwise it is rejected at build time (sections 2.2 and
  *   3.3: the reference structure / lookahead is used to reject context-dependent tokens).  Planes
- *   built with the filter are shared between grammars only where the follow sets agree.          */
+ *   built with the filter are shared between grammars only where the follow sets agree.
+ * jit (default 0): 1 = just-in-time compilation (section 3.5): xg2_compile_grammar builds only the
+ *   jit_prebuild planes with the largest estimated cost; every other plane is built by the first
+ *   xg2_fill_next_token_bitmask call whose matchers reach it (looked up in the pool first), on that
+ *   call's stream, before the masks are filled.  The masks are the same either way.             */
 typedef struct xg2_compile_opts {
     int32_t context_depth;
     int32_t merge_equivalent;
     int32_t follow_filter;
+    int32_t jit;
+    int32_t jit_prebuild;
 } xg2_compile_opts;
 
 /* Counters filled by xg2_compile_grammar. */
@@ -129,6 +135,9 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
 void    xg2_mask_cache_destroy(xg2_mask_cache*);
 int32_t xg2_mask_cache_num_positions(const xg2_mask_cache*, int32_t* out);
 int32_t xg2_mask_cache_num_planes(const xg2_mask_cache*, int32_t* out);
+/* Just-in-time caches: planes that hold a row by now, build launches issued by fill calls so far and
+ * their summed device time in milliseconds (each argument may be NULL).                          */
+int32_t xg2_mask_cache_jit_stats(const xg2_mask_cache*, int32_t* n_built, int32_t* n_builds_in_fill, double* device_ms_in_fill);
 /* The representative the planes of index k were built for.  Names stay valid while the cache lives;
  * *parent_rule is NULL (and *parent_state -1) for a plane without context.                        */
 int32_t xg2_mask_cache_plane_info(const xg2_mask_cache*, int32_t k, const char** rule, int32_t* state,
@@ -137,7 +146,8 @@ int32_t xg2_mask_cache_plane_info(const xg2_mask_cache*, int32_t k, const char**
  * no context]; *k = -1 if the cache holds no plane for that combination.                          */
 int32_t xg2_mask_cache_find_plane(const xg2_mask_cache*, const char* rule, int32_t state,
                                   const char* parent_rule, int32_t parent_state, int32_t* k);
-/* Copies plane k to host arrays of W int32 words each (synchronises).                              */
+/* Copies plane k to host arrays of W int32 words each (synchronises).  XG2_EINVAL if the plane has
+ * not been built yet (just-in-time cache).                                                        */
 int32_t xg2_mask_cache_get_planes(const xg2_mask_cache*, int32_t k, int32_t* accepted_host, int32_t* uncertain_host);
 
 /* ---- matchers (one per sequence) ---------------------------------------------------------------

@@ -22,7 +22,7 @@ XG2_F32, XG2_BF16 = 0, 1
 EXPORTS = [
     "xg2_last_error", "xg2_vocab_create", "xg2_vocab_destroy", "xg2_grammar_create", "xg2_grammar_destroy",
     "xg2_grammar_describe", "xg2_grammar_num_positions", "xg2_pool_create", "xg2_pool_destroy", "xg2_pool_stats",
-    "xg2_compile_grammar", "xg2_mask_cache_destroy", "xg2_mask_cache_num_positions", "xg2_mask_cache_num_planes",
+    "xg2_compile_grammar", "xg2_mask_cache_destroy", "xg2_mask_cache_num_positions", "xg2_mask_cache_num_planes", "xg2_mask_cache_jit_stats",
     "xg2_mask_cache_plane_info", "xg2_mask_cache_find_plane", "xg2_mask_cache_get_planes", "xg2_matcher_create", "xg2_matcher_create_host", "xg2_matcher_destroy",
     "xg2_matcher_accept_token", "xg2_matcher_accept_tokens", "xg2_matcher_reset", "xg2_matcher_is_terminated", "xg2_matcher_frontier",
     "xg2_fill_next_token_bitmask", "xg2_fill_last_device_us", "xg2_apply_token_bitmask",
@@ -46,7 +46,8 @@ class CompileStats(ctypes.Structure):
 
 
 class CompileOpts(ctypes.Structure):
-    _fields_ = [("context_depth", ctypes.c_int32), ("merge_equivalent", ctypes.c_int32), ("follow_filter", ctypes.c_int32)]
+    _fields_ = [("context_depth", ctypes.c_int32), ("merge_equivalent", ctypes.c_int32), ("follow_filter", ctypes.c_int32),
+                ("jit", ctypes.c_int32), ("jit_prebuild", ctypes.c_int32)]
 
 
 def _load() -> ctypes.CDLL:
@@ -77,6 +78,7 @@ def _load() -> ctypes.CDLL:
     L.xg2_mask_cache_destroy.argtypes = [vp]
     L.xg2_mask_cache_num_positions.argtypes = [vp, ctypes.POINTER(i32)]
     L.xg2_mask_cache_num_planes.argtypes = [vp, ctypes.POINTER(i32)]
+    L.xg2_mask_cache_jit_stats.argtypes = [vp, ctypes.POINTER(i32), ctypes.POINTER(i32), ctypes.POINTER(ctypes.c_double)]
     L.xg2_mask_cache_plane_info.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(i32),
                                             ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(i32)]
     L.xg2_mask_cache_find_plane.argtypes = [vp, ctypes.c_char_p, i32, ctypes.c_char_p, i32, ctypes.POINTER(i32)]
@@ -177,6 +179,12 @@ class MaskCache:
         _check(lib.xg2_mask_cache_num_positions(self.h, ctypes.byref(n)))
         return n.value
 
+    def jit_stats(self) -> Tuple[int, int, float]:
+        """(planes built so far, build launches issued by fill calls, their summed device time in ms)."""
+        n, calls, ms = ctypes.c_int32(0), ctypes.c_int32(0), ctypes.c_double(0)
+        _check(lib.xg2_mask_cache_jit_stats(self.h, ctypes.byref(n), ctypes.byref(calls), ctypes.byref(ms)))
+        return n.value, calls.value, ms.value
+
     def num_planes(self) -> int:
         n = ctypes.c_int32(0)
         _check(lib.xg2_mask_cache_num_planes(self.h, ctypes.byref(n)))
@@ -208,11 +216,12 @@ class MaskCache:
 
 
 def compile_grammar(vocab: Vocab, ebnf: str, root: str = "root", pool: Optional[Pool] = None, stream: int = 0,
-                    context_depth: int = 2, merge_equivalent: bool = True, follow_filter: bool = True) -> MaskCache:
+                    context_depth: int = 2, merge_equivalent: bool = True, follow_filter: bool = True,
+                    jit: bool = False, jit_prebuild: int = 0) -> MaskCache:
     data = ebnf.encode("utf-8")
     h = ctypes.c_void_p()
     stats = CompileStats()
-    opts = CompileOpts(context_depth, 1 if merge_equivalent else 0, 1 if follow_filter else 0)
+    opts = CompileOpts(context_depth, 1 if merge_equivalent else 0, 1 if follow_filter else 0, 1 if jit else 0, jit_prebuild)
     _check(lib.xg2_compile_grammar(vocab.h, data, len(data), root.encode(), ctypes.byref(opts), pool.h if pool else None,
                                    ctypes.c_void_p(stream), ctypes.byref(h), ctypes.byref(stats)))
     return MaskCache(h, vocab, stats, pool)

@@ -209,8 +209,24 @@ struct PoolImpl {
 };
 
 // ---- mask cache -----------------------------------------------------------------------------------------
-struct PlaneInfo { int32_t rule, state, parent_rule, parent_state; uint32_t* row; bool no_uncertain; };   // the representative it was built for
+struct PlaneInfo {
+    int32_t rule, state, parent_rule, parent_state;         // the representative it is built for
+    uint32_t* row;                                          // accepted row (uncertain at + W words); null until built
+    bool no_uncertain;
+    PlaneKey key;                                           // identity in the pool
+    uint32_t sid; int64_t waiter_sid;                       // start of the build: position, and the waiting parent state or -1
+    uint64_t cost;                                          // estimate of the build work (tokens whose first byte the state reads)
+};
+struct BuildResult {
+    int64_t built = 0, executed = 0, slow = 0, n_accepted = 0, n_uncertain = 0;
+    double host_ms = 0;
+    float device_ms = 0.f, kernel_ms = 0.f;
+};
 struct CacheImpl {
+    bool follow = true;
+    std::vector<uint32_t> site_off, site_tgt;               // per rule: states in which referencing rules continue
+    int64_t n_built = 0, jit_calls = 0;                     // planes holding a row; build launches issued by fill
+    double jit_device_ms = 0;
     std::shared_ptr<VocabImpl> vocab;
     std::shared_ptr<PoolImpl> pool;
     std::shared_ptr<GrammarImpl> gram;
@@ -300,6 +316,179 @@ struct xg2_grammar { std::shared_ptr<GrammarImpl> p; };
 struct xg2_pool { std::shared_ptr<PoolImpl> p; };
 struct xg2_mask_cache { std::shared_ptr<CacheImpl> p; };
 struct xg2_matcher { std::unique_ptr<MatcherImpl> p; };
+
+// Builds the planes `todo` of a cache that do not hold a row yet: rows the pool already has are taken from it, the
+// others are allocated, planned (closed start set, live first-byte ranges, chunks) and classed on the device.
+// with_tables: the packed grammar tables travel in the same upload and stay with the cache (first call only).
+// The caller holds the pool's mutex and the mutex of the large-capacity scratch.  Returns after the kernels have
+// finished.
+int32_t build_planes(CacheImpl& cache, const std::vector<int32_t>& todo, hipStream_t stream, bool with_tables, SlowScratch S, BuildResult& res) {
+    auto t1 = std::chrono::steady_clock::now();
+    PoolImpl& pool = *cache.pool;
+    VocabImpl& V = *cache.vocab;
+    const FlatTables& ft = cache.gram->ft;
+    const size_t row_bytes = (size_t)V.W * 2 * sizeof(uint32_t);
+    std::vector<int32_t> build;                                 // plane indices to class now
+    std::vector<uint32_t*> build_rows;
+    for (int32_t k : todo) {
+        PlaneInfo& pi = cache.planes[(size_t)k];
+        if (pi.row) continue;
+        uint32_t*& row = pool.rows[pi.key];
+        if (row) { pi.row = row; pi.no_uncertain = pool.no_uncertain.count(row) != 0; ++cache.n_built; continue; }   // another grammar built it
+        row = pool.alloc_row(row_bytes, stream);
+        build.push_back(k);
+        build_rows.push_back(row);
+    }
+    if (build.empty() && !with_tables) return XG2_OK;
+
+    // plan: closed start set and live first-byte ranges of every plane to build
+    std::vector<uint32_t> ctx_items, ctx_wait, ctx_wait_off;
+    std::vector<uint4> chunks, plane_ctx;
+    int64_t executed = 0;
+    EarleyChart chart(&ft);
+    for (size_t k = 0; k < build.size(); ++k) {
+        const PlaneInfo& pi = cache.planes[(size_t)build[k]];
+        if (pi.waiter_sid < 0) chart.start(pi.sid);
+        else chart.start_pair(pi.sid, (uint32_t)pi.waiter_sid);
+        const std::vector<ChartSet>& sets = chart.sets();
+        auto loc = [](int32_t o) { return o < 0 ? kRootOrigin : (uint32_t)o; };
+        bool live[257] = {false};
+        const uint32_t item0 = (uint32_t)ctx_items.size();
+        for (const ChartItem& it : sets.back().scan) {
+            ctx_items.push_back(pack_item(ft.ref(it.sid), loc(it.origin)));
+            const StateInfo& si = ft.state_info[it.sid];
+            for (uint32_t e = 0; e < (si.counts & 0xFFFF); ++e) {
+                const ByteEdge& be = ft.byte_edges[si.byte_off + e];
+                for (uint32_t b = be.lohi & 0xFF; b <= ((be.lohi >> 8) & 0xFF); ++b) live[b] = true;
+            }
+        }
+        plane_ctx.push_back(make_uint4(item0, (uint32_t)ctx_items.size() - item0, (uint32_t)ctx_wait_off.size(), (uint32_t)sets.size()));
+        // a start set that is one item with byte edges only is walked as a plain automaton; the others need the
+        // Earley steps from the first byte on and go first, so that the long workgroups do not end the launch
+        const uint32_t heavy = (ctx_items.size() - item0 == 1 && (ctx_items[item0] & (kHasByte | kHasRef | kFinal)) == kHasByte) ? 0u : 1u;
+        for (const ChartSet& cs : sets) {
+            ctx_wait_off.push_back((uint32_t)(ctx_wait.size() / 2));
+            for (const ChartItem& it : cs.wait) chart.push_triples(it, loc(it.origin), ctx_wait);
+        }
+        ctx_wait_off.push_back((uint32_t)(ctx_wait.size() / 2));
+        for (int b = 0; b < 256;) {
+            if (!live[b]) { ++b; continue; }
+            int e = b;
+            while (live[e + 1]) ++e;
+            uint32_t lo = V.fb_start[b], hi = V.fb_start[e + 1];
+            for (uint32_t c = lo; c < hi; c += kBuildChunk) chunks.push_back(make_uint4((uint32_t)k, c, std::min(hi, c + kBuildChunk), heavy));
+            executed += hi - lo;
+            b = e + 1;
+        }
+    }
+    std::stable_sort(chunks.begin(), chunks.end(), [](const uint4& a, const uint4& b) { return a.w > b.w; });
+
+    // everything the device needs goes up in one copy: (the tables,) the plan, and a few zeroed words (overflow
+    // counter and flag, bit counts per built plane).  With the tables the block stays with the cache.
+    std::vector<uint32_t> zeros(8 + 2 * build_rows.size(), 0u);
+    Packer tab;
+    size_t o_state = 0, o_exp = 0, o_soff = 0, o_stgt = 0, o_trans = 0, o_cls = 0;
+    if (with_tables) {
+        o_state = tab.add(ft.dev_state); o_exp = tab.add(ft.exp_list); o_soff = tab.add(cache.site_off); o_stgt = tab.add(cache.site_tgt);
+        o_trans = tab.add(ft.trans); o_cls = tab.add(ft.byte_class_words);
+    }
+    const size_t o_chunks = tab.add(chunks), o_pctx = tab.add(plane_ctx), o_items = tab.add(ctx_items), o_wait = tab.add(ctx_wait),
+                 o_wait_off = tab.add(ctx_wait_off), o_rows = tab.add(build_rows), o_zero = tab.add(zeros);
+    tab.stage();
+    res.host_ms = ms_since(t1);
+
+    hipEvent_t ev0, ev1, evk0, evk1;
+    HIP_CHECK(hipEventCreate(&ev0));
+    HIP_CHECK(hipEventCreate(&ev1));
+    HIP_CHECK(hipEventCreate(&evk0));
+    HIP_CHECK(hipEventCreate(&evk1));
+    HIP_CHECK(hipEventRecord(ev0, stream));
+    tab.copy(stream);
+    if (with_tables) {
+        cache.d_tables = tab.release_dev();
+        cache.dt.state = tab.at<const uint4>(o_state);
+        cache.dt.exp_list = tab.at<const uint32_t>(o_exp);
+        cache.dt.trans = tab.at<const uint32_t>(o_trans);
+        cache.dt.byte_class_words = tab.at<const uint32_t>(o_cls);
+        cache.dt.n_classes = ft.n_classes;
+        cache.dt.site_off = tab.at<const uint32_t>(o_soff);
+        cache.dt.site_tgt = tab.at<const uint32_t>(o_stgt);
+    }
+    uint32_t* d_counts = tab.at<uint32_t>(o_zero) + 8;
+    S.count = tab.at<uint32_t>(o_zero) + 4;                       // this call's own overflow counter and flag, zero on arrival
+    BuildPlan P{};
+    P.chunk = tab.at<const uint4>(o_chunks); P.n_chunks = (uint32_t)chunks.size();
+    P.plane_ctx = tab.at<const uint4>(o_pctx);
+    P.ctx_items = tab.at<const uint32_t>(o_items);
+    P.ctx_wait = tab.at<const uint2>(o_wait); P.ctx_wait_off = tab.at<const uint32_t>(o_wait_off);
+    P.plane_ptr = tab.at<uint32_t*>(o_rows);
+    P.follow_filter = cache.follow ? 1u : 0u;
+    uint32_t* const* d_rows_p = tab.at<uint32_t*>(o_rows);
+    HIP_CHECK(hipEventRecord(evk0, stream));
+    if (!build.empty()) launch_build(cache.dt, V.dv, P, S, stream);
+    HIP_CHECK(hipEventRecord(evk1, stream));
+    if (!build.empty()) launch_build_slow(cache.dt, V.dv, P, S, stream);
+    HIP_CHECK(hipEventRecord(ev1, stream));                              // every plane is written
+    if (!build.empty()) launch_popcount(d_rows_p, (uint32_t)build_rows.size(), V.W, d_counts, stream);   // statistics
+    uint32_t slow_counts[2] = {0, 0};
+    std::vector<uint32_t> plane_counts(2 * build_rows.size(), 0);
+    HIP_CHECK(hipMemcpyAsync(slow_counts, S.count, sizeof(slow_counts), hipMemcpyDeviceToHost, stream));
+    if (!build_rows.empty()) HIP_CHECK(hipMemcpyAsync(plane_counts.data(), d_counts, plane_counts.size() * sizeof(uint32_t), hipMemcpyDeviceToHost, stream));
+    HIP_CHECK(hipStreamSynchronize(stream));
+    HIP_CHECK(hipGetLastError());
+    HIP_CHECK(hipEventElapsedTime(&res.device_ms, ev0, ev1));
+    HIP_CHECK(hipEventElapsedTime(&res.kernel_ms, evk0, evk1));
+    (void)hipEventDestroy(ev0); (void)hipEventDestroy(ev1); (void)hipEventDestroy(evk0); (void)hipEventDestroy(evk1);
+    if (slow_counts[1]) {
+        for (int32_t k : build) pool.rows.erase(cache.planes[(size_t)k].key);      // these rows hold partial results: forget them
+        return fail(XG2_EOVERFLOW, "mask cache build: Earley item sets exceeded the large-capacity limit");
+    }
+    for (size_t k = 0; k < build.size(); ++k) {
+        PlaneInfo& pi = cache.planes[(size_t)build[k]];
+        pi.row = build_rows[k];
+        pi.no_uncertain = plane_counts[2 * k + 1] == 0;
+        if (pi.no_uncertain) pool.no_uncertain.insert(build_rows[k]);
+        res.n_accepted += plane_counts[2 * k]; res.n_uncertain += plane_counts[2 * k + 1];
+    }
+    cache.n_built += (int64_t)build.size();
+    res.built = (int64_t)build.size();
+    res.executed = executed;
+    res.slow = slow_counts[0];
+    return XG2_OK;
+}
+
+// Calls visit(plane index, accepted_only) for every plane the scannable frontier of a matcher needs: the plain plane
+// of items of the root instance (or of every item at context depth 1), else one plane per waiting parent of the item.
+template <class F>
+int32_t for_frontier_planes(const MatcherImpl& M, F&& visit) {
+    const Grammar& G = M.gram->g;
+    const FlatTables& FT = M.gram->ft;
+    for (const ChartItem& it : M.chart.last().scan) {
+        if (G.sid_to_pos[it.sid] < 0) continue;                         // nothing to scan from this item
+        if (it.origin < 0 || M.cache->context_depth == 1) {
+            // the root instance: leaving the rule leaves the grammar, so uncertain tokens are never allowed
+            int32_t plane = M.cache->plain_plane[it.sid];
+            if (plane < 0) return fail(XG2_EINVAL, "xg2_fill_next_token_bitmask: frontier item without a plane");
+            visit(plane, it.origin < 0);
+            continue;
+        }
+        const uint32_t rule = FT.state_info[it.sid].rule_final & 0x7FFFFFFFu;
+        bool any_parent = false;
+        for (const ChartItem& w : M.chart.sets()[(size_t)it.origin].wait) {
+            const StateInfo& wi = FT.state_info[w.sid];
+            for (uint32_t k = 0; k < (wi.counts >> 16); ++k) {
+                const RefEdgeP& e = FT.ref_edges[wi.ref_off + k];
+                if (e.rule != rule) continue;
+                auto pp = M.cache->pair_plane.find(((uint64_t)it.sid << 32) | e.tgt);
+                if (pp == M.cache->pair_plane.end()) return fail(XG2_EINVAL, "xg2_fill_next_token_bitmask: frontier item without a plane");
+                visit(pp->second, false);
+                any_parent = true;
+            }
+        }
+        if (!any_parent) return fail(XG2_EINVAL, "xg2_fill_next_token_bitmask: frontier item without a referencing item");
+    }
+    return XG2_OK;
+}
 
 extern "C" {
 
@@ -408,6 +597,7 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
         const int32_t depth = opts ? opts->context_depth : 2;
         const bool merge = opts ? opts->merge_equivalent != 0 : true;
         const bool follow = opts ? opts->follow_filter != 0 : true;
+        const int32_t jit = (opts && opts->jit) ? std::max(opts->jit_prebuild, 0) : -1;   // -1: build every plane now
         if (depth != 1 && depth != 2) return fail(XG2_EINVAL, "xg2_compile_grammar: context_depth must be 1 or 2");
         hipStream_t stream = (hipStream_t)hip_stream;
         auto t0 = std::chrono::steady_clock::now();
@@ -480,12 +670,7 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
                         else if (fq.canon_id[(size_t)e.tgt] < fq.canon_id[(size_t)it->second.x]) it->second = st;
                     }
 
-        // planes of this grammar; rows missing from the pool are built now
-        const size_t row_bytes = (size_t)V.W * 2 * sizeof(uint32_t);
-        struct ToBuild { uint32_t sid; int64_t waiter_sid; };
-        std::vector<ToBuild> build;
-        std::vector<uint32_t*> build_rows;
-        std::vector<PlaneKey> build_keys;
+        // planes of this grammar
         std::map<PlaneKey, int32_t> local_plane;
         auto plane_for = [&](int rp, int sp_rep, const Site* site) -> int32_t {
             const RuleFsm& fp = g.rules[(size_t)rp];
@@ -494,15 +679,19 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
             if (follow) key[4] = (int64_t)(follow_sig[(size_t)(site ? site->q : rp)] | 1);
             auto lp = local_plane.find(key);
             if (lp != local_plane.end()) return lp->second;
-            uint32_t*& row = pool.rows[key];
-            if (!row) {
-                row = pool.alloc_row(row_bytes, stream);
-                build.push_back({(uint32_t)g.sid(rp, sp_rep), site ? (int64_t)g.sid(site->q, site->waiter) : -1});
-                build_rows.push_back(row);
-                build_keys.push_back(key);
+            const uint32_t sid = (uint32_t)g.sid(rp, sp_rep);
+            // cost estimate: tokens that start with a byte the state itself reads, weighted up when the start set
+            // is more than a plain automaton state
+            const StateInfo& si = ft.state_info[sid];
+            uint64_t cost = 0;
+            for (uint32_t e = 0; e < (si.counts & 0xFFFF); ++e) {
+                const ByteEdge& be = ft.byte_edges[si.byte_off + e];
+                cost += V.fb_start[((be.lohi >> 8) & 0xFF) + 1] - V.fb_start[be.lohi & 0xFF];
             }
+            if ((si.counts >> 16) || (si.rule_final >> 31)) cost *= 4;
             int32_t idx = (int32_t)cache->planes.size();
-            cache->planes.push_back({rp, sp_rep, site ? site->q : -1, site ? site->x : -1, row, false});
+            cache->planes.push_back({rp, sp_rep, site ? site->q : -1, site ? site->x : -1, nullptr, false, key, sid,
+                                     site ? (int64_t)g.sid(site->q, site->waiter) : -1, cost});
             local_plane.emplace(key, idx);
             return idx;
         };
@@ -516,10 +705,10 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
                     cache->pair_plane[((uint64_t)(uint32_t)ps.sid << 32) | (uint32_t)g.sid(st.q, st.x)] = plane_for(ps.rule, sp_rep, &sr);
                 }
         }
-        double host_ms_a = ms_since(t0);
 
         // per rule, the states referencing rules continue in: one per class of indistinguishable states
-        std::vector<uint32_t> site_off{0}, site_tgt;
+        cache->follow = follow;
+        cache->site_off.assign(1, 0);
         if (follow) {
             std::vector<std::vector<uint32_t>> by_rule((size_t)R);
             for (int q = 0; q < R; ++q)
@@ -529,128 +718,35 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
             for (auto& v : by_rule) {
                 std::sort(v.begin(), v.end());
                 v.erase(std::unique(v.begin(), v.end()), v.end());
-                site_tgt.insert(site_tgt.end(), v.begin(), v.end());
-                site_off.push_back((uint32_t)site_tgt.size());
+                cache->site_tgt.insert(cache->site_tgt.end(), v.begin(), v.end());
+                cache->site_off.push_back((uint32_t)cache->site_tgt.size());
             }
-        } else site_off.assign((size_t)R + 1, 0);
+        } else cache->site_off.assign((size_t)R + 1, 0);
 
-        // plan: closed start set and live first-byte ranges of every plane to build
-        auto t1 = std::chrono::steady_clock::now();
-        std::vector<uint32_t> ctx_items, ctx_wait, ctx_wait_off;
-        std::vector<uint4> chunks, plane_ctx;
-        int64_t executed = 0;
-        EarleyChart chart(&ft);
-        for (size_t k = 0; k < build.size(); ++k) {
-            if (build[k].waiter_sid < 0) chart.start(build[k].sid);
-            else chart.start_pair(build[k].sid, (uint32_t)build[k].waiter_sid);
-            const std::vector<ChartSet>& sets = chart.sets();
-            auto loc = [](int32_t o) { return o < 0 ? kRootOrigin : (uint32_t)o; };
-            bool live[257] = {false};
-            const uint32_t item0 = (uint32_t)ctx_items.size();
-            for (const ChartItem& it : sets.back().scan) {
-                ctx_items.push_back(pack_item(ft.ref(it.sid), loc(it.origin)));
-                const StateInfo& si = ft.state_info[it.sid];
-                for (uint32_t e = 0; e < (si.counts & 0xFFFF); ++e) {
-                    const ByteEdge& be = ft.byte_edges[si.byte_off + e];
-                    for (uint32_t b = be.lohi & 0xFF; b <= ((be.lohi >> 8) & 0xFF); ++b) live[b] = true;
-                }
-            }
-            plane_ctx.push_back(make_uint4(item0, (uint32_t)ctx_items.size() - item0, (uint32_t)ctx_wait_off.size(), (uint32_t)sets.size()));
-            // a start set that is one item with byte edges only is walked as a plain automaton; the others need the
-            // Earley steps from the first byte on and go first, so that the long workgroups do not end the launch
-            const uint32_t heavy = (ctx_items.size() - item0 == 1 && (ctx_items[item0] & (kHasByte | kHasRef | kFinal)) == kHasByte) ? 0u : 1u;
-            for (const ChartSet& cs : sets) {
-                ctx_wait_off.push_back((uint32_t)(ctx_wait.size() / 2));
-                for (const ChartItem& it : cs.wait) chart.push_triples(it, loc(it.origin), ctx_wait);
-            }
-            ctx_wait_off.push_back((uint32_t)(ctx_wait.size() / 2));
-            for (int b = 0; b < 256;) {
-                if (!live[b]) { ++b; continue; }
-                int e = b;
-                while (live[e + 1]) ++e;
-                uint32_t lo = V.fb_start[b], hi = V.fb_start[e + 1];
-                for (uint32_t c = lo; c < hi; c += kBuildChunk) chunks.push_back(make_uint4((uint32_t)k, c, std::min(hi, c + kBuildChunk), heavy));
-                executed += hi - lo;
-                b = e + 1;
-            }
+        // which planes to build now: all of them, or (section 3.5) the jit_prebuild most expensive ones
+        std::vector<int32_t> todo((size_t)cache->planes.size());
+        std::iota(todo.begin(), todo.end(), 0);
+        if (jit >= 0 && (size_t)jit < todo.size()) {
+            std::stable_sort(todo.begin(), todo.end(), [&](int32_t a, int32_t b) { return cache->planes[(size_t)a].cost > cache->planes[(size_t)b].cost; });
+            todo.resize((size_t)jit);
+            std::sort(todo.begin(), todo.end());
         }
-
-        std::stable_sort(chunks.begin(), chunks.end(), [](const uint4& a, const uint4& b) { return a.w > b.w; });
-        // everything the device needs goes up in one copy and stays with the cache: the tables, the plan, and a
-        // few zeroed words (overflow counter and flag, bit counts per built plane)
-        std::vector<uint32_t> zeros(8 + 2 * build_rows.size(), 0u);
-        Packer tab;
-        const size_t o_state = tab.add(ft.dev_state), o_exp = tab.add(ft.exp_list),
-                     o_soff = tab.add(site_off), o_stgt = tab.add(site_tgt), o_trans = tab.add(ft.trans),
-                     o_cls = tab.add(ft.byte_class_words);
-        const size_t o_chunks = tab.add(chunks), o_pctx = tab.add(plane_ctx), o_items = tab.add(ctx_items), o_wait = tab.add(ctx_wait),
-                     o_wait_off = tab.add(ctx_wait_off), o_rows = tab.add(build_rows), o_zero = tab.add(zeros);
-        tab.stage();
-        double host_ms_b = ms_since(t1);
-
-        hipEvent_t ev0, ev1, evk0, evk1;
-        HIP_CHECK(hipEventCreate(&ev0));
-        HIP_CHECK(hipEventCreate(&ev1));
-        HIP_CHECK(hipEventCreate(&evk0));
-        HIP_CHECK(hipEventCreate(&evk1));
-        HIP_CHECK(hipEventRecord(ev0, stream));
-        tab.copy(stream);
-        cache->d_tables = tab.release_dev();
-        cache->dt.state = tab.at<const uint4>(o_state);
-        cache->dt.exp_list = tab.at<const uint32_t>(o_exp);
-        cache->dt.trans = tab.at<const uint32_t>(o_trans);
-        cache->dt.byte_class_words = tab.at<const uint32_t>(o_cls);
-        cache->dt.n_classes = ft.n_classes;
-        cache->dt.site_off = tab.at<const uint32_t>(o_soff);
-        cache->dt.site_tgt = tab.at<const uint32_t>(o_stgt);
-        uint32_t* d_counts = tab.at<uint32_t>(o_zero) + 8;
-        S.count = tab.at<uint32_t>(o_zero) + 4;                   // this call's own overflow counter and flag, zero on arrival
-        BuildPlan P{};
-        P.chunk = tab.at<const uint4>(o_chunks); P.n_chunks = (uint32_t)chunks.size();
-        P.plane_ctx = tab.at<const uint4>(o_pctx);
-        P.ctx_items = tab.at<const uint32_t>(o_items);
-        P.ctx_wait = tab.at<const uint2>(o_wait); P.ctx_wait_off = tab.at<const uint32_t>(o_wait_off);
-        P.plane_ptr = tab.at<uint32_t*>(o_rows);
-        P.follow_filter = follow ? 1u : 0u;
-        uint32_t* const* d_rows_p = tab.at<uint32_t*>(o_rows);
-        HIP_CHECK(hipEventRecord(evk0, stream));
-        if (!build.empty()) launch_build(cache->dt, V.dv, P, S, stream);
-        HIP_CHECK(hipEventRecord(evk1, stream));
-        if (!build.empty()) launch_build_slow(cache->dt, V.dv, P, S, stream);
-        HIP_CHECK(hipEventRecord(ev1, stream));                          // every plane is written
-        if (!build.empty()) launch_popcount(d_rows_p, (uint32_t)build_rows.size(), V.W, d_counts, stream);   // statistics
-        uint32_t slow_counts[2] = {0, 0};
-        unsigned long long bit_counts[2] = {0, 0};
-        std::vector<uint32_t> plane_counts(2 * build_rows.size(), 0);
-        HIP_CHECK(hipMemcpyAsync(slow_counts, S.count, sizeof(slow_counts), hipMemcpyDeviceToHost, stream));
-        if (!build_rows.empty()) HIP_CHECK(hipMemcpyAsync(plane_counts.data(), d_counts, plane_counts.size() * sizeof(uint32_t), hipMemcpyDeviceToHost, stream));
-        HIP_CHECK(hipStreamSynchronize(stream));
-        HIP_CHECK(hipGetLastError());
-        float dev_ms = 0.f, kern_ms = 0.f;
-        HIP_CHECK(hipEventElapsedTime(&dev_ms, ev0, ev1));
-        HIP_CHECK(hipEventElapsedTime(&kern_ms, evk0, evk1));
-        (void)hipEventDestroy(ev0); (void)hipEventDestroy(ev1); (void)hipEventDestroy(evk0); (void)hipEventDestroy(evk1);
-        if (slow_counts[1]) {
-            for (const PlaneKey& key : build_keys) pool.rows.erase(key);      // rows of this call hold partial results: forget them
-            return fail(XG2_EOVERFLOW, "xg2_compile_grammar: Earley item sets exceeded the large-capacity limit");
-        }
-        for (size_t k = 0; k < build_rows.size(); ++k) {
-            bit_counts[0] += plane_counts[2 * k]; bit_counts[1] += plane_counts[2 * k + 1];
-            if (!plane_counts[2 * k + 1]) pool.no_uncertain.insert(build_rows[k]);
-        }
-        for (PlaneInfo& pi : cache->planes) pi.no_uncertain = pool.no_uncertain.count(pi.row) != 0;
+        double host_ms_a = ms_since(t0);
+        BuildResult res;
+        int32_t rc = build_planes(*cache, todo, stream, true, S, res);
+        if (rc != XG2_OK) return rc;
         if (stats) {
             stats->positions = (int64_t)g.positions.size();
             stats->unique = (int64_t)cache->planes.size();
-            stats->built = (int64_t)build.size();
-            stats->checks = (int64_t)build.size() * (int64_t)V.n_sorted;
-            stats->executed_checks = executed;
-            stats->slow_path = slow_counts[0];
-            stats->n_accepted = (int64_t)bit_counts[0];
-            stats->n_uncertain = (int64_t)bit_counts[1];
-            stats->host_lower_ms = host_ms_a + host_ms_b;
-            stats->device_ms = dev_ms;
-            stats->kernel_ms = kern_ms;
+            stats->built = res.built;
+            stats->checks = res.built * (int64_t)V.n_sorted;
+            stats->executed_checks = res.executed;
+            stats->slow_path = res.slow;
+            stats->n_accepted = res.n_accepted;
+            stats->n_uncertain = res.n_uncertain;
+            stats->host_lower_ms = host_ms_a + res.host_ms;
+            stats->device_ms = res.device_ms;
+            stats->kernel_ms = res.kernel_ms;
         }
         *out = new xg2_mask_cache{cache};
         return XG2_OK;
@@ -661,6 +757,13 @@ void xg2_mask_cache_destroy(xg2_mask_cache* c) { delete c; }
 int32_t xg2_mask_cache_num_positions(const xg2_mask_cache* c, int32_t* out) {
     if (!c || !out) return fail(XG2_EINVAL, "xg2_mask_cache_num_positions: bad argument");
     *out = (int32_t)c->p->gram->g.positions.size();
+    return XG2_OK;
+}
+int32_t xg2_mask_cache_jit_stats(const xg2_mask_cache* c, int32_t* n_built, int32_t* n_builds_in_fill, double* device_ms_in_fill) {
+    if (!c) return fail(XG2_EINVAL, "xg2_mask_cache_jit_stats: null cache");
+    if (n_built) *n_built = (int32_t)c->p->n_built;
+    if (n_builds_in_fill) *n_builds_in_fill = (int32_t)c->p->jit_calls;
+    if (device_ms_in_fill) *device_ms_in_fill = c->p->jit_device_ms;
     return XG2_OK;
 }
 int32_t xg2_mask_cache_num_planes(const xg2_mask_cache* c, int32_t* out) {
@@ -698,6 +801,7 @@ int32_t xg2_mask_cache_get_planes(const xg2_mask_cache* c, int32_t k, int32_t* a
         if (!c || k < 0 || (size_t)k >= c->p->planes.size()) return fail(XG2_EINVAL, "xg2_mask_cache_get_planes: bad argument");
         const uint32_t W = c->p->vocab->W;
         const uint32_t* row = c->p->planes[(size_t)k].row;
+        if (!row) return fail(XG2_EINVAL, "xg2_mask_cache_get_planes: this plane has not been built yet (cache compiled just in time)");
         HIP_CHECK(hipDeviceSynchronize());
         if (accepted_host) HIP_CHECK(hipMemcpy(accepted_host, row, W * sizeof(uint32_t), hipMemcpyDeviceToHost));
         if (uncertain_host) HIP_CHECK(hipMemcpy(uncertain_host, row + W, W * sizeof(uint32_t), hipMemcpyDeviceToHost));
@@ -797,6 +901,33 @@ int32_t xg2_fill_next_token_bitmask(xg2_matcher* const* matchers, int32_t B, int
         if (row_stride_words < (int64_t)V.W) return fail(XG2_EINVAL, "xg2_fill_next_token_bitmask: row stride smaller than ceil(V/32)");
         V.ensure_device();
 
+        // caches compiled just in time (section 3.5): the planes this step's frontiers need and that hold no row yet
+        // are built first, on the same stream
+        {
+            std::map<CacheImpl*, std::vector<int32_t>> missing;
+            for (int32_t b = 0; b < B; ++b) {
+                const MatcherImpl& M = *matchers[b]->p;
+                if (M.terminated || M.cache->n_built == (int64_t)M.cache->planes.size()) continue;
+                std::vector<int32_t>& v = missing[M.cache.get()];
+                int32_t rc = for_frontier_planes(M, [&](int32_t plane, bool) { if (!M.cache->planes[(size_t)plane].row) v.push_back(plane); });
+                if (rc != XG2_OK) return rc;
+            }
+            for (auto& kv : missing) {
+                std::vector<int32_t>& v = kv.second;
+                std::sort(v.begin(), v.end());
+                v.erase(std::unique(v.begin(), v.end()), v.end());
+                if (v.empty()) continue;
+                CacheImpl& C = *kv.first;
+                std::lock_guard<std::mutex> pool_lock(C.pool->mu);
+                std::lock_guard<std::mutex> slow_lock(slow().mu);
+                slow().ensure();
+                BuildResult res;
+                int32_t rc = build_planes(C, v, stream, false, slow().s, res);
+                if (rc != XG2_OK) return rc;
+                if (res.built) { ++C.jit_calls; C.jit_device_ms += res.device_ms; }     // rows found in the pool cost no launch
+            }
+        }
+
         std::vector<FillRow> rows((size_t)B);
         std::vector<uint64_t> front;
         std::vector<uint32_t> items, wait, wait_off;
@@ -818,39 +949,12 @@ int32_t xg2_fill_next_token_bitmask(xg2_matcher* const* matchers, int32_t B, int
             r.flags = M.chart.last().root_done ? 1u : 0u;
             if (!M.chart.context(ctx)) return fail(XG2_EOVERFLOW, "xg2_fill_next_token_bitmask: parser context too deep");
             size_t f0 = front.size();
-            auto push_plane = [&](int32_t plane, bool accepted_only) {
+            int32_t rc = for_frontier_planes(M, [&](int32_t plane, bool accepted_only) {
                 const PlaneInfo& pi = M.cache->planes[(size_t)plane];
                 uint64_t row = (uint64_t)(uintptr_t)pi.row | ((accepted_only || pi.no_uncertain) ? 1u : 0u);
                 if (std::find(front.begin() + (long)f0, front.end(), row) == front.end()) front.push_back(row);
-            };
-            const Grammar& G = M.gram->g;
-            const FlatTables& FT = M.gram->ft;
-            for (const ChartItem& it : M.chart.last().scan) {
-                if (G.sid_to_pos[it.sid] < 0) continue;                         // nothing to scan from this item
-                if (it.origin < 0 || M.cache->context_depth == 1) {
-                    // the root instance: leaving the rule leaves the grammar, so uncertain tokens are never allowed
-                    int32_t plane = M.cache->plain_plane[it.sid];
-                    if (plane < 0) return fail(XG2_EINVAL, "xg2_fill_next_token_bitmask: frontier item without a plane");
-                    push_plane(plane, it.origin < 0);
-                    continue;
-                }
-                const uint32_t rule = FT.state_info[it.sid].rule_final & 0x7FFFFFFFu;
-                size_t before = front.size();
-                bool any_parent = false;
-                for (const ChartItem& w : M.chart.sets()[(size_t)it.origin].wait) {
-                    const StateInfo& wi = FT.state_info[w.sid];
-                    for (uint32_t k = 0; k < (wi.counts >> 16); ++k) {
-                        const RefEdgeP& e = FT.ref_edges[wi.ref_off + k];
-                        if (e.rule != rule) continue;
-                        auto pp = M.cache->pair_plane.find(((uint64_t)it.sid << 32) | e.tgt);
-                        if (pp == M.cache->pair_plane.end()) return fail(XG2_EINVAL, "xg2_fill_next_token_bitmask: frontier item without a plane");
-                        push_plane(pp->second, false);
-                        any_parent = true;
-                    }
-                }
-                (void)before;
-                if (!any_parent) return fail(XG2_EINVAL, "xg2_fill_next_token_bitmask: frontier item without a referencing item");
-            }
+            });
+            if (rc != XG2_OK) return rc;
             r.front_n = (uint32_t)(front.size() - f0);
             r.item_n = (uint32_t)ctx.items.size();
             r.H = ctx.H;

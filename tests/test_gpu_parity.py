@@ -196,6 +196,42 @@ def test_config5_repetition_planes_and_decode(xg):
     assert n >= 140
 
 
+@pytest.mark.parametrize("index,prebuild,batch,steps,every", [(1, 0, 4, 64, 1), (1, 7, 4, 64, 1), (2, 0, 64, 40, 5), (3, 16, 64, 24, 11)])
+def test_jit_compilation_gives_the_same_masks(xg, index, prebuild, batch, steps, every):
+    """Section 3.5: nothing (or only the costliest planes) built at compile time, the rest by the fill calls that
+    reach them.  Masks equal the oracle's on every checked step; planes built on the way equal the oracle's classes;
+    planes never reached stay unbuilt."""
+    cfg, vocab, va = load(index)
+    ebnf, root = cfg.grammars[0]
+    pool = xg.Pool()
+    cache = xg.compile_grammar(vocab, ebnf, root, pool=pool, stream=_stream(), jit=True, jit_prebuild=prebuild)
+    total = cache.num_planes()
+    assert cache.stats.built == min(prebuild, total) and cache.jit_stats()[0] == min(prebuild, total)
+    orc = oracle.Oracle(ebnf, root)
+    n = run_decode(xg, cfg, vocab, va, cache, orc, batch=batch, steps=steps, seed=70 + index, check_every=every)
+    assert n >= batch * steps // every
+    built, launches, ms = cache.jit_stats()
+    assert min(prebuild, total) < built <= total and launches >= 1 and ms > 0
+    rng = random.Random(index)
+    seen_built = seen_unbuilt = 0
+    for k in rng.sample(range(total), min(total, 60)):
+        pos, parent = cache.plane_info(k)
+        try:
+            acc, unc = cache.get_planes(k)
+        except xg.Xg2Error as e:
+            assert e.code == -1                                # XG2_EINVAL: not built yet
+            seen_unbuilt += 1
+            continue
+        seen_built += 1
+        want_a, want_u = planes_of(orc, pos, va, parent, True)
+        assert np.array_equal(acc, want_a) and np.array_equal(unc, want_u), (pos, parent)
+    assert seen_built > 0
+    # a second cache of the same grammar on the same pool finds every plane the first one built
+    cache2 = xg.compile_grammar(vocab, ebnf, root, pool=pool, stream=_stream(), jit=True, jit_prebuild=0)
+    n2 = run_decode(xg, cfg, vocab, va, cache2, orc, batch=batch, steps=steps, seed=70 + index, check_every=every * 3 + 1)
+    assert n2 > 0 and cache2.jit_stats()[1] == 0 and pool.stats()[0] == built
+
+
 def test_config4_cross_grammar_pool(xg):
     """Reduced cross-grammar workload: planes are built once per distinct structure, later grammars reuse them,
     and what a reusing grammar sees equals what the oracle computes for that grammar alone."""
