@@ -1,9 +1,9 @@
 // gfx950 (CDNA4, wave64) kernels of the token-mask cache path:
 //   k_build        classes of (position, token) pairs by a rule-scoped Earley recogniser, one lane per
 //                  token, item sets in LDS                              (XGrammar-2 section 3.4)
-//   k_build_slow   the same recogniser with large item sets in device memory, for lanes that overflowed
-//   k_fill         union of cached planes over the scannable frontier + re-check of uncertain tokens
-//                  against the full Earley context                      (section 3.4, runtime part)
+//   k_build_slow   the same recogniser with larger item sets (LDS, then device memory), for lanes that overflowed
+//   k_fill_or      union of cached planes over the scannable frontier   (section 3.4, runtime part)
+//   k_recheck      re-check of uncertain tokens against the full Earley context, and its large-capacity twin
 //   k_apply_*      logits of disallowed tokens := -infinity, in place    (section 2.1)
 // No MFMA: nothing here is a contraction.  All device writes are vector stores or LDS/L2 atomics.
 #include <algorithm>
@@ -43,6 +43,27 @@ struct LdsStore {
         return (uint32_t)((j < 8 ? ws_lo >> (8 * j) : ws_hi >> (8 * (j - 8))) & 0xFF);
     }
 };
+
+// The same layout with more room and the set starts in LDS too: the first resort of the large-capacity kernels
+// (one wave per workgroup, 37 KB), before the lists in device memory.
+template <int K_, int WM_, int MAXLEN_>
+struct LdsStoreWide {
+    static constexpr int K = K_, WM = WM_, MAXLEN = MAXLEN_, SLOTS = 2 * K_ + 2 * WM_ + MAXLEN_ + 1;
+    uint32_t* cur; uint32_t* nxt; uint32_t* wait; uint32_t* ws;
+    __device__ void init(uint32_t* base) { cur = base; nxt = base + K * 64; wait = base + 2 * K * 64; ws = base + (2 * K + 2 * WM) * 64; }
+    __device__ uint32_t get_cur(int k) const { return cur[k * 64]; }
+    __device__ void set_cur(int k, uint32_t v) { cur[k * 64] = v; }
+    __device__ uint32_t get_nxt(int k) const { return nxt[k * 64]; }
+    __device__ void set_nxt(int k, uint32_t v) { nxt[k * 64] = v; }
+    __device__ uint32_t wait_rule(int k) const { return wait[k * 128]; }
+    __device__ uint32_t wait_tgt(int k) const { return wait[k * 128 + 64]; }
+    __device__ void set_wait(int k, uint32_t rule, uint32_t tgt) { wait[k * 128] = rule; wait[k * 128 + 64] = tgt; }
+    __device__ void swap() { uint32_t* t = cur; cur = nxt; nxt = t; }
+    __device__ void reset() {}
+    __device__ void set_wstart(int j, uint32_t v) { ws[j * 64] = v; }
+    __device__ uint32_t get_wstart(int j) const { return ws[j * 64]; }
+};
+using MidStore = LdsStoreWide<16, 32, 48>;
 
 // Device memory: word (slot, lane) lives at slot * n_lanes + lane (coalesced across lanes).
 struct GlobalStore {
@@ -203,26 +224,38 @@ __global__ __launch_bounds__(64) void k_build(DevTables T, DevVocab Vd, BuildPla
     if (n_follow) follow_batch(T, Vd, P, S, cls_words, f_plane, f_rank, 0, n_follow, lane, st);
 }
 
+// Both runs of one (plane, token) pair with the lists in `st`: the plain one and, if the token left the outermost
+// rule early and died, the follow-language one.
+template <class S>
+__device__ int classify_slow(const DevTables& T, const DevVocab& Vd, const BuildPlan& P, const DevCtx& C, uint32_t off, int n, S& st) {
+    st.reset();
+    MemBytes tok{Vd.bytes + off};
+    int res = scan_token<S, false, MemBytes>(T, T.byte_class_words, C, tok, n, st);
+    if (P.follow_filter && !(res & (RES_ALIVE | RES_OVERFLOW)) && (res & RES_EARLY)) {
+        st.reset();
+        int res2 = scan_token<S, true, MemBytes>(T, T.byte_class_words, C, tok, n, st);
+        if (res2 & RES_OVERFLOW) res = RES_OVERFLOW;
+        else if (!(res2 & RES_ALIVE)) res = 0;
+    }
+    return res;
+}
+
 __global__ __launch_bounds__(64) void k_build_slow(DevTables T, DevVocab Vd, BuildPlan P, SlowScratch S) {
+    __shared__ uint32_t lds[MidStore::SLOTS * 64];
     const uint32_t gl = blockIdx.x * 64 + threadIdx.x;
     uint32_t count = S.count[0];
     if (count > S.list_cap) count = S.list_cap;
+    MidStore mid;
+    mid.init(lds + threadIdx.x);
     GlobalStore st;
     st.init(S.mem + gl, S.n_lanes);
     for (uint32_t idx = gl; idx < count; idx += S.n_lanes) {
         const uint32_t p = S.list[2 * idx], rank = S.list[2 * idx + 1];
         const uint32_t off = Vd.off[rank];
         const int n = (int)(Vd.off[rank + 1] - off);
-        st.reset();
         DevCtx C = position_ctx(P, p);
-        MemBytes tok{Vd.bytes + off};
-        int res = scan_token<GlobalStore, false, MemBytes>(T, T.byte_class_words, C, tok, n, st);
-        if (P.follow_filter && !(res & (RES_ALIVE | RES_OVERFLOW)) && (res & RES_EARLY)) {
-            st.reset();
-            int res2 = scan_token<GlobalStore, true, MemBytes>(T, T.byte_class_words, C, tok, n, st);
-            if (res2 & RES_OVERFLOW) res = RES_OVERFLOW;
-            else if (!(res2 & RES_ALIVE)) res = 0;
-        }
+        int res = classify_slow(T, Vd, P, C, off, n, mid);           // returns RES_OVERFLOW at once if the token is too long for it
+        if (res & RES_OVERFLOW) res = classify_slow(T, Vd, P, C, off, n, st);
         if (res & RES_OVERFLOW) { atomicOr(S.count + 1, 2u); continue; }
         store_class(P, p, Vd.W, Vd.perm[rank], res);
     }
@@ -385,9 +418,12 @@ __global__ __launch_bounds__(64 * RECHECK_WAVES) void k_recheck(FillBatch F, Dev
 }
 
 __global__ __launch_bounds__(64) void k_recheck_slow(FillBatch F, DevVocab Vd, int32_t* bitmask, long long row_stride, SlowScratch S) {
+    __shared__ uint32_t lds[MidStore::SLOTS * 64];
     const uint32_t gl = blockIdx.x * 64 + threadIdx.x;
     uint32_t count = S.count[0];
     if (count > S.list_cap) count = S.list_cap;
+    MidStore mid;
+    mid.init(lds + threadIdx.x);
     GlobalStore st;
     st.init(S.mem + gl, S.n_lanes);
     for (uint32_t idx = gl; idx < count; idx += S.n_lanes) {
@@ -397,10 +433,14 @@ __global__ __launch_bounds__(64) void k_recheck_slow(FillBatch F, DevVocab Vd, i
         if (rank >= Vd.n_sorted) continue;
         const uint32_t off = Vd.off[rank];
         const int n = (int)(Vd.off[rank + 1] - off);
-        st.reset();
         const DevTables T = F.tables[r.tables_idx];
         MemBytes tok{Vd.bytes + off};
-        int res = scan_token<GlobalStore, false, MemBytes>(T, T.byte_class_words, row_ctx(F, r), tok, n, st);
+        mid.reset();
+        int res = scan_token<MidStore, false, MemBytes>(T, T.byte_class_words, row_ctx(F, r), tok, n, mid);
+        if (res & RES_OVERFLOW) {
+            st.reset();
+            res = scan_token<GlobalStore, false, MemBytes>(T, T.byte_class_words, row_ctx(F, r), tok, n, st);
+        }
         if (res & RES_OVERFLOW) { atomicOr(S.count + 1, 2u); continue; }
         if (res & RES_ALIVE) atomicOr(reinterpret_cast<uint32_t*>(bitmask) + (long long)b * row_stride + (id >> 5), 1u << (id & 31));
     }
