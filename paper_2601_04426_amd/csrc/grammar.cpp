@@ -422,18 +422,38 @@ void build_nfa(const Node& nd, Nfa& nfa, int s, int e, const std::map<std::strin
 }
 
 // ------------------------------------------------------------------------------------------------
-// deterministic automaton with dense byte rows (one rule at a time, so the memory is transient)
+// deterministic automaton with dense rows over byte classes (one rule at a time, so the memory is transient).
+// Bytes of one class behave alike in every state; classes are numbered in the order of their smallest byte, so
+// visiting the classes in ascending order visits targets in the order of ascending bytes.
 struct Dfa {
-    std::vector<std::array<int32_t, 256>> bt;                 // byte -> target or -1
+    int ncls = 1;
+    std::array<uint8_t, 256> cls{};                           // byte -> class
+    std::vector<int32_t> bt;                                  // [state * ncls + class] -> target or -1
     std::vector<std::vector<std::pair<int, int>>> rt;         // (rule decl index, target), sorted by rule
     std::vector<uint8_t> fin;
     int start = 0;
     int add(bool f) {
-        bt.emplace_back(); bt.back().fill(-1);
+        bt.resize(bt.size() + (size_t)ncls, -1);
         rt.emplace_back(); fin.push_back(f ? 1 : 0);
         return (int)fin.size() - 1;
     }
     int n() const { return (int)fin.size(); }
+    int32_t& at(int q, int c) { return bt[(size_t)q * (size_t)ncls + (size_t)c]; }
+    int32_t at(int q, int c) const { return bt[(size_t)q * (size_t)ncls + (size_t)c]; }
+    int32_t byte_target(int q, int b) const { return at(q, cls[(size_t)b]); }
+    // classes from a list of byte sets: two bytes are alike if they are in the same sets
+    void classes_from(const std::vector<ByteSet>& sets) {
+        std::vector<std::vector<uint8_t>> sig(256);
+        for (size_t k = 0; k < sets.size(); ++k)
+            for (int b = 0; b < 256; ++b) if (sets[k].test(b)) { if (sig[(size_t)b].size() <= k / 8) sig[(size_t)b].resize(k / 8 + 1, 0); sig[(size_t)b][k / 8] |= (uint8_t)(1u << (k % 8)); }
+        std::map<std::vector<uint8_t>, int> ids;
+        ncls = 0;
+        for (int b = 0; b < 256; ++b) {
+            auto it = ids.find(sig[(size_t)b]);
+            if (it == ids.end()) it = ids.emplace(sig[(size_t)b], ncls++).first;
+            cls[(size_t)b] = (uint8_t)it->second;
+        }
+    }
 };
 
 Dfa subset_construction(const Nfa& nfa, int start, int end) {
@@ -452,6 +472,16 @@ Dfa subset_construction(const Nfa& nfa, int start, int end) {
         return out;
     };
     Dfa d;
+    {   // byte classes of the whole automaton: the distinct byte sets on its edges
+        std::vector<ByteSet> sets;
+        std::set<std::array<uint64_t, 4>> seen;
+        for (auto& es : nfa.e)
+            for (const NEdge& ed : es)
+                if (ed.kind == 1 && seen.insert({ed.set.w[0], ed.set.w[1], ed.set.w[2], ed.set.w[3]}).second) sets.push_back(ed.set);
+        d.classes_from(sets);
+    }
+    std::vector<int> rep_byte((size_t)d.ncls, 0);
+    for (int b = 255; b >= 0; --b) rep_byte[d.cls[(size_t)b]] = b;
     std::map<std::vector<int>, int> ids;
     std::vector<std::vector<int>> sets;
     auto intern = [&](std::vector<int> S) {
@@ -471,40 +501,22 @@ Dfa subset_construction(const Nfa& nfa, int start, int end) {
                 if (ed.kind == 1) bedges.push_back(&ed);
                 else if (ed.kind == 2) by_rule[ed.rule].push_back(ed.dst);
             }
-        // bytes with the same set of matching edges go to the same target
-        if (bedges.size() <= 64) {
-            // the set of matching edges as a bit mask per byte; equal masks are grouped by a linear search over
-            // the few distinct masks of one state
-            uint64_t masks[256];
-            for (int b = 0; b < 256; ++b) masks[b] = 0;
-            for (size_t k = 0; k < bedges.size(); ++k)
-                for (int b = 0; b < 256; ++b) if (bedges[k]->set.test(b)) masks[b] |= 1ull << k;
-            std::vector<std::pair<uint64_t, int>> seen;             // mask -> target
-            for (int b = 0; b < 256; ++b) {
-                if (!masks[b]) continue;
-                int t = -1;
-                for (auto& sm : seen) if (sm.first == masks[b]) { t = sm.second; break; }
-                if (t < 0) {
-                    std::vector<int> seed;
-                    for (size_t k = 0; k < bedges.size(); ++k) if ((masks[b] >> k) & 1) seed.push_back(bedges[k]->dst);
-                    t = intern(closure(seed));
-                    seen.emplace_back(masks[b], t);
-                }
-                d.bt[cur][(size_t)b] = t;
-            }
-        } else {
-            std::map<std::vector<int>, std::vector<int>> groups;   // edge indices -> bytes
-            for (int b = 0; b < 256; ++b) {
-                std::vector<int> hit;
-                for (size_t k = 0; k < bedges.size(); ++k) if (bedges[k]->set.test(b)) hit.push_back((int)k);
-                if (!hit.empty()) groups[hit].push_back(b);
-            }
-            for (auto& g : groups) {
+        // classes with the same set of matching edges go to the same target
+        std::vector<std::pair<std::vector<int>, int>> seen;        // matching edges -> target: few per state
+        std::vector<int> hit;
+        for (int c = 0; c < d.ncls; ++c) {
+            hit.clear();
+            for (size_t k = 0; k < bedges.size(); ++k) if (bedges[k]->set.test(rep_byte[(size_t)c])) hit.push_back((int)k);
+            if (hit.empty()) continue;
+            int t = -1;
+            for (auto& sm : seen) if (sm.first == hit) { t = sm.second; break; }
+            if (t < 0) {
                 std::vector<int> seed;
-                for (int k : g.first) seed.push_back(bedges[(size_t)k]->dst);
-                int t = intern(closure(seed));
-                for (int b : g.second) d.bt[cur][(size_t)b] = t;
+                for (int k : hit) seed.push_back(bedges[(size_t)k]->dst);
+                t = intern(closure(seed));
+                seen.emplace_back(hit, t);
             }
+            d.at((int)cur, c) = t;
         }
         for (auto& r : by_rule) { int t = intern(closure(r.second)); d.rt[cur].emplace_back(r.first, t); }
     }
@@ -560,6 +572,12 @@ Dfa tagdispatch_automaton(const Node& nd, const std::map<std::string, int>& inde
         }
     }
     Dfa d;
+    {   // every byte of a tag or stop string is a class of its own, all other bytes are one class
+        std::vector<ByteSet> sets;
+        bool used[256] = {false};
+        for (auto& pat : pats) for (unsigned char c : pat) if (!used[c]) { used[c] = true; ByteSet bs; bs.set(c); sets.push_back(bs); }
+        d.classes_from(sets);
+    }
     bool no_stops = nd.stops.empty();
     std::vector<int> state_of(trie.size(), -1);
     for (size_t u = 0; u < trie.size(); ++u) if (trie[u].pat < 0) state_of[u] = d.add(no_stops);
@@ -576,7 +594,7 @@ Dfa tagdispatch_automaton(const Node& nd, const std::map<std::string, int>& inde
         for (int c = 0; c < 256; ++c) {
             int v = go[u][(size_t)c];
             int p = trie[(size_t)v].pat;
-            d.bt[(size_t)state_of[u]][(size_t)c] = p < 0 ? state_of[(size_t)v] : (size_t)p < nd.tags.size() ? after_tag[(size_t)p] : exit_state;
+            d.at(state_of[u], d.cls[(size_t)c]) = p < 0 ? state_of[(size_t)v] : (size_t)p < nd.tags.size() ? after_tag[(size_t)p] : exit_state;
         }
     }
     d.start = state_of[0];
@@ -588,6 +606,7 @@ Dfa tagdispatch_automaton(const Node& nd, const std::map<std::string, int>& inde
 // visited by ascending byte, then by ascending declaration index of the referenced rule.
 Dfa minimise_canonical(const Dfa& in, const std::string& rule_name) {
     int n0 = in.n();
+    const int nc0 = in.ncls;
     std::vector<uint8_t> reach((size_t)n0, 0), live((size_t)n0, 0);
     std::vector<int> stack{in.start};
     reach[(size_t)in.start] = 1;
@@ -595,13 +614,13 @@ Dfa minimise_canonical(const Dfa& in, const std::string& rule_name) {
     while (!stack.empty()) {
         int q = stack.back(); stack.pop_back();
         auto visit = [&](int t) { if (t >= 0 && !reach[(size_t)t]) { reach[(size_t)t] = 1; stack.push_back(t); } };
-        for (int b = 0; b < 256; ++b) visit(in.bt[(size_t)q][(size_t)b]);
+        for (int c = 0; c < nc0; ++c) visit(in.at(q, c));
         for (auto& r : in.rt[(size_t)q]) visit(r.second);
     }
     for (int q = 0; q < n0; ++q) {
         if (!reach[(size_t)q]) continue;
         int last = -1;
-        for (int b = 0; b < 256; ++b) { int t = in.bt[(size_t)q][(size_t)b]; if (t >= 0 && t != last) { rev[(size_t)t].push_back(q); last = t; } }
+        for (int c = 0; c < nc0; ++c) { int t = in.at(q, c); if (t >= 0 && t != last) { rev[(size_t)t].push_back(q); last = t; } }
         for (auto& r : in.rt[(size_t)q]) rev[(size_t)r.second].push_back(q);
     }
     for (int q = 0; q < n0; ++q) if (reach[(size_t)q] && in.fin[(size_t)q]) { live[(size_t)q] = 1; stack.push_back(q); }
@@ -614,28 +633,29 @@ Dfa minimise_canonical(const Dfa& in, const std::string& rule_name) {
     for (int q = 0; q < n0; ++q) if (reach[(size_t)q] && live[(size_t)q]) { keep_id[(size_t)q] = (int)keep.size(); keep.push_back(q); }
     int n = (int)keep.size();
 
-    // byte classes: two bytes are alike if they lead to the same target in every kept state
-    std::vector<int> bclass(256, 0);
+    // byte classes: two input classes merge if they lead to the same target in every kept state.  New classes are
+    // numbered by first occurrence over ascending input classes, i.e. still by their smallest byte.
+    std::vector<int> cclass((size_t)nc0, 0);                   // input class -> class so far
     int nclass = 1;
     {
         struct Split { int old_class, target, new_class; };
         std::vector<Split> splits;                                  // few per state: searched linearly
         for (int q : keep) {
             splits.clear();
-            for (int b = 0; b < 256; ++b) {
-                int t = in.bt[(size_t)q][(size_t)b];
+            for (int c = 0; c < nc0; ++c) {
+                int t = in.at(q, c);
                 t = t >= 0 ? keep_id[(size_t)t] : -1;
-                const int oc = bclass[(size_t)b];
+                const int oc = cclass[(size_t)c];
                 int nc = -1;
                 for (const Split& sp : splits) if (sp.old_class == oc && sp.target == t) { nc = sp.new_class; break; }
                 if (nc < 0) { nc = (int)splits.size(); splits.push_back({oc, t, nc}); }
-                bclass[(size_t)b] = nc;
+                cclass[(size_t)c] = nc;
             }
             nclass = std::max(nclass, (int)splits.size());
         }
     }
-    std::vector<int> class_rep((size_t)nclass, 0);
-    for (int b = 255; b >= 0; --b) class_rep[(size_t)bclass[(size_t)b]] = b;
+    std::vector<int> class_rep((size_t)nclass, 0);              // an input class of each class
+    for (int c = nc0 - 1; c >= 0; --c) class_rep[(size_t)cclass[(size_t)c]] = c;
     std::vector<int> rule_syms;
     for (int q : keep) for (auto& r : in.rt[(size_t)q]) if (keep_id[(size_t)r.second] >= 0) rule_syms.push_back(r.first);
     std::sort(rule_syms.begin(), rule_syms.end());
@@ -644,7 +664,7 @@ Dfa minimise_canonical(const Dfa& in, const std::string& rule_name) {
     std::vector<int> delta((size_t)n * (size_t)nsym, -1);
     for (int i = 0; i < n; ++i) {
         int q = keep[(size_t)i];
-        for (int c = 0; c < nclass; ++c) { int t = in.bt[(size_t)q][(size_t)class_rep[(size_t)c]]; delta[(size_t)i * nsym + c] = t >= 0 ? keep_id[(size_t)t] : -1; }
+        for (int c = 0; c < nclass; ++c) { int t = in.at(q, class_rep[(size_t)c]); delta[(size_t)i * nsym + c] = t >= 0 ? keep_id[(size_t)t] : -1; }
         for (auto& r : in.rt[(size_t)q]) {
             int t = keep_id[(size_t)r.second];
             if (t < 0) continue;
@@ -702,25 +722,27 @@ Dfa minimise_canonical(const Dfa& in, const std::string& rule_name) {
             X.clear();
         }
     }
-    // quotient automaton, renamed breadth-first on the way: out-edges by ascending byte, then by rule
+    // quotient automaton over the merged classes, renamed breadth-first on the way: out-edges by ascending class
+    // (= ascending smallest byte), then by rule
     int nb = (int)blocks.size();
     const int start_block = block_of[(size_t)keep_id[(size_t)in.start]];
-    auto byte_target = [&](int b, int c) { int t = delta[(size_t)blocks[(size_t)b][0] * nsym + bclass[(size_t)c]]; return t >= 0 ? block_of[(size_t)t] : -1; };
+    auto class_target = [&](int b, int c) { int t = delta[(size_t)blocks[(size_t)b][0] * nsym + c]; return t >= 0 ? block_of[(size_t)t] : -1; };
     auto rule_target = [&](int b, size_t r) { int t = delta[(size_t)blocks[(size_t)b][0] * nsym + nclass + (int)r]; return t >= 0 ? block_of[(size_t)t] : -1; };
     std::vector<int> ident((size_t)nb, -1), order{start_block};
     ident[(size_t)start_block] = 0;
     for (size_t k = 0; k < order.size(); ++k) {
         int q = order[k];
         auto visit = [&](int t) { if (t >= 0 && ident[(size_t)t] < 0) { ident[(size_t)t] = (int)order.size(); order.push_back(t); } };
-        int last = -2;
-        for (int c = 0; c < 256; ++c) { int t = byte_target(q, c); if (t != last) { visit(t); last = t; } }
+        for (int c = 0; c < nclass; ++c) visit(class_target(q, c));
         for (size_t r = 0; r < rule_syms.size(); ++r) visit(rule_target(q, r));
     }
     Dfa out;
+    out.ncls = nclass;
+    for (int b = 0; b < 256; ++b) out.cls[(size_t)b] = (uint8_t)cclass[(size_t)in.cls[(size_t)b]];
     for (int q : order) out.add(in.fin[(size_t)keep[(size_t)blocks[(size_t)q][0]]]);
     for (size_t k = 0; k < order.size(); ++k) {
         int q = order[k];
-        for (int c = 0; c < 256; ++c) { int t = byte_target(q, c); out.bt[k][(size_t)c] = t >= 0 ? ident[(size_t)t] : -1; }
+        for (int c = 0; c < nclass; ++c) { int t = class_target(q, c); out.at((int)k, c) = t >= 0 ? ident[(size_t)t] : -1; }
         for (size_t r = 0; r < rule_syms.size(); ++r) { int t = rule_target(q, r); if (t >= 0) out.rt[k].emplace_back(rule_syms[r], ident[(size_t)t]); }
     }
     out.start = 0;
@@ -916,9 +938,9 @@ Grammar lower_grammar(const std::string& ebnf, const std::string& root_rule) {
         for (int q = 0; q < n; ++q) {
             int b = 0;
             while (b < 256) {
-                int t = d.bt[(size_t)q][(size_t)b];
+                int t = d.byte_target(q, b);
                 int e = b;
-                while (e + 1 < 256 && d.bt[(size_t)q][(size_t)(e + 1)] == t) ++e;
+                while (e + 1 < 256 && d.byte_target(q, e + 1) == t) ++e;
                 if (t >= 0) f.bedges[(size_t)q].push_back({(uint8_t)b, (uint8_t)e, t});
                 b = e + 1;
             }

@@ -143,10 +143,12 @@ __device__ __forceinline__ void follow_batch(const DevTables& T, const DevVocab&
 __global__ __launch_bounds__(64) void k_build(DevTables T, DevVocab Vd, BuildPlan P, SlowScratch S) {
     __shared__ uint32_t lds[BuildStore::SLOTS * 64];
     __shared__ uint32_t cls_words[64];
+    __shared__ uint8_t cls_bytes[256];                              // the same table, one byte an entry
     __shared__ uint32_t deferred[kBuildChunk];
     __shared__ uint32_t f_plane[128], f_rank[128];
     const uint32_t lane = threadIdx.x;
     cls_words[lane] = T.byte_class_words[lane];
+    reinterpret_cast<uint32_t*>(cls_bytes)[lane] = T.byte_class_words[lane];
     BuildStore st;
     st.init(lds + lane);
     uint32_t n_follow = 0;                                          // same in every lane
@@ -163,25 +165,28 @@ __global__ __launch_bounds__(64) void k_build(DevTables T, DevVocab Vd, BuildPla
             for (uint32_t rank0 = chunk.y; rank0 < chunk.z; rank0 += 64) {
                 const uint32_t rank = rank0 + lane;
                 bool defer = false;
-                if (rank < chunk.z) {
-                    const int n = (int)(Vd.off[rank + 1] - Vd.off[rank]);
-                    if (n > BuildStore::MAXLEN) defer = true;       // phase 2 hands it to the large-capacity kernel
-                    else {
-                        RegBytes tok;
-                        tok.v = Vd.tok16[rank];
-                        uint32_t sid = item0 & SID_MASK;
-                        bool dead = false;
-                        for (int i = 0; i < n; ++i) {
-                            const uint32_t b = tok.next();
-                            const uint32_t cls = (cls_words[b >> 2] >> ((b & 3) * 8)) & 0xFF;
-                            const uint32_t tgt = T.trans[sid * T.n_classes + cls];
-                            if (tgt == NO_TARGET) { dead = true; break; }
-                            if (tgt & (F_REF | F_FINAL)) { defer = true; break; }
-                            sid = tgt & SID_MASK;
+                int n = 0;
+                uint4 tv = make_uint4(0, 0, 0, 0);
+                if (rank < chunk.z) { n = (int)(Vd.off[rank + 1] - Vd.off[rank]); tv = Vd.tok16[rank]; }
+                if (n > BuildStore::MAXLEN) { defer = true; n = 0; }   // phase 2 hands it to the large-capacity kernel
+                bool walking = n > 0;
+                uint32_t sid = item0 & SID_MASK;
+                const uint32_t words[4] = {tv.x, tv.y, tv.z, tv.w};
+#pragma unroll
+                for (int wi = 0; wi < 4; ++wi) {                    // unrolled: byte j of word wi is one bit-field extract
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        if (walking && wi * 4 + j < n) {
+                            const uint32_t b = (words[wi] >> (8 * j)) & 0xFF;
+                            const uint32_t tgt = T.trans[sid * T.n_classes + cls_bytes[b]];
+                            if (tgt == NO_TARGET) walking = false;                                   // dead: rejected
+                            else if (tgt & (F_REF | F_FINAL)) { walking = false; defer = true; }   // predicts or completes
+                            else sid = tgt & SID_MASK;
                         }
-                        if (!dead && !defer) store_class(P, p, Vd.W, Vd.perm[rank], RES_ALIVE);
                     }
+                    if (!__any(walking && (wi + 1) * 4 < n)) break;
                 }
+                if (walking) store_class(P, p, Vd.W, Vd.perm[rank], RES_ALIVE);                  // reached its end alive
                 const unsigned long long m = __ballot(defer);
                 if (defer) deferred[n_work + (uint32_t)__popcll(m & ((1ull << lane) - 1))] = rank;
                 n_work += (uint32_t)__popcll(m);
