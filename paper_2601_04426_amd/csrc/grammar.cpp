@@ -1036,14 +1036,16 @@ std::vector<std::vector<int32_t>> bounded_classes(const Grammar& g, int32_t budg
                 std::vector<int64_t>& sg = base[(size_t)x];
                 sg.push_back(prev[(size_t)x]);
                 sg.push_back(f.is_final[(size_t)x]);
-                int32_t by_byte[256];
-                for (int b = 0; b < 256; ++b) by_byte[b] = -1;
-                for (auto& e : f.bedges[(size_t)x]) for (int b = e.lo; b <= e.hi; ++b) by_byte[b] = prev[(size_t)e.tgt];
-                for (int b = 0; b < 256;) {
-                    int e = b;
-                    while (e + 1 < 256 && by_byte[e + 1] == by_byte[b]) ++e;
-                    if (by_byte[b] >= 0) { sg.push_back(b); sg.push_back(e); sg.push_back(by_byte[b]); }
-                    b = e + 1;
+                // maximal runs of consecutive bytes that lead to the same class (edges are sorted and disjoint)
+                {
+                    int run_lo = -1, run_hi = -1; int32_t run_cls = -1;
+                    for (auto& e : f.bedges[(size_t)x]) {
+                        const int32_t c = prev[(size_t)e.tgt];
+                        if (run_lo >= 0 && (int)e.lo == run_hi + 1 && c == run_cls) { run_hi = e.hi; continue; }
+                        if (run_lo >= 0) { sg.push_back(run_lo); sg.push_back(run_hi); sg.push_back(run_cls); }
+                        run_lo = e.lo; run_hi = e.hi; run_cls = c;
+                    }
+                    if (run_lo >= 0) { sg.push_back(run_lo); sg.push_back(run_hi); sg.push_back(run_cls); }
                 }
                 sg.push_back(-7);
                 std::vector<std::pair<int64_t, int64_t>> refs;
@@ -1058,6 +1060,9 @@ std::vector<std::vector<int32_t>> bounded_classes(const Grammar& g, int32_t budg
             }
             // coarsest partition stable under "a nullable rule edge leads to the same class of this level"
             std::vector<int32_t> cur((size_t)n, 0);
+            bool any_nullable_edge = false;
+            for (int x = 0; x < n && !any_nullable_edge; ++x)
+                for (auto& e : f.redges[(size_t)x]) if (g.rules[(size_t)e.rule].nullable) { any_nullable_edge = true; break; }
             for (size_t n_classes = 0;;) {
                 std::map<std::vector<int64_t>, int32_t> ids;
                 std::vector<int32_t> nxt((size_t)n);
@@ -1072,7 +1077,7 @@ std::vector<std::vector<int32_t>> bounded_classes(const Grammar& g, int32_t budg
                     nxt[(size_t)x] = ids.emplace(std::move(sg), (int32_t)ids.size()).first->second;
                 }
                 cur.swap(nxt);
-                if (ids.size() == n_classes) break;
+                if (ids.size() == n_classes || !any_nullable_edge) break;      // without such edges one pass is the fixed point
                 n_classes = ids.size();
             }
             level.push_back(cur);
@@ -1128,15 +1133,15 @@ std::vector<uint64_t> follow_signatures(const Grammar& g, int32_t budget) {
             for (int x = 0; x < n; ++x) if (cyclic[(size_t)x]) unfold[(size_t)d][(size_t)g.sid(r, x)] = hash_combine(0xC1C1ull, g_unshareable_salt.fetch_add(1));
             for (int x : order) {
                 uint64_t h = hash_combine(0x51ull, f.is_final[(size_t)x]);
-                uint64_t by_byte[256];
-                bool has[256];
-                for (int b = 0; b < 256; ++b) { by_byte[b] = 0; has[b] = false; }
-                for (auto& e : f.bedges[(size_t)x]) for (int b = e.lo; b <= e.hi; ++b) { by_byte[b] = unfold[(size_t)d - 1][(size_t)g.sid(r, e.tgt)]; has[b] = true; }
-                for (int b = 0; b < 256;) {
-                    int e = b;
-                    while (e + 1 < 256 && has[e + 1] == has[b] && by_byte[e + 1] == by_byte[b]) ++e;
-                    if (has[b]) h = hash_combine(hash_combine(hash_combine(h, (uint64_t)b), (uint64_t)e), by_byte[b]);
-                    b = e + 1;
+                {   // maximal runs of consecutive bytes with the same unfolding (edges are sorted and disjoint)
+                    int run_lo = -1, run_hi = -1; uint64_t run_h = 0;
+                    for (auto& e : f.bedges[(size_t)x]) {
+                        const uint64_t u = unfold[(size_t)d - 1][(size_t)g.sid(r, e.tgt)];
+                        if (run_lo >= 0 && (int)e.lo == run_hi + 1 && u == run_h) { run_hi = e.hi; continue; }
+                        if (run_lo >= 0) h = hash_combine(hash_combine(hash_combine(h, (uint64_t)run_lo), (uint64_t)run_hi), run_h);
+                        run_lo = e.lo; run_hi = e.hi; run_h = u;
+                    }
+                    if (run_lo >= 0) h = hash_combine(hash_combine(hash_combine(h, (uint64_t)run_lo), (uint64_t)run_hi), run_h);
                 }
                 std::vector<std::pair<uint64_t, uint64_t>> refs;
                 for (auto& e : f.redges[(size_t)x]) {
