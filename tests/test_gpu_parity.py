@@ -320,6 +320,57 @@ def test_long_tokens_and_item_overflow_take_the_slow_path(xg):
         hist += toks[tid]
 
 
+TRICKY = [
+    # (grammar, alphabet, sentences): recursion, nullable left recursion, nullable chains, ambiguity, nesting, dispatch
+    ('root ::= "a" root "b" | ""', b"ab", [b"aaabbb", b"ab", b""]),
+    ('root ::= root "x" | ""', b"xy", [b"xxxxx", b""]),
+    ('root ::= a b c\na ::= "p"?\nb ::= a a | "q"\nc ::= [0-9]* a', b"pq01", [b"pq10p", b"pp", b"q", b"ppp01"]),
+    ('root ::= (item ",")* item\nitem ::= "[" root "]" | [a-c]{1,3}', b"[],abc", [b"[[a,bc],abc,[c]]", b"a", b"[[[[b]]]]"]),
+    ('root ::= e\ne ::= e "+" t | t\nt ::= t "*" f | f\nf ::= "(" e ")" | [0-9]+', b"()+*12", [b"1+2*(1+22)*2", b"((1))", b"12"]),
+    ('root ::= s\ns ::= s s | "a" | ""', b"ab", [b"aaaa", b""]),
+    ('root ::= TagDispatch(("<t>", body), ("<u>", num), stop_strs=("END",))\nbody ::= [a-z]+ "</t>"\nnum ::= [0-9]{1,3} ";"',
+     b"<>tu/END1;az", [b"zz<t>az</t>a<u>11;END", b"END", b"<u>1;END"]),
+]
+
+
+@pytest.mark.parametrize("case", range(len(TRICKY)))
+@pytest.mark.parametrize("depth,follow", [(1, False), (2, False), (2, True)])
+def test_tricky_grammars_planes_and_masks(xg, case, depth, follow):
+    """Hand-written grammars that stress the recogniser (left and nested recursion, nullable rules, ambiguity,
+    dispatch) over a vocabulary of every string of up to three bytes of the alphabet plus longer samples: every plane
+    and every served context equal to the oracle's classes, and the masks along sentences equal to the oracle's."""
+    import itertools
+    import torch
+    ebnf, alphabet, sentences = TRICKY[case]
+    rng = random.Random(case)
+    toks = [b""] + [bytes(t) for n in (1, 2, 3) for t in itertools.product(alphabet, repeat=n)]
+    toks += sorted({bytes(rng.choice(alphabet) for _ in range(rng.randrange(4, 20))) for _ in range(300)} - set(toks))
+    for sent in sentences:                                          # whole sentences and their halves as tokens too
+        for piece in (sent, sent[: len(sent) // 2], sent[len(sent) // 2:]):
+            if piece and piece not in toks:
+                toks.append(piece)
+    vocab = xg.Vocab(toks, 0, [0])
+    va = oracle.VocabArrays(toks, 0, [0])
+
+    class Cfg:                                                      # what check_planes reads
+        class vocab:
+            tokens = toks
+    cache, orc = check_planes(xg, Cfg, vocab, va, ebnf, "root", depth=depth, merge=True, follow=follow, max_contexts=100000)
+    single = {bytes([b]): toks.index(bytes([b])) for b in alphabet}
+    bm = torch.full((1, vocab.words), -1, dtype=torch.int32, device="cuda:0")
+    for sent in sentences:
+        m = xg.Matcher(cache)
+        for i in range(len(sent) + 1):
+            xg.fill_next_token_bitmask([m], bm.data_ptr(), vocab.words, _stream())
+            torch.cuda.synchronize()
+            want = oracle.pack_bitmask(orc.mask(sent[:i], va))
+            got = bm.cpu().numpy()[0]
+            assert np.array_equal(got, want), (sent[:i], diff_words(got, want, toks))
+            if i < len(sent):
+                assert m.accept_token(single[sent[i:i + 1]])
+        assert m.accept_token(0) and m.is_terminated()
+
+
 def test_edge_cases(xg):
     import torch
     toks = [b"", b"a", b"", b"b", b"ab", b"\xff"]                     # id 2 is an empty non-special token

@@ -63,6 +63,9 @@ TINY = [
     ('root ::= a b c\na ::= "p"?\nb ::= a a | "q"\nc ::= [0-9]* a', "root", [b"p", b"q", b"pp", b"ppp", b"pq", b"q1", b"pp12p", b"1", b"12p", b"pppp", b"qpp"], b"pq12p"),
     ('root ::= (item ",")* item\nitem ::= "[" root "]" | [a-c]{1,3}', "root",
      [b"a", b"ab", b"abc", b"abca", b"[", b"]", b",", b"[a", b"a]", b"a,b", b"[[a],b]", b"],[", b"a],", b"]]", b",,", b"[[[[[[[[[[[[[[[["], b"[[a,bc],abc,[c]]"),
+    ('root ::= e\ne ::= e "+" t | t\nt ::= t "*" f | f\nf ::= "(" e ")" | [0-9]+', "root",
+     [b"1", b"12", b"1+", b"+1", b"(1", b"1)", b"(1+2)*3", b"((((((((", b"))))", b"1*2+3*4+5", b"1++2", b"()"], b"1+2*(1+22)*2"),
+    ('root ::= s\ns ::= s s | "a" | ""', "root", [b"a", b"aa", b"aaaaaaaa", b"b", b"ab"], b"aaaa"),
     ('root ::= TagDispatch(("<t>", body), ("<u>", num), stop_strs=("END",))\nbody ::= [a-z]+ "</t>"\nnum ::= [0-9]{1,3} ";"', "root",
      [b"<", b"<t", b"<t>", b"t>ab", b"x<t>ab</t>y", b"<u>12;", b"<u>1234", b"EN", b"END", b"ENDx", b"<t>a</t>END", b">", b"</t>", b"9;<"], b"zz<t>abc</t>q<u>7;END"),
 ]
