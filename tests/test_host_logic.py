@@ -64,6 +64,79 @@ def test_lowering_small_grammars_and_errors(xg):
         assert e.value.code == code, bad
 
 
+def _random_grammar(rng):
+    """A small random EBNF over the letters a-d: 2-4 rules, alternation, optional / star / plus / bounded repetition,
+    classes, references (recursion included).  May be unreduced; the caller skips those."""
+    n_rules = rng.randrange(2, 5)
+    names = ["root"] + ["r%d" % i for i in range(1, n_rules)]
+
+    def atom(depth):
+        k = rng.random()
+        if k < 0.35:
+            return '"%s"' % "".join(rng.choice("abcd") for _ in range(rng.randrange(1, 3)))
+        if k < 0.5:
+            return rng.choice(["[a-b]", "[a-d]", "[^a]", "[bd]"])
+        if k < 0.8 or depth > 2:
+            return rng.choice(names)
+        return "(" + alt(depth + 1) + ")"
+
+    def factor(depth):
+        a = atom(depth)
+        k = rng.random()
+        if k < 0.15:
+            return a + "?"
+        if k < 0.25:
+            return a + "*"
+        if k < 0.32:
+            return a + "+"
+        if k < 0.4:
+            lo = rng.randrange(0, 3)
+            return a + "{%d,%d}" % (lo, lo + rng.randrange(0, 3))
+        return a
+
+    def alt(depth):
+        return " | ".join(" ".join(factor(depth) for _ in range(rng.randrange(1, 4))) for _ in range(rng.randrange(1, 4)))
+
+    return "".join("%s ::= %s\n" % (nm, alt(0)) for nm in names)
+
+
+def test_random_grammars_lower_alike_and_match_alike(xg):
+    """Seeded random grammars: the library either rejects a grammar the oracle also finds unreduced, or lowers it to
+    the oracle's automata, and its host matcher then accepts exactly the oracle's viable prefixes byte by byte."""
+    rng = random.Random(20260104)
+    done = 0
+    for trial in range(400):
+        ebnf = _random_grammar(rng)
+        try:
+            o = oracle.Oracle(ebnf, "root")
+        except Exception:
+            with pytest.raises(xg.Xg2Error):
+                xg.Grammar(ebnf)
+            continue
+        d, o = _same_automata(xg, ebnf)
+        g = xg.Grammar(ebnf)
+        toks = [b""] + [bytes([c]) for c in b"abcde"]
+        v = xg.Vocab(toks, 0, [0])
+        va = oracle.VocabArrays(toks, 0, [0])
+        m = xg.Matcher(grammar=g, vocab=v)
+        hist = b""
+        for step in range(12):
+            mask = o.mask(hist, va)
+            fr, can_end = m.frontier()
+            assert can_end == bool(mask[0]), (ebnf, hist)
+            allowed = [t for t in range(1, len(toks)) if mask[t]]
+            for t in range(1, len(toks)):
+                if not mask[t]:
+                    assert not m.accept_token(t), (ebnf, hist, toks[t])
+            if not allowed:
+                break
+            t = rng.choice(allowed)
+            assert m.accept_token(t), (ebnf, hist, toks[t])
+            hist += toks[t]
+        done += 1
+    assert done >= 100
+
+
 def test_hash_is_structural(xg):
     """Algorithm 1: the hash ignores rule names and declaration order and sees every edge; Algorithm 2: the rules of a
     simple cycle get distinct hashes that do not depend on names."""
