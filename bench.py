@@ -63,6 +63,9 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=5, help="workload index (5 = runtime stress, the metric's configuration)")
     ap.add_argument("--batch", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cross-grammar", type=int, default=0, metavar="N",
+                    help="also compile the first N grammars of the cross-grammar workload (config 4; 256 = all) into one pool and "
+                         "report planes built once versus positions, and checks/s (adds build launches of other sizes)")
     ap.add_argument("--jit", action="store_true", help="also time 32 decode steps on a cache compiled just in time (adds small launches of "
                                                        "the build and fill kernels, so per-kernel averages of a profile no longer match the main figures)")
     ap.add_argument("--cpu-positions", type=int, default=4096, help="positions in the oracle's timed sample")
@@ -246,6 +249,29 @@ def main() -> int:
 
     # just-in-time compilation (section 3.5), beside the main figures: nothing built at compile time, planes built by the
     # fill calls that first reach them; per-step latency of fill (host + device, synchronised) over fresh sentences
+    if args.cross_grammar:
+        cfg4 = gen.build_config(4)
+        vocab4 = xg.Vocab(cfg4.vocab.tokens, cfg4.vocab.eos_id, cfg4.vocab.special_ids)
+        n_tok4 = sum(1 for i, t in enumerate(cfg4.vocab.tokens) if t and i not in cfg4.vocab.special_ids)
+        pool4 = xg.Pool()
+        tot = {"positions": 0, "planes_used": 0, "planes_built": 0, "device_ms": 0.0, "host_ms": 0.0, "executed": 0}
+        t4 = time.perf_counter()
+        keep = []
+        for ebnf4, root4 in cfg4.grammars[:args.cross_grammar]:
+            c4 = xg.compile_grammar(vocab4, ebnf4, root4, pool=pool4, stream=stream)
+            s4 = c4.stats
+            tot["positions"] += s4.positions; tot["planes_used"] += s4.unique; tot["planes_built"] += s4.built
+            tot["device_ms"] += s4.device_ms; tot["host_ms"] += s4.host_lower_ms; tot["executed"] += s4.executed_checks
+            keep.append(c4)
+        wall4 = time.perf_counter() - t4
+        out["cross_grammar"] = {"grammars": len(keep), "vocab": cfg4.vocab.size, "positions": tot["positions"], "planes_used": tot["planes_used"],
+                                "planes_built_once": tot["planes_built"], "pool_rows": pool4.stats()[0], "pool_device_bytes": pool4.stats()[1],
+                                "device_ms": tot["device_ms"], "host_lower_ms": tot["host_ms"], "wall_s": wall4,
+                                "checks_per_s_device": tot["planes_built"] * n_tok4 / (tot["device_ms"] * 1e-3),
+                                "checks_per_s_served_device": tot["planes_used"] * n_tok4 / (tot["device_ms"] * 1e-3),
+                                "executed_checks": tot["executed"]}
+        del keep, pool4
+
     if args.jit:
         jit_cache = xg.compile_grammar(vocab, ebnf, root, stream=stream, jit=True, jit_prebuild=0)
         jm = [xg.Matcher(jit_cache) for _ in range(B)]
