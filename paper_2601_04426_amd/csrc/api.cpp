@@ -651,8 +651,9 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
             rep.resize((size_t)R);
             for (int r = 0; r < R; ++r) { rep[(size_t)r].resize((size_t)g.rules[(size_t)r].n_states()); std::iota(rep[(size_t)r].begin(), rep[(size_t)r].end(), 0); }
         }
-        std::vector<uint64_t> follow_sig;
-        if (follow) follow_sig = follow_signatures(g, (int32_t)std::max<uint32_t>(V.max_len, 1));
+        FollowInfo follow_info;
+        const int32_t budget = (int32_t)std::max<uint32_t>(V.max_len, 1);
+        if (follow) follow_info = follow_signatures(g, budget);
         // reference sites of every rule, one representative per class of the state the referencing rule continues in
         struct Site { int32_t q, waiter, x; };
         std::vector<std::vector<Site>> sites((size_t)R);            // all sites
@@ -676,7 +677,15 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
             const RuleFsm& fp = g.rules[(size_t)rp];
             PlaneKey key{entry[(size_t)rp], fp.canon_id[(size_t)sp_rep], -1, -1, 0};
             if (site) { key[2] = entry[(size_t)site->q]; key[3] = g.rules[(size_t)site->q].canon_id[(size_t)site->x]; }
-            if (follow) key[4] = (int64_t)(follow_sig[(size_t)(site ? site->q : rp)] | 1);
+            if (follow) {
+                // a token reaches what follows the outermost rule only after the shortest way out of the plane's rules, so
+                // the plane depends on the follow language no deeper than the bytes that are left then: planes whose way out
+                // is long are shared between grammars that differ only further on
+                int64_t need = follow_info.min_suf[(size_t)rp][(size_t)sp_rep];
+                if (site) need += follow_info.min_suf[(size_t)site->q][(size_t)site->x];
+                const int64_t depth_left = std::max<int64_t>(0, (int64_t)budget - std::max<int64_t>(1, need));
+                key[4] = (int64_t)(follow_info.sig[(size_t)(site ? site->q : rp)][(size_t)depth_left] | 1);
+            }
             auto lp = local_plane.find(key);
             if (lp != local_plane.end()) return lp->second;
             const uint32_t sid = (uint32_t)g.sid(rp, sp_rep);

@@ -1094,7 +1094,7 @@ std::vector<std::vector<int32_t>> bounded_classes(const Grammar& g, int32_t budg
     return rep;
 }
 
-std::vector<uint64_t> follow_signatures(const Grammar& g, int32_t budget) {
+FollowInfo follow_signatures(const Grammar& g, int32_t budget) {
     const int R = (int)g.rules.size();
     const int32_t INF = 1 << 28;
     // shortest completion of every state, in bytes
@@ -1184,8 +1184,11 @@ std::vector<uint64_t> follow_signatures(const Grammar& g, int32_t budget) {
         memo[key] = h;
         return h;
     };
-    std::vector<uint64_t> out((size_t)R);
-    for (int r = 0; r < R; ++r) out[(size_t)r] = sig(r, budget);
+    FollowInfo out;
+    out.sig.assign((size_t)R, std::vector<uint64_t>((size_t)budget + 1, 0));
+    for (int r = 0; r < R; ++r)
+        for (int32_t d = 0; d <= budget; ++d) out.sig[(size_t)r][(size_t)d] = sig(r, d);
+    out.min_suf = std::move(min_suf);
     return out;
 }
 

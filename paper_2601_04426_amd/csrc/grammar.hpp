@@ -61,14 +61,18 @@ uint64_t hash_combine(uint64_t h, uint64_t v);        // the order-sensitive has
 // equivalent states have equal planes.
 std::vector<std::vector<int32_t>> bounded_classes(const Grammar& g, int32_t budget, const std::vector<uint64_t>& ref_identity);
 
-// Per rule, a 64-bit signature of everything that can follow an instance of the rule within `budget`
-// bytes in this grammar: the set of states referencing rules continue in (as structural hashes of their
+// Per rule and per depth d <= budget, a 64-bit signature of everything that can follow an instance of the rule within
+// d bytes in this grammar: the set of states referencing rules continue in (as structural hashes of their
 // unfolding to the bytes that are left), recursively through rules that can end within the budget, and
 // whether the input may end (root rule).  Two rules with equal signatures reject the same uncertain
 // tokens by context expansion (section 2.2), so filtered planes can be shared across grammars
 // (section 3.3: reuse needs matching lookahead).  Rules on a reference cycle through rule ends, or behind
 // a cycle of nullable rule edges, get a process-unique signature (never shared, always sound).
-std::vector<uint64_t> follow_signatures(const Grammar& g, int32_t budget);
+struct FollowInfo {
+    std::vector<std::vector<uint64_t>> sig;        // [rule][d], d = 0..budget: what can follow the rule within d bytes
+    std::vector<std::vector<int32_t>> min_suf;     // [rule][state]: bytes of the shortest completion of the rule from the state
+};
+FollowInfo follow_signatures(const Grammar& g, int32_t budget);
 
 // Exact serialisation of one rule in Algorithm 1's canonical order; a reference to rule r is
 // written as ref_id[r].  Two rules with equal text and equal meaning of the ids are isomorphic.
