@@ -172,6 +172,9 @@ struct PoolImpl {
     std::unordered_multimap<uint64_t, int> by_hash;
     std::map<PlaneKey, uint32_t*> rows;
     std::unordered_set<const uint32_t*> no_uncertain;      // rows whose uncertain plane is all zero (need not be read)
+    // bounded-bisimulation classes of interned rules, in canonical state numbers: (entry, token-length budget) -> for
+    // canonical state c, the canonical state of its representative
+    std::map<std::pair<int, int32_t>, std::vector<int32_t>> class_memo;
     std::vector<void*> slabs;
     uint8_t* slab_cur = nullptr; size_t slab_left = 0;
     size_t device_bytes = 0;
@@ -645,7 +648,30 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
 
         // states that tokens cannot tell apart share planes
         std::vector<std::vector<int32_t>> rep, classes;
-        if (merge || follow) classes = bounded_classes(g, (int32_t)std::max<uint32_t>(V.max_len, 1), ref_id);
+        if (merge || follow) {
+            const int32_t class_budget = (int32_t)std::max<uint32_t>(V.max_len, 1);
+            classes.resize((size_t)R);
+            for (int r = 0; r < R; ++r) {
+                const RuleFsm& f = g.rules[(size_t)r];
+                const int n = f.n_states();
+                std::vector<int32_t> by_canon((size_t)n);             // canonical number -> state
+                for (int x = 0; x < n; ++x) by_canon[(size_t)f.canon_id[(size_t)x]] = x;
+                auto key = std::make_pair(entry[(size_t)r], class_budget);
+                auto hit = f.shareable ? pool.class_memo.find(key) : pool.class_memo.end();
+                if (hit != pool.class_memo.end() && (int)hit->second.size() == n) {
+                    // an identical rule was analysed before (this grammar or an earlier one): translate through the canonical numbers
+                    classes[(size_t)r].resize((size_t)n);
+                    for (int x = 0; x < n; ++x) classes[(size_t)r][(size_t)x] = by_canon[(size_t)hit->second[(size_t)f.canon_id[(size_t)x]]];
+                    continue;
+                }
+                classes[(size_t)r] = bounded_classes_rule(g, r, class_budget, ref_id);
+                if (f.shareable) {
+                    std::vector<int32_t> canon((size_t)n);
+                    for (int x = 0; x < n; ++x) canon[(size_t)f.canon_id[(size_t)x]] = f.canon_id[(size_t)classes[(size_t)r][(size_t)x]];
+                    pool.class_memo.emplace(key, std::move(canon));
+                }
+            }
+        }
         if (merge) rep = classes;
         else {
             rep.resize((size_t)R);

@@ -1023,7 +1023,14 @@ Grammar lower_grammar(const std::string& ebnf, const std::string& root_rule) {
 
 std::vector<std::vector<int32_t>> bounded_classes(const Grammar& g, int32_t budget, const std::vector<uint64_t>& ref_identity) {
     std::vector<std::vector<int32_t>> rep(g.rules.size());
-    for (size_t r = 0; r < g.rules.size(); ++r) {
+    for (size_t r = 0; r < g.rules.size(); ++r) rep[r] = bounded_classes_rule(g, (int32_t)r, budget, ref_identity);
+    return rep;
+}
+
+std::vector<int32_t> bounded_classes_rule(const Grammar& g, int32_t rule, int32_t budget, const std::vector<uint64_t>& ref_identity) {
+    std::vector<int32_t> rep_r;
+    {
+        const size_t r = (size_t)rule;
         const RuleFsm& f = g.rules[r];
         const int n = f.n_states();
         // level[d][x] = class of x with d bytes left; level 0 tells nothing apart
@@ -1088,10 +1095,10 @@ std::vector<std::vector<int32_t>> bounded_classes(const Grammar& g, int32_t budg
             auto it = best.find(fin[(size_t)x]);
             if (it == best.end() || f.canon_id[(size_t)x] < f.canon_id[(size_t)it->second]) best[fin[(size_t)x]] = x;
         }
-        rep[r].resize((size_t)n);
-        for (int x = 0; x < n; ++x) rep[r][(size_t)x] = best[fin[(size_t)x]];
+        rep_r.resize((size_t)n);
+        for (int x = 0; x < n; ++x) rep_r[(size_t)x] = best[fin[(size_t)x]];
     }
-    return rep;
+    return rep_r;
 }
 
 FollowInfo follow_signatures(const Grammar& g, int32_t budget) {

@@ -60,6 +60,9 @@ uint64_t hash_combine(uint64_t h, uint64_t v);        // the order-sensitive has
 // that the states inside a repetition differ minimally): tokens are at most `budget` bytes long, so
 // equivalent states have equal planes.
 std::vector<std::vector<int32_t>> bounded_classes(const Grammar& g, int32_t budget, const std::vector<uint64_t>& ref_identity);
+// One rule of the above.  The result depends only on the rule's structure and on the identities (and through them the
+// shortest sentence and nullability) of the rules it references.
+std::vector<int32_t> bounded_classes_rule(const Grammar& g, int32_t rule, int32_t budget, const std::vector<uint64_t>& ref_identity);
 
 // Per rule and per depth d <= budget, a 64-bit signature of everything that can follow an instance of the rule within
 // d bytes in this grammar: the set of states referencing rules continue in (as structural hashes of their
