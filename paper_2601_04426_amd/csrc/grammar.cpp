@@ -8,6 +8,8 @@
 #include <deque>
 #include <functional>
 #include <map>
+#include <memory>
+#include <mutex>
 #include <set>
 #include <sstream>
 #include <unordered_map>
@@ -896,6 +898,38 @@ std::string serialise_rule(const Grammar& g, int32_t rule, const std::vector<uin
     return text;
 }
 
+// ---- process-wide memo of lowered rule bodies ------------------------------------------------------------
+std::mutex g_body_memo_mu;
+std::unordered_map<std::string, std::shared_ptr<Dfa>> g_body_memo;
+
+void collect_refs(const Node& nd, const std::map<std::string, int>& index, std::vector<int>& out, bool& ok) {
+    auto add = [&](const std::string& name) { auto it = index.find(name); if (it == index.end()) ok = false; else out.push_back(it->second); };
+    if (nd.k == NK::Ref) add(nd.name);
+    for (auto& t : nd.tags) add(t.second);
+    for (const Node& k : nd.kids) collect_refs(k, index, out, ok);
+}
+
+void body_key(const Node& nd, const std::map<std::string, int>& index, const std::vector<int>& ref_decl, std::string& out) {
+    auto put = [&](uint64_t v) { for (int k = 0; k < 8; ++k) out.push_back((char)((v >> (8 * k)) & 0xFF)); };
+    auto rank = [&](const std::string& name) { return (uint64_t)(std::lower_bound(ref_decl.begin(), ref_decl.end(), index.at(name)) - ref_decl.begin()); };
+    out.push_back((char)('A' + (int)nd.k));
+    switch (nd.k) {
+        case NK::Lit: put(nd.cps.size()); for (uint32_t c : nd.cps) put(c); break;
+        case NK::Cls: put(nd.neg); put(nd.ranges.size()); for (auto& r : nd.ranges) { put(r.first); put(r.second); } break;
+        case NK::Ref: put(rank(nd.name)); break;
+        case NK::Rep: put((uint64_t)(int64_t)nd.m); put((uint64_t)(int64_t)nd.n); break;
+        case NK::Tag:
+            put(nd.tags.size());
+            for (auto& t : nd.tags) { put(t.first.size()); out += t.first; put(rank(t.second)); }
+            put(nd.stops.size());
+            for (auto& st : nd.stops) { put(st.size()); out += st; }
+            break;
+        default: break;
+    }
+    put(nd.kids.size());
+    for (const Node& k : nd.kids) body_key(k, index, ref_decl, out);
+}
+
 Grammar lower_grammar(const std::string& ebnf, const std::string& root_rule) {
     std::vector<std::string> order;
     std::map<std::string, Node> rules;
@@ -911,15 +945,44 @@ Grammar lower_grammar(const std::string& ebnf, const std::string& root_rule) {
         int r = todo.back(); todo.pop_back();
         if (dfas.count(r)) continue;
         const Node& body = rules.at(order[(size_t)r]);
-        Dfa raw;
-        if (body.k == NK::Tag) raw = tagdispatch_automaton(body, index);
-        else {
-            Nfa nfa;
-            int s = nfa.add(), e = nfa.add();
-            build_nfa(body, nfa, s, e, index);
-            raw = subset_construction(nfa, s, e);
+        // Rule bodies recur across grammars (the same tool schema in many requests): the minimal automaton of a body is
+        // kept process-wide under its structure, references written as their rank among the body's references by
+        // declaration index (which is all the canonical numbering depends on).
+        std::vector<int> ref_decl;                                  // declaration indices referenced, ascending
+        bool refs_ok = true;
+        collect_refs(body, index, ref_decl, refs_ok);
+        std::sort(ref_decl.begin(), ref_decl.end());
+        ref_decl.erase(std::unique(ref_decl.begin(), ref_decl.end()), ref_decl.end());
+        std::string key;
+        if (refs_ok) body_key(body, index, ref_decl, key);
+        Dfa d;
+        bool from_memo = false;
+        if (refs_ok) {
+            std::lock_guard<std::mutex> lk(g_body_memo_mu);
+            auto it = g_body_memo.find(key);
+            if (it != g_body_memo.end()) { d = *it->second; from_memo = true; }
         }
-        Dfa d = minimise_canonical(raw, order[(size_t)r]);
+        if (from_memo) {
+            for (auto& es : d.rt) for (auto& e : es) e.first = ref_decl[(size_t)e.first];   // rank -> declaration index here
+        } else {
+            Dfa raw;
+            if (body.k == NK::Tag) raw = tagdispatch_automaton(body, index);
+            else {
+                Nfa nfa;
+                int s = nfa.add(), e = nfa.add();
+                build_nfa(body, nfa, s, e, index);
+                raw = subset_construction(nfa, s, e);
+            }
+            d = minimise_canonical(raw, order[(size_t)r]);
+            if (refs_ok) {
+                auto keep = std::make_shared<Dfa>(d);
+                for (auto& es : keep->rt)
+                    for (auto& e : es) e.first = (int)(std::lower_bound(ref_decl.begin(), ref_decl.end(), e.first) - ref_decl.begin());
+                std::lock_guard<std::mutex> lk(g_body_memo_mu);
+                if (g_body_memo.size() > 200000) g_body_memo.clear();   // a bound on memory, not a policy
+                g_body_memo.emplace(std::move(key), std::move(keep));
+            }
+        }
         for (auto& es : d.rt) for (auto& e : es) todo.push_back(e.first);
         dfas.emplace(r, std::move(d));
     }
