@@ -186,6 +186,12 @@ int32_t xg2_fill_next_token_bitmask(xg2_matcher* const* matchers, int32_t B, int
  * (context upload, plane union, re-check), from HIP events on its stream.  Waits for that work.   */
 int32_t xg2_fill_last_device_us(float* out);
 
+/* What became of the re-checks of the latest fill call of this process (waits for its device work): how
+ * many (row, token) pairs needed the large-capacity kernel, and whether one of them exceeded even its
+ * item lists (256 items, 1024 wait entries, tokens of 1024 bytes) -- such a token's bit is left 0 although
+ * the token might be allowed.  fill itself returns before the device work runs and cannot report this.   */
+int32_t xg2_fill_last_status(int32_t* large_capacity_tokens, int32_t* overflowed);
+
 /* ---- apply_token_bitmask(logits[B, V], bitmask) -------------------------------------------------
  * In place: logits[b, v] = -infinity where bit v of bitmask row b is 0; other elements keep
  * their bit pattern.  dtype: XG2_F32 or XG2_BF16.  logits_dev: device, B rows of

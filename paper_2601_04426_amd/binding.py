@@ -25,7 +25,7 @@ EXPORTS = [
     "xg2_compile_grammar", "xg2_mask_cache_destroy", "xg2_mask_cache_num_positions", "xg2_mask_cache_num_planes", "xg2_mask_cache_jit_stats",
     "xg2_mask_cache_plane_info", "xg2_mask_cache_find_plane", "xg2_mask_cache_get_planes", "xg2_matcher_create", "xg2_matcher_create_host", "xg2_matcher_destroy",
     "xg2_matcher_accept_token", "xg2_matcher_accept_tokens", "xg2_matcher_reset", "xg2_matcher_is_terminated", "xg2_matcher_frontier",
-    "xg2_fill_next_token_bitmask", "xg2_fill_last_device_us", "xg2_apply_token_bitmask",
+    "xg2_fill_next_token_bitmask", "xg2_fill_last_device_us", "xg2_fill_last_status", "xg2_apply_token_bitmask",
 ]
 
 
@@ -93,6 +93,7 @@ def _load() -> ctypes.CDLL:
     L.xg2_matcher_frontier.argtypes = [vp, vp, i32, ctypes.POINTER(i32), ctypes.POINTER(i32)]
     L.xg2_fill_next_token_bitmask.argtypes = [vp, i32, vp, i64, vp]
     L.xg2_fill_last_device_us.argtypes = [ctypes.POINTER(ctypes.c_float)]
+    L.xg2_fill_last_status.argtypes = [ctypes.POINTER(i32), ctypes.POINTER(i32)]
     L.xg2_apply_token_bitmask.argtypes = [vp, i32, i32, i32, i64, vp, i64, vp]
     for name in EXPORTS:
         if name not in ("xg2_last_error",) and not name.endswith("_destroy"):
@@ -295,6 +296,13 @@ def fill_next_token_bitmask(matchers, bitmask_ptr: int, row_stride_words: int, s
         arr = (ctypes.c_void_p * len(matchers))(*[m.h for m in matchers])
     _check(lib.xg2_fill_next_token_bitmask(arr, len(matchers), ctypes.c_void_p(bitmask_ptr), row_stride_words,
                                            ctypes.c_void_p(stream)))
+
+
+def fill_last_status() -> Tuple[int, bool]:
+    """(pairs re-checked by the large-capacity kernel, whether one of them overflowed even that) of the latest fill."""
+    n, over = ctypes.c_int32(0), ctypes.c_int32(0)
+    _check(lib.xg2_fill_last_status(ctypes.byref(n), ctypes.byref(over)))
+    return n.value, bool(over.value)
 
 
 def fill_last_device_us() -> float:

@@ -248,6 +248,14 @@ struct MatcherImpl {
     std::shared_ptr<VocabImpl> vocab;
     EarleyChart chart;
     bool terminated = false;
+    // what fill needs from this state, computed once per state (by the batched accept, else by the next fill)
+    struct Prep {
+        bool valid = false;
+        int32_t status = XG2_OK;                             // an error found while preparing, reported by fill
+        std::string error;
+        ScanContext ctx;
+        std::vector<std::pair<int32_t, bool>> planes;        // (plane index, only the accepted row counts)
+    } prep;
     MatcherImpl(std::shared_ptr<GrammarImpl> g, std::shared_ptr<VocabImpl> v) : gram(std::move(g)), vocab(std::move(v)), chart(&gram->ft) {
         chart.start(gram->ft.root_start);
     }
@@ -264,6 +272,7 @@ struct FillWorkspace {
     int next = 0;
     DevBuf<uint32_t> cand_words, work_list, row_count;
     hipEvent_t t_begin = nullptr, t_end = nullptr;          // around the device work of the latest fill
+    const uint32_t* last_flags = nullptr;                   // device: overflow-list length and flag of the latest fill
     bool timed = false;
     void ensure_scratch(size_t words, size_t rows) {
         if (row_count.n < rows) row_count.alloc(rows * 2);
@@ -491,6 +500,25 @@ int32_t for_frontier_planes(const MatcherImpl& M, F&& visit) {
         if (!any_parent) return fail(XG2_EINVAL, "xg2_fill_next_token_bitmask: frontier item without a referencing item");
     }
     return XG2_OK;
+}
+
+// The fill-side view of a matcher's current state: scan context and the planes of its frontier.
+void prepare_matcher(MatcherImpl& M) {
+    MatcherImpl::Prep& P = M.prep;
+    if (P.valid || !M.cache) return;
+    P.status = XG2_OK;
+    P.planes.clear();
+    if (!M.terminated) {
+        if (!M.chart.context(P.ctx)) { P.status = XG2_EOVERFLOW; P.error = "xg2_fill_next_token_bitmask: parser context too deep"; }
+        else {
+            P.status = for_frontier_planes(M, [&](int32_t plane, bool accepted_only) {
+                for (auto& pl : P.planes) if (pl.first == plane) { pl.second = pl.second && accepted_only; return; }
+                P.planes.emplace_back(plane, accepted_only);
+            });
+            if (P.status != XG2_OK) P.error = g_error;
+        }
+    }
+    P.valid = true;
 }
 
 extern "C" {
@@ -871,10 +899,12 @@ int32_t xg2_matcher_accept_token(xg2_matcher* m, int32_t token_id) {
         if (token_id == M.vocab->eos) {
             if (!M.chart.last().root_done) return fail(XG2_EREJECTED, "end of sequence is not allowed here");
             M.terminated = true;
+            M.prep.valid = false;
             return XG2_OK;
         }
         if (M.vocab->special[(size_t)token_id]) return fail(XG2_EREJECTED, "special or empty tokens are never allowed");
         if (!M.chart.advance(M.vocab->tok(token_id), M.vocab->len(token_id))) return fail(XG2_EREJECTED, "token is not allowed here");
+        M.prep.valid = false;
         return XG2_OK;
     });
 }
@@ -884,7 +914,10 @@ int32_t xg2_matcher_accept_tokens(xg2_matcher* const* matchers, const int32_t* t
     // matchers are independent: a few host threads each take a contiguous share (a handle listed twice would race)
     const int32_t n_threads = std::max<int32_t>(1, std::min<int32_t>({(int32_t)std::thread::hardware_concurrency(), 8, B / 64}));
     auto work = [&](int32_t lo, int32_t hi) {
-        for (int32_t b = lo; b < hi; ++b) status_host[b] = token_ids[b] < 0 ? XG2_OK : xg2_matcher_accept_token(matchers[b], token_ids[b]);
+        for (int32_t b = lo; b < hi; ++b) {
+            status_host[b] = token_ids[b] < 0 ? XG2_OK : xg2_matcher_accept_token(matchers[b], token_ids[b]);
+            prepare_matcher(*matchers[b]->p);                   // the next fill finds the state ready
+        }
     };
     if (n_threads == 1) { work(0, B); return XG2_OK; }
     std::vector<std::thread> pool;
@@ -897,6 +930,7 @@ int32_t xg2_matcher_reset(xg2_matcher* m) {
     if (!m) return fail(XG2_EINVAL, "xg2_matcher_reset: null matcher");
     m->p->chart.start(m->p->gram->ft.root_start);
     m->p->terminated = false;
+    m->p->prep.valid = false;
     return XG2_OK;
 }
 int32_t xg2_matcher_is_terminated(const xg2_matcher* m, int32_t* out) {
@@ -941,11 +975,12 @@ int32_t xg2_fill_next_token_bitmask(xg2_matcher* const* matchers, int32_t B, int
         {
             std::map<CacheImpl*, std::vector<int32_t>> missing;
             for (int32_t b = 0; b < B; ++b) {
-                const MatcherImpl& M = *matchers[b]->p;
+                MatcherImpl& M = *matchers[b]->p;
+                prepare_matcher(M);
+                if (M.prep.status != XG2_OK) return fail(M.prep.status, M.prep.error.c_str());
                 if (M.terminated || M.cache->n_built == (int64_t)M.cache->planes.size()) continue;
                 std::vector<int32_t>& v = missing[M.cache.get()];
-                int32_t rc = for_frontier_planes(M, [&](int32_t plane, bool) { if (!M.cache->planes[(size_t)plane].row) v.push_back(plane); });
-                if (rc != XG2_OK) return rc;
+                for (auto& pl : M.prep.planes) if (!M.cache->planes[(size_t)pl.first].row) v.push_back(pl.first);
             }
             for (auto& kv : missing) {
                 std::vector<int32_t>& v = kv.second;
@@ -968,7 +1003,6 @@ int32_t xg2_fill_next_token_bitmask(xg2_matcher* const* matchers, int32_t B, int
         std::vector<uint32_t> items, wait, wait_off;
         std::vector<DevTables> tables;
         std::map<const CacheImpl*, uint32_t> table_idx;
-        ScanContext ctx;
         for (int32_t b = 0; b < B; ++b) {
             const MatcherImpl& M = *matchers[b]->p;
             FillRow& r = rows[(size_t)b];
@@ -982,14 +1016,13 @@ int32_t xg2_fill_next_token_bitmask(xg2_matcher* const* matchers, int32_t B, int
             r.waitoff_off = (uint32_t)wait_off.size();
             if (M.terminated) { r.flags = 2; continue; }
             r.flags = M.chart.last().root_done ? 1u : 0u;
-            if (!M.chart.context(ctx)) return fail(XG2_EOVERFLOW, "xg2_fill_next_token_bitmask: parser context too deep");
+            const ScanContext& ctx = M.prep.ctx;
             size_t f0 = front.size();
-            int32_t rc = for_frontier_planes(M, [&](int32_t plane, bool accepted_only) {
-                const PlaneInfo& pi = M.cache->planes[(size_t)plane];
-                uint64_t row = (uint64_t)(uintptr_t)pi.row | ((accepted_only || pi.no_uncertain) ? 1u : 0u);
+            for (auto& pl : M.prep.planes) {
+                const PlaneInfo& pi = M.cache->planes[(size_t)pl.first];
+                uint64_t row = (uint64_t)(uintptr_t)pi.row | ((pl.second || pi.no_uncertain) ? 1u : 0u);
                 if (std::find(front.begin() + (long)f0, front.end(), row) == front.end()) front.push_back(row);
-            });
-            if (rc != XG2_OK) return rc;
+            }
             r.front_n = (uint32_t)(front.size() - f0);
             r.item_n = (uint32_t)ctx.items.size();
             r.H = ctx.H;
@@ -1039,6 +1072,7 @@ int32_t xg2_fill_next_token_bitmask(xg2_matcher* const* matchers, int32_t B, int
         HIP_CHECK(hipGetLastError());
         HIP_CHECK(hipEventRecord(fill_ws().t_end, stream));
         fill_ws().timed = true;
+        fill_ws().last_flags = S.count;
         HIP_CHECK(hipEventRecord(slot.done, stream));
         slot.in_flight = true;
         return XG2_OK;
@@ -1054,6 +1088,19 @@ int32_t xg2_fill_last_device_us(float* out) {
         float ms = 0.f;
         HIP_CHECK(hipEventElapsedTime(&ms, fill_ws().t_begin, fill_ws().t_end));
         *out = ms * 1e3f;
+        return XG2_OK;
+    });
+}
+
+int32_t xg2_fill_last_status(int32_t* large_capacity_tokens, int32_t* overflowed) {
+    return guarded([&]() -> int32_t {
+        std::lock_guard<std::mutex> ws_lock(fill_ws().mu);
+        if (!fill_ws().timed) return fail(XG2_EINVAL, "xg2_fill_last_status: no fill call yet");
+        HIP_CHECK(hipEventSynchronize(fill_ws().t_end));
+        uint32_t words[2] = {0, 0};
+        HIP_CHECK(hipMemcpy(words, fill_ws().last_flags, sizeof(words), hipMemcpyDeviceToHost));
+        if (large_capacity_tokens) *large_capacity_tokens = (int32_t)words[0];
+        if (overflowed) *overflowed = words[1] ? 1 : 0;
         return XG2_OK;
     });
 }

@@ -312,6 +312,8 @@ def test_long_tokens_and_item_overflow_take_the_slow_path(xg):
         got = bitmask.cpu().numpy()[0]
         want = oracle.pack_bitmask(orc.mask(hist, va))
         assert np.array_equal(got, want), (hist, diff_words(got, want, toks))
+        n_large, overflowed = xg.fill_last_status()
+        assert n_large >= 0 and not overflowed                          # nothing was left undecided
         allowed = [i for i in range(1, len(toks)) if (int(got[i // 32]) >> (i % 32)) & 1]
         if not allowed:
             break
