@@ -23,7 +23,9 @@
  *     bits at or beyond V in the last word are 0.
  *   - Device work is enqueued on the HIP stream given by the caller (a hipStream_t passed as
  *     void*, NULL = the default stream).  xg2_compile_grammar returns after its kernels have
- *     finished; fill and apply return as soon as their work is enqueued.
+ *     finished; fill and apply return as soon as their work is enqueued.  Compile and fill calls share
+ *     device scratch buffers: their device work must not overlap, so give them one stream (or order the
+ *     streams with events).  apply has no such state.
  *   - There is no CPU fallback: without a usable HIP device every call that needs one fails
  *     with XG2_EHIP.
  */

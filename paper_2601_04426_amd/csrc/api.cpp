@@ -142,7 +142,7 @@ struct GrammarImpl {
 // ---- large-capacity scratch shared by the slow kernels (one per process; calls are serialised) --------
 struct SlowImpl {
     std::mutex mu;
-    DevBuf<uint32_t> mem, list, count;
+    DevBuf<uint32_t> mem, list;                 // the counter and flag of the list belong to each call's upload
     SlowScratch s{};
     bool ready = false;
     void ensure() {
@@ -151,9 +151,7 @@ struct SlowImpl {
         s.list_cap = 1u << 20;
         mem.alloc((size_t)s.n_lanes * kSlowSlots);
         list.alloc((size_t)s.list_cap * 2);
-        count.alloc(2);
-        HIP_CHECK(hipMemset(count.p, 0, 2 * sizeof(uint32_t)));
-        s.mem = mem.p; s.list = list.p; s.count = count.p;
+        s.mem = mem.p; s.list = list.p; s.count = nullptr;
         ready = true;
     }
 };
