@@ -33,6 +33,8 @@ PMC = {
     "k_build": (14465.1, 31867.2),
     "k_fill_or": (4067.8, 19165.6),
     "k_apply_vec<8>": (98629.2, 303872.0),
+    # wave instructions of one k_build launch (rocprofv3 --pmc SQ_INSTS_VALU + SALU + BRANCH + LDS + VMEM_RD + VMEM_WR + SMEM)
+    "k_build_wave_instructions": 56463750.0,
     "k_apply_vec<4>": (182229.9, 605511.0),
 }
 KERNEL_SOURCES = ("kernels.hip", "earley_core.hpp", "device.hpp")
@@ -234,6 +236,14 @@ def main() -> int:
                      "note": "algorithmic bytes = built planes x (sum of token bytes + 4.25 B per token), every logical check counted; "
                              "the kernel is bound by instruction issue and load latency, not by HBM (measured traffic is far below)"},
     }
+    # the build kernel is an interpreter: what bounds it is the rate at which the SIMDs issue wave instructions
+    # (256 CUs x 4 SIMDs x 2.4 GHz, one instruction of a wave every 4 cycles)
+    issue_peak = 256 * 4 * 2.4e9 / 4
+    n_instr = PMC["k_build_wave_instructions"] if (default_workload and kernel_sources_sha256() == PMC["sources_sha256"]) else None
+    out["roofline_alu"] = {"kernel": "k_build", "bound": "alu", "achieved": (n_instr / (kernel_ms * 1e-3)) if n_instr else None,
+                           "peak": issue_peak, "unit": "wave-instructions/s",
+                           "frac": (n_instr / (kernel_ms * 1e-3) / issue_peak) if n_instr else None, "traffic": None,
+                           "note": "instruction count from rocprofv3 SQ counters for these kernel sources; scalar and branch instructions are 63 % of it"}
     for name, key, e in (("roofline_apply_bf16", "apply_bf16_us", 2), ("roofline_apply_f32", "apply_f32_us", 4)):
         t = med(acc[key]) * 1e-6
         rmw = (B * W * 4 + 2 * B * V * e) / t / 1e9
