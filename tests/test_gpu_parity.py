@@ -373,6 +373,46 @@ def test_tricky_grammars_planes_and_masks(xg, case, depth, follow):
         assert m.accept_token(0) and m.is_terminated()
 
 
+def test_one_fill_call_over_matchers_of_different_grammars(xg):
+    """Matchers of several caches (one vocabulary) in one fill call, as when requests with different grammars are
+    served in one batch: every row equals the oracle's mask for its own grammar."""
+    import torch
+    cfg, vocab, va = load(1)
+    grammars = [cfg.grammars[0],
+                ('root ::= "[" ws (num (ws "," ws num)*)? ws "]"\nnum ::= "-"? [0-9]{1,4}\nws ::= [ \t\n]*\n', "root"),
+                ('root ::= item+\nitem ::= "<" [a-z]{1,8} ">" | [A-Z ]\n', "root")]
+    pool = xg.Pool()
+    caches = [xg.compile_grammar(vocab, e, r, pool=pool, stream=_stream()) for e, r in grammars]
+    orcs = [oracle.Oracle(e, r) for e, r in grammars]
+    rng = random.Random(404)
+    B = 24
+    which = [rng.randrange(len(grammars)) for _ in range(B)]
+    matchers = [xg.Matcher(caches[g]) for g in which]
+    hist = [b""] * B
+    bitmask = torch.zeros((B, vocab.words), dtype=torch.int32, device="cuda:0")
+    for step in range(20):
+        xg.fill_next_token_bitmask(matchers, bitmask.data_ptr(), vocab.words, _stream())
+        torch.cuda.synchronize()
+        got = bitmask.cpu().numpy()
+        ids = []
+        for b in range(B):
+            if matchers[b].is_terminated():
+                want = np.zeros(vocab.size, dtype=bool)
+                want[cfg.vocab.eos_id] = True
+                ids.append(-1)
+            else:
+                want = orcs[which[b]].mask(hist[b], va)
+                allowed = np.nonzero(want)[0]
+                assert len(allowed) > 0
+                ids.append(int(rng.choice(list(allowed))))
+            assert np.array_equal(got[b], oracle.pack_bitmask(want)), (step, b, which[b], hist[b])
+        status = xg.MatcherBatch(matchers).accept_tokens(ids)
+        assert not status.any()
+        for b in range(B):
+            if ids[b] > 0:
+                hist[b] += cfg.vocab.tokens[ids[b]]
+
+
 def test_edge_cases(xg):
     import torch
     toks = [b"", b"a", b"", b"b", b"ab", b"\xff"]                     # id 2 is an empty non-special token
