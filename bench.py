@@ -313,9 +313,30 @@ def main() -> int:
         for p in sample:
             orc.classes(p, va, threads=threads)
         dt = time.perf_counter() - t0
+        # the same on one core (the paper's timings are single-threaded), on a smaller seeded sample
+        one = prng.sample(pos, min(96, len(pos)))
+        t0 = time.perf_counter()
+        for p in one:
+            orc.classes(p, va, threads=1)
+        dt1 = time.perf_counter() - t0
+        # decode side: the plain-definition mask of a few rows of the batch, and a plain masking loop over one row of logits
+        rows_sample = [b for b in range(0, B, max(1, B // 4))][:4]
+        hist = [b"".join(cfg.vocab.tokens[t] for t in traces[b][:cursor[b]] if t != cfg.vocab.eos_id) for b in rows_sample]
+        t0 = time.perf_counter()
+        for h in hist:
+            orc.mask(h, va, threads=threads)
+        dtm = (time.perf_counter() - t0) / len(hist)
+        bits = np.ascontiguousarray(logits32_src[0].cpu().numpy()).view(np.uint32).reshape(1, V).copy()
+        bm_row = bitmask[:1].cpu().numpy()
+        t0 = time.perf_counter()
+        oracle.apply_f32(bits, bm_row)
+        dta = time.perf_counter() - t0
         out["cpu_baseline"] = {"value": len(sample) * n_checkable / dt, "unit": "checks/s", "cores": threads, "kind": "oracle",
                                "sample": "%d of %d positions (seeded sample) x all %d tokens, textbook Earley per pair, %.1f s"
-                                         % (len(sample), len(pos), n_checkable, dt)}
+                                         % (len(sample), len(pos), n_checkable, dt),
+                               "value_one_core": len(one) * n_checkable / dt1,
+                               "decode_mask_us_per_row": dtm * 1e6, "apply_f32_us_per_row": dta * 1e6,
+                               "decode_note": "plain-definition mask of one row (oracle, %d threads) and masking of one fp32 row; the GPU figures above are for %d rows" % (threads, B)}
     print(json.dumps(out))
     return 0
 
