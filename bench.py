@@ -259,6 +259,14 @@ def main() -> int:
 
     # just-in-time compilation (section 3.5), beside the main figures: nothing built at compile time, planes built by the
     # fill calls that first reach them; per-step latency of fill (host + device, synchronised) over fresh sentences
+    # fill + apply as one unit (the decode half of the metric): bitmask written once and read once, logits read-modify-written
+    for name, key, e in (("roofline_fill_apply_bf16", "apply_bf16_us", 2), ("roofline_fill_apply_f32", "apply_f32_us", 4)):
+        t = (med(acc["fill_device_us"]) + med(acc[key])) * 1e-6
+        gbs = (2 * B * W * 4 + 2 * B * V * e) / t / 1e9
+        out[name] = {"kernel": "k_fill_or + k_recheck + k_apply_vec", "bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": gbs / HBM_PEAK_GBS, "traffic": None, "us_per_step": t * 1e6,
+                     "accounting": "bitmask write + bitmask read + read-modify-write of all logits, over fill's and apply's device time"}
+
     if args.cross_grammar:
         cfg4 = gen.build_config(4)
         vocab4 = xg.Vocab(cfg4.vocab.tokens, cfg4.vocab.eos_id, cfg4.vocab.special_ids)
