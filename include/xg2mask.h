@@ -117,7 +117,9 @@ int32_t xg2_grammar_num_positions(const xg2_grammar*, int32_t* out);
 /* ---- cross-grammar pool (section 3.3) ---------------------------------------------------------
  * Planes of structurally identical rule positions are built once and shared by every grammar
  * compiled with the same pool and vocabulary.  max_bytes bounds the device memory of the pool
- * (0 = unbounded); when it would be exceeded compile fails with XG2_EOVERFLOW.                  */
+ * (0 = unbounded).  When it is reached, planes that no live mask cache uses are given up, least
+ * recently used first, and built again if a later grammar needs them; if every plane is in use,
+ * compile (or a just-in-time fill) fails with XG2_EOVERFLOW.                                     */
 int32_t xg2_pool_create(size_t max_bytes, xg2_pool** out);
 void    xg2_pool_destroy(xg2_pool*);
 int32_t xg2_pool_stats(const xg2_pool*, int64_t* n_positions, int64_t* device_bytes);

@@ -173,6 +173,13 @@ struct PoolImpl {
     // bounded-bisimulation classes of interned rules, in canonical state numbers: (entry, token-length budget) -> for
     // canonical state c, the canonical state of its representative
     std::map<std::pair<int, int32_t>, std::vector<int32_t>> class_memo;
+    // rows in use: by how many live caches, and when last taken into a cache.  When max_bytes is reached, rows that no
+    // live cache uses are given up, least recently used first, and their memory is handed out again.
+    struct RowMeta { PlaneKey key; int32_t refs; uint64_t stamp; };
+    std::unordered_map<const uint32_t*, RowMeta> meta;
+    std::vector<uint32_t*> free_rows;
+    uint64_t clock = 0;
+    int64_t n_evicted = 0;
     std::vector<void*> slabs;
     uint8_t* slab_cur = nullptr; size_t slab_left = 0;
     size_t device_bytes = 0;
@@ -191,19 +198,52 @@ struct PoolImpl {
         if (shareable) by_hash.emplace(hash, id);
         return id;
     }
+    void take(uint32_t* row, const PlaneKey& key) {              // a cache starts using the row
+        RowMeta& m = meta[row];
+        if (m.refs == 0 && m.stamp == 0) m.key = key;
+        ++m.refs;
+        m.stamp = ++clock;
+    }
+    void release(const uint32_t* row) {
+        auto it = meta.find(row);
+        if (it != meta.end() && it->second.refs > 0) --it->second.refs;
+    }
+    void forget(uint32_t* row) {                                 // the row's content is void: its memory can be reused
+        auto it = meta.find(row);
+        if (it != meta.end()) { rows.erase(it->second.key); meta.erase(it); }
+        no_uncertain.erase(row);
+        free_rows.push_back(row);
+        --n_rows;
+    }
     uint32_t* alloc_row(size_t row_bytes, hipStream_t stream) {
-        if (slab_left < row_bytes) {
+        if (free_rows.empty() && slab_left < row_bytes) {
             size_t want = std::max<size_t>(row_bytes * 64, (size_t)64 << 20);
+            if (max_bytes && device_bytes + want > max_bytes) want = row_bytes * 16;
             if (max_bytes && device_bytes + want > max_bytes) want = row_bytes;
-            if (max_bytes && device_bytes + want > max_bytes) throw std::length_error("cross-grammar pool is full");
-            void* p = nullptr;
-            HIP_CHECK(hipMalloc(&p, want));
-            slabs.push_back(p);
-            HIP_CHECK(hipMemsetAsync(p, 0, want, stream));       // rows are handed out once, so they start as zeros
-            slab_cur = (uint8_t*)p; slab_left = want; device_bytes += want;
+            if (max_bytes && device_bytes + want > max_bytes) {
+                // full: give up the least recently used rows that no live cache uses (a batch, so that the scan is rare)
+                std::vector<std::pair<uint64_t, uint32_t*>> idle;
+                for (auto& kv : meta) if (kv.second.refs == 0) idle.emplace_back(kv.second.stamp, const_cast<uint32_t*>(kv.first));
+                if (idle.empty()) throw std::length_error("cross-grammar pool is full (max_bytes reached and every row is in use)");
+                const size_t batch = std::min<size_t>(idle.size(), std::max<size_t>(64, idle.size() / 8));
+                std::partial_sort(idle.begin(), idle.begin() + (long)batch, idle.end());
+                for (size_t k = 0; k < batch; ++k) { forget(idle[k].second); ++n_evicted; }
+            } else {
+                void* p = nullptr;
+                HIP_CHECK(hipMalloc(&p, want));
+                slabs.push_back(p);
+                HIP_CHECK(hipMemsetAsync(p, 0, want, stream));       // rows are handed out as zeros
+                slab_cur = (uint8_t*)p; slab_left = want; device_bytes += want;
+            }
         }
-        uint32_t* row = (uint32_t*)slab_cur;
-        slab_cur += row_bytes; slab_left -= row_bytes;
+        uint32_t* row;
+        if (!free_rows.empty()) {
+            row = free_rows.back(); free_rows.pop_back();
+            HIP_CHECK(hipMemsetAsync(row, 0, row_bytes, stream));
+        } else {
+            row = (uint32_t*)slab_cur;
+            slab_cur += row_bytes; slab_left -= row_bytes;
+        }
         ++n_rows;
         return row;
     }
@@ -232,7 +272,13 @@ struct CacheImpl {
     std::shared_ptr<PoolImpl> pool;
     std::shared_ptr<GrammarImpl> gram;
     uint8_t* d_tables = nullptr;                            // one device block holding all packed tables
-    ~CacheImpl() { if (d_tables) (void)hipFree(d_tables); }
+    ~CacheImpl() {
+        if (d_tables) (void)hipFree(d_tables);
+        if (pool) {
+            std::lock_guard<std::mutex> lk(pool->mu);
+            for (const PlaneInfo& pi : planes) if (pi.row) pool->release(pi.row);
+        }
+    }
     DevTables dt{};
     int32_t context_depth = 2;
     std::vector<PlaneInfo> planes;
@@ -344,7 +390,7 @@ int32_t build_planes(CacheImpl& cache, const std::vector<int32_t>& todo, hipStre
         PlaneInfo& pi = cache.planes[(size_t)k];
         if (pi.row) continue;
         uint32_t*& row = pool.rows[pi.key];
-        if (row) { pi.row = row; pi.no_uncertain = pool.no_uncertain.count(row) != 0; ++cache.n_built; continue; }   // another grammar built it
+        if (row) { pi.row = row; pi.no_uncertain = pool.no_uncertain.count(row) != 0; pool.take(row, pi.key); ++cache.n_built; continue; }   // another grammar built it
         row = pool.alloc_row(row_bytes, stream);
         build.push_back(k);
         build_rows.push_back(row);
@@ -450,12 +496,17 @@ int32_t build_planes(CacheImpl& cache, const std::vector<int32_t>& todo, hipStre
     HIP_CHECK(hipEventElapsedTime(&res.kernel_ms, evk0, evk1));
     (void)hipEventDestroy(ev0); (void)hipEventDestroy(ev1); (void)hipEventDestroy(evk0); (void)hipEventDestroy(evk1);
     if (slow_counts[1]) {
-        for (int32_t k : build) pool.rows.erase(cache.planes[(size_t)k].key);      // these rows hold partial results: forget them
+        for (size_t k = 0; k < build.size(); ++k) {                       // these rows hold partial results: forget them
+            pool.rows.erase(cache.planes[(size_t)build[k]].key);
+            pool.free_rows.push_back(build_rows[k]);
+            --pool.n_rows;
+        }
         return fail(XG2_EOVERFLOW, "mask cache build: Earley item sets exceeded the large-capacity limit");
     }
     for (size_t k = 0; k < build.size(); ++k) {
         PlaneInfo& pi = cache.planes[(size_t)build[k]];
         pi.row = build_rows[k];
+        pool.take(pi.row, pi.key);
         pi.no_uncertain = plane_counts[2 * k + 1] == 0;
         if (pi.no_uncertain) pool.no_uncertain.insert(build_rows[k]);
         res.n_accepted += plane_counts[2 * k]; res.n_uncertain += plane_counts[2 * k + 1];

@@ -278,6 +278,35 @@ def test_config4_cross_grammar_pool(xg):
     assert built1 == pool1.stats()[0] == len(distinct)              # exact count of distinct structures, the slow way
 
 
+def test_pool_gives_up_unused_planes_when_full(xg):
+    """A pool bounded by max_bytes: planes of destroyed caches are evicted (least recently used first) to make room,
+    rebuilt when needed again, and always equal to the oracle's; a pool whose planes are all in use reports overflow."""
+    cfg, vocab, va = load(1)
+    row_bytes = 2 * vocab.words * 4
+    grammars = ['root ::= "[" [0-9]{1,3} ("," [0-9]{1,3})* "]"\n', 'root ::= "{" ws pair ws "}"\npair ::= "\\"" [a-z]+ "\\"" ws ":" ws [0-9]+\nws ::= " "*\n',
+                'root ::= ("a" | "b" x)+\nx ::= "c" x | "d"\n', 'root ::= t ("+" t)*\nt ::= [0-9]+ | "(" root ")"\n']
+    sizes = []
+    for e in grammars:
+        c = xg.compile_grammar(vocab, e, "root", stream=_stream())
+        sizes.append(c.num_planes())
+        del c
+    cap = max(sizes) + min(sizes) // 2                              # room for the largest grammar plus a few rows
+    pool = xg.Pool(max_bytes=cap * row_bytes)
+    built_total = 0
+    for rnd in range(2):
+        for gi, e in enumerate(grammars):
+            cache, orc = check_planes(xg, cfg, vocab, va, e, "root", pool=pool, max_contexts=1000)   # every plane against the oracle
+            built_total += cache.stats.built
+            assert pool.stats()[0] <= cap and pool.stats()[1] <= cap * row_bytes
+            del cache, orc
+    assert built_total > sum(sizes)                                 # something was evicted and built again
+    keep = xg.compile_grammar(vocab, grammars[sizes.index(max(sizes))], "root", pool=pool, stream=_stream())
+    with pytest.raises(xg.Xg2Error) as err:
+        others = [xg.compile_grammar(vocab, e, "root", pool=pool, stream=_stream()) for e in grammars]
+    assert err.value.code == -4                                     # XG2_EOVERFLOW: every row is in use
+    del keep
+
+
 def test_long_tokens_and_item_overflow_take_the_slow_path(xg):
     """Tokens longer than the LDS path handles (16 bytes) and grammars whose item sets outgrow the LDS
     lists are finished by the large-capacity kernel with the same result."""
