@@ -114,7 +114,8 @@ def test_config1_planes_and_decode(xg, depth, merge, follow):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("B,V,pad", [(2, 2048, 0), (3, 1000, 24), (1, 37, 3), (4, 151936, 0), (2, 4099, 5)])
+@pytest.mark.parametrize("B,V,pad", [(2, 2048, 0), (3, 1000, 24), (1, 37, 3), (4, 151936, 0), (2, 4099, 5),
+                                     (1024, 151936, 0)])               # the last: the shape the benchmark times
 def test_apply_matches_oracle(xg, dtype, B, V, pad):
     import torch
     dev = torch.device("cuda:0")
