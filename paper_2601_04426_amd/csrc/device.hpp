@@ -52,6 +52,7 @@ struct SlowScratch {                     // large-capacity per-lane Earley scrat
     uint32_t* count;                     // [0] = entries in list, [1] = sticky error flag
 };
 constexpr uint32_t kSlowK = 256, kSlowWM = 1024, kSlowMaxLen = 1024;
+constexpr uint32_t kSlowSearchBudget = 1u << 20;     // list entries one token may compare against in the device-memory lists
 constexpr uint32_t kSlowSlots = 2 * kSlowK + 2 * kSlowWM + kSlowMaxLen + 1;
 
 void launch_build(const DevTables& T, const DevVocab& Vd, const BuildPlan& P, const SlowScratch& S, hipStream_t stream);

@@ -59,6 +59,7 @@ constexpr uint32_t EXP_CURRENT = 1u << REF_BITS;
 template <class S>
 __device__ __forceinline__ bool add_nxt(S& st, uint32_t item, int& nn, bool& fresh) {
     fresh = false;
+    if (!st.charge(nn)) return false;                            // large lists: a bound on the searching of one token
     for (int k = 0; k < nn; ++k) if (st.get_nxt(k) == item) return true;
     if (nn == S::K) return false;
     st.set_nxt(nn++, item);
@@ -68,6 +69,7 @@ __device__ __forceinline__ bool add_nxt(S& st, uint32_t item, int& nn, bool& fre
 
 template <class S>
 __device__ __forceinline__ bool add_wait(S& st, uint32_t rule, uint32_t tgt, int& nw, int wbeg) {
+    if (!st.charge(nw - wbeg)) return false;
     for (int k = wbeg; k < nw; ++k) if (st.wait_tgt(k) == tgt && st.wait_rule(k) == rule) return true;
     if (nw == S::WM) return false;
     st.set_wait(nw++, rule, tgt);

@@ -33,6 +33,7 @@ struct LdsStore {
     __device__ uint32_t wait_tgt(int k) const { return wait[k * 128 + 64]; }
     __device__ void set_wait(int k, uint32_t rule, uint32_t tgt) { wait[k * 128] = rule; wait[k * 128 + 64] = tgt; }
     __device__ void swap() { uint32_t* t = cur; cur = nxt; nxt = t; }
+    __device__ bool charge(int) { return true; }   // short lists: nothing to bound
     __device__ void reset() { ws_lo = 0; ws_hi = 0; }
     __device__ void set_wstart(int j, uint32_t v) {
         const int sh = 8 * (j & 7);
@@ -59,6 +60,7 @@ struct LdsStoreWide {
     __device__ uint32_t wait_tgt(int k) const { return wait[k * 128 + 64]; }
     __device__ void set_wait(int k, uint32_t rule, uint32_t tgt) { wait[k * 128] = rule; wait[k * 128 + 64] = tgt; }
     __device__ void swap() { uint32_t* t = cur; cur = nxt; nxt = t; }
+    __device__ bool charge(int) { return true; }
     __device__ void reset() {}
     __device__ void set_wstart(int j, uint32_t v) { ws[j * 64] = v; }
     __device__ uint32_t get_wstart(int j) const { return ws[j * 64]; }
@@ -69,6 +71,8 @@ using MidStore = LdsStoreWide<16, 32, 48>;
 struct GlobalStore {
     static constexpr int K = kSlowK, WM = kSlowWM, MAXLEN = kSlowMaxLen;
     uint32_t* cur; uint32_t* nxt; uint32_t* wait; uint32_t* ws; size_t stride;
+    uint32_t budget = kSlowSearchBudget;           // list entries one token may still compare against: a bound on its run time
+    __device__ bool charge(int n) { if ((uint32_t)n > budget) { budget = 0; return false; } budget -= (uint32_t)n; return true; }
     __device__ void init(uint32_t* base, size_t n_lanes) {
         stride = n_lanes; cur = base; nxt = base + (size_t)K * stride; wait = base + (size_t)2 * K * stride; ws = base + (size_t)(2 * K + 2 * WM) * stride;
     }
@@ -80,7 +84,7 @@ struct GlobalStore {
     __device__ uint32_t wait_tgt(int k) const { return wait[(size_t)(2 * k + 1) * stride]; }
     __device__ void set_wait(int k, uint32_t rule, uint32_t tgt) { wait[(size_t)(2 * k) * stride] = rule; wait[(size_t)(2 * k + 1) * stride] = tgt; }
     __device__ void swap() { uint32_t* t = cur; cur = nxt; nxt = t; }
-    __device__ void reset() {}
+    __device__ void reset() { budget = kSlowSearchBudget; }
     __device__ void set_wstart(int j, uint32_t v) { ws[(size_t)j * stride] = v; }
     __device__ uint32_t get_wstart(int j) const { return ws[(size_t)j * stride]; }
 };
@@ -255,6 +259,7 @@ __global__ __launch_bounds__(64) void k_build_slow(DevTables T, DevVocab Vd, Bui
     GlobalStore st;
     st.init(S.mem + gl, S.n_lanes);
     for (uint32_t idx = gl; idx < count; idx += S.n_lanes) {
+        if (*reinterpret_cast<volatile uint32_t*>(S.count + 1) & 2u) break;      // the build fails anyway: do not spend more on it
         const uint32_t p = S.list[2 * idx], rank = S.list[2 * idx + 1];
         const uint32_t off = Vd.off[rank];
         const int n = (int)(Vd.off[rank + 1] - off);

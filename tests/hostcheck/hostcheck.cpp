@@ -33,6 +33,7 @@ struct HostStore {
     uint32_t wait_tgt(int k) const { return w[2 * (size_t)k + 1]; }
     void set_wait(int k, uint32_t r, uint32_t t) { w[2 * (size_t)k] = r; w[2 * (size_t)k + 1] = t; }
     void swap() { std::swap(cur, nxt); }
+    bool charge(int) { return true; }
     void reset() {}
     void set_wstart(int j, uint32_t v) { ws.at((size_t)j) = v; }
     uint32_t get_wstart(int j) const { return ws.at((size_t)j); }
