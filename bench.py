@@ -28,14 +28,14 @@ HBM_PEAK_GBS = 8000.0
 # valid only for the kernel sources they were taken with.  The same counters read 303,884 KiB (FETCH_SIZE) and
 # 607,744 KiB (WRITE_SIZE) for a device-to-device copy of 607,744 KiB, hence the scale factors.
 PMC = {
-    "sources_sha256": "e169d8a3a2cb093a4eae6889f7e62b3f5aab8428f98af9a821df03b209650d00",
+    "sources_sha256": "4f3b35eb31bcf4cc71a664f415b0bd21de081a3f0323c4887601b8a3a6f76379",
     "fetch_scale": 2.0, "write_scale": 1.0,
-    "k_build": (14465.1, 31867.2),
-    "k_fill_or": (4067.8, 19165.6),
-    "k_apply_vec<8>": (98629.2, 303872.0),
+    "k_build": (14432.9, 31867.2),
+    "k_fill_or": (4066.4, 19165.3),
+    "k_apply_vec<8>": (98626.9, 303872.0),
     # wave instructions of one k_build launch (rocprofv3 --pmc SQ_INSTS_VALU + SALU + BRANCH + LDS + VMEM_RD + VMEM_WR + SMEM)
     "k_build_wave_instructions": 56463750.0,
-    "k_apply_vec<4>": (182229.9, 605511.0),
+    "k_apply_vec<4>": (182234.0, 605511.0),
 }
 KERNEL_SOURCES = ("kernels.hip", "earley_core.hpp", "device.hpp")
 
