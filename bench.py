@@ -28,14 +28,14 @@ HBM_PEAK_GBS = 8000.0
 # valid only for the kernel sources they were taken with.  The same counters read 303,884 KiB (FETCH_SIZE) and
 # 607,744 KiB (WRITE_SIZE) for a device-to-device copy of 607,744 KiB, hence the scale factors.
 PMC = {
-    "sources_sha256": "4f3b35eb31bcf4cc71a664f415b0bd21de081a3f0323c4887601b8a3a6f76379",
+    "sources_sha256": "134ad2b460f5227909a322128fd82469c74cf8b237e46e3dd9c1dc6bddca0d7a",
     "fetch_scale": 2.0, "write_scale": 1.0,
-    "k_build": (14432.9, 31867.2),
-    "k_fill_or": (4066.4, 19165.3),
-    "k_apply_vec<8>": (98626.9, 303872.0),
+    "k_build": (10874.3, 3381.5),
+    "k_fill_or": (4067.4, 19165.1),
+    "k_apply_vec<8>": (98627.4, 303872.0),
     # wave instructions of one k_build launch (rocprofv3 --pmc SQ_INSTS_VALU + SALU + BRANCH + LDS + VMEM_RD + VMEM_WR + SMEM)
-    "k_build_wave_instructions": 56463750.0,
-    "k_apply_vec<4>": (182234.0, 605511.0),
+    "k_build_wave_instructions": 33494421.0,
+    "k_apply_vec<4>": (182233.5, 605511.0),
 }
 KERNEL_SOURCES = ("kernels.hip", "earley_core.hpp", "device.hpp")
 

@@ -55,6 +55,19 @@ struct DevBuf {                                    // owning device array
     }
 };
 
+// Pinned host memory to device memory on `stream`: small blocks by a copy kernel that reads the host memory through its
+// device-side address (less latency than the copy engine), large ones by the runtime.  bytes: a multiple of 16.
+constexpr size_t kUploadByKernelMax = (size_t)4 << 20;
+inline void upload_pinned(void* dev, void* host, size_t bytes, hipStream_t stream) {
+    if (bytes <= kUploadByKernelMax) {
+        void* mapped = nullptr;
+        HIP_CHECK(hipHostGetDevicePointer(&mapped, host, 0));
+        launch_upload(dev, mapped, bytes, stream);
+    } else {
+        HIP_CHECK(hipMemcpyAsync(dev, host, bytes, hipMemcpyHostToDevice, stream));
+    }
+}
+
 // Several host arrays laid out back to back (256-byte aligned) in one pinned buffer, moved to the device
 // with one copy.
 struct Packer {
@@ -76,7 +89,7 @@ struct Packer {
         HIP_CHECK(hipMalloc((void**)&dev, n));
         for (const Seg& s : segs) if (s.bytes) std::memcpy(host + s.off, s.src, s.bytes);
     }
-    void copy(hipStream_t stream) { if (total) HIP_CHECK(hipMemcpyAsync(dev, host, total, hipMemcpyHostToDevice, stream)); }
+    void copy(hipStream_t stream) { if (total) upload_pinned(dev, host, total, stream); }
     template <typename T> T* at(size_t off) const { return reinterpret_cast<T*>(dev + off); }
     uint8_t* release_dev() { own_dev = false; return dev; }
     ~Packer() { if (host) (void)hipHostFree(host); if (dev && own_dev) (void)hipFree(dev); }
@@ -106,6 +119,12 @@ struct VocabImpl {
     bool on_device = false;
     DevBuf<uint8_t> d_bytes; DevBuf<uint32_t> d_off, d_perm, d_rank; DevBuf<uint4> d_tok16;
     DevVocab dv{};
+    // per length bound d = 1 .. near_depths: the sorted ranks of the tokens longer than d bytes (ascending; list d is
+    // long_rank[long_off[d] .. long_off[d + 1])), and on the device also the mask, in token ids, of the checkable tokens
+    // of at most d bytes (row d - 1 of d_short_mask)
+    uint32_t near_depths = 0;
+    std::vector<uint32_t> long_rank, long_off;
+    DevBuf<uint32_t> d_long_rank, d_short_mask;
 
     const uint8_t* tok(int32_t id) const { return bytes.data() + offs[(size_t)id]; }
     size_t len(int32_t id) const { return (size_t)(offs[(size_t)id + 1] - offs[(size_t)id]); }
@@ -124,7 +143,22 @@ struct VocabImpl {
         for (uint32_t r = 0; r < n_sorted; ++r)
             std::memcpy(&tok16[r], s_bytes.data() + s_off[r], std::min<size_t>(16, s_off[r + 1] - s_off[r]));
         d_tok16.upload(tok16, nullptr);
+        near_depths = max_len > 1 ? std::min<uint32_t>(max_len - 1, (uint32_t)kMaxNearDepth) : 0;
+        long_off.assign((size_t)near_depths + 2, 0);
+        std::vector<uint32_t> short_mask((size_t)std::max<uint32_t>(near_depths, 1) * W, 0u);
+        for (uint32_t d = 1; d <= near_depths; ++d) {
+            long_off[d] = (uint32_t)long_rank.size();
+            for (uint32_t r = 0; r < n_sorted; ++r) {
+                if (s_off[r + 1] - s_off[r] > d) long_rank.push_back(r);
+                else short_mask[(size_t)(d - 1) * W + (perm[r] >> 5)] |= 1u << (perm[r] & 31);
+            }
+        }
+        long_off[(size_t)near_depths + 1] = (uint32_t)long_rank.size();
+        if (long_rank.empty()) long_rank.push_back(0);
+        d_long_rank.upload(long_rank, nullptr);
+        d_short_mask.upload(short_mask, nullptr);
         HIP_CHECK(hipStreamSynchronize(nullptr));
+        dv.long_rank = d_long_rank.p;
         dv.tok16 = d_tok16.p;
         dv.bytes = d_bytes.p; dv.off = d_off.p; dv.perm = d_perm.p; dv.rank = d_rank.p;
         dv.n_sorted = n_sorted; dv.V = (uint32_t)V; dv.W = W;
@@ -172,7 +206,8 @@ struct PoolImpl {
     std::unordered_set<const uint32_t*> no_uncertain;      // rows whose uncertain plane is all zero (need not be read)
     // bounded-bisimulation classes of interned rules, in canonical state numbers: (entry, token-length budget) -> for
     // canonical state c, the canonical state of its representative
-    std::map<std::pair<int, int32_t>, std::vector<int32_t>> class_memo;
+    struct ClassMemo { std::vector<int32_t> rep, base, depth; };            // by canonical state number
+    std::map<std::pair<int, int32_t>, ClassMemo> class_memo;
     // rows in use: by how many live caches, and when last taken into a cache.  When max_bytes is reached, rows that no
     // live cache uses are given up, least recently used first, and their memory is handed out again.
     struct RowMeta { PlaneKey key; int32_t refs; uint64_t stamp; };
@@ -257,6 +292,7 @@ struct PlaneInfo {
     PlaneKey key;                                           // identity in the pool
     uint32_t sid; int64_t waiter_sid;                       // start of the build: position, and the waiting parent state or -1
     uint64_t cost;                                          // estimate of the build work (tokens whose first byte the state reads)
+    int32_t near_plane = -1, near_depth = 0;                // a plane with the same classes for every token of at most near_depth bytes
 };
 struct BuildResult {
     int64_t built = 0, executed = 0, slow = 0, n_accepted = 0, n_uncertain = 0;
@@ -400,10 +436,28 @@ int32_t build_planes(CacheImpl& cache, const std::vector<int32_t>& todo, hipStre
     // plan: closed start set and live first-byte ranges of every plane to build
     std::vector<uint32_t> ctx_items, ctx_wait, ctx_wait_off;
     std::vector<uint4> chunks, plane_ctx;
+    std::vector<CopyJob> copies;
     int64_t executed = 0;
     EarleyChart chart(&ft);
+    std::map<int32_t, size_t> building;                         // plane index -> position in build
+    for (size_t k = 0; k < build.size(); ++k) building.emplace(build[k], k);
     for (size_t k = 0; k < build.size(); ++k) {
         const PlaneInfo& pi = cache.planes[(size_t)build[k]];
+        // short tokens from a plane that agrees on them, if that plane is there or is being built in this call
+        uint32_t near_d = 0;
+        if (pi.near_plane >= 0 && pi.near_depth >= 1 && V.near_depths >= 1) {
+            const uint32_t* src = cache.planes[(size_t)pi.near_plane].row;
+            if (!src) {
+                auto pr = pool.rows.find(cache.planes[(size_t)pi.near_plane].key);
+                auto bi = building.find(pi.near_plane);
+                if (bi != building.end()) src = build_rows[bi->second];
+                else if (pr != pool.rows.end() && pr->second) src = pr->second;
+            }
+            if (src) {
+                near_d = std::min<uint32_t>((uint32_t)pi.near_depth, V.near_depths);
+                copies.push_back({build_rows[k], src, V.d_short_mask.p + (size_t)(near_d - 1) * V.W, 0});
+            }
+        }
         if (pi.waiter_sid < 0) chart.start(pi.sid);
         else chart.start_pair(pi.sid, (uint32_t)pi.waiter_sid);
         const std::vector<ChartSet>& sets = chart.sets();
@@ -431,13 +485,22 @@ int32_t build_planes(CacheImpl& cache, const std::vector<int32_t>& todo, hipStre
             if (!live[b]) { ++b; continue; }
             int e = b;
             while (live[e + 1]) ++e;
-            uint32_t lo = V.fb_start[b], hi = V.fb_start[e + 1];
-            for (uint32_t c = lo; c < hi; c += kBuildChunk) chunks.push_back(make_uint4((uint32_t)k, c, std::min(hi, c + kBuildChunk), heavy));
+            uint32_t lo = V.fb_start[b], hi = V.fb_start[e + 1], listed = 0;
+            if (near_d) {                                            // the same ranks, in the list of the tokens longer than near_d
+                const uint32_t* first = V.long_rank.data() + V.long_off[near_d];
+                const uint32_t* last = V.long_rank.data() + V.long_off[near_d + 1];
+                lo = (uint32_t)(std::lower_bound(first, last, lo) - V.long_rank.data());
+                hi = (uint32_t)(std::lower_bound(first, last, hi) - V.long_rank.data());
+                listed = kChunkListed;
+            }
+            const uint32_t step = heavy ? kHeavyChunk : kBuildChunk;
+            for (uint32_t c = lo; c < hi; c += step)
+                chunks.push_back(make_uint4((uint32_t)k, c, std::min(hi, c + step), listed | (heavy ? kChunkHeavy : 0u)));
             executed += hi - lo;
             b = e + 1;
         }
     }
-    std::stable_sort(chunks.begin(), chunks.end(), [](const uint4& a, const uint4& b) { return a.w > b.w; });
+    std::stable_sort(chunks.begin(), chunks.end(), [](const uint4& a, const uint4& b) { return (a.w & kChunkHeavy) > (b.w & kChunkHeavy); });
 
     // everything the device needs goes up in one copy: (the tables,) the plan, and a few zeroed words (overflow
     // counter and flag, bit counts per built plane).  With the tables the block stays with the cache.
@@ -449,7 +512,7 @@ int32_t build_planes(CacheImpl& cache, const std::vector<int32_t>& todo, hipStre
         o_trans = tab.add(ft.trans); o_cls = tab.add(ft.byte_class_words);
     }
     const size_t o_chunks = tab.add(chunks), o_pctx = tab.add(plane_ctx), o_items = tab.add(ctx_items), o_wait = tab.add(ctx_wait),
-                 o_wait_off = tab.add(ctx_wait_off), o_rows = tab.add(build_rows), o_zero = tab.add(zeros);
+                 o_wait_off = tab.add(ctx_wait_off), o_rows = tab.add(build_rows), o_copies = tab.add(copies), o_zero = tab.add(zeros);
     tab.stage();
     res.host_ms = ms_since(t1);
 
@@ -484,6 +547,7 @@ int32_t build_planes(CacheImpl& cache, const std::vector<int32_t>& todo, hipStre
     if (!build.empty()) launch_build(cache.dt, V.dv, P, S, stream);
     HIP_CHECK(hipEventRecord(evk1, stream));
     if (!build.empty()) launch_build_slow(cache.dt, V.dv, P, S, stream);
+    launch_copy_masked(tab.at<const CopyJob>(o_copies), (uint32_t)copies.size(), V.W, stream);
     HIP_CHECK(hipEventRecord(ev1, stream));                              // every plane is written
     if (!build.empty()) launch_popcount(d_rows_p, (uint32_t)build_rows.size(), V.W, d_counts, stream);   // statistics
     uint32_t slow_counts[2] = {0, 0};
@@ -725,6 +789,7 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
 
         // states that tokens cannot tell apart share planes
         std::vector<std::vector<int32_t>> rep, classes;
+        std::vector<NearClasses> near((size_t)R);
         if (merge || follow) {
             const int32_t class_budget = (int32_t)std::max<uint32_t>(V.max_len, 1);
             classes.resize((size_t)R);
@@ -735,17 +800,31 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
                 for (int x = 0; x < n; ++x) by_canon[(size_t)f.canon_id[(size_t)x]] = x;
                 auto key = std::make_pair(entry[(size_t)r], class_budget);
                 auto hit = f.shareable ? pool.class_memo.find(key) : pool.class_memo.end();
-                if (hit != pool.class_memo.end() && (int)hit->second.size() == n) {
+                NearClasses& nr = near[(size_t)r];
+                if (hit != pool.class_memo.end() && (int)hit->second.rep.size() == n) {
                     // an identical rule was analysed before (this grammar or an earlier one): translate through the canonical numbers
+                    const PoolImpl::ClassMemo& cm = hit->second;
                     classes[(size_t)r].resize((size_t)n);
-                    for (int x = 0; x < n; ++x) classes[(size_t)r][(size_t)x] = by_canon[(size_t)hit->second[(size_t)f.canon_id[(size_t)x]]];
+                    nr.base.resize((size_t)n); nr.depth.resize((size_t)n);
+                    for (int x = 0; x < n; ++x) {
+                        const size_t c = (size_t)f.canon_id[(size_t)x];
+                        classes[(size_t)r][(size_t)x] = by_canon[(size_t)cm.rep[c]];
+                        nr.base[(size_t)x] = cm.base[c] < 0 ? -1 : by_canon[(size_t)cm.base[c]];
+                        nr.depth[(size_t)x] = cm.depth[c];
+                    }
                     continue;
                 }
-                classes[(size_t)r] = bounded_classes_rule(g, r, class_budget, ref_id);
+                classes[(size_t)r] = bounded_classes_rule(g, r, class_budget, ref_id, &nr);
                 if (f.shareable) {
-                    std::vector<int32_t> canon((size_t)n);
-                    for (int x = 0; x < n; ++x) canon[(size_t)f.canon_id[(size_t)x]] = f.canon_id[(size_t)classes[(size_t)r][(size_t)x]];
-                    pool.class_memo.emplace(key, std::move(canon));
+                    PoolImpl::ClassMemo cm;
+                    cm.rep.resize((size_t)n); cm.base.resize((size_t)n); cm.depth.resize((size_t)n);
+                    for (int x = 0; x < n; ++x) {
+                        const size_t c = (size_t)f.canon_id[(size_t)x];
+                        cm.rep[c] = f.canon_id[(size_t)classes[(size_t)r][(size_t)x]];
+                        cm.base[c] = nr.base[(size_t)x] < 0 ? -1 : f.canon_id[(size_t)nr.base[(size_t)x]];
+                        cm.depth[c] = nr.depth[(size_t)x];
+                    }
+                    pool.class_memo.emplace(key, std::move(cm));
                 }
             }
         }
@@ -776,19 +855,23 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
 
         // planes of this grammar
         std::map<PlaneKey, int32_t> local_plane;
-        auto plane_for = [&](int rp, int sp_rep, const Site* site) -> int32_t {
+        auto make_key = [&](int rp, int sp_rep, int site_q, int site_x) -> PlaneKey {
             const RuleFsm& fp = g.rules[(size_t)rp];
             PlaneKey key{entry[(size_t)rp], fp.canon_id[(size_t)sp_rep], -1, -1, 0};
-            if (site) { key[2] = entry[(size_t)site->q]; key[3] = g.rules[(size_t)site->q].canon_id[(size_t)site->x]; }
+            if (site_q >= 0) { key[2] = entry[(size_t)site_q]; key[3] = g.rules[(size_t)site_q].canon_id[(size_t)site_x]; }
             if (follow) {
                 // a token reaches what follows the outermost rule only after the shortest way out of the plane's rules, so
                 // the plane depends on the follow language no deeper than the bytes that are left then: planes whose way out
                 // is long are shared between grammars that differ only further on
                 int64_t need = follow_info.min_suf[(size_t)rp][(size_t)sp_rep];
-                if (site) need += follow_info.min_suf[(size_t)site->q][(size_t)site->x];
+                if (site_q >= 0) need += follow_info.min_suf[(size_t)site_q][(size_t)site_x];
                 const int64_t depth_left = std::max<int64_t>(0, (int64_t)budget - std::max<int64_t>(1, need));
-                key[4] = (int64_t)(follow_info.sig[(size_t)(site ? site->q : rp)][(size_t)depth_left] | 1);
+                key[4] = (int64_t)(follow_info.sig[(size_t)(site_q >= 0 ? site_q : rp)][(size_t)depth_left] | 1);
             }
+            return key;
+        };
+        auto plane_for = [&](int rp, int sp_rep, const Site* site) -> int32_t {
+            const PlaneKey key = make_key(rp, sp_rep, site ? site->q : -1, site ? site->x : -1);
             auto lp = local_plane.find(key);
             if (lp != local_plane.end()) return lp->second;
             const uint32_t sid = (uint32_t)g.sid(rp, sp_rep);
@@ -817,6 +900,18 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
                     cache->pair_plane[((uint64_t)(uint32_t)ps.sid << 32) | (uint32_t)g.sid(st.q, st.x)] = plane_for(ps.rule, sp_rep, &sr);
                 }
         }
+
+        // planes that coincide with another plane of the same rule and context on all short tokens (section 3.6: the states
+        // near the end of a long repetition differ from the ones inside it only on tokens long enough to reach the bound)
+        if (merge)
+            for (PlaneInfo& pi : cache->planes) {
+                const NearClasses& nr = near[(size_t)pi.rule];
+                if (nr.base.empty() || nr.base[(size_t)pi.state] < 0) continue;
+                auto lp = local_plane.find(make_key(pi.rule, nr.base[(size_t)pi.state], pi.parent_rule, pi.parent_state));
+                if (lp == local_plane.end()) continue;
+                pi.near_plane = lp->second;
+                pi.near_depth = nr.depth[(size_t)pi.state];
+            }
 
         // per rule, the states referencing rules continue in: one per class of indistinguishable states
         cache->follow = follow;
@@ -1103,7 +1198,7 @@ int32_t xg2_fill_next_token_bitmask(xg2_matcher* const* matchers, int32_t B, int
         std::memset(slot.host + o_zero, 0, 4 * sizeof(uint32_t));
         fill_ws().ensure_scratch((size_t)B * V.W, (size_t)B);
         HIP_CHECK(hipEventRecord(fill_ws().t_begin, stream));
-        HIP_CHECK(hipMemcpyAsync(slot.dev, slot.host, total, hipMemcpyHostToDevice, stream));
+        upload_pinned(slot.dev, slot.host, total, stream);
         FillBatch F{};
         F.rows = reinterpret_cast<const FillRow*>(slot.dev + o_rows); F.B = (uint32_t)B;
         F.front_planes = reinterpret_cast<const uint64_t*>(slot.dev + o_front);

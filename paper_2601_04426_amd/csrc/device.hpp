@@ -24,20 +24,27 @@ struct DevVocab {                        // byte-sorted vocabulary in HBM
                                          // instead of sixteen byte loads for the tokens the LDS path handles
     const uint32_t* perm;                // sorted rank -> token id
     const uint32_t* rank;                // token id -> sorted rank, 0xFFFFFFFF for tokens never checked
+    const uint32_t* long_rank;           // per length bound d, ascending: the sorted ranks of the tokens longer than d bytes
     uint32_t n_sorted;                   // checkable tokens (non-special, non-empty)
     uint32_t V, W;
 };
 
 // Work plan of one cache build.  Chunk c covers sorted ranks [chunk[c].y, chunk[c].z) of plane chunk[c].x
-// (at most kBuildChunk tokens, all with a first byte the plane's start set can read); the workgroups of a
-// persistent grid take chunks round-robin.  plane_ctx[k] = {first item, number of items, first wait offset, H} describes the closed start
+// (at most kBuildChunk tokens, all with a first byte the plane's start set can read); with bit 0 of chunk[c].w
+// set, y and z index DevVocab::long_rank instead and the ranks are read from there (a plane that needs only
+// its long tokens checked).  The workgroups of a persistent grid take chunks round-robin.  plane_ctx[k] = {first item, number of items, first wait offset, H} describes the closed start
 // set of plane k as a scan context (H = 1: the position alone; H = 2: the position inside one level of
 // referencing rule).  ctx_wait holds, set after set, what the waiting items wait for as pairs
 // {rule, state reference of the target | origin << 21}; ctx_wait_off counts pairs.
 #ifndef XG2_BUILD_CHUNK
-#define XG2_BUILD_CHUNK 256
+#define XG2_BUILD_CHUNK 128
 #endif
 constexpr uint32_t kBuildChunk = XG2_BUILD_CHUNK;
+#ifndef XG2_HEAVY_CHUNK
+#define XG2_HEAVY_CHUNK XG2_BUILD_CHUNK
+#endif
+constexpr uint32_t kHeavyChunk = XG2_HEAVY_CHUNK;             // chunk size of planes whose tokens all take the Earley steps
+static_assert(kHeavyChunk <= kBuildChunk, "the deferred list is sized for kBuildChunk");
 struct BuildPlan {
     const uint4* chunk; uint32_t n_chunks;
     const uint4* plane_ctx;                                     // [n_planes]
@@ -54,6 +61,13 @@ struct SlowScratch {                     // large-capacity per-lane Earley scrat
 constexpr uint32_t kSlowK = 256, kSlowWM = 1024, kSlowMaxLen = 1024;
 constexpr uint32_t kSlowSearchBudget = 1u << 20;     // list entries one token may compare against in the device-memory lists
 constexpr uint32_t kSlowSlots = 2 * kSlowK + 2 * kSlowWM + kSlowMaxLen + 1;
+
+constexpr uint32_t kChunkListed = 1u, kChunkHeavy = 2u;      // bits of chunk[c].w
+
+// dst gets, for the tokens in mask (token ids, W words), the bits src holds: both rows of a plane at once
+// (accepted at [0, W), uncertain at [W, 2 W)).  The mask bits of dst must be clear before.
+struct CopyJob { uint32_t* dst; const uint32_t* src; const uint32_t* mask; uint64_t pad; };
+void launch_copy_masked(const CopyJob* jobs_dev, uint32_t n_jobs, uint32_t W, hipStream_t stream);
 
 void launch_build(const DevTables& T, const DevVocab& Vd, const BuildPlan& P, const SlowScratch& S, hipStream_t stream);
 void launch_build_slow(const DevTables& T, const DevVocab& Vd, const BuildPlan& P, const SlowScratch& S, hipStream_t stream);
@@ -86,6 +100,10 @@ void launch_fill(const FillBatch& F, const DevVocab& Vd, int32_t* bitmask_dev, i
                  const SlowScratch& S, hipStream_t stream);
 void launch_recheck_slow(const FillBatch& F, const DevVocab& Vd, int32_t* bitmask_dev, int64_t row_stride_words,
                          const SlowScratch& S, hipStream_t stream);
+
+// Copies `bytes` (a multiple of 16) from pinned host memory, given by its device-side address, to device memory with
+// a kernel: for the small per-call uploads this has less latency than the copy engine.
+void launch_upload(void* dst_dev, const void* src_host_mapped, size_t bytes, hipStream_t stream);
 
 void launch_apply(void* logits_dev, int32_t dtype, int32_t B, int32_t V, int64_t row_stride_elems,
                   const int32_t* bitmask_dev, int64_t bm_row_stride_words, hipStream_t stream);

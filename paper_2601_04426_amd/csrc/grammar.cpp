@@ -1090,7 +1090,8 @@ std::vector<std::vector<int32_t>> bounded_classes(const Grammar& g, int32_t budg
     return rep;
 }
 
-std::vector<int32_t> bounded_classes_rule(const Grammar& g, int32_t rule, int32_t budget, const std::vector<uint64_t>& ref_identity) {
+std::vector<int32_t> bounded_classes_rule(const Grammar& g, int32_t rule, int32_t budget, const std::vector<uint64_t>& ref_identity,
+                                          NearClasses* near) {
     std::vector<int32_t> rep_r;
     {
         const size_t r = (size_t)rule;
@@ -1160,6 +1161,32 @@ std::vector<int32_t> bounded_classes_rule(const Grammar& g, int32_t rule, int32_
         }
         rep_r.resize((size_t)n);
         for (int x = 0; x < n; ++x) rep_r[(size_t)x] = best[fin[(size_t)x]];
+        if (near) {
+            // classes in the order of falling size (the class a long repetition collapses into comes first); each looks
+            // for the deepest level at which it still coincides with a class that is built in full
+            near->base.assign((size_t)n, -1);
+            near->depth.assign((size_t)n, 0);
+            std::map<int32_t, int32_t> weight;
+            for (int x = 0; x < n; ++x) ++weight[fin[(size_t)x]];
+            std::vector<int32_t> reps;
+            for (auto& kv : best) reps.push_back(kv.second);
+            std::stable_sort(reps.begin(), reps.end(), [&](int32_t a, int32_t b) {
+                const int32_t wa = weight[fin[(size_t)a]], wb = weight[fin[(size_t)b]];
+                return wa != wb ? wa > wb : f.canon_id[(size_t)a] < f.canon_id[(size_t)b];
+            });
+            const int32_t top = std::min<int32_t>(budget - 1, kMaxNearDepth);
+            std::vector<std::map<int32_t, int32_t>> full((size_t)std::max(top + 1, 1));   // per level: class -> a class built in full
+            for (int32_t x : reps) {
+                if (f.bedges[(size_t)x].empty()) continue;                               // no plane
+                int32_t d = top;
+                for (; d >= kMinNearDepth; --d) {
+                    auto it = full[(size_t)d].find(level[(size_t)d][(size_t)x]);
+                    if (it != full[(size_t)d].end()) { near->base[(size_t)x] = it->second; near->depth[(size_t)x] = d; break; }
+                }
+                if (d < kMinNearDepth)
+                    for (int32_t e = kMinNearDepth; e <= top; ++e) full[(size_t)e].emplace(level[(size_t)e][(size_t)x], x);
+            }
+        }
     }
     return rep_r;
 }

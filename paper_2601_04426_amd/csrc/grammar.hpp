@@ -62,7 +62,15 @@ uint64_t hash_combine(uint64_t h, uint64_t v);        // the order-sensitive has
 std::vector<std::vector<int32_t>> bounded_classes(const Grammar& g, int32_t budget, const std::vector<uint64_t>& ref_identity);
 // One rule of the above.  The result depends only on the rule's structure and on the identities (and through them the
 // shortest sentence and nullability) of the rules it references.
-std::vector<int32_t> bounded_classes_rule(const Grammar& g, int32_t rule, int32_t budget, const std::vector<uint64_t>& ref_identity);
+// near (optional): for the representative x of a class, near->base[x] is the representative of another class of the
+// same rule that no string of at most near->depth[x] bytes tells apart from x (-1: none worth using), so the plane of
+// x equals the plane of base[x] on every token of at most depth[x] bytes and only the longer tokens need checking.
+// Bases are never derived themselves.
+struct NearClasses { std::vector<int32_t> base, depth; };
+constexpr int32_t kMinNearDepth = 3;       // shorter agreements save too few tokens to be worth a second pass
+constexpr int32_t kMaxNearDepth = 32;
+std::vector<int32_t> bounded_classes_rule(const Grammar& g, int32_t rule, int32_t budget, const std::vector<uint64_t>& ref_identity,
+                                          NearClasses* near = nullptr);
 
 // Per rule and per depth d <= budget, a 64-bit signature of everything that can follow an instance of the rule within
 // d bytes in this grammar: the set of states referencing rules continue in (as structural hashes of their

@@ -163,15 +163,19 @@ __global__ __launch_bounds__(64) void k_build(DevTables T, DevVocab Vd, BuildPla
         const DevCtx C = position_ctx(P, p);
         const uint32_t item0 = C.items[0];
         const bool walkable = C.n_items == 1 && (item0 & (F_BYTE | F_REF | F_FINAL)) == F_BYTE;   // same for the whole chunk
+        const bool listed = chunk.w & kChunkListed;                 // ranks come from a list of long tokens
         uint32_t n_work = chunk.z - chunk.y;
         if (walkable) {
             n_work = 0;
             for (uint32_t rank0 = chunk.y; rank0 < chunk.z; rank0 += 64) {
-                const uint32_t rank = rank0 + lane;
+                uint32_t rank = rank0 + lane;
                 bool defer = false;
                 int n = 0;
                 uint4 tv = make_uint4(0, 0, 0, 0);
-                if (rank < chunk.z) { n = (int)(Vd.off[rank + 1] - Vd.off[rank]); tv = Vd.tok16[rank]; }
+                if (rank < chunk.z) {
+                    if (listed) rank = Vd.long_rank[rank];
+                    n = (int)(Vd.off[rank + 1] - Vd.off[rank]); tv = Vd.tok16[rank];
+                }
                 if (n > BuildStore::MAXLEN) { defer = true; n = 0; }   // phase 2 hands it to the large-capacity kernel
                 bool walking = n > 0;
                 uint32_t sid = item0 & SID_MASK;
@@ -202,7 +206,7 @@ __global__ __launch_bounds__(64) void k_build(DevTables T, DevVocab Vd, BuildPla
             bool again = false;
             uint32_t rank = 0;
             if (idx < n_work) {
-                rank = walkable ? deferred[idx] : chunk.y + idx;
+                rank = walkable ? deferred[idx] : listed ? Vd.long_rank[chunk.y + idx] : chunk.y + idx;
                 const int n = (int)(Vd.off[rank + 1] - Vd.off[rank]);
                 RegBytes tok;
                 tok.v = Vd.tok16[rank];
@@ -272,6 +276,20 @@ __global__ __launch_bounds__(64) void k_build_slow(DevTables T, DevVocab Vd, Bui
 }
 
 // Set bits of the freshly built planes: counts[2p] = accepted, counts[2p + 1] = uncertain bits of plane p.
+__global__ __launch_bounds__(256) void k_upload(uint4* dst, const uint4* src, size_t n) {
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) dst[i] = src[i];
+}
+
+__global__ __launch_bounds__(256) void k_copy_masked(const CopyJob* jobs, uint32_t W) {
+    const CopyJob j = jobs[blockIdx.y];
+    const uint32_t w = blockIdx.x * 256 + threadIdx.x;
+    if (w >= W) return;
+    const uint32_t m = j.mask[w];
+    if (!m) return;
+    j.dst[w] |= j.src[w] & m;
+    j.dst[W + w] |= j.src[W + w] & m;
+}
+
 __global__ __launch_bounds__(256) void k_popcount(const uint32_t* const* plane_ptr, uint32_t n_pos, uint32_t W, uint32_t* counts) {
     __shared__ uint32_t part[2][4];
     const uint32_t p = blockIdx.x;
@@ -530,6 +548,21 @@ void launch_build(const DevTables& T, const DevVocab& Vd, const BuildPlan& P, co
 
 void launch_build_slow(const DevTables& T, const DevVocab& Vd, const BuildPlan& P, const SlowScratch& S, hipStream_t stream) {
     hipLaunchKernelGGL(k_build_slow, dim3(S.n_lanes / 64), dim3(64), 0, stream, T, Vd, P, S);
+}
+
+void launch_upload(void* dst_dev, const void* src_host_mapped, size_t bytes, hipStream_t stream) {
+    const size_t n = bytes / sizeof(uint4);
+    if (!n) return;
+    const uint32_t grid = (uint32_t)std::min<size_t>((n + 255) / 256, 2048);
+    hipLaunchKernelGGL(k_upload, dim3(grid), dim3(256), 0, stream, static_cast<uint4*>(dst_dev), static_cast<const uint4*>(src_host_mapped), n);
+}
+
+void launch_copy_masked(const CopyJob* jobs_dev, uint32_t n_jobs, uint32_t W, hipStream_t stream) {
+    if (!n_jobs) return;
+    for (uint32_t first = 0; first < n_jobs; first += 65535) {      // grid.y limit
+        const uint32_t n = std::min<uint32_t>(65535, n_jobs - first);
+        hipLaunchKernelGGL(k_copy_masked, dim3((W + 255) / 256, n), dim3(256), 0, stream, jobs_dev + first, W);
+    }
 }
 
 void launch_popcount(const uint32_t* const* plane_ptr_dev, uint32_t n_pos, uint32_t W, uint32_t* counts_dev, hipStream_t stream) {
