@@ -148,3 +148,59 @@ extern "C" long long xg2hc_check(const char* ebnf, size_t len, const char* root,
         return -1;
     }
 }
+
+// States the library treats as equivalent on short tokens: for every state x that the bounded-class analysis gives a
+// base b and a depth d (no string of at most d bytes tells x from b), the host parser must give every token of at
+// most d bytes the same result from x as from b, alone and inside every state that references the rule.  Returns the
+// number of (state, context, token) comparisons, or -(1 + that number) at the first difference; *n_near = states
+// that have a base.  Rules are given distinct identities, as for a grammar compiled without a pool.
+extern "C" long long xg2hc_check_near(const char* ebnf, size_t len, const char* root, const uint8_t* bytes, const uint64_t* offs, int n_tok,
+                                      char* msg, size_t msg_cap, long long* n_near, long long* max_depth) {
+    try {
+        Grammar g = lower_grammar(std::string(ebnf, len), root);
+        FlatTables ft = flatten(g);
+        int32_t budget = 1;
+        for (int k = 0; k < n_tok; ++k) budget = std::max<int32_t>(budget, (int32_t)(offs[k + 1] - offs[k]));
+        std::vector<uint64_t> ids(g.rules.size());
+        for (size_t r = 0; r < ids.size(); ++r) ids[r] = r + 1;
+        long long checked = 0, near_states = 0, deepest = 0;
+        EarleyChart cx(&ft), cb(&ft);
+        for (size_t r = 0; r < g.rules.size(); ++r) {
+            NearClasses nc;
+            std::vector<int32_t> rep = bounded_classes_rule(g, (int32_t)r, budget, ids, &nc);
+            std::vector<int64_t> waiters{-1};
+            for (size_t w = 0; w < ft.state_info.size(); ++w) {
+                const StateInfo& wi = ft.state_info[w];
+                for (uint32_t e = 0; e < (wi.counts >> 16); ++e)
+                    if (ft.ref_edges[wi.ref_off + e].rule == (uint32_t)r) { waiters.push_back((int64_t)w); break; }
+            }
+            for (int x = 0; x < g.rules[r].n_states(); ++x) {
+                const int32_t b = nc.base[(size_t)x], d = nc.depth[(size_t)x];
+                if (b < 0) continue;
+                ++near_states;
+                deepest = std::max<long long>(deepest, d);
+                if (nc.base[(size_t)b] >= 0) { snprintf(msg, msg_cap, "rule %zu: base %d of state %d has a base itself", r, b, x); return -checked - 1; }
+                for (int64_t w : waiters) {
+                    if (w < 0) { cx.start((uint32_t)g.sid((int32_t)r, x)); cb.start((uint32_t)g.sid((int32_t)r, b)); }
+                    else { cx.start_pair((uint32_t)g.sid((int32_t)r, x), (uint32_t)w); cb.start_pair((uint32_t)g.sid((int32_t)r, b), (uint32_t)w); }
+                    for (int k = 0; k < n_tok; ++k) {
+                        const size_t n = (size_t)(offs[k + 1] - offs[k]);
+                        if (n == 0 || n > (size_t)d) continue;
+                        ++checked;
+                        const int rx = host_result(cx, bytes + offs[k], n), rb = host_result(cb, bytes + offs[k], n);
+                        if (rx != rb) {
+                            snprintf(msg, msg_cap, "rule %zu state %d (base %d, depth %d) waiter %lld token %d: %d vs %d", r, x, b, d, (long long)w, k, rx, rb);
+                            return -checked - 1;
+                        }
+                    }
+                }
+            }
+        }
+        if (n_near) *n_near = near_states;
+        if (max_depth) *max_depth = deepest;
+        return checked;
+    } catch (const std::exception& e) {
+        snprintf(msg, msg_cap, "exception: %s", e.what());
+        return -1;
+    }
+}

@@ -92,3 +92,44 @@ def test_core_matches_host_parser_on_workloads(hostcheck, index, n_tokens, max_c
     assert n >= len(sample) * 10
     # the capacities of the LDS path are meant to cover these workloads without the device-memory path
     assert small <= n // 100
+
+
+def run_near(h, ebnf, root, tokens):
+    blob = b"".join(tokens)
+    offs = [0]
+    for t in tokens:
+        offs.append(offs[-1] + len(t))
+    offs_c = (ctypes.c_uint64 * len(offs))(*offs)
+    msg = ctypes.create_string_buffer(512)
+    near, deepest = ctypes.c_longlong(0), ctypes.c_longlong(0)
+    e = ebnf.encode()
+    h.xg2hc_check_near.restype = ctypes.c_longlong
+    n = h.xg2hc_check_near(e, ctypes.c_size_t(len(e)), root.encode(), blob, offs_c, len(tokens), msg, ctypes.c_size_t(512),
+                           ctypes.byref(near), ctypes.byref(deepest))
+    assert n >= 0, msg.value.decode()
+    return n, near.value, deepest.value
+
+
+def test_near_equivalent_states_agree_on_short_tokens_bounded_string(hostcheck):
+    """Section 3.6: states near the end of a bounded repetition differ from the ones inside it only on tokens long
+    enough to reach the bound.  Every string over the alphabet up to six bytes is a token here, so the claim
+    "no string of at most d bytes tells the two states apart" is checked exhaustively for d <= 6."""
+    import itertools
+    alphabet = [b"a", b"b", b'"', b","]
+    tokens = [b"".join(p) for n in range(1, 7) for p in itertools.product(alphabet, repeat=n)]
+    ebnf = 'root ::= str ("," str){0,3}\nstr ::= "\\"" [a-b]{0,20} "\\""'
+    n, near, deepest = run_near(hostcheck, ebnf, "root", tokens)
+    assert near >= 2 and n > 1000         # the states 3, 4, 5 characters before the bound lean on the inner state
+    assert 3 <= deepest <= 5
+
+
+@pytest.mark.parametrize("index", [2, 3, 5])
+def test_near_equivalent_states_agree_on_short_tokens_workloads(hostcheck, index):
+    cfg = gen.build_config(index, n_tools=4) if index == 3 else gen.build_config(index)
+    ebnf, root = cfg.grammars[0]
+    rng = random.Random(2000 + index)
+    tokens = [t for i, t in enumerate(cfg.vocab.tokens) if t and i not in cfg.vocab.special_ids]
+    sample = rng.sample(tokens, min(1500, len(tokens)))
+    n, near, deepest = run_near(hostcheck, ebnf, root, sample)
+    if index == 5:
+        assert near >= 10 and n > 5000    # the string and digit counters close to their bounds
