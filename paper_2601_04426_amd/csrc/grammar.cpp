@@ -1097,94 +1097,148 @@ std::vector<int32_t> bounded_classes_rule(const Grammar& g, int32_t rule, int32_
         const size_t r = (size_t)rule;
         const RuleFsm& f = g.rules[r];
         const int n = f.n_states();
-        // level[d][x] = class of x with d bytes left; level 0 tells nothing apart
+        // level[d][x] = class of x with d bytes left; level 0 tells nothing apart.  Signatures of one level lie back to
+        // back in one buffer; states are grouped through a hash table whose hits are confirmed by comparing the
+        // signatures themselves, and classes are numbered in the order of their first state.
         std::vector<std::vector<int32_t>> level(1, std::vector<int32_t>((size_t)n, 0));
+        bool any_nullable_edge = false;
+        for (int x = 0; x < n && !any_nullable_edge; ++x)
+            for (auto& e : f.redges[(size_t)x]) if (g.rules[(size_t)e.rule].nullable) { any_nullable_edge = true; break; }
+        std::vector<int64_t> base, full;
+        std::vector<size_t> base_off((size_t)n + 1), full_off((size_t)n + 1);
+        std::vector<std::pair<int64_t, int64_t>> refs;
+        std::vector<int32_t> slot_state;                            // open addressing: slot -> first state of the class, or -1
+        auto group = [&](const std::vector<int64_t>& buf, const std::vector<size_t>& off, std::vector<int32_t>& out) -> size_t {
+            size_t cap = 16;
+            while (cap < (size_t)n * 2) cap <<= 1;
+            slot_state.assign(cap, -1);
+            size_t n_classes = 0;
+            for (int x = 0; x < n; ++x) {
+                const int64_t* sx = buf.data() + off[(size_t)x];
+                const size_t lx = off[(size_t)x + 1] - off[(size_t)x];
+                uint64_t h = 0x9E3779B97F4A7C15ull ^ lx;
+                for (size_t k = 0; k < lx; ++k) { h ^= (uint64_t)sx[k]; h *= 0xFF51AFD7ED558CCDull; h ^= h >> 32; }
+                for (size_t at = (size_t)h & (cap - 1);; at = (at + 1) & (cap - 1)) {
+                    const int32_t y = slot_state[at];
+                    if (y < 0) { slot_state[at] = x; out[(size_t)x] = (int32_t)n_classes++; break; }
+                    const size_t ly = off[(size_t)y + 1] - off[(size_t)y];
+                    if (ly == lx && std::equal(sx, sx + lx, buf.data() + off[(size_t)y])) { out[(size_t)x] = out[(size_t)y]; break; }
+                }
+            }
+            return n_classes;
+        };
+        // Levels only refine.  Level d is a function of level d - 1 and of the levels d - m for the shortest sentences m
+        // of the referenced rules, so once the partition has not changed over max m (at least one) levels in a row it
+        // never changes again.
+        int32_t settle = 1;
+        for (int x = 0; x < n; ++x)
+            for (auto& e : f.redges[(size_t)x]) {
+                const RuleFsm& c = g.rules[(size_t)e.rule];
+                if (!c.nullable && c.min_len <= budget) settle = std::max(settle, c.min_len);
+            }
+        size_t last_count = 1;
+        int32_t unchanged = 0;
         for (int32_t d = 1; d <= budget; ++d) {
+            if (unchanged >= settle) { level.push_back(level.back()); continue; }
             const std::vector<int32_t>& prev = level.back();
             // part of the signature that does not depend on the level being computed
-            std::vector<std::vector<int64_t>> base((size_t)n);
+            base.clear();
             for (int x = 0; x < n; ++x) {
-                std::vector<int64_t>& sg = base[(size_t)x];
-                sg.push_back(prev[(size_t)x]);
-                sg.push_back(f.is_final[(size_t)x]);
+                base_off[(size_t)x] = base.size();
+                base.push_back(prev[(size_t)x]);
+                base.push_back(f.is_final[(size_t)x]);
                 // maximal runs of consecutive bytes that lead to the same class (edges are sorted and disjoint)
                 {
                     int run_lo = -1, run_hi = -1; int32_t run_cls = -1;
                     for (auto& e : f.bedges[(size_t)x]) {
                         const int32_t c = prev[(size_t)e.tgt];
                         if (run_lo >= 0 && (int)e.lo == run_hi + 1 && c == run_cls) { run_hi = e.hi; continue; }
-                        if (run_lo >= 0) { sg.push_back(run_lo); sg.push_back(run_hi); sg.push_back(run_cls); }
+                        if (run_lo >= 0) { base.push_back(run_lo); base.push_back(run_hi); base.push_back(run_cls); }
                         run_lo = e.lo; run_hi = e.hi; run_cls = c;
                     }
-                    if (run_lo >= 0) { sg.push_back(run_lo); sg.push_back(run_hi); sg.push_back(run_cls); }
+                    if (run_lo >= 0) { base.push_back(run_lo); base.push_back(run_hi); base.push_back(run_cls); }
                 }
-                sg.push_back(-7);
-                std::vector<std::pair<int64_t, int64_t>> refs;
+                base.push_back(-7);
+                refs.clear();
                 for (auto& e : f.redges[(size_t)x]) {
                     const RuleFsm& c = g.rules[(size_t)e.rule];
                     if (c.nullable) continue;
                     int32_t left = d - c.min_len;
                     refs.emplace_back((int64_t)ref_identity[(size_t)e.rule], left >= 0 ? level[(size_t)left][(size_t)e.tgt] : -1);
                 }
-                std::sort(refs.begin(), refs.end());
-                for (auto& p : refs) { sg.push_back(p.first); sg.push_back(p.second); }
+                if (refs.size() > 1) std::sort(refs.begin(), refs.end());
+                for (auto& p : refs) { base.push_back(p.first); base.push_back(p.second); }
             }
-            // coarsest partition stable under "a nullable rule edge leads to the same class of this level"
+            base_off[(size_t)n] = base.size();
             std::vector<int32_t> cur((size_t)n, 0);
-            bool any_nullable_edge = false;
-            for (int x = 0; x < n && !any_nullable_edge; ++x)
-                for (auto& e : f.redges[(size_t)x]) if (g.rules[(size_t)e.rule].nullable) { any_nullable_edge = true; break; }
-            for (size_t n_classes = 0;;) {
-                std::map<std::vector<int64_t>, int32_t> ids;
+            size_t count = 0;
+            if (!any_nullable_edge) {
+                count = group(base, base_off, cur);
+            } else {
+                // coarsest partition stable under "a nullable rule edge leads to the same class of this level"; it refines
+                // the previous level, so the iteration may start there
+                cur = prev;
                 std::vector<int32_t> nxt((size_t)n);
-                for (int x = 0; x < n; ++x) {
-                    std::vector<int64_t> sg = base[(size_t)x];
-                    sg.push_back(-9);
-                    std::vector<std::pair<int64_t, int64_t>> refs;
-                    for (auto& e : f.redges[(size_t)x])
-                        if (g.rules[(size_t)e.rule].nullable) refs.emplace_back((int64_t)ref_identity[(size_t)e.rule], cur[(size_t)e.tgt]);
-                    std::sort(refs.begin(), refs.end());
-                    for (auto& p : refs) { sg.push_back(p.first); sg.push_back(p.second); }
-                    nxt[(size_t)x] = ids.emplace(std::move(sg), (int32_t)ids.size()).first->second;
+                for (size_t n_classes = 0;;) {
+                    full.clear();
+                    for (int x = 0; x < n; ++x) {
+                        full_off[(size_t)x] = full.size();
+                        full.insert(full.end(), base.begin() + (long)base_off[(size_t)x], base.begin() + (long)base_off[(size_t)x + 1]);
+                        full.push_back(-9);
+                        refs.clear();
+                        for (auto& e : f.redges[(size_t)x])
+                            if (g.rules[(size_t)e.rule].nullable) refs.emplace_back((int64_t)ref_identity[(size_t)e.rule], cur[(size_t)e.tgt]);
+                        if (refs.size() > 1) std::sort(refs.begin(), refs.end());
+                        for (auto& p : refs) { full.push_back(p.first); full.push_back(p.second); }
+                    }
+                    full_off[(size_t)n] = full.size();
+                    const size_t got = group(full, full_off, nxt);
+                    cur.swap(nxt);
+                    count = got;
+                    if (got == n_classes) break;
+                    n_classes = got;
                 }
-                cur.swap(nxt);
-                if (ids.size() == n_classes || !any_nullable_edge) break;      // without such edges one pass is the fixed point
-                n_classes = ids.size();
             }
+            unchanged = count == last_count ? unchanged + 1 : 0;
+            last_count = count;
             level.push_back(cur);
         }
         const std::vector<int32_t>& fin = level.back();
-        std::map<int32_t, int32_t> best;                         // class -> member with the smallest canonical id
+        std::vector<int32_t> best((size_t)n, -1);                // class (numbered below n) -> member with the smallest canonical id
         for (int x = 0; x < n; ++x) {
-            auto it = best.find(fin[(size_t)x]);
-            if (it == best.end() || f.canon_id[(size_t)x] < f.canon_id[(size_t)it->second]) best[fin[(size_t)x]] = x;
+            int32_t& b = best[(size_t)fin[(size_t)x]];
+            if (b < 0 || f.canon_id[(size_t)x] < f.canon_id[(size_t)b]) b = x;
         }
         rep_r.resize((size_t)n);
-        for (int x = 0; x < n; ++x) rep_r[(size_t)x] = best[fin[(size_t)x]];
+        for (int x = 0; x < n; ++x) rep_r[(size_t)x] = best[(size_t)fin[(size_t)x]];
         if (near) {
             // classes in the order of falling size (the class a long repetition collapses into comes first); each looks
             // for the deepest level at which it still coincides with a class that is built in full
             near->base.assign((size_t)n, -1);
             near->depth.assign((size_t)n, 0);
-            std::map<int32_t, int32_t> weight;
-            for (int x = 0; x < n; ++x) ++weight[fin[(size_t)x]];
+            std::vector<int32_t> weight((size_t)n, 0);                                    // by class number (< n)
+            for (int x = 0; x < n; ++x) ++weight[(size_t)fin[(size_t)x]];
+            std::vector<std::array<int32_t, 3>> keyed;                                   // {-size, canonical id, state}
+            for (int c = 0; c < n; ++c) if (best[(size_t)c] >= 0) keyed.push_back({-weight[(size_t)c], f.canon_id[(size_t)best[(size_t)c]], best[(size_t)c]});
+            std::sort(keyed.begin(), keyed.end());
             std::vector<int32_t> reps;
-            for (auto& kv : best) reps.push_back(kv.second);
-            std::stable_sort(reps.begin(), reps.end(), [&](int32_t a, int32_t b) {
-                const int32_t wa = weight[fin[(size_t)a]], wb = weight[fin[(size_t)b]];
-                return wa != wb ? wa > wb : f.canon_id[(size_t)a] < f.canon_id[(size_t)b];
-            });
+            for (auto& k : keyed) reps.push_back(k[2]);
             const int32_t top = std::min<int32_t>(budget - 1, kMaxNearDepth);
-            std::vector<std::map<int32_t, int32_t>> full((size_t)std::max(top + 1, 1));   // per level: class -> a class built in full
+            // per level: class -> a class built in full (-1: none yet)
+            std::vector<std::vector<int32_t>> full((size_t)std::max(top + 1, 1));
+            for (int32_t e = kMinNearDepth; e <= top; ++e) full[(size_t)e].assign((size_t)n, -1);
             for (int32_t x : reps) {
                 if (f.bedges[(size_t)x].empty()) continue;                               // no plane
                 int32_t d = top;
                 for (; d >= kMinNearDepth; --d) {
-                    auto it = full[(size_t)d].find(level[(size_t)d][(size_t)x]);
-                    if (it != full[(size_t)d].end()) { near->base[(size_t)x] = it->second; near->depth[(size_t)x] = d; break; }
+                    const int32_t y = full[(size_t)d][(size_t)level[(size_t)d][(size_t)x]];
+                    if (y >= 0) { near->base[(size_t)x] = y; near->depth[(size_t)x] = d; break; }
                 }
                 if (d < kMinNearDepth)
-                    for (int32_t e = kMinNearDepth; e <= top; ++e) full[(size_t)e].emplace(level[(size_t)e][(size_t)x], x);
+                    for (int32_t e = kMinNearDepth; e <= top; ++e) {
+                        int32_t& y = full[(size_t)e][(size_t)level[(size_t)e][(size_t)x]];
+                        if (y < 0) y = x;
+                    }
             }
         }
     }
