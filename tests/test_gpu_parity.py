@@ -403,6 +403,67 @@ def test_tricky_grammars_planes_and_masks(xg, case, depth, follow):
         assert m.accept_token(0) and m.is_terminated()
 
 
+def test_near_bound_repetition_planes_full_jit_and_pool(xg):
+    """Section 3.6: the states of a bounded repetition within one token length of the bound.  Their planes take the
+    short tokens from the plane of the inner states and check only the long ones.  Built all at once, built just in time
+    before the inner plane exists, after it exists in the same cache, and after it exists only in the pool: every
+    plane and every mask equal to the oracle's."""
+    import itertools
+    import torch
+    alphabet = b'ab",[]'
+    rng = random.Random(36)
+    toks = [b""] + [bytes(t) for n in (1, 2, 3) for t in itertools.product(alphabet, repeat=n)]
+    toks += sorted({bytes(rng.choice(b'aab"') for _ in range(rng.randrange(4, 9))) for _ in range(400)} - set(toks))
+    ebnf = 'root ::= "[" str ("," str){0,2} "]"\nstr ::= "\\"" [ab]{0,12} "\\""'
+    vocab = xg.Vocab(toks, 0, [0])
+    va = oracle.VocabArrays(toks, 0, [0])
+
+    class Cfg:
+        class vocab:
+            tokens = toks
+    cache, orc = check_planes(xg, Cfg, vocab, va, ebnf, "root", max_contexts=100000)
+    single = {bytes([b]): toks.index(bytes([b])) for b in alphabet}
+    bm = torch.full((1, vocab.words), -1, dtype=torch.int32, device="cuda:0")
+
+    def mask_after(c, text):
+        m = xg.Matcher(c)
+        for i in range(len(text)):
+            assert m.accept_token(single[text[i:i + 1]])
+        xg.fill_next_token_bitmask([m], bm.data_ptr(), vocab.words, _stream())
+        torch.cuda.synchronize()
+        got = bm.cpu().numpy()[0]
+        want = oracle.pack_bitmask(orc.mask(text, va))
+        assert np.array_equal(got, want), (text, diff_words(got, want, toks))
+
+    def built_planes_match(c):
+        n = 0
+        for k in range(c.num_planes()):
+            try:
+                acc, unc = c.get_planes(k)
+            except xg.Xg2Error:
+                continue
+            pos, parent = c.plane_info(k)
+            want_a, want_u = planes_of(orc, pos, va, parent, True)
+            assert np.array_equal(acc, want_a) and np.array_equal(unc, want_u), (pos, parent)
+            n += 1
+        return n
+
+    pool = xg.Pool()
+    a = xg.compile_grammar(vocab, ebnf, "root", pool=pool, stream=_stream(), jit=True, jit_prebuild=0)
+    mask_after(a, b'["' + b"a" * 7)                  # near the bound first: the inner plane is not there to lean on
+    n1 = built_planes_match(a)
+    mask_after(a, b'["')                             # now the inner plane
+    mask_after(a, b'["' + b"ab" * 3)                 # leans on the inner plane held by this cache
+    mask_after(a, b'["ab","' + b"b" * 8)             # another site of the same rule
+    n2 = built_planes_match(a)
+    assert 0 < n1 < n2 < a.num_planes()
+    b = xg.compile_grammar(vocab, ebnf, "root", pool=pool, stream=_stream(), jit=True, jit_prebuild=0)
+    mask_after(b, b'["' + b"a" * 5)                  # the inner plane is in the pool only
+    mask_after(b, b'["' + b"a" * 9)
+    mask_after(b, b'["' + b"a" * 12)
+    assert built_planes_match(b) >= 3
+
+
 def random_grammar(rng):
     """A small random EBNF over the letters a-d: 2-4 rules; alternation, ? * + {m,n}, classes; a rule refers to later
     rules (so the references form a DAG) and now and then to itself inside brackets, as grammars of nested data do.
