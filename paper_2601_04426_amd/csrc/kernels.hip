@@ -2,6 +2,8 @@
 //   k_build        classes of (position, token) pairs by a rule-scoped Earley recogniser, one lane per
 //                  token, item sets in LDS                              (XGrammar-2 section 3.4)
 //   k_build_slow   the same recogniser with larger item sets (LDS, then device memory), for lanes that overflowed
+//   k_copy_masked  short tokens of a plane taken from the plane of a state they cannot tell apart (section 3.6)
+//   k_upload       per-call plan and tables from pinned host memory
 //   k_fill_or      union of cached planes over the scannable frontier   (section 3.4, runtime part)
 //   k_recheck      re-check of uncertain tokens against the full Earley context, and its large-capacity twin
 //   k_apply_*      logits of disallowed tokens := -infinity, in place    (section 2.1)
