@@ -59,7 +59,10 @@ typedef struct xg2_matcher xg2_matcher;
  *   plane (the context expansion that section 2.2 and section 3.3 recall); far fewer tokens stay
  *   uncertain.  Positions of the root rule have no referencing rule and keep a plain plane.
  * merge_equivalent (default 1): states that no string as long as the longest token can tell apart
- *   share one plane (section 3.6: states inside a repetition differ minimally).
+ *   share one plane (section 3.6: states inside a repetition differ minimally).  States that no
+ *   string of at most d bytes (3 <= d <= 32) can tell apart have equal planes on the tokens of at
+ *   most d bytes: such a plane is checked for its longer tokens only and takes the others from the
+ *   plane it agrees with.  The planes are the same with or without the option.
  * follow_filter (default 1): a token that leaves the plane's (outermost) rule before its last byte
  *   stays uncertain only if the rest of the token is a viable prefix of what can follow that rule
  *   at some reference site of the grammar; otherwise it is rejected at build time (sections 2.2 and
@@ -83,7 +86,8 @@ typedef struct xg2_compile_stats {
     int64_t unique;           /* distinct planes this grammar uses (after dedupe and merging)     */
     int64_t built;            /* planes computed by this call (pool misses)                       */
     int64_t checks;           /* built * (number of checkable tokens): logical (plane, token)     */
-    int64_t executed_checks;  /* (plane, token) pairs a lane actually stepped through             */
+    int64_t executed_checks;  /* (plane, token) pairs a lane actually stepped through (not the
+                                 tokens skipped by their first byte or taken from another plane)  */
     int64_t slow_path;        /* pairs finished by the large-capacity kernel                      */
     int64_t n_accepted;       /* set bits over the built accepted planes                          */
     int64_t n_uncertain;      /* set bits over the built uncertain planes                         */
