@@ -291,23 +291,32 @@ def main() -> int:
         del keep, pool4
 
     if args.jit:
+        # per-step latency of fill (host + device, synchronised) along 128 decode steps of B fresh sentences: on a cache
+        # compiled just in time (nothing pre-built) and, for reference, on the fully built one
+        def step_latencies(c):
+            ms_ = [xg.Matcher(c) for _ in range(B)]
+            batch_ = xg.MatcherBatch(ms_)
+            rng_ = random.Random(4242)
+            tr = [seg.segment(cfg.sample_text(rng_, 0), rng_) + [cfg.vocab.eos_id] for _ in range(B)]
+            lat = []
+            for stp in range(128):
+                torch.cuda.synchronize()
+                tj = time.perf_counter()
+                xg.fill_next_token_bitmask(batch_, bitmask.data_ptr(), W, stream)
+                torch.cuda.synchronize()
+                lat.append((time.perf_counter() - tj) * 1e3)
+                batch_.accept_tokens([t[stp] if stp < len(t) else -1 for t in tr])
+            return sorted(lat)
         jit_cache = xg.compile_grammar(vocab, ebnf, root, stream=stream, jit=True, jit_prebuild=0)
-        jm = [xg.Matcher(jit_cache) for _ in range(B)]
-        jbatch = xg.MatcherBatch(jm)
-        jtr = [seg.segment(cfg.sample_text(rng, 0), rng) + [cfg.vocab.eos_id] for _ in range(B)]
-        jlat = []
-        for stp in range(32):
-            torch.cuda.synchronize()
-            tj = time.perf_counter()
-            xg.fill_next_token_bitmask(jbatch, bitmask.data_ptr(), W, stream)
-            torch.cuda.synchronize()
-            jlat.append((time.perf_counter() - tj) * 1e3)
-            jbatch.accept_tokens([t[stp] if stp < len(t) else -1 for t in jtr])
+        jlat = step_latencies(jit_cache)
+        flat = step_latencies(cache0)
         jbuilt, jlaunches, jms = jit_cache.jit_stats()
-        out["jit"] = {"compile_device_ms": jit_cache.stats.device_ms, "planes_total": jit_cache.num_planes(), "planes_built_after_32_steps": jbuilt,
+        pct = lambda v, q: v[min(len(v) - 1, int(q * len(v)))]
+        out["jit"] = {"compile_device_ms": jit_cache.stats.device_ms, "planes_total": jit_cache.num_planes(), "planes_built_after_128_steps": jbuilt,
                       "build_launches_in_fill": jlaunches, "build_device_ms_in_fill": jms,
-                      "fill_step_ms_mean": mean(jlat), "fill_step_ms_max": max(jlat), "fill_step_ms_median": med(jlat)}
-        del jm, jbatch, jit_cache
+                      "fill_step_ms": {"median": pct(jlat, 0.5), "p99": pct(jlat, 0.99), "max": jlat[-1], "mean": mean(jlat)},
+                      "fill_step_ms_fully_built_cache": {"median": pct(flat, 0.5), "p99": pct(flat, 0.99), "max": flat[-1], "mean": mean(flat)}}
+        del jit_cache
 
     if not args.no_cpu_baseline:
         import oracle

@@ -197,6 +197,36 @@ def test_config5_repetition_planes_and_decode(xg):
     assert n >= 140
 
 
+def test_plane_count_does_not_depend_on_repetition_bound(xg):
+    """Section 3.6: a repetition of 4,096 instead of 1,000 objects makes the grammar four times as large and the mask
+    cache no larger; masks deep inside the repetition equal the oracle's."""
+    import torch
+    cfg, vocab, va = load(5)
+    small = xg.compile_grammar(vocab, gen.grammars.repetition_stress_ebnf(1000), "root", stream=_stream())
+    ebnf = gen.grammars.repetition_stress_ebnf(4096)
+    big = xg.compile_grammar(vocab, ebnf, "root", stream=_stream())
+    assert big.stats.positions > 3 * small.stats.positions
+    assert big.stats.unique == small.stats.unique and big.stats.built == small.stats.built
+    assert big.stats.executed_checks == small.stats.executed_checks
+    orc = oracle.Oracle(ebnf, "root")
+    rng = random.Random(4096)
+    seg = gen.Segmenter(cfg.vocab)
+    text = b'[' + b','.join(b'{"s":"ab","n":%d}' % k for k in range(40))
+    ids = seg.segment(text, rng)
+    m = xg.Matcher(big)
+    bm = torch.full((1, vocab.words), -1, dtype=torch.int32, device="cuda:0")
+    hist = b""
+    for i, tid in enumerate(ids):
+        if i % 29 == 0 or i == len(ids) - 1:
+            xg.fill_next_token_bitmask([m], bm.data_ptr(), vocab.words, _stream())
+            torch.cuda.synchronize()
+            got = bm.cpu().numpy()[0]
+            want = oracle.pack_bitmask(orc.mask(hist, va))
+            assert np.array_equal(got, want), (hist[-30:], diff_words(got, want, cfg.vocab.tokens))
+        assert m.accept_token(tid)
+        hist += cfg.vocab.tokens[tid]
+
+
 @pytest.mark.parametrize("index,prebuild,batch,steps,every", [(1, 0, 4, 64, 1), (1, 7, 4, 64, 1), (2, 0, 64, 40, 5), (3, 16, 64, 24, 11)])
 def test_jit_compilation_gives_the_same_masks(xg, index, prebuild, batch, steps, every):
     """Section 3.5: nothing (or only the costliest planes) built at compile time, the rest by the fill calls that
