@@ -435,7 +435,7 @@ int32_t build_planes(CacheImpl& cache, const std::vector<int32_t>& todo, hipStre
 
     // plan: closed start set and live first-byte ranges of every plane to build
     std::vector<uint32_t> ctx_items, ctx_wait, ctx_wait_off;
-    std::vector<uint4> chunks, plane_ctx;
+    std::vector<uint4> chunks, plane_ctx, ranges;
     std::vector<CopyJob> copies;
     int64_t executed = 0;
     EarleyChart chart(&ft);
@@ -493,14 +493,23 @@ int32_t build_planes(CacheImpl& cache, const std::vector<int32_t>& todo, hipStre
                 hi = (uint32_t)(std::lower_bound(first, last, hi) - V.long_rank.data());
                 listed = kChunkListed;
             }
-            const uint32_t step = heavy ? kHeavyChunk : kBuildChunk;
-            for (uint32_t c = lo; c < hi; c += step)
-                chunks.push_back(make_uint4((uint32_t)k, c, std::min(hi, c + step), listed | (heavy ? kChunkHeavy : 0u)));
+            if (lo < hi) ranges.push_back(make_uint4((uint32_t)k, lo, hi, listed | (heavy ? kChunkHeavy : 0u)));
             executed += hi - lo;
             b = e + 1;
         }
     }
-    std::stable_sort(chunks.begin(), chunks.end(), [](const uint4& a, const uint4& b) { return (a.w & kChunkHeavy) > (b.w & kChunkHeavy); });
+    // chunks of the heavy ranges first, then the others, each group in plane order
+    {
+        size_t n_chunks = 0;
+        for (const uint4& r : ranges) n_chunks += (r.z - r.y + ((r.w & kChunkHeavy) ? kHeavyChunk : kBuildChunk) - 1) / ((r.w & kChunkHeavy) ? kHeavyChunk : kBuildChunk);
+        chunks.reserve(n_chunks);
+        for (uint32_t pass_heavy : {kChunkHeavy, 0u})
+            for (const uint4& r : ranges) {
+                if ((r.w & kChunkHeavy) != pass_heavy) continue;
+                const uint32_t step = pass_heavy ? kHeavyChunk : kBuildChunk;
+                for (uint32_t c = r.y; c < r.z; c += step) chunks.push_back(make_uint4(r.x, c, std::min(r.z, c + step), r.w));
+            }
+    }
 
     // everything the device needs goes up in one copy: (the tables,) the plan, and a few zeroed words (overflow
     // counter and flag, bit counts per built plane).  With the tables the block stays with the cache.
@@ -835,7 +844,7 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
         }
         FollowInfo follow_info;
         const int32_t budget = (int32_t)std::max<uint32_t>(V.max_len, 1);
-        if (follow) follow_info = follow_signatures(g, budget);
+        if (follow) follow_info = follow_signatures(g, budget, &classes);
         // reference sites of every rule, one representative per class of the state the referencing rule continues in
         struct Site { int32_t q, waiter, x; };
         std::vector<std::vector<Site>> sites((size_t)R);            // all sites

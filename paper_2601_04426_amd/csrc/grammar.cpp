@@ -2,6 +2,7 @@
 #include "grammar.hpp"
 
 #include <algorithm>
+#include <queue>
 #include <array>
 #include <atomic>
 #include <cstring>
@@ -1245,7 +1246,7 @@ std::vector<int32_t> bounded_classes_rule(const Grammar& g, int32_t rule, int32_
     return rep_r;
 }
 
-FollowInfo follow_signatures(const Grammar& g, int32_t budget) {
+FollowInfo follow_signatures(const Grammar& g, int32_t budget, const std::vector<std::vector<int32_t>>* rep) {
     const int R = (int)g.rules.size();
     const int32_t INF = 1 << 28;
     // shortest completion of every state, in bytes
@@ -1254,75 +1255,97 @@ FollowInfo follow_signatures(const Grammar& g, int32_t budget) {
         const RuleFsm& f = g.rules[(size_t)r];
         std::vector<int32_t>& d = min_suf[(size_t)r];
         d.assign((size_t)f.n_states(), INF);
-        for (int q = 0; q < f.n_states(); ++q) if (f.is_final[(size_t)q]) d[(size_t)q] = 0;
-        for (bool moved = true; moved;) {
-            moved = false;
-            for (int q = 0; q < f.n_states(); ++q) {
-                for (auto& e : f.bedges[(size_t)q]) if (d[(size_t)e.tgt] + 1 < d[(size_t)q]) { d[(size_t)q] = d[(size_t)e.tgt] + 1; moved = true; }
-                for (auto& e : f.redges[(size_t)q]) {
-                    int32_t c = d[(size_t)e.tgt] + g.rules[(size_t)e.rule].min_len;
-                    if (c < d[(size_t)q]) { d[(size_t)q] = c; moved = true; }
-                }
-            }
+        // shortest paths to a final state over the reversed edges (a byte costs 1, a rule its shortest sentence)
+        const int n = f.n_states();
+        std::vector<std::vector<std::pair<int32_t, int32_t>>> back((size_t)n);      // target -> (source, cost)
+        for (int q = 0; q < n; ++q) {
+            for (auto& e : f.bedges[(size_t)q]) back[(size_t)e.tgt].emplace_back(q, 1);
+            for (auto& e : f.redges[(size_t)q]) back[(size_t)e.tgt].emplace_back(q, g.rules[(size_t)e.rule].min_len);
+        }
+        std::priority_queue<std::pair<int32_t, int32_t>, std::vector<std::pair<int32_t, int32_t>>, std::greater<>> heap;
+        for (int q = 0; q < n; ++q) if (f.is_final[(size_t)q]) { d[(size_t)q] = 0; heap.emplace(0, q); }
+        while (!heap.empty()) {
+            const auto [dist, q] = heap.top();
+            heap.pop();
+            if (dist > d[(size_t)q]) continue;
+            for (auto& [src, cost] : back[(size_t)q])
+                if (dist + cost < d[(size_t)src]) { d[(size_t)src] = dist + cost; heap.emplace(dist + cost, src); }
         }
     }
-    // unfold[d][sid]: structural hash of the state's behaviour on at most d bytes
-    std::vector<std::vector<uint64_t>> unfold((size_t)budget + 1, std::vector<uint64_t>((size_t)g.n_states, 0));
+    // unfold(d, rule, state): structural hash of the state's behaviour on at most d bytes (0 for d = 0).  Computed on
+    // demand: only the states in which referencing rules continue, and what is within d bytes of them, are ever asked
+    // for.  States on a cycle of nullable rule edges get a fresh salt.
+    std::vector<uint8_t> cyclic((size_t)g.n_states, 1);
     for (int r = 0; r < R; ++r) {
         const RuleFsm& f = g.rules[(size_t)r];
         const int n = f.n_states();
-        // order in which nullable rule edges are resolved (targets first); states on a cycle of such edges are salted
         std::vector<int> indeg((size_t)n, 0), order;
         std::vector<std::vector<int>> preds((size_t)n);
         for (int x = 0; x < n; ++x)
             for (auto& e : f.redges[(size_t)x]) if (g.rules[(size_t)e.rule].nullable) { ++indeg[(size_t)x]; preds[(size_t)e.tgt].push_back(x); }
         for (int x = 0; x < n; ++x) if (indeg[(size_t)x] == 0) order.push_back(x);
         for (size_t k = 0; k < order.size(); ++k) for (int p : preds[(size_t)order[k]]) if (--indeg[(size_t)p] == 0) order.push_back(p);
-        std::vector<uint8_t> cyclic((size_t)n, 1);
-        for (int x : order) cyclic[(size_t)x] = 0;
-        for (int32_t d = 1; d <= budget; ++d) {
-            for (int x = 0; x < n; ++x) if (cyclic[(size_t)x]) unfold[(size_t)d][(size_t)g.sid(r, x)] = hash_combine(0xC1C1ull, g_unshareable_salt.fetch_add(1));
-            for (int x : order) {
-                uint64_t h = hash_combine(0x51ull, f.is_final[(size_t)x]);
-                {   // maximal runs of consecutive bytes with the same unfolding (edges are sorted and disjoint)
-                    int run_lo = -1, run_hi = -1; uint64_t run_h = 0;
-                    for (auto& e : f.bedges[(size_t)x]) {
-                        const uint64_t u = unfold[(size_t)d - 1][(size_t)g.sid(r, e.tgt)];
-                        if (run_lo >= 0 && (int)e.lo == run_hi + 1 && u == run_h) { run_hi = e.hi; continue; }
-                        if (run_lo >= 0) h = hash_combine(hash_combine(hash_combine(h, (uint64_t)run_lo), (uint64_t)run_hi), run_h);
-                        run_lo = e.lo; run_hi = e.hi; run_h = u;
-                    }
+        for (int x : order) cyclic[(size_t)g.sid(r, x)] = 0;
+    }
+    std::vector<std::vector<uint64_t>> unfold_memo((size_t)budget + 1);
+    std::vector<std::vector<uint8_t>> unfold_have((size_t)budget + 1);
+    std::function<uint64_t(int32_t, int, int)> unfold = [&](int32_t d, int r, int x) -> uint64_t {
+        if (d <= 0) return 0;
+        if (unfold_memo[(size_t)d].empty()) { unfold_memo[(size_t)d].assign((size_t)g.n_states, 0); unfold_have[(size_t)d].assign((size_t)g.n_states, 0); }
+        const size_t sid = (size_t)g.sid(r, x);
+        if (unfold_have[(size_t)d][sid]) return unfold_memo[(size_t)d][sid];
+        const RuleFsm& f = g.rules[(size_t)r];
+        uint64_t h;
+        if (cyclic[sid]) {
+            h = hash_combine(0xC1C1ull, g_unshareable_salt.fetch_add(1));
+        } else {
+            h = hash_combine(0x51ull, f.is_final[(size_t)x]);
+            {   // maximal runs of consecutive bytes with the same unfolding (edges are sorted and disjoint)
+                int run_lo = -1, run_hi = -1; uint64_t run_h = 0;
+                for (auto& e : f.bedges[(size_t)x]) {
+                    const uint64_t u = unfold(d - 1, r, e.tgt);
+                    if (run_lo >= 0 && (int)e.lo == run_hi + 1 && u == run_h) { run_hi = e.hi; continue; }
                     if (run_lo >= 0) h = hash_combine(hash_combine(hash_combine(h, (uint64_t)run_lo), (uint64_t)run_hi), run_h);
+                    run_lo = e.lo; run_hi = e.hi; run_h = u;
                 }
+                if (run_lo >= 0) h = hash_combine(hash_combine(hash_combine(h, (uint64_t)run_lo), (uint64_t)run_hi), run_h);
+            }
+            if (!f.redges[(size_t)x].empty()) {
                 std::vector<std::pair<uint64_t, uint64_t>> refs;
                 for (auto& e : f.redges[(size_t)x]) {
                     const RuleFsm& c = g.rules[(size_t)e.rule];
                     int32_t left = c.nullable ? d : d - c.min_len;
-                    refs.emplace_back(c.hash, left >= 0 ? unfold[(size_t)left][(size_t)g.sid(r, e.tgt)] : 0x7777ull);
+                    refs.emplace_back(c.hash, left >= 0 ? unfold(left, r, e.tgt) : 0x7777ull);
                 }
                 std::sort(refs.begin(), refs.end());
                 for (auto& p : refs) h = hash_combine(hash_combine(hash_combine(h, 0xEFull), p.first), p.second);
-                unfold[(size_t)d][(size_t)g.sid(r, x)] = h;
             }
         }
-    }
+        unfold_memo[(size_t)d][sid] = h;
+        unfold_have[(size_t)d][sid] = 1;
+        return h;
+    };
     // reference sites of every rule
     struct Site { int q, x; };
     std::vector<std::vector<Site>> sites((size_t)R);
     for (int q = 0; q < R; ++q)
         for (int s = 0; s < g.rules[(size_t)q].n_states(); ++s)
-            for (auto& e : g.rules[(size_t)q].redges[(size_t)s]) sites[(size_t)e.rule].push_back({q, e.tgt});
-    std::map<std::pair<int, int>, uint64_t> memo;
-    std::set<std::pair<int, int>> open;
+            for (auto& e : g.rules[(size_t)q].redges[(size_t)s]) sites[(size_t)e.rule].push_back({q, rep ? (*rep)[(size_t)q][(size_t)e.tgt] : e.tgt});
+    for (auto& v : sites) {                                         // one site per state (class) a referencing rule continues in
+        std::sort(v.begin(), v.end(), [](const Site& a, const Site& b) { return a.q != b.q ? a.q < b.q : a.x < b.x; });
+        v.erase(std::unique(v.begin(), v.end(), [](const Site& a, const Site& b) { return a.q == b.q && a.x == b.x; }), v.end());
+    }
+    std::vector<uint64_t> memo((size_t)R * ((size_t)budget + 1), 0);
+    std::vector<uint8_t> memo_state((size_t)R * ((size_t)budget + 1), 0);      // 0 unknown, 1 being computed, 2 known
     std::function<uint64_t(int, int)> sig = [&](int rule, int d) -> uint64_t {
-        auto key = std::make_pair(rule, d);
-        auto it = memo.find(key);
-        if (it != memo.end()) return it->second;
-        if (!open.insert(key).second) return hash_combine(0xCCCCull, g_unshareable_salt.fetch_add(1));   // cycle through rule ends
+        const size_t key = (size_t)rule * ((size_t)budget + 1) + (size_t)d;
+        if (memo_state[key] == 2) return memo[key];
+        if (memo_state[key] == 1) return hash_combine(0xCCCCull, g_unshareable_salt.fetch_add(1));   // cycle through rule ends
+        memo_state[key] = 1;
         std::vector<uint64_t> parts;
         if (rule == g.root) parts.push_back(0xE0Full);                      // the input may end here
         for (const Site& st : sites[(size_t)rule]) {
-            uint64_t h = unfold[(size_t)d][(size_t)g.sid(st.q, st.x)];
+            uint64_t h = unfold(d, st.q, st.x);
             int32_t left = d - min_suf[(size_t)st.q][(size_t)st.x];
             if (left > 0 || (left == 0 && d > 0 && min_suf[(size_t)st.q][(size_t)st.x] == 0)) h = hash_combine(h, sig(st.q, left));
             parts.push_back(h);
@@ -1331,7 +1354,7 @@ FollowInfo follow_signatures(const Grammar& g, int32_t budget) {
         parts.erase(std::unique(parts.begin(), parts.end()), parts.end());
         uint64_t h = 0xF011ull;
         for (uint64_t p : parts) h = hash_combine(h, p);
-        open.erase(key);
+        memo_state[key] = 2;
         memo[key] = h;
         return h;
     };

@@ -83,7 +83,9 @@ struct FollowInfo {
     std::vector<std::vector<uint64_t>> sig;        // [rule][d], d = 0..budget: what can follow the rule within d bytes
     std::vector<std::vector<int32_t>> min_suf;     // [rule][state]: bytes of the shortest completion of the rule from the state
 };
-FollowInfo follow_signatures(const Grammar& g, int32_t budget);
+// rep (optional): per rule and state, a state that no string of at most `budget` bytes tells apart from it; sites are then
+// taken at these representatives, which leaves the follow language as it is and the work independent of repetition bounds.
+FollowInfo follow_signatures(const Grammar& g, int32_t budget, const std::vector<std::vector<int32_t>>* rep = nullptr);
 
 // Exact serialisation of one rule in Algorithm 1's canonical order; a reference to rule r is
 // written as ref_id[r].  Two rules with equal text and equal meaning of the ids are isomorphic.

@@ -62,10 +62,21 @@ FlatTables flatten(const Grammar& g) {
             t.dev_state[sid] = ds;
         }
     }
-    // byte classes: refine by (class so far, target) state after state
+    // byte classes: refine by (class so far, target) state after state.  Every edge is a byte range, so bytes between
+    // two consecutive range boundaries always behave alike: the refinement runs over those intervals, not over bytes.
     const size_t n = t.state_info.size();
-    std::vector<uint32_t> cls(256, 0);
-    std::vector<int64_t> row(256);
+    std::vector<uint8_t> is_bound(257, 0);
+    is_bound[0] = 1;
+    for (const ByteEdge& e : t.byte_edges) { is_bound[e.lohi & 0xFF] = 1; is_bound[((e.lohi >> 8) & 0xFF) + 1] = 1; }
+    std::vector<uint32_t> iv_lo;                                    // first byte of every interval, ascending
+    std::vector<uint32_t> iv_of(256);
+    for (uint32_t b = 0; b < 256; ++b) {
+        if (is_bound[b]) iv_lo.push_back(b);
+        iv_of[b] = (uint32_t)iv_lo.size() - 1;
+    }
+    const size_t m = iv_lo.size();
+    std::vector<uint32_t> cls(m, 0);
+    std::vector<int64_t> row(m);
     struct Split { uint32_t old_class; int64_t target; uint32_t new_class; };
     std::vector<Split> splits;
     for (size_t sid = 0; sid < n; ++sid) {
@@ -74,28 +85,29 @@ FlatTables flatten(const Grammar& g) {
         std::fill(row.begin(), row.end(), -1);
         for (uint32_t k = 0; k < (si.counts & 0xFFFF); ++k) {
             const ByteEdge& e = t.byte_edges[si.byte_off + k];
-            for (uint32_t b = e.lohi & 0xFF; b <= ((e.lohi >> 8) & 0xFF); ++b) row[b] = e.tgt;
+            for (uint32_t j = iv_of[e.lohi & 0xFF]; j <= iv_of[(e.lohi >> 8) & 0xFF]; ++j) row[j] = e.tgt;
         }
         splits.clear();                                             // few per state: searched linearly
-        for (int b = 0; b < 256; ++b) {
-            const uint32_t oc = cls[(size_t)b];
-            const int64_t tg = row[(size_t)b];
+        for (size_t j = 0; j < m; ++j) {
+            const uint32_t oc = cls[j];
+            const int64_t tg = row[j];
             int nc = -1;
             for (const Split& sp : splits) if (sp.old_class == oc && sp.target == tg) { nc = (int)sp.new_class; break; }
             if (nc < 0) { nc = (int)splits.size(); splits.push_back({oc, tg, (uint32_t)nc}); }
-            cls[(size_t)b] = (uint32_t)nc;
+            cls[j] = (uint32_t)nc;
         }
     }
     t.n_classes = *std::max_element(cls.begin(), cls.end()) + 1;
     if (t.n_classes > 256) throw std::logic_error("more byte classes than bytes");
     t.byte_class_words.assign(64, 0);
-    for (int b = 0; b < 256; ++b) t.byte_class_words[(size_t)b >> 2] |= cls[(size_t)b] << ((b & 3) * 8);
+    for (int b = 0; b < 256; ++b) t.byte_class_words[(size_t)b >> 2] |= cls[iv_of[(size_t)b]] << ((b & 3) * 8);
     t.trans.assign(n * t.n_classes, kNoTarget);
     for (size_t sid = 0; sid < n; ++sid) {
         const StateInfo& si = t.state_info[sid];
         for (uint32_t k = 0; k < (si.counts & 0xFFFF); ++k) {
             const ByteEdge& e = t.byte_edges[si.byte_off + k];
-            for (uint32_t b = e.lohi & 0xFF; b <= ((e.lohi >> 8) & 0xFF); ++b) t.trans[sid * t.n_classes + cls[b]] = t.ref(e.tgt);
+            const uint32_t ref = t.ref(e.tgt);
+            for (uint32_t j = iv_of[e.lohi & 0xFF]; j <= iv_of[(e.lohi >> 8) & 0xFF]; ++j) t.trans[sid * t.n_classes + cls[j]] = ref;
         }
     }
     return t;
