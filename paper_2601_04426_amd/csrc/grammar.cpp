@@ -999,15 +999,23 @@ Grammar lower_grammar(const std::string& ebnf, const std::string& root_rule) {
         f.is_final.assign(d.fin.begin(), d.fin.end());
         f.bedges.resize((size_t)n);
         f.redges.resize((size_t)n);
+        // maximal runs of consecutive bytes of one class: the same for every state of the automaton
+        std::vector<std::array<int, 3>> class_runs;                 // {lo, hi, class}
+        for (int b = 0; b < 256;) {
+            int e = b;
+            while (e + 1 < 256 && d.cls[(size_t)(e + 1)] == d.cls[(size_t)b]) ++e;
+            class_runs.push_back({b, e, (int)d.cls[(size_t)b]});
+            b = e + 1;
+        }
         for (int q = 0; q < n; ++q) {
-            int b = 0;
-            while (b < 256) {
-                int t = d.byte_target(q, b);
-                int e = b;
-                while (e + 1 < 256 && d.byte_target(q, e + 1) == t) ++e;
-                if (t >= 0) f.bedges[(size_t)q].push_back({(uint8_t)b, (uint8_t)e, t});
-                b = e + 1;
+            int lo = -1, hi = -1, tgt = -1;                          // run of bytes with one target being grown
+            for (const auto& cr : class_runs) {
+                const int t = d.at(q, cr[2]);
+                if (t == tgt && lo >= 0 && cr[0] == hi + 1) { hi = cr[1]; continue; }
+                if (lo >= 0 && tgt >= 0) f.bedges[(size_t)q].push_back({(uint8_t)lo, (uint8_t)hi, tgt});
+                lo = cr[0]; hi = cr[1]; tgt = t;
             }
+            if (lo >= 0 && tgt >= 0) f.bedges[(size_t)q].push_back({(uint8_t)lo, (uint8_t)hi, tgt});
             for (auto& r : d.rt[(size_t)q]) f.redges[(size_t)q].push_back({remap.at(r.first), r.second});
         }
         g.rules.push_back(std::move(f));
