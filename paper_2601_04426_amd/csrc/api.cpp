@@ -5,6 +5,7 @@
 
 #include <algorithm>
 #include <array>
+#include <atomic>
 #include <chrono>
 #include <cstring>
 #include <map>
@@ -12,6 +13,8 @@
 #include <mutex>
 #include <numeric>
 #include <string>
+#include <condition_variable>
+#include <functional>
 #include <thread>
 #include <unordered_map>
 #include <unordered_set>
@@ -375,6 +378,50 @@ struct FillWorkspace {
     }
 };
 FillWorkspace& fill_ws() { static FillWorkspace* w = new FillWorkspace(); return *w; }
+
+// A few host threads that stay around between calls (starting threads costs more than the work of a decode step).
+// run(parts, job) calls job(0 .. parts - 1), the caller taking shares too, and returns when all are done; calls are
+// serialised.  The pool is created at first use and lives until the process ends.
+class HostWorkers {
+    std::mutex call_mu, mu;
+    std::condition_variable cv_work, cv_done;
+    std::vector<std::thread> threads;
+    const std::function<void(int32_t)>* job = nullptr;
+    int32_t n_parts = 0, next = 0, pending = 0;
+    void worker() {
+        std::unique_lock<std::mutex> lk(mu);
+        for (;;) {
+            cv_work.wait(lk, [&] { return job && next < n_parts; });
+            take(lk);
+        }
+    }
+    void take(std::unique_lock<std::mutex>& lk) {               // runs parts until none is left; lk is held on entry and exit
+        while (job && next < n_parts) {
+            const int32_t part = next++;
+            const std::function<void(int32_t)>* f = job;
+            lk.unlock();
+            (*f)(part);
+            lk.lock();
+            if (--pending == 0) { job = nullptr; cv_done.notify_all(); }
+        }
+    }
+  public:
+    explicit HostWorkers(int32_t n) { for (int32_t k = 0; k < n; ++k) threads.emplace_back([this] { worker(); }); for (auto& t : threads) t.detach(); }
+    int32_t size() const { return (int32_t)threads.size(); }
+    void run(int32_t parts, const std::function<void(int32_t)>& f) {
+        if (parts <= 0) return;
+        std::lock_guard<std::mutex> one_call(call_mu);
+        std::unique_lock<std::mutex> lk(mu);
+        job = &f; n_parts = parts; next = 0; pending = parts;
+        cv_work.notify_all();
+        take(lk);
+        cv_done.wait(lk, [&] { return pending == 0; });
+    }
+};
+HostWorkers& host_workers() {
+    static HostWorkers* w = new HostWorkers(std::max<int32_t>(0, std::min<int32_t>((int32_t)std::thread::hardware_concurrency(), 8) - 1));
+    return *w;
+}
 
 template <typename F>
 int32_t guarded(F&& f) {
@@ -1065,18 +1112,26 @@ int32_t xg2_matcher_accept_tokens(xg2_matcher* const* matchers, const int32_t* t
     if (B < 0 || (B > 0 && (!matchers || !token_ids || !status_host))) return fail(XG2_EINVAL, "xg2_matcher_accept_tokens: bad argument");
     for (int32_t b = 0; b < B; ++b) if (!matchers[b]) return fail(XG2_EINVAL, "xg2_matcher_accept_tokens: null matcher");
     // matchers are independent: a few host threads each take a contiguous share (a handle listed twice would race)
-    const int32_t n_threads = std::max<int32_t>(1, std::min<int32_t>({(int32_t)std::thread::hardware_concurrency(), 8, B / 64}));
-    auto work = [&](int32_t lo, int32_t hi) {
-        for (int32_t b = lo; b < hi; ++b) {
-            status_host[b] = token_ids[b] < 0 ? XG2_OK : xg2_matcher_accept_token(matchers[b], token_ids[b]);
-            prepare_matcher(*matchers[b]->p);                   // the next fill finds the state ready
+    std::atomic<bool> failed{false};
+    std::string what;
+    std::mutex what_mu;
+    const int32_t share = 32;                                   // matchers per part: small enough to balance, large enough to amortise the hand-over
+    const int32_t parts = (B + share - 1) / share;
+    const std::function<void(int32_t)> work = [&](int32_t part) {
+        try {
+            for (int32_t b = part * share; b < std::min(B, (part + 1) * share); ++b) {
+                status_host[b] = token_ids[b] < 0 ? XG2_OK : xg2_matcher_accept_token(matchers[b], token_ids[b]);
+                prepare_matcher(*matchers[b]->p);               // the next fill finds the state ready
+            }
+        } catch (const std::exception& e) {
+            failed = true;
+            std::lock_guard<std::mutex> lk(what_mu);
+            what = e.what();
         }
     };
-    if (n_threads == 1) { work(0, B); return XG2_OK; }
-    std::vector<std::thread> pool;
-    const int32_t share = (B + n_threads - 1) / n_threads;
-    for (int32_t t = 0; t < n_threads; ++t) pool.emplace_back(work, std::min(B, t * share), std::min(B, (t + 1) * share));
-    for (std::thread& th : pool) th.join();
+    if (parts <= 2) { for (int32_t p = 0; p < parts; ++p) work(p); }
+    else host_workers().run(parts, work);
+    if (failed) return fail(XG2_EINVAL, "xg2_matcher_accept_tokens: " + what);
     return XG2_OK;
 }
 int32_t xg2_matcher_reset(xg2_matcher* m) {
