@@ -1181,6 +1181,23 @@ int32_t xg2_fill_next_token_bitmask(xg2_matcher* const* matchers, int32_t B, int
         // caches compiled just in time (section 3.5): the planes this step's frontiers need and that hold no row yet
         // are built first, on the same stream
         {
+            // matchers that moved since their last fill (and were not advanced by the batched accept call, which leaves them
+            // ready) get their context slice and frontier planes first, on the host threads when there are many
+            std::vector<MatcherImpl*> stale;
+            for (int32_t b = 0; b < B; ++b) if (!matchers[b]->p->prep.valid) stale.push_back(matchers[b]->p.get());
+            std::sort(stale.begin(), stale.end());
+            stale.erase(std::unique(stale.begin(), stale.end()), stale.end());
+            if (stale.size() >= 128) {
+                const int32_t share = 32, parts = ((int32_t)stale.size() + share - 1) / share;
+                std::atomic<bool> failed{false};
+                const std::function<void(int32_t)> work = [&](int32_t part) {
+                    try {
+                        for (size_t k = (size_t)part * share; k < std::min(stale.size(), (size_t)(part + 1) * share); ++k) prepare_matcher(*stale[k]);
+                    } catch (const std::exception&) { failed = true; }
+                };
+                host_workers().run(parts, work);
+                if (failed) return fail(XG2_EINVAL, "xg2_fill_next_token_bitmask: preparing a matcher failed");
+            }
             std::map<CacheImpl*, std::vector<int32_t>> missing;
             for (int32_t b = 0; b < B; ++b) {
                 MatcherImpl& M = *matchers[b]->p;
