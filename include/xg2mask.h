@@ -169,7 +169,8 @@ int32_t xg2_matcher_accept_token(xg2_matcher*, int32_t token_id);
 /* One token for each of B matchers (the sampled tokens of a decoding step; section 3.4: the parser traces
  * the output).  token_ids[b] < 0 skips matcher b.  status_host[b] receives what xg2_matcher_accept_token
  * would have returned for matcher b; the call itself fails only on bad arguments.  The matchers must be
- * distinct; several host threads share the work.                                                    */
+ * distinct; several host threads share the work (a small pool that the library starts at the first
+ * such call and keeps until the process ends).                                                     */
 int32_t xg2_matcher_accept_tokens(xg2_matcher* const* matchers, const int32_t* token_ids, int32_t B, int32_t* status_host);
 int32_t xg2_matcher_reset(xg2_matcher*);
 int32_t xg2_matcher_is_terminated(const xg2_matcher*, int32_t* out);
