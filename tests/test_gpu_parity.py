@@ -494,7 +494,7 @@ def test_near_bound_repetition_planes_full_jit_and_pool(xg):
     assert built_planes_match(b) >= 3
 
 
-def random_grammar(rng):
+def random_grammar(rng, counting=False):
     """A small random EBNF over the letters a-d: 2-4 rules; alternation, ? * + {m,n}, classes; a rule refers to later
     rules (so the references form a DAG) and now and then to itself inside brackets, as grammars of nested data do.
     Unrestricted references between random rules give grammars so ambiguous that item sets exceed any fixed capacity;
@@ -521,6 +521,9 @@ def random_grammar(rng):
         if " " in a and not a.startswith("("):
             a = "(" + a + ")"
         k = rng.random()
+        if counting and k < 0.5 and (a.startswith("[") or a.startswith('"')):
+            lo = rng.randrange(0, 4)                                # long enough for states near the bound to differ
+            return a + "{%d,%d}" % (lo, lo + rng.randrange(4, 14))  # from the inner ones on long tokens only
         if k < 0.15:
             return a + "?"
         if k < 0.25:
@@ -538,7 +541,7 @@ def random_grammar(rng):
     return "".join("%s ::= %s\n" % (nm, alt(i, 0)) for i, nm in enumerate(names))
 
 
-def run_random_grammars(xg, seed, wanted):
+def run_random_grammars(xg, seed, wanted, counting=False):
     """Seeded random grammars over a vocabulary of every string of up to three letters of a-e plus longer samples:
     every plane equal to the oracle's classes (depth 2, merged, follow filter), masks along a random walk equal too."""
     import itertools
@@ -555,11 +558,13 @@ def run_random_grammars(xg, seed, wanted):
     bm = torch.full((1, vocab.words), -1, dtype=torch.int32, device="cuda:0")
     done = skipped = 0
     while done < wanted:
-        ebnf = random_grammar(rng)
+        ebnf = random_grammar(rng, counting)
         try:
-            oracle.Oracle(ebnf, "root")
+            probe = oracle.Oracle(ebnf, "root")
         except Exception:
             continue                                                # not reduced: the CPU tests cover the error path
+        if len(probe.positions()) > 600:
+            continue                                                # keeps the oracle's share of the test to seconds
         try:
             cache, orc = check_planes(xg, Cfg, vocab, va, ebnf, "root", max_contexts=100000)
         except xg.Xg2Error as e:
@@ -587,6 +592,12 @@ def run_random_grammars(xg, seed, wanted):
 
 def test_random_grammars_planes_and_masks(xg):
     assert run_random_grammars(xg, seed=31337, wanted=40) == 40
+
+
+def test_random_counting_grammars_planes_and_masks(xg):
+    """The same with bounded repetitions of up to 16: planes of states near a bound take their short tokens from the
+    plane of the inner states (section 3.6) and must still equal the oracle's classes bit for bit."""
+    assert run_random_grammars(xg, seed=2718, wanted=25, counting=True) == 25
 
 
 def test_one_fill_call_over_matchers_of_different_grammars(xg):
