@@ -73,29 +73,55 @@ inline void upload_pinned(void* dev, void* host, size_t bytes, hipStream_t strea
 
 // Several host arrays laid out back to back (256-byte aligned) in one pinned buffer, moved to the device
 // with one copy.
+// The pinned host buffer and, for uploads that need not outlive the call, the device buffer are kept between calls
+// (allocating them costs more than a small build); the caller serialises uses (the mutex of the large-capacity
+// scratch) and waits for the stream before the next use.
+struct Staging {
+    uint8_t* host = nullptr; size_t host_cap = 0;
+    uint8_t* dev = nullptr; size_t dev_cap = 0;
+};
+Staging& staging() { static Staging* s = new Staging(); return *s; }
+
 struct Packer {
     struct Seg { const void* src; size_t bytes, off; };
     std::vector<Seg> segs;
     size_t total = 0;
     uint8_t* host = nullptr;
     uint8_t* dev = nullptr;
-    bool own_dev = true;
     template <typename T> size_t add(const std::vector<T>& v) {
         size_t off = total;
         segs.push_back({v.data(), v.size() * sizeof(T), off});
         total = (total + v.size() * sizeof(T) + 255) & ~(size_t)255;
         return off;
     }
-    void stage() {
-        size_t n = std::max<size_t>(total, 256);
-        HIP_CHECK(hipHostMalloc((void**)&host, n, hipHostMallocDefault));
-        HIP_CHECK(hipMalloc((void**)&dev, n));
+    // own_dev: the device block is allocated for this upload and belongs to the caller afterwards
+    void stage(bool own_dev) {
+        const size_t n = std::max<size_t>(total, 256);
+        Staging& S = staging();
+        if (S.host_cap < n) {
+            if (S.host) (void)hipHostFree(S.host);
+            S.host = nullptr; S.host_cap = 0;
+            const size_t cap = std::max<size_t>(n + n / 2, (size_t)1 << 20);
+            HIP_CHECK(hipHostMalloc((void**)&S.host, cap, hipHostMallocDefault));
+            S.host_cap = cap;
+        }
+        host = S.host;
+        if (own_dev) {
+            HIP_CHECK(hipMalloc((void**)&dev, n));
+        } else {
+            if (S.dev_cap < n) {
+                if (S.dev) (void)hipFree(S.dev);
+                S.dev = nullptr; S.dev_cap = 0;
+                const size_t cap = std::max<size_t>(n + n / 2, (size_t)1 << 20);
+                HIP_CHECK(hipMalloc((void**)&S.dev, cap));
+                S.dev_cap = cap;
+            }
+            dev = S.dev;
+        }
         for (const Seg& s : segs) if (s.bytes) std::memcpy(host + s.off, s.src, s.bytes);
     }
     void copy(hipStream_t stream) { if (total) upload_pinned(dev, host, total, stream); }
     template <typename T> T* at(size_t off) const { return reinterpret_cast<T*>(dev + off); }
-    uint8_t* release_dev() { own_dev = false; return dev; }
-    ~Packer() { if (host) (void)hipHostFree(host); if (dev && own_dev) (void)hipFree(dev); }
 };
 
 void require_device() {
@@ -569,7 +595,8 @@ int32_t build_planes(CacheImpl& cache, const std::vector<int32_t>& todo, hipStre
     }
     const size_t o_chunks = tab.add(chunks), o_pctx = tab.add(plane_ctx), o_items = tab.add(ctx_items), o_wait = tab.add(ctx_wait),
                  o_wait_off = tab.add(ctx_wait_off), o_rows = tab.add(build_rows), o_copies = tab.add(copies), o_zero = tab.add(zeros);
-    tab.stage();
+    tab.stage(with_tables);
+    if (with_tables) cache.d_tables = tab.dev;                     // the cache owns the block from here on
     res.host_ms = ms_since(t1);
 
     hipEvent_t ev0, ev1, evk0, evk1;
@@ -580,7 +607,6 @@ int32_t build_planes(CacheImpl& cache, const std::vector<int32_t>& todo, hipStre
     HIP_CHECK(hipEventRecord(ev0, stream));
     tab.copy(stream);
     if (with_tables) {
-        cache.d_tables = tab.release_dev();
         cache.dt.state = tab.at<const uint4>(o_state);
         cache.dt.exp_list = tab.at<const uint32_t>(o_exp);
         cache.dt.trans = tab.at<const uint32_t>(o_trans);
