@@ -28,14 +28,14 @@ HBM_PEAK_GBS = 8000.0
 # valid only for the kernel sources they were taken with.  The same counters read 303,884 KiB (FETCH_SIZE) and
 # 607,744 KiB (WRITE_SIZE) for a device-to-device copy of 607,744 KiB, hence the scale factors.
 PMC = {
-    "sources_sha256": "438dc757d725c46aac3bf0665d6d0d1a9b2df72069817fb716d465703a848177",
+    "sources_sha256": "a5dbcf0f681191a88f610b237ba4161e3688235f8342b2b632804dafd3fdbfd3",
     "fetch_scale": 2.0, "write_scale": 1.0,
-    "k_build": (10874.3, 3381.5),
-    "k_fill_or": (4067.4, 19165.1),
-    "k_apply_vec<8>": (98627.4, 303872.0),
+    "k_build": (10874.8, 3381.5),
+    "k_fill_or": (4112.1, 19163.0),
+    "k_apply_vec<8>": (98622.1, 303872.0),
     # wave instructions of one k_build launch (rocprofv3 --pmc SQ_INSTS_VALU + SALU + BRANCH + LDS + VMEM_RD + VMEM_WR + SMEM)
     "k_build_wave_instructions": 33494421.0,
-    "k_apply_vec<4>": (182233.5, 605511.0),
+    "k_apply_vec<4>": (182227.2, 605511.0),
 }
 KERNEL_SOURCES = ("kernels.hip", "earley_core.hpp", "device.hpp")
 

@@ -315,6 +315,7 @@ __global__ __launch_bounds__(256) void k_popcount(const uint32_t* const* plane_p
 // k_recheck: each wave takes 64 listed words, spreads their set bits densely over its lanes and runs the
 // Earley routine from the row's context; survivors are OR-ed into the bitmask.
 constexpr int FILL_THREADS = 256;
+constexpr int FILL_BLOCK = 5;                          // steps of the union whose loads are issued together
 constexpr int FILL_K = 8, FILL_WM = 12;
 constexpr int RECHECK_WAVES = 4;
 constexpr uint32_t RECHECK_CHUNK = 16;                    // listed words per wave per round (few, so that many waves share the work)
@@ -359,38 +360,56 @@ __global__ __launch_bounds__(FILL_THREADS) void k_fill_or(FillBatch F, DevVocab 
     const uint32_t eos_word = F.eos_id >> 5, eos_bit = 1u << (F.eos_id & 31);
     uint32_t* out = reinterpret_cast<uint32_t*>(bitmask) + (long long)b * row_stride;
     const uint32_t n_steps = (Vd.W / WORDS + FILL_THREADS - 1) / FILL_THREADS;        // same for every thread: the ballots see whole waves
-    for (uint32_t step = 0; step < n_steps; ++step) {
-        const uint32_t v = step * FILL_THREADS + threadIdx.x;
-        const bool in_row = v < Vd.W / WORDS;
-        uint32_t acc[WORDS], unc[WORDS];
+    // FILL_BLOCK steps at a time: first every load of the block (plane after plane, so that a thread has several
+    // independent loads in flight), then the candidates and the stores
+    for (uint32_t step0 = 0; step0 < n_steps; step0 += FILL_BLOCK) {
+        uint32_t acc[FILL_BLOCK][WORDS], unc[FILL_BLOCK][WORDS];
 #pragma unroll
-        for (int c = 0; c < WORDS; ++c) { acc[c] = 0; unc[c] = 0; }
-        if (in_row && !(flags & 2u))
+        for (int s = 0; s < FILL_BLOCK; ++s)
+#pragma unroll
+            for (int c = 0; c < WORDS; ++c) { acc[s][c] = 0; unc[s][c] = 0; }
+        if (!(flags & 2u))
             for (uint32_t k = 0; k < front_n; ++k) {
                 const uint64_t addr = F.front_planes[front_off + k];
                 const uint32_t* row = reinterpret_cast<const uint32_t*>(addr & ~(uint64_t)1);
-                if (WORDS == 4) {
-                    const uint4 a = reinterpret_cast<const uint4*>(row)[v];
-                    acc[0] |= a.x; acc[1 % WORDS] |= a.y; acc[2 % WORDS] |= a.z; acc[3 % WORDS] |= a.w;
-                    if (!(addr & 1)) {
-                        const uint4 u = reinterpret_cast<const uint4*>(row + Vd.W)[v];
-                        unc[0] |= u.x; unc[1 % WORDS] |= u.y; unc[2 % WORDS] |= u.z; unc[3 % WORDS] |= u.w;
+                const bool with_unc = !(addr & 1);
+#pragma unroll
+                for (int s = 0; s < FILL_BLOCK; ++s) {
+                    const uint32_t v = (step0 + s) * FILL_THREADS + threadIdx.x;
+                    if (v >= Vd.W / WORDS) continue;
+                    if (WORDS == 4) {
+                        const uint4 a = reinterpret_cast<const uint4*>(row)[v];
+                        acc[s][0] |= a.x; acc[s][1 % WORDS] |= a.y; acc[s][2 % WORDS] |= a.z; acc[s][3 % WORDS] |= a.w;
+                        if (with_unc) {
+                            const uint4 u = reinterpret_cast<const uint4*>(row + Vd.W)[v];
+                            unc[s][0] |= u.x; unc[s][1 % WORDS] |= u.y; unc[s][2 % WORDS] |= u.z; unc[s][3 % WORDS] |= u.w;
+                        }
+                    } else {
+                        acc[s][0] |= row[v];
+                        if (with_unc) unc[s][0] |= row[Vd.W + v];
                     }
-                } else {
-                    acc[0] |= row[v];
-                    if (!(addr & 1)) unc[0] |= row[Vd.W + v];
                 }
             }
 #pragma unroll
-        for (int c = 0; c < WORDS; ++c) {
-            const uint32_t w = v * WORDS + c;
-            const uint32_t cand = in_row ? (unc[c] & ~acc[c]) : 0u;
-            if ((flags & 3u) && eos_word == w) acc[c] |= eos_bit;
-            list_candidates(F, &n_listed, cand, b * Vd.W, w);
-        }
-        if (in_row) {
-            if (WORDS == 4) reinterpret_cast<uint4*>(out)[v] = make_uint4(acc[0], acc[1 % WORDS], acc[2 % WORDS], acc[3 % WORDS]);
-            else out[v] = acc[0];
+        for (int s = 0; s < FILL_BLOCK; ++s) {
+            if (step0 + s >= n_steps) break;                        // same for every thread
+            const uint32_t v = (step0 + s) * FILL_THREADS + threadIdx.x;
+            const bool in_row = v < Vd.W / WORDS;
+            uint32_t cand[WORDS], any = 0;
+#pragma unroll
+            for (int c = 0; c < WORDS; ++c) {
+                cand[c] = in_row ? (unc[s][c] & ~acc[s][c]) : 0u;
+                any |= cand[c];
+                if ((flags & 3u) && eos_word == v * WORDS + c) acc[s][c] |= eos_bit;
+            }
+            if (__any(any != 0)) {                                  // candidates are few: most wavefronts have none
+#pragma unroll
+                for (int c = 0; c < WORDS; ++c) list_candidates(F, &n_listed, cand[c], b * Vd.W, v * WORDS + c);
+            }
+            if (in_row) {
+                if (WORDS == 4) reinterpret_cast<uint4*>(out)[v] = make_uint4(acc[s][0], acc[s][1 % WORDS], acc[s][2 % WORDS], acc[s][3 % WORDS]);
+                else out[v] = acc[s][0];
+            }
         }
     }
     __syncthreads();
