@@ -220,6 +220,46 @@ def test_batched_accept_equals_one_by_one(xg):
                 assert batched[b].frontier() == single[b].frontier()
 
 
+def test_batched_accept_from_several_threads(xg):
+    """The host threads behind xg2_matcher_accept_tokens are shared by all callers: four caller threads, each with its
+    own matchers, many calls each, end in the same states as one call per matcher, and nothing waits for ever."""
+    import threading
+    cfg = gen.build_config(1)
+    ebnf, root = cfg.grammars[0]
+    g = xg.Grammar(ebnf, root)
+    v = xg.Vocab(cfg.vocab.tokens, 0, [0])
+    seg = gen.Segmenter(cfg.vocab)
+    B, steps, callers = 160, 10, 4
+    errors = []
+
+    def caller(seed):
+        try:
+            rng = random.Random(seed)
+            single = [xg.Matcher(grammar=g, vocab=v) for _ in range(B)]
+            batched = [xg.Matcher(grammar=g, vocab=v) for _ in range(B)]
+            batch = xg.MatcherBatch(batched)
+            traces = [seg.segment(cfg.sample_text(rng, 0), rng) + [0] for _ in range(B)]
+            for step in range(steps):
+                ids = [traces[b][min(step, len(traces[b]) - 1)] if rng.random() < 0.8 else rng.randrange(1, cfg.vocab.size) for b in range(B)]
+                status = batch.accept_tokens(ids)
+                for b in range(B):
+                    want = xg.lib.xg2_matcher_accept_token(single[b].h, ids[b])
+                    assert status[b] == want, (seed, step, b)
+                    assert batched[b].is_terminated() == single[b].is_terminated()
+                    if not single[b].is_terminated():
+                        assert batched[b].frontier() == single[b].frontier()
+        except Exception as e:                                   # reported by the main thread
+            errors.append(repr(e))
+
+    threads = [threading.Thread(target=caller, args=(900 + k,)) for k in range(callers)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join(timeout=120)
+    assert not any(t.is_alive() for t in threads), "a caller is stuck"
+    assert not errors, errors
+
+
 def test_device_calls_fail_loudly_without_a_gpu(xg, has_gpu):
     if has_gpu:
         pytest.skip("a GPU is present")
