@@ -79,6 +79,8 @@ inline void upload_pinned(void* dev, void* host, size_t bytes, hipStream_t strea
 struct Staging {
     uint8_t* host = nullptr; size_t host_cap = 0;
     uint8_t* dev = nullptr; size_t dev_cap = 0;
+    hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};   // around a build and around its classification kernel
+    void ensure_events() { for (hipEvent_t& e : ev) if (!e) HIP_CHECK(hipEventCreate(&e)); }
 };
 Staging& staging() { static Staging* s = new Staging(); return *s; }
 
@@ -599,11 +601,8 @@ int32_t build_planes(CacheImpl& cache, const std::vector<int32_t>& todo, hipStre
     if (with_tables) cache.d_tables = tab.dev;                     // the cache owns the block from here on
     res.host_ms = ms_since(t1);
 
-    hipEvent_t ev0, ev1, evk0, evk1;
-    HIP_CHECK(hipEventCreate(&ev0));
-    HIP_CHECK(hipEventCreate(&ev1));
-    HIP_CHECK(hipEventCreate(&evk0));
-    HIP_CHECK(hipEventCreate(&evk1));
+    staging().ensure_events();
+    const hipEvent_t ev0 = staging().ev[0], ev1 = staging().ev[1], evk0 = staging().ev[2], evk1 = staging().ev[3];
     HIP_CHECK(hipEventRecord(ev0, stream));
     tab.copy(stream);
     if (with_tables) {
@@ -640,7 +639,6 @@ int32_t build_planes(CacheImpl& cache, const std::vector<int32_t>& todo, hipStre
     HIP_CHECK(hipGetLastError());
     HIP_CHECK(hipEventElapsedTime(&res.device_ms, ev0, ev1));
     HIP_CHECK(hipEventElapsedTime(&res.kernel_ms, evk0, evk1));
-    (void)hipEventDestroy(ev0); (void)hipEventDestroy(ev1); (void)hipEventDestroy(evk0); (void)hipEventDestroy(evk1);
     if (slow_counts[1]) {
         for (size_t k = 0; k < build.size(); ++k) {                       // these rows hold partial results: forget them
             pool.rows.erase(cache.planes[(size_t)build[k]].key);
