@@ -309,6 +309,31 @@ def test_config4_cross_grammar_pool(xg):
     assert built1 == pool1.stats()[0] == len(distinct)              # exact count of distinct structures, the slow way
 
 
+def test_config4_full_size_sampled_planes(xg):
+    """The cross-grammar workload at its full size (256 grammars over 512 tools, one pool, 151,936 tokens): sampled planes
+    of grammars compiled late, most of them served by planes that earlier grammars built, equal the oracle's classes
+    for that grammar alone."""
+    cfg, vocab, va = load(4)
+    pool = xg.Pool()
+    keep = {}
+    for gi, (ebnf, root) in enumerate(cfg.grammars):
+        cache = xg.compile_grammar(vocab, ebnf, root, pool=pool, stream=_stream())
+        if gi in (130, 255):
+            keep[gi] = cache
+    assert pool.stats()[0] < 700000                                  # far fewer rows than the 3 million planes in use
+    rng = random.Random(4)
+    for gi, cache in sorted(keep.items()):
+        assert cache.stats.built < cache.stats.unique / 4            # mostly reuse by now
+        ebnf, root = cfg.grammars[gi]
+        orc = oracle.Oracle(ebnf, root)
+        for k in rng.sample(range(cache.num_planes()), 25):
+            pos, parent = cache.plane_info(k)
+            acc, unc = cache.get_planes(k)
+            want_a, want_u = planes_of(orc, pos, va, parent, True)
+            assert np.array_equal(acc, want_a), ("accepted", gi, pos, parent, diff_words(acc, want_a, cfg.vocab.tokens))
+            assert np.array_equal(unc, want_u), ("uncertain", gi, pos, parent, diff_words(unc, want_u, cfg.vocab.tokens))
+
+
 def test_pool_gives_up_unused_planes_when_full(xg):
     """A pool bounded by max_bytes: planes of destroyed caches are evicted (least recently used first) to make room,
     rebuilt when needed again, and always equal to the oracle's; a pool whose planes are all in use reports overflow."""
