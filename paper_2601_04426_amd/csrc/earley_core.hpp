@@ -52,51 +52,47 @@ struct MemBytes {
 // happens.  A state with rule edges brings its expansion: every item that prediction, and advancing over
 // rules that derive the empty string, add (already followed to the end on the host, so nothing added here
 // needs expanding again) and one wait entry {rule, target | origin} per rule edge involved.  The flags
-// travel with the state reference; memory is read only for expansions.  Returns false when a list is full.
+// travel with the state reference; memory is read only for expansions.
 constexpr uint32_t REF_MASK = (1u << REF_BITS) - 1;
 constexpr uint32_t EXP_CURRENT = 1u << REF_BITS;
 
+// A list that is full, or a search bound that is used up, sets `full` and drops the entry; the caller looks at the flag
+// once per byte (one way out of the step instead of one per call keeps the divergent control flow small).
 template <class S>
-__device__ __forceinline__ bool add_nxt(S& st, uint32_t item, int& nn, bool& fresh) {
-    fresh = false;
-    if (!st.charge(nn)) return false;                            // large lists: a bound on the searching of one token
-    for (int k = 0; k < nn; ++k) if (st.get_nxt(k) == item) return true;
-    if (nn == S::K) return false;
+__device__ __forceinline__ bool add_nxt(S& st, uint32_t item, int& nn, bool& full) {
+    if (!st.charge(nn)) { full = true; return false; }           // large lists: a bound on the searching of one token
+    for (int k = 0; k < nn; ++k) if (st.get_nxt(k) == item) return false;
+    if (nn == S::K) { full = true; return false; }
     st.set_nxt(nn++, item);
-    fresh = true;
-    return true;
+    return true;                                                 // new in the list
 }
 
 template <class S>
-__device__ __forceinline__ bool add_wait(S& st, uint32_t rule, uint32_t tgt, int& nw, int wbeg) {
-    if (!st.charge(nw - wbeg)) return false;
-    for (int k = wbeg; k < nw; ++k) if (st.wait_tgt(k) == tgt && st.wait_rule(k) == rule) return true;
-    if (nw == S::WM) return false;
+__device__ __forceinline__ void add_wait(S& st, uint32_t rule, uint32_t tgt, int& nw, int wbeg, bool& full) {
+    if (!st.charge(nw - wbeg)) { full = true; return; }
+    for (int k = wbeg; k < nw; ++k) if (st.wait_tgt(k) == tgt && st.wait_rule(k) == rule) return;
+    if (nw == S::WM) { full = true; return; }
     st.set_wait(nw++, rule, tgt);
-    return true;
 }
 
 template <class S>
-__device__ __forceinline__ bool enter(const DevTables& T, S& st, uint32_t ref, uint32_t origin, uint32_t set_idx, int& nn, int& nw, int wbeg) {
-    bool fresh;
+__device__ __forceinline__ void enter(const DevTables& T, S& st, uint32_t ref, uint32_t origin, uint32_t set_idx, int& nn, int& nw, int wbeg, bool& full) {
     if ((ref & (F_BYTE | F_FINAL)) || !(ref & F_REF)) {
-        if (!add_nxt(st, ref | (origin << REF_BITS), nn, fresh)) return false;
-        if (!fresh) return true;
+        if (!add_nxt(st, ref | (origin << REF_BITS), nn, full)) return;      // there already (or no room): nothing more to add
     }
     if (ref & F_REF) {
         const uint4 d = T.state[ref & SID_MASK];
         const uint32_t* e = T.exp_list + d.y;
         for (uint32_t k = 0; k < d.z; ++k) {
             const uint32_t w = e[k];
-            if (!add_nxt(st, (w & REF_MASK) | (((w & EXP_CURRENT) ? set_idx : origin) << REF_BITS), nn, fresh)) return false;
+            add_nxt(st, (w & REF_MASK) | (((w & EXP_CURRENT) ? set_idx : origin) << REF_BITS), nn, full);
         }
         e += d.z;
         for (uint32_t k = 0; k < d.w; ++k) {
             const uint32_t w = e[2 * k + 1];
-            if (!add_wait(st, e[2 * k], (w & REF_MASK) | (((w & EXP_CURRENT) ? set_idx : origin) << REF_BITS), nw, wbeg)) return false;
+            add_wait(st, e[2 * k], (w & REF_MASK) | (((w & EXP_CURRENT) ? set_idx : origin) << REF_BITS), nw, wbeg, full);
         }
     }
-    return true;
 }
 
 // Earley recognition of the n bytes at tok, continuing from context C.  New item sets are numbered
@@ -139,8 +135,9 @@ __device__ int scan_token(const DevTables& T, const uint32_t* cls_words, const D
         int nn = 0;
         const int wbeg = nw;
         const uint32_t set_idx = C.H + (uint32_t)i;
+        bool full = false;
         if (pending != NO_TARGET) {
-            if (!enter(T, st, pending, one >> REF_BITS, set_idx, nn, nw, wbeg)) return RES_OVERFLOW;
+            enter(T, st, pending, one >> REF_BITS, set_idx, nn, nw, wbeg, full);
         } else {
             const uint32_t b = tok.next();
             const uint32_t cls = (cls_words[b >> 2] >> ((b & 3) * 8)) & 0xFF;
@@ -148,7 +145,7 @@ __device__ int scan_token(const DevTables& T, const uint32_t* cls_words, const D
                 const uint32_t it = st.get_cur(k);
                 if (!(it & F_BYTE)) continue;
                 const uint32_t tgt = T.trans[(it & SID_MASK) * T.n_classes + cls];
-                if (tgt != NO_TARGET && !enter(T, st, tgt, it >> REF_BITS, set_idx, nn, nw, wbeg)) return RES_OVERFLOW;
+                if (tgt != NO_TARGET) enter(T, st, tgt, it >> REF_BITS, set_idx, nn, nw, wbeg, full);
             }
         }
         // completer over the growing item list (prediction happened on entering)
@@ -162,7 +159,7 @@ __device__ int scan_token(const DevTables& T, const uint32_t* cls_words, const D
                 if (FOLLOW) {
                     const uint32_t rule = T.state[it & SID_MASK].x;
                     for (uint32_t k = T.site_off[rule]; k < T.site_off[rule + 1]; ++k)
-                        if (!enter(T, st, T.site_tgt[k], ROOT_ORIGIN, set_idx, nn, nw, wbeg)) return RES_OVERFLOW;
+                        enter(T, st, T.site_tgt[k], ROOT_ORIGIN, set_idx, nn, nw, wbeg, full);
                 }
                 continue;
             }
@@ -174,9 +171,10 @@ __device__ int scan_token(const DevTables& T, const uint32_t* cls_words, const D
                 uint32_t wr, wt;
                 if (local) { wr = st.wait_rule(k); wt = st.wait_tgt(k); }
                 else { const uint2 w = C.wait[k]; wr = w.x; wt = w.y; }
-                if (wr == rule && !enter(T, st, wt & REF_MASK, wt >> REF_BITS, set_idx, nn, nw, wbeg)) return RES_OVERFLOW;
+                if (wr == rule) enter(T, st, wt & REF_MASK, wt >> REF_BITS, set_idx, nn, nw, wbeg, full);
             }
         }
+        if (full) return RES_OVERFLOW;
         if (nn == 0 && nw == wbeg) return res;               // dead: nothing survives this byte
         if (root_now && i + 1 < n) res |= RES_EARLY;
         st.swap();
