@@ -28,14 +28,14 @@ HBM_PEAK_GBS = 8000.0
 # valid only for the kernel sources they were taken with.  The same counters read 303,884 KiB (FETCH_SIZE) and
 # 607,744 KiB (WRITE_SIZE) for a device-to-device copy of 607,744 KiB, hence the scale factors.
 PMC = {
-    "sources_sha256": "a5dbcf0f681191a88f610b237ba4161e3688235f8342b2b632804dafd3fdbfd3",
+    "sources_sha256": "8b57db1ddd17c43dd08c6063f3ed546c0c121913a114e198b882a1efa53b1516",
     "fetch_scale": 2.0, "write_scale": 1.0,
-    "k_build": (10874.8, 3381.5),
-    "k_fill_or": (4112.1, 19163.0),
-    "k_apply_vec<8>": (98622.1, 303872.0),
+    "k_build": (10810.8, 3381.5),
+    "k_fill_or": (4116.5, 19166.2),
+    "k_apply_vec<8>": (98622.6, 303872.0),
     # wave instructions of one k_build launch (rocprofv3 --pmc SQ_INSTS_VALU + SALU + BRANCH + LDS + VMEM_RD + VMEM_WR + SMEM)
-    "k_build_wave_instructions": 33494421.0,
-    "k_apply_vec<4>": (182227.2, 605511.0),
+    "k_build_wave_instructions": 31911390.0,
+    "k_apply_vec<4>": (182233.1, 605511.0),
 }
 KERNEL_SOURCES = ("kernels.hip", "earley_core.hpp", "device.hpp")
 

@@ -61,7 +61,9 @@ constexpr uint32_t EXP_CURRENT = 1u << REF_BITS;
 template <class S>
 __device__ __forceinline__ bool add_nxt(S& st, uint32_t item, int& nn, bool& full) {
     if (!st.charge(nn)) { full = true; return false; }           // large lists: a bound on the searching of one token
-    for (int k = 0; k < nn; ++k) if (st.get_nxt(k) == item) return false;
+    bool found = false;                                          // no way out of the loop: one compare more costs less than the exit
+    for (int k = 0; k < nn; ++k) found |= st.get_nxt(k) == item;
+    if (found) return false;
     if (nn == S::K) { full = true; return false; }
     st.set_nxt(nn++, item);
     return true;                                                 // new in the list
@@ -70,7 +72,9 @@ __device__ __forceinline__ bool add_nxt(S& st, uint32_t item, int& nn, bool& ful
 template <class S>
 __device__ __forceinline__ void add_wait(S& st, uint32_t rule, uint32_t tgt, int& nw, int wbeg, bool& full) {
     if (!st.charge(nw - wbeg)) { full = true; return; }
-    for (int k = wbeg; k < nw; ++k) if (st.wait_tgt(k) == tgt && st.wait_rule(k) == rule) return;
+    bool found = false;
+    for (int k = wbeg; k < nw; ++k) found |= (st.wait_tgt(k) == tgt) & (st.wait_rule(k) == rule);
+    if (found) return;
     if (nw == S::WM) { full = true; return; }
     st.set_wait(nw++, rule, tgt);
 }
@@ -136,40 +140,49 @@ __device__ int scan_token(const DevTables& T, const uint32_t* cls_words, const D
         const int wbeg = nw;
         const uint32_t set_idx = C.H + (uint32_t)i;
         bool full = false;
-        if (pending != NO_TARGET) {
-            enter(T, st, pending, one >> REF_BITS, set_idx, nn, nw, wbeg, full);
-        } else {
-            const uint32_t b = tok.next();
-            const uint32_t cls = (cls_words[b >> 2] >> ((b & 3) * 8)) & 0xFF;
-            for (int k = 0; k < nc; ++k) {                       // scanner: one table word per scannable item
-                const uint32_t it = st.get_cur(k);
-                if (!(it & F_BYTE)) continue;
-                const uint32_t tgt = T.trans[(it & SID_MASK) * T.n_classes + cls];
-                if (tgt != NO_TARGET) enter(T, st, tgt, it >> REF_BITS, set_idx, nn, nw, wbeg, full);
+        {
+            // scanner: one table word per scannable item (the automaton walk has looked its one word up already)
+            const bool walked = pending != NO_TARGET;
+            uint32_t cls = 0;
+            if (!walked) {
+                const uint32_t b = tok.next();
+                cls = (cls_words[b >> 2] >> ((b & 3) * 8)) & 0xFF;
+            }
+            const int n_scan = walked ? 1 : nc;
+            for (int k = 0; k < n_scan; ++k) {
+                uint32_t tgt = pending, origin = one >> REF_BITS;
+                if (!walked) {
+                    const uint32_t it = st.get_cur(k);
+                    if (!(it & F_BYTE)) continue;
+                    tgt = T.trans[(it & SID_MASK) * T.n_classes + cls];
+                    origin = it >> REF_BITS;
+                }
+                if (tgt != NO_TARGET) enter(T, st, tgt, origin, set_idx, nn, nw, wbeg, full);
             }
         }
-        // completer over the growing item list (prediction happened on entering)
+        // completer over the growing item list (prediction happened on entering).  What a completed item brings in
+        // comes from one of three lists: the wait entries of its origin set made during this token, those of the
+        // context, or (follow mode, end of the root instance) the states in which referencing rules continue.
         bool root_now = false;
         for (int pn = 0; pn < nn; ++pn) {
             const uint32_t it = st.get_nxt(pn);
             const uint32_t origin = it >> REF_BITS;
             if (!(it & F_FINAL) || origin == set_idx) continue;  // rules that derive the empty string were advanced over on entering
-            if (origin == ROOT_ORIGIN) {
+            const bool root_end = origin == ROOT_ORIGIN;
+            if (root_end) {
                 root_now = true;
-                if (FOLLOW) {
-                    const uint32_t rule = T.state[it & SID_MASK].x;
-                    for (uint32_t k = T.site_off[rule]; k < T.site_off[rule + 1]; ++k)
-                        enter(T, st, T.site_tgt[k], ROOT_ORIGIN, set_idx, nn, nw, wbeg, full);
-                }
-                continue;
+                if (!FOLLOW) continue;
             }
             const uint32_t rule = T.state[it & SID_MASK].x;
-            const bool local = origin >= C.H;
-            const int lo = local ? (int)st.get_wstart((int)(origin - C.H)) : (int)C.wait_off[origin];
-            const int hi = local ? (int)st.get_wstart((int)(origin - C.H) + 1) : (int)C.wait_off[origin + 1];
+            const bool local = !root_end && origin >= C.H;
+            int lo, hi;
+            if (root_end) { lo = (int)T.site_off[rule]; hi = (int)T.site_off[rule + 1]; }
+            else if (local) { lo = (int)st.get_wstart((int)(origin - C.H)); hi = (int)st.get_wstart((int)(origin - C.H) + 1); }
+            else { lo = (int)C.wait_off[origin]; hi = (int)C.wait_off[origin + 1]; }
             for (int k = lo; k < hi; ++k) {
                 uint32_t wr, wt;
-                if (local) { wr = st.wait_rule(k); wt = st.wait_tgt(k); }
+                if (root_end) { wr = rule; wt = T.site_tgt[k] | (ROOT_ORIGIN << REF_BITS); }
+                else if (local) { wr = st.wait_rule(k); wt = st.wait_tgt(k); }
                 else { const uint2 w = C.wait[k]; wr = w.x; wt = w.y; }
                 if (wr == rule) enter(T, st, wt & REF_MASK, wt >> REF_BITS, set_idx, nn, nw, wbeg, full);
             }
