@@ -14,7 +14,7 @@ ARCH = "gfx950"
 
 def build(verbose: bool = False) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, f"--offload-arch={ARCH}", "-O3", "-std=c++17", "-fPIC", "-shared",
+    cmd = [hipcc, f"--offload-arch={ARCH}", "-O3", "-Xarch_device", "-Os", "-std=c++17", "-fPIC", "-shared",
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
            "-Wall", "-Wno-unused-command-line-argument",
            "-o", LIB] + [os.path.join(CSRC, s) for s in SOURCES]
