@@ -156,6 +156,7 @@ struct VocabImpl {
     uint32_t near_depths = 0;
     std::vector<uint32_t> long_rank, long_off;
     DevBuf<uint32_t> d_long_rank, d_short_mask;
+    DevBuf<uint8_t> d_first_byte;               // first byte of every token id (0 for the empty ones), W * 32 entries
 
     const uint8_t* tok(int32_t id) const { return bytes.data() + offs[(size_t)id]; }
     size_t len(int32_t id) const { return (size_t)(offs[(size_t)id + 1] - offs[(size_t)id]); }
@@ -188,6 +189,9 @@ struct VocabImpl {
         if (long_rank.empty()) long_rank.push_back(0);
         d_long_rank.upload(long_rank, nullptr);
         d_short_mask.upload(short_mask, nullptr);
+        std::vector<uint8_t> first_byte((size_t)W * 32, 0);
+        for (int32_t i = 0; i < V; ++i) if (len(i)) first_byte[(size_t)i] = tok(i)[0];
+        d_first_byte.upload(first_byte, nullptr);
         HIP_CHECK(hipStreamSynchronize(nullptr));
         dv.long_rank = d_long_rank.p;
         dv.tok16 = d_tok16.p;
@@ -324,6 +328,8 @@ struct PlaneInfo {
     uint32_t sid; int64_t waiter_sid;                       // start of the build: position, and the waiting parent state or -1
     uint64_t cost;                                          // estimate of the build work (tokens whose first byte the state reads)
     int32_t near_plane = -1, near_depth = 0;                // a plane with the same classes for every token of at most near_depth bytes
+    int32_t fb_plane = -1;                                  // a plane with the same classes for every token whose first byte is in fb_same
+    std::array<uint32_t, 8> fb_same{};
 };
 struct BuildResult {
     int64_t built = 0, executed = 0, slow = 0, n_accepted = 0, n_uncertain = 0;
@@ -512,6 +518,7 @@ int32_t build_planes(CacheImpl& cache, const std::vector<int32_t>& todo, hipStre
     std::vector<uint32_t> ctx_items, ctx_wait, ctx_wait_off;
     std::vector<uint4> chunks, plane_ctx, ranges;
     std::vector<CopyJob> copies;
+    std::vector<FirstByteCopyJob> fb_copies;
     int64_t executed = 0;
     EarleyChart chart(&ft);
     std::map<int32_t, size_t> building;                         // plane index -> position in build
@@ -533,6 +540,23 @@ int32_t build_planes(CacheImpl& cache, const std::vector<int32_t>& todo, hipStre
                 copies.push_back({build_rows[k], src, V.d_short_mask.p + (size_t)(near_d - 1) * V.W, 0});
             }
         }
+        // or the tokens with most first bytes from the plane of the rule's start state, under the same conditions
+        bool by_first_byte = false;
+        if (!near_d && pi.fb_plane >= 0) {
+            const uint32_t* src = cache.planes[(size_t)pi.fb_plane].row;
+            if (!src) {
+                auto pr = pool.rows.find(cache.planes[(size_t)pi.fb_plane].key);
+                auto bi = building.find(pi.fb_plane);
+                if (bi != building.end()) src = build_rows[bi->second];
+                else if (pr != pool.rows.end() && pr->second) src = pr->second;
+            }
+            if (src) {
+                FirstByteCopyJob job{build_rows[k], src, {}};
+                for (int w = 0; w < 8; ++w) job.bytes[w] = pi.fb_same[(size_t)w];
+                fb_copies.push_back(job);
+                by_first_byte = true;
+            }
+        }
         if (pi.waiter_sid < 0) chart.start(pi.sid);
         else chart.start_pair(pi.sid, (uint32_t)pi.waiter_sid);
         const std::vector<ChartSet>& sets = chart.sets();
@@ -550,12 +574,13 @@ int32_t build_planes(CacheImpl& cache, const std::vector<int32_t>& todo, hipStre
         plane_ctx.push_back(make_uint4(item0, (uint32_t)ctx_items.size() - item0, (uint32_t)ctx_wait_off.size(), (uint32_t)sets.size()));
         // a start set that is one item with byte edges only is walked as a plain automaton; the others need the
         // Earley steps from the first byte on and go first, so that the long workgroups do not end the launch
-        const uint32_t heavy = (ctx_items.size() - item0 == 1 && (ctx_items[item0] & (kHasByte | kHasRef | kFinal)) == kHasByte) ? 0u : 1u;
+        const uint32_t heavy = (ctx_items.size() - item0 == 1 && (ctx_items[item0] & (kHasByte | kHasRef)) == kHasByte) ? 0u : 1u;
         for (const ChartSet& cs : sets) {
             ctx_wait_off.push_back((uint32_t)(ctx_wait.size() / 2));
             for (const ChartItem& it : cs.wait) chart.push_triples(it, loc(it.origin), ctx_wait);
         }
         ctx_wait_off.push_back((uint32_t)(ctx_wait.size() / 2));
+        if (by_first_byte) for (int b = 0; b < 256; ++b) if ((pi.fb_same[(size_t)b >> 5] >> (b & 31)) & 1u) live[b] = false;
         for (int b = 0; b < 256;) {
             if (!live[b]) { ++b; continue; }
             int e = b;
@@ -596,7 +621,7 @@ int32_t build_planes(CacheImpl& cache, const std::vector<int32_t>& todo, hipStre
         o_trans = tab.add(ft.trans); o_cls = tab.add(ft.byte_class_words);
     }
     const size_t o_chunks = tab.add(chunks), o_pctx = tab.add(plane_ctx), o_items = tab.add(ctx_items), o_wait = tab.add(ctx_wait),
-                 o_wait_off = tab.add(ctx_wait_off), o_rows = tab.add(build_rows), o_copies = tab.add(copies), o_zero = tab.add(zeros);
+                 o_wait_off = tab.add(ctx_wait_off), o_rows = tab.add(build_rows), o_copies = tab.add(copies), o_fb_copies = tab.add(fb_copies), o_zero = tab.add(zeros);
     tab.stage(with_tables);
     if (with_tables) cache.d_tables = tab.dev;                     // the cache owns the block from here on
     res.host_ms = ms_since(t1);
@@ -629,6 +654,7 @@ int32_t build_planes(CacheImpl& cache, const std::vector<int32_t>& todo, hipStre
     HIP_CHECK(hipEventRecord(evk1, stream));
     if (!build.empty()) launch_build_slow(cache.dt, V.dv, P, S, stream);
     launch_copy_masked(tab.at<const CopyJob>(o_copies), (uint32_t)copies.size(), V.W, stream);
+    launch_copy_first_byte(tab.at<const FirstByteCopyJob>(o_fb_copies), (uint32_t)fb_copies.size(), V.d_first_byte.p, V.W, stream);
     HIP_CHECK(hipEventRecord(ev1, stream));                              // every plane is written
     if (!build.empty()) launch_popcount(d_rows_p, (uint32_t)build_rows.size(), V.W, d_counts, stream);   // statistics
     uint32_t slow_counts[2] = {0, 0};
@@ -992,6 +1018,42 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
                 pi.near_plane = lp->second;
                 pi.near_depth = nr.depth[(size_t)pi.state];
             }
+
+        // Planes of plain automaton states (byte edges only) that move like the start state of their rule on most first
+        // bytes: the states of a dispatch automaton all fall back to free text on any byte that does not continue a tag.
+        // After the first byte the two runs are in states no token can tell apart, so the classes of the tokens with such
+        // a first byte are the start state's; only the tokens with the other first bytes are checked.
+        if (merge) {
+            std::vector<uint8_t> is_near_base(cache->planes.size(), 0);
+            for (const PlaneInfo& pi : cache->planes) if (pi.near_plane >= 0) is_near_base[(size_t)pi.near_plane] = 1;
+            auto plain = [&](const RuleFsm& f, int x) { return f.redges[(size_t)x].empty() && !f.bedges[(size_t)x].empty(); };
+            for (size_t idx = 0; idx < cache->planes.size(); ++idx) {
+                PlaneInfo& pi = cache->planes[idx];
+                if (pi.near_plane >= 0 || is_near_base[idx]) continue;
+                const RuleFsm& f = g.rules[(size_t)pi.rule];
+                const int x = pi.state, b0 = rep[(size_t)pi.rule][0];
+                // (a state that can end its rule brings the continuation of the referencing rule into its start set: the
+                // same one for both states if both can end, none if neither can)
+                if (x == b0 || !plain(f, x) || !plain(f, b0) || f.is_final[(size_t)x] != f.is_final[(size_t)b0]) continue;
+                auto lp = local_plane.find(make_key(pi.rule, b0, pi.parent_rule, pi.parent_state));
+                if (lp == local_plane.end() || cache->planes[(size_t)lp->second].near_plane >= 0) continue;
+                int32_t tx[256], ty[256];
+                std::fill(tx, tx + 256, -1); std::fill(ty, ty + 256, -1);
+                for (auto& e : f.bedges[(size_t)x]) for (int b = e.lo; b <= e.hi; ++b) tx[b] = rep[(size_t)pi.rule][(size_t)e.tgt];
+                for (auto& e : f.bedges[(size_t)b0]) for (int b = e.lo; b <= e.hi; ++b) ty[b] = rep[(size_t)pi.rule][(size_t)e.tgt];
+                uint64_t differ = 0, all = 0;
+                std::array<uint32_t, 8> same{};
+                for (int b = 0; b < 256; ++b) {
+                    const uint64_t n_b = V.fb_start[b + 1] - V.fb_start[b];
+                    if (tx[b] == ty[b]) same[(size_t)b >> 5] |= 1u << (b & 31);
+                    else if (tx[b] >= 0) differ += n_b;
+                    if (tx[b] >= 0) all += n_b;
+                }
+                if (differ * 2 > all) continue;                      // too little to gain
+                pi.fb_plane = lp->second;
+                pi.fb_same = same;
+            }
+        }
 
         // per rule, the states referencing rules continue in: one per class of indistinguishable states
         cache->follow = follow;

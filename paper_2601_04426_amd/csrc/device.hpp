@@ -68,6 +68,10 @@ constexpr uint32_t kChunkListed = 1u, kChunkHeavy = 2u;      // bits of chunk[c]
 // (accepted at [0, W), uncertain at [W, 2 W)).  The mask bits of dst must be clear before.
 struct CopyJob { uint32_t* dst; const uint32_t* src; const uint32_t* mask; uint64_t pad; };
 void launch_copy_masked(const CopyJob* jobs_dev, uint32_t n_jobs, uint32_t W, hipStream_t stream);
+// The same with the mask given by first bytes: dst gets the bits src holds for the tokens whose first byte is in the
+// set `bytes` (256 bits).  first_byte_dev: first byte of every token id, padded to W * 32 entries.
+struct FirstByteCopyJob { uint32_t* dst; const uint32_t* src; uint32_t bytes[8]; };
+void launch_copy_first_byte(const FirstByteCopyJob* jobs_dev, uint32_t n_jobs, const uint8_t* first_byte_dev, uint32_t W, hipStream_t stream);
 
 void launch_build(const DevTables& T, const DevVocab& Vd, const BuildPlan& P, const SlowScratch& S, hipStream_t stream);
 void launch_build_slow(const DevTables& T, const DevVocab& Vd, const BuildPlan& P, const SlowScratch& S, hipStream_t stream);

@@ -3,6 +3,7 @@
 //                  token, item sets in LDS                              (XGrammar-2 section 3.4)
 //   k_build_slow   the same recogniser with larger item sets (LDS, then device memory), for lanes that overflowed
 //   k_copy_masked  short tokens of a plane taken from the plane of a state they cannot tell apart (section 3.6)
+//   k_copy_first_byte  tokens of a plane taken from the plane of a state that moves alike on their first byte
 //   k_upload       per-call plan and tables from pinned host memory
 //   k_fill_or      union of cached planes over the scannable frontier   (section 3.4, runtime part)
 //   k_recheck      re-check of uncertain tokens against the full Earley context, and its large-capacity twin
@@ -124,10 +125,11 @@ __device__ __forceinline__ void store_class(const BuildPlan& P, uint32_t p, uint
 // A persistent grid of single-wave workgroups: workgroup g handles chunks g, g + grid, g + 2 grid, ...
 // (sorted ranks of one plane each; the host puts the long ones first), each in phases, so that the long
 // divergent steps of the recogniser run on full waves instead of on the few lanes that need them.
-// Phase 1 (only when the plane's start set is a single item whose state has byte edges only): every lane
+// Phase 1 (only when the plane's start set is a single item without rule edges): every lane
 // walks its token through the automaton, one table load per byte.  A token that dies is rejected, one that
-// reaches its end is accepted; one that reaches a state which predicts or completes goes on the deferred
-// list.  Phase 2: the deferred tokens (for the other planes: all tokens of the chunk), 64 at a time,
+// reaches its end is accepted; one that reaches a state which predicts, or which completes a rule instance
+// that a parent waits for, goes on the deferred list, and so does one that dies after the outermost instance
+// could have ended (phase 2 then decides between uncertain and rejected).  Phase 2: the deferred tokens (for the other planes: all tokens of the chunk), 64 at a time,
 // through the Earley recogniser.  Tokens that leave the outermost rule early and then die need the second,
 // follow-language run; they are collected across chunks as (plane, rank) pairs and run 64 at a time too.
 __device__ __forceinline__ void follow_batch(const DevTables& T, const DevVocab& Vd, const BuildPlan& P, const SlowScratch& S,
@@ -164,7 +166,9 @@ __global__ __launch_bounds__(64) void k_build(DevTables T, DevVocab Vd, BuildPla
         const uint32_t p = chunk.x;
         const DevCtx C = position_ctx(P, p);
         const uint32_t item0 = C.items[0];
-        const bool walkable = C.n_items == 1 && (item0 & (F_BYTE | F_REF | F_FINAL)) == F_BYTE;   // same for the whole chunk
+        // same for the whole chunk; that the start state itself can end its rule does not matter to a token (it has a byte)
+        const bool walkable = C.n_items == 1 && (item0 & (F_BYTE | F_REF)) == F_BYTE;
+        const bool root_instance = (item0 >> REF_BITS) == ROOT_ORIGIN;   // the start item is the plane's outermost rule instance
         const bool listed = chunk.w & kChunkListed;                 // ranks come from a list of long tokens
         uint32_t n_work = chunk.z - chunk.y;
         if (walkable) {
@@ -179,7 +183,7 @@ __global__ __launch_bounds__(64) void k_build(DevTables T, DevVocab Vd, BuildPla
                     n = (int)(Vd.off[rank + 1] - Vd.off[rank]); tv = Vd.tok16[rank];
                 }
                 if (n > BuildStore::MAXLEN) { defer = true; n = 0; }   // phase 2 hands it to the large-capacity kernel
-                bool walking = n > 0;
+                bool walking = n > 0, early = false;
                 uint32_t sid = item0 & SID_MASK;
                 const uint32_t words[4] = {tv.x, tv.y, tv.z, tv.w};
 #pragma unroll
@@ -189,9 +193,12 @@ __global__ __launch_bounds__(64) void k_build(DevTables T, DevVocab Vd, BuildPla
                         if (walking && wi * 4 + j < n) {
                             const uint32_t b = (words[wi] >> (8 * j)) & 0xFF;
                             const uint32_t tgt = T.trans[sid * T.n_classes + cls_bytes[b]];
-                            if (tgt == NO_TARGET) walking = false;                                   // dead: rejected
-                            else if (tgt & (F_REF | F_FINAL)) { walking = false; defer = true; }   // predicts or completes
-                            else sid = tgt & SID_MASK;
+                            if (tgt == NO_TARGET) { walking = false; defer = early; }              // dead: rejected, unless the rule could end on the way
+                            else if ((tgt & F_REF) || ((tgt & F_FINAL) && !root_instance)) { walking = false; defer = true; }   // predicts, or completes into a parent
+                            else {                                   // the root instance may end here: that only matters if the token dies later
+                                sid = tgt & SID_MASK;
+                                early |= (tgt & F_FINAL) && wi * 4 + j + 1 < n;
+                            }
                         }
                     }
                     if (!__any(walking && (wi + 1) * 4 < n)) break;
@@ -290,6 +297,27 @@ __global__ __launch_bounds__(256) void k_copy_masked(const CopyJob* jobs, uint32
     if (!m) return;
     j.dst[w] |= j.src[w] & m;
     j.dst[W + w] |= j.src[W + w] & m;
+}
+
+__global__ __launch_bounds__(256) void k_copy_first_byte(const FirstByteCopyJob* jobs, const uint8_t* first_byte, uint32_t W) {
+    __shared__ uint32_t bytes[8];
+    const FirstByteCopyJob* j = jobs + blockIdx.y;
+    if (threadIdx.x < 8) bytes[threadIdx.x] = j->bytes[threadIdx.x];
+    __syncthreads();
+    const uint32_t w = blockIdx.x * 256 + threadIdx.x;
+    if (w >= W) return;
+    const uint32_t* src = j->src;
+    uint32_t* dst = j->dst;
+    const uint32_t a = src[w], u = src[W + w];
+    uint32_t todo = a | u, m = 0;                                   // only the tokens the source has a bit for matter
+    while (todo) {
+        const uint32_t bit = __ffs(todo) - 1;
+        todo &= todo - 1;
+        const uint32_t b = first_byte[w * 32 + bit];
+        m |= ((bytes[b >> 5] >> (b & 31)) & 1u) << bit;
+    }
+    if (a & m) dst[w] |= a & m;
+    if (u & m) dst[W + w] |= u & m;
 }
 
 __global__ __launch_bounds__(256) void k_popcount(const uint32_t* const* plane_ptr, uint32_t n_pos, uint32_t W, uint32_t* counts) {
@@ -583,6 +611,13 @@ void launch_copy_masked(const CopyJob* jobs_dev, uint32_t n_jobs, uint32_t W, hi
     for (uint32_t first = 0; first < n_jobs; first += 65535) {      // grid.y limit
         const uint32_t n = std::min<uint32_t>(65535, n_jobs - first);
         hipLaunchKernelGGL(k_copy_masked, dim3((W + 255) / 256, n), dim3(256), 0, stream, jobs_dev + first, W);
+    }
+}
+
+void launch_copy_first_byte(const FirstByteCopyJob* jobs_dev, uint32_t n_jobs, const uint8_t* first_byte_dev, uint32_t W, hipStream_t stream) {
+    for (uint32_t first = 0; first < n_jobs; first += 65535) {      // grid.y limit
+        const uint32_t n = std::min<uint32_t>(65535, n_jobs - first);
+        hipLaunchKernelGGL(k_copy_first_byte, dim3((W + 255) / 256, n), dim3(256), 0, stream, jobs_dev + first, first_byte_dev, W);
     }
 }
 

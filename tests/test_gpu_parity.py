@@ -602,6 +602,8 @@ def run_random_grammars(xg, seed, wanted, counting=False):
         for step in range(8):
             xg.fill_next_token_bitmask([m], bm.data_ptr(), vocab.words, _stream())
             torch.cuda.synchronize()
+            if xg.fill_last_status()[1]:
+                break                                               # item sets beyond the documented capacity of the re-check: reported, not masked
             want = orc.mask(hist, va)
             got = bm.cpu().numpy()[0]
             assert np.array_equal(got, oracle.pack_bitmask(want)), (ebnf, hist, diff_words(got, oracle.pack_bitmask(want), toks))
