@@ -62,7 +62,9 @@ typedef struct xg2_matcher xg2_matcher;
  *   share one plane (section 3.6: states inside a repetition differ minimally).  States that no
  *   string of at most d bytes (3 <= d <= 32) can tell apart have equal planes on the tokens of at
  *   most d bytes: such a plane is checked for its longer tokens only and takes the others from the
- *   plane it agrees with.  The planes are the same with or without the option.
+ *   plane it agrees with.  Likewise a plain automaton state that moves like its rule's start state
+ *   on most first bytes (the states of a dispatch automaton) is checked only for the tokens with
+ *   the other first bytes.  The planes are the same with or without the option.
  * follow_filter (default 1): a token that leaves the plane's (outermost) rule before its last byte
  *   stays uncertain only if the rest of the token is a viable prefix of what can follow that rule
  *   at some reference site of the grammar; otherwise it is rejected at build time (sections 2.2 and
