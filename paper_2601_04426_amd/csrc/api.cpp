@@ -1027,6 +1027,9 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
             std::vector<uint8_t> is_near_base(cache->planes.size(), 0);
             for (const PlaneInfo& pi : cache->planes) if (pi.near_plane >= 0) is_near_base[(size_t)pi.near_plane] = 1;
             auto plain = [&](const RuleFsm& f, int x) { return f.redges[(size_t)x].empty() && !f.bedges[(size_t)x].empty(); };
+            struct FirstByteAlike { std::array<uint32_t, 8> same; bool worth; };
+            std::vector<FirstByteAlike> fb_memo;
+            std::vector<std::vector<int32_t>> fb_of((size_t)R);      // per rule and state: index into fb_memo, or -1
             for (size_t idx = 0; idx < cache->planes.size(); ++idx) {
                 PlaneInfo& pi = cache->planes[idx];
                 if (pi.near_plane >= 0 || is_near_base[idx]) continue;
@@ -1035,23 +1038,32 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
                 // (a state that can end its rule brings the continuation of the referencing rule into its start set: the
                 // same one for both states if both can end, none if neither can)
                 if (x == b0 || !plain(f, x) || !plain(f, b0) || f.is_final[(size_t)x] != f.is_final[(size_t)b0]) continue;
+                // the comparison depends on the state only, not on the site: done once per state
+                std::vector<int32_t>& of = fb_of[(size_t)pi.rule];
+                if (of.empty()) of.assign((size_t)f.n_states(), -1);
+                if (of[(size_t)x] < 0) {
+                    int32_t tx[256], ty[256];
+                    std::fill(tx, tx + 256, -1); std::fill(ty, ty + 256, -1);
+                    for (auto& e : f.bedges[(size_t)x]) for (int b = e.lo; b <= e.hi; ++b) tx[b] = rep[(size_t)pi.rule][(size_t)e.tgt];
+                    for (auto& e : f.bedges[(size_t)b0]) for (int b = e.lo; b <= e.hi; ++b) ty[b] = rep[(size_t)pi.rule][(size_t)e.tgt];
+                    uint64_t differ = 0, all = 0;
+                    FirstByteAlike fa{};
+                    for (int b = 0; b < 256; ++b) {
+                        const uint64_t n_b = V.fb_start[b + 1] - V.fb_start[b];
+                        if (tx[b] == ty[b]) fa.same[(size_t)b >> 5] |= 1u << (b & 31);
+                        else if (tx[b] >= 0) differ += n_b;
+                        if (tx[b] >= 0) all += n_b;
+                    }
+                    fa.worth = differ * 2 <= all;                    // else too little to gain
+                    of[(size_t)x] = (int32_t)fb_memo.size();
+                    fb_memo.push_back(fa);
+                }
+                const FirstByteAlike* memo = &fb_memo[(size_t)of[(size_t)x]];
+                if (!memo->worth) continue;
                 auto lp = local_plane.find(make_key(pi.rule, b0, pi.parent_rule, pi.parent_state));
                 if (lp == local_plane.end() || cache->planes[(size_t)lp->second].near_plane >= 0) continue;
-                int32_t tx[256], ty[256];
-                std::fill(tx, tx + 256, -1); std::fill(ty, ty + 256, -1);
-                for (auto& e : f.bedges[(size_t)x]) for (int b = e.lo; b <= e.hi; ++b) tx[b] = rep[(size_t)pi.rule][(size_t)e.tgt];
-                for (auto& e : f.bedges[(size_t)b0]) for (int b = e.lo; b <= e.hi; ++b) ty[b] = rep[(size_t)pi.rule][(size_t)e.tgt];
-                uint64_t differ = 0, all = 0;
-                std::array<uint32_t, 8> same{};
-                for (int b = 0; b < 256; ++b) {
-                    const uint64_t n_b = V.fb_start[b + 1] - V.fb_start[b];
-                    if (tx[b] == ty[b]) same[(size_t)b >> 5] |= 1u << (b & 31);
-                    else if (tx[b] >= 0) differ += n_b;
-                    if (tx[b] >= 0) all += n_b;
-                }
-                if (differ * 2 > all) continue;                      // too little to gain
                 pi.fb_plane = lp->second;
-                pi.fb_same = same;
+                pi.fb_same = memo->same;
             }
         }
 
