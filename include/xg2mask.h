@@ -64,7 +64,8 @@ typedef struct xg2_matcher xg2_matcher;
  *   most d bytes: such a plane is checked for its longer tokens only and takes the others from the
  *   plane it agrees with.  Likewise a plain automaton state that moves like its rule's start state
  *   on most first bytes (the states of a dispatch automaton) is checked only for the tokens with
- *   the other first bytes.  The planes are the same with or without the option.
+ *   the other first bytes, and the planes of one state under several referencing sites share the
+ *   tokens that cannot leave the rule.  The planes are the same with or without the option.
  * follow_filter (default 1): a token that leaves the plane's (outermost) rule before its last byte
  *   stays uncertain only if the rest of the token is a viable prefix of what can follow that rule
  *   at some reference site of the grammar; otherwise it is rejected at build time (sections 2.2 and

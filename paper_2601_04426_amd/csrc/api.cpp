@@ -157,6 +157,32 @@ struct VocabImpl {
     std::vector<uint32_t> long_rank, long_off;
     DevBuf<uint32_t> d_long_rank, d_short_mask;
     DevBuf<uint8_t> d_first_byte;               // first byte of every token id (0 for the empty ones), W * 32 entries
+    // per byte set asked for so far: the sorted ranks of the tokens that contain a byte of the set (ascending, appended
+    // to long_rank) and, on the device, the mask in token ids of the checkable tokens that contain none
+    struct ByteSetList { std::array<uint32_t, 8> bytes; uint32_t off, n; std::unique_ptr<DevBuf<uint32_t>> d_without; };
+    std::vector<ByteSetList> byte_lists;
+    // The caller serialises (the mutex of the large-capacity scratch) and no kernel is in flight on the lists.
+    int32_t list_of_tokens_with(const std::array<uint32_t, 8>& bytes) {
+        for (size_t k = 0; k < byte_lists.size(); ++k) if (byte_lists[k].bytes == bytes) return (int32_t)k;
+        ByteSetList bl;
+        bl.bytes = bytes;
+        bl.off = (uint32_t)long_rank.size();
+        std::vector<uint32_t> without(W, 0u);
+        for (uint32_t r = 0; r < n_sorted; ++r) {
+            bool has = false;
+            for (uint32_t k = s_off[r]; k < s_off[r + 1] && !has; ++k) has = (bytes[s_bytes[k] >> 5] >> (s_bytes[k] & 31)) & 1u;
+            if (has) long_rank.push_back(r);
+            else without[perm[r] >> 5] |= 1u << (perm[r] & 31);
+        }
+        bl.n = (uint32_t)long_rank.size() - bl.off;
+        bl.d_without.reset(new DevBuf<uint32_t>());
+        bl.d_without->upload(without, nullptr);
+        d_long_rank.upload(long_rank, nullptr);
+        HIP_CHECK(hipStreamSynchronize(nullptr));
+        dv.long_rank = d_long_rank.p;
+        byte_lists.push_back(std::move(bl));
+        return (int32_t)byte_lists.size() - 1;
+    }
 
     const uint8_t* tok(int32_t id) const { return bytes.data() + offs[(size_t)id]; }
     size_t len(int32_t id) const { return (size_t)(offs[(size_t)id + 1] - offs[(size_t)id]); }
@@ -330,6 +356,7 @@ struct PlaneInfo {
     int32_t near_plane = -1, near_depth = 0;                // a plane with the same classes for every token of at most near_depth bytes
     int32_t fb_plane = -1;                                  // a plane with the same classes for every token whose first byte is in fb_same
     std::array<uint32_t, 8> fb_same{};
+    int32_t site_plane = -1, site_list = -1;                // the same state under another site: same classes for every token outside that list
 };
 struct BuildResult {
     int64_t built = 0, executed = 0, slow = 0, n_accepted = 0, n_uncertain = 0;
@@ -557,6 +584,21 @@ int32_t build_planes(CacheImpl& cache, const std::vector<int32_t>& todo, hipStre
                 by_first_byte = true;
             }
         }
+        // or every token that cannot leave the plain states of the rule from the plane of the same state under another site
+        const VocabImpl::ByteSetList* by_list = nullptr;
+        if (!near_d && !by_first_byte && pi.site_plane >= 0) {
+            const uint32_t* src = cache.planes[(size_t)pi.site_plane].row;
+            if (!src) {
+                auto pr = pool.rows.find(cache.planes[(size_t)pi.site_plane].key);
+                auto bi = building.find(pi.site_plane);
+                if (bi != building.end()) src = build_rows[bi->second];
+                else if (pr != pool.rows.end() && pr->second) src = pr->second;
+            }
+            if (src) {
+                by_list = &V.byte_lists[(size_t)pi.site_list];
+                copies.push_back({build_rows[k], src, by_list->d_without->p, 0});
+            }
+        }
         if (pi.waiter_sid < 0) chart.start(pi.sid);
         else chart.start_pair(pi.sid, (uint32_t)pi.waiter_sid);
         const std::vector<ChartSet>& sets = chart.sets();
@@ -586,9 +628,9 @@ int32_t build_planes(CacheImpl& cache, const std::vector<int32_t>& todo, hipStre
             int e = b;
             while (live[e + 1]) ++e;
             uint32_t lo = V.fb_start[b], hi = V.fb_start[e + 1], listed = 0;
-            if (near_d) {                                            // the same ranks, in the list of the tokens longer than near_d
-                const uint32_t* first = V.long_rank.data() + V.long_off[near_d];
-                const uint32_t* last = V.long_rank.data() + V.long_off[near_d + 1];
+            if (near_d || by_list) {                                 // the same ranks, in the list of the tokens longer than near_d / with such bytes
+                const uint32_t* first = V.long_rank.data() + (near_d ? V.long_off[near_d] : by_list->off);
+                const uint32_t* last = V.long_rank.data() + (near_d ? V.long_off[near_d + 1] : by_list->off + by_list->n);
                 lo = (uint32_t)(std::lower_bound(first, last, lo) - V.long_rank.data());
                 hi = (uint32_t)(std::lower_bound(first, last, hi) - V.long_rank.data());
                 listed = kChunkListed;
@@ -1064,6 +1106,50 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
                 if (lp == local_plane.end() || cache->planes[(size_t)lp->second].near_plane >= 0) continue;
                 pi.fb_plane = lp->second;
                 pi.fb_same = memo->same;
+            }
+        }
+
+        // The planes of one state under different referencing sites: as long as a token stays among the plain states of the
+        // rule that cannot end it, the site plays no part.  Only the tokens that contain a byte on which some such state
+        // (reachable from the plane's state) predicts or ends the rule are checked for every site; for the rest the plane of
+        // the first site serves all.
+        if (merge && depth == 2) {
+            std::vector<uint8_t> is_base(cache->planes.size(), 0);
+            for (const PlaneInfo& pi : cache->planes) {
+                if (pi.near_plane >= 0) is_base[(size_t)pi.near_plane] = 1;
+                if (pi.fb_plane >= 0) is_base[(size_t)pi.fb_plane] = 1;
+            }
+            std::map<std::pair<int32_t, int32_t>, std::vector<int32_t>> groups;      // (rule, state) -> planes with a site
+            for (size_t idx = 0; idx < cache->planes.size(); ++idx) {
+                const PlaneInfo& pi = cache->planes[idx];
+                if (pi.parent_rule < 0 || pi.near_plane >= 0 || pi.fb_plane >= 0 || is_base[idx]) continue;
+                const RuleFsm& f = g.rules[(size_t)pi.rule];
+                if (!f.redges[(size_t)pi.state].empty() || f.is_final[(size_t)pi.state] || f.bedges[(size_t)pi.state].empty()) continue;
+                groups[std::make_pair(pi.rule, pi.state)].push_back((int32_t)idx);
+            }
+            for (auto& kv : groups) {
+                if (kv.second.size() < 2) continue;
+                const RuleFsm& f = g.rules[(size_t)kv.first.first];
+                // plain states that cannot end the rule, reachable from the state; bytes that lead out of them
+                std::array<uint32_t, 8> out{};
+                std::vector<uint8_t> seen((size_t)f.n_states(), 0);
+                std::vector<int> stack{kv.first.second};
+                seen[(size_t)kv.first.second] = 1;
+                while (!stack.empty()) {
+                    const int q = stack.back(); stack.pop_back();
+                    for (auto& e : f.bedges[(size_t)q]) {
+                        const bool inside = f.redges[(size_t)e.tgt].empty() && !f.is_final[(size_t)e.tgt];
+                        if (!inside) { for (int b = e.lo; b <= e.hi; ++b) out[(size_t)b >> 5] |= 1u << (b & 31); }
+                        else if (!seen[(size_t)e.tgt]) { seen[(size_t)e.tgt] = 1; stack.push_back(e.tgt); }
+                    }
+                }
+                const int32_t list = V.list_of_tokens_with(out);
+                if ((uint64_t)V.byte_lists[(size_t)list].n * 2 > cache->planes[(size_t)kv.second[0]].cost) continue;   // too little to gain
+                for (size_t k = 1; k < kv.second.size(); ++k) {
+                    PlaneInfo& pi = cache->planes[(size_t)kv.second[k]];
+                    pi.site_plane = kv.second[0];
+                    pi.site_list = list;
+                }
             }
         }
 
