@@ -28,14 +28,14 @@ HBM_PEAK_GBS = 8000.0
 # valid only for the kernel sources they were taken with.  The same counters read 303,884 KiB (FETCH_SIZE) and
 # 607,744 KiB (WRITE_SIZE) for a device-to-device copy of 607,744 KiB, hence the scale factors.
 PMC = {
-    "sources_sha256": "d2628ea11267b2feb0c9f823aec49f668457ddc723c84d71e407ac299dae7b81",
+    "sources_sha256": "4082be428ec9ccc861382e0ba1bc6d14f8e4c37f54989ef74cc07c77d6de7059",
     "fetch_scale": 2.0, "write_scale": 1.0,
-    "k_build": (10824.8, 3374.7),
-    "k_fill_or": (4110.9, 19164.9),
-    "k_apply_vec<8>": (98622.6, 303872.0),
+    "k_build": (10924.6, 3374.7),
+    "k_fill_or": (4115.9, 19165.4),
+    "k_apply_vec<8>": (98619.5, 303872.0),
     # wave instructions of one k_build launch (rocprofv3 --pmc SQ_INSTS_VALU + SALU + BRANCH + LDS + VMEM_RD + VMEM_WR + SMEM)
-    "k_build_wave_instructions": 32547950.0,
-    "k_apply_vec<4>": (182228.5, 605511.0),
+    "k_build_wave_instructions": 32699167.0,
+    "k_apply_vec<4>": (182232.7, 605511.0),
 }
 KERNEL_SOURCES = ("csrc/kernels.hip", "csrc/earley_core.hpp", "csrc/device.hpp", "build.py")   # code and compiler flags
 

@@ -622,6 +622,36 @@ int32_t build_planes(CacheImpl& cache, const std::vector<int32_t>& todo, hipStre
             for (const ChartItem& it : cs.wait) chart.push_triples(it, loc(it.origin), ctx_wait);
         }
         ctx_wait_off.push_back((uint32_t)(ctx_wait.size() / 2));
+        // A start set of at most two items that scan, none of them predicting, where the end of a waited-for instance
+        // leads to one state of the outermost instance that does not predict either, is walked as a few automaton
+        // threads; the two items and what each one's end leads to follow the plane's items.
+        uint32_t threads = 0;
+        if (heavy) {
+            uint32_t desc[4] = {kNoThread, 0u, kNoThread, 0u};
+            uint32_t nb = 0;
+            bool ok = true;
+            for (size_t q = item0; q < item0 + plane_ctx.back().y && ok; ++q) {
+                const uint32_t it = ctx_items[q];
+                if (!(it & kHasByte)) continue;
+                if ((it & kHasRef) || nb == 2) { ok = false; break; }
+                uint32_t lead = 0;
+                const uint32_t origin = it >> kRefBits;
+                if (origin != kRootOrigin) {
+                    const uint32_t rule = ft.state_info[it & kSidMask].rule_final & 0x7FFFFFFFu;
+                    const uint32_t w0 = ctx_wait_off[plane_ctx.back().z + origin], w1 = ctx_wait_off[plane_ctx.back().z + origin + 1];
+                    uint32_t n_lead = 0;
+                    for (uint32_t w = w0; w < w1; ++w)
+                        if (ctx_wait[2 * (size_t)w] == rule) { ++n_lead; lead = ctx_wait[2 * (size_t)w + 1]; }
+                    ok = n_lead == 1 && !(lead & kHasRef) && (lead >> kRefBits) == kRootOrigin;
+                }
+                desc[2 * nb] = it; desc[2 * nb + 1] = lead;
+                ++nb;
+            }
+            if (ok && nb) {
+                ctx_items.insert(ctx_items.end(), desc, desc + 4);
+                threads = kChunkThreads;
+            }
+        }
         if (by_first_byte) for (int b = 0; b < 256; ++b) if ((pi.fb_same[(size_t)b >> 5] >> (b & 31)) & 1u) live[b] = false;
         for (int b = 0; b < 256;) {
             if (!live[b]) { ++b; continue; }
@@ -635,7 +665,7 @@ int32_t build_planes(CacheImpl& cache, const std::vector<int32_t>& todo, hipStre
                 hi = (uint32_t)(std::lower_bound(first, last, hi) - V.long_rank.data());
                 listed = kChunkListed;
             }
-            if (lo < hi) ranges.push_back(make_uint4((uint32_t)k, lo, hi, listed | (heavy ? kChunkHeavy : 0u)));
+            if (lo < hi) ranges.push_back(make_uint4((uint32_t)k, lo, hi, listed | threads | (heavy ? kChunkHeavy : 0u)));
             executed += hi - lo;
             b = e + 1;
         }

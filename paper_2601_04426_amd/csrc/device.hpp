@@ -35,7 +35,10 @@ struct DevVocab {                        // byte-sorted vocabulary in HBM
 // its long tokens checked).  The workgroups of a persistent grid take chunks round-robin.  plane_ctx[k] = {first item, number of items, first wait offset, H} describes the closed start
 // set of plane k as a scan context (H = 1: the position alone; H = 2: the position inside one level of
 // referencing rule).  ctx_wait holds, set after set, what the waiting items wait for as pairs
-// {rule, state reference of the target | origin << 21}; ctx_wait_off counts pairs.
+// {rule, state reference of the target | origin << 21}; ctx_wait_off counts pairs.  With bit 2 of chunk[c].w set,
+// four more words follow the plane's items in ctx_items: {item a, lead a, item b or kNoThread, lead b}, the start
+// set's one or two scanning items and, for an item of a waited-for instance, the item of the outermost instance
+// that its end leads to (the only wait entry of its rule; neither predicts) — the kernel walks these as threads.
 #ifndef XG2_BUILD_CHUNK
 #define XG2_BUILD_CHUNK 128
 #endif
@@ -62,7 +65,8 @@ constexpr uint32_t kSlowK = 256, kSlowWM = 1024, kSlowMaxLen = 1024;
 constexpr uint32_t kSlowSearchBudget = 1u << 20;     // list entries one token may compare against in the device-memory lists
 constexpr uint32_t kSlowSlots = 2 * kSlowK + 2 * kSlowWM + kSlowMaxLen + 1;
 
-constexpr uint32_t kChunkListed = 1u, kChunkHeavy = 2u;      // bits of chunk[c].w
+constexpr uint32_t kChunkListed = 1u, kChunkHeavy = 2u, kChunkThreads = 4u;   // bits of chunk[c].w
+constexpr uint32_t kNoThread = 0xFFFFFFFFu;                  // an empty slot of the thread walk (what the transition table holds for "no edge")
 
 // dst gets, for the tokens in mask (token ids, W words), the bits src holds: both rows of a plane at once
 // (accepted at [0, W), uncertain at [W, 2 W)).  The mask bits of dst must be clear before.

@@ -125,13 +125,15 @@ __device__ __forceinline__ void store_class(const BuildPlan& P, uint32_t p, uint
 // A persistent grid of single-wave workgroups: workgroup g handles chunks g, g + grid, g + 2 grid, ...
 // (sorted ranks of one plane each; the host puts the long ones first), each in phases, so that the long
 // divergent steps of the recogniser run on full waves instead of on the few lanes that need them.
-// Phase 1 (only when the plane's start set is a single item without rule edges): every lane
-// walks its token through the automaton, one table load per byte.  A token that dies is rejected, one that
-// reaches its end is accepted; one that reaches a state which predicts, or which completes a rule instance
-// that a parent waits for, goes on the deferred list, and so does one that dies after the outermost instance
-// could have ended (phase 2 then decides between uncertain and rejected).  Phase 2: the deferred tokens (for the other planes: all tokens of the chunk), 64 at a time,
-// through the Earley recogniser.  Tokens that leave the outermost rule early and then die need the second,
-// follow-language run; they are collected across chunks as (plane, rank) pairs and run 64 at a time too.
+// Phase 1 (when the plane's start set is a single item without rule edges, or one or two such items whose
+// ends lead back into the outermost instance): every lane walks its token through the automaton, one table
+// load per byte and thread.  A token that dies is rejected, one that reaches its end is accepted; one that
+// reaches a state which predicts, or which completes a rule instance in a way the walk does not follow, goes
+// on the deferred list.  One that dies after the outermost instance could have ended is what the plain run
+// would call "left early": it goes straight to the follow-language run (or is stored as uncertain when that
+// run is switched off).  Phase 2: the deferred tokens (for the other planes: all tokens of the chunk), 64 at
+// a time, through the Earley recogniser.  Tokens that leave the outermost rule early and then die need the
+// second, follow-language run; they are collected across chunks as (plane, rank) pairs and run 64 at a time too.
 __device__ __forceinline__ void follow_batch(const DevTables& T, const DevVocab& Vd, const BuildPlan& P, const SlowScratch& S,
                                              const uint32_t* cls_words, const uint32_t* f_plane, const uint32_t* f_rank,
                                              uint32_t first, uint32_t count, uint32_t lane, BuildStore& st) {
@@ -170,7 +172,30 @@ __global__ __launch_bounds__(64) void k_build(DevTables T, DevVocab Vd, BuildPla
         const bool walkable = C.n_items == 1 && (item0 & (F_BYTE | F_REF)) == F_BYTE;
         const bool root_instance = (item0 >> REF_BITS) == ROOT_ORIGIN;   // the start item is the plane's outermost rule instance
         const bool listed = chunk.w & kChunkListed;                 // ranks come from a list of long tokens
+        const bool threaded = chunk.w & kChunkThreads;              // two thread descriptors follow the plane's items
         uint32_t n_work = chunk.z - chunk.y;
+        // a token that left the outermost rule early and died: queued for the follow-language run, which starts
+        // when 64 of them are there (`again` differs between lanes; everything else here is the same in all)
+        auto queue_follow = [&](bool again, uint32_t rank) {
+            const unsigned long long m = __ballot(again);
+            if (!m) return;
+            if (again) {
+                const uint32_t at = n_follow + (uint32_t)__popcll(m & ((1ull << lane) - 1));
+                f_plane[at] = p; f_rank[at] = rank;
+            }
+            n_follow += (uint32_t)__popcll(m);
+            __syncthreads();
+            if (n_follow >= 64) {
+                n_follow -= 64;
+                follow_batch(T, Vd, P, S, cls_words, f_plane, f_rank, n_follow, 64, lane, st);
+                __syncthreads();
+            }
+        };
+        // what phase 1 does with such a token: the plain run would end dead with the early mark, so it is not made
+        auto died_early = [&](bool yes, uint32_t rank) {
+            if (yes && !P.follow_filter) { store_class(P, p, Vd.W, Vd.perm[rank], RES_EARLY); yes = false; }
+            queue_follow(yes, rank);
+        };
         if (walkable) {
             n_work = 0;
             for (uint32_t rank0 = chunk.y; rank0 < chunk.z; rank0 += 64) {
@@ -183,7 +208,7 @@ __global__ __launch_bounds__(64) void k_build(DevTables T, DevVocab Vd, BuildPla
                     n = (int)(Vd.off[rank + 1] - Vd.off[rank]); tv = Vd.tok16[rank];
                 }
                 if (n > BuildStore::MAXLEN) { defer = true; n = 0; }   // phase 2 hands it to the large-capacity kernel
-                bool walking = n > 0, early = false;
+                bool walking = n > 0, early = false, dead_early = false;
                 uint32_t sid = item0 & SID_MASK;
                 const uint32_t words[4] = {tv.x, tv.y, tv.z, tv.w};
 #pragma unroll
@@ -193,7 +218,7 @@ __global__ __launch_bounds__(64) void k_build(DevTables T, DevVocab Vd, BuildPla
                         if (walking && wi * 4 + j < n) {
                             const uint32_t b = (words[wi] >> (8 * j)) & 0xFF;
                             const uint32_t tgt = T.trans[sid * T.n_classes + cls_bytes[b]];
-                            if (tgt == NO_TARGET) { walking = false; defer = early; }              // dead: rejected, unless the rule could end on the way
+                            if (tgt == NO_TARGET) { walking = false; dead_early = early; }         // dead: rejected, unless the rule could end on the way
                             else if ((tgt & F_REF) || ((tgt & F_FINAL) && !root_instance)) { walking = false; defer = true; }   // predicts, or completes into a parent
                             else {                                   // the root instance may end here: that only matters if the token dies later
                                 sid = tgt & SID_MASK;
@@ -204,6 +229,72 @@ __global__ __launch_bounds__(64) void k_build(DevTables T, DevVocab Vd, BuildPla
                     if (!__any(walking && (wi + 1) * 4 < n)) break;
                 }
                 if (walking) store_class(P, p, Vd.W, Vd.perm[rank], RES_ALIVE);                  // reached its end alive
+                died_early(dead_early, rank);
+                const unsigned long long m = __ballot(defer);
+                if (defer) deferred[n_work + (uint32_t)__popcll(m & ((1ull << lane) - 1))] = rank;
+                n_work += (uint32_t)__popcll(m);
+            }
+            __syncthreads();
+        } else if (threaded) {
+            // Phase 1 for a start set of one or two scanning items that do not predict: each item is an automaton
+            // thread; a thread of a waited-for instance that reaches a final state starts one thread of the outermost
+            // instance at the state the host has looked up.  Three slots; anything else (a state that predicts, a
+            // fourth thread) goes to phase 2.
+            const uint32_t* d = C.items + C.n_items;
+            const uint32_t it_a = d[0], lead_a = d[1], it_b = d[2], lead_b = d[3];
+            n_work = 0;
+            for (uint32_t rank0 = chunk.y; rank0 < chunk.z; rank0 += 64) {
+                uint32_t rank = rank0 + lane;
+                bool defer = false;
+                int n = 0;
+                RegBytes tok;
+                tok.v = make_uint4(0, 0, 0, 0);
+                if (rank < chunk.z) {
+                    if (listed) rank = Vd.long_rank[rank];
+                    n = (int)(Vd.off[rank + 1] - Vd.off[rank]); tok.v = Vd.tok16[rank];
+                }
+                if (n > BuildStore::MAXLEN) { defer = true; n = 0; }
+                uint32_t s0 = n > 0 ? it_a : kNoThread, s1 = n > 0 ? it_b : kNoThread, s2 = kNoThread;
+                bool early = false;
+                for (int i = 0; __any(i < n && !defer && (s0 & s1 & s2) != kNoThread); ++i) {
+                    if (i < n && !defer && (s0 & s1 & s2) != kNoThread) {
+                        const uint32_t cls = cls_bytes[tok.next()];
+                        const bool more = i + 1 < n;
+                        uint32_t start_a = kNoThread, start_b = kNoThread;
+                        auto step = [&](uint32_t& s, uint32_t lead, uint32_t& start) {
+                            if (s == kNoThread) return;
+                            const uint32_t tgt = T.trans[(s & SID_MASK) * T.n_classes + cls];
+                            if (tgt == NO_TARGET) { s = kNoThread; return; }
+                            if (tgt & F_REF) { defer = true; return; }
+                            s = tgt | (s & ~REF_MASK);
+                            if (tgt & F_FINAL) {
+                                if ((s >> REF_BITS) == ROOT_ORIGIN) early |= more;
+                                else start = lead;
+                            }
+                        };
+                        uint32_t none = kNoThread;
+                        step(s0, lead_a, start_a);
+                        step(s1, lead_b, start_b);
+                        step(s2, 0u, none);                          // only threads of the outermost instance get here
+                        auto begin = [&](uint32_t item) {
+                            if (item == kNoThread) return;
+                            if (item & F_FINAL) early |= more;
+                            if (item == s0 || item == s1 || item == s2) return;
+                            if (s2 == kNoThread) s2 = item;
+                            else if (s1 == kNoThread) s1 = item;
+                            else if (s0 == kNoThread) s0 = item;
+                            else defer = true;
+                        };
+                        begin(start_a);
+                        begin(start_b);
+                    }
+                }
+                bool dead_early = false;
+                if (n > 0 && !defer) {
+                    if ((s0 & s1 & s2) != kNoThread) store_class(P, p, Vd.W, Vd.perm[rank], RES_ALIVE);
+                    else dead_early = early;
+                }
+                died_early(dead_early, rank);
                 const unsigned long long m = __ballot(defer);
                 if (defer) deferred[n_work + (uint32_t)__popcll(m & ((1ull << lane) - 1))] = rank;
                 n_work += (uint32_t)__popcll(m);
@@ -215,7 +306,7 @@ __global__ __launch_bounds__(64) void k_build(DevTables T, DevVocab Vd, BuildPla
             bool again = false;
             uint32_t rank = 0;
             if (idx < n_work) {
-                rank = walkable ? deferred[idx] : listed ? Vd.long_rank[chunk.y + idx] : chunk.y + idx;
+                rank = (walkable || threaded) ? deferred[idx] : listed ? Vd.long_rank[chunk.y + idx] : chunk.y + idx;
                 const int n = (int)(Vd.off[rank + 1] - Vd.off[rank]);
                 RegBytes tok;
                 tok.v = Vd.tok16[rank];
@@ -226,20 +317,7 @@ __global__ __launch_bounds__(64) void k_build(DevTables T, DevVocab Vd, BuildPla
                 if (res & RES_OVERFLOW) push_overflow(S, p, rank);
                 else if (!again) store_class(P, p, Vd.W, Vd.perm[rank], res);
             }
-            const unsigned long long m = __ballot(again);
-            if (m) {
-                if (again) {
-                    const uint32_t at = n_follow + (uint32_t)__popcll(m & ((1ull << lane) - 1));
-                    f_plane[at] = p; f_rank[at] = rank;
-                }
-                n_follow += (uint32_t)__popcll(m);
-                __syncthreads();
-                if (n_follow >= 64) {
-                    n_follow -= 64;
-                    follow_batch(T, Vd, P, S, cls_words, f_plane, f_rank, n_follow, 64, lane, st);
-                    __syncthreads();
-                }
-            }
+            queue_follow(again, rank);
         }
     }
     __syncthreads();

@@ -458,6 +458,50 @@ def test_tricky_grammars_planes_and_masks(xg, case, depth, follow):
         assert m.accept_token(0) and m.is_terminated()
 
 
+def test_nullable_and_final_rule_instances_under_sites(xg):
+    """Planes whose start set is a rule instance under a referencing site plus the state the site continues in
+    (whitespace that may be empty, a number that may end after any digit): the build walks these as a few automaton
+    threads instead of Earley steps.  Sites that continue in a plain state, in a final state of the root, and in a
+    state that predicts (which the walk must hand on); with and without the follow filter; every plane and the masks
+    along a walk equal to the oracle's."""
+    import itertools
+    import torch
+    alphabet = b' 1.,[]x'
+    rng = random.Random(77)
+    toks = [b""] + [bytes(t) for n in (1, 2, 3) for t in itertools.product(alphabet, repeat=n)]
+    toks += sorted({bytes(rng.choice(b'  11.,]x') for _ in range(rng.randrange(4, 17))) for _ in range(600)} - set(toks))
+    grammars = [
+        'root ::= "[" ws num ws ("," ws num ws)* "]" ws\nws ::= [ ]*\nnum ::= [1]+ ("." [1]+)?',
+        'root ::= item ws | "[" ws item ws "]"\nitem ::= num | "x" ws num\nws ::= [ ]*\nnum ::= [1]+ ("." [1]+)?',
+        'root ::= "[" pair ("," pair){0,3} "]"\npair ::= ws num ws "x"? ws\nws ::= [ ]*\nnum ::= [1]+',
+    ]
+    vocab = xg.Vocab(toks, 0, [0])
+    va = oracle.VocabArrays(toks, 0, [0])
+
+    class Cfg:
+        class vocab:
+            tokens = toks
+    bm = torch.full((1, vocab.words), -1, dtype=torch.int32, device="cuda:0")
+    for ebnf in grammars:
+        for follow in (True, False):
+            cache, orc = check_planes(xg, Cfg, vocab, va, ebnf, "root", follow=follow, max_contexts=100000)
+        m = xg.Matcher(cache)
+        hist = b""
+        for step in range(10):
+            xg.fill_next_token_bitmask([m], bm.data_ptr(), vocab.words, _stream())
+            torch.cuda.synchronize()
+            assert not xg.fill_last_status()[1]
+            want = orc.mask(hist, va)
+            got = bm.cpu().numpy()[0]
+            assert np.array_equal(got, oracle.pack_bitmask(want)), (ebnf, hist, diff_words(got, oracle.pack_bitmask(want), toks))
+            allowed = [t for t in np.nonzero(want)[0] if t != 0]
+            if not allowed:
+                break
+            t = int(rng.choice(allowed))
+            assert m.accept_token(t)
+            hist += toks[t]
+
+
 def test_near_bound_repetition_planes_full_jit_and_pool(xg):
     """Section 3.6: the states of a bounded repetition within one token length of the bound.  Their planes take the
     short tokens from the plane of the inner states and check only the long ones.  Built all at once, built just in time
