@@ -30,12 +30,12 @@ HBM_PEAK_GBS = 8000.0
 PMC = {
     "sources_sha256": "4082be428ec9ccc861382e0ba1bc6d14f8e4c37f54989ef74cc07c77d6de7059",
     "fetch_scale": 2.0, "write_scale": 1.0,
-    "k_build": (10924.6, 3374.7),
-    "k_fill_or": (4115.9, 19165.4),
-    "k_apply_vec<8>": (98619.5, 303872.0),
+    "k_build": (10924.8, 3374.7),
+    "k_fill_or": (4114.0, 19167.8),
+    "k_apply_vec<8>": (98619.9, 303872.0),
     # wave instructions of one k_build launch (rocprofv3 --pmc SQ_INSTS_VALU + SALU + BRANCH + LDS + VMEM_RD + VMEM_WR + SMEM)
     "k_build_wave_instructions": 32699167.0,
-    "k_apply_vec<4>": (182232.7, 605511.0),
+    "k_apply_vec<4>": (182233.6, 605511.0),
 }
 KERNEL_SOURCES = ("csrc/kernels.hip", "csrc/earley_core.hpp", "csrc/device.hpp", "build.py")   # code and compiler flags
 

@@ -311,9 +311,12 @@ struct PoolImpl {
         free_rows.push_back(row);
         --n_rows;
     }
-    uint32_t* alloc_row(size_t row_bytes, hipStream_t stream) {
+    // rows_ahead: how many rows the caller is about to ask for, this one included (sizes a new slab: what is
+    // allocated is zeroed on the stream at once, so a small build should not pay for a large slab)
+    uint32_t* alloc_row(size_t row_bytes, hipStream_t stream, size_t rows_ahead = 1) {
         if (free_rows.empty() && slab_left < row_bytes) {
-            size_t want = std::max<size_t>(row_bytes * 64, (size_t)64 << 20);
+            size_t want = std::min<size_t>(std::max<size_t>({row_bytes * 64, (size_t)8 << 20, rows_ahead * row_bytes}), (size_t)256 << 20);
+            want = std::max(want, row_bytes);
             if (max_bytes && device_bytes + want > max_bytes) want = row_bytes * 16;
             if (max_bytes && device_bytes + want > max_bytes) want = row_bytes;
             if (max_bytes && device_bytes + want > max_bytes) {
@@ -530,12 +533,13 @@ int32_t build_planes(CacheImpl& cache, const std::vector<int32_t>& todo, hipStre
     const size_t row_bytes = (size_t)V.W * 2 * sizeof(uint32_t);
     std::vector<int32_t> build;                                 // plane indices to class now
     std::vector<uint32_t*> build_rows;
-    for (int32_t k : todo) {
+    for (size_t i = 0; i < todo.size(); ++i) {
+        const int32_t k = todo[i];
         PlaneInfo& pi = cache.planes[(size_t)k];
         if (pi.row) continue;
         uint32_t*& row = pool.rows[pi.key];
         if (row) { pi.row = row; pi.no_uncertain = pool.no_uncertain.count(row) != 0; pool.take(row, pi.key); ++cache.n_built; continue; }   // another grammar built it
-        row = pool.alloc_row(row_bytes, stream);
+        row = pool.alloc_row(row_bytes, stream, todo.size() - i);
         build.push_back(k);
         build_rows.push_back(row);
     }
