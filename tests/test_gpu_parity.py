@@ -610,7 +610,7 @@ def random_grammar(rng, counting=False):
     return "".join("%s ::= %s\n" % (nm, alt(i, 0)) for i, nm in enumerate(names))
 
 
-def run_random_grammars(xg, seed, wanted, counting=False):
+def run_random_grammars(xg, seed, wanted, counting=False, follow=True):
     """Seeded random grammars over a vocabulary of every string of up to three letters of a-e plus longer samples:
     every plane equal to the oracle's classes (depth 2, merged, follow filter), masks along a random walk equal too."""
     import itertools
@@ -635,7 +635,7 @@ def run_random_grammars(xg, seed, wanted, counting=False):
         if len(probe.positions()) > 600:
             continue                                                # keeps the oracle's share of the test to seconds
         try:
-            cache, orc = check_planes(xg, Cfg, vocab, va, ebnf, "root", max_contexts=100000)
+            cache, orc = check_planes(xg, Cfg, vocab, va, ebnf, "root", follow=follow, max_contexts=100000)
         except xg.Xg2Error as e:
             assert e.code == -4, ebnf                               # XG2_EOVERFLOW: item sets beyond the documented capacity
             skipped += 1                                            # (highly ambiguous grammars); nothing partial is returned
@@ -663,6 +663,12 @@ def run_random_grammars(xg, seed, wanted, counting=False):
 
 def test_random_grammars_planes_and_masks(xg):
     assert run_random_grammars(xg, seed=31337, wanted=40) == 40
+
+
+def test_random_grammars_without_follow_filter(xg):
+    """The same with the follow filter off: a token that leaves the outermost rule and dies is uncertain whatever
+    follows, and the build stores that without a second run."""
+    assert run_random_grammars(xg, seed=161803, wanted=20, follow=False) == 20
 
 
 def test_random_counting_grammars_planes_and_masks(xg):
