@@ -469,7 +469,7 @@ def test_nullable_and_final_rule_instances_under_sites(xg):
     alphabet = b' 1.,[]x'
     rng = random.Random(77)
     toks = [b""] + [bytes(t) for n in (1, 2, 3) for t in itertools.product(alphabet, repeat=n)]
-    toks += sorted({bytes(rng.choice(b'  11.,]x') for _ in range(rng.randrange(4, 17))) for _ in range(600)} - set(toks))
+    toks += sorted({bytes(rng.choice(b'  11.,]x') for _ in range(rng.randrange(4, 25))) for _ in range(600)} - set(toks))   # some beyond the 16 bytes of the fast path
     grammars = [
         'root ::= "[" ws num ws ("," ws num ws)* "]" ws\nws ::= [ ]*\nnum ::= [1]+ ("." [1]+)?',
         'root ::= item ws | "[" ws item ws "]"\nitem ::= num | "x" ws num\nws ::= [ ]*\nnum ::= [1]+ ("." [1]+)?',
