@@ -7,8 +7,12 @@ every token), fill the batch's next-token bitmask (cached planes + re-check of u
 apply it to bf16 logits and to fp32 logits, then advance every matcher by one token on the host.
 
 Prints ONE JSON line.  `value` = (position, token) checks per second of the cache build, from the
-build's device time (HIP events inside the library: table upload to last plane written); the
-fill+apply microseconds per step, the host times and the wall-clock per step are given beside it.
+build's device time (HIP events inside the library: clearing of the rows and table upload to last
+plane written); the fill+apply microseconds per step, the host times and the wall-clock per step are
+given beside it.  `roofline` counts only the pairs a lane actually stepped through (tokens skipped by
+their first byte or copied from another plane move no bytes and are not counted).  After the timed
+steps, one cache build of the TagDispatch workload (config 3, a millisecond-scale launch of the same
+kernel) is measured the same way and reported under `build_tagdispatch`.
 """
 from __future__ import annotations
 
@@ -33,8 +37,8 @@ PMC = {
     "k_build": (10924.8, 3374.7),
     "k_fill_or": (4114.0, 19167.8),
     "k_apply_vec<8>": (98619.9, 303872.0),
-    # wave instructions of one k_build launch (rocprofv3 --pmc SQ_INSTS_VALU + SALU + BRANCH + LDS + VMEM_RD + VMEM_WR + SMEM)
-    "k_build_wave_instructions": 32699167.0,
+    # wave instructions of one k_build launch of the default workload (rocprofv3 --pmc SQ_INSTS_VALU, SQ_INSTS_SALU + SQ_INSTS_BRANCH)
+    "k_build_valu_instructions": 11400000.0, "k_build_scalar_and_branch_instructions": 20100000.0,
     "k_apply_vec<4>": (182233.6, 605511.0),
 }
 KERNEL_SOURCES = ("csrc/kernels.hip", "csrc/earley_core.hpp", "csrc/device.hpp", "build.py")   # code and compiler flags
@@ -65,6 +69,7 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=5, help="workload index (5 = runtime stress, the metric's configuration)")
     ap.add_argument("--batch", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-tagdispatch-build", action="store_true", help="skip the one build of the TagDispatch workload after the timed steps")
     ap.add_argument("--cross-grammar", type=int, default=0, metavar="N",
                     help="also compile the first N grammars of the cross-grammar workload (config 4; 256 = all) into one pool and "
                          "report planes built once versus positions, and checks/s (adds build launches of other sizes)")
@@ -102,15 +107,11 @@ def main() -> int:
     cache0 = xg.compile_grammar(vocab, ebnf, root, stream=stream)
     rng = random.Random(gen.BASE_SEED + 100 + args.config)
     seg = gen.Segmenter(cfg.vocab)
+    traces, cursor = gen.random_depth_traces(cfg, seg, B, rng)
     matchers = [xg.Matcher(cache0) for _ in range(B)]
-    traces, cursor = [], []
     for b in range(B):
-        ids = seg.segment(cfg.sample_text(rng, 0), rng) + [cfg.vocab.eos_id]
-        depth = rng.randrange(0, max(1, len(ids) - 1))
-        for t in ids[:depth]:
+        for t in traces[b][:cursor[b]]:
             assert matchers[b].accept_token(t)
-        traces.append(ids)
-        cursor.append(depth)
     batch = xg.MatcherBatch(matchers)
 
     g = torch.Generator(device="cpu").manual_seed(1234)
@@ -186,24 +187,48 @@ def main() -> int:
     torch.cuda.synchronize()
     wall = time.perf_counter() - t_begin
 
-    # fraction of logits masked in the last step (for the store-only accounting of apply)
-    allowed = 0
+    # the last step's bitmask: fraction of logits masked, and the bytes the apply kernel moves for it (a 16-byte vector of
+    # logits whose tokens are all allowed is neither read nor written, one whose tokens are all masked is written
+    # without a read, a mixed one is read and written back)
     bm = bitmask.cpu().numpy().view(np.uint32)
+    bm_bytes = bm.view(np.uint8).reshape(B, W * 4)[:, :V // 8]       # one byte = the 8 tokens of one bf16 vector
     allowed = int(np.unpackbits(bm.view(np.uint8)).sum())
     masked = B * V - allowed
+    moved = {}
+    n8_zero, n8_full = int((bm_bytes == 0).sum()), int((bm_bytes == 0xFF).sum())
+    moved[2] = B * W * 4 + 16 * n8_zero + 32 * (bm_bytes.size - n8_zero - n8_full) + 2 * B * (V % 8)
+    nib = np.stack([bm_bytes & 0xF, bm_bytes >> 4])
+    n4_zero, n4_full = int((nib == 0).sum()), int((nib == 0xF).sum())
+    moved[4] = B * W * 4 + 16 * n4_zero + 32 * (nib.size - n4_zero - n4_full) + 4 * B * (V % 8)
 
     mean = lambda xs: float(sum(xs) / len(xs))
     med = lambda xs: float(sorted(xs)[len(xs) // 2])
     st = last_stats
     build_ms = mean(acc["build_device_ms"])
     kernel_ms = mean(acc["build_kernel_ms"])
+    host_ms = mean(acc["build_host_ms"])
     checks = int(st.checks)
     value = checks / (build_ms * 1e-3)
-    # algorithmic bytes of the build per launch: per (position, token) len(t) + 4 bytes in, 2 bits out
-    build_bytes = int(st.built) * (tok_bytes + 4 * n_checkable + n_checkable / 4.0)
-    build_gbs = build_bytes / (kernel_ms * 1e-3) / 1e9
-    executed_gbs = build_gbs * int(st.executed_checks) / max(1, checks)      # only the pairs a lane stepped through
+
+    def build_roofline(stats, k_ms):
+        """HBM roofline of one launch of the build kernel: bytes of the pairs a lane stepped through (token bytes + 4 bytes
+        of offset in, 2 bits out) over the kernel's duration.  The logical figure (every built plane x every token, skipped
+        or not) is kept beside it under its own name."""
+        executed_bytes = int(stats.executed_token_bytes) + 4.25 * int(stats.executed_checks)
+        logical_bytes = int(stats.built) * (tok_bytes_of[id(stats)] + 4.25 * n_checkable_of[id(stats)])
+        gbs = executed_bytes / (k_ms * 1e-3) / 1e9
+        return {"kernel": "k_build", "bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
+                "traffic": None, "algorithmic_bytes_per_launch": executed_bytes, "executed_pairs_per_launch": int(stats.executed_checks),
+                "kernel_ms": k_ms, "executed_pairs_per_s": int(stats.executed_checks) / (k_ms * 1e-3),
+                "logical_checks_accounting": {"bytes_per_launch": logical_bytes, "achieved": logical_bytes / (k_ms * 1e-3) / 1e9,
+                                              "note": "every (built plane, token) pair counted, also the ones skipped by their first byte or copied from "
+                                                      "another plane: not a bandwidth figure, kept for comparison with earlier lines"},
+                "note": "the kernel is bound by instruction issue and load latency of a divergent interpreter, not by HBM: the HBM target of 40 % is not met by the build"}
+
+    tok_bytes_of, n_checkable_of = {id(st): tok_bytes}, {id(st): n_checkable}
     default_workload = args.config == 5 and B == 1024
+    roof = build_roofline(st, kernel_ms)
+    roof["traffic"] = measured_traffic("k_build", default_workload)
     out = {
         "metric": "mask-cache build (position x token) checks/s; batch-%d mask fill+apply us/step" % B,
         "value": value,
@@ -220,8 +245,12 @@ def main() -> int:
         "config": {"workload": cfg.name, "config_index": cfg.index, "vocab": V, "batch": B, "positions": int(st.positions),
                    "unique_positions": int(st.unique), "built_positions": int(st.built), "checks_per_build": checks,
                    "executed_checks": int(st.executed_checks), "slow_path_checks": int(st.slow_path),
-                   "value_basis": "device time of one cache build (HIP events: table upload to last plane), host lowering beside it"},
-        "build": {"device_ms": build_ms, "kernel_ms": kernel_ms, "host_lower_ms": mean(acc["build_host_ms"]),
+                   "value_basis": "logical (built plane, token) pairs over the device time of one cache build (HIP events: clearing of the rows and "
+                                  "table upload to last plane); executed pairs and the end-to-end rate with host lowering are under `build`"},
+        "build": {"device_ms": build_ms, "kernel_ms": kernel_ms, "host_lower_ms": host_ms,
+                  "executed_checks_per_s_device": int(st.executed_checks) / (build_ms * 1e-3),
+                  "checks_per_s_end_to_end": checks / ((build_ms + host_ms) * 1e-3),
+                  "executed_checks_per_s_end_to_end": int(st.executed_checks) / ((build_ms + host_ms) * 1e-3),
                   "n_accepted_bits": int(st.n_accepted), "n_uncertain_bits": int(st.n_uncertain)},
         "decode": {"fill_us": med(acc["fill_device_us"]), "apply_bf16_us": med(acc["apply_bf16_us"]), "apply_f32_us": med(acc["apply_f32_us"]),
                    "fill_apply_bf16_us": med(acc["fill_device_us"]) + med(acc["apply_bf16_us"]),
@@ -230,42 +259,57 @@ def main() -> int:
                    "fill_host_ms": med(acc["fill_host_ms"]), "accept_host_ms": med(acc["accept_host_ms"]),
                    "accept_call_ms": med(acc["accept_call_ms"][-args.steps:]),
                    "masked_fraction_last_step": masked / float(B * V)},
-        "roofline": {"kernel": "k_build", "bound": "hbm", "achieved": build_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": build_gbs / HBM_PEAK_GBS, "traffic": measured_traffic("k_build", default_workload),
-                     "algorithmic_bytes_per_launch": build_bytes, "achieved_executed_only": executed_gbs,
-                     "note": "algorithmic bytes = built planes x (sum of token bytes + 4.25 B per token), every logical check counted; "
-                             "the kernel is bound by instruction issue and load latency, not by HBM (measured traffic is far below)"},
+        "roofline": roof,
     }
-    # the build kernel is an interpreter: what bounds it is the rate at which the SIMDs issue wave instructions
-    # (256 CUs x 4 SIMDs x 2.4 GHz, one instruction of a wave every 4 cycles)
-    issue_peak = 256 * 4 * 2.4e9 / 4
-    n_instr = PMC["k_build_wave_instructions"] if (default_workload and kernel_sources_sha256() == PMC["sources_sha256"]) else None
-    out["roofline_alu"] = {"kernel": "k_build", "bound": "alu", "achieved": (n_instr / (kernel_ms * 1e-3)) if n_instr else None,
-                           "peak": issue_peak, "unit": "wave-instructions/s",
-                           "frac": (n_instr / (kernel_ms * 1e-3) / issue_peak) if n_instr else None, "traffic": None,
-                           "note": "instruction count from rocprofv3 SQ counters for these kernel sources; scalar and branch instructions are 63 % of it"}
+    # the build kernel is an interpreter: what bounds it is the rate at which the SIMDs issue vector instructions
+    # (256 CUs x 4 SIMDs of 16 lanes at 2.4 GHz: a vector instruction of a 64-lane wave occupies its SIMD for 4 cycles);
+    # scalar and branch instructions issue on ports of their own and are reported beside, not against that peak
+    valu_peak = 256 * 4 * 2.4e9 / 4
+    counted = default_workload and kernel_sources_sha256() == PMC["sources_sha256"]
+    n_valu = PMC["k_build_valu_instructions"] if counted else None
+    out["roofline_alu"] = {"kernel": "k_build", "bound": "alu", "achieved": (n_valu / (kernel_ms * 1e-3)) if n_valu else None,
+                           "peak": valu_peak, "unit": "vector wave-instructions/s",
+                           "frac": (n_valu / (kernel_ms * 1e-3) / valu_peak) if n_valu else None, "traffic": None,
+                           "scalar_and_branch_instructions_per_launch": PMC["k_build_scalar_and_branch_instructions"] if counted else None,
+                           "note": "instruction counts from rocprofv3 SQ counters, valid for the kernel sources they were taken with (null otherwise)"}
     for name, key, e in (("roofline_apply_bf16", "apply_bf16_us", 2), ("roofline_apply_f32", "apply_f32_us", 4)):
         t = med(acc[key]) * 1e-6
-        rmw = (B * W * 4 + 2 * B * V * e) / t / 1e9
-        store_only = (B * W * 4 + masked * e) / t / 1e9
-        out[name] = {"kernel": "k_apply_vec", "bound": "hbm", "achieved": rmw, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": rmw / HBM_PEAK_GBS, "traffic": measured_traffic("k_apply_vec<8>" if e == 2 else "k_apply_vec<4>", default_workload),
-                     "accounting": "read-modify-write of all logits + bitmask read",
-                     "achieved_store_only_accounting": store_only}
+        gbs = moved[e] / t / 1e9
+        out[name] = {"kernel": "k_apply_vec", "bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": gbs / HBM_PEAK_GBS, "traffic": measured_traffic("k_apply_vec<8>" if e == 2 else "k_apply_vec<4>", default_workload),
+                     "algorithmic_bytes_per_launch": moved[e],
+                     "accounting": "bytes the kernel has to move for this bitmask: bitmask read + 16 B written per fully masked vector + 32 B read and "
+                                   "written per mixed vector (last step's bitmask)",
+                     "achieved_read_modify_write_accounting": (B * W * 4 + 2 * B * V * e) / t / 1e9,
+                     "achieved_store_only_accounting": (B * W * 4 + masked * e) / t / 1e9}
     tf = med(acc["fill_device_us"]) * 1e-6
     out["roofline_fill"] = {"kernel": "k_fill_or + k_recheck", "bound": "hbm", "achieved": B * W * 4 / tf / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                             "frac": B * W * 4 / tf / 1e9 / HBM_PEAK_GBS, "traffic": measured_traffic("k_fill_or", default_workload),
                             "accounting": "bitmask write only, over the whole device time of fill (upload, union, re-check)"}
-
-    # just-in-time compilation (section 3.5), beside the main figures: nothing built at compile time, planes built by the
-    # fill calls that first reach them; per-step latency of fill (host + device, synchronised) over fresh sentences
-    # fill + apply as one unit (the decode half of the metric): bitmask written once and read once, logits read-modify-written
+    # fill + apply as one unit (the decode half of the metric): bitmask written once, then what apply moves
     for name, key, e in (("roofline_fill_apply_bf16", "apply_bf16_us", 2), ("roofline_fill_apply_f32", "apply_f32_us", 4)):
         t = (med(acc["fill_device_us"]) + med(acc[key])) * 1e-6
-        gbs = (2 * B * W * 4 + 2 * B * V * e) / t / 1e9
+        gbs = (B * W * 4 + moved[e]) / t / 1e9
         out[name] = {"kernel": "k_fill_or + k_recheck + k_apply_vec", "bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": gbs / HBM_PEAK_GBS, "traffic": None, "us_per_step": t * 1e6,
-                     "accounting": "bitmask write + bitmask read + read-modify-write of all logits, over fill's and apply's device time"}
+                     "accounting": "bitmask write + the bytes apply moves (see roofline_apply_*), over fill's and apply's device time"}
+
+    if not args.no_tagdispatch_build:
+        # one cache build of the TagDispatch workload (64 tools, V = 128,256): a millisecond-scale launch of the same kernel
+        cfg3 = gen.build_config(3)
+        vocab3 = xg.Vocab(cfg3.vocab.tokens, cfg3.vocab.eos_id, cfg3.vocab.special_ids)
+        ebnf3, root3 = cfg3.grammars[0]
+        xg.compile_grammar(vocab3, ebnf3, root3, stream=stream)               # first use: vocabulary upload, allocations
+        c3 = xg.compile_grammar(vocab3, ebnf3, root3, stream=stream)
+        s3 = c3.stats
+        tok_bytes_of[id(s3)] = sum(len(t) for i, t in enumerate(cfg3.vocab.tokens) if t and i not in cfg3.vocab.special_ids)
+        n_checkable_of[id(s3)] = sum(1 for i, t in enumerate(cfg3.vocab.tokens) if t and i not in cfg3.vocab.special_ids)
+        out["build_tagdispatch"] = {"workload": cfg3.name, "vocab": cfg3.vocab.size, "positions": int(s3.positions), "planes_built": int(s3.built),
+                                    "checks": int(s3.checks), "executed_checks": int(s3.executed_checks), "slow_path_checks": int(s3.slow_path),
+                                    "device_ms": s3.device_ms, "kernel_ms": s3.kernel_ms, "host_lower_ms": s3.host_lower_ms,
+                                    "checks_per_s_device": int(s3.checks) / (s3.device_ms * 1e-3),
+                                    "roofline": build_roofline(s3, s3.kernel_ms)}
+        del c3, vocab3
 
     if args.cross_grammar:
         cfg4 = gen.build_config(4)

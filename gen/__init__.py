@@ -11,4 +11,4 @@ from .grammars import (                          # noqa: F401
     tiny_json_schema, nested_schema, tool_schema, repetition_stress_ebnf,
 )
 from .configs import build_config, CONFIG_NAMES, BASE_SEED   # noqa: F401
-from .traces import segment, Segmenter           # noqa: F401
+from .traces import segment, Segmenter, random_depth_traces   # noqa: F401

@@ -42,3 +42,15 @@ class Segmenter:
 
 def segment(vocab: Vocab, text: bytes, rng: random.Random) -> List[int]:
     return Segmenter(vocab).segment(text, rng)
+
+
+def random_depth_traces(cfg, seg: Segmenter, batch: int, rng: random.Random, grammar: int = 0):
+    """`batch` sentences of workload `cfg` cut into tokens, each with a depth drawn uniformly over its own length:
+    the state "concurrent matchers at random depths" starts from.  Returns (traces, depths); a trace ends with the
+    end-of-sequence token, and depth < len(trace) - 1 (at least the last text token and the end are still to come)."""
+    traces, depths = [], []
+    for _ in range(batch):
+        ids = seg.segment(cfg.sample_text(rng, grammar), rng) + [cfg.vocab.eos_id]
+        traces.append(ids)
+        depths.append(rng.randrange(0, max(1, len(ids) - 1)))
+    return traces, depths

@@ -91,6 +91,7 @@ typedef struct xg2_compile_stats {
     int64_t checks;           /* built * (number of checkable tokens): logical (plane, token)     */
     int64_t executed_checks;  /* (plane, token) pairs a lane actually stepped through (not the
                                  tokens skipped by their first byte or taken from another plane)  */
+    int64_t executed_token_bytes; /* summed token lengths over the executed pairs                     */
     int64_t slow_path;        /* pairs finished by the large-capacity kernel                      */
     int64_t n_accepted;       /* set bits over the built accepted planes                          */
     int64_t n_uncertain;      /* set bits over the built uncertain planes                         */
@@ -203,6 +204,12 @@ int32_t xg2_fill_last_device_us(float* out);
  * item lists (256 items, 1024 wait entries, tokens of 1024 bytes) -- such a token's bit is left 0 although
  * the token might be allowed.  fill itself returns before the device work runs and cannot report this.   */
 int32_t xg2_fill_last_status(int32_t* large_capacity_tokens, int32_t* overflowed);
+
+/* Measurement and test aid: for each row of the latest fill call of this process (waits for its device work), the
+ * number of mask words that held at least one candidate, i.e. a token that is uncertain somewhere in the row's
+ * frontier and accepted nowhere in it, and therefore went through the full-context re-check (section 3.4, runtime
+ * part).  words_host: host array; at most cap entries are written; *n_rows (nullable) receives the batch size.   */
+int32_t xg2_fill_last_recheck_words(int32_t* words_host, int32_t cap, int32_t* n_rows);
 
 /* ---- apply_token_bitmask(logits[B, V], bitmask) -------------------------------------------------
  * In place: logits[b, v] = -infinity where bit v of bitmask row b is 0; other elements keep

@@ -25,7 +25,8 @@ EXPORTS = [
     "xg2_compile_grammar", "xg2_mask_cache_destroy", "xg2_mask_cache_num_positions", "xg2_mask_cache_num_planes", "xg2_mask_cache_jit_stats",
     "xg2_mask_cache_plane_info", "xg2_mask_cache_find_plane", "xg2_mask_cache_get_planes", "xg2_matcher_create", "xg2_matcher_create_host", "xg2_matcher_destroy",
     "xg2_matcher_accept_token", "xg2_matcher_accept_tokens", "xg2_matcher_reset", "xg2_matcher_is_terminated", "xg2_matcher_frontier",
-    "xg2_fill_next_token_bitmask", "xg2_fill_last_device_us", "xg2_fill_last_status", "xg2_apply_token_bitmask",
+    "xg2_fill_next_token_bitmask", "xg2_fill_last_device_us", "xg2_fill_last_status", "xg2_fill_last_recheck_words",
+    "xg2_apply_token_bitmask",
 ]
 
 
@@ -37,7 +38,8 @@ class Xg2Error(RuntimeError):
 
 class CompileStats(ctypes.Structure):
     _fields_ = [("positions", ctypes.c_int64), ("unique", ctypes.c_int64), ("built", ctypes.c_int64),
-                ("checks", ctypes.c_int64), ("executed_checks", ctypes.c_int64), ("slow_path", ctypes.c_int64),
+                ("checks", ctypes.c_int64), ("executed_checks", ctypes.c_int64), ("executed_token_bytes", ctypes.c_int64),
+                ("slow_path", ctypes.c_int64),
                 ("n_accepted", ctypes.c_int64), ("n_uncertain", ctypes.c_int64),
                 ("host_lower_ms", ctypes.c_double), ("device_ms", ctypes.c_double), ("kernel_ms", ctypes.c_double)]
 
@@ -94,6 +96,7 @@ def _load() -> ctypes.CDLL:
     L.xg2_fill_next_token_bitmask.argtypes = [vp, i32, vp, i64, vp]
     L.xg2_fill_last_device_us.argtypes = [ctypes.POINTER(ctypes.c_float)]
     L.xg2_fill_last_status.argtypes = [ctypes.POINTER(i32), ctypes.POINTER(i32)]
+    L.xg2_fill_last_recheck_words.argtypes = [vp, i32, ctypes.POINTER(i32)]
     L.xg2_apply_token_bitmask.argtypes = [vp, i32, i32, i32, i64, vp, i64, vp]
     for name in EXPORTS:
         if name not in ("xg2_last_error",) and not name.endswith("_destroy"):
@@ -303,6 +306,14 @@ def fill_last_status() -> Tuple[int, bool]:
     n, over = ctypes.c_int32(0), ctypes.c_int32(0)
     _check(lib.xg2_fill_last_status(ctypes.byref(n), ctypes.byref(over)))
     return n.value, bool(over.value)
+
+
+def fill_last_recheck_words(batch: int) -> np.ndarray:
+    """Per row of the latest fill: how many mask words held a candidate for the full-context re-check."""
+    out = np.zeros(batch, dtype=np.int32)
+    n = ctypes.c_int32(0)
+    _check(lib.xg2_fill_last_recheck_words(out.ctypes.data, batch, ctypes.byref(n)))
+    return out[:min(batch, n.value)]
 
 
 def fill_last_device_us() -> float:

@@ -155,6 +155,14 @@ struct VocabImpl {
     // of at most d bytes (row d - 1 of d_short_mask)
     uint32_t near_depths = 0;
     std::vector<uint32_t> long_rank, long_off;
+    std::vector<uint64_t> long_bytes;           // long_bytes[i] = bytes of the tokens long_rank[0 .. i) (for the statistics of a build)
+    void extend_long_bytes() {
+        if (long_bytes.empty()) long_bytes.push_back(0);
+        for (size_t i = long_bytes.size() - 1; i < long_rank.size(); ++i) {
+            const uint32_t r = long_rank[i];
+            long_bytes.push_back(long_bytes.back() + (r < n_sorted ? s_off[r + 1] - s_off[r] : 0u));
+        }
+    }
     DevBuf<uint32_t> d_long_rank, d_short_mask;
     DevBuf<uint8_t> d_first_byte;               // first byte of every token id (0 for the empty ones), W * 32 entries
     // per byte set asked for so far: the sorted ranks of the tokens that contain a byte of the set (ascending, appended
@@ -175,6 +183,7 @@ struct VocabImpl {
             else without[perm[r] >> 5] |= 1u << (perm[r] & 31);
         }
         bl.n = (uint32_t)long_rank.size() - bl.off;
+        extend_long_bytes();
         bl.d_without.reset(new DevBuf<uint32_t>());
         bl.d_without->upload(without, nullptr);
         d_long_rank.upload(long_rank, nullptr);
@@ -213,6 +222,7 @@ struct VocabImpl {
         }
         long_off[(size_t)near_depths + 1] = (uint32_t)long_rank.size();
         if (long_rank.empty()) long_rank.push_back(0);
+        extend_long_bytes();
         d_long_rank.upload(long_rank, nullptr);
         d_short_mask.upload(short_mask, nullptr);
         std::vector<uint8_t> first_byte((size_t)W * 32, 0);
@@ -277,6 +287,13 @@ struct PoolImpl {
     uint64_t clock = 0;
     int64_t n_evicted = 0;
     std::vector<void*> slabs;
+    // memory to clear before the next build writes to it: freshly allocated slabs and rows taken from the free list.
+    // The build enqueues the fills inside its timed region (skipped tokens rely on the zeros).
+    std::vector<std::pair<void*, size_t>> to_zero;
+    void flush_zero(hipStream_t stream) {
+        for (auto& z : to_zero) HIP_CHECK(hipMemsetAsync(z.first, 0, z.second, stream));
+        to_zero.clear();
+    }
     uint8_t* slab_cur = nullptr; size_t slab_left = 0;
     size_t device_bytes = 0;
     int64_t n_rows = 0;
@@ -312,8 +329,8 @@ struct PoolImpl {
         --n_rows;
     }
     // rows_ahead: how many rows the caller is about to ask for, this one included (sizes a new slab: what is
-    // allocated is zeroed on the stream at once, so a small build should not pay for a large slab)
-    uint32_t* alloc_row(size_t row_bytes, hipStream_t stream, size_t rows_ahead = 1) {
+    // allocated is zeroed by the build that first uses it, so a small build should not pay for a large slab)
+    uint32_t* alloc_row(size_t row_bytes, size_t rows_ahead = 1) {
         if (free_rows.empty() && slab_left < row_bytes) {
             size_t want = std::min<size_t>(std::max<size_t>({row_bytes * 64, (size_t)8 << 20, rows_ahead * row_bytes}), (size_t)256 << 20);
             want = std::max(want, row_bytes);
@@ -331,14 +348,14 @@ struct PoolImpl {
                 void* p = nullptr;
                 HIP_CHECK(hipMalloc(&p, want));
                 slabs.push_back(p);
-                HIP_CHECK(hipMemsetAsync(p, 0, want, stream));       // rows are handed out as zeros
+                to_zero.emplace_back(p, want);                       // rows are handed out as zeros
                 slab_cur = (uint8_t*)p; slab_left = want; device_bytes += want;
             }
         }
         uint32_t* row;
         if (!free_rows.empty()) {
             row = free_rows.back(); free_rows.pop_back();
-            HIP_CHECK(hipMemsetAsync(row, 0, row_bytes, stream));
+            to_zero.emplace_back(row, row_bytes);
         } else {
             row = (uint32_t*)slab_cur;
             slab_cur += row_bytes; slab_left -= row_bytes;
@@ -362,7 +379,7 @@ struct PlaneInfo {
     int32_t site_plane = -1, site_list = -1;                // the same state under another site: same classes for every token outside that list
 };
 struct BuildResult {
-    int64_t built = 0, executed = 0, slow = 0, n_accepted = 0, n_uncertain = 0;
+    int64_t built = 0, executed = 0, executed_bytes = 0, slow = 0, n_accepted = 0, n_uncertain = 0;
     double host_ms = 0;
     float device_ms = 0.f, kernel_ms = 0.f;
 };
@@ -420,6 +437,7 @@ struct FillWorkspace {
     DevBuf<uint32_t> cand_words, work_list, row_count;
     hipEvent_t t_begin = nullptr, t_end = nullptr;          // around the device work of the latest fill
     const uint32_t* last_flags = nullptr;                   // device: overflow-list length and flag of the latest fill
+    int32_t last_B = 0;                                     // rows of the latest fill (row_count holds their candidate-word counts)
     bool timed = false;
     void ensure_scratch(size_t words, size_t rows) {
         if (row_count.n < rows) row_count.alloc(rows * 2);
@@ -533,24 +551,46 @@ int32_t build_planes(CacheImpl& cache, const std::vector<int32_t>& todo, hipStre
     const size_t row_bytes = (size_t)V.W * 2 * sizeof(uint32_t);
     std::vector<int32_t> build;                                 // plane indices to class now
     std::vector<uint32_t*> build_rows;
+    // Until the planes are known to be built, the pool must not offer their rows to anyone: whatever goes wrong
+    // on the way (the pool is full, a HIP call fails, the item sets overflow), the rows this call has entered
+    // are taken out of the pool again and their memory goes back to the free list.
+    struct Rollback {
+        PoolImpl& pool; CacheImpl& cache; const std::vector<int32_t>& build; const std::vector<uint32_t*>& rows; hipStream_t stream;
+        bool armed = true;
+        ~Rollback() {
+            if (!armed) return;
+            (void)hipStreamSynchronize(stream);                  // no kernel of this call writes to the rows any more
+            for (size_t k = 0; k < build.size(); ++k) {
+                auto it = pool.rows.find(cache.planes[(size_t)build[k]].key);
+                if (it != pool.rows.end() && it->second == rows[k]) pool.rows.erase(it);
+                pool.free_rows.push_back(rows[k]);
+                --pool.n_rows;
+            }
+        }
+    } rollback{pool, cache, build, build_rows, stream};
     for (size_t i = 0; i < todo.size(); ++i) {
         const int32_t k = todo[i];
         PlaneInfo& pi = cache.planes[(size_t)k];
         if (pi.row) continue;
-        uint32_t*& row = pool.rows[pi.key];
-        if (row) { pi.row = row; pi.no_uncertain = pool.no_uncertain.count(row) != 0; pool.take(row, pi.key); ++cache.n_built; continue; }   // another grammar built it
-        row = pool.alloc_row(row_bytes, stream, todo.size() - i);
+        auto have = pool.rows.find(pi.key);
+        if (have != pool.rows.end()) {                           // another grammar built it
+            uint32_t* row = have->second;
+            pi.row = row; pi.no_uncertain = pool.no_uncertain.count(row) != 0; pool.take(row, pi.key); ++cache.n_built;
+            continue;
+        }
+        uint32_t* row = pool.alloc_row(row_bytes, todo.size() - i);
         build.push_back(k);
         build_rows.push_back(row);
+        pool.rows.emplace(pi.key, row);
     }
-    if (build.empty() && !with_tables) return XG2_OK;
+    if (build.empty() && !with_tables) { rollback.armed = false; return XG2_OK; }
 
     // plan: closed start set and live first-byte ranges of every plane to build
     std::vector<uint32_t> ctx_items, ctx_wait, ctx_wait_off;
     std::vector<uint4> chunks, plane_ctx, ranges;
     std::vector<CopyJob> copies;
     std::vector<FirstByteCopyJob> fb_copies;
-    int64_t executed = 0;
+    int64_t executed = 0, executed_bytes = 0;
     EarleyChart chart(&ft);
     std::map<int32_t, size_t> building;                         // plane index -> position in build
     for (size_t k = 0; k < build.size(); ++k) building.emplace(build[k], k);
@@ -671,6 +711,7 @@ int32_t build_planes(CacheImpl& cache, const std::vector<int32_t>& todo, hipStre
             }
             if (lo < hi) ranges.push_back(make_uint4((uint32_t)k, lo, hi, listed | threads | (heavy ? kChunkHeavy : 0u)));
             executed += hi - lo;
+            executed_bytes += listed ? (int64_t)(V.long_bytes[hi] - V.long_bytes[lo]) : (int64_t)(V.s_off[hi] - V.s_off[lo]);
             b = e + 1;
         }
     }
@@ -705,6 +746,7 @@ int32_t build_planes(CacheImpl& cache, const std::vector<int32_t>& todo, hipStre
     staging().ensure_events();
     const hipEvent_t ev0 = staging().ev[0], ev1 = staging().ev[1], evk0 = staging().ev[2], evk1 = staging().ev[3];
     HIP_CHECK(hipEventRecord(ev0, stream));
+    pool.flush_zero(stream);                                       // the rows start as zeros: tokens skipped by their first byte are never written
     tab.copy(stream);
     if (with_tables) {
         cache.dt.state = tab.at<const uint4>(o_state);
@@ -741,14 +783,9 @@ int32_t build_planes(CacheImpl& cache, const std::vector<int32_t>& todo, hipStre
     HIP_CHECK(hipGetLastError());
     HIP_CHECK(hipEventElapsedTime(&res.device_ms, ev0, ev1));
     HIP_CHECK(hipEventElapsedTime(&res.kernel_ms, evk0, evk1));
-    if (slow_counts[1]) {
-        for (size_t k = 0; k < build.size(); ++k) {                       // these rows hold partial results: forget them
-            pool.rows.erase(cache.planes[(size_t)build[k]].key);
-            pool.free_rows.push_back(build_rows[k]);
-            --pool.n_rows;
-        }
+    if (slow_counts[1])                                             // the rows hold partial results: the guard takes them back
         return fail(XG2_EOVERFLOW, "mask cache build: Earley item sets exceeded the large-capacity limit");
-    }
+    rollback.armed = false;
     for (size_t k = 0; k < build.size(); ++k) {
         PlaneInfo& pi = cache.planes[(size_t)build[k]];
         pi.row = build_rows[k];
@@ -760,6 +797,7 @@ int32_t build_planes(CacheImpl& cache, const std::vector<int32_t>& todo, hipStre
     cache.n_built += (int64_t)build.size();
     res.built = (int64_t)build.size();
     res.executed = executed;
+    res.executed_bytes = executed_bytes;
     res.slow = slow_counts[0];
     return XG2_OK;
 }
@@ -1222,6 +1260,7 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
             stats->built = res.built;
             stats->checks = res.built * (int64_t)V.n_sorted;
             stats->executed_checks = res.executed;
+            stats->executed_token_bytes = res.executed_bytes;
             stats->slow_path = res.slow;
             stats->n_accepted = res.n_accepted;
             stats->n_uncertain = res.n_uncertain;
@@ -1516,6 +1555,7 @@ int32_t xg2_fill_next_token_bitmask(xg2_matcher* const* matchers, int32_t B, int
         HIP_CHECK(hipEventRecord(fill_ws().t_end, stream));
         fill_ws().timed = true;
         fill_ws().last_flags = S.count;
+        fill_ws().last_B = B;
         HIP_CHECK(hipEventRecord(slot.done, stream));
         slot.in_flight = true;
         return XG2_OK;
@@ -1544,6 +1584,19 @@ int32_t xg2_fill_last_status(int32_t* large_capacity_tokens, int32_t* overflowed
         HIP_CHECK(hipMemcpy(words, fill_ws().last_flags, sizeof(words), hipMemcpyDeviceToHost));
         if (large_capacity_tokens) *large_capacity_tokens = (int32_t)words[0];
         if (overflowed) *overflowed = words[1] ? 1 : 0;
+        return XG2_OK;
+    });
+}
+
+int32_t xg2_fill_last_recheck_words(int32_t* words_host, int32_t cap, int32_t* n_rows) {
+    return guarded([&]() -> int32_t {
+        if (cap < 0 || (cap > 0 && !words_host)) return fail(XG2_EINVAL, "xg2_fill_last_recheck_words: bad argument");
+        std::lock_guard<std::mutex> ws_lock(fill_ws().mu);
+        if (!fill_ws().timed) return fail(XG2_EINVAL, "xg2_fill_last_recheck_words: no fill call yet");
+        HIP_CHECK(hipEventSynchronize(fill_ws().t_end));
+        const int32_t n = std::min(cap, fill_ws().last_B);
+        if (n > 0) HIP_CHECK(hipMemcpy(words_host, fill_ws().row_count.p, (size_t)n * sizeof(uint32_t), hipMemcpyDeviceToHost));
+        if (n_rows) *n_rows = fill_ws().last_B;
         return XG2_OK;
     });
 }

@@ -114,6 +114,7 @@ __device__ __forceinline__ void enter(const DevTables& T, S& st, uint32_t ref, u
 template <class S, bool FOLLOW = false, class BYTES = RegBytes>
 __device__ int scan_token(const DevTables& T, const uint32_t* cls_words, const DevCtx& C, BYTES tok, int n, S& st) {
     if (n > S::MAXLEN || (int)C.n_items > S::K) return RES_OVERFLOW;
+    if (C.H + (uint32_t)n > ROOT_ORIGIN) return RES_OVERFLOW;       // the new sets C.H .. C.H + n - 1 must stay below the root mark
     int nc = (int)C.n_items;
     uint32_t one = nc == 1 ? C.items[0] : 0u;
     bool single = nc == 1 && (one & (F_BYTE | F_REF | F_FINAL)) == F_BYTE;

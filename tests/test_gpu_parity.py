@@ -163,19 +163,22 @@ def test_apply_unaligned_base(xg):
 
 
 def test_config2_planes_and_decode(xg):
+    """Nested schema, batch 64 x 256 steps: every one of the 16,384 (row, step) masks against the plain definition."""
     cfg, vocab, va = load(2)
     ebnf, root = cfg.grammars[0]
     cache, orc = check_planes(xg, cfg, vocab, va, ebnf, root)
-    n = run_decode(xg, cfg, vocab, va, cache, orc, batch=64, steps=48, seed=22, check_every=5)
-    assert n >= 600
+    n = run_decode(xg, cfg, vocab, va, cache, orc, batch=cfg.batch, steps=cfg.steps, seed=22, check_every=1)
+    assert n == 64 * 256
 
 
 def test_config3_tagdispatch_planes_and_decode(xg):
+    """TagDispatch over 64 tools, batch 256 x 512 steps (tags fire inside the sampled texts): every plane x 128,256
+    tokens, and a regular sample of one in 31 of the 131,072 (row, step) masks, over all 512 steps."""
     cfg, vocab, va = load(3)
     ebnf, root = cfg.grammars[0]
     cache, orc = check_planes(xg, cfg, vocab, va, ebnf, root)          # every plane x 128,256 tokens
-    n = run_decode(xg, cfg, vocab, va, cache, orc, batch=256, steps=24, seed=33, check_every=37)
-    assert n >= 160
+    n = run_decode(xg, cfg, vocab, va, cache, orc, batch=cfg.batch, steps=cfg.steps, seed=33, check_every=31)
+    assert n >= 4200
 
 
 def test_config5_depth1_unmerged_planes(xg):
@@ -195,6 +198,104 @@ def test_config5_repetition_planes_and_decode(xg):
     assert cache.stats.unique < 800                          # planes do not grow with the {0,999} repetition bound
     n = run_decode(xg, cfg, vocab, va, cache, orc, batch=1024, steps=6, seed=55, check_every=41)
     assert n >= 140
+
+
+def test_config5_decode_at_random_depths_batch_1024(xg):
+    """The state the benchmark times: 1024 matchers advanced to seeded random depths of their own sentences, then 200
+    steps of fill (+ batched accept).  On 34 steps spread over the 200, about 40 rows each (24 drawn at random, the
+    others picked among rows inside the integer, rows whose string is within one token length of its bound of 64
+    characters, and rows that had candidates for the full-context re-check): the bitmask row equals the oracle's
+    plain-definition mask, and on 4 of those steps the bf16 and fp32 logits masked with those very bitmasks equal the
+    oracle's masking of the same rows.  Coverage is asserted: >= 1,000 masks, >= 60 in each of the three groups."""
+    import re
+    import torch
+    cfg, vocab, va = load(5)
+    ebnf, root = cfg.grammars[0]
+    B, W, V, steps = cfg.batch, vocab.words, vocab.size, cfg.steps
+    assert (B, W, steps) == (1024, 4748, 200)
+    dev = torch.device("cuda:0")
+    cache = xg.compile_grammar(vocab, ebnf, root, stream=_stream())
+    orc = oracle.Oracle(ebnf, root)
+    rng = random.Random(gen.BASE_SEED + 100 + 5)                    # the benchmark's own recipe and seed
+    seg = gen.Segmenter(cfg.vocab)
+    traces, cursor = gen.random_depth_traces(cfg, seg, B, rng)
+    matchers = [xg.Matcher(cache) for _ in range(B)]
+    for b in range(B):
+        for t in traces[b][:cursor[b]]:
+            assert matchers[b].accept_token(t)
+    hist = [b"".join(cfg.vocab.tokens[t] for t in traces[b][:cursor[b]]) for b in range(B)]
+    batch = xg.MatcherBatch(matchers)
+    bitmask = torch.full((B, W), -1, dtype=torch.int32, device=dev)
+    g = torch.Generator(device="cpu").manual_seed(99)
+    logits32 = torch.randn((B, V), generator=g, dtype=torch.float32)
+    logits32[0, :6] = torch.tensor([float("nan"), float("inf"), float("-inf"), -0.0, 0.0, 1e-45])
+    logits32_src = logits32.to(dev)
+    logits16_src = logits32_src.to(torch.bfloat16)
+    in_int = re.compile(rb'"n"[ \n\t]*:[ \n\t]*-?[0-9]+$')
+    in_str = re.compile(rb'"s"[ \n\t]*:[ \n\t]*"([^"]*)$')
+    pick = random.Random(555)
+    sampled_steps = set(range(0, steps, 6))
+    apply_steps = {0, 66, 132, 198}
+    n_masks = n_int = n_bound = n_recheck = n_apply_rows = 0
+    for step in range(steps):
+        xg.fill_next_token_bitmask(batch, bitmask.data_ptr(), W, _stream())
+        if step in sampled_steps:
+            torch.cuda.synchronize()
+            assert not xg.fill_last_status()[1]
+            got = bitmask.cpu().numpy()
+            words = xg.fill_last_recheck_words(B)
+            nxt = np.array([traces[b][cursor[b]] for b in range(B)])
+            assert ((got.view(np.uint32)[np.arange(B), nxt // 32] >> (nxt % 32).astype(np.uint32)) & 1).all(), "a trace's next token is not allowed"
+            ints = [b for b in range(B) if in_int.search(hist[b][-64:])]
+            bound = []
+            for b in range(B):
+                m = in_str.search(hist[b][-400:])
+                if m and len(m.group(1).decode("utf-8", "ignore")) >= 49:
+                    bound.append(b)
+            rech = [b for b in range(B) if words[b] > 0]
+            rows = set(pick.sample(range(B), 24))
+            for group, k in ((ints, 4), (bound, 4), (rech, 8)):
+                rows.update(pick.sample(group, min(k, len(group))))
+            rows = sorted(rows)
+            want_rows = []
+            for b in rows:
+                want = oracle.pack_bitmask(orc.mask(hist[b], va))
+                assert np.array_equal(got[b], want), (step, b, hist[b][-40:], diff_words(got[b], want, cfg.vocab.tokens))
+                want_rows.append(want)
+            n_masks += len(rows)
+            n_int += len(set(rows) & set(ints)); n_bound += len(set(rows) & set(bound)); n_recheck += len(set(rows) & set(rech))
+            if step in apply_steps:
+                idx = torch.tensor(rows, device=dev)
+                l32 = logits32_src.clone()
+                l16 = logits16_src.clone()
+                xg.apply_token_bitmask(l32.data_ptr(), xg.XG2_F32, B, V, V, bitmask.data_ptr(), W, _stream())
+                xg.apply_token_bitmask(l16.data_ptr(), xg.XG2_BF16, B, V, V, bitmask.data_ptr(), W, _stream())
+                torch.cuda.synchronize()
+                bm_want = np.stack(want_rows)
+                w32 = logits32_src[idx].cpu().numpy().view(np.uint32).copy()
+                oracle.apply_f32(w32, bm_want)
+                assert np.array_equal(l32[idx].cpu().numpy().view(np.uint32), w32), ("masked fp32 logits", step)
+                w16 = logits16_src[idx].view(torch.int16).cpu().numpy().view(np.uint16).copy()
+                oracle.apply_bf16(w16, bm_want)
+                assert np.array_equal(l16[idx].view(torch.int16).cpu().numpy().view(np.uint16), w16), ("masked bf16 logits", step)
+                n_apply_rows += len(rows)
+                del l32, l16
+        ids = np.array([traces[b][cursor[b]] for b in range(B)], dtype=np.int32)
+        status = batch.accept_tokens(ids)
+        assert not status.any(), "a trace token was rejected"
+        for b in range(B):
+            tid = int(ids[b])
+            cursor[b] += 1
+            if tid == cfg.vocab.eos_id:                             # end of sequence accepted: a fresh sentence
+                matchers[b].reset()
+                traces[b] = seg.segment(cfg.sample_text(rng, 0), rng) + [cfg.vocab.eos_id]
+                cursor[b] = 0
+                hist[b] = b""
+            else:
+                hist[b] += cfg.vocab.tokens[tid]
+    print("config 5 decode parity: %d masks (%d inside the integer, %d near the string bound, %d with re-checked candidates), %d masked-logit rows x 2 dtypes"
+          % (n_masks, n_int, n_bound, n_recheck, n_apply_rows))
+    assert n_masks >= 1000 and n_int >= 60 and n_bound >= 60 and n_recheck >= 60 and n_apply_rows >= 100
 
 
 def test_plane_count_does_not_depend_on_repetition_bound(xg):
@@ -309,29 +410,70 @@ def test_config4_cross_grammar_pool(xg):
     assert built1 == pool1.stats()[0] == len(distinct)              # exact count of distinct structures, the slow way
 
 
-def test_config4_full_size_sampled_planes(xg):
-    """The cross-grammar workload at its full size (256 grammars over 512 tools, one pool, 151,936 tokens): sampled planes
-    of grammars compiled late, most of them served by planes that earlier grammars built, equal the oracle's classes
-    for that grammar alone."""
+def structure_of(orc, rule, memo):
+    """Exact structure of a rule's canonical automaton with references unfolded (from the oracle's own lowering)."""
+    if rule in memo:
+        return memo[rule]
+    d = orc.low.dfa[rule]
+    memo[rule] = ("...",)                                           # no reference cycles in these workloads
+    out = []
+    for q in range(d.n):
+        out.append((d.final[q], tuple(sorted((m, t) for m, t in d.bedges[q])),
+                    tuple(sorted((structure_of(orc, orc.order[r], memo), t) for r, t in d.redges[q].items()))))
+    memo[rule] = tuple(out)
+    return memo[rule]
+
+
+def test_config4_exact_distinct_structures_64_grammars(xg):
+    """Section 3.3 at the full vocabulary: the first 64 request grammars of the cross-grammar workload, one plane per
+    position, nothing merged: the pool builds exactly one row per distinct (unfolded rule structure, state), counted
+    the slow way from the oracle's automata."""
+    cfg, vocab, va = load(4)
+    pool = xg.Pool()
+    built = positions = 0
+    distinct = set()
+    interned = {}                                                   # structures are large: count them by identity
+    for ebnf, root in cfg.grammars[:64]:
+        c = xg.compile_grammar(vocab, ebnf, root, pool=pool, stream=_stream(), context_depth=1, merge_equivalent=False, follow_filter=False)
+        built += c.stats.built
+        positions += c.stats.positions
+        orc = oracle.Oracle(ebnf, root)
+        memo = {}
+        for (rule, q) in orc.positions():
+            st = structure_of(orc, rule, memo)
+            distinct.add((interned.setdefault(st, len(interned)), q))
+        del c
+    print("config 4, 64 grammars: %d positions, %d distinct structures, %d rows built" % (positions, len(distinct), built))
+    assert built == pool.stats()[0] == len(distinct) and built < positions / 3
+
+
+def test_config4_full_size_planes_of_late_grammars(xg):
+    """The cross-grammar workload at its full size (256 grammars over 512 tools, one pool, 151,936 tokens): every
+    plane of four grammars compiled late (mostly served by planes that earlier grammars built) equals the oracle's
+    classes for that grammar alone."""
     cfg, vocab, va = load(4)
     pool = xg.Pool()
     keep = {}
+    late = (97, 130, 201, 255)
     for gi, (ebnf, root) in enumerate(cfg.grammars):
         cache = xg.compile_grammar(vocab, ebnf, root, pool=pool, stream=_stream())
-        if gi in (130, 255):
+        if gi in late:
             keep[gi] = cache
     assert pool.stats()[0] < 700000                                  # far fewer rows than the 3 million planes in use
-    rng = random.Random(4)
+    n_planes = 0
     for gi, cache in sorted(keep.items()):
-        assert cache.stats.built < cache.stats.unique / 4            # mostly reuse by now
+        assert cache.stats.built < cache.stats.unique / 3            # mostly reuse by now
         ebnf, root = cfg.grammars[gi]
         orc = oracle.Oracle(ebnf, root)
-        for k in rng.sample(range(cache.num_planes()), 25):
+        for k in range(cache.num_planes()):
             pos, parent = cache.plane_info(k)
             acc, unc = cache.get_planes(k)
             want_a, want_u = planes_of(orc, pos, va, parent, True)
             assert np.array_equal(acc, want_a), ("accepted", gi, pos, parent, diff_words(acc, want_a, cfg.vocab.tokens))
             assert np.array_equal(unc, want_u), ("uncertain", gi, pos, parent, diff_words(unc, want_u, cfg.vocab.tokens))
+        n_planes += cache.num_planes()
+    print("config 4 at full size: %d planes of grammars %s compared" % (n_planes, late))
+    assert n_planes > 20000
 
 
 def test_pool_gives_up_unused_planes_when_full(xg):
@@ -361,6 +503,12 @@ def test_pool_gives_up_unused_planes_when_full(xg):
         others = [xg.compile_grammar(vocab, e, "root", pool=pool, stream=_stream()) for e in grammars]
     assert err.value.code == -4                                     # XG2_EOVERFLOW: every row is in use
     del keep
+    # the failed compile left nothing half-built behind: the same grammars in the same pool, every plane against the oracle
+    n_rows = pool.stats()[0]
+    assert n_rows <= cap
+    for e in grammars:
+        cache, orc = check_planes(xg, cfg, vocab, va, e, "root", pool=pool, max_contexts=1000)
+        del cache, orc
 
 
 def test_long_tokens_and_item_overflow_take_the_slow_path(xg):
