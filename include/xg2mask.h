@@ -195,6 +195,21 @@ int32_t xg2_matcher_frontier(const xg2_matcher*, int32_t* positions_host, int32_
 int32_t xg2_fill_next_token_bitmask(xg2_matcher* const* matchers, int32_t B, int32_t* bitmask_dev,
                                     int64_t row_stride_words, void* hip_stream);
 
+/* The same masks for callers that cannot allocate device memory: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  This call allocates and frees nothing (no hipMalloc, no hipFree, no pinned memory, no
+ * event): its device scratch (staging of the per-row records, candidate words, work lists, the large-capacity item lists)
+ * is one fixed array of 13 MiB per GPU that the library holds until the process ends, and its two pinned host buffers are
+ * made when the first vocabulary is laid out on the device.  Limits per call: B <= 4096 rows, B * ceil(V/32) <= 2^20 mask
+ * words, 1 MiB of per-row records (frontier planes and parser contexts); beyond them the call fails with XG2_EOVERFLOW and
+ * enqueues nothing.  Every plane the frontiers need must have been built (XG2_EINVAL otherwise: a cache compiled just in time
+ * builds, and therefore allocates, inside xg2_fill_next_token_bitmask only).  All calls on one GPU share the one array,
+ * which keeps the previous call's contents (what must start at zero is cleared by the call itself): calls whose device work
+ * overlaps on one GPU race, so keep them on one stream or order them with events.  Arguments, bitmask layout and errors are
+ * otherwise those of xg2_fill_next_token_bitmask; xg2_fill_last_status and xg2_fill_last_recheck_words work after it (they
+ * wait for the stream), xg2_fill_last_device_us does not (no events are recorded).                                          */
+int32_t xg2_fill_next_token_bitmask_noalloc(xg2_matcher* const* matchers, int32_t B, int32_t* bitmask_dev,
+                                            int64_t row_stride_words, void* hip_stream);
+
 /* Measurement aid: device time in microseconds of the work the latest fill call of this process enqueued
  * (context upload, plane union, re-check), from HIP events on its stream.  Waits for that work.   */
 int32_t xg2_fill_last_device_us(float* out);

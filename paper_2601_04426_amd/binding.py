@@ -25,7 +25,7 @@ EXPORTS = [
     "xg2_compile_grammar", "xg2_mask_cache_destroy", "xg2_mask_cache_num_positions", "xg2_mask_cache_num_planes", "xg2_mask_cache_jit_stats",
     "xg2_mask_cache_plane_info", "xg2_mask_cache_find_plane", "xg2_mask_cache_get_planes", "xg2_matcher_create", "xg2_matcher_create_host", "xg2_matcher_destroy",
     "xg2_matcher_accept_token", "xg2_matcher_accept_tokens", "xg2_matcher_reset", "xg2_matcher_is_terminated", "xg2_matcher_frontier",
-    "xg2_fill_next_token_bitmask", "xg2_fill_last_device_us", "xg2_fill_last_status", "xg2_fill_last_recheck_words",
+    "xg2_fill_next_token_bitmask", "xg2_fill_next_token_bitmask_noalloc", "xg2_fill_last_device_us", "xg2_fill_last_status", "xg2_fill_last_recheck_words",
     "xg2_apply_token_bitmask",
 ]
 
@@ -94,6 +94,7 @@ def _load() -> ctypes.CDLL:
     L.xg2_matcher_is_terminated.argtypes = [vp, ctypes.POINTER(i32)]
     L.xg2_matcher_frontier.argtypes = [vp, vp, i32, ctypes.POINTER(i32), ctypes.POINTER(i32)]
     L.xg2_fill_next_token_bitmask.argtypes = [vp, i32, vp, i64, vp]
+    L.xg2_fill_next_token_bitmask_noalloc.argtypes = [vp, i32, vp, i64, vp]
     L.xg2_fill_last_device_us.argtypes = [ctypes.POINTER(ctypes.c_float)]
     L.xg2_fill_last_status.argtypes = [ctypes.POINTER(i32), ctypes.POINTER(i32)]
     L.xg2_fill_last_recheck_words.argtypes = [vp, i32, ctypes.POINTER(i32)]
@@ -299,6 +300,16 @@ def fill_next_token_bitmask(matchers, bitmask_ptr: int, row_stride_words: int, s
         arr = (ctypes.c_void_p * len(matchers))(*[m.h for m in matchers])
     _check(lib.xg2_fill_next_token_bitmask(arr, len(matchers), ctypes.c_void_p(bitmask_ptr), row_stride_words,
                                            ctypes.c_void_p(stream)))
+
+
+def fill_next_token_bitmask_noalloc(matchers, bitmask_ptr: int, row_stride_words: int, stream: int = 0) -> None:
+    """The variant that allocates nothing (fixed device scratch, bounded batch)."""
+    if isinstance(matchers, MatcherBatch):
+        arr = matchers.arr
+    else:
+        arr = (ctypes.c_void_p * len(matchers))(*[m.h for m in matchers])
+    _check(lib.xg2_fill_next_token_bitmask_noalloc(arr, len(matchers), ctypes.c_void_p(bitmask_ptr), row_stride_words,
+                                                   ctypes.c_void_p(stream)))
 
 
 def fill_last_status() -> Tuple[int, bool]:

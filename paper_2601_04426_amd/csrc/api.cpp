@@ -126,6 +126,30 @@ struct Packer {
     template <typename T> T* at(size_t off) const { return reinterpret_cast<T*>(dev + off); }
 };
 
+// What the entry point that allocates nothing needs besides the fixed device array: two pinned host buffers for the
+// per-row records and an event each, made when the first vocabulary goes to the device (set-up), never in the entry
+// point itself.
+struct NoAllocHost {
+    std::mutex mu;
+    bool ready = false;
+    uint8_t* host[2] = {nullptr, nullptr};
+    hipEvent_t done[2] = {nullptr, nullptr};
+    bool in_flight[2] = {false, false};
+    int next = 0;
+    void* scratch_dev = nullptr;
+    void setup() {
+        std::lock_guard<std::mutex> lk(mu);
+        if (ready) return;
+        HIP_CHECK(noalloc_scratch(&scratch_dev));
+        for (int k = 0; k < 2; ++k) {
+            HIP_CHECK(hipHostMalloc((void**)&host[k], kNoAllocStagingBytes, hipHostMallocDefault));
+            HIP_CHECK(hipEventCreateWithFlags(&done[k], hipEventDisableTiming));
+        }
+        ready = true;
+    }
+};
+NoAllocHost& noalloc_host() { static NoAllocHost* h = new NoAllocHost(); return *h; }
+
 void require_device() {
     int n = 0;
     hipError_t e = hipGetDeviceCount(&n);
@@ -233,6 +257,7 @@ struct VocabImpl {
         dv.tok16 = d_tok16.p;
         dv.bytes = d_bytes.p; dv.off = d_off.p; dv.perm = d_perm.p; dv.rank = d_rank.p;
         dv.n_sorted = n_sorted; dv.V = (uint32_t)V; dv.W = W;
+        noalloc_host().setup();
         on_device = true;
     }
 };
@@ -437,8 +462,16 @@ struct FillWorkspace {
     DevBuf<uint32_t> cand_words, work_list, row_count;
     hipEvent_t t_begin = nullptr, t_end = nullptr;          // around the device work of the latest fill
     const uint32_t* last_flags = nullptr;                   // device: overflow-list length and flag of the latest fill
-    int32_t last_B = 0;                                     // rows of the latest fill (row_count holds their candidate-word counts)
-    bool timed = false;
+    int32_t last_B = 0;                                     // rows of the latest fill
+    const uint32_t* last_counts = nullptr;                  // device: their candidate-word counts
+    hipStream_t last_stream = nullptr;
+    bool timed = false;                                     // the latest fill recorded its events
+    bool any = false;                                       // there has been a fill
+    // waits for the device work of the latest fill
+    void wait_last() {
+        if (timed) HIP_CHECK(hipEventSynchronize(t_end));
+        else HIP_CHECK(hipStreamSynchronize(last_stream));
+    }
     void ensure_scratch(size_t words, size_t rows) {
         if (row_count.n < rows) row_count.alloc(rows * 2);
         if (!t_begin) { HIP_CHECK(hipEventCreate(&t_begin)); HIP_CHECK(hipEventCreate(&t_end)); }
@@ -1419,8 +1452,14 @@ int32_t xg2_matcher_frontier(const xg2_matcher* m, int32_t* positions_host, int3
     return XG2_OK;
 }
 
-int32_t xg2_fill_next_token_bitmask(xg2_matcher* const* matchers, int32_t B, int32_t* bitmask_dev, int64_t row_stride_words,
-                                    void* hip_stream) {
+}  // extern "C"
+
+namespace {
+// The body of both fill entry points.  no_alloc: every device buffer comes from the library's fixed scratch array, the
+// per-row records are copied from ordinary host memory, nothing is allocated and nothing is built (a plane that is
+// still missing is an error), no events are recorded.
+int32_t fill_common(xg2_matcher* const* matchers, int32_t B, int32_t* bitmask_dev, int64_t row_stride_words,
+                    void* hip_stream, bool no_alloc) {
     return guarded([&]() -> int32_t {
         if (B < 0 || (B > 0 && (!matchers || !bitmask_dev))) return fail(XG2_EINVAL, "xg2_fill_next_token_bitmask: bad argument");
         if (B == 0) return XG2_OK;
@@ -1433,7 +1472,12 @@ int32_t xg2_fill_next_token_bitmask(xg2_matcher* const* matchers, int32_t B, int
         }
         VocabImpl& V = *matchers[0]->p->vocab;
         if (row_stride_words < (int64_t)V.W) return fail(XG2_EINVAL, "xg2_fill_next_token_bitmask: row stride smaller than ceil(V/32)");
-        V.ensure_device();
+        if (no_alloc) {
+            if (!V.on_device) return fail(XG2_EINVAL, "xg2_fill_next_token_bitmask_noalloc: the vocabulary is not on the device");
+            if ((size_t)B > kNoAllocMaxRows || (size_t)B * V.W > kNoAllocMaskWords)
+                return fail(XG2_EOVERFLOW, "xg2_fill_next_token_bitmask_noalloc: batch beyond the fixed scratch (at most " + std::to_string(kNoAllocMaxRows) +
+                                           " rows and " + std::to_string(kNoAllocMaskWords) + " mask words, rows x ceil(V/32), per call)");
+        } else V.ensure_device();
 
         // caches compiled just in time (section 3.5): the planes this step's frontiers need and that hold no row yet
         // are built first, on the same stream
@@ -1469,6 +1513,8 @@ int32_t xg2_fill_next_token_bitmask(xg2_matcher* const* matchers, int32_t B, int
                 std::sort(v.begin(), v.end());
                 v.erase(std::unique(v.begin(), v.end()), v.end());
                 if (v.empty()) continue;
+                if (no_alloc) return fail(XG2_EINVAL, "xg2_fill_next_token_bitmask_noalloc: a plane of a cache compiled just in time is not built yet "
+                                                      "(building allocates: use xg2_fill_next_token_bitmask for such caches)");
                 CacheImpl& C = *kv.first;
                 std::lock_guard<std::mutex> pool_lock(C.pool->mu);
                 std::lock_guard<std::mutex> slow_lock(slow().mu);
@@ -1524,49 +1570,97 @@ int32_t xg2_fill_next_token_bitmask(xg2_matcher* const* matchers, int32_t B, int
 
         std::lock_guard<std::mutex> ws_lock(fill_ws().mu);
         std::lock_guard<std::mutex> slow_lock(slow().mu);
-        slow().ensure();
-        SlowScratch S = slow().s;
-        FillSlot& slot = fill_ws().acquire(total);
-        std::memcpy(slot.host + o_rows, rows.data(), rows.size() * sizeof(FillRow));
-        if (!front.empty()) std::memcpy(slot.host + o_front, front.data(), front.size() * sizeof(uint64_t));
-        if (!items.empty()) std::memcpy(slot.host + o_items, items.data(), items.size() * sizeof(uint32_t));
-        if (!wait.empty()) std::memcpy(slot.host + o_wait, wait.data(), wait.size() * sizeof(uint32_t));
-        if (!wait_off.empty()) std::memcpy(slot.host + o_woff, wait_off.data(), wait_off.size() * sizeof(uint32_t));
-        std::memcpy(slot.host + o_tabs, tables.data(), tables.size() * sizeof(DevTables));
-        std::memset(slot.host + o_zero, 0, 4 * sizeof(uint32_t));
-        fill_ws().ensure_scratch((size_t)B * V.W, (size_t)B);
-        HIP_CHECK(hipEventRecord(fill_ws().t_begin, stream));
-        upload_pinned(slot.dev, slot.host, total, stream);
+        auto pack = [&](uint8_t* host) {
+            std::memcpy(host + o_rows, rows.data(), rows.size() * sizeof(FillRow));
+            if (!front.empty()) std::memcpy(host + o_front, front.data(), front.size() * sizeof(uint64_t));
+            if (!items.empty()) std::memcpy(host + o_items, items.data(), items.size() * sizeof(uint32_t));
+            if (!wait.empty()) std::memcpy(host + o_wait, wait.data(), wait.size() * sizeof(uint32_t));
+            if (!wait_off.empty()) std::memcpy(host + o_woff, wait_off.data(), wait_off.size() * sizeof(uint32_t));
+            std::memcpy(host + o_tabs, tables.data(), tables.size() * sizeof(DevTables));
+            std::memset(host + o_zero, 0, 4 * sizeof(uint32_t));
+        };
+        SlowScratch S{};
         FillBatch F{};
-        F.rows = reinterpret_cast<const FillRow*>(slot.dev + o_rows); F.B = (uint32_t)B;
-        F.front_planes = reinterpret_cast<const uint64_t*>(slot.dev + o_front);
-        F.ctx_items = reinterpret_cast<const uint32_t*>(slot.dev + o_items);
-        F.ctx_wait = reinterpret_cast<const uint2*>(slot.dev + o_wait);
-        F.ctx_wait_off = reinterpret_cast<const uint32_t*>(slot.dev + o_woff);
-        F.tables = reinterpret_cast<const DevTables*>(slot.dev + o_tabs);
+        uint8_t* dev = nullptr;
+        FillSlot* slot = nullptr;
+        if (no_alloc) {
+            // everything lives in the fixed array: [staging | candidate words | work lists | row counts | overflow list | item lists]
+            if (total > kNoAllocStagingBytes)
+                return fail(XG2_EOVERFLOW, "xg2_fill_next_token_bitmask_noalloc: the matchers' parser contexts exceed the fixed staging area");
+            NoAllocHost& NH = noalloc_host();
+            if (!NH.ready) return fail(XG2_EINVAL, "xg2_fill_next_token_bitmask_noalloc: the library has not been set up on this device");
+            void* base = nullptr;
+            HIP_CHECK(noalloc_scratch(&base));                       // a table look-up after the first time on a device
+            uint8_t* p = static_cast<uint8_t*>(base);
+            dev = p; p += kNoAllocStagingBytes;
+            F.cand_words = reinterpret_cast<uint32_t*>(p); p += kNoAllocMaskWords * 4;
+            F.work_list = reinterpret_cast<uint32_t*>(p); p += kNoAllocMaskWords * 4;
+            F.row_count = reinterpret_cast<uint32_t*>(p); p += kNoAllocMaxRows * 4;
+            S.list = reinterpret_cast<uint32_t*>(p); S.list_cap = kNoAllocListCap; p += (size_t)kNoAllocListCap * 8;
+            S.mem = reinterpret_cast<uint32_t*>(p); S.n_lanes = kNoAllocSlowLanes;
+            const int k = NH.next;
+            NH.next ^= 1;
+            if (NH.in_flight[k]) { HIP_CHECK(hipEventSynchronize(NH.done[k])); NH.in_flight[k] = false; }   // the call before last has read it
+            pack(NH.host[k]);
+            upload_pinned(dev, NH.host[k], total, stream);
+            HIP_CHECK(hipEventRecord(NH.done[k], stream));
+            NH.in_flight[k] = true;
+        } else {
+            slow().ensure();
+            S = slow().s;
+            slot = &fill_ws().acquire(total);
+            pack(slot->host);
+            fill_ws().ensure_scratch((size_t)B * V.W, (size_t)B);
+            HIP_CHECK(hipEventRecord(fill_ws().t_begin, stream));
+            upload_pinned(slot->dev, slot->host, total, stream);
+            dev = slot->dev;
+            F.cand_words = fill_ws().cand_words.p; F.work_list = fill_ws().work_list.p;
+            F.row_count = fill_ws().row_count.p;
+        }
+        F.rows = reinterpret_cast<const FillRow*>(dev + o_rows); F.B = (uint32_t)B;
+        F.front_planes = reinterpret_cast<const uint64_t*>(dev + o_front);
+        F.ctx_items = reinterpret_cast<const uint32_t*>(dev + o_items);
+        F.ctx_wait = reinterpret_cast<const uint2*>(dev + o_wait);
+        F.ctx_wait_off = reinterpret_cast<const uint32_t*>(dev + o_woff);
+        F.tables = reinterpret_cast<const DevTables*>(dev + o_tabs);
         F.eos_id = (uint32_t)V.eos;
-        fill_ws().ensure_scratch((size_t)B * V.W, (size_t)B);
-        F.cand_words = fill_ws().cand_words.p; F.work_list = fill_ws().work_list.p;
-        F.row_count = fill_ws().row_count.p;
-        S.count = reinterpret_cast<uint32_t*>(slot.dev + o_zero);          // this call's overflow counter and flag, zero on arrival
+        S.count = reinterpret_cast<uint32_t*>(dev + o_zero);               // this call's overflow counter and flag, zero on arrival
         launch_fill(F, V.dv, bitmask_dev, row_stride_words, S, stream);
         launch_recheck_slow(F, V.dv, bitmask_dev, row_stride_words, S, stream);
         HIP_CHECK(hipGetLastError());
-        HIP_CHECK(hipEventRecord(fill_ws().t_end, stream));
-        fill_ws().timed = true;
         fill_ws().last_flags = S.count;
+        fill_ws().last_counts = F.row_count;
         fill_ws().last_B = B;
-        HIP_CHECK(hipEventRecord(slot.done, stream));
-        slot.in_flight = true;
+        fill_ws().last_stream = stream;
+        fill_ws().timed = !no_alloc;
+        fill_ws().any = true;
+        if (!no_alloc) {
+            HIP_CHECK(hipEventRecord(fill_ws().t_end, stream));
+            HIP_CHECK(hipEventRecord(slot->done, stream));
+            slot->in_flight = true;
+        }
         return XG2_OK;
     });
+}
+}  // namespace
+
+extern "C" {
+
+int32_t xg2_fill_next_token_bitmask(xg2_matcher* const* matchers, int32_t B, int32_t* bitmask_dev, int64_t row_stride_words,
+                                    void* hip_stream) {
+    return fill_common(matchers, B, bitmask_dev, row_stride_words, hip_stream, false);
+}
+
+int32_t xg2_fill_next_token_bitmask_noalloc(xg2_matcher* const* matchers, int32_t B, int32_t* bitmask_dev, int64_t row_stride_words,
+                                            void* hip_stream) {
+    return fill_common(matchers, B, bitmask_dev, row_stride_words, hip_stream, true);
 }
 
 int32_t xg2_fill_last_device_us(float* out) {
     return guarded([&]() -> int32_t {
         if (!out) return fail(XG2_EINVAL, "xg2_fill_last_device_us: null out");
         std::lock_guard<std::mutex> ws_lock(fill_ws().mu);
-        if (!fill_ws().timed) return fail(XG2_EINVAL, "xg2_fill_last_device_us: no fill call yet");
+        if (!fill_ws().timed) return fail(XG2_EINVAL, "xg2_fill_last_device_us: the latest fill call recorded no events (none yet, or the one that allocates nothing)");
         HIP_CHECK(hipEventSynchronize(fill_ws().t_end));
         float ms = 0.f;
         HIP_CHECK(hipEventElapsedTime(&ms, fill_ws().t_begin, fill_ws().t_end));
@@ -1578,8 +1672,8 @@ int32_t xg2_fill_last_device_us(float* out) {
 int32_t xg2_fill_last_status(int32_t* large_capacity_tokens, int32_t* overflowed) {
     return guarded([&]() -> int32_t {
         std::lock_guard<std::mutex> ws_lock(fill_ws().mu);
-        if (!fill_ws().timed) return fail(XG2_EINVAL, "xg2_fill_last_status: no fill call yet");
-        HIP_CHECK(hipEventSynchronize(fill_ws().t_end));
+        if (!fill_ws().any) return fail(XG2_EINVAL, "xg2_fill_last_status: no fill call yet");
+        fill_ws().wait_last();
         uint32_t words[2] = {0, 0};
         HIP_CHECK(hipMemcpy(words, fill_ws().last_flags, sizeof(words), hipMemcpyDeviceToHost));
         if (large_capacity_tokens) *large_capacity_tokens = (int32_t)words[0];
@@ -1592,10 +1686,10 @@ int32_t xg2_fill_last_recheck_words(int32_t* words_host, int32_t cap, int32_t* n
     return guarded([&]() -> int32_t {
         if (cap < 0 || (cap > 0 && !words_host)) return fail(XG2_EINVAL, "xg2_fill_last_recheck_words: bad argument");
         std::lock_guard<std::mutex> ws_lock(fill_ws().mu);
-        if (!fill_ws().timed) return fail(XG2_EINVAL, "xg2_fill_last_recheck_words: no fill call yet");
-        HIP_CHECK(hipEventSynchronize(fill_ws().t_end));
+        if (!fill_ws().any) return fail(XG2_EINVAL, "xg2_fill_last_recheck_words: no fill call yet");
+        fill_ws().wait_last();
         const int32_t n = std::min(cap, fill_ws().last_B);
-        if (n > 0) HIP_CHECK(hipMemcpy(words_host, fill_ws().row_count.p, (size_t)n * sizeof(uint32_t), hipMemcpyDeviceToHost));
+        if (n > 0) HIP_CHECK(hipMemcpy(words_host, fill_ws().last_counts, (size_t)n * sizeof(uint32_t), hipMemcpyDeviceToHost));
         if (n_rows) *n_rows = fill_ws().last_B;
         return XG2_OK;
     });

@@ -113,6 +113,18 @@ void launch_recheck_slow(const FillBatch& F, const DevVocab& Vd, int32_t* bitmas
 // a kernel: for the small per-call uploads this has less latency than the copy engine.
 void launch_upload(void* dst_dev, const void* src_host_mapped, size_t bytes, hipStream_t stream);
 
+// The entry point that allocates nothing works in a fixed device array of the library (one per GPU, kept until the
+// process ends) instead of buffers that grow with the batch: staging of the per-row records, candidate words and
+// work lists, row counts, the overflow list and the large-capacity item lists.  noalloc_scratch gives the array's
+// device address on the current device (looked up once per device).
+constexpr size_t kNoAllocStagingBytes = (size_t)1 << 20;            // per-row records, frontier planes, context slices
+constexpr size_t kNoAllocMaskWords = (size_t)1 << 20;               // rows x ceil(V/32) of one call
+constexpr size_t kNoAllocMaxRows = 4096;
+constexpr uint32_t kNoAllocSlowLanes = 256, kNoAllocListCap = 1u << 16;
+constexpr size_t kNoAllocScratchBytes = kNoAllocStagingBytes + 2 * kNoAllocMaskWords * 4 + kNoAllocMaxRows * 4
+                                        + (size_t)kNoAllocListCap * 8 + (size_t)kNoAllocSlowLanes * kSlowSlots * 4;
+hipError_t noalloc_scratch(void** ptr_out);
+
 void launch_apply(void* logits_dev, int32_t dtype, int32_t B, int32_t V, int64_t row_stride_elems,
                   const int32_t* bitmask_dev, int64_t bm_row_stride_words, hipStream_t stream);
 

@@ -10,6 +10,7 @@
 //   k_apply_*      logits of disallowed tokens := -infinity, in place    (section 2.1)
 // No MFMA: nothing here is a contraction.  All device writes are vector stores or LDS/L2 atomics.
 #include <algorithm>
+#include <mutex>
 
 #include "device.hpp"
 #include "earley_core.hpp"
@@ -660,6 +661,31 @@ __global__ __launch_bounds__(256) void k_apply_scalar(E* logits, long long row_s
 }
 
 }  // namespace
+
+// ---- scratch of the entry point that allocates nothing ---------------------------------------------
+// One array per GPU the library runs on, held until the process ends.  In host code the array's name is only
+// a stand-in: the device address comes from hipGetSymbolAddress, once per device, and only that address is
+// handed to kernels and copies.
+static __device__ __align__(256) unsigned char scratch[kNoAllocScratchBytes];
+
+hipError_t noalloc_scratch(void** ptr_out) {
+    constexpr int kMaxDevices = 64;
+    static void* ptr_of[kMaxDevices] = {};
+    static std::mutex mu;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lk(mu);
+    if (!ptr_of[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        ptr_of[dev] = p;
+    }
+    *ptr_out = ptr_of[dev];
+    return hipSuccess;
+}
 
 void launch_build(const DevTables& T, const DevVocab& Vd, const BuildPlan& P, const SlowScratch& S, hipStream_t stream) {
     if (P.n_chunks == 0) return;
