@@ -75,6 +75,8 @@ def main() -> int:
                          "report planes built once versus positions, and checks/s (adds build launches of other sizes)")
     ap.add_argument("--jit", action="store_true", help="also time 32 decode steps on a cache compiled just in time (adds small launches of "
                                                        "the build and fill kernels, so per-kernel averages of a profile no longer match the main figures)")
+    ap.add_argument("--build-only", action="store_true",
+                    help="time cache builds of --config only (steps = builds; no decode, no oracle): the command the build kernel's profiles are taken with")
     ap.add_argument("--cpu-positions", type=int, default=4096, help="positions in the oracle's timed sample")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -102,6 +104,35 @@ def main() -> int:
     W = vocab.words
     n_checkable = sum(1 for i, t in enumerate(cfg.vocab.tokens) if t and i not in cfg.vocab.special_ids)
     tok_bytes = sum(len(t) for i, t in enumerate(cfg.vocab.tokens) if t and i not in cfg.vocab.special_ids)
+
+    if args.build_only:
+        def roof(stats, k_ms):
+            b = int(stats.executed_token_bytes) + 4.25 * int(stats.executed_checks)
+            return {"kernel": "k_build", "bound": "hbm", "achieved": b / (k_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": b / (k_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "traffic": None, "algorithmic_bytes_per_launch": b}
+        ks, ds, hs = [], [], []
+        t_begin = None
+        for it in range(args.warmup + args.steps):
+            if it == args.warmup:
+                torch.cuda.synchronize()
+                t_begin = time.perf_counter()
+            c = xg.compile_grammar(vocab, ebnf, root, stream=stream)
+            st = c.stats
+            if it >= args.warmup:
+                ks.append(st.kernel_ms); ds.append(st.device_ms); hs.append(st.host_lower_ms)
+            del c
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t_begin
+        k_ms, d_ms = sum(ks) / len(ks), sum(ds) / len(ds)
+        print(json.dumps({"metric": "mask-cache build (position x token) checks/s", "value": int(st.checks) / (d_ms * 1e-3), "unit": "checks/s",
+                          "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": wall / args.steps * 1e3, "higher_is_better": True,
+                          "scaling": "weak", "vs_baseline": None, "dtype": "u8", "data": "synthetic",
+                          "config": {"workload": cfg.name + " (cache builds only)", "config_index": cfg.index, "vocab": V, "positions": int(st.positions),
+                                     "built_positions": int(st.built), "checks_per_build": int(st.checks), "executed_checks": int(st.executed_checks)},
+                          "build": {"device_ms": d_ms, "kernel_ms": k_ms, "host_lower_ms": sum(hs) / len(hs),
+                                    "executed_pairs_per_s": int(st.executed_checks) / (k_ms * 1e-3)},
+                          "roofline": roof(st, k_ms)}))
+        return 0
 
     # matchers at random depths of their own sentences (set-up, untimed)
     cache0 = xg.compile_grammar(vocab, ebnf, root, stream=stream)

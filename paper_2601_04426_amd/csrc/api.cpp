@@ -553,7 +553,7 @@ std::shared_ptr<GrammarImpl> make_grammar(const char* ebnf, size_t len, const ch
     if (!ebnf || !root) throw GrammarError("null grammar text or root rule");
     auto gi = std::make_shared<GrammarImpl>();
     gi->g = lower_grammar(std::string(ebnf, len), root);
-    if ((uint32_t)gi->g.n_states > kSidMask) throw std::length_error("grammar has too many automaton states");
+    if ((uint32_t)gi->g.n_states + 1 > kSidMask) throw std::length_error("grammar has too many automaton states");
     gi->ft = flatten(gi->g);
     for (auto& r : gi->g.rules) gi->rule_names.push_back(r.name);
     return gi;
@@ -752,12 +752,19 @@ int32_t build_planes(CacheImpl& cache, const std::vector<int32_t>& todo, hipStre
     {
         size_t n_chunks = 0;
         for (const uint4& r : ranges) n_chunks += (r.z - r.y + ((r.w & kChunkHeavy) ? kHeavyChunk : kBuildChunk) - 1) / ((r.w & kChunkHeavy) ? kHeavyChunk : kBuildChunk);
-        chunks.reserve(n_chunks);
+        chunks.reserve(2 * n_chunks);
         for (uint32_t pass_heavy : {kChunkHeavy, 0u})
             for (const uint4& r : ranges) {
                 if ((r.w & kChunkHeavy) != pass_heavy) continue;
                 const uint32_t step = pass_heavy ? kHeavyChunk : kBuildChunk;
-                for (uint32_t c = r.y; c < r.z; c += step) chunks.push_back(make_uint4(r.x, c, std::min(r.z, c + step), r.w));
+                // the second half of the record: what phase 1 needs of the plane (first start item, number of items, row address)
+                const uint4& pc = plane_ctx[r.x];
+                const uint64_t row = (uint64_t)(uintptr_t)build_rows[r.x];
+                const uint4 second = make_uint4(ctx_items[pc.x], pc.y, (uint32_t)row, (uint32_t)(row >> 32));
+                for (uint32_t c = r.y; c < r.z; c += step) {
+                    chunks.push_back(make_uint4(r.x, c, std::min(r.z, c + step), r.w));
+                    chunks.push_back(second);
+                }
             }
     }
 
@@ -787,13 +794,14 @@ int32_t build_planes(CacheImpl& cache, const std::vector<int32_t>& todo, hipStre
         cache.dt.trans = tab.at<const uint32_t>(o_trans);
         cache.dt.byte_class_words = tab.at<const uint32_t>(o_cls);
         cache.dt.n_classes = ft.n_classes;
+        cache.dt.sink = ft.sink;
         cache.dt.site_off = tab.at<const uint32_t>(o_soff);
         cache.dt.site_tgt = tab.at<const uint32_t>(o_stgt);
     }
     uint32_t* d_counts = tab.at<uint32_t>(o_zero) + 8;
     S.count = tab.at<uint32_t>(o_zero) + 4;                       // this call's own overflow counter and flag, zero on arrival
     BuildPlan P{};
-    P.chunk = tab.at<const uint4>(o_chunks); P.n_chunks = (uint32_t)chunks.size();
+    P.chunk = tab.at<const uint4>(o_chunks); P.n_chunks = (uint32_t)(chunks.size() / 2);
     P.plane_ctx = tab.at<const uint4>(o_pctx);
     P.ctx_items = tab.at<const uint32_t>(o_items);
     P.ctx_wait = tab.at<const uint2>(o_wait); P.ctx_wait_off = tab.at<const uint32_t>(o_wait_off);

@@ -10,9 +10,10 @@ struct DevTables {                       // packed grammar tables (see tables.hp
     const uint4* state;                  // {rule, expansion offset, n_items, n_triples}: loaded only for states with
                                          // rule edges (what entering them adds) and for completing items (their rule)
     const uint32_t* exp_list;            // expansions: item words, then {rule, target} pairs
-    const uint32_t* trans;               // [n_states * n_classes] state reference of the byte target or 0xFFFFFFFF
+    const uint32_t* trans;               // [(n_states + 1) * n_classes] state reference of the byte target, or `sink`
     const uint32_t* byte_class_words;    // [64] byte -> class, four per word
     uint32_t n_classes;
+    uint32_t sink;                       // the state (without flags) that missing edges lead to; its own row leads back to it
     const uint32_t* site_off;            // per rule: states in which referencing rules continue (CSR)
     const uint32_t* site_tgt;
 };
@@ -29,7 +30,10 @@ struct DevVocab {                        // byte-sorted vocabulary in HBM
     uint32_t V, W;
 };
 
-// Work plan of one cache build.  Chunk c covers sorted ranks [chunk[c].y, chunk[c].z) of plane chunk[c].x
+// Work plan of one cache build.  A chunk is a record of two uint4: the first {plane, first rank, end rank, flags}, the
+// second what the automaton walk needs of the plane without a further load {first item of the start set, number of
+// its items, row address low, row address high}.  Below, chunk[c] stands for the first half of record c.
+// Chunk c covers sorted ranks [chunk[c].y, chunk[c].z) of plane chunk[c].x
 // (at most kBuildChunk tokens, all with a first byte the plane's start set can read); with bit 0 of chunk[c].w
 // set, y and z index DevVocab::long_rank instead and the ranks are read from there (a plane that needs only
 // its long tokens checked).  The workgroups of a persistent grid take chunks round-robin.  plane_ctx[k] = {first item, number of items, first wait offset, H} describes the closed start
@@ -49,11 +53,12 @@ constexpr uint32_t kBuildChunk = XG2_BUILD_CHUNK;
 constexpr uint32_t kHeavyChunk = XG2_HEAVY_CHUNK;             // chunk size of planes whose tokens all take the Earley steps
 static_assert(kHeavyChunk <= kBuildChunk, "the deferred list is sized for kBuildChunk");
 struct BuildPlan {
-    const uint4* chunk; uint32_t n_chunks;
+    const uint4* chunk; uint32_t n_chunks;                      // 2 * n_chunks uint4
     const uint4* plane_ctx;                                     // [n_planes]
     const uint32_t* ctx_items; const uint2* ctx_wait; const uint32_t* ctx_wait_off;
     uint32_t* const* plane_ptr;                                 // [n_planes] accepted row; uncertain row at + W words
     uint32_t follow_filter;                                     // drop uncertain tokens that no reference site can continue
+    uint32_t large_lists, list_k, list_wm;                      // set by launch_build: long or short item lists; item and wait-entry capacity a lane
 };
 
 struct SlowScratch {                     // large-capacity per-lane Earley scratch in device memory
@@ -77,7 +82,7 @@ void launch_copy_masked(const CopyJob* jobs_dev, uint32_t n_jobs, uint32_t W, hi
 struct FirstByteCopyJob { uint32_t* dst; const uint32_t* src; uint32_t bytes[8]; };
 void launch_copy_first_byte(const FirstByteCopyJob* jobs_dev, uint32_t n_jobs, const uint8_t* first_byte_dev, uint32_t W, hipStream_t stream);
 
-void launch_build(const DevTables& T, const DevVocab& Vd, const BuildPlan& P, const SlowScratch& S, hipStream_t stream);
+void launch_build(const DevTables& T, const DevVocab& Vd, BuildPlan P, const SlowScratch& S, hipStream_t stream);
 void launch_build_slow(const DevTables& T, const DevVocab& Vd, const BuildPlan& P, const SlowScratch& S, hipStream_t stream);
 // counts_dev[2p], counts_dev[2p + 1] = set bits of the accepted and of the uncertain row of plane p
 void launch_popcount(const uint32_t* const* plane_ptr_dev, uint32_t n_pos, uint32_t W, uint32_t* counts_dev, hipStream_t stream);

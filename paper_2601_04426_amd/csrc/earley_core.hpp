@@ -11,8 +11,10 @@ namespace core {
 
 #if defined(__HIP_DEVICE_COMPILE__)
 __device__ __forceinline__ uint32_t funnel_shift(uint32_t hi, uint32_t lo, uint32_t s) { return __builtin_amdgcn_alignbit(hi, lo, s); }
+__device__ __forceinline__ bool wave_any(bool x) { return __any(x); }
 #else
 __device__ __forceinline__ uint32_t funnel_shift(uint32_t hi, uint32_t lo, uint32_t s) { return (uint32_t)(((((unsigned long long)hi) << 32) | lo) >> s); }
+__device__ __forceinline__ bool wave_any(bool x) { return x; }      // the host build steps one lane at a time
 #endif
 
 // A state reference is 21 bits: state id (18) | has byte edge | has rule edge | final; an item is a state
@@ -21,7 +23,7 @@ constexpr uint32_t SID_MASK = (1u << 18) - 1;
 constexpr uint32_t F_BYTE = 1u << 18, F_REF = 1u << 19, F_FINAL = 1u << 20;
 constexpr uint32_t REF_BITS = 21;
 constexpr uint32_t ROOT_ORIGIN = (1u << (32 - REF_BITS)) - 1;
-constexpr uint32_t NO_TARGET = 0xFFFFFFFFu;
+constexpr uint32_t NO_TARGET = 0xFFFFFFFFu;          // "none" marker in registers; the tables mark a missing edge by DevTables::sink
 
 constexpr int RES_ALIVE = 1, RES_EARLY = 2, RES_OVERFLOW = 4;
 
@@ -33,6 +35,7 @@ struct DevCtx {                      // closed item set to continue from, plus w
 // ---- token bytes, consumed front to back: in registers (at most 16) or in device memory ----------------
 struct RegBytes {
     uint4 v;                                                    // a 128-bit shift register: no indexed access, no spill
+    __device__ uint32_t peek() const { return v.x & 0xFF; }     // the byte next() would return
     __device__ uint32_t next() {
         const uint32_t b = v.x & 0xFF;
         v.x = funnel_shift(v.y, v.x, 8);
@@ -44,6 +47,7 @@ struct RegBytes {
 };
 struct MemBytes {
     const uint8_t* p;
+    __device__ uint32_t peek() const { return *p; }
     __device__ uint32_t next() { return *p++; }
 };
 
@@ -64,7 +68,7 @@ __device__ __forceinline__ bool add_nxt(S& st, uint32_t item, int& nn, bool& ful
     bool found = false;                                          // no way out of the loop: one compare more costs less than the exit
     for (int k = 0; k < nn; ++k) found |= st.get_nxt(k) == item;
     if (found) return false;
-    if (nn == S::K) { full = true; return false; }
+    if (nn == st.K) { full = true; return false; }
     st.set_nxt(nn++, item);
     return true;                                                 // new in the list
 }
@@ -75,13 +79,21 @@ __device__ __forceinline__ void add_wait(S& st, uint32_t rule, uint32_t tgt, int
     bool found = false;
     for (int k = wbeg; k < nw; ++k) found |= (st.wait_tgt(k) == tgt) & (st.wait_rule(k) == rule);
     if (found) return;
-    if (nw == S::WM) { full = true; return; }
+    if (nw == st.WM) { full = true; return; }
     st.set_wait(nw++, rule, tgt);
 }
 
+// One byte of lookahead keeps the lists short: an item whose state has byte edges only and is not final can do nothing
+// but scan, so if it has no edge for the byte that comes next it is left out (`la` = class of that byte, or NO_TARGET
+// after the token's last byte, where every item counts because only "is the set empty" is asked).
+__device__ __forceinline__ bool inert(const DevTables& T, uint32_t ref, uint32_t la) {
+    return la != NO_TARGET && (ref & (F_BYTE | F_REF | F_FINAL)) == F_BYTE && T.trans[(ref & SID_MASK) * T.n_classes + la] == T.sink;
+}
+
 template <class S>
-__device__ __forceinline__ void enter(const DevTables& T, S& st, uint32_t ref, uint32_t origin, uint32_t set_idx, int& nn, int& nw, int wbeg, bool& full) {
+__device__ __forceinline__ void enter(const DevTables& T, S& st, uint32_t ref, uint32_t origin, uint32_t set_idx, uint32_t la, int& nn, int& nw, int wbeg, bool& full) {
     if ((ref & (F_BYTE | F_FINAL)) || !(ref & F_REF)) {
+        if (inert(T, ref, la)) return;
         if (!add_nxt(st, ref | (origin << REF_BITS), nn, full)) return;      // there already (or no room): nothing more to add
     }
     if (ref & F_REF) {
@@ -89,6 +101,7 @@ __device__ __forceinline__ void enter(const DevTables& T, S& st, uint32_t ref, u
         const uint32_t* e = T.exp_list + d.y;
         for (uint32_t k = 0; k < d.z; ++k) {
             const uint32_t w = e[k];
+            if (inert(T, w, la)) continue;
             add_nxt(st, (w & REF_MASK) | (((w & EXP_CURRENT) ? set_idx : origin) << REF_BITS), nn, full);
         }
         e += d.z;
@@ -113,7 +126,7 @@ __device__ __forceinline__ void enter(const DevTables& T, S& st, uint32_t ref, u
 // set shrinks back to one such item (older wait entries stay where they are).
 template <class S, bool FOLLOW = false, class BYTES = RegBytes>
 __device__ int scan_token(const DevTables& T, const uint32_t* cls_words, const DevCtx& C, BYTES tok, int n, S& st) {
-    if (n > S::MAXLEN || (int)C.n_items > S::K) return RES_OVERFLOW;
+    if (n > S::MAXLEN || (int)C.n_items > st.K) return RES_OVERFLOW;
     if (C.H + (uint32_t)n > ROOT_ORIGIN) return RES_OVERFLOW;       // the new sets C.H .. C.H + n - 1 must stay below the root mark
     int nc = (int)C.n_items;
     uint32_t one = nc == 1 ? C.items[0] : 0u;
@@ -129,7 +142,7 @@ __device__ int scan_token(const DevTables& T, const uint32_t* cls_words, const D
             const uint32_t b = tok.next();
             const uint32_t cls = (cls_words[b >> 2] >> ((b & 3) * 8)) & 0xFF;
             const uint32_t tgt = T.trans[(one & SID_MASK) * T.n_classes + cls];
-            if (tgt == NO_TARGET) return res;                    // dead
+            if (tgt == T.sink) return res;                       // dead
             if (tgt & (F_REF | F_FINAL)) { pending = tgt; single = false; break; }   // this state predicts or completes
             one = tgt | (one & ~REF_MASK);
             ++i;
@@ -141,6 +154,7 @@ __device__ int scan_token(const DevTables& T, const uint32_t* cls_words, const D
         const int wbeg = nw;
         const uint32_t set_idx = C.H + (uint32_t)i;
         bool full = false;
+        uint32_t la = NO_TARGET;                                 // class of byte i + 1, if there is one
         {
             // scanner: one table word per scannable item (the automaton walk has looked its one word up already)
             const bool walked = pending != NO_TARGET;
@@ -148,6 +162,10 @@ __device__ int scan_token(const DevTables& T, const uint32_t* cls_words, const D
             if (!walked) {
                 const uint32_t b = tok.next();
                 cls = (cls_words[b >> 2] >> ((b & 3) * 8)) & 0xFF;
+            }
+            if (i + 1 < n) {                                     // (the automaton walk has consumed byte i already)
+                const uint32_t b = tok.peek();
+                la = (cls_words[b >> 2] >> ((b & 3) * 8)) & 0xFF;
             }
             const int n_scan = walked ? 1 : nc;
             for (int k = 0; k < n_scan; ++k) {
@@ -158,7 +176,7 @@ __device__ int scan_token(const DevTables& T, const uint32_t* cls_words, const D
                     tgt = T.trans[(it & SID_MASK) * T.n_classes + cls];
                     origin = it >> REF_BITS;
                 }
-                if (tgt != NO_TARGET) enter(T, st, tgt, origin, set_idx, nn, nw, wbeg, full);
+                if (tgt != T.sink) enter(T, st, tgt, origin, set_idx, la, nn, nw, wbeg, full);
             }
         }
         // completer over the growing item list (prediction happened on entering).  What a completed item brings in
@@ -185,7 +203,7 @@ __device__ int scan_token(const DevTables& T, const uint32_t* cls_words, const D
                 if (root_end) { wr = rule; wt = T.site_tgt[k] | (ROOT_ORIGIN << REF_BITS); }
                 else if (local) { wr = st.wait_rule(k); wt = st.wait_tgt(k); }
                 else { const uint2 w = C.wait[k]; wr = w.x; wt = w.y; }
-                if (wr == rule) enter(T, st, wt & REF_MASK, wt >> REF_BITS, set_idx, nn, nw, wbeg, full);
+                if (wr == rule) enter(T, st, wt & REF_MASK, wt >> REF_BITS, set_idx, la, nn, nw, wbeg, full);
             }
         }
         if (full) return RES_OVERFLOW;
@@ -201,6 +219,36 @@ __device__ int scan_token(const DevTables& T, const uint32_t* cls_words, const D
         }
     }
     return res | RES_ALIVE;
+}
+
+
+// Phase 1 for a start set that is one item with byte edges only: the plain automaton walk of a wave's 64 tokens,
+// without a branch inside.  A missing edge leads to the sink row of the table, which leads to itself, so a dead token
+// simply stays there; a lane past the end of its token keeps its state.  What the walk met on the way is gathered in
+// `seen` (the OR of the state references after each byte) and, for a plane whose start item is its outermost instance
+// (ROOT: final states do not stop the walk, they only matter if the token dies later), in `seen_before_last` (the
+// same without the last byte's target).
+struct WalkResult { uint32_t state, seen, seen_before_last; };
+template <bool ROOT>
+__device__ __forceinline__ WalkResult walk_tokens(const uint32_t* __restrict__ trans, uint32_t n_classes, uint32_t sink, const uint8_t* cls_bytes,
+                                                  uint32_t start, const uint4 tv, int n) {
+    WalkResult r{n > 0 ? start : sink, 0u, 0u};
+    const uint32_t words[4] = {tv.x, tv.y, tv.z, tv.w};
+#pragma unroll
+    for (int wi = 0; wi < 4; ++wi) {                                // unrolled: byte j of word wi is one bit-field extract
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int i = wi * 4 + j;
+            const uint32_t b = (words[wi] >> (8 * j)) & 0xFF;
+            const uint32_t t = trans[(r.state & SID_MASK) * n_classes + cls_bytes[b]];
+            const bool live = i < n;
+            if (ROOT) r.seen_before_last = live ? r.seen : r.seen_before_last;
+            r.state = live ? t : r.state;
+            r.seen |= r.state;                                      // idempotent once the token has ended
+        }
+        if (!wave_any(r.state != sink && (wi + 1) * 4 < n)) break;
+    }
+    return r;
 }
 
 }  // namespace core

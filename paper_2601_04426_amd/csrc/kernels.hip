@@ -10,6 +10,8 @@
 //   k_apply_*      logits of disallowed tokens := -infinity, in place    (section 2.1)
 // No MFMA: nothing here is a contraction.  All device writes are vector stores or LDS/L2 atomics.
 #include <algorithm>
+#include <cstdio>
+#include <cstdlib>
 #include <mutex>
 
 #include "device.hpp"
@@ -93,12 +95,49 @@ struct GlobalStore {
     __device__ uint32_t get_wstart(int j) const { return ws[(size_t)j * stride]; }
 };
 
-#ifndef XG2_BUILD_K
-#define XG2_BUILD_K 6
-#define XG2_BUILD_WM 10
+// Item-list capacities of the LDS path with all 64 lanes at work: the host picks one of two sizes per launch (see
+// launch_build); the LDS of a workgroup is sized to match.
+#ifndef XG2_BUILD_K_SMALL
+#define XG2_BUILD_K_SMALL 3
+#define XG2_BUILD_WM_SMALL 5
 #endif
-constexpr int BUILD_K = XG2_BUILD_K, BUILD_WM = XG2_BUILD_WM;   // item-list capacities of the LDS path (tuning knobs)
-using BuildStore = LdsStore<BUILD_K, BUILD_WM>;
+constexpr int BUILD_K_SMALL = XG2_BUILD_K_SMALL, BUILD_WM_SMALL = XG2_BUILD_WM_SMALL, BUILD_K_LARGE = 6, BUILD_WM_LARGE = 10;
+
+// The build kernel's item lists: the LDS layout above with capacities chosen at run time.  The lists are kept short
+// because their size bounds how many workgroups a compute unit holds, and the kernel lives on hiding the latency of
+// dependent table loads behind other wavefronts.  A token that outgrows them is run again with only the lower 32 lanes
+// at work, each with two lanes' worth of the same memory (word (slot, lane) at slot * 32 + lane): twice the capacity,
+// no more LDS.
+struct BuildStore {
+    static constexpr int MAXLEN = 16;
+    int K, WM, sh;                                  // capacities; log2 of the distance between a lane's consecutive slots
+    uint32_t* cur; uint32_t* nxt; uint32_t* wait;
+    unsigned long long ws_lo = 0, ws_hi = 0;        // wait-list length at the start of each new set, 8 bits each
+    // lds: the workgroup's (2 k + 2 wm) * 64 words for lists of k items and wm wait entries a lane; wide: lanes 0..31 only,
+    // double capacity
+    __device__ void init(uint32_t* lds, uint32_t lane, int k, int wm, bool wide) {
+        K = wide ? 2 * k : k; WM = wide ? 2 * wm : wm; sh = wide ? 5 : 6;
+        cur = lds + lane; nxt = lds + k * 64 + lane; wait = lds + 2 * k * 64 + lane;
+    }
+    __device__ uint32_t get_cur(int k) const { return cur[k << sh]; }
+    __device__ void set_cur(int k, uint32_t v) { cur[k << sh] = v; }
+    __device__ uint32_t get_nxt(int k) const { return nxt[k << sh]; }
+    __device__ void set_nxt(int k, uint32_t v) { nxt[k << sh] = v; }
+    __device__ uint32_t wait_rule(int k) const { return wait[(2 * k) << sh]; }
+    __device__ uint32_t wait_tgt(int k) const { return wait[(2 * k + 1) << sh]; }
+    __device__ void set_wait(int k, uint32_t rule, uint32_t tgt) { wait[(2 * k) << sh] = rule; wait[(2 * k + 1) << sh] = tgt; }
+    __device__ void swap() { uint32_t* t = cur; cur = nxt; nxt = t; }
+    __device__ bool charge(int) { return true; }
+    __device__ void reset() { ws_lo = 0; ws_hi = 0; }
+    __device__ void set_wstart(int j, uint32_t v) {
+        const int s8 = 8 * (j & 7);
+        unsigned long long& w = j < 8 ? ws_lo : ws_hi;
+        w = (w & ~(0xFFull << s8)) | ((unsigned long long)v << s8);
+    }
+    __device__ uint32_t get_wstart(int j) const {
+        return (uint32_t)((j < 8 ? ws_lo >> (8 * j) : ws_hi >> (8 * (j - 8))) & 0xFF);
+    }
+};
 
 __device__ __forceinline__ void push_overflow(const SlowScratch& S, uint32_t a, uint32_t b) {
     uint32_t idx = atomicAdd(S.count, 1u);
@@ -117,10 +156,12 @@ __device__ __forceinline__ DevCtx position_ctx(const BuildPlan& P, uint32_t p) {
     return C;
 }
 
-__device__ __forceinline__ void store_class(const BuildPlan& P, uint32_t p, uint32_t W, uint32_t id, int res) {
-    uint32_t* row = P.plane_ptr[p];
+__device__ __forceinline__ void store_class(uint32_t* row, uint32_t W, uint32_t id, int res) {
     if (res & RES_ALIVE) atomicOr(row + (id >> 5), 1u << (id & 31));
     else if (res & RES_EARLY) atomicOr(row + W + (id >> 5), 1u << (id & 31));
+}
+__device__ __forceinline__ void store_class(const BuildPlan& P, uint32_t p, uint32_t W, uint32_t id, int res) {
+    store_class(P.plane_ptr[p], W, id, res);
 }
 
 // A persistent grid of single-wave workgroups: workgroup g handles chunks g, g + grid, g + 2 grid, ...
@@ -136,23 +177,46 @@ __device__ __forceinline__ void store_class(const BuildPlan& P, uint32_t p, uint
 // a time, through the Earley recogniser.  Tokens that leave the outermost rule early and then die need the
 // second, follow-language run; they are collected across chunks as (plane, rank) pairs and run 64 at a time too.
 __device__ __forceinline__ void follow_batch(const DevTables& T, const DevVocab& Vd, const BuildPlan& P, const SlowScratch& S,
-                                             const uint32_t* cls_words, const uint32_t* f_plane, const uint32_t* f_rank,
-                                             uint32_t first, uint32_t count, uint32_t lane, BuildStore& st) {
-    if (lane < count) {
-        const uint32_t p = f_plane[first + lane], rank = f_rank[first + lane];
-        const DevCtx C = position_ctx(P, p);
-        const int n = (int)(Vd.off[rank + 1] - Vd.off[rank]);
-        RegBytes tok;
-        tok.v = Vd.tok16[rank];
-        st.reset();
-        const int res = scan_token<BuildStore, true>(T, cls_words, C, tok, n, st);
-        if (res & RES_OVERFLOW) push_overflow(S, p, rank);
-        else if (res & RES_ALIVE) store_class(P, p, Vd.W, Vd.perm[rank], RES_EARLY);   // some context can take the rest: uncertain
+                                          const uint32_t* cls_words, uint32_t* lds, uint32_t* f_plane, uint32_t* f_rank,
+                                          uint32_t first, uint32_t count, uint32_t lane) {
+    // round 0: the batch, one token a lane; later rounds: the tokens that outgrew the lists, 32 at a time with twice the
+    // room (their entries have moved to the front of the batch's part of the queue, which has been read)
+    uint32_t n_over = 0;
+    for (uint32_t round = 0;; ++round) {
+        const bool wide = round > 0;
+        const uint32_t off = wide ? (round - 1) * 32 : 0, cnt = wide ? n_over : count;
+        if (off >= cnt) break;
+        BuildStore st;
+        st.init(lds, lane, (int)P.list_k, (int)P.list_wm, wide);
+        bool over = false;
+        uint32_t p = 0, rank = 0;
+        if (lane < (wide ? 32u : 64u) && off + lane < cnt) {
+            p = f_plane[first + off + lane]; rank = f_rank[first + off + lane];
+            const DevCtx C = position_ctx(P, p);
+            const int n = (int)(Vd.off[rank + 1] - Vd.off[rank]);
+            RegBytes tok;
+            tok.v = Vd.tok16[rank];
+            const int res = scan_token<BuildStore, true>(T, cls_words, C, tok, n, st);
+            over = res & RES_OVERFLOW;
+            if (over && wide) push_overflow(S, p, rank);            // the large-capacity kernel takes it
+            else if (res & RES_ALIVE) store_class(P, p, Vd.W, Vd.perm[rank], RES_EARLY);   // some context can take the rest: uncertain
+        }
+        if (!wide) {
+            const unsigned long long mo = __ballot(over);
+            n_over = (uint32_t)__popcll(mo);
+            if (!mo) break;
+            __syncthreads();
+            if (over) {
+                const uint32_t at = first + (uint32_t)__popcll(mo & ((1ull << lane) - 1));
+                f_plane[at] = p; f_rank[at] = rank;
+            }
+            __syncthreads();
+        }
     }
 }
 
 __global__ __launch_bounds__(64) void k_build(DevTables T, DevVocab Vd, BuildPlan P, SlowScratch S) {
-    __shared__ uint32_t lds[BuildStore::SLOTS * 64];
+    extern __shared__ uint32_t lds[];                               // the item lists: (2 K + 2 WM) * 64 words, sized by the launch
     __shared__ uint32_t cls_words[64];
     __shared__ uint8_t cls_bytes[256];                              // the same table, one byte an entry
     __shared__ uint32_t deferred[kBuildChunk];
@@ -160,17 +224,15 @@ __global__ __launch_bounds__(64) void k_build(DevTables T, DevVocab Vd, BuildPla
     const uint32_t lane = threadIdx.x;
     cls_words[lane] = T.byte_class_words[lane];
     reinterpret_cast<uint32_t*>(cls_bytes)[lane] = T.byte_class_words[lane];
-    BuildStore st;
-    st.init(lds + lane);
     uint32_t n_follow = 0;                                          // same in every lane
     for (uint32_t chunk_idx = blockIdx.x; chunk_idx < P.n_chunks; chunk_idx += gridDim.x) {
         __syncthreads();                                            // one wave: orders the LDS traffic of the phases
-        const uint4 chunk = P.chunk[chunk_idx];
+        const uint4 chunk = P.chunk[2 * chunk_idx], chunk_b = P.chunk[2 * chunk_idx + 1];   // one 32-byte record: nothing else is loaded before the walk
         const uint32_t p = chunk.x;
-        const DevCtx C = position_ctx(P, p);
-        const uint32_t item0 = C.items[0];
+        const uint32_t item0 = chunk_b.x;
+        uint32_t* const row = reinterpret_cast<uint32_t*>(((uint64_t)chunk_b.w << 32) | chunk_b.z);
         // same for the whole chunk; that the start state itself can end its rule does not matter to a token (it has a byte)
-        const bool walkable = C.n_items == 1 && (item0 & (F_BYTE | F_REF)) == F_BYTE;
+        const bool walkable = chunk_b.y == 1 && (item0 & (F_BYTE | F_REF)) == F_BYTE;
         const bool root_instance = (item0 >> REF_BITS) == ROOT_ORIGIN;   // the start item is the plane's outermost rule instance
         const bool listed = chunk.w & kChunkListed;                 // ranks come from a list of long tokens
         const bool threaded = chunk.w & kChunkThreads;              // two thread descriptors follow the plane's items
@@ -188,49 +250,35 @@ __global__ __launch_bounds__(64) void k_build(DevTables T, DevVocab Vd, BuildPla
             __syncthreads();
             if (n_follow >= 64) {
                 n_follow -= 64;
-                follow_batch(T, Vd, P, S, cls_words, f_plane, f_rank, n_follow, 64, lane, st);
+                follow_batch(T, Vd, P, S, cls_words, lds, f_plane, f_rank, n_follow, 64, lane);
                 __syncthreads();
             }
         };
         // what phase 1 does with such a token: the plain run would end dead with the early mark, so it is not made
         auto died_early = [&](bool yes, uint32_t rank) {
-            if (yes && !P.follow_filter) { store_class(P, p, Vd.W, Vd.perm[rank], RES_EARLY); yes = false; }
+            if (yes && !P.follow_filter) { store_class(row, Vd.W, Vd.perm[rank], RES_EARLY); yes = false; }
             queue_follow(yes, rank);
         };
         if (walkable) {
             n_work = 0;
             for (uint32_t rank0 = chunk.y; rank0 < chunk.z; rank0 += 64) {
                 uint32_t rank = rank0 + lane;
-                bool defer = false;
                 int n = 0;
                 uint4 tv = make_uint4(0, 0, 0, 0);
                 if (rank < chunk.z) {
                     if (listed) rank = Vd.long_rank[rank];
                     n = (int)(Vd.off[rank + 1] - Vd.off[rank]); tv = Vd.tok16[rank];
                 }
-                if (n > BuildStore::MAXLEN) { defer = true; n = 0; }   // phase 2 hands it to the large-capacity kernel
-                bool walking = n > 0, early = false, dead_early = false;
-                uint32_t sid = item0 & SID_MASK;
-                const uint32_t words[4] = {tv.x, tv.y, tv.z, tv.w};
-#pragma unroll
-                for (int wi = 0; wi < 4; ++wi) {                    // unrolled: byte j of word wi is one bit-field extract
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        if (walking && wi * 4 + j < n) {
-                            const uint32_t b = (words[wi] >> (8 * j)) & 0xFF;
-                            const uint32_t tgt = T.trans[sid * T.n_classes + cls_bytes[b]];
-                            if (tgt == NO_TARGET) { walking = false; dead_early = early; }         // dead: rejected, unless the rule could end on the way
-                            else if ((tgt & F_REF) || ((tgt & F_FINAL) && !root_instance)) { walking = false; defer = true; }   // predicts, or completes into a parent
-                            else {                                   // the root instance may end here: that only matters if the token dies later
-                                sid = tgt & SID_MASK;
-                                early |= (tgt & F_FINAL) && wi * 4 + j + 1 < n;
-                            }
-                        }
-                    }
-                    if (!__any(walking && (wi + 1) * 4 < n)) break;
-                }
-                if (walking) store_class(P, p, Vd.W, Vd.perm[rank], RES_ALIVE);                  // reached its end alive
-                died_early(dead_early, rank);
+                bool defer = n > BuildStore::MAXLEN;                 // phase 2 hands it to the large-capacity kernel
+                if (defer) n = 0;
+                const WalkResult r = root_instance ? walk_tokens<true>(T.trans, T.n_classes, T.sink, cls_bytes, item0 & REF_MASK, tv, n)
+                                                   : walk_tokens<false>(T.trans, T.n_classes, T.sink, cls_bytes, item0 & REF_MASK, tv, n);
+                // a state that predicts, or that completes into a parent, is where the walk hands over to the recogniser
+                defer |= n > 0 && (r.seen & (root_instance ? F_REF : (F_REF | F_FINAL))) != 0;
+                const bool dead = r.state == T.sink;
+                if (n > 0 && !dead && !defer) store_class(row, Vd.W, Vd.perm[rank], RES_ALIVE);      // reached its end alive
+                // dead: rejected, unless the outermost rule could have ended on the way
+                died_early(root_instance && n > 0 && dead && !defer && (r.seen_before_last & F_FINAL), rank);
                 const unsigned long long m = __ballot(defer);
                 if (defer) deferred[n_work + (uint32_t)__popcll(m & ((1ull << lane) - 1))] = rank;
                 n_work += (uint32_t)__popcll(m);
@@ -241,7 +289,8 @@ __global__ __launch_bounds__(64) void k_build(DevTables T, DevVocab Vd, BuildPla
             // thread; a thread of a waited-for instance that reaches a final state starts one thread of the outermost
             // instance at the state the host has looked up.  Three slots; anything else (a state that predicts, a
             // fourth thread) goes to phase 2.
-            const uint32_t* d = C.items + C.n_items;
+            const uint4 pc = P.plane_ctx[p];
+            const uint32_t* d = P.ctx_items + pc.x + pc.y;
             const uint32_t it_a = d[0], lead_a = d[1], it_b = d[2], lead_b = d[3];
             n_work = 0;
             for (uint32_t rank0 = chunk.y; rank0 < chunk.z; rank0 += 64) {
@@ -265,7 +314,7 @@ __global__ __launch_bounds__(64) void k_build(DevTables T, DevVocab Vd, BuildPla
                         auto step = [&](uint32_t& s, uint32_t lead, uint32_t& start) {
                             if (s == kNoThread) return;
                             const uint32_t tgt = T.trans[(s & SID_MASK) * T.n_classes + cls];
-                            if (tgt == NO_TARGET) { s = kNoThread; return; }
+                            if (tgt == T.sink) { s = kNoThread; return; }
                             if (tgt & F_REF) { defer = true; return; }
                             s = tgt | (s & ~REF_MASK);
                             if (tgt & F_FINAL) {
@@ -292,7 +341,7 @@ __global__ __launch_bounds__(64) void k_build(DevTables T, DevVocab Vd, BuildPla
                 }
                 bool dead_early = false;
                 if (n > 0 && !defer) {
-                    if ((s0 & s1 & s2) != kNoThread) store_class(P, p, Vd.W, Vd.perm[rank], RES_ALIVE);
+                    if ((s0 & s1 & s2) != kNoThread) store_class(row, Vd.W, Vd.perm[rank], RES_ALIVE);
                     else dead_early = early;
                 }
                 died_early(dead_early, rank);
@@ -302,27 +351,50 @@ __global__ __launch_bounds__(64) void k_build(DevTables T, DevVocab Vd, BuildPla
             }
             __syncthreads();
         }
+        if (n_work == 0) continue;
+        const DevCtx C = position_ctx(P, p);                        // only the recogniser needs the whole start set
         for (uint32_t base = 0; base < n_work; base += 64) {
-            const uint32_t idx = base + lane;
-            bool again = false;
-            uint32_t rank = 0;
-            if (idx < n_work) {
-                rank = (walkable || threaded) ? deferred[idx] : listed ? Vd.long_rank[chunk.y + idx] : chunk.y + idx;
-                const int n = (int)(Vd.off[rank + 1] - Vd.off[rank]);
-                RegBytes tok;
-                tok.v = Vd.tok16[rank];
-                st.reset();
-                const int res = scan_token(T, cls_words, C, tok, n, st);
-                // leaves the rule early and dies: it stays uncertain only if some context can take the rest of the token
-                again = P.follow_filter && !(res & (RES_ALIVE | RES_OVERFLOW)) && (res & RES_EARLY);
-                if (res & RES_OVERFLOW) push_overflow(S, p, rank);
-                else if (!again) store_class(P, p, Vd.W, Vd.perm[rank], res);
+            // round 0: 64 tokens of the list, one a lane; later rounds: those of them that outgrew the item lists, 32 at a
+            // time with half the lanes and twice the room (their ranks go through the part of the deferred list that
+            // this batch has read)
+            uint32_t n_over = 0;
+            for (uint32_t round = 0;; ++round) {
+                const bool wide = round > 0;
+                const uint32_t off = wide ? (round - 1) * 32 : 0, cnt = wide ? n_over : min(64u, n_work - base);
+                if (off >= cnt) break;
+                BuildStore st;
+                st.init(lds, lane, (int)P.list_k, (int)P.list_wm, wide);
+                bool again = false, over = false;
+                uint32_t rank = 0;
+                if (lane < (wide ? 32u : 64u) && off + lane < cnt) {
+                    const uint32_t idx = base + off + lane;
+                    rank = (wide || walkable || threaded) ? deferred[idx] : listed ? Vd.long_rank[chunk.y + idx] : chunk.y + idx;
+                    const int n = (int)(Vd.off[rank + 1] - Vd.off[rank]);
+                    RegBytes tok;
+                    tok.v = Vd.tok16[rank];
+                    const int res = scan_token(T, cls_words, C, tok, n, st);
+                    over = res & RES_OVERFLOW;
+                    if (over && wide) push_overflow(S, p, rank);     // the large-capacity kernel takes it
+                    else if (!over) {
+                        // leaves the rule early and dies: it stays uncertain only if some context can take the rest of the token
+                        again = P.follow_filter && !(res & RES_ALIVE) && (res & RES_EARLY);
+                        if (!again) store_class(row, Vd.W, Vd.perm[rank], res);
+                    }
+                }
+                queue_follow(again, rank);
+                if (!wide) {
+                    const unsigned long long mo = __ballot(over);
+                    n_over = (uint32_t)__popcll(mo);
+                    if (!mo) break;
+                    __syncthreads();
+                    if (over) deferred[base + (uint32_t)__popcll(mo & ((1ull << lane) - 1))] = rank;
+                    __syncthreads();
+                }
             }
-            queue_follow(again, rank);
         }
     }
     __syncthreads();
-    if (n_follow) follow_batch(T, Vd, P, S, cls_words, f_plane, f_rank, 0, n_follow, lane, st);
+    if (n_follow) follow_batch(T, Vd, P, S, cls_words, lds, f_plane, f_rank, 0, n_follow, lane);
 }
 
 // Both runs of one (plane, token) pair with the lists in `st`: the plain one and, if the token left the outermost
@@ -687,16 +759,35 @@ hipError_t noalloc_scratch(void** ptr_out) {
     return hipSuccess;
 }
 
-void launch_build(const DevTables& T, const DevVocab& Vd, const BuildPlan& P, const SlowScratch& S, hipStream_t stream) {
+void launch_build(const DevTables& T, const DevVocab& Vd, BuildPlan P, const SlowScratch& S, hipStream_t stream) {
     if (P.n_chunks == 0) return;
-    // as many single-wave workgroups as the device can hold at once at full occupancy (32 waves per compute unit)
-    static const uint32_t resident = [] {
+    // Short item lists let a compute unit hold more workgroups, which is what hides the latency of the automaton
+    // walks' dependent table loads when there is far more work than the device holds at once; long ones spare the
+    // tokens that need them a second run at half width, which is what counts when the launch is a few chunks per
+    // wave slot and lasts as long as its slowest workgroup.
+    static const uint32_t wave_slots = [] {
         int dev = 0, cus = 0;
         if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
             cus = 256;
-        return (uint32_t)cus * 32u;
+        return (uint32_t)cus * 32u;                                 // 4 SIMDs of 8 wave slots each
     }();
-    hipLaunchKernelGGL(k_build, dim3(std::min(P.n_chunks, resident)), dim3(64), 0, stream, T, Vd, P, S);
+    P.large_lists = P.n_chunks <= 4 * wave_slots ? 1u : 0u;
+#ifdef XG2_BUILD_FORCE_LISTS
+    P.large_lists = XG2_BUILD_FORCE_LISTS;
+#endif
+    P.list_k = P.large_lists ? BUILD_K_LARGE : BUILD_K_SMALL;
+    P.list_wm = P.large_lists ? BUILD_WM_LARGE : BUILD_WM_SMALL;
+    const uint32_t lds_bytes = (2 * P.list_k + 2 * P.list_wm) * 64 * sizeof(uint32_t);
+    // Workgroup g takes chunks g, g + grid, ...  At least one workgroup per wave slot of the device; a large launch is cut
+    // into shares of about a dozen chunks, small enough for the hardware to even out the load as workgroups end and
+    // large enough for a workgroup's tokens for the follow-language run to fill whole batches (measured: 8,192 for the
+    // 10,063 chunks of the repetition workload, 65,536 for the 856,956 of the dispatch workload).
+    uint32_t grid = std::min(P.n_chunks, std::max(wave_slots, std::min(P.n_chunks / 12, 8 * wave_slots)));
+#ifdef XG2_TUNE
+    if (const char* e = getenv("XG2_BUILD_GRID")) grid = std::min<uint32_t>(P.n_chunks, (uint32_t)atoi(e));
+    if (getenv("XG2_DEBUG_PLAN")) fprintf(stderr, "launch: chunks %u grid %u lds %u\n", P.n_chunks, grid, lds_bytes);
+#endif
+    hipLaunchKernelGGL(k_build, dim3(grid), dim3(64), lds_bytes, stream, T, Vd, P, S);
 }
 
 void launch_build_slow(const DevTables& T, const DevVocab& Vd, const BuildPlan& P, const SlowScratch& S, hipStream_t stream) {

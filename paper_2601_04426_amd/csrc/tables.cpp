@@ -101,7 +101,10 @@ FlatTables flatten(const Grammar& g) {
     if (t.n_classes > 256) throw std::logic_error("more byte classes than bytes");
     t.byte_class_words.assign(64, 0);
     for (int b = 0; b < 256; ++b) t.byte_class_words[(size_t)b >> 2] |= cls[iv_of[(size_t)b]] << ((b & 3) * 8);
-    t.trans.assign(n * t.n_classes, kNoTarget);
+    // one row more than there are states: the sink, which every missing edge leads to and which leads to itself, so
+    // that an automaton walk needs no "is there an edge" branch (a dead run just stays in the sink)
+    t.sink = (uint32_t)n;
+    t.trans.assign((n + 1) * t.n_classes, t.sink);
     for (size_t sid = 0; sid < n; ++sid) {
         const StateInfo& si = t.state_info[sid];
         for (uint32_t k = 0; k < (si.counts & 0xFFFF); ++k) {

@@ -45,16 +45,17 @@ struct FlatTables {
     std::vector<DevState> dev_state;
     std::vector<uint32_t> exp_list;
     // dense byte transitions: bytes that lead to the same state from every state form one class;
-    // trans[sid * n_classes + class] = state reference of the target or kNoTarget
+    // trans[sid * n_classes + class] = state reference of the target, or `sink` where the state has no edge for the
+    // byte; sink = number of states, a row of its own whose entries are all `sink` (no flags)
     std::vector<uint32_t> byte_class_words;      // 64 words: class of byte b = byte (b & 3) of word b >> 2
     uint32_t n_classes = 0;
+    uint32_t sink = 0;
     std::vector<uint32_t> trans;
     uint32_t ref(uint32_t sid) const {
         const StateInfo& si = state_info[sid];
         return sid | ((si.counts & 0xFFFF) ? kHasByte : 0u) | ((si.counts >> 16) ? kHasRef : 0u) | ((si.rule_final >> 31) ? kFinal : 0u);
     }
 };
-constexpr uint32_t kNoTarget = 0xFFFFFFFFu;
 
 FlatTables flatten(const Grammar& g);
 

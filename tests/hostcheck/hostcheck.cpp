@@ -11,7 +11,7 @@
 #include "../../paper_2601_04426_amd/csrc/tables.hpp"
 
 #ifndef HC_K
-#define HC_K 6      // capacities of the LDS path of the build kernel
+#define HC_K 6      // capacities of the LDS path of the build kernel (its long lists; the short ones fall back to these at half width)
 #define HC_WM 10
 #endif
 using namespace xg2;
@@ -102,7 +102,8 @@ extern "C" long long xg2hc_check(const char* ebnf, size_t len, const char* root,
         T.trans = ft.trans.data();
         T.byte_class_words = ft.byte_class_words.data();
         T.n_classes = ft.n_classes;
-        long long checked = 0, small_over = 0;
+        T.sink = ft.sink;
+        long long checked = 0, small_over = 0, n_walked = 0;
         int n_ctx = 0;
         auto run = [&](const EarleyChart& chart, bool renumber, const std::string& what) -> bool {
             Ctx c = ctx_of(chart, renumber);
@@ -117,6 +118,27 @@ extern "C" long long xg2hc_check(const char* ebnf, size_t len, const char* root,
                 if (got != want) {
                     snprintf(msg, msg_cap, "%s token %d: host parser %d, recogniser core %d", what.c_str(), k, want, got);
                     return false;
+                }
+                // the branch-free automaton walk of the build's first phase, where the start set is one plain automaton state
+                if (c.items.size() == 1 && (c.items[0] & (F_BYTE | F_REF)) == F_BYTE && n <= 16) {
+                    uint4 tv = make_uint4(0, 0, 0, 0);
+                    std::memcpy(&tv, t, n);
+                    const bool root = (c.items[0] >> REF_BITS) == ROOT_ORIGIN;
+                    const uint8_t* cls = reinterpret_cast<const uint8_t*>(ft.byte_class_words.data());
+                    const WalkResult r = root ? walk_tokens<true>(T.trans, T.n_classes, T.sink, cls, c.items[0] & REF_MASK, tv, (int)n)
+                                              : walk_tokens<false>(T.trans, T.n_classes, T.sink, cls, c.items[0] & REF_MASK, tv, (int)n);
+                    const bool defer = (r.seen & (root ? F_REF : (F_REF | F_FINAL))) != 0;
+                    if (!defer) {
+                        const bool alive = r.state != T.sink;
+                        const bool dead_early = root && !alive && (r.seen_before_last & F_FINAL);
+                        const int walked = alive ? RES_ALIVE : dead_early ? RES_EARLY : 0;
+                        const int expect = (want & RES_ALIVE) ? RES_ALIVE : (want & RES_EARLY);
+                        ++n_walked;
+                        if (walked != expect) {
+                            snprintf(msg, msg_cap, "%s token %d: host parser %d, automaton walk %d", what.c_str(), k, want, walked);
+                            return false;
+                        }
+                    }
                 }
             }
             return true;
@@ -142,6 +164,7 @@ extern "C" long long xg2hc_check(const char* ebnf, size_t len, const char* root,
             if (i < sentence_len && !chart.advance(sentence + i, 1)) { snprintf(msg, msg_cap, "sentence rejected at byte %zu", i); return -checked - 1; }
         }
         if (n_small_overflow) *n_small_overflow = small_over;
+        if (n_walked == 0 && checked > 1000) { snprintf(msg, msg_cap, "no context exercised the automaton walk"); return -1; }
         return checked;
     } catch (const std::exception& e) {
         snprintf(msg, msg_cap, "exception: %s", e.what());
