@@ -96,9 +96,16 @@ struct Packer {
         total = (total + v.size() * sizeof(T) + 255) & ~(size_t)255;
         return off;
     }
+    // room in the device block behind the uploaded arrays, written by kernels only
+    size_t reserved = 0;
+    size_t reserve(size_t bytes) {
+        const size_t off = total + reserved;
+        reserved = (reserved + bytes + 255) & ~(size_t)255;
+        return off;
+    }
     // own_dev: the device block is allocated for this upload and belongs to the caller afterwards
     void stage(bool own_dev) {
-        const size_t n = std::max<size_t>(total, 256);
+        const size_t n = std::max<size_t>(total, 256), n_dev = n + reserved;
         Staging& S = staging();
         if (S.host_cap < n) {
             if (S.host) (void)hipHostFree(S.host);
@@ -109,12 +116,12 @@ struct Packer {
         }
         host = S.host;
         if (own_dev) {
-            HIP_CHECK(hipMalloc((void**)&dev, n));
+            HIP_CHECK(hipMalloc((void**)&dev, n_dev));
         } else {
-            if (S.dev_cap < n) {
+            if (S.dev_cap < n_dev) {
                 if (S.dev) (void)hipFree(S.dev);
                 S.dev = nullptr; S.dev_cap = 0;
-                const size_t cap = std::max<size_t>(n + n / 2, (size_t)1 << 20);
+                const size_t cap = std::max<size_t>(n_dev + n_dev / 2, (size_t)1 << 20);
                 HIP_CHECK(hipMalloc((void**)&S.dev, cap));
                 S.dev_cap = cap;
             }
@@ -620,7 +627,7 @@ int32_t build_planes(CacheImpl& cache, const std::vector<int32_t>& todo, hipStre
 
     // plan: closed start set and live first-byte ranges of every plane to build
     std::vector<uint32_t> ctx_items, ctx_wait, ctx_wait_off;
-    std::vector<uint4> chunks, plane_ctx, ranges;
+    std::vector<uint4> plane_ctx, ranges;
     std::vector<CopyJob> copies;
     std::vector<FirstByteCopyJob> fb_copies;
     int64_t executed = 0, executed_bytes = 0;
@@ -748,25 +755,28 @@ int32_t build_planes(CacheImpl& cache, const std::vector<int32_t>& todo, hipStre
             b = e + 1;
         }
     }
-    // chunks of the heavy ranges first, then the others, each group in plane order
-    {
-        size_t n_chunks = 0;
-        for (const uint4& r : ranges) n_chunks += (r.z - r.y + ((r.w & kChunkHeavy) ? kHeavyChunk : kBuildChunk) - 1) / ((r.w & kChunkHeavy) ? kHeavyChunk : kBuildChunk);
-        chunks.reserve(2 * n_chunks);
-        for (uint32_t pass_heavy : {kChunkHeavy, 0u})
-            for (const uint4& r : ranges) {
-                if ((r.w & kChunkHeavy) != pass_heavy) continue;
-                const uint32_t step = pass_heavy ? kHeavyChunk : kBuildChunk;
-                // the second half of the record: what phase 1 needs of the plane (first start item, number of items, row address)
-                const uint4& pc = plane_ctx[r.x];
-                const uint64_t row = (uint64_t)(uintptr_t)build_rows[r.x];
-                const uint4 second = make_uint4(ctx_items[pc.x], pc.y, (uint32_t)row, (uint32_t)(row >> 32));
-                for (uint32_t c = r.y; c < r.z; c += step) {
-                    chunks.push_back(make_uint4(r.x, c, std::min(r.z, c + step), r.w));
-                    chunks.push_back(second);
-                }
+    // The chunk records are written on the device (k_expand_chunks) from the ranges: per range {plane, first rank, end
+    // rank, flags}, the index of its first chunk and what the walk needs of its plane.  Chunks of the heavy ranges come
+    // first, then the others, each group in plane order; a long range is cut so that one thread writes at most 32 chunks.
+    std::vector<uint4> range_a, range_b;
+    std::vector<uint32_t> range_first;
+    size_t n_chunks = 0;
+    for (uint32_t pass_heavy : {kChunkHeavy, 0u})
+        for (const uint4& r : ranges) {
+            if ((r.w & kChunkHeavy) != pass_heavy) continue;
+            const uint32_t step = pass_heavy ? kHeavyChunk : kBuildChunk;
+            const uint4& pc = plane_ctx[r.x];
+            const uint64_t row = (uint64_t)(uintptr_t)build_rows[r.x];
+            const uint4 second = make_uint4(ctx_items[pc.x], pc.y, (uint32_t)row, (uint32_t)(row >> 32));
+            for (uint32_t lo = r.y; lo < r.z; lo += 32 * step) {
+                const uint32_t hi = std::min(r.z, lo + 32 * step);
+                range_a.push_back(make_uint4(r.x, lo, hi, r.w));
+                range_b.push_back(second);
+                range_first.push_back((uint32_t)n_chunks);
+                n_chunks += (hi - lo + step - 1) / step;
             }
-    }
+        }
+    if (n_chunks > 0xFFFFFFF0ull) throw std::length_error("mask cache build: too many chunks in one launch");
 
     // everything the device needs goes up in one copy: (the tables,) the plan, and a few zeroed words (overflow
     // counter and flag, bit counts per built plane).  With the tables the block stays with the cache.
@@ -777,8 +787,9 @@ int32_t build_planes(CacheImpl& cache, const std::vector<int32_t>& todo, hipStre
         o_state = tab.add(ft.dev_state); o_exp = tab.add(ft.exp_list); o_soff = tab.add(cache.site_off); o_stgt = tab.add(cache.site_tgt);
         o_trans = tab.add(ft.trans); o_cls = tab.add(ft.byte_class_words);
     }
-    const size_t o_chunks = tab.add(chunks), o_pctx = tab.add(plane_ctx), o_items = tab.add(ctx_items), o_wait = tab.add(ctx_wait),
+    const size_t o_range_a = tab.add(range_a), o_range_b = tab.add(range_b), o_range_first = tab.add(range_first), o_pctx = tab.add(plane_ctx), o_items = tab.add(ctx_items), o_wait = tab.add(ctx_wait),
                  o_wait_off = tab.add(ctx_wait_off), o_rows = tab.add(build_rows), o_copies = tab.add(copies), o_fb_copies = tab.add(fb_copies), o_zero = tab.add(zeros);
+    const size_t o_chunks = tab.reserve(n_chunks * 2 * sizeof(uint4));
     tab.stage(with_tables);
     if (with_tables) cache.d_tables = tab.dev;                     // the cache owns the block from here on
     res.host_ms = ms_since(t1);
@@ -801,13 +812,15 @@ int32_t build_planes(CacheImpl& cache, const std::vector<int32_t>& todo, hipStre
     uint32_t* d_counts = tab.at<uint32_t>(o_zero) + 8;
     S.count = tab.at<uint32_t>(o_zero) + 4;                       // this call's own overflow counter and flag, zero on arrival
     BuildPlan P{};
-    P.chunk = tab.at<const uint4>(o_chunks); P.n_chunks = (uint32_t)(chunks.size() / 2);
+    P.chunk = tab.at<const uint4>(o_chunks); P.n_chunks = (uint32_t)n_chunks;
     P.plane_ctx = tab.at<const uint4>(o_pctx);
     P.ctx_items = tab.at<const uint32_t>(o_items);
     P.ctx_wait = tab.at<const uint2>(o_wait); P.ctx_wait_off = tab.at<const uint32_t>(o_wait_off);
     P.plane_ptr = tab.at<uint32_t*>(o_rows);
     P.follow_filter = cache.follow ? 1u : 0u;
     uint32_t* const* d_rows_p = tab.at<uint32_t*>(o_rows);
+    launch_expand_chunks(tab.at<const uint4>(o_range_a), tab.at<const uint4>(o_range_b), tab.at<const uint32_t>(o_range_first),
+                         (uint32_t)range_a.size(), tab.at<uint4>(o_chunks), stream);
     HIP_CHECK(hipEventRecord(evk0, stream));
     if (!build.empty()) launch_build(cache.dt, V.dv, P, S, stream);
     HIP_CHECK(hipEventRecord(evk1, stream));

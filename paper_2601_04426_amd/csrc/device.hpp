@@ -51,7 +51,7 @@ constexpr uint32_t kBuildChunk = XG2_BUILD_CHUNK;
 #define XG2_HEAVY_CHUNK XG2_BUILD_CHUNK
 #endif
 constexpr uint32_t kHeavyChunk = XG2_HEAVY_CHUNK;             // chunk size of planes whose tokens all take the Earley steps
-static_assert(kHeavyChunk <= kBuildChunk, "the deferred list is sized for kBuildChunk");
+static_assert(kHeavyChunk <= kBuildChunk && kBuildChunk <= 256, "the deferred list is sized for kBuildChunk and holds one-byte offsets");
 struct BuildPlan {
     const uint4* chunk; uint32_t n_chunks;                      // 2 * n_chunks uint4
     const uint4* plane_ctx;                                     // [n_planes]
@@ -82,6 +82,10 @@ void launch_copy_masked(const CopyJob* jobs_dev, uint32_t n_jobs, uint32_t W, hi
 struct FirstByteCopyJob { uint32_t* dst; const uint32_t* src; uint32_t bytes[8]; };
 void launch_copy_first_byte(const FirstByteCopyJob* jobs_dev, uint32_t n_jobs, const uint8_t* first_byte_dev, uint32_t W, hipStream_t stream);
 
+// Writes the chunk records of a build: thread r cuts range_a[r] = {plane, first rank, end rank, flags} into chunks of
+// kBuildChunk (kHeavyChunk with kChunkHeavy) ranks, records first[r], first[r] + 1, ..., each followed by range_b[r].
+void launch_expand_chunks(const uint4* range_a_dev, const uint4* range_b_dev, const uint32_t* first_dev, uint32_t n_ranges,
+                          uint4* chunk_dev, hipStream_t stream);
 void launch_build(const DevTables& T, const DevVocab& Vd, BuildPlan P, const SlowScratch& S, hipStream_t stream);
 void launch_build_slow(const DevTables& T, const DevVocab& Vd, const BuildPlan& P, const SlowScratch& S, hipStream_t stream);
 // counts_dev[2p], counts_dev[2p + 1] = set bits of the accepted and of the uncertain row of plane p

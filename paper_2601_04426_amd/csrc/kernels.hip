@@ -95,11 +95,14 @@ struct GlobalStore {
     __device__ uint32_t get_wstart(int j) const { return ws[(size_t)j * stride]; }
 };
 
+#ifndef XG2_BUILD_ATTR
+#define XG2_BUILD_ATTR
+#endif
 // Item-list capacities of the LDS path with all 64 lanes at work: the host picks one of two sizes per launch (see
 // launch_build); the LDS of a workgroup is sized to match.
 #ifndef XG2_BUILD_K_SMALL
 #define XG2_BUILD_K_SMALL 3
-#define XG2_BUILD_WM_SMALL 5
+#define XG2_BUILD_WM_SMALL 4
 #endif
 constexpr int BUILD_K_SMALL = XG2_BUILD_K_SMALL, BUILD_WM_SMALL = XG2_BUILD_WM_SMALL, BUILD_K_LARGE = 6, BUILD_WM_LARGE = 10;
 
@@ -215,15 +218,14 @@ __device__ __forceinline__ void follow_batch(const DevTables& T, const DevVocab&
     }
 }
 
-__global__ __launch_bounds__(64) void k_build(DevTables T, DevVocab Vd, BuildPlan P, SlowScratch S) {
+__global__ __launch_bounds__(64) XG2_BUILD_ATTR void k_build(DevTables T, DevVocab Vd, BuildPlan P, SlowScratch S) {
     extern __shared__ uint32_t lds[];                               // the item lists: (2 K + 2 WM) * 64 words, sized by the launch
-    __shared__ uint32_t cls_words[64];
-    __shared__ uint8_t cls_bytes[256];                              // the same table, one byte an entry
-    __shared__ uint32_t deferred[kBuildChunk];
+    __shared__ uint32_t cls_words[64];                              // byte -> class, four a word
+    const uint8_t* cls_bytes = reinterpret_cast<const uint8_t*>(cls_words);   // the same table, one byte an entry
+    __shared__ uint8_t deferred[kBuildChunk];                       // tokens of the chunk for phase 2, as offsets from the chunk's first rank
     __shared__ uint32_t f_plane[128], f_rank[128];
     const uint32_t lane = threadIdx.x;
     cls_words[lane] = T.byte_class_words[lane];
-    reinterpret_cast<uint32_t*>(cls_bytes)[lane] = T.byte_class_words[lane];
     uint32_t n_follow = 0;                                          // same in every lane
     for (uint32_t chunk_idx = blockIdx.x; chunk_idx < P.n_chunks; chunk_idx += gridDim.x) {
         __syncthreads();                                            // one wave: orders the LDS traffic of the phases
@@ -280,7 +282,7 @@ __global__ __launch_bounds__(64) void k_build(DevTables T, DevVocab Vd, BuildPla
                 // dead: rejected, unless the outermost rule could have ended on the way
                 died_early(root_instance && n > 0 && dead && !defer && (r.seen_before_last & F_FINAL), rank);
                 const unsigned long long m = __ballot(defer);
-                if (defer) deferred[n_work + (uint32_t)__popcll(m & ((1ull << lane) - 1))] = rank;
+                if (defer) deferred[n_work + (uint32_t)__popcll(m & ((1ull << lane) - 1))] = (uint8_t)(rank0 + lane - chunk.y);
                 n_work += (uint32_t)__popcll(m);
             }
             __syncthreads();
@@ -346,7 +348,7 @@ __global__ __launch_bounds__(64) void k_build(DevTables T, DevVocab Vd, BuildPla
                 }
                 died_early(dead_early, rank);
                 const unsigned long long m = __ballot(defer);
-                if (defer) deferred[n_work + (uint32_t)__popcll(m & ((1ull << lane) - 1))] = rank;
+                if (defer) deferred[n_work + (uint32_t)__popcll(m & ((1ull << lane) - 1))] = (uint8_t)(rank0 + lane - chunk.y);
                 n_work += (uint32_t)__popcll(m);
             }
             __syncthreads();
@@ -365,10 +367,11 @@ __global__ __launch_bounds__(64) void k_build(DevTables T, DevVocab Vd, BuildPla
                 BuildStore st;
                 st.init(lds, lane, (int)P.list_k, (int)P.list_wm, wide);
                 bool again = false, over = false;
-                uint32_t rank = 0;
+                uint32_t rank = 0, at = 0;                           // the token: sorted rank, and offset in the chunk
                 if (lane < (wide ? 32u : 64u) && off + lane < cnt) {
                     const uint32_t idx = base + off + lane;
-                    rank = (wide || walkable || threaded) ? deferred[idx] : listed ? Vd.long_rank[chunk.y + idx] : chunk.y + idx;
+                    at = (wide || walkable || threaded) ? deferred[idx] : idx;
+                    rank = listed ? Vd.long_rank[chunk.y + at] : chunk.y + at;
                     const int n = (int)(Vd.off[rank + 1] - Vd.off[rank]);
                     RegBytes tok;
                     tok.v = Vd.tok16[rank];
@@ -387,7 +390,7 @@ __global__ __launch_bounds__(64) void k_build(DevTables T, DevVocab Vd, BuildPla
                     n_over = (uint32_t)__popcll(mo);
                     if (!mo) break;
                     __syncthreads();
-                    if (over) deferred[base + (uint32_t)__popcll(mo & ((1ull << lane) - 1))] = rank;
+                    if (over) deferred[base + (uint32_t)__popcll(mo & ((1ull << lane) - 1))] = (uint8_t)at;
                     __syncthreads();
                 }
             }
@@ -438,6 +441,18 @@ __global__ __launch_bounds__(64) void k_build_slow(DevTables T, DevVocab Vd, Bui
 // Set bits of the freshly built planes: counts[2p] = accepted, counts[2p + 1] = uncertain bits of plane p.
 __global__ __launch_bounds__(256) void k_upload(uint4* dst, const uint4* src, size_t n) {
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) dst[i] = src[i];
+}
+
+__global__ __launch_bounds__(256) void k_expand_chunks(const uint4* range_a, const uint4* range_b, const uint32_t* first, uint32_t n_ranges, uint4* chunk) {
+    const uint32_t r = blockIdx.x * 256 + threadIdx.x;
+    if (r >= n_ranges) return;
+    const uint4 a = range_a[r], b = range_b[r];
+    const uint32_t step = (a.w & kChunkHeavy) ? kHeavyChunk : kBuildChunk;
+    uint4* out = chunk + 2 * (size_t)first[r];
+    for (uint32_t lo = a.y; lo < a.z; lo += step, out += 2) {
+        out[0] = make_uint4(a.x, lo, min(a.z, lo + step), a.w);
+        out[1] = b;
+    }
 }
 
 __global__ __launch_bounds__(256) void k_copy_masked(const CopyJob* jobs, uint32_t W) {
@@ -757,6 +772,12 @@ hipError_t noalloc_scratch(void** ptr_out) {
     }
     *ptr_out = ptr_of[dev];
     return hipSuccess;
+}
+
+void launch_expand_chunks(const uint4* range_a_dev, const uint4* range_b_dev, const uint32_t* first_dev, uint32_t n_ranges,
+                          uint4* chunk_dev, hipStream_t stream) {
+    if (!n_ranges) return;
+    hipLaunchKernelGGL(k_expand_chunks, dim3((n_ranges + 255) / 256), dim3(256), 0, stream, range_a_dev, range_b_dev, first_dev, n_ranges, chunk_dev);
 }
 
 void launch_build(const DevTables& T, const DevVocab& Vd, BuildPlan P, const SlowScratch& S, hipStream_t stream) {
