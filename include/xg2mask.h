@@ -226,6 +226,33 @@ int32_t xg2_fill_last_status(int32_t* large_capacity_tokens, int32_t* overflowed
  * part).  words_host: host array; at most cap entries are written; *n_rows (nullable) receives the batch size.   */
 int32_t xg2_fill_last_recheck_words(int32_t* words_host, int32_t cap, int32_t* n_rows);
 
+/* ---- matchers that live on the device (section 3.4 and the appendix on Earley parsing: the parser that traces the
+ * output, one per sequence) ------------------------------------------------------------------------------------------
+ * A batch holds B matcher slots in device memory: per slot the scannable items of the current closed Earley set, what the
+ * waiting items of every older set still reachable wait for, and the planes of the scannable frontier.  A decoding step
+ * then needs nothing from the host: xg2_batch_accept_tokens runs the sampled tokens (a device array, e.g. the sampler's
+ * output) through the Earley recogniser, one lane per slot, and leaves each slot's next state in place;
+ * xg2_batch_fill_next_token_bitmask reads the slots directly.  Both only enqueue kernels on the caller's stream.
+ * Capacities of a slot: 64 scannable items, 240 reachable sets, 512 wait entries, 16 frontier planes (a grammar whose
+ * parse needs more, e.g. deeply right-recursive rules, makes the slot fail with XG2_EOVERFLOW until it is reassigned: use
+ * host matchers for it).  Caches compiled just in time are not accepted (XG2_EINVAL): every plane must exist.            */
+typedef struct xg2_batch xg2_batch;
+int32_t xg2_batch_create(xg2_vocab* vocab, int32_t B, xg2_batch** out);
+void    xg2_batch_destroy(xg2_batch*);
+/* Slots rows_host[0 .. n) (host array; NULL = all B slots) start a new sequence of `cache`, which the batch keeps alive; at
+ * most 256 different caches per batch.  Waits for the assignment to finish.                                              */
+int32_t xg2_batch_assign(xg2_batch*, const int32_t* rows_host, int32_t n, const xg2_mask_cache* cache, void* hip_stream);
+/* token_ids_dev: device, B int32: the token slot b accepts; -1 = none for this slot; -2 = slot b starts a new sequence of its
+ * cache.  status_dev (device, B int32, may be NULL) receives per slot what xg2_matcher_accept_token would return: XG2_OK,
+ * XG2_EREJECTED (state unchanged), XG2_EINVAL (terminated, or id out of range), XG2_EOVERFLOW (slot capacity exceeded; sticky
+ * until the slot is reset or reassigned).  Accepting the end-of-sequence token where the root rule can end terminates the slot.  */
+int32_t xg2_batch_accept_tokens(xg2_batch*, const int32_t* token_ids_dev, int32_t* status_dev, void* hip_stream);
+/* The masks of xg2_fill_next_token_bitmask for the B slots, row b for slot b; nothing is uploaded.                        */
+int32_t xg2_batch_fill_next_token_bitmask(xg2_batch*, int32_t* bitmask_dev, int64_t row_stride_words, void* hip_stream);
+/* Test aid (synchronises): info_host[8] = {root can end, terminated, sticky error, reachable sets, scannable items, wait
+ * entries, frontier planes, index of the slot's cache in the batch or -1}.                                               */
+int32_t xg2_batch_row_info(xg2_batch*, int32_t row, int32_t* info_host);
+
 /* ---- apply_token_bitmask(logits[B, V], bitmask) -------------------------------------------------
  * In place: logits[b, v] = -infinity where bit v of bitmask row b is 0; other elements keep
  * their bit pattern.  dtype: XG2_F32 or XG2_BF16.  logits_dev: device, B rows of

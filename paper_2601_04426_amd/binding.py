@@ -26,7 +26,8 @@ EXPORTS = [
     "xg2_mask_cache_plane_info", "xg2_mask_cache_find_plane", "xg2_mask_cache_get_planes", "xg2_matcher_create", "xg2_matcher_create_host", "xg2_matcher_destroy",
     "xg2_matcher_accept_token", "xg2_matcher_accept_tokens", "xg2_matcher_reset", "xg2_matcher_is_terminated", "xg2_matcher_frontier",
     "xg2_fill_next_token_bitmask", "xg2_fill_next_token_bitmask_noalloc", "xg2_fill_last_device_us", "xg2_fill_last_status", "xg2_fill_last_recheck_words",
-    "xg2_apply_token_bitmask",
+    "xg2_apply_token_bitmask", "xg2_batch_create", "xg2_batch_destroy", "xg2_batch_assign", "xg2_batch_accept_tokens",
+    "xg2_batch_fill_next_token_bitmask", "xg2_batch_row_info",
 ]
 
 
@@ -99,6 +100,12 @@ def _load() -> ctypes.CDLL:
     L.xg2_fill_last_status.argtypes = [ctypes.POINTER(i32), ctypes.POINTER(i32)]
     L.xg2_fill_last_recheck_words.argtypes = [vp, i32, ctypes.POINTER(i32)]
     L.xg2_apply_token_bitmask.argtypes = [vp, i32, i32, i32, i64, vp, i64, vp]
+    L.xg2_batch_create.argtypes = [vp, i32, pvp]
+    L.xg2_batch_destroy.argtypes = [vp]
+    L.xg2_batch_assign.argtypes = [vp, vp, i32, vp, vp]
+    L.xg2_batch_accept_tokens.argtypes = [vp, vp, vp, vp]
+    L.xg2_batch_fill_next_token_bitmask.argtypes = [vp, vp, i64, vp]
+    L.xg2_batch_row_info.argtypes = [vp, i32, vp]
     for name in EXPORTS:
         if name not in ("xg2_last_error",) and not name.endswith("_destroy"):
             getattr(L, name).restype = i32
@@ -290,6 +297,41 @@ class MatcherBatch:
         status = np.zeros(len(self.matchers), dtype=np.int32)
         _check(lib.xg2_matcher_accept_tokens(self.arr, ids.ctypes.data, len(self.matchers), status.ctypes.data))
         return status
+
+
+class DeviceBatch:
+    """B matcher slots in device memory (argument marshalling only)."""
+
+    def __init__(self, vocab: Vocab, batch: int):
+        self.h = ctypes.c_void_p()
+        self.vocab, self.batch, self._caches = vocab, batch, []
+        _check(lib.xg2_batch_create(vocab.h, batch, ctypes.byref(self.h)))
+
+    def assign(self, cache: "MaskCache", rows: Optional[Sequence[int]] = None, stream: int = 0) -> None:
+        self._caches.append(cache)
+        if rows is None:
+            _check(lib.xg2_batch_assign(self.h, None, 0, cache.h, ctypes.c_void_p(stream)))
+        else:
+            arr = np.ascontiguousarray(rows, dtype=np.int32)
+            _check(lib.xg2_batch_assign(self.h, arr.ctypes.data, len(arr), cache.h, ctypes.c_void_p(stream)))
+
+    def accept_tokens(self, token_ids_ptr: int, status_ptr: int = 0, stream: int = 0) -> None:
+        _check(lib.xg2_batch_accept_tokens(self.h, ctypes.c_void_p(token_ids_ptr), ctypes.c_void_p(status_ptr) if status_ptr else None,
+                                           ctypes.c_void_p(stream)))
+
+    def fill_next_token_bitmask(self, bitmask_ptr: int, row_stride_words: int, stream: int = 0) -> None:
+        _check(lib.xg2_batch_fill_next_token_bitmask(self.h, ctypes.c_void_p(bitmask_ptr), row_stride_words, ctypes.c_void_p(stream)))
+
+    def row_info(self, row: int) -> dict:
+        out = np.zeros(8, dtype=np.int32)
+        _check(lib.xg2_batch_row_info(self.h, row, out.ctypes.data))
+        keys = ("can_end", "terminated", "error", "sets", "items", "wait_entries", "planes", "cache")
+        return dict(zip(keys, (int(v) for v in out)))
+
+    def __del__(self):
+        if getattr(self, "h", None):
+            lib.xg2_batch_destroy(self.h)
+            self.h = None
 
 
 def fill_next_token_bitmask(matchers, bitmask_ptr: int, row_stride_words: int, stream: int = 0) -> None:

@@ -434,6 +434,16 @@ struct CacheImpl {
     DevTables dt{};
     int32_t context_depth = 2;
     std::vector<PlaneInfo> planes;
+    // for matchers that live on the device: plane look-up tables and the start state, made at first use
+    struct OnDevice {
+        std::mutex mu;
+        bool ready = false;
+        DevBuf<uint64_t> plain_row, pair_row, start_front;
+        DevBuf<uint32_t> pair_off, pair_key, start_items, start_wait_off;
+        DevBuf<uint2> start_wait;
+        CacheDev cd{};
+        uint32_t n_start_wait = 0;
+    } on_device;
     std::vector<int32_t> plain_plane;                       // [sid] -> plane without context, or -1
     std::unordered_map<uint64_t, int32_t> pair_plane;       // (sid << 32 | parent continuation sid) -> plane
 };
@@ -906,6 +916,81 @@ void prepare_matcher(MatcherImpl& M) {
         }
     }
     P.valid = true;
+}
+
+// ---- matchers on the device -----------------------------------------------------------------------------------
+struct BatchImpl {
+    static constexpr uint32_t KI = 64, KH = 240, KW = 512, KF = 16, kMaxCaches = 256;
+    std::mutex mu;
+    std::shared_ptr<VocabImpl> vocab;
+    int32_t B = 0;
+    BatchDev d{};
+    DevBuf<FillRow> rows;
+    DevBuf<uint64_t> front, slow_front;
+    DevBuf<uint32_t> items, wait_off, slow_mem, flag_words;
+    DevBuf<uint2> wait;
+    DevBuf<uint8_t> slow_map;
+    DevBuf<CacheDev> caches_dev;
+    DevBuf<DevTables> tables_dev;
+    DevBuf<int32_t> row_list;
+    std::vector<std::shared_ptr<CacheImpl>> caches;
+    std::vector<uint8_t> assigned;
+    int32_t n_assigned = 0;
+};
+
+struct xg2_batch { std::unique_ptr<BatchImpl> p; };
+
+// Plane look-up tables and start state of a fully built cache, on the device.
+void ensure_cache_on_device(const std::shared_ptr<CacheImpl>& cp) {
+    CacheImpl& C = *cp;
+    std::lock_guard<std::mutex> lk(C.on_device.mu);
+    if (C.on_device.ready) return;
+    if (C.n_built != (int64_t)C.planes.size())
+        throw GrammarError("matchers on the device need a fully built mask cache (this one was compiled just in time)");
+    CacheImpl::OnDevice& D = C.on_device;
+    const size_t n_states = (size_t)C.gram->g.n_states;
+    auto row_word = [&](int32_t plane, bool accepted_only) {
+        const PlaneInfo& pi = C.planes[(size_t)plane];
+        return (uint64_t)(uintptr_t)pi.row | ((accepted_only || pi.no_uncertain) ? 1u : 0u);
+    };
+    std::vector<uint64_t> plain(n_states, 0);
+    for (size_t sid = 0; sid < n_states; ++sid) if (C.plain_plane[sid] >= 0) plain[sid] = row_word(C.plain_plane[sid], false);
+    std::vector<std::array<uint64_t, 3>> pairs;                 // (state, state the referencing rule continues in, row)
+    pairs.reserve(C.pair_plane.size());
+    for (auto& kv : C.pair_plane) pairs.push_back({kv.first >> 32, kv.first & 0xFFFFFFFFull, row_word(kv.second, false)});
+    std::sort(pairs.begin(), pairs.end());
+    std::vector<uint32_t> pair_off(n_states + 1, 0), pair_key(std::max<size_t>(pairs.size(), 1), 0);
+    std::vector<uint64_t> pair_row(std::max<size_t>(pairs.size(), 1), 0);
+    for (size_t k = 0; k < pairs.size(); ++k) { ++pair_off[(size_t)pairs[k][0] + 1]; pair_key[k] = (uint32_t)pairs[k][1]; pair_row[k] = pairs[k][2]; }
+    for (size_t sid = 0; sid < n_states; ++sid) pair_off[sid + 1] += pair_off[sid];
+    // the start state, through the host parser
+    MatcherImpl M(C.gram, C.vocab);
+    M.cache = cp;
+    prepare_matcher(M);
+    if (M.prep.status != XG2_OK) throw GrammarError(M.prep.error);
+    std::vector<uint32_t> s_items;
+    for (uint32_t it : M.prep.ctx.items) if (it & kHasByte) s_items.push_back(it);
+    std::vector<uint64_t> s_front;
+    for (auto& pl : M.prep.planes) {
+        const uint64_t w = row_word(pl.first, pl.second);
+        bool seen = false;
+        for (uint64_t& have : s_front) if ((have & ~(uint64_t)1) == (w & ~(uint64_t)1)) { have &= w | ~(uint64_t)1; seen = true; }
+        if (!seen) s_front.push_back(w);
+    }
+    std::vector<uint2> s_wait(M.prep.ctx.wait.size() / 2);
+    for (size_t k = 0; k < s_wait.size(); ++k) s_wait[k] = make_uint2(M.prep.ctx.wait[2 * k], M.prep.ctx.wait[2 * k + 1]);
+    D.plain_row.upload(plain, nullptr); D.pair_off.upload(pair_off, nullptr); D.pair_key.upload(pair_key, nullptr); D.pair_row.upload(pair_row, nullptr);
+    D.start_items.upload(s_items, nullptr); D.start_front.upload(s_front, nullptr); D.start_wait.upload(s_wait, nullptr);
+    D.start_wait_off.upload(M.prep.ctx.wait_off, nullptr);
+    HIP_CHECK(hipStreamSynchronize(nullptr));
+    D.cd.T = C.dt;
+    D.cd.plain_row = D.plain_row.p; D.cd.pair_off = D.pair_off.p; D.cd.pair_key = D.pair_key.p; D.cd.pair_row = D.pair_row.p;
+    D.cd.context_depth = (uint32_t)C.context_depth;
+    D.cd.start_n_items = (uint32_t)s_items.size(); D.cd.start_H = M.prep.ctx.H; D.cd.start_n_front = (uint32_t)s_front.size();
+    D.cd.start_flags = M.chart.last().root_done ? 1u : 0u;
+    D.cd.start_items = D.start_items.p; D.cd.start_wait = D.start_wait.p; D.cd.start_wait_off = D.start_wait_off.p; D.cd.start_front = D.start_front.p;
+    D.n_start_wait = (uint32_t)s_wait.size();
+    D.ready = true;
 }
 
 extern "C" {
@@ -1726,6 +1811,137 @@ int32_t xg2_apply_token_bitmask(void* logits_dev, int32_t dtype, int32_t B, int3
         require_device();
         launch_apply(logits_dev, dtype, B, V, row_stride_elems, bitmask_dev, bm_row_stride_words, (hipStream_t)hip_stream);
         HIP_CHECK(hipGetLastError());
+        return XG2_OK;
+    });
+}
+
+// ---- matchers on the device ---------------------------------------------------------------------------------------
+
+int32_t xg2_batch_create(xg2_vocab* vocab, int32_t B, xg2_batch** out) {
+    return guarded([&]() -> int32_t {
+        if (!vocab || !out || B <= 0 || B > (1 << 20)) return fail(XG2_EINVAL, "xg2_batch_create: bad argument");
+        vocab->p->ensure_device();
+        auto b = std::make_unique<BatchImpl>();
+        b->vocab = vocab->p;
+        b->B = B;
+        const size_t n = (size_t)B;
+        b->rows.alloc(n); b->front.alloc(n * BatchImpl::KF); b->slow_front.alloc(n * BatchImpl::KF);
+        b->items.alloc(2 * n * BatchImpl::KI); b->wait.alloc(2 * n * BatchImpl::KW); b->wait_off.alloc(2 * n * (BatchImpl::KH + 1));
+        b->slow_mem.alloc(n * kSlowSlots); b->slow_map.alloc(n * (BatchImpl::KH + kSlowMaxLen + 1));
+        b->flag_words.alloc(4);
+        b->caches_dev.alloc(BatchImpl::kMaxCaches); b->tables_dev.alloc(BatchImpl::kMaxCaches);
+        b->row_list.alloc(n);
+        HIP_CHECK(hipMemset(b->rows.p, 0, n * sizeof(FillRow)));
+        HIP_CHECK(hipMemset(b->flag_words.p, 0, 4 * sizeof(uint32_t)));
+        b->assigned.assign(n, 0);
+        BatchDev& d = b->d;
+        d.B = (uint32_t)B; d.KI = BatchImpl::KI; d.KH = BatchImpl::KH; d.KW = BatchImpl::KW; d.KF = BatchImpl::KF;
+        d.rows = b->rows.p; d.front = b->front.p; d.items = b->items.p; d.wait = b->wait.p; d.wait_off = b->wait_off.p;
+        d.caches = b->caches_dev.p; d.tables = b->tables_dev.p;
+        d.slow_mem = b->slow_mem.p; d.slow_map = b->slow_map.p; d.slow_front = b->slow_front.p;
+        *out = new xg2_batch{std::move(b)};
+        return XG2_OK;
+    });
+}
+void xg2_batch_destroy(xg2_batch* b) {
+    if (b) (void)hipDeviceSynchronize();                        // kernels may still be reading the slots
+    delete b;
+}
+
+int32_t xg2_batch_assign(xg2_batch* batch, const int32_t* rows_host, int32_t n, const xg2_mask_cache* cache, void* hip_stream) {
+    return guarded([&]() -> int32_t {
+        if (!batch || !cache || n < 0) return fail(XG2_EINVAL, "xg2_batch_assign: bad argument");
+        BatchImpl& Bt = *batch->p;
+        std::lock_guard<std::mutex> lk(Bt.mu);
+        if (cache->p->vocab.get() != Bt.vocab.get()) return fail(XG2_EINVAL, "xg2_batch_assign: the cache was compiled for another vocabulary");
+        if (!rows_host) n = Bt.B;
+        if (n > Bt.B) return fail(XG2_EINVAL, "xg2_batch_assign: more rows than slots");
+        for (int32_t k = 0; rows_host && k < n; ++k)
+            if (rows_host[k] < 0 || rows_host[k] >= Bt.B) return fail(XG2_EINVAL, "xg2_batch_assign: row out of range");
+        if (n == 0) return XG2_OK;
+        hipStream_t stream = (hipStream_t)hip_stream;
+        ensure_cache_on_device(cache->p);
+        const CacheImpl::OnDevice& od = cache->p->on_device;
+        if (od.cd.start_n_items > BatchImpl::KI || od.cd.start_H > BatchImpl::KH || od.n_start_wait > BatchImpl::KW || od.cd.start_n_front > BatchImpl::KF)
+            return fail(XG2_EOVERFLOW, "xg2_batch_assign: the grammar's start state exceeds a matcher slot");
+        size_t ci = 0;
+        while (ci < Bt.caches.size() && Bt.caches[ci].get() != cache->p.get()) ++ci;
+        if (ci == Bt.caches.size()) {
+            if (ci >= BatchImpl::kMaxCaches) return fail(XG2_EOVERFLOW, "xg2_batch_assign: too many different caches in one batch");
+            Bt.caches.push_back(cache->p);                      // kept alive while the batch lives
+            HIP_CHECK(hipMemcpyAsync(Bt.caches_dev.p + ci, &od.cd, sizeof(CacheDev), hipMemcpyHostToDevice, stream));
+            HIP_CHECK(hipMemcpyAsync(Bt.tables_dev.p + ci, &od.cd.T, sizeof(DevTables), hipMemcpyHostToDevice, stream));
+        }
+        if (rows_host) HIP_CHECK(hipMemcpyAsync(Bt.row_list.p, rows_host, (size_t)n * sizeof(int32_t), hipMemcpyHostToDevice, stream));
+        launch_batch_assign(Bt.d, rows_host ? Bt.row_list.p : nullptr, (uint32_t)n, (uint32_t)ci, stream);
+        HIP_CHECK(hipGetLastError());
+        HIP_CHECK(hipStreamSynchronize(stream));                // row_list and the host arrays may be reused by the next call
+        for (int32_t k = 0; k < n; ++k) {
+            uint8_t& a = Bt.assigned[(size_t)(rows_host ? rows_host[k] : k)];
+            if (!a) { a = 1; ++Bt.n_assigned; }
+        }
+        return XG2_OK;
+    });
+}
+
+int32_t xg2_batch_accept_tokens(xg2_batch* batch, const int32_t* token_ids_dev, int32_t* status_dev, void* hip_stream) {
+    return guarded([&]() -> int32_t {
+        if (!batch || !token_ids_dev) return fail(XG2_EINVAL, "xg2_batch_accept_tokens: bad argument");
+        BatchImpl& Bt = *batch->p;
+        std::lock_guard<std::mutex> lk(Bt.mu);
+        if (Bt.n_assigned != Bt.B) return fail(XG2_EINVAL, "xg2_batch_accept_tokens: every slot needs a cache first (xg2_batch_assign)");
+        launch_accept(Bt.d, Bt.vocab->dv, (uint32_t)Bt.vocab->eos, token_ids_dev, status_dev, (hipStream_t)hip_stream);
+        HIP_CHECK(hipGetLastError());
+        return XG2_OK;
+    });
+}
+
+int32_t xg2_batch_fill_next_token_bitmask(xg2_batch* batch, int32_t* bitmask_dev, int64_t row_stride_words, void* hip_stream) {
+    return guarded([&]() -> int32_t {
+        if (!batch || !bitmask_dev) return fail(XG2_EINVAL, "xg2_batch_fill_next_token_bitmask: bad argument");
+        BatchImpl& Bt = *batch->p;
+        std::lock_guard<std::mutex> lk(Bt.mu);
+        VocabImpl& V = *Bt.vocab;
+        if (row_stride_words < (int64_t)V.W) return fail(XG2_EINVAL, "xg2_batch_fill_next_token_bitmask: row stride smaller than ceil(V/32)");
+        if (Bt.n_assigned != Bt.B) return fail(XG2_EINVAL, "xg2_batch_fill_next_token_bitmask: every slot needs a cache first (xg2_batch_assign)");
+        hipStream_t stream = (hipStream_t)hip_stream;
+        std::lock_guard<std::mutex> ws_lock(fill_ws().mu);
+        std::lock_guard<std::mutex> slow_lock(slow().mu);
+        slow().ensure();
+        SlowScratch S = slow().s;
+        fill_ws().ensure_scratch((size_t)Bt.B * V.W, (size_t)Bt.B);
+        FillBatch F{};
+        F.rows = Bt.d.rows; F.B = (uint32_t)Bt.B;
+        F.front_planes = Bt.d.front; F.ctx_items = Bt.d.items; F.ctx_wait = Bt.d.wait; F.ctx_wait_off = Bt.d.wait_off;
+        F.tables = Bt.d.tables;
+        F.eos_id = (uint32_t)V.eos;
+        F.cand_words = fill_ws().cand_words.p; F.work_list = fill_ws().work_list.p; F.row_count = fill_ws().row_count.p;
+        F.zero_words = Bt.flag_words.p;                         // nothing is uploaded: the union kernel clears the overflow counter
+        S.count = Bt.flag_words.p;
+        HIP_CHECK(hipEventRecord(fill_ws().t_begin, stream));
+        launch_fill(F, V.dv, bitmask_dev, row_stride_words, S, stream);
+        launch_recheck_slow(F, V.dv, bitmask_dev, row_stride_words, S, stream);
+        HIP_CHECK(hipGetLastError());
+        HIP_CHECK(hipEventRecord(fill_ws().t_end, stream));
+        fill_ws().last_flags = S.count; fill_ws().last_counts = F.row_count; fill_ws().last_B = Bt.B; fill_ws().last_stream = stream;
+        fill_ws().timed = true; fill_ws().any = true;
+        return XG2_OK;
+    });
+}
+
+int32_t xg2_batch_row_info(xg2_batch* batch, int32_t row, int32_t* info_host) {
+    return guarded([&]() -> int32_t {
+        if (!batch || !info_host || row < 0 || row >= batch->p->B) return fail(XG2_EINVAL, "xg2_batch_row_info: bad argument");
+        BatchImpl& Bt = *batch->p;
+        std::lock_guard<std::mutex> lk(Bt.mu);
+        HIP_CHECK(hipDeviceSynchronize());
+        FillRow r;
+        HIP_CHECK(hipMemcpy(&r, Bt.rows.p + row, sizeof(r), hipMemcpyDeviceToHost));
+        uint32_t n_wait = 0;
+        HIP_CHECK(hipMemcpy(&n_wait, Bt.wait_off.p + r.waitoff_off + r.H, sizeof(uint32_t), hipMemcpyDeviceToHost));
+        info_host[0] = (r.flags & 1u) ? 1 : 0; info_host[1] = (r.flags & 2u) ? 1 : 0; info_host[2] = (int32_t)r.pad[1];
+        info_host[3] = (int32_t)r.H; info_host[4] = (int32_t)r.item_n; info_host[5] = (int32_t)n_wait; info_host[6] = (int32_t)r.front_n;
+        info_host[7] = Bt.assigned[(size_t)row] ? (int32_t)r.tables_idx : -1;
         return XG2_OK;
     });
 }

@@ -112,11 +112,48 @@ struct FillBatch {
     uint32_t* cand_words;                // [B * W]
     uint32_t* work_list;                 // [B * W], row b's list starts at b * W
     uint32_t* row_count;                 // [B], written by the union kernel
+    uint32_t* zero_words;                // if not null: two words the union kernel clears (the overflow list's length and flag, where
+                                         // no upload brings them in as zeros)
 };
 void launch_fill(const FillBatch& F, const DevVocab& Vd, int32_t* bitmask_dev, int64_t row_stride_words,
                  const SlowScratch& S, hipStream_t stream);
 void launch_recheck_slow(const FillBatch& F, const DevVocab& Vd, int32_t* bitmask_dev, int64_t row_stride_words,
                          const SlowScratch& S, hipStream_t stream);
+
+// ---- matchers that live on the device ------------------------------------------------------------------------
+// What a matcher needs of its mask cache besides the tables: the plane of every (state) and (state, state the
+// referencing rule continues in), as device addresses of accepted rows with bit 0 = "only the accepted row counts"
+// (an all-zero uncertain row), and the matcher state a new sequence starts from.
+struct CacheDev {
+    DevTables T;
+    const uint64_t* plain_row;           // [n_states] plane of a position without context (root rule, or context depth 1), 0 = none
+    const uint32_t* pair_off;            // [n_states + 1] CSR over states: the planes of the state under its referencing sites
+    const uint32_t* pair_key;            //   state id the referencing rule continues in
+    const uint64_t* pair_row;
+    uint32_t context_depth;
+    uint32_t start_n_items, start_H, start_n_front, start_flags;
+    const uint32_t* start_items; const uint2* start_wait; const uint32_t* start_wait_off; const uint64_t* start_front;
+};
+// B matcher slots of fixed capacity.  Slot b's state is what FillRow b points at: its frontier planes at front[b * KF ..],
+// and its parser context (items of the current closed set that can scan; per reachable older set what its waiting items
+// wait for) in one of two buffers, c = rows[b].pad[0]: items[(c * B + b) * KI ..], wait[(c * B + b) * KW ..],
+// wait_off[(c * B + b) * (KH + 1) ..].  Accepting a token writes the other buffer and switches.  rows[b].pad[1] holds a
+// sticky error (a capacity was exceeded: the slot is unusable until it is reset), rows[b].tables_idx the slot's cache.
+struct BatchDev {
+    uint32_t B, KI, KH, KW, KF;
+    FillRow* rows;
+    uint64_t* front; uint32_t* items; uint2* wait; uint32_t* wait_off;
+    const CacheDev* caches; const DevTables* tables;     // [number of caches in use] (tables: the same DevTables, as fill wants them)
+    uint32_t* slow_mem;                                   // item lists in device memory for tokens the LDS lists cannot take: B * kSlowSlots words
+    uint8_t* slow_map;                                    // and the set renumbering table: B * (KH + kSlowMaxLen + 1) bytes
+    uint64_t* slow_front;                                 // B * KF staging words
+};
+constexpr int32_t kTokenReset = -2;      // xg2_batch_accept_tokens: "start a new sequence in this slot"
+// status codes written per slot (the XG2_* values of the C ABI)
+constexpr int32_t kAccOk = 0, kAccInvalid = -1, kAccRejected = -3, kAccOverflow = -4;
+void launch_accept(const BatchDev& D, const DevVocab& Vd, uint32_t eos_id, const int32_t* token_ids_dev, int32_t* status_dev, hipStream_t stream);
+// rows_dev (n of them; nullptr = slots 0 .. n - 1) start a new sequence of cache `cache_idx`
+void launch_batch_assign(const BatchDev& D, const int32_t* rows_dev, uint32_t n, uint32_t cache_idx, hipStream_t stream);
 
 // Copies `bytes` (a multiple of 16) from pinned host memory, given by its device-side address, to device memory with
 // a kernel: for the small per-call uploads this has less latency than the copy engine.

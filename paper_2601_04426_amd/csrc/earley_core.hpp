@@ -124,8 +124,15 @@ __device__ __forceinline__ void enter(const DevTables& T, S& st, uint32_t ref, u
 // recogniser is a plain automaton walk: the item stays in a register and a byte costs one table load.
 // The lists in `st` are used from the first state that predicts or completes, and left again when the
 // set shrinks back to one such item (older wait entries stay where they are).
-template <class S, bool FOLLOW = false, class BYTES = RegBytes>
-__device__ int scan_token(const DevTables& T, const uint32_t* cls_words, const DevCtx& C, BYTES tok, int n, S& st) {
+// What is left in the lists after the last byte, for a caller that goes on from there (a matcher accepting a token):
+// the items of the last set are `one` if `single`, else cur[0 .. nc); the wait entries made during the token are
+// wait[0 .. nw), those of new set j at [wstart(j), wstart(j + 1)) with wstart(n) = nw (with this output every new set's
+// start is recorded, also the sets the automaton walk makes); root_done: the root instance can end after the last byte.
+struct NoScanOut { static constexpr bool on = false; int nc; uint32_t one; bool single; int nw; bool root_done; };
+struct ScanOut { static constexpr bool on = true; int nc = 0; uint32_t one = 0; bool single = false; int nw = 0; bool root_done = false; };
+
+template <class S, bool FOLLOW = false, class BYTES = RegBytes, class OUT = NoScanOut>
+__device__ int scan_token(const DevTables& T, const uint32_t* cls_words, const DevCtx& C, BYTES tok, int n, S& st, OUT* out = nullptr) {
     if (n > S::MAXLEN || (int)C.n_items > st.K) return RES_OVERFLOW;
     if (C.H + (uint32_t)n > ROOT_ORIGIN) return RES_OVERFLOW;       // the new sets C.H .. C.H + n - 1 must stay below the root mark
     int nc = (int)C.n_items;
@@ -135,6 +142,8 @@ __device__ int scan_token(const DevTables& T, const uint32_t* cls_words, const D
     int nw = 0;
     int res = 0;
     int i = 0;
+    bool last_root = false;                                      // (OUT only) the root instance could end after the latest byte
+    if (OUT::on) st.set_wstart(0, 0u);
     for (;;) {
         // ---- automaton walk: one item, in a register; a byte costs one table load ----------------
         uint32_t pending = NO_TARGET;
@@ -146,6 +155,7 @@ __device__ int scan_token(const DevTables& T, const uint32_t* cls_words, const D
             if (tgt & (F_REF | F_FINAL)) { pending = tgt; single = false; break; }   // this state predicts or completes
             one = tgt | (one & ~REF_MASK);
             ++i;
+            if (OUT::on) { last_root = false; if (i < n) st.set_wstart(i, (uint32_t)nw); }
         }
         if (i >= n) break;
         // ---- one general step for byte i ---------------------------------------------------------
@@ -209,6 +219,7 @@ __device__ int scan_token(const DevTables& T, const uint32_t* cls_words, const D
         if (full) return RES_OVERFLOW;
         if (nn == 0 && nw == wbeg) return res;               // dead: nothing survives this byte
         if (root_now && i + 1 < n) res |= RES_EARLY;
+        if (OUT::on) last_root = root_now;
         st.swap();
         nc = nn;
         ++i;
@@ -218,6 +229,7 @@ __device__ int scan_token(const DevTables& T, const uint32_t* cls_words, const D
             single = (one & (F_BYTE | F_REF | F_FINAL)) == F_BYTE;
         }
     }
+    if (OUT::on) { out->nc = nc; out->one = one; out->single = single; out->nw = nw; out->root_done = last_root; }
     return res | RES_ALIVE;
 }
 

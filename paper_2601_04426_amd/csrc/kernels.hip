@@ -16,6 +16,7 @@
 
 #include "device.hpp"
 #include "earley_core.hpp"
+#include "accept_core.hpp"
 
 namespace xg2 {
 namespace {
@@ -549,6 +550,7 @@ __global__ __launch_bounds__(FILL_THREADS) void k_fill_or(FillBatch F, DevVocab 
     __shared__ uint32_t n_listed;
     const uint32_t b = blockIdx.x;
     if (threadIdx.x == 0) n_listed = 0;
+    if (F.zero_words && b == 0 && threadIdx.x < 2) F.zero_words[threadIdx.x] = 0;
     __syncthreads();
     const uint32_t front_off = F.rows[b].front_off, front_n = F.rows[b].front_n, flags = F.rows[b].flags;
     const uint32_t eos_word = F.eos_id >> 5, eos_bit = 1u << (F.eos_id & 31);
@@ -689,6 +691,105 @@ __global__ __launch_bounds__(64) void k_recheck_slow(FillBatch F, DevVocab Vd, i
     }
 }
 
+// ---- matchers on the device ------------------------------------------------------------------------
+// k_accept: one lane per matcher slot takes the slot's sampled token through the recogniser and writes the slot's
+// next context and frontier planes (accept_core.hpp).  The common case runs with the item lists, the renumbering
+// table and the frontier staging in LDS; a token or context too large for that runs again with all three in device
+// memory.  A slot whose capacity is exceeded gets a sticky error and answers XG2_EOVERFLOW until it is reset.
+constexpr int ACCEPT_MAP = 240 + 16, ACCEPT_FRONT = 16;            // sets the LDS table renumbers; planes the LDS staging holds
+struct LdsScratchX {
+    uint8_t* map; uint64_t* front;                                  // this lane's columns
+    __device__ uint32_t map_cap() const { return ACCEPT_MAP; }
+    __device__ uint32_t front_cap() const { return ACCEPT_FRONT; }
+    __device__ uint32_t map_get(uint32_t i) const { return map[i * 64]; }
+    __device__ void map_set(uint32_t i, uint32_t v) { map[i * 64] = (uint8_t)v; }
+    __device__ uint64_t front_get(uint32_t k) const { return front[k * 64]; }
+    __device__ void front_set(uint32_t k, uint64_t v) { front[k * 64] = v; }
+};
+struct GlobalScratchX {
+    uint8_t* map; uint64_t* front; size_t stride; uint32_t n_map, n_front;
+    __device__ uint32_t map_cap() const { return n_map; }
+    __device__ uint32_t front_cap() const { return n_front; }
+    __device__ uint32_t map_get(uint32_t i) const { return map[(size_t)i * stride]; }
+    __device__ void map_set(uint32_t i, uint32_t v) { map[(size_t)i * stride] = (uint8_t)v; }
+    __device__ uint64_t front_get(uint32_t k) const { return front[(size_t)k * stride]; }
+    __device__ void front_set(uint32_t k, uint64_t v) { front[(size_t)k * stride] = v; }
+};
+
+__device__ __forceinline__ void start_sequence(const BatchDev& D, uint32_t b, uint32_t cache_idx) {
+    const CacheDev& Cd = D.caches[cache_idx];
+    FillRow r{};
+    r.front_off = b * D.KF; r.front_n = Cd.start_n_front;
+    r.item_off = b * D.KI; r.item_n = Cd.start_n_items;
+    r.wait_base = b * D.KW; r.waitoff_off = b * (D.KH + 1); r.H = Cd.start_H;
+    r.tables_idx = cache_idx; r.flags = Cd.start_flags;
+    r.pad[0] = 0; r.pad[1] = 0; r.pad[2] = 0;
+    for (uint32_t k = 0; k < Cd.start_n_front; ++k) D.front[r.front_off + k] = Cd.start_front[k];
+    for (uint32_t k = 0; k < Cd.start_n_items; ++k) D.items[r.item_off + k] = Cd.start_items[k];
+    for (uint32_t k = 0; k <= Cd.start_H; ++k) D.wait_off[r.waitoff_off + k] = Cd.start_wait_off[k];
+    for (uint32_t k = 0; k < Cd.start_wait_off[Cd.start_H]; ++k) D.wait[r.wait_base + k] = Cd.start_wait[k];
+    D.rows[b] = r;
+}
+
+__global__ __launch_bounds__(256) void k_batch_assign(BatchDev D, const int32_t* rows, uint32_t n, uint32_t cache_idx) {
+    const uint32_t i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    const uint32_t b = rows ? (uint32_t)rows[i] : i;
+    if (b < D.B) start_sequence(D, b, cache_idx);
+}
+
+__global__ __launch_bounds__(64) void k_accept(BatchDev D, DevVocab Vd, uint32_t eos_id, const int32_t* token_ids, int32_t* status) {
+    __shared__ uint32_t lds_store[FillStore::SLOTS * 64];
+    __shared__ uint8_t lds_map[ACCEPT_MAP * 64];
+    __shared__ uint64_t lds_front[ACCEPT_FRONT * 64];
+    const uint32_t lane = threadIdx.x, b = blockIdx.x * 64 + lane;
+    if (b >= D.B) return;
+    const int32_t tok = token_ids[b];
+    int32_t code = kAccOk;
+    FillRow r = D.rows[b];
+    if (tok == kTokenReset) start_sequence(D, b, r.tables_idx);
+    else if (tok < 0) code = kAccOk;                                 // nothing for this slot
+    else if (r.pad[1]) code = kAccOverflow;                          // unusable until reset
+    else if ((r.flags & 2u) || (uint32_t)tok >= Vd.V) code = kAccInvalid;
+    else if ((uint32_t)tok == eos_id) {
+        if (r.flags & 1u) D.rows[b].flags = r.flags | 2u;            // the sequence ends here
+        else code = kAccRejected;
+    } else {
+        const uint32_t rank = Vd.rank[tok];
+        if (rank >= Vd.n_sorted) code = kAccRejected;                // special and empty tokens are never allowed
+        else {
+            const uint32_t off = Vd.off[rank];
+            const int n = (int)(Vd.off[rank + 1] - off);
+            const uint32_t cur = r.pad[0], nb = cur ^ 1u;
+            const CacheDev& Cd = D.caches[r.tables_idx];
+            MatcherIn in{D.items + r.item_off, r.item_n, D.wait + r.wait_base, D.wait_off + r.waitoff_off, r.H};
+            const size_t slot = (size_t)nb * D.B + b;
+            MatcherOut out{D.items + slot * D.KI, D.wait + slot * D.KW, D.wait_off + slot * (D.KH + 1), D.front + (size_t)b * D.KF,
+                           D.KI, D.KH, D.KW, D.KF, 0, 0, 0, 0};
+            FillStore st;
+            st.init(lds_store + lane);
+            LdsScratchX x{lds_map + lane, lds_front + lane};
+            int acc = accept_token(Cd, Cd.T.byte_class_words, in, Vd.bytes + off, n, st, x, out);
+            if (acc == ACC_RETRY) {
+                GlobalStore gs;
+                gs.init(D.slow_mem + b, D.B);
+                GlobalScratchX gx{D.slow_map + b, D.slow_front + b, D.B, D.KH + kSlowMaxLen + 1, D.KF};
+                acc = accept_token(Cd, Cd.T.byte_class_words, in, Vd.bytes + off, n, gs, gx, out);
+            }
+            if (acc == ACC_OK) {
+                r.front_n = out.n_front;
+                r.item_off = (uint32_t)(slot * D.KI); r.item_n = out.n_items;
+                r.wait_base = (uint32_t)(slot * D.KW); r.waitoff_off = (uint32_t)(slot * (D.KH + 1)); r.H = out.H;
+                r.flags = out.root_done;
+                r.pad[0] = nb;
+                D.rows[b] = r;
+            } else if (acc == ACC_REJECTED) code = kAccRejected;
+            else { D.rows[b].pad[1] = 1u; code = kAccOverflow; }     // a capacity of the slot (or of the device-memory lists) was exceeded
+        }
+    }
+    if (status) status[b] = code;
+}
+
 // ---- apply -----------------------------------------------------------------------------------------
 // One 16-byte vector per thread per step: 4 fp32 or 8 bf16.  A vector whose tokens are all allowed is
 // left alone (no read, no write); one whose tokens are all disallowed is overwritten without a read;
@@ -813,6 +914,16 @@ void launch_build(const DevTables& T, const DevVocab& Vd, BuildPlan P, const Slo
 
 void launch_build_slow(const DevTables& T, const DevVocab& Vd, const BuildPlan& P, const SlowScratch& S, hipStream_t stream) {
     hipLaunchKernelGGL(k_build_slow, dim3(S.n_lanes / 64), dim3(64), 0, stream, T, Vd, P, S);
+}
+
+void launch_accept(const BatchDev& D, const DevVocab& Vd, uint32_t eos_id, const int32_t* token_ids_dev, int32_t* status_dev, hipStream_t stream) {
+    if (!D.B) return;
+    hipLaunchKernelGGL(k_accept, dim3((D.B + 63) / 64), dim3(64), 0, stream, D, Vd, eos_id, token_ids_dev, status_dev);
+}
+
+void launch_batch_assign(const BatchDev& D, const int32_t* rows_dev, uint32_t n, uint32_t cache_idx, hipStream_t stream) {
+    if (!n) return;
+    hipLaunchKernelGGL(k_batch_assign, dim3((n + 255) / 256), dim3(256), 0, stream, D, rows_dev, n, cache_idx);
 }
 
 void launch_upload(void* dst_dev, const void* src_host_mapped, size_t bytes, hipStream_t stream) {

@@ -6,6 +6,10 @@
 #include <string>
 #include <vector>
 
+#include <algorithm>
+#include <map>
+
+#include "../../paper_2601_04426_amd/csrc/accept_core.hpp"
 #include "../../paper_2601_04426_amd/csrc/earley_core.hpp"
 #include "../../paper_2601_04426_amd/csrc/grammar.hpp"
 #include "../../paper_2601_04426_amd/csrc/tables.hpp"
@@ -221,6 +225,186 @@ extern "C" long long xg2hc_check_near(const char* ebnf, size_t len, const char* 
         }
         if (n_near) *n_near = near_states;
         if (max_depth) *max_depth = deepest;
+        return checked;
+    } catch (const std::exception& e) {
+        snprintf(msg, msg_cap, "exception: %s", e.what());
+        return -1;
+    }
+}
+
+
+// The device matcher's "accept a token" step (accept_core.hpp), compiled for the host, against the host Earley parser:
+// along every token sequence given (ids into the token list, -1 ends a sequence) the context it writes must equal
+// EarleyChart::context() after the same tokens (same sets in the same order; items and wait entries as sets), the
+// root-can-end flag must agree, rejected tokens must be rejected and leave the state alone, and the frontier planes must
+// be the ones the host's rule gives (plane tables here hold made-up row numbers, one per (state) and (state, site)).
+// Extra tokens tried at every step (try_ids) exercise rejection.  Returns steps checked or -1 with a message.
+namespace {
+struct HostX {
+    std::vector<uint8_t> map; std::vector<uint64_t> front;
+    HostX(size_t n_map, size_t n_front) : map(n_map), front(n_front) {}
+    uint32_t map_cap() const { return (uint32_t)map.size(); }
+    uint32_t front_cap() const { return (uint32_t)front.size(); }
+    uint32_t map_get(uint32_t i) const { return map.at(i); }
+    void map_set(uint32_t i, uint32_t v) { map.at(i) = (uint8_t)v; }
+    uint64_t front_get(uint32_t k) const { return front.at(k); }
+    void front_set(uint32_t k, uint64_t v) { front.at(k) = v; }
+};
+}  // namespace
+
+extern "C" long long xg2hc_check_accept(const char* ebnf, size_t len, const char* root, const uint8_t* bytes, const uint64_t* offs, int n_tok,
+                                        const int32_t* seq, int n_seq, const int32_t* try_ids, int n_try, int small_lists, char* msg, size_t msg_cap) {
+    try {
+        Grammar g = lower_grammar(std::string(ebnf, len), root);
+        FlatTables ft = flatten(g);
+        CacheDev Cd{};
+        Cd.T.state = reinterpret_cast<const uint4*>(ft.dev_state.data());
+        Cd.T.exp_list = ft.exp_list.data();
+        Cd.T.trans = ft.trans.data();
+        Cd.T.byte_class_words = ft.byte_class_words.data();
+        Cd.T.n_classes = ft.n_classes;
+        Cd.T.sink = ft.sink;
+        Cd.context_depth = 2;
+        // made-up plane rows: plain plane of state s = (s + 1) << 4; plane of (s, site state x) numbered as listed
+        const size_t n_states = ft.state_info.size();
+        std::vector<uint64_t> plain(n_states);
+        for (size_t sid = 0; sid < n_states; ++sid) plain[sid] = (uint64_t)(sid + 1) << 4;
+        std::vector<uint32_t> pair_off(n_states + 1, 0), pair_key;
+        std::vector<uint64_t> pair_row;
+        std::map<std::pair<uint32_t, uint32_t>, uint64_t> pair_of;
+        for (size_t sid = 0; sid < n_states; ++sid) {
+            const uint32_t rule = ft.state_info[sid].rule_final & 0x7FFFFFFFu;
+            for (const RefEdgeP& e : ft.ref_edges)
+                if (e.rule == rule) {
+                    if (pair_of.count({(uint32_t)sid, e.tgt})) continue;
+                    const uint64_t row = ((uint64_t)(n_states + pair_key.size() + 1)) << 4;
+                    pair_of[{(uint32_t)sid, e.tgt}] = row;
+                    pair_key.push_back(e.tgt); pair_row.push_back(row);
+                }
+            pair_off[sid + 1] = (uint32_t)pair_key.size();
+        }
+        if (pair_key.empty()) { pair_key.push_back(0); pair_row.push_back(0); }
+        Cd.plain_row = plain.data(); Cd.pair_off = pair_off.data(); Cd.pair_key = pair_key.data(); Cd.pair_row = pair_row.data();
+        const uint32_t KI = 64, KH = 240, KW = 512, KF = 16;
+        struct State { std::vector<uint32_t> items, wait_off; std::vector<uint2> wait; uint32_t H = 0; bool root_done = false; std::vector<uint64_t> front; };
+        auto host_state = [&](const EarleyChart& chart) {
+            State s;
+            // sets still reachable from the items that can scan (and the current set), through the origins of waiting items
+            const auto& sets = chart.sets();
+            const int32_t J = (int32_t)sets.size() - 1;
+            std::vector<uint8_t> need(sets.size(), 0);
+            need[(size_t)J] = 1;
+            for (const ChartItem& it : sets[(size_t)J].scan)
+                if ((ft.state_info[it.sid].counts & 0xFFFF) && it.origin >= 0) need[(size_t)it.origin] = 1;
+            for (int32_t k = J; k >= 0; --k)
+                if (need[(size_t)k]) for (const ChartItem& w : sets[(size_t)k].wait) if (w.origin >= 0) need[(size_t)w.origin] = 1;
+            std::vector<uint32_t> local(sets.size(), 0);
+            for (size_t k = 0; k < sets.size(); ++k) if (need[k]) local[k] = s.H++;
+            auto loc = [&](int32_t o) { return o < 0 ? kRootOrigin : local[(size_t)o]; };
+            for (const ChartItem& it : sets[(size_t)J].scan)
+                if (ft.state_info[it.sid].counts & 0xFFFF) s.items.push_back(pack_item(ft.ref(it.sid), loc(it.origin)));
+            std::vector<uint32_t> flat;
+            for (size_t k = 0; k < sets.size(); ++k) {
+                if (!need[k]) continue;
+                s.wait_off.push_back((uint32_t)s.wait.size());
+                flat.clear();
+                for (const ChartItem& w : sets[k].wait) chart.push_triples(w, loc(w.origin), flat);
+                for (size_t q = 0; q + 1 < flat.size(); q += 2) s.wait.push_back(make_uint2(flat[q], flat[q + 1]));
+            }
+            s.wait_off.push_back((uint32_t)s.wait.size());
+            s.root_done = chart.last().root_done;
+            // the host's rule for the frontier planes
+            for (const ChartItem& it : chart.last().scan) {
+                const StateInfo& si = ft.state_info[it.sid];
+                if (!(si.counts & 0xFFFF)) continue;
+                auto add = [&](uint64_t row) {
+                    for (uint64_t& have : s.front) if ((have & ~(uint64_t)1) == (row & ~(uint64_t)1)) { have &= row | ~(uint64_t)1; return; }
+                    s.front.push_back(row);
+                };
+                if (it.origin < 0) { add(plain[it.sid] | 1u); continue; }
+                const uint32_t rule = si.rule_final & 0x7FFFFFFFu;
+                for (const ChartItem& w : chart.sets()[(size_t)it.origin].wait) {
+                    const StateInfo& wi = ft.state_info[w.sid];
+                    for (uint32_t k = 0; k < (wi.counts >> 16); ++k) {
+                        const RefEdgeP& e = ft.ref_edges[wi.ref_off + k];
+                        if (e.rule == rule) add(pair_of.at({it.sid, e.tgt}));
+                    }
+                }
+            }
+            return s;
+        };
+        auto same = [&](const State& a, const State& b, std::string& why) {
+            if (a.H != b.H) { why = "number of sets " + std::to_string(a.H) + " vs " + std::to_string(b.H); return false; }
+            if (a.root_done != b.root_done) { why = "root-can-end flag"; return false; }
+            std::vector<uint32_t> ia = a.items, ib = b.items;
+            std::sort(ia.begin(), ia.end()); std::sort(ib.begin(), ib.end());
+            if (ia != ib) { why = "items"; return false; }
+            for (uint32_t s = 0; s < a.H; ++s) {
+                std::vector<std::pair<uint32_t, uint32_t>> wa, wb;
+                for (uint32_t k = a.wait_off[s]; k < a.wait_off[s + 1]; ++k) wa.emplace_back(a.wait[k].x, a.wait[k].y);
+                for (uint32_t k = b.wait_off[s]; k < b.wait_off[s + 1]; ++k) wb.emplace_back(b.wait[k].x, b.wait[k].y);
+                std::sort(wa.begin(), wa.end()); wa.erase(std::unique(wa.begin(), wa.end()), wa.end());
+                std::sort(wb.begin(), wb.end()); wb.erase(std::unique(wb.begin(), wb.end()), wb.end());
+                if (wa != wb) { why = "wait entries of set " + std::to_string(s); return false; }
+            }
+            std::vector<uint64_t> fa = a.front, fb = b.front;
+            std::sort(fa.begin(), fa.end()); std::sort(fb.begin(), fb.end());
+            if (fa != fb) { why = "frontier planes"; return false; }
+            return true;
+        };
+        // one accept step on the device-side state `cur`: 0 accepted (next filled), 1 rejected, else error
+        auto step = [&](const State& cur, const uint8_t* t, int n, State& next) -> int {
+            MatcherIn in{cur.items.data(), (uint32_t)cur.items.size(), cur.wait.data(), cur.wait_off.data(), cur.H};
+            next.items.assign(KI, 0); next.wait.assign(KW, make_uint2(0, 0)); next.wait_off.assign(KH + 1, 0); next.front.assign(KF, 0);
+            MatcherOut out{next.items.data(), next.wait.data(), next.wait_off.data(), next.front.data(), KI, KH, KW, KF, 0, 0, 0, 0};
+            int acc;
+            if (small_lists) {
+                HostStore<8, 12, 16> st;
+                HostX x(256, 16);
+                acc = accept_token(Cd, ft.byte_class_words.data(), in, t, n, st, x, out);
+                if (acc != ACC_RETRY) goto done;
+            }
+            {
+                HostStore<256, 1024, 1024> st;
+                HostX x(KH + 1025, KF);
+                acc = accept_token(Cd, ft.byte_class_words.data(), in, t, n, st, x, out);
+            }
+        done:
+            if (acc == ACC_REJECTED) return 1;
+            if (acc != ACC_OK) return 2 + acc;
+            next.items.resize(out.n_items); next.H = out.H; next.wait_off.resize(out.H + 1); next.wait.resize(next.wait_off[out.H]);
+            next.front.resize(out.n_front); next.root_done = out.root_done != 0;
+            return 0;
+        };
+        long long checked = 0;
+        EarleyChart chart(&ft);
+        chart.start(ft.root_start);
+        State cur = host_state(chart);
+        for (int q = 0; q < n_seq; ++q) {
+            if (seq[q] < 0) { chart.start(ft.root_start); cur = host_state(chart); continue; }
+            // tokens that may or may not be allowed here
+            for (int k = 0; k <= n_try; ++k) {
+                const int id = k < n_try ? try_ids[k] : seq[q];
+                const uint8_t* t = bytes + offs[id];
+                const int n = (int)(offs[id + 1] - offs[id]);
+                if (n == 0) continue;
+                EarleyChart probe = chart;
+                const bool host_ok = probe.advance(t, (size_t)n);
+                State next;
+                const int rc = step(cur, t, n, next);
+                ++checked;
+                if (rc > 1) { snprintf(msg, msg_cap, "step %d token %d: accept failed with code %d", q, id, rc - 2); return -1; }
+                if ((rc == 0) != host_ok) { snprintf(msg, msg_cap, "step %d token %d: host parser %s, device matcher %s", q, id, host_ok ? "accepts" : "rejects", rc == 0 ? "accepts" : "rejects"); return -1; }
+                if (host_ok) {
+                    std::string why;
+                    if (!same(next, host_state(probe), why)) { snprintf(msg, msg_cap, "step %d token %d: %s differ", q, id, why.c_str()); return -1; }
+                }
+                if (k == n_try) {
+                    if (!host_ok) { snprintf(msg, msg_cap, "step %d: the sequence's own token %d is rejected", q, id); return -1; }
+                    chart = probe; cur = next;
+                }
+            }
+        }
         return checked;
     } catch (const std::exception& e) {
         snprintf(msg, msg_cap, "exception: %s", e.what());

@@ -184,3 +184,58 @@ def test_near_equivalent_states_agree_on_short_tokens_random_grammars(hostcheck)
         done += 1
         with_near += near > 0
     assert done >= 40 and with_near >= 10
+
+
+def run_accept(h, ebnf, root, tokens, seq, try_ids, small_lists):
+    blob = b"".join(tokens)
+    offs = [0]
+    for t in tokens:
+        offs.append(offs[-1] + len(t))
+    offs_c = (ctypes.c_uint64 * len(offs))(*offs)
+    seq_c = (ctypes.c_int32 * len(seq))(*seq)
+    try_c = (ctypes.c_int32 * max(1, len(try_ids)))(*(try_ids or [0]))
+    msg = ctypes.create_string_buffer(512)
+    e = ebnf.encode()
+    h.xg2hc_check_accept.restype = ctypes.c_longlong
+    n = h.xg2hc_check_accept(e, ctypes.c_size_t(len(e)), root.encode(), blob, offs_c, len(tokens), seq_c, len(seq), try_c, len(try_ids),
+                             1 if small_lists else 0, msg, ctypes.c_size_t(512))
+    assert n > 0, msg.value.decode()
+    return n
+
+
+@pytest.mark.parametrize("small_lists", [True, False])
+@pytest.mark.parametrize("index", [1, 2, 3, 5])
+def test_device_accept_step_matches_host_parser_on_workloads(hostcheck, index, small_lists):
+    """The step a device-resident matcher takes per token (recogniser run, garbage collection and renumbering of the
+    reachable item sets, frontier planes), compiled for the host, along three sentences of the workload: after every
+    token its context equals what the host parser's chart gives, the root-can-end flag agrees, and a dozen random
+    tokens tried at every step are accepted or rejected as the host parser says (rejection leaves the state alone)."""
+    cfg = gen.build_config(index, n_tools=4) if index == 3 else gen.build_config(index)
+    ebnf, root = cfg.grammars[0]
+    rng = random.Random(3000 + index)
+    seg = gen.Segmenter(cfg.vocab)
+    seq = []
+    for _ in range(3):
+        seq += seg.segment(cfg.sample_text(rng, 0), rng) + [-1]
+    try_ids = rng.sample(range(1, cfg.vocab.size), 12)
+    n = run_accept(hostcheck, ebnf, root, cfg.vocab.tokens, seq, try_ids, small_lists)
+    assert n >= 13 * (len(seq) - 3)
+
+
+@pytest.mark.parametrize("case", range(len(TINY)))
+def test_device_accept_step_matches_host_parser_on_tiny_grammars(hostcheck, case):
+    """The same on the hand-written grammars (left and nested recursion, nullable chains, ambiguity, dispatch): the
+    sentence byte by byte and cut into the listed tokens where they fit, with every listed token tried at every step."""
+    ebnf, root, tokens, sentence = TINY[case]
+    toks = list(tokens) + sorted({bytes([b]) for b in set(b"".join(tokens)) | set(sentence)} - set(tokens))
+    single = {t: i for i, t in enumerate(toks) if len(t) == 1}
+    seq = [single[sentence[i:i + 1]] for i in range(len(sentence))] + [-1]
+    # greedy longest-match segmentation as a second sequence
+    pos = 0
+    while pos < len(sentence):
+        best = max((i for i, t in enumerate(toks) if sentence.startswith(t, pos)), key=lambda i: len(toks[i]))
+        seq.append(best)
+        pos += len(toks[best])
+    seq.append(-1)
+    for small in (True, False):
+        assert run_accept(hostcheck, ebnf, root, toks, seq, list(range(len(toks))), small) > len(sentence)
