@@ -69,6 +69,7 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=5, help="workload index (5 = runtime stress, the metric's configuration)")
     ap.add_argument("--batch", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-host-matchers", action="store_true", help="skip the comparison leg with the parsers on the host")
     ap.add_argument("--no-tagdispatch-build", action="store_true", help="skip the one build of the TagDispatch workload after the timed steps")
     ap.add_argument("--cross-grammar", type=int, default=0, metavar="N",
                     help="also compile the first N grammars of the cross-grammar workload (config 4; 256 = all) into one pool and "
@@ -134,16 +135,24 @@ def main() -> int:
                           "roofline": roof(st, k_ms)}))
         return 0
 
-    # matchers at random depths of their own sentences (set-up, untimed)
+    # matchers at random depths of their own sentences (set-up, untimed): B slots in device memory, advanced by the accept kernel
     cache0 = xg.compile_grammar(vocab, ebnf, root, stream=stream)
     rng = random.Random(gen.BASE_SEED + 100 + args.config)
     seg = gen.Segmenter(cfg.vocab)
     traces, cursor = gen.random_depth_traces(cfg, seg, B, rng)
-    matchers = [xg.Matcher(cache0) for _ in range(B)]
-    for b in range(B):
-        for t in traces[b][:cursor[b]]:
-            assert matchers[b].accept_token(t)
-    batch = xg.MatcherBatch(matchers)
+    db = xg.DeviceBatch(vocab, B)
+    db.assign(cache0, stream=stream)
+    ids_host = torch.zeros(B, dtype=torch.int32).pin_memory()
+    ids_dev = torch.zeros(B, dtype=torch.int32, device=dev)
+    status_dev = torch.zeros(B, dtype=torch.int32, device=dev)
+    ids_np = ids_host.numpy()
+    for d in range(max(cursor)):
+        for b in range(B):
+            ids_np[b] = traces[b][d] if d < cursor[b] else -1
+        ids_dev.copy_(ids_host)
+        db.accept_tokens(ids_dev.data_ptr(), status_dev.data_ptr(), stream)
+    assert not status_dev.cpu().numpy().any(), "a trace token was rejected during set-up"
+    ended = [False] * B
 
     g = torch.Generator(device="cpu").manual_seed(1234)
     logits32_src = torch.randn((B, V), generator=g, dtype=torch.float32).to(dev)
@@ -152,27 +161,23 @@ def main() -> int:
     logits16 = torch.empty_like(logits16_src)
     bitmask = torch.zeros((B, W), dtype=torch.int32, device=dev)
 
-    import numpy as _np
-    next_ids = _np.zeros(B, dtype=_np.int32)
-
-    def advance():
-        # one batched accept for the whole batch; matchers that ended restart on a fresh sentence
+    def next_tokens():
+        # what the sampler would hand over: here the next token of each slot's own sentence; a slot whose sentence has
+        # ended starts a fresh one (-2)
         for b in range(B):
-            next_ids[b] = traces[b][cursor[b]] if cursor[b] < len(traces[b]) else -1
-        tc = time.perf_counter()
-        status = batch.accept_tokens(next_ids)
-        acc["accept_call_ms"].append((time.perf_counter() - tc) * 1e3)
-        assert not status.any(), "a trace token was rejected"
-        for b in range(B):
-            cursor[b] += 1
-            if cursor[b] >= len(traces[b]):                       # end of sequence was just accepted
-                matchers[b].reset()
+            if ended[b]:
+                ids_np[b] = -2
                 traces[b] = seg.segment(cfg.sample_text(rng, 0), rng) + [cfg.vocab.eos_id]
                 cursor[b] = 0
+                ended[b] = False
+            else:
+                ids_np[b] = traces[b][cursor[b]]
+                cursor[b] += 1
+                ended[b] = cursor[b] >= len(traces[b])              # the end-of-sequence token goes in now
 
-    ev = [torch.cuda.Event(enable_timing=True) for _ in range(5)]
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(6)]
     acc = {"build_device_ms": [], "build_kernel_ms": [], "build_host_ms": [], "fill_us": [], "apply_bf16_us": [],
-           "apply_f32_us": [], "fill_device_us": [], "fill_host_ms": [], "accept_host_ms": [], "accept_call_ms": [], "masked_frac": []}
+           "apply_f32_us": [], "fill_device_us": [], "fill_call_ms": [], "accept_call_ms": [], "accept_us": []}
     last_stats = None
 
     def step(record: bool):
@@ -184,17 +189,22 @@ def main() -> int:
         st = cache.stats
         t0 = time.perf_counter()
         ev[0].record()
-        xg.fill_next_token_bitmask(batch, bitmask.data_ptr(), W, stream)      # a3 + a4
+        db.fill_next_token_bitmask(bitmask.data_ptr(), W, stream)             # a3 + a4, nothing uploaded
         t1 = time.perf_counter()
         ev[1].record()
         xg.apply_token_bitmask(logits16.data_ptr(), xg.XG2_BF16, B, V, V, bitmask.data_ptr(), W, stream)   # a5
         ev[2].record()
         xg.apply_token_bitmask(logits32.data_ptr(), xg.XG2_F32, B, V, V, bitmask.data_ptr(), W, stream)
         ev[3].record()
+        next_tokens()
+        ids_dev.copy_(ids_host, non_blocking=True)
         t2 = time.perf_counter()
-        advance()                                                             # a6 (host)
+        ev[4].record()
+        db.accept_tokens(ids_dev.data_ptr(), status_dev.data_ptr(), stream)   # a6, on the device
+        ev[5].record()
         t3 = time.perf_counter()
-        ev[3].synchronize()
+        ev[5].synchronize()
+        assert not status_dev.cpu().numpy().any(), "a trace token was rejected"
         fill_dev_us = xg.fill_last_device_us()
         if record:
             last_stats = st
@@ -205,8 +215,9 @@ def main() -> int:
             acc["fill_us"].append(ev[0].elapsed_time(ev[1]) * 1e3)
             acc["apply_bf16_us"].append(ev[1].elapsed_time(ev[2]) * 1e3)
             acc["apply_f32_us"].append(ev[2].elapsed_time(ev[3]) * 1e3)
-            acc["fill_host_ms"].append((t1 - t0) * 1e3)
-            acc["accept_host_ms"].append((t3 - t2) * 1e3)
+            acc["accept_us"].append(ev[4].elapsed_time(ev[5]) * 1e3)
+            acc["fill_call_ms"].append((t1 - t0) * 1e3)
+            acc["accept_call_ms"].append((t3 - t2) * 1e3)
         del cache
 
     for _ in range(args.warmup):
@@ -283,12 +294,13 @@ def main() -> int:
                   "checks_per_s_end_to_end": checks / ((build_ms + host_ms) * 1e-3),
                   "executed_checks_per_s_end_to_end": int(st.executed_checks) / ((build_ms + host_ms) * 1e-3),
                   "n_accepted_bits": int(st.n_accepted), "n_uncertain_bits": int(st.n_uncertain)},
-        "decode": {"fill_us": med(acc["fill_device_us"]), "apply_bf16_us": med(acc["apply_bf16_us"]), "apply_f32_us": med(acc["apply_f32_us"]),
+        "decode": {"matchers": "device-resident (accept kernel, fill without upload)",
+                   "fill_us": med(acc["fill_device_us"]), "apply_bf16_us": med(acc["apply_bf16_us"]), "apply_f32_us": med(acc["apply_f32_us"]),
+                   "accept_us": med(acc["accept_us"]),
                    "fill_apply_bf16_us": med(acc["fill_device_us"]) + med(acc["apply_bf16_us"]),
                    "fill_apply_f32_us": med(acc["fill_device_us"]) + med(acc["apply_f32_us"]),
-                   "fill_call_us_incl_host_prep": med(acc["fill_us"]),
-                   "fill_host_ms": med(acc["fill_host_ms"]), "accept_host_ms": med(acc["accept_host_ms"]),
-                   "accept_call_ms": med(acc["accept_call_ms"][-args.steps:]),
+                   "fill_between_events_us": med(acc["fill_us"]),
+                   "fill_call_host_us": med(acc["fill_call_ms"]) * 1e3, "accept_call_host_us": med(acc["accept_call_ms"]) * 1e3,
                    "masked_fraction_last_step": masked / float(B * V)},
         "roofline": roof,
     }
@@ -341,6 +353,37 @@ def main() -> int:
                                     "checks_per_s_device": int(s3.checks) / (s3.device_ms * 1e-3),
                                     "roofline": build_roofline(s3, s3.kernel_ms)}
         del c3, vocab3
+
+    if not args.no_host_matchers:
+        # the same decode step with the parsers on the host (one Earley chart per matcher, frontier and context uploaded by
+        # every fill call), for comparison: 10 steps from the state the timed loop ended in
+        hm = [xg.Matcher(cache0) for _ in range(B)]
+        for b in range(B):
+            if not ended[b]:
+                for t in traces[b][:cursor[b]]:
+                    assert hm[b].accept_token(t)
+        hbatch = xg.MatcherBatch(hm)
+        h_fill, h_fill_dev, h_acc = [], [], []
+        nxt = np.zeros(B, dtype=np.int32)
+        for _ in range(10):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            xg.fill_next_token_bitmask(hbatch, bitmask.data_ptr(), W, stream)
+            h_fill.append((time.perf_counter() - t0) * 1e6)
+            h_fill_dev.append(xg.fill_last_device_us())
+            for b in range(B):
+                if ended[b] or cursor[b] >= len(traces[b]):
+                    nxt[b] = -1
+                else:
+                    nxt[b] = traces[b][cursor[b]]
+                    cursor[b] += 1
+            t0 = time.perf_counter()
+            stt = hbatch.accept_tokens(nxt)
+            h_acc.append((time.perf_counter() - t0) * 1e6)
+            assert not stt.any()
+        out["decode_host_matchers"] = {"fill_call_host_us": med(h_fill), "fill_device_us": med(h_fill_dev), "accept_call_host_us": med(h_acc),
+                                       "note": "host Earley parsers; fill uploads the frontier planes and context slices of all rows every step"}
+        del hbatch, hm
 
     if args.cross_grammar:
         cfg4 = gen.build_config(4)

@@ -116,9 +116,14 @@ __device__ int accept_token(const CacheDev& Cd, const uint32_t* cls_words, const
             wait_at(o, k, wr, wt);
             if (wr != rule) continue;
             const uint32_t key = wt & SID_MASK;
-            uint64_t row = 0;
-            for (uint32_t j = Cd.pair_off[sid]; j < Cd.pair_off[sid + 1]; ++j)
-                if (Cd.pair_key[j] == key) { row = Cd.pair_row[j]; break; }
+            // the state's planes are sorted by site (a state inside a long repetition is referenced from thousands of states)
+            uint32_t lo_j = Cd.pair_off[sid], hi_j = Cd.pair_off[sid + 1];
+            while (lo_j < hi_j) {
+                const uint32_t mid = (lo_j + hi_j) >> 1;
+                if (Cd.pair_key[mid] < key) lo_j = mid + 1; else hi_j = mid;
+            }
+            if (lo_j >= Cd.pair_off[sid + 1] || Cd.pair_key[lo_j] != key) return ACC_NO_PLANE;
+            const uint64_t row = Cd.pair_row[lo_j];
             if (!row) return ACC_NO_PLANE;
             if (!add_plane(row)) return ACC_OVERFLOW;
             any = true;

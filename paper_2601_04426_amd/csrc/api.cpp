@@ -920,7 +920,7 @@ void prepare_matcher(MatcherImpl& M) {
 
 // ---- matchers on the device -----------------------------------------------------------------------------------
 struct BatchImpl {
-    static constexpr uint32_t KI = 64, KH = 240, KW = 512, KF = 16, kMaxCaches = 256;
+    static constexpr uint32_t KI = kSlotItems, KH = kSlotSets, KW = kSlotWaits, KF = kSlotPlanes, kMaxCaches = 256;
     std::mutex mu;
     std::shared_ptr<VocabImpl> vocab;
     int32_t B = 0;

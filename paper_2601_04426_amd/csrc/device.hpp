@@ -128,7 +128,7 @@ struct CacheDev {
     DevTables T;
     const uint64_t* plain_row;           // [n_states] plane of a position without context (root rule, or context depth 1), 0 = none
     const uint32_t* pair_off;            // [n_states + 1] CSR over states: the planes of the state under its referencing sites
-    const uint32_t* pair_key;            //   state id the referencing rule continues in
+    const uint32_t* pair_key;            //   state id the referencing rule continues in, ascending within a state
     const uint64_t* pair_row;
     uint32_t context_depth;
     uint32_t start_n_items, start_H, start_n_front, start_flags;
@@ -139,8 +139,9 @@ struct CacheDev {
 // wait for) in one of two buffers, c = rows[b].pad[0]: items[(c * B + b) * KI ..], wait[(c * B + b) * KW ..],
 // wait_off[(c * B + b) * (KH + 1) ..].  Accepting a token writes the other buffer and switches.  rows[b].pad[1] holds a
 // sticky error (a capacity was exceeded: the slot is unusable until it is reset), rows[b].tables_idx the slot's cache.
+constexpr uint32_t kSlotItems = 64, kSlotSets = 240, kSlotWaits = 512, kSlotPlanes = 16;   // capacities of a matcher slot
 struct BatchDev {
-    uint32_t B, KI, KH, KW, KF;
+    uint32_t B, KI, KH, KW, KF;                          // KI .. KF: the four capacities above
     FillRow* rows;
     uint64_t* front; uint32_t* items; uint2* wait; uint32_t* wait_off;
     const CacheDev* caches; const DevTables* tables;     // [number of caches in use] (tables: the same DevTables, as fill wants them)

@@ -692,19 +692,38 @@ __global__ __launch_bounds__(64) void k_recheck_slow(FillBatch F, DevVocab Vd, i
 }
 
 // ---- matchers on the device ------------------------------------------------------------------------
-// k_accept: one lane per matcher slot takes the slot's sampled token through the recogniser and writes the slot's
-// next context and frontier planes (accept_core.hpp).  The common case runs with the item lists, the renumbering
-// table and the frontier staging in LDS; a token or context too large for that runs again with all three in device
-// memory.  A slot whose capacity is exceeded gets a sticky error and answers XG2_EOVERFLOW until it is reset.
-constexpr int ACCEPT_MAP = 240 + 16, ACCEPT_FRONT = 16;            // sets the LDS table renumbers; planes the LDS staging holds
-struct LdsScratchX {
-    uint8_t* map; uint64_t* front;                                  // this lane's columns
-    __device__ uint32_t map_cap() const { return ACCEPT_MAP; }
-    __device__ uint32_t front_cap() const { return ACCEPT_FRONT; }
-    __device__ uint32_t map_get(uint32_t i) const { return map[i * 64]; }
-    __device__ void map_set(uint32_t i, uint32_t v) { map[i * 64] = (uint8_t)v; }
-    __device__ uint64_t front_get(uint32_t k) const { return front[k * 64]; }
-    __device__ void front_set(uint32_t k, uint64_t v) { front[k * 64] = v; }
+// k_accept: one wavefront per matcher slot.  The lanes bring the slot's context into LDS, lane 0 takes the sampled token
+// through the recogniser and writes the slot's next context and frontier planes (accept_core.hpp) into an LDS staging
+// area, with its item lists, the renumbering table and the frontier staging in LDS too, and the lanes copy the result
+// out.  A token or context too large for that runs again with everything in device memory.  A slot whose capacity is
+// exceeded gets a sticky error and answers XG2_EOVERFLOW until it is reset.
+constexpr int ACCEPT_K = 64, ACCEPT_WM = 256, ACCEPT_MAXLEN = 48;  // lane 0's item lists
+struct OneLaneStore {
+    static constexpr int K = ACCEPT_K, WM = ACCEPT_WM, MAXLEN = ACCEPT_MAXLEN, WORDS = 2 * ACCEPT_K + 2 * ACCEPT_WM + ACCEPT_MAXLEN + 1;
+    uint32_t* cur; uint32_t* nxt; uint32_t* wait; uint32_t* ws;
+    __device__ void init(uint32_t* base) { cur = base; nxt = base + K; wait = base + 2 * K; ws = base + 2 * K + 2 * WM; }
+    __device__ uint32_t get_cur(int k) const { return cur[k]; }
+    __device__ void set_cur(int k, uint32_t v) { cur[k] = v; }
+    __device__ uint32_t get_nxt(int k) const { return nxt[k]; }
+    __device__ void set_nxt(int k, uint32_t v) { nxt[k] = v; }
+    __device__ uint32_t wait_rule(int k) const { return wait[2 * k]; }
+    __device__ uint32_t wait_tgt(int k) const { return wait[2 * k + 1]; }
+    __device__ void set_wait(int k, uint32_t rule, uint32_t tgt) { wait[2 * k] = rule; wait[2 * k + 1] = tgt; }
+    __device__ void swap() { uint32_t* t = cur; cur = nxt; nxt = t; }
+    __device__ bool charge(int) { return true; }
+    __device__ void reset() {}
+    __device__ void set_wstart(int j, uint32_t v) { ws[j] = v; }
+    __device__ uint32_t get_wstart(int j) const { return ws[j]; }
+};
+template <int N_MAP, int N_FRONT>
+struct OneLaneScratchX {
+    uint8_t* map; uint64_t* front;
+    __device__ uint32_t map_cap() const { return N_MAP; }
+    __device__ uint32_t front_cap() const { return N_FRONT; }
+    __device__ uint32_t map_get(uint32_t i) const { return map[i]; }
+    __device__ void map_set(uint32_t i, uint32_t v) { map[i] = (uint8_t)v; }
+    __device__ uint64_t front_get(uint32_t k) const { return front[k]; }
+    __device__ void front_set(uint32_t k, uint64_t v) { front[k] = v; }
 };
 struct GlobalScratchX {
     uint8_t* map; uint64_t* front; size_t stride; uint32_t n_map, n_front;
@@ -716,7 +735,7 @@ struct GlobalScratchX {
     __device__ void front_set(uint32_t k, uint64_t v) { front[(size_t)k * stride] = v; }
 };
 
-__device__ __forceinline__ void start_sequence(const BatchDev& D, uint32_t b, uint32_t cache_idx) {
+__device__ __forceinline__ void start_sequence(const BatchDev& D, uint32_t b, uint32_t cache_idx, uint32_t lane, uint32_t n_lanes) {
     const CacheDev& Cd = D.caches[cache_idx];
     FillRow r{};
     r.front_off = b * D.KF; r.front_n = Cd.start_n_front;
@@ -724,70 +743,104 @@ __device__ __forceinline__ void start_sequence(const BatchDev& D, uint32_t b, ui
     r.wait_base = b * D.KW; r.waitoff_off = b * (D.KH + 1); r.H = Cd.start_H;
     r.tables_idx = cache_idx; r.flags = Cd.start_flags;
     r.pad[0] = 0; r.pad[1] = 0; r.pad[2] = 0;
-    for (uint32_t k = 0; k < Cd.start_n_front; ++k) D.front[r.front_off + k] = Cd.start_front[k];
-    for (uint32_t k = 0; k < Cd.start_n_items; ++k) D.items[r.item_off + k] = Cd.start_items[k];
-    for (uint32_t k = 0; k <= Cd.start_H; ++k) D.wait_off[r.waitoff_off + k] = Cd.start_wait_off[k];
-    for (uint32_t k = 0; k < Cd.start_wait_off[Cd.start_H]; ++k) D.wait[r.wait_base + k] = Cd.start_wait[k];
-    D.rows[b] = r;
+    for (uint32_t k = lane; k < Cd.start_n_front; k += n_lanes) D.front[r.front_off + k] = Cd.start_front[k];
+    for (uint32_t k = lane; k < Cd.start_n_items; k += n_lanes) D.items[r.item_off + k] = Cd.start_items[k];
+    for (uint32_t k = lane; k <= Cd.start_H; k += n_lanes) D.wait_off[r.waitoff_off + k] = Cd.start_wait_off[k];
+    const uint32_t n_wait = Cd.start_wait_off[Cd.start_H];
+    for (uint32_t k = lane; k < n_wait; k += n_lanes) D.wait[r.wait_base + k] = Cd.start_wait[k];
+    if (lane == 0) D.rows[b] = r;
 }
 
 __global__ __launch_bounds__(256) void k_batch_assign(BatchDev D, const int32_t* rows, uint32_t n, uint32_t cache_idx) {
     const uint32_t i = blockIdx.x * 256 + threadIdx.x;
     if (i >= n) return;
     const uint32_t b = rows ? (uint32_t)rows[i] : i;
-    if (b < D.B) start_sequence(D, b, cache_idx);
+    if (b < D.B) start_sequence(D, b, cache_idx, 0, 1);
 }
 
+constexpr uint32_t ACC_KI = kSlotItems, ACC_KH = kSlotSets, ACC_KW = kSlotWaits, ACC_KF = kSlotPlanes;     // the slot capacities the LDS staging is laid out for
 __global__ __launch_bounds__(64) void k_accept(BatchDev D, DevVocab Vd, uint32_t eos_id, const int32_t* token_ids, int32_t* status) {
-    __shared__ uint32_t lds_store[FillStore::SLOTS * 64];
-    __shared__ uint8_t lds_map[ACCEPT_MAP * 64];
-    __shared__ uint64_t lds_front[ACCEPT_FRONT * 64];
-    const uint32_t lane = threadIdx.x, b = blockIdx.x * 64 + lane;
-    if (b >= D.B) return;
+    __shared__ uint32_t in_items[ACC_KI], in_wait_off[ACC_KH + 1], out_items[ACC_KI], out_wait_off[ACC_KH + 1];
+    __shared__ uint2 in_wait[ACC_KW], out_wait[ACC_KW];
+    __shared__ uint64_t out_front[ACC_KF], x_front[ACC_KF];
+    __shared__ uint32_t lists[OneLaneStore::WORDS];
+    __shared__ uint8_t x_map[ACC_KH + ACCEPT_MAXLEN + 4];
+    __shared__ uint32_t cls_words[64];
+    __shared__ int sh_acc;
+    __shared__ uint32_t sh_out[4];                                 // n_items, H, n_front, root_done
+    const uint32_t lane = threadIdx.x, b = blockIdx.x;              // one wavefront per slot: everything below is the same in all lanes
     const int32_t tok = token_ids[b];
     int32_t code = kAccOk;
     FillRow r = D.rows[b];
-    if (tok == kTokenReset) start_sequence(D, b, r.tables_idx);
+    if (tok == kTokenReset) start_sequence(D, b, r.tables_idx, lane, 64);
     else if (tok < 0) code = kAccOk;                                 // nothing for this slot
     else if (r.pad[1]) code = kAccOverflow;                          // unusable until reset
     else if ((r.flags & 2u) || (uint32_t)tok >= Vd.V) code = kAccInvalid;
     else if ((uint32_t)tok == eos_id) {
-        if (r.flags & 1u) D.rows[b].flags = r.flags | 2u;            // the sequence ends here
-        else code = kAccRejected;
+        if (!(r.flags & 1u)) code = kAccRejected;
+        else if (lane == 0) D.rows[b].flags = r.flags | 2u;          // the sequence ends here
     } else {
         const uint32_t rank = Vd.rank[tok];
         if (rank >= Vd.n_sorted) code = kAccRejected;                // special and empty tokens are never allowed
         else {
             const uint32_t off = Vd.off[rank];
             const int n = (int)(Vd.off[rank + 1] - off);
-            const uint32_t cur = r.pad[0], nb = cur ^ 1u;
-            const CacheDev& Cd = D.caches[r.tables_idx];
-            MatcherIn in{D.items + r.item_off, r.item_n, D.wait + r.wait_base, D.wait_off + r.waitoff_off, r.H};
+            const uint32_t nb = r.pad[0] ^ 1u;
+            const CacheDev Cd = D.caches[r.tables_idx];             // by value: no reload after every store
             const size_t slot = (size_t)nb * D.B + b;
-            MatcherOut out{D.items + slot * D.KI, D.wait + slot * D.KW, D.wait_off + slot * (D.KH + 1), D.front + (size_t)b * D.KF,
-                           D.KI, D.KH, D.KW, D.KF, 0, 0, 0, 0};
-            FillStore st;
-            st.init(lds_store + lane);
-            LdsScratchX x{lds_map + lane, lds_front + lane};
-            int acc = accept_token(Cd, Cd.T.byte_class_words, in, Vd.bytes + off, n, st, x, out);
-            if (acc == ACC_RETRY) {
-                GlobalStore gs;
-                gs.init(D.slow_mem + b, D.B);
-                GlobalScratchX gx{D.slow_map + b, D.slow_front + b, D.B, D.KH + kSlowMaxLen + 1, D.KF};
-                acc = accept_token(Cd, Cd.T.byte_class_words, in, Vd.bytes + off, n, gs, gx, out);
+            // the byte classes and the slot's context into LDS
+            cls_words[lane] = Cd.T.byte_class_words[lane];
+            const uint32_t n_wait_in = D.wait_off[r.waitoff_off + r.H];
+            for (uint32_t k = lane; k < r.item_n; k += 64) in_items[k] = D.items[r.item_off + k];
+            for (uint32_t k = lane; k <= r.H; k += 64) in_wait_off[k] = D.wait_off[r.waitoff_off + k];
+            for (uint32_t k = lane; k < n_wait_in; k += 64) in_wait[k] = D.wait[r.wait_base + k];
+            __syncthreads();
+            if (lane == 0) {
+                MatcherIn in{in_items, r.item_n, in_wait, in_wait_off, r.H};
+                MatcherOut out{out_items, out_wait, out_wait_off, out_front, ACC_KI, ACC_KH, ACC_KW, ACC_KF, 0, 0, 0, 0};
+                OneLaneStore st;
+                st.init(lists);
+                OneLaneScratchX<ACC_KH + ACCEPT_MAXLEN, ACC_KF> x{x_map, x_front};
+                int acc = accept_token(Cd, cls_words, in, Vd.bytes + off, n, st, x, out);
+                if (acc == ACC_RETRY) {
+                    // lists in device memory, results straight to the slot's other buffer
+                    MatcherIn gin{D.items + r.item_off, r.item_n, D.wait + r.wait_base, D.wait_off + r.waitoff_off, r.H};
+                    MatcherOut gout{D.items + slot * D.KI, D.wait + slot * D.KW, D.wait_off + slot * (D.KH + 1), D.front + (size_t)b * D.KF,
+                                    D.KI, D.KH, D.KW, D.KF, 0, 0, 0, 0};
+                    GlobalStore gs;
+                    gs.init(D.slow_mem + b, D.B);
+                    GlobalScratchX gx{D.slow_map + b, D.slow_front + b, D.B, D.KH + kSlowMaxLen + 1, D.KF};
+                    acc = accept_token(Cd, cls_words, gin, Vd.bytes + off, n, gs, gx, gout);
+                    out.n_items = gout.n_items; out.H = gout.H; out.n_front = gout.n_front; out.root_done = gout.root_done;
+                    if (acc == ACC_OK) acc = -1;                     // done, nothing to copy out
+                }
+                sh_acc = acc;
+                sh_out[0] = out.n_items; sh_out[1] = out.H; sh_out[2] = out.n_front; sh_out[3] = out.root_done;
             }
-            if (acc == ACC_OK) {
-                r.front_n = out.n_front;
-                r.item_off = (uint32_t)(slot * D.KI); r.item_n = out.n_items;
-                r.wait_base = (uint32_t)(slot * D.KW); r.waitoff_off = (uint32_t)(slot * (D.KH + 1)); r.H = out.H;
-                r.flags = out.root_done;
-                r.pad[0] = nb;
-                D.rows[b] = r;
+            __syncthreads();
+            const int acc = sh_acc;
+            if (acc == ACC_OK || acc == -1) {
+                const uint32_t n_items = sh_out[0], H = sh_out[1], n_front = sh_out[2];
+                if (acc == ACC_OK) {
+                    for (uint32_t k = lane; k < n_items; k += 64) D.items[slot * D.KI + k] = out_items[k];
+                    for (uint32_t k = lane; k <= H; k += 64) D.wait_off[slot * (D.KH + 1) + k] = out_wait_off[k];
+                    const uint32_t n_wait = out_wait_off[H];
+                    for (uint32_t k = lane; k < n_wait; k += 64) D.wait[slot * D.KW + k] = out_wait[k];
+                    for (uint32_t k = lane; k < n_front; k += 64) D.front[(size_t)b * D.KF + k] = out_front[k];
+                }
+                if (lane == 0) {
+                    r.front_n = n_front;
+                    r.item_off = (uint32_t)(slot * D.KI); r.item_n = n_items;
+                    r.wait_base = (uint32_t)(slot * D.KW); r.waitoff_off = (uint32_t)(slot * (D.KH + 1)); r.H = H;
+                    r.flags = sh_out[3];
+                    r.pad[0] = nb;
+                    D.rows[b] = r;
+                }
             } else if (acc == ACC_REJECTED) code = kAccRejected;
-            else { D.rows[b].pad[1] = 1u; code = kAccOverflow; }     // a capacity of the slot (or of the device-memory lists) was exceeded
+            else { if (lane == 0) D.rows[b].pad[1] = 1u; code = kAccOverflow; }   // a capacity of the slot (or of the device-memory lists) was exceeded
         }
     }
-    if (status) status[b] = code;
+    if (status && lane == 0) status[b] = code;
 }
 
 // ---- apply -----------------------------------------------------------------------------------------
@@ -917,8 +970,8 @@ void launch_build_slow(const DevTables& T, const DevVocab& Vd, const BuildPlan& 
 }
 
 void launch_accept(const BatchDev& D, const DevVocab& Vd, uint32_t eos_id, const int32_t* token_ids_dev, int32_t* status_dev, hipStream_t stream) {
-    if (!D.B) return;
-    hipLaunchKernelGGL(k_accept, dim3((D.B + 63) / 64), dim3(64), 0, stream, D, Vd, eos_id, token_ids_dev, status_dev);
+    if (!D.B || D.KI != ACC_KI || D.KH != ACC_KH || D.KW != ACC_KW || D.KF != ACC_KF) return;
+    hipLaunchKernelGGL(k_accept, dim3(D.B), dim3(64), 0, stream, D, Vd, eos_id, token_ids_dev, status_dev);
 }
 
 void launch_batch_assign(const BatchDev& D, const int32_t* rows_dev, uint32_t n, uint32_t cache_idx, hipStream_t stream) {

@@ -275,14 +275,16 @@ extern "C" long long xg2hc_check_accept(const char* ebnf, size_t len, const char
         for (size_t sid = 0; sid < n_states; ++sid) {
             const uint32_t rule = ft.state_info[sid].rule_final & 0x7FFFFFFFu;
             for (const RefEdgeP& e : ft.ref_edges)
-                if (e.rule == rule) {
-                    if (pair_of.count({(uint32_t)sid, e.tgt})) continue;
-                    const uint64_t row = ((uint64_t)(n_states + pair_key.size() + 1)) << 4;
+                if (e.rule == rule && !pair_of.count({(uint32_t)sid, e.tgt})) {
+                    const uint64_t row = ((uint64_t)(n_states + pair_of.size() + 1)) << 4;
                     pair_of[{(uint32_t)sid, e.tgt}] = row;
-                    pair_key.push_back(e.tgt); pair_row.push_back(row);
                 }
-            pair_off[sid + 1] = (uint32_t)pair_key.size();
         }
+        for (auto& kv : pair_of) {                                  // sorted by state, then by site: the order the look-up expects
+            pair_key.push_back(kv.first.second); pair_row.push_back(kv.second);
+            ++pair_off[(size_t)kv.first.first + 1];
+        }
+        for (size_t sid = 0; sid < n_states; ++sid) pair_off[sid + 1] += pair_off[sid];
         if (pair_key.empty()) { pair_key.push_back(0); pair_row.push_back(0); }
         Cd.plain_row = plain.data(); Cd.pair_off = pair_off.data(); Cd.pair_key = pair_key.data(); Cd.pair_row = pair_row.data();
         const uint32_t KI = 64, KH = 240, KW = 512, KF = 16;
