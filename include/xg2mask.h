@@ -220,6 +220,21 @@ int32_t xg2_fill_last_device_us(float* out);
  * the token might be allowed.  fill itself returns before the device work runs and cannot report this.   */
 int32_t xg2_fill_last_status(int32_t* large_capacity_tokens, int32_t* overflowed);
 
+/* A fill call returns before its kernels run, so it cannot itself report that the large-capacity re-check left a (row,
+ * token) pair undecided.  It is reported by the next call instead: the next xg2_fill_next_token_bitmask,
+ * xg2_matcher_accept_token or xg2_matcher_accept_tokens call of the process fails with XG2_EOVERFLOW, once, and changes
+ * nothing (for matchers on the device: the slot is marked and its next accept answers XG2_EOVERFLOW).  To get the exact
+ * mask instead, call xg2_fill_resolve_overflow after the fill, with the same matchers and bitmask, before the mask is
+ * used: it waits for the fill, decides every listed pair with the host parser (which has no capacity limit), sets the bits
+ * of the allowed ones in bitmask_dev and clears the pending error.  *n_decided (nullable) = pairs looked at (0 almost
+ * always).  Not for xg2_fill_next_token_bitmask_noalloc (use xg2_fill_last_status there) nor for xg2_batch_*.          */
+int32_t xg2_fill_resolve_overflow(xg2_matcher* const* matchers, int32_t B, int32_t* bitmask_dev, int64_t row_stride_words,
+                                  int32_t* n_decided);
+
+/* Test aid: lowers the capacities of the large-capacity item lists (256 items, 1024 wait entries; 0 = back to these) for
+ * the build and fill calls that follow, so that the handling of their overflow can be exercised with small grammars.   */
+int32_t xg2_debug_set_large_capacity(int32_t items, int32_t wait_entries);
+
 /* Measurement and test aid: for each row of the latest fill call of this process (waits for its device work), the
  * number of mask words that held at least one candidate, i.e. a token that is uncertain somewhere in the row's
  * frontier and accepted nowhere in it, and therefore went through the full-context re-check (section 3.4, runtime
@@ -233,7 +248,7 @@ int32_t xg2_fill_last_recheck_words(int32_t* words_host, int32_t cap, int32_t* n
  * then needs nothing from the host: xg2_batch_accept_tokens runs the sampled tokens (a device array, e.g. the sampler's
  * output) through the Earley recogniser, one lane per slot, and leaves each slot's next state in place;
  * xg2_batch_fill_next_token_bitmask reads the slots directly.  Both only enqueue kernels on the caller's stream.
- * Capacities of a slot: 64 scannable items, 240 reachable sets, 512 wait entries, 16 frontier planes (a grammar whose
+ * Capacities of a slot: 64 scannable items, 240 reachable sets, 512 wait entries, 32 frontier planes (a grammar whose
  * parse needs more, e.g. deeply right-recursive rules, makes the slot fail with XG2_EOVERFLOW until it is reassigned: use
  * host matchers for it).  Caches compiled just in time are not accepted (XG2_EINVAL): every plane must exist.            */
 typedef struct xg2_batch xg2_batch;

@@ -25,7 +25,8 @@ EXPORTS = [
     "xg2_compile_grammar", "xg2_mask_cache_destroy", "xg2_mask_cache_num_positions", "xg2_mask_cache_num_planes", "xg2_mask_cache_jit_stats",
     "xg2_mask_cache_plane_info", "xg2_mask_cache_find_plane", "xg2_mask_cache_get_planes", "xg2_matcher_create", "xg2_matcher_create_host", "xg2_matcher_destroy",
     "xg2_matcher_accept_token", "xg2_matcher_accept_tokens", "xg2_matcher_reset", "xg2_matcher_is_terminated", "xg2_matcher_frontier",
-    "xg2_fill_next_token_bitmask", "xg2_fill_next_token_bitmask_noalloc", "xg2_fill_last_device_us", "xg2_fill_last_status", "xg2_fill_last_recheck_words",
+    "xg2_fill_next_token_bitmask", "xg2_fill_next_token_bitmask_noalloc", "xg2_fill_resolve_overflow", "xg2_debug_set_large_capacity",
+    "xg2_fill_last_device_us", "xg2_fill_last_status", "xg2_fill_last_recheck_words",
     "xg2_apply_token_bitmask", "xg2_batch_create", "xg2_batch_destroy", "xg2_batch_assign", "xg2_batch_accept_tokens",
     "xg2_batch_fill_next_token_bitmask", "xg2_batch_row_info",
 ]
@@ -96,6 +97,8 @@ def _load() -> ctypes.CDLL:
     L.xg2_matcher_frontier.argtypes = [vp, vp, i32, ctypes.POINTER(i32), ctypes.POINTER(i32)]
     L.xg2_fill_next_token_bitmask.argtypes = [vp, i32, vp, i64, vp]
     L.xg2_fill_next_token_bitmask_noalloc.argtypes = [vp, i32, vp, i64, vp]
+    L.xg2_fill_resolve_overflow.argtypes = [vp, i32, vp, i64, ctypes.POINTER(i32)]
+    L.xg2_debug_set_large_capacity.argtypes = [i32, i32]
     L.xg2_fill_last_device_us.argtypes = [ctypes.POINTER(ctypes.c_float)]
     L.xg2_fill_last_status.argtypes = [ctypes.POINTER(i32), ctypes.POINTER(i32)]
     L.xg2_fill_last_recheck_words.argtypes = [vp, i32, ctypes.POINTER(i32)]
@@ -352,6 +355,18 @@ def fill_next_token_bitmask_noalloc(matchers, bitmask_ptr: int, row_stride_words
         arr = (ctypes.c_void_p * len(matchers))(*[m.h for m in matchers])
     _check(lib.xg2_fill_next_token_bitmask_noalloc(arr, len(matchers), ctypes.c_void_p(bitmask_ptr), row_stride_words,
                                                    ctypes.c_void_p(stream)))
+
+
+def fill_resolve_overflow(matchers, bitmask_ptr: int, row_stride_words: int) -> int:
+    """Decides on the host what the latest fill's large-capacity re-check left undecided; returns the number of pairs."""
+    arr = matchers.arr if isinstance(matchers, MatcherBatch) else (ctypes.c_void_p * len(matchers))(*[m.h for m in matchers])
+    n = ctypes.c_int32(0)
+    _check(lib.xg2_fill_resolve_overflow(arr, len(matchers), ctypes.c_void_p(bitmask_ptr), row_stride_words, ctypes.byref(n)))
+    return n.value
+
+
+def debug_set_large_capacity(items: int = 0, wait_entries: int = 0) -> None:
+    _check(lib.xg2_debug_set_large_capacity(items, wait_entries))
 
 
 def fill_last_status() -> Tuple[int, bool]:

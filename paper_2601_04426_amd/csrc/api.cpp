@@ -282,7 +282,9 @@ struct SlowImpl {
     DevBuf<uint32_t> mem, list;                 // the counter and flag of the list belong to each call's upload
     SlowScratch s{};
     bool ready = false;
+    uint32_t k_cap = kSlowK, wm_cap = kSlowWM;  // capacities in use (lowered only by the test hook)
     void ensure() {
+        s.k_cap = k_cap; s.wm_cap = wm_cap;
         if (ready) return;
         s.n_lanes = 64 * 64;
         s.list_cap = 1u << 20;
@@ -468,10 +470,13 @@ struct MatcherImpl {
 };
 
 // ---- fill workspace: pinned staging ring + device mirror ---------------------------------------------------
+constexpr uint32_t kUnresolvedCap = 255;                    // (row, token) pairs a fill call can report as undecided
 struct FillSlot {
     uint8_t* host = nullptr; uint8_t* dev = nullptr; size_t cap = 0;
     hipEvent_t done = nullptr; bool in_flight = false;
+    uint32_t* res_host = nullptr;                           // pinned: {any, more than fit, pairs ...} written by the large-capacity re-check
 };
+struct MatcherImpl;
 struct FillWorkspace {
     std::mutex mu;
     FillSlot slots[4];
@@ -484,6 +489,8 @@ struct FillWorkspace {
     hipStream_t last_stream = nullptr;
     bool timed = false;                                     // the latest fill recorded its events
     bool any = false;                                       // there has been a fill
+    // the latest fill whose undecided pairs nobody has looked at yet: its slot and its matchers
+    struct Pending { bool active = false; FillSlot* slot = nullptr; std::vector<MatcherImpl*> matchers; } pending;
     // waits for the device work of the latest fill
     void wait_last() {
         if (timed) HIP_CHECK(hipEventSynchronize(t_end));
@@ -498,6 +505,7 @@ struct FillWorkspace {
         FillSlot& s = slots[next];
         next = (next + 1) % 4;
         if (!s.done) HIP_CHECK(hipEventCreateWithFlags(&s.done, hipEventDisableTiming));
+        if (!s.res_host) HIP_CHECK(hipHostMalloc((void**)&s.res_host, (2 + 2 * (size_t)kUnresolvedCap) * sizeof(uint32_t), hipHostMallocDefault));
         if (s.in_flight) { HIP_CHECK(hipEventSynchronize(s.done)); s.in_flight = false; }
         if (s.cap < bytes) {
             if (s.host) (void)hipHostFree(s.host);
@@ -510,6 +518,24 @@ struct FillWorkspace {
     }
 };
 FillWorkspace& fill_ws() { static FillWorkspace* w = new FillWorkspace(); return *w; }
+
+// A fill call returns before its kernels run.  If the large-capacity re-check could not decide some (row, token) pair
+// (item sets beyond even its lists), the mask has a 0 where a 1 may belong: the next call that touches matchers or masks
+// fails with XG2_EOVERFLOW, once, unless xg2_fill_resolve_overflow has decided the pairs on the host in between.
+// The caller holds no lock.
+int32_t report_undecided_pairs() {
+    FillWorkspace& W = fill_ws();
+    std::lock_guard<std::mutex> lk(W.mu);
+    if (!W.pending.active) return XG2_OK;
+    if (hipEventSynchronize(W.pending.slot->done) != hipSuccess) return XG2_OK;
+    W.pending.active = false;
+    if (!W.pending.slot->res_host[0]) return XG2_OK;
+    uint32_t n = 0;
+    while (n < kUnresolvedCap && W.pending.slot->res_host[2 + 2 * n] != 0xFFFFFFFFu) ++n;
+    return fail(XG2_EOVERFLOW, "the previous xg2_fill_next_token_bitmask call left " + std::to_string(n) + (W.pending.slot->res_host[1] ? "+" : "") +
+                               " (row, token) pairs undecided: their Earley item sets exceed the large-capacity lists, and their mask bits are 0 "
+                               "(xg2_fill_resolve_overflow decides them with the host parser)");
+}
 
 // A few host threads that stay around between calls (starting threads costs more than the work of a decode step).
 // run(parts, job) calls job(0 .. parts - 1), the caller taking shares too, and returns when all are done; calls are
@@ -1486,7 +1512,12 @@ int32_t xg2_matcher_create_host(const xg2_grammar* g, const xg2_vocab* v, xg2_ma
 }
 void xg2_matcher_destroy(xg2_matcher* m) { delete m; }
 
+static int32_t accept_one(xg2_matcher* m, int32_t token_id);
 int32_t xg2_matcher_accept_token(xg2_matcher* m, int32_t token_id) {
+    if (int32_t rc = report_undecided_pairs()) return rc;
+    return accept_one(m, token_id);
+}
+static int32_t accept_one(xg2_matcher* m, int32_t token_id) {
     return guarded([&]() -> int32_t {
         if (!m) return fail(XG2_EINVAL, "xg2_matcher_accept_token: null matcher");
         MatcherImpl& M = *m->p;
@@ -1507,6 +1538,7 @@ int32_t xg2_matcher_accept_token(xg2_matcher* m, int32_t token_id) {
 int32_t xg2_matcher_accept_tokens(xg2_matcher* const* matchers, const int32_t* token_ids, int32_t B, int32_t* status_host) {
     if (B < 0 || (B > 0 && (!matchers || !token_ids || !status_host))) return fail(XG2_EINVAL, "xg2_matcher_accept_tokens: bad argument");
     for (int32_t b = 0; b < B; ++b) if (!matchers[b]) return fail(XG2_EINVAL, "xg2_matcher_accept_tokens: null matcher");
+    if (int32_t rc = report_undecided_pairs()) return rc;
     // matchers are independent: a few host threads each take a contiguous share (a handle listed twice would race)
     std::atomic<bool> failed{false};
     std::string what;
@@ -1516,7 +1548,7 @@ int32_t xg2_matcher_accept_tokens(xg2_matcher* const* matchers, const int32_t* t
     const std::function<void(int32_t)> work = [&](int32_t part) {
         try {
             for (int32_t b = part * share; b < std::min(B, (part + 1) * share); ++b) {
-                status_host[b] = token_ids[b] < 0 ? XG2_OK : xg2_matcher_accept_token(matchers[b], token_ids[b]);
+                status_host[b] = token_ids[b] < 0 ? XG2_OK : accept_one(matchers[b], token_ids[b]);
                 prepare_matcher(*matchers[b]->p);               // the next fill finds the state ready
             }
         } catch (const std::exception& e) {
@@ -1569,6 +1601,7 @@ int32_t fill_common(xg2_matcher* const* matchers, int32_t B, int32_t* bitmask_de
     return guarded([&]() -> int32_t {
         if (B < 0 || (B > 0 && (!matchers || !bitmask_dev))) return fail(XG2_EINVAL, "xg2_fill_next_token_bitmask: bad argument");
         if (B == 0) return XG2_OK;
+        if (int32_t rc = report_undecided_pairs()) return rc;
         hipStream_t stream = (hipStream_t)hip_stream;
         for (int32_t b = 0; b < B; ++b) {
             if (!matchers[b]) return fail(XG2_EINVAL, "xg2_fill_next_token_bitmask: null matcher");
@@ -1704,6 +1737,7 @@ int32_t fill_common(xg2_matcher* const* matchers, int32_t B, int32_t* bitmask_de
             F.row_count = reinterpret_cast<uint32_t*>(p); p += kNoAllocMaxRows * 4;
             S.list = reinterpret_cast<uint32_t*>(p); S.list_cap = kNoAllocListCap; p += (size_t)kNoAllocListCap * 8;
             S.mem = reinterpret_cast<uint32_t*>(p); S.n_lanes = kNoAllocSlowLanes;
+            S.k_cap = slow().k_cap; S.wm_cap = slow().wm_cap;
             const int k = NH.next;
             NH.next ^= 1;
             if (NH.in_flight[k]) { HIP_CHECK(hipEventSynchronize(NH.done[k])); NH.in_flight[k] = false; }   // the call before last has read it
@@ -1716,6 +1750,11 @@ int32_t fill_common(xg2_matcher* const* matchers, int32_t B, int32_t* bitmask_de
             S = slow().s;
             slot = &fill_ws().acquire(total);
             pack(slot->host);
+            slot->res_host[0] = 0; slot->res_host[1] = 0;
+            std::memset(slot->res_host + 2, 0xFF, 2 * (size_t)kUnresolvedCap * sizeof(uint32_t));
+            void* res_dev = nullptr;
+            HIP_CHECK(hipHostGetDevicePointer(&res_dev, slot->res_host, 0));
+            S.unresolved = static_cast<uint32_t*>(res_dev); S.unresolved_cap = kUnresolvedCap;
             fill_ws().ensure_scratch((size_t)B * V.W, (size_t)B);
             HIP_CHECK(hipEventRecord(fill_ws().t_begin, stream));
             upload_pinned(slot->dev, slot->host, total, stream);
@@ -1744,6 +1783,10 @@ int32_t fill_common(xg2_matcher* const* matchers, int32_t B, int32_t* bitmask_de
             HIP_CHECK(hipEventRecord(fill_ws().t_end, stream));
             HIP_CHECK(hipEventRecord(slot->done, stream));
             slot->in_flight = true;
+            FillWorkspace::Pending& pd = fill_ws().pending;
+            pd.active = true; pd.slot = slot;
+            pd.matchers.resize((size_t)B);
+            for (int32_t b = 0; b < B; ++b) pd.matchers[(size_t)b] = matchers[b]->p.get();
         }
         return XG2_OK;
     });
@@ -1760,6 +1803,50 @@ int32_t xg2_fill_next_token_bitmask(xg2_matcher* const* matchers, int32_t B, int
 int32_t xg2_fill_next_token_bitmask_noalloc(xg2_matcher* const* matchers, int32_t B, int32_t* bitmask_dev, int64_t row_stride_words,
                                             void* hip_stream) {
     return fill_common(matchers, B, bitmask_dev, row_stride_words, hip_stream, true);
+}
+
+int32_t xg2_fill_resolve_overflow(xg2_matcher* const* matchers, int32_t B, int32_t* bitmask_dev, int64_t row_stride_words, int32_t* n_decided) {
+    return guarded([&]() -> int32_t {
+        if (n_decided) *n_decided = 0;
+        if (B < 0 || (B > 0 && (!matchers || !bitmask_dev))) return fail(XG2_EINVAL, "xg2_fill_resolve_overflow: bad argument");
+        FillWorkspace& W = fill_ws();
+        std::lock_guard<std::mutex> lk(W.mu);
+        if (!W.pending.slot) return XG2_OK;
+        FillSlot& slot = *W.pending.slot;
+        HIP_CHECK(hipEventSynchronize(slot.done));
+        W.pending.active = false;
+        if (!slot.res_host[0]) return XG2_OK;
+        if ((size_t)B != W.pending.matchers.size()) return fail(XG2_EINVAL, "xg2_fill_resolve_overflow: not the batch of the latest fill call");
+        for (int32_t b = 0; b < B; ++b)
+            if (!matchers[b] || matchers[b]->p.get() != W.pending.matchers[(size_t)b]) return fail(XG2_EINVAL, "xg2_fill_resolve_overflow: not the matchers of the latest fill call");
+        if (slot.res_host[1]) return fail(XG2_EOVERFLOW, "xg2_fill_resolve_overflow: more undecided pairs than the list holds");
+        int32_t n = 0;
+        for (uint32_t k = 0; k < kUnresolvedCap && slot.res_host[2 + 2 * k] != 0xFFFFFFFFu; ++k) {
+            const uint32_t b = slot.res_host[2 + 2 * k], id = slot.res_host[3 + 2 * k];
+            if (b >= (uint32_t)B) return fail(XG2_EINVAL, "xg2_fill_resolve_overflow: corrupt list");
+            MatcherImpl& M = *matchers[b]->p;
+            if (id >= (uint32_t)M.vocab->V) return fail(XG2_EINVAL, "xg2_fill_resolve_overflow: corrupt list");
+            EarleyChart probe = M.chart;                           // the host parser has no capacity limit
+            if (!M.terminated && !M.vocab->special[id] && probe.advance(M.vocab->tok((int32_t)id), M.vocab->len((int32_t)id))) {
+                uint32_t word = 0;
+                uint32_t* at = reinterpret_cast<uint32_t*>(bitmask_dev) + (size_t)b * (size_t)row_stride_words + (id >> 5);
+                HIP_CHECK(hipMemcpy(&word, at, sizeof(word), hipMemcpyDeviceToHost));
+                word |= 1u << (id & 31);
+                HIP_CHECK(hipMemcpy(at, &word, sizeof(word), hipMemcpyHostToDevice));
+            }
+            ++n;
+        }
+        slot.res_host[0] = 0;
+        if (n_decided) *n_decided = n;
+        return XG2_OK;
+    });
+}
+
+int32_t xg2_debug_set_large_capacity(int32_t items, int32_t wait_entries) {
+    std::lock_guard<std::mutex> slow_lock(slow().mu);
+    slow().k_cap = items <= 0 ? kSlowK : std::min<uint32_t>((uint32_t)items, kSlowK);
+    slow().wm_cap = wait_entries <= 0 ? kSlowWM : std::min<uint32_t>((uint32_t)wait_entries, kSlowWM);
+    return XG2_OK;
 }
 
 int32_t xg2_fill_last_device_us(float* out) {
@@ -1918,6 +2005,7 @@ int32_t xg2_batch_fill_next_token_bitmask(xg2_batch* batch, int32_t* bitmask_dev
         F.cand_words = fill_ws().cand_words.p; F.work_list = fill_ws().work_list.p; F.row_count = fill_ws().row_count.p;
         F.zero_words = Bt.flag_words.p;                         // nothing is uploaded: the union kernel clears the overflow counter
         S.count = Bt.flag_words.p;
+        S.mark_rows = Bt.d.rows;                                // an undecided pair makes its slot unusable: the next accept says so
         HIP_CHECK(hipEventRecord(fill_ws().t_begin, stream));
         launch_fill(F, V.dv, bitmask_dev, row_stride_words, S, stream);
         launch_recheck_slow(F, V.dv, bitmask_dev, row_stride_words, S, stream);

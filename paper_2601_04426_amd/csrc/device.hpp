@@ -61,10 +61,17 @@ struct BuildPlan {
     uint32_t large_lists, list_k, list_wm;                      // set by launch_build: long or short item lists; item and wait-entry capacity a lane
 };
 
+struct FillRow;
 struct SlowScratch {                     // large-capacity per-lane Earley scratch in device memory
     uint32_t* mem; uint32_t n_lanes;     // mem holds n_lanes * kSlowSlots words
     uint32_t* list; uint32_t list_cap;   // overflow work list: pairs (a, b)
     uint32_t* count;                     // [0] = entries in list, [1] = sticky error flag
+    uint32_t k_cap, wm_cap;              // item and wait-entry capacity in use (at most kSlowK, kSlowWM; smaller only in tests
+                                         // of the overflow handling); below the LDS lists' 16 / 32 those are skipped
+    // fill only: where the (row, token) pairs that even these lists could not decide are reported: a counter and a list in
+    // pinned host memory (device-side address; null: not reported), and, for matchers on the device, the slots' rows
+    uint32_t* unresolved; uint32_t unresolved_cap;       // [0] = 1 if any, [1] = 1 if more than fit; pairs from word 2 on (the host presets them to ~0)
+    FillRow* mark_rows;                                  // not null: rows[b].pad[1] gets the sticky error
 };
 constexpr uint32_t kSlowK = 256, kSlowWM = 1024, kSlowMaxLen = 1024;
 constexpr uint32_t kSlowSearchBudget = 1u << 20;     // list entries one token may compare against in the device-memory lists
@@ -112,7 +119,7 @@ struct FillBatch {
     uint32_t* cand_words;                // [B * W]
     uint32_t* work_list;                 // [B * W], row b's list starts at b * W
     uint32_t* row_count;                 // [B], written by the union kernel
-    uint32_t* zero_words;                // if not null: two words the union kernel clears (the overflow list's length and flag, where
+    uint32_t* zero_words;                // if not null: four words the union kernel clears (the overflow list's length and flag, where
                                          // no upload brings them in as zeros)
 };
 void launch_fill(const FillBatch& F, const DevVocab& Vd, int32_t* bitmask_dev, int64_t row_stride_words,
@@ -139,7 +146,7 @@ struct CacheDev {
 // wait for) in one of two buffers, c = rows[b].pad[0]: items[(c * B + b) * KI ..], wait[(c * B + b) * KW ..],
 // wait_off[(c * B + b) * (KH + 1) ..].  Accepting a token writes the other buffer and switches.  rows[b].pad[1] holds a
 // sticky error (a capacity was exceeded: the slot is unusable until it is reset), rows[b].tables_idx the slot's cache.
-constexpr uint32_t kSlotItems = 64, kSlotSets = 240, kSlotWaits = 512, kSlotPlanes = 16;   // capacities of a matcher slot
+constexpr uint32_t kSlotItems = 64, kSlotSets = 240, kSlotWaits = 512, kSlotPlanes = 32;   // capacities of a matcher slot
 struct BatchDev {
     uint32_t B, KI, KH, KW, KF;                          // KI .. KF: the four capacities above
     FillRow* rows;

@@ -76,12 +76,15 @@ using MidStore = LdsStoreWide<16, 32, 48>;
 
 // Device memory: word (slot, lane) lives at slot * n_lanes + lane (coalesced across lanes).
 struct GlobalStore {
-    static constexpr int K = kSlowK, WM = kSlowWM, MAXLEN = kSlowMaxLen;
+    static constexpr int MAXLEN = kSlowMaxLen;
+    int K = kSlowK, WM = kSlowWM;                   // capacities in use (the memory is laid out for kSlowK, kSlowWM)
     uint32_t* cur; uint32_t* nxt; uint32_t* wait; uint32_t* ws; size_t stride;
     uint32_t budget = kSlowSearchBudget;           // list entries one token may still compare against: a bound on its run time
     __device__ bool charge(int n) { if ((uint32_t)n > budget) { budget = 0; return false; } budget -= (uint32_t)n; return true; }
-    __device__ void init(uint32_t* base, size_t n_lanes) {
-        stride = n_lanes; cur = base; nxt = base + (size_t)K * stride; wait = base + (size_t)2 * K * stride; ws = base + (size_t)(2 * K + 2 * WM) * stride;
+    __device__ void init(uint32_t* base, size_t n_lanes, uint32_t k_cap = kSlowK, uint32_t wm_cap = kSlowWM) {
+        K = (int)min(k_cap, kSlowK); WM = (int)min(wm_cap, kSlowWM);
+        stride = n_lanes; cur = base; nxt = base + (size_t)kSlowK * stride; wait = base + (size_t)2 * kSlowK * stride;
+        ws = base + (size_t)(2 * kSlowK + 2 * kSlowWM) * stride;
     }
     __device__ uint32_t get_cur(int k) const { return cur[(size_t)k * stride]; }
     __device__ void set_cur(int k, uint32_t v) { cur[(size_t)k * stride] = v; }
@@ -425,14 +428,14 @@ __global__ __launch_bounds__(64) void k_build_slow(DevTables T, DevVocab Vd, Bui
     MidStore mid;
     mid.init(lds + threadIdx.x);
     GlobalStore st;
-    st.init(S.mem + gl, S.n_lanes);
+    st.init(S.mem + gl, S.n_lanes, S.k_cap, S.wm_cap);
     for (uint32_t idx = gl; idx < count; idx += S.n_lanes) {
         if (*reinterpret_cast<volatile uint32_t*>(S.count + 1) & 2u) break;      // the build fails anyway: do not spend more on it
         const uint32_t p = S.list[2 * idx], rank = S.list[2 * idx + 1];
         const uint32_t off = Vd.off[rank];
         const int n = (int)(Vd.off[rank + 1] - off);
         DevCtx C = position_ctx(P, p);
-        int res = classify_slow(T, Vd, P, C, off, n, mid);           // returns RES_OVERFLOW at once if the token is too long for it
+        int res = S.k_cap >= (uint32_t)MidStore::K ? classify_slow(T, Vd, P, C, off, n, mid) : RES_OVERFLOW;   // (overflows at once if the token is too long for it)
         if (res & RES_OVERFLOW) res = classify_slow(T, Vd, P, C, off, n, st);
         if (res & RES_OVERFLOW) { atomicOr(S.count + 1, 2u); continue; }
         store_class(P, p, Vd.W, Vd.perm[rank], res);
@@ -550,7 +553,7 @@ __global__ __launch_bounds__(FILL_THREADS) void k_fill_or(FillBatch F, DevVocab 
     __shared__ uint32_t n_listed;
     const uint32_t b = blockIdx.x;
     if (threadIdx.x == 0) n_listed = 0;
-    if (F.zero_words && b == 0 && threadIdx.x < 2) F.zero_words[threadIdx.x] = 0;
+    if (F.zero_words && b == 0 && threadIdx.x < 4) F.zero_words[threadIdx.x] = 0;
     __syncthreads();
     const uint32_t front_off = F.rows[b].front_off, front_n = F.rows[b].front_n, flags = F.rows[b].flags;
     const uint32_t eos_word = F.eos_id >> 5, eos_bit = 1u << (F.eos_id & 31);
@@ -670,7 +673,7 @@ __global__ __launch_bounds__(64) void k_recheck_slow(FillBatch F, DevVocab Vd, i
     MidStore mid;
     mid.init(lds + threadIdx.x);
     GlobalStore st;
-    st.init(S.mem + gl, S.n_lanes);
+    st.init(S.mem + gl, S.n_lanes, S.k_cap, S.wm_cap);
     for (uint32_t idx = gl; idx < count; idx += S.n_lanes) {
         const uint32_t b = S.list[2 * idx], id = S.list[2 * idx + 1];
         const FillRow r = F.rows[b];
@@ -681,12 +684,24 @@ __global__ __launch_bounds__(64) void k_recheck_slow(FillBatch F, DevVocab Vd, i
         const DevTables T = F.tables[r.tables_idx];
         MemBytes tok{Vd.bytes + off};
         mid.reset();
-        int res = scan_token<MidStore, false, MemBytes>(T, T.byte_class_words, row_ctx(F, r), tok, n, mid);
+        int res = S.k_cap >= (uint32_t)MidStore::K ? scan_token<MidStore, false, MemBytes>(T, T.byte_class_words, row_ctx(F, r), tok, n, mid) : RES_OVERFLOW;
         if (res & RES_OVERFLOW) {
             st.reset();
             res = scan_token<GlobalStore, false, MemBytes>(T, T.byte_class_words, row_ctx(F, r), tok, n, st);
         }
-        if (res & RES_OVERFLOW) { atomicOr(S.count + 1, 2u); continue; }
+        if (res & RES_OVERFLOW) {
+            // undecided: the bit stays 0, and the call must not pass for complete.  The pair goes to the host's list (it
+            // can decide it with its own parser), a slot on the device is marked unusable.
+            atomicOr(S.count + 1, 2u);
+            if (S.mark_rows) S.mark_rows[b].pad[1] = 2u;
+            if (S.unresolved) {                                      // plain stores only: the list is host memory
+                const uint32_t at = atomicAdd(S.count + 2, 1u);
+                S.unresolved[0] = 1u;
+                if (at < S.unresolved_cap) { S.unresolved[2 + 2 * at] = b; S.unresolved[3 + 2 * at] = id; }
+                else S.unresolved[1] = 1u;
+            }
+            continue;
+        }
         if (res & RES_ALIVE) atomicOr(reinterpret_cast<uint32_t*>(bitmask) + (long long)b * row_stride + (id >> 5), 1u << (id & 31));
     }
 }

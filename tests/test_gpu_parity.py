@@ -555,6 +555,71 @@ def test_long_tokens_and_item_overflow_take_the_slow_path(xg):
         hist += toks[tid]
 
 
+def test_undecided_recheck_pairs_are_reported_and_resolved(xg):
+    """Item sets beyond the large-capacity lists during fill (forced here by lowering their capacity to the LDS lists'
+    through the test hook): the mask bit of such a token stays 0, and that must not pass silently.  The fill call's
+    status says so, xg2_fill_resolve_overflow decides the pairs with the host parser and the mask then equals the
+    oracle's; without it the next accept call fails with XG2_EOVERFLOW, once.  A slot on the device is marked and its
+    next accept answers XG2_EOVERFLOW."""
+    import torch
+    alts = " | ".join(f'r{i}' for i in range(20))
+    ebnf = ('root ::= "(" list ")"\nlist ::= item ("," item)*\nitem ::= ' + alts + ' | "(" list ")"\n'
+            + "".join(f'r{i} ::= "a"{{{i + 1}}} "b"*\n' for i in range(20)))
+    toks = [b"", b"(", b")", b",", b"a", b"b", b"ab,a", b"a,a", b"b,aa", b"b,a", b"ab", b"a,(", b"b),a", b"x"]
+    vocab = xg.Vocab(toks, 0, [0])
+    va = oracle.VocabArrays(toks, 0, [0])
+    cache = xg.compile_grammar(vocab, ebnf, "root", stream=_stream())
+    orc = oracle.Oracle(ebnf, "root")
+    m = xg.Matcher(cache)
+    for t in (b"(", b"a"):
+        assert m.accept_token(toks.index(t))
+    hist = b"(a"
+    want = oracle.pack_bitmask(orc.mask(hist, va))
+    bm = torch.zeros((1, vocab.words), dtype=torch.int32, device="cuda:0")
+    xg.fill_next_token_bitmask([m], bm.data_ptr(), vocab.words, _stream())
+    torch.cuda.synchronize()
+    n_large, overflowed = xg.fill_last_status()
+    assert np.array_equal(bm.cpu().numpy()[0], want) and n_large > 0 and not overflowed     # the large lists decide them
+    assert xg.fill_resolve_overflow([m], bm.data_ptr(), vocab.words) == 0
+    try:
+        xg.debug_set_large_capacity(8, 12)
+        xg.fill_next_token_bitmask([m], bm.data_ptr(), vocab.words, _stream())
+        torch.cuda.synchronize()
+        assert xg.fill_last_status()[1]
+        got = bm.cpu().numpy()[0]
+        assert not np.array_equal(got, want) and not (got & ~want).any()      # bits missing, none too many
+        n = xg.fill_resolve_overflow([m], bm.data_ptr(), vocab.words)
+        assert n > 0 and np.array_equal(bm.cpu().numpy()[0], want)            # decided on the host: exact again
+        assert m.accept_token(toks.index(b"x")) is False                       # no pending error: an ordinary rejection
+        # the same without resolving: the next call fails loudly, once
+        xg.fill_next_token_bitmask([m], bm.data_ptr(), vocab.words, _stream())
+        torch.cuda.synchronize()
+        with pytest.raises(xg.Xg2Error) as err:
+            m.accept_token(toks.index(b"a"))
+        assert err.value.code == -4 and "undecided" in str(err.value)
+        assert m.accept_token(toks.index(b"a"))                                # reported once; the matcher is unchanged by the failed call
+        hist += b"a"
+        # a matcher on the device: its slot is marked
+        db = xg.DeviceBatch(vocab, 1)
+        db.assign(cache, stream=_stream())
+        ids = torch.tensor([toks.index(b"(")], dtype=torch.int32, device="cuda:0")
+        st = torch.zeros(1, dtype=torch.int32, device="cuda:0")
+        db.accept_tokens(ids.data_ptr(), st.data_ptr(), _stream())
+        ids.copy_(torch.tensor([toks.index(b"a")], dtype=torch.int32))
+        db.accept_tokens(ids.data_ptr(), st.data_ptr(), _stream())
+        assert st.cpu().numpy()[0] == 0
+        db.fill_next_token_bitmask(bm.data_ptr(), vocab.words, _stream())
+        torch.cuda.synchronize()
+        assert xg.fill_last_status()[1] and db.row_info(0)["error"] == 2
+        db.accept_tokens(ids.data_ptr(), st.data_ptr(), _stream())
+        assert st.cpu().numpy()[0] == -4
+    finally:
+        xg.debug_set_large_capacity(0, 0)
+    xg.fill_next_token_bitmask([m], bm.data_ptr(), vocab.words, _stream())
+    torch.cuda.synchronize()
+    assert np.array_equal(bm.cpu().numpy()[0], oracle.pack_bitmask(orc.mask(hist, va))) and not xg.fill_last_status()[1]
+
+
 TRICKY = [
     # (grammar, alphabet, sentences): recursion, nullable left recursion, nullable chains, ambiguity, nesting, dispatch
     ('root ::= "a" root "b" | ""', b"ab", [b"aaabbb", b"ab", b""]),
@@ -794,8 +859,8 @@ def run_random_grammars(xg, seed, wanted, counting=False, follow=True):
         for step in range(8):
             xg.fill_next_token_bitmask([m], bm.data_ptr(), vocab.words, _stream())
             torch.cuda.synchronize()
-            if xg.fill_last_status()[1]:
-                break                                               # item sets beyond the documented capacity of the re-check: reported, not masked
+            if xg.fill_last_status()[1]:                            # item sets beyond the capacity of the re-check: never silent;
+                assert xg.fill_resolve_overflow([m], bm.data_ptr(), vocab.words) > 0   # the host parser decides those pairs, the mask is exact
             want = orc.mask(hist, va)
             got = bm.cpu().numpy()[0]
             assert np.array_equal(got, oracle.pack_bitmask(want)), (ebnf, hist, diff_words(got, oracle.pack_bitmask(want), toks))
