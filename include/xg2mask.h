@@ -22,10 +22,11 @@
  *   - Bit v%32 (least significant bit = 0) of int32 word v/32 stands for token v; 1 = allowed;
  *     bits at or beyond V in the last word are 0.
  *   - Device work is enqueued on the HIP stream given by the caller (a hipStream_t passed as
- *     void*, NULL = the default stream).  xg2_compile_grammar returns after its kernels have
- *     finished; fill and apply return as soon as their work is enqueued.  Compile and fill calls share
- *     device scratch buffers: their device work must not overlap, so give them one stream (or order the
- *     streams with events).  apply has no such state.
+ *     void*, NULL = the default stream); compile, fill, accept and apply all return as soon as their
+ *     work is enqueued.  Cache builds follow one another on the device whatever their streams (the
+ *     library orders them with events), and a fill waits on the device for the builds enqueued before
+ *     it, so a build may run on one stream while fill and apply of other caches run on another.  Fill
+ *     calls share one scratch: keep them on one stream (or order their streams).  apply has no state.
  *   - There is no CPU fallback: without a usable HIP device every call that needs one fails
  *     with XG2_EHIP.
  */
@@ -140,11 +141,17 @@ int32_t xg2_pool_stats(const xg2_pool*, int64_t* n_positions, int64_t* device_by
  *   accepted  = tokens that are a prefix of a string of Suf(position) [. Suf(parent)],
  *   uncertain = the other tokens with a proper non-empty prefix that is a whole such string
  *               (and, with follow_filter, a rest that some reference site can continue).
- * opts and stats may be NULL.                                                                    */
+ * opts and stats may be NULL.  The call returns once the build is enqueued on hip_stream; stats then
+ * holds what the host knows (positions, planes, checks, executed checks, host time) and zeros for what
+ * the device reports (xg2_mask_cache_stats waits and gives everything).                          */
 int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, const char* root_rule,
                             const xg2_compile_opts* opts, xg2_pool* pool, void* hip_stream,
                             xg2_mask_cache** out, xg2_compile_stats* stats);
 void    xg2_mask_cache_destroy(xg2_mask_cache*);
+/* xg2_compile_grammar returns when the build is enqueued; this call waits for it and gives the full statistics.  It is
+ * also where a failed build is reported: XG2_EOVERFLOW if item sets exceeded even the large-capacity lists (so do
+ * xg2_mask_cache_get_planes, xg2_batch_assign and fill calls on such a cache; nothing partial is ever served).          */
+int32_t xg2_mask_cache_stats(xg2_mask_cache*, xg2_compile_stats* stats);
 int32_t xg2_mask_cache_num_positions(const xg2_mask_cache*, int32_t* out);
 int32_t xg2_mask_cache_num_planes(const xg2_mask_cache*, int32_t* out);
 /* Just-in-time caches: planes that hold a row by now, build launches issued by fill calls so far and

@@ -22,7 +22,7 @@ XG2_F32, XG2_BF16 = 0, 1
 EXPORTS = [
     "xg2_last_error", "xg2_vocab_create", "xg2_vocab_destroy", "xg2_grammar_create", "xg2_grammar_destroy",
     "xg2_grammar_describe", "xg2_grammar_num_positions", "xg2_pool_create", "xg2_pool_destroy", "xg2_pool_stats",
-    "xg2_compile_grammar", "xg2_mask_cache_destroy", "xg2_mask_cache_num_positions", "xg2_mask_cache_num_planes", "xg2_mask_cache_jit_stats",
+    "xg2_compile_grammar", "xg2_mask_cache_destroy", "xg2_mask_cache_stats", "xg2_mask_cache_num_positions", "xg2_mask_cache_num_planes", "xg2_mask_cache_jit_stats",
     "xg2_mask_cache_plane_info", "xg2_mask_cache_find_plane", "xg2_mask_cache_get_planes", "xg2_matcher_create", "xg2_matcher_create_host", "xg2_matcher_destroy",
     "xg2_matcher_accept_token", "xg2_matcher_accept_tokens", "xg2_matcher_reset", "xg2_matcher_is_terminated", "xg2_matcher_frontier",
     "xg2_fill_next_token_bitmask", "xg2_fill_next_token_bitmask_noalloc", "xg2_fill_resolve_overflow", "xg2_debug_set_large_capacity",
@@ -80,6 +80,7 @@ def _load() -> ctypes.CDLL:
     L.xg2_compile_grammar.argtypes = [vp, ctypes.c_char_p, sz, ctypes.c_char_p, ctypes.POINTER(CompileOpts), vp, vp, pvp,
                                       ctypes.POINTER(CompileStats)]
     L.xg2_mask_cache_destroy.argtypes = [vp]
+    L.xg2_mask_cache_stats.argtypes = [vp, ctypes.POINTER(CompileStats)]
     L.xg2_mask_cache_num_positions.argtypes = [vp, ctypes.POINTER(i32)]
     L.xg2_mask_cache_num_planes.argtypes = [vp, ctypes.POINTER(i32)]
     L.xg2_mask_cache_jit_stats.argtypes = [vp, ctypes.POINTER(i32), ctypes.POINTER(i32), ctypes.POINTER(ctypes.c_double)]
@@ -187,7 +188,17 @@ class Pool:
 
 class MaskCache:
     def __init__(self, h, vocab: Vocab, stats: CompileStats, pool: Optional[Pool]):
-        self.h, self.vocab, self.stats, self.pool = h, vocab, stats, pool
+        self.h, self.vocab, self.host_stats, self.pool = h, vocab, stats, pool
+        self._stats = None
+
+    @property
+    def stats(self) -> CompileStats:
+        """Full statistics of the compile call; the first access waits for the build (and raises if it failed)."""
+        if self._stats is None:
+            st = CompileStats()
+            _check(lib.xg2_mask_cache_stats(self.h, ctypes.byref(st)))
+            self._stats = st
+        return self._stats
 
     def num_positions(self) -> int:
         n = ctypes.c_int32(0)

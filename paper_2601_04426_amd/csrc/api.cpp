@@ -8,6 +8,7 @@
 #include <atomic>
 #include <chrono>
 #include <cstring>
+#include <deque>
 #include <map>
 #include <memory>
 #include <mutex>
@@ -73,16 +74,39 @@ inline void upload_pinned(void* dev, void* host, size_t bytes, hipStream_t strea
 
 // Several host arrays laid out back to back (256-byte aligned) in one pinned buffer, moved to the device
 // with one copy.
-// The pinned host buffer and, for uploads that need not outlive the call, the device buffer are kept between calls
-// (allocating them costs more than a small build); the caller serialises uses (the mutex of the large-capacity
-// scratch) and waits for the stream before the next use.
-struct Staging {
+// A build does not wait for its kernels, so the pinned host buffer, the device buffer (for uploads that need not
+// outlive the build), the pinned words its results come back in and its events belong to one staging set from the
+// moment the build is enqueued until it has been looked at (finalised); sets are kept and handed out again
+// (allocating them costs more than a small build).
+struct StagingSet {
     uint8_t* host = nullptr; size_t host_cap = 0;
     uint8_t* dev = nullptr; size_t dev_cap = 0;
-    hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};   // around a build and around its classification kernel
+    uint32_t* res = nullptr; size_t res_cap = 0;                // pinned: overflow counter and flag, bit counts per built plane
+    hipEvent_t ev[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};   // around the build, around its classification kernel, results copied
+    bool in_use = false;
     void ensure_events() { for (hipEvent_t& e : ev) if (!e) HIP_CHECK(hipEventCreate(&e)); }
+    void ensure_res(size_t words) {
+        if (res_cap >= words) return;
+        if (res) (void)hipHostFree(res);
+        res = nullptr; res_cap = 0;
+        const size_t cap = std::max<size_t>(words * 2, 1024);
+        HIP_CHECK(hipHostMalloc((void**)&res, cap * sizeof(uint32_t), hipHostMallocDefault));
+        res_cap = cap;
+    }
 };
-Staging& staging() { static Staging* s = new Staging(); return *s; }
+struct StagingPool {
+    std::mutex mu;
+    std::vector<std::unique_ptr<StagingSet>> sets;
+    StagingSet* acquire() {
+        std::lock_guard<std::mutex> lk(mu);
+        for (auto& p : sets) if (!p->in_use) { p->in_use = true; return p.get(); }
+        sets.emplace_back(new StagingSet());
+        sets.back()->in_use = true;
+        return sets.back().get();
+    }
+    void release(StagingSet* s) { std::lock_guard<std::mutex> lk(mu); s->in_use = false; }
+};
+StagingPool& staging_pool() { static StagingPool* s = new StagingPool(); return *s; }
 
 struct Packer {
     struct Seg { const void* src; size_t bytes, off; };
@@ -104,9 +128,8 @@ struct Packer {
         return off;
     }
     // own_dev: the device block is allocated for this upload and belongs to the caller afterwards
-    void stage(bool own_dev) {
+    void stage(bool own_dev, StagingSet& S) {
         const size_t n = std::max<size_t>(total, 256), n_dev = n + reserved;
-        Staging& S = staging();
         if (S.host_cap < n) {
             if (S.host) (void)hipHostFree(S.host);
             S.host = nullptr; S.host_cap = 0;
@@ -217,6 +240,7 @@ struct VocabImpl {
         extend_long_bytes();
         bl.d_without.reset(new DevBuf<uint32_t>());
         bl.d_without->upload(without, nullptr);
+        HIP_CHECK(hipDeviceSynchronize());                           // builds in flight read the list that is replaced here
         d_long_rank.upload(long_rank, nullptr);
         HIP_CHECK(hipStreamSynchronize(nullptr));
         dv.long_rank = d_long_rank.p;
@@ -294,12 +318,46 @@ struct SlowImpl {
         ready = true;
     }
 };
-SlowImpl& slow() { static SlowImpl* s = new SlowImpl(); return *s; }
+SlowImpl& slow() { static SlowImpl* s = new SlowImpl(); return *s; }             // of the fill calls
+SlowImpl& build_slow() { static SlowImpl* s = new SlowImpl(); return *s; }       // of the cache builds (which may run beside a fill)
+// The library's own stream (default priority) for the builds that fill calls issue just in time.
+hipStream_t jit_stream() {
+    static hipStream_t s = [] {
+        hipStream_t st = nullptr;
+        if (hipStreamCreateWithFlags(&st, hipStreamNonBlocking) != hipSuccess) st = nullptr;
+        return st;
+    }();
+    return s;
+}
 
 // ---- cross-grammar pool -------------------------------------------------------------------------------
 // A plane is identified by (pool entry of the position's rule, canonical state, pool entry of the
 // referencing rule or -1, canonical state the referencing rule continues in or -1).
 using PlaneKey = std::array<int64_t, 5>;   // the fifth word: follow signature of the outermost rule (0 = unfiltered)
+struct PoolImpl;
+// One enqueued cache build.  Compile (and a fill that builds just in time) returns once the kernels are enqueued; whoever
+// needs their outcome next (statistics, planes copied to the host, the next compile or fill) finalises the ticket: waits for
+// its last event, reads the counters the device copied to pinned memory, and either marks the planes' rows as good
+// (noting the ones without uncertain tokens) or, if item sets overflowed even the large-capacity lists, takes the rows
+// out of the pool again and fails every cache that uses them.
+struct BuildTicket {
+    StagingSet* staging = nullptr;
+    std::shared_ptr<PoolImpl> pool;
+    hipStream_t stream = nullptr;
+    std::vector<uint32_t*> rows;                                // the rows being built, with their keys in the pool
+    std::vector<PlaneKey> keys;
+    int64_t executed = 0, executed_bytes = 0;
+    double host_ms = 0;
+    int state = 0;                                              // 0 enqueued, 1 good, 2 failed
+    int64_t slow = 0, n_accepted = 0, n_uncertain = 0;
+    float device_ms = 0.f, kernel_ms = 0.f;
+    ~BuildTicket() { if (staging) { (void)hipEventSynchronize(staging->ev[4]); staging_pool().release(staging); } }
+};
+// Builds follow one another on the device whatever streams they were given: each waits for the event of the one before
+// (they share the large-capacity scratch, and a later one may copy from rows an earlier one writes).
+struct BuildChain { std::mutex mu; std::shared_ptr<BuildTicket> last; };
+BuildChain& build_chain() { static BuildChain* c = new BuildChain(); return *c; }
+
 struct PoolImpl {
     size_t max_bytes = 0;
     std::mutex mu;
@@ -316,6 +374,8 @@ struct PoolImpl {
     // rows in use: by how many live caches, and when last taken into a cache.  When max_bytes is reached, rows that no
     // live cache uses are given up, least recently used first, and their memory is handed out again.
     struct RowMeta { PlaneKey key; int32_t refs; uint64_t stamp; };
+    std::unordered_map<const uint32_t*, std::shared_ptr<BuildTicket>> building;   // rows whose build has not been finalised
+    std::deque<std::shared_ptr<BuildTicket>> pending;                             // tickets not finalised yet, oldest first
     std::unordered_map<const uint32_t*, RowMeta> meta;
     std::vector<uint32_t*> free_rows;
     uint64_t clock = 0;
@@ -412,13 +472,17 @@ struct PlaneInfo {
     std::array<uint32_t, 8> fb_same{};
     int32_t site_plane = -1, site_list = -1;                // the same state under another site: same classes for every token outside that list
 };
-struct BuildResult {
-    int64_t built = 0, executed = 0, executed_bytes = 0, slow = 0, n_accepted = 0, n_uncertain = 0;
-    double host_ms = 0;
-    float device_ms = 0.f, kernel_ms = 0.f;
-};
 struct CacheImpl {
     bool follow = true;
+    // builds this cache depends on that have not been finalised (its own, and those of other caches it took rows from);
+    // the planes that got a row from them; what its own compile build reported; whether one of the builds failed
+    std::vector<std::shared_ptr<BuildTicket>> tickets;
+    std::vector<int32_t> fresh_planes;
+    std::shared_ptr<BuildTicket> compile_ticket;
+    bool failed = false;
+    std::vector<std::shared_ptr<BuildTicket>> jit_tickets;  // builds issued by fill calls whose device time has not been added up yet
+    double host_lower_ms = 0;                               // EBNF -> tables and plan, of the compile call
+    int64_t compile_built = 0;
     std::vector<uint32_t> site_off, site_tgt;               // per rule: states in which referencing rules continue
     int64_t n_built = 0, jit_calls = 0;                     // planes holding a row; build launches issued by fill
     double jit_device_ms = 0;
@@ -426,13 +490,7 @@ struct CacheImpl {
     std::shared_ptr<PoolImpl> pool;
     std::shared_ptr<GrammarImpl> gram;
     uint8_t* d_tables = nullptr;                            // one device block holding all packed tables
-    ~CacheImpl() {
-        if (d_tables) (void)hipFree(d_tables);
-        if (pool) {
-            std::lock_guard<std::mutex> lk(pool->mu);
-            for (const PlaneInfo& pi : planes) if (pi.row) pool->release(pi.row);
-        }
-    }
+    ~CacheImpl();
     DevTables dt{};
     int32_t context_depth = 2;
     std::vector<PlaneInfo> planes;
@@ -614,12 +672,76 @@ struct xg2_pool { std::shared_ptr<PoolImpl> p; };
 struct xg2_mask_cache { std::shared_ptr<CacheImpl> p; };
 struct xg2_matcher { std::unique_ptr<MatcherImpl> p; };
 
-// Builds the planes `todo` of a cache that do not hold a row yet: rows the pool already has are taken from it, the
-// others are allocated, planned (closed start set, live first-byte ranges, chunks) and classed on the device.
-// with_tables: the packed grammar tables travel in the same upload and stay with the cache (first call only).
-// The caller holds the pool's mutex and the mutex of the large-capacity scratch.  Returns after the kernels have
-// finished.
-int32_t build_planes(CacheImpl& cache, const std::vector<int32_t>& todo, hipStream_t stream, bool with_tables, SlowScratch S, BuildResult& res) {
+// Looks at a finished build.  The caller holds the pool's mutex.
+void finalize_ticket(BuildTicket& T) {
+    if (T.state) return;
+    PoolImpl& pool = *T.pool;
+    StagingSet& S = *T.staging;
+    hipError_t e = hipEventSynchronize(S.ev[4]);
+    bool failed = e != hipSuccess;
+    if (!failed) {
+        (void)hipEventElapsedTime(&T.device_ms, S.ev[0], S.ev[1]);
+        (void)hipEventElapsedTime(&T.kernel_ms, S.ev[2], S.ev[3]);
+        T.slow = S.res[0];
+        failed = S.res[1] != 0;                                     // item sets exceeded even the large-capacity lists
+    }
+    for (size_t k = 0; k < T.rows.size(); ++k) {
+        pool.building.erase(T.rows[k]);
+        if (failed) {
+            // partial results: nobody may take the row from the pool any more (caches that did are failed through this
+            // ticket); its memory is not handed out again while they may still hold it
+            auto it = pool.rows.find(T.keys[k]);
+            if (it != pool.rows.end() && it->second == T.rows[k]) pool.rows.erase(it);
+            continue;
+        }
+        const uint32_t n_acc = S.res[2 + 2 * k], n_unc = S.res[3 + 2 * k];
+        if (n_unc == 0) pool.no_uncertain.insert(T.rows[k]);
+        T.n_accepted += n_acc; T.n_uncertain += n_unc;
+    }
+    T.state = failed ? 2 : 1;
+    for (auto it = pool.pending.begin(); it != pool.pending.end(); ++it) if (it->get() == &T) { pool.pending.erase(it); break; }
+    {
+        std::lock_guard<std::mutex> ck(build_chain().mu);
+        staging_pool().release(T.staging);
+        T.staging = nullptr;
+        if (build_chain().last.get() == &T) build_chain().last.reset();
+    }
+}
+
+// Finalises every build the cache depends on; afterwards its planes know whether their uncertain rows are empty, and
+// cache.failed says whether one of the builds overflowed.  Takes the pool's mutex.
+void finalize_cache(CacheImpl& cache) {
+    if (cache.tickets.empty() && cache.fresh_planes.empty()) return;
+    std::lock_guard<std::mutex> lk(cache.pool->mu);
+    for (auto& t : cache.tickets) { finalize_ticket(*t); if (t->state == 2) cache.failed = true; }
+    cache.tickets.clear();
+    for (int32_t k : cache.fresh_planes) {
+        PlaneInfo& pi = cache.planes[(size_t)k];
+        pi.no_uncertain = pi.row && cache.pool->no_uncertain.count(pi.row) != 0;
+    }
+    cache.fresh_planes.clear();
+}
+int32_t cache_failed() { return fail(XG2_EOVERFLOW, "mask cache build: Earley item sets exceeded the large-capacity limit"); }
+
+CacheImpl::~CacheImpl() {
+    if (pool) {
+        // its own builds may still be writing: look at them first, so that the pool learns what became of the rows
+        try { finalize_cache(*this); } catch (...) {}
+        std::lock_guard<std::mutex> lk(pool->mu);
+        for (const PlaneInfo& pi : planes) if (pi.row) pool->release(pi.row);
+    }
+    if (d_tables) (void)hipFree(d_tables);
+}
+
+// Enqueues the build of the planes `todo` of a cache that do not hold a row yet: rows the pool already has are taken
+// from it, the others are allocated, planned (closed start set, live first-byte ranges, chunks) and classed on the
+// device, on `stream`, after the build enqueued before this one.  with_tables: the packed grammar tables travel in the
+// same upload and stay with the cache (first call only).  Does not wait: the planes have their rows when the call
+// returns, the outcome is looked at by finalize_cache.  The caller holds the pool's mutex and the mutex of the
+// large-capacity scratch.  *ticket_out = the build, or null if nothing had to be built.
+int32_t build_planes(CacheImpl& cache, const std::vector<int32_t>& todo, hipStream_t stream, bool with_tables, SlowScratch S,
+                     std::shared_ptr<BuildTicket>* ticket_out) {
+    if (ticket_out) ticket_out->reset();
     auto t1 = std::chrono::steady_clock::now();
     PoolImpl& pool = *cache.pool;
     VocabImpl& V = *cache.vocab;
@@ -649,9 +771,14 @@ int32_t build_planes(CacheImpl& cache, const std::vector<int32_t>& todo, hipStre
         PlaneInfo& pi = cache.planes[(size_t)k];
         if (pi.row) continue;
         auto have = pool.rows.find(pi.key);
-        if (have != pool.rows.end()) {                           // another grammar built it
+        if (have != pool.rows.end()) {                           // another grammar built it, or is building it
             uint32_t* row = have->second;
             pi.row = row; pi.no_uncertain = pool.no_uncertain.count(row) != 0; pool.take(row, pi.key); ++cache.n_built;
+            auto bt = pool.building.find(row);
+            if (bt != pool.building.end()) {
+                if (std::find(cache.tickets.begin(), cache.tickets.end(), bt->second) == cache.tickets.end()) cache.tickets.push_back(bt->second);
+                cache.fresh_planes.push_back(k);
+            }
             continue;
         }
         uint32_t* row = pool.alloc_row(row_bytes, todo.size() - i);
@@ -660,6 +787,14 @@ int32_t build_planes(CacheImpl& cache, const std::vector<int32_t>& todo, hipStre
         pool.rows.emplace(pi.key, row);
     }
     if (build.empty() && !with_tables) { rollback.armed = false; return XG2_OK; }
+    // keep the number of builds nobody has looked at small: finished ones are finalised on the way, the oldest is waited for
+    while (!pool.pending.empty() && (pool.pending.size() > 6 || hipEventQuery(pool.pending.front()->staging->ev[4]) == hipSuccess))
+        finalize_ticket(*std::shared_ptr<BuildTicket>(pool.pending.front()));
+    auto ticket = std::make_shared<BuildTicket>();
+    ticket->pool = cache.pool;
+    ticket->stream = stream;
+    ticket->staging = staging_pool().acquire();
+    StagingSet& SS = *ticket->staging;
 
     // plan: closed start set and live first-byte ranges of every plane to build
     std::vector<uint32_t> ctx_items, ctx_wait, ctx_wait_off;
@@ -826,12 +961,19 @@ int32_t build_planes(CacheImpl& cache, const std::vector<int32_t>& todo, hipStre
     const size_t o_range_a = tab.add(range_a), o_range_b = tab.add(range_b), o_range_first = tab.add(range_first), o_pctx = tab.add(plane_ctx), o_items = tab.add(ctx_items), o_wait = tab.add(ctx_wait),
                  o_wait_off = tab.add(ctx_wait_off), o_rows = tab.add(build_rows), o_copies = tab.add(copies), o_fb_copies = tab.add(fb_copies), o_zero = tab.add(zeros);
     const size_t o_chunks = tab.reserve(n_chunks * 2 * sizeof(uint4));
-    tab.stage(with_tables);
+    tab.stage(with_tables, SS);
     if (with_tables) cache.d_tables = tab.dev;                     // the cache owns the block from here on
-    res.host_ms = ms_since(t1);
+    ticket->host_ms = ms_since(t1);
 
-    staging().ensure_events();
-    const hipEvent_t ev0 = staging().ev[0], ev1 = staging().ev[1], evk0 = staging().ev[2], evk1 = staging().ev[3];
+    SS.ensure_events();
+    SS.ensure_res(2 + 2 * build_rows.size());
+    const hipEvent_t ev0 = SS.ev[0], ev1 = SS.ev[1], evk0 = SS.ev[2], evk1 = SS.ev[3];
+    {
+        // after the build enqueued before this one, whatever its stream
+        std::lock_guard<std::mutex> ck(build_chain().mu);
+        std::shared_ptr<BuildTicket>& last = build_chain().last;
+        if (last && last->state == 0 && last->staging && last->stream != stream) HIP_CHECK(hipStreamWaitEvent(stream, last->staging->ev[4], 0));
+    }
     HIP_CHECK(hipEventRecord(ev0, stream));
     pool.flush_zero(stream);                                       // the rows start as zeros: tokens skipped by their first byte are never written
     tab.copy(stream);
@@ -865,30 +1007,28 @@ int32_t build_planes(CacheImpl& cache, const std::vector<int32_t>& todo, hipStre
     launch_copy_first_byte(tab.at<const FirstByteCopyJob>(o_fb_copies), (uint32_t)fb_copies.size(), V.d_first_byte.p, V.W, stream);
     HIP_CHECK(hipEventRecord(ev1, stream));                              // every plane is written
     if (!build.empty()) launch_popcount(d_rows_p, (uint32_t)build_rows.size(), V.W, d_counts, stream);   // statistics
-    uint32_t slow_counts[2] = {0, 0};
-    std::vector<uint32_t> plane_counts(2 * build_rows.size(), 0);
-    HIP_CHECK(hipMemcpyAsync(slow_counts, S.count, sizeof(slow_counts), hipMemcpyDeviceToHost, stream));
-    if (!build_rows.empty()) HIP_CHECK(hipMemcpyAsync(plane_counts.data(), d_counts, plane_counts.size() * sizeof(uint32_t), hipMemcpyDeviceToHost, stream));
-    HIP_CHECK(hipStreamSynchronize(stream));
+    HIP_CHECK(hipMemcpyAsync(SS.res, S.count, 2 * sizeof(uint32_t), hipMemcpyDeviceToHost, stream));
+    if (!build_rows.empty()) HIP_CHECK(hipMemcpyAsync(SS.res + 2, d_counts, 2 * build_rows.size() * sizeof(uint32_t), hipMemcpyDeviceToHost, stream));
+    HIP_CHECK(hipEventRecord(SS.ev[4], stream));
     HIP_CHECK(hipGetLastError());
-    HIP_CHECK(hipEventElapsedTime(&res.device_ms, ev0, ev1));
-    HIP_CHECK(hipEventElapsedTime(&res.kernel_ms, evk0, evk1));
-    if (slow_counts[1])                                             // the rows hold partial results: the guard takes them back
-        return fail(XG2_EOVERFLOW, "mask cache build: Earley item sets exceeded the large-capacity limit");
+    // from here on the build is under way: the planes have their rows, the ticket says what became of them
     rollback.armed = false;
+    ticket->rows = build_rows;
+    ticket->executed = executed; ticket->executed_bytes = executed_bytes;
     for (size_t k = 0; k < build.size(); ++k) {
         PlaneInfo& pi = cache.planes[(size_t)build[k]];
         pi.row = build_rows[k];
+        pi.no_uncertain = false;                                    // not known yet
         pool.take(pi.row, pi.key);
-        pi.no_uncertain = plane_counts[2 * k + 1] == 0;
-        if (pi.no_uncertain) pool.no_uncertain.insert(build_rows[k]);
-        res.n_accepted += plane_counts[2 * k]; res.n_uncertain += plane_counts[2 * k + 1];
+        pool.building.emplace(pi.row, ticket);
+        ticket->keys.push_back(pi.key);
+        cache.fresh_planes.push_back(build[k]);
     }
     cache.n_built += (int64_t)build.size();
-    res.built = (int64_t)build.size();
-    res.executed = executed;
-    res.executed_bytes = executed_bytes;
-    res.slow = slow_counts[0];
+    cache.tickets.push_back(ticket);
+    pool.pending.push_back(ticket);
+    { std::lock_guard<std::mutex> ck(build_chain().mu); build_chain().last = ticket; }
+    if (ticket_out) *ticket_out = ticket;
     return XG2_OK;
 }
 
@@ -971,6 +1111,8 @@ void ensure_cache_on_device(const std::shared_ptr<CacheImpl>& cp) {
     CacheImpl& C = *cp;
     std::lock_guard<std::mutex> lk(C.on_device.mu);
     if (C.on_device.ready) return;
+    finalize_cache(C);
+    if (C.failed) throw std::length_error("mask cache build: Earley item sets exceeded the large-capacity limit");
     if (C.n_built != (int64_t)C.planes.size())
         throw GrammarError("matchers on the device need a fully built mask cache (this one was compiled just in time)");
     CacheImpl::OnDevice& D = C.on_device;
@@ -1143,9 +1285,9 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
         std::lock_guard<std::mutex> pool_lock(pool.mu);
         if (!pool.vocab) pool.vocab = vocab->p;
         else if (pool.vocab.get() != vocab->p.get()) return fail(XG2_EINVAL, "xg2_compile_grammar: pool is bound to another vocabulary");
-        std::lock_guard<std::mutex> slow_lock(slow().mu);
-        slow().ensure();
-        SlowScratch S = slow().s;
+        std::lock_guard<std::mutex> slow_lock(build_slow().mu);
+        build_slow().ensure();
+        SlowScratch S = build_slow().s;
         const int R = (int)g.rules.size();
 
         // intern every rule in the pool, referenced rules first
@@ -1416,28 +1558,50 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
             std::sort(todo.begin(), todo.end());
         }
         double host_ms_a = ms_since(t0);
-        BuildResult res;
-        int32_t rc = build_planes(*cache, todo, stream, true, S, res);
+        std::shared_ptr<BuildTicket> ticket;
+        int32_t rc = build_planes(*cache, todo, stream, true, S, &ticket);
         if (rc != XG2_OK) return rc;
-        if (stats) {
+        cache->compile_ticket = ticket;
+        cache->host_lower_ms = host_ms_a + (ticket ? ticket->host_ms : 0.0);
+        cache->compile_built = ticket ? (int64_t)ticket->rows.size() : 0;
+        if (stats) {                                            // what is known without waiting for the device
+            std::memset(stats, 0, sizeof(*stats));
             stats->positions = (int64_t)g.positions.size();
             stats->unique = (int64_t)cache->planes.size();
-            stats->built = res.built;
-            stats->checks = res.built * (int64_t)V.n_sorted;
-            stats->executed_checks = res.executed;
-            stats->executed_token_bytes = res.executed_bytes;
-            stats->slow_path = res.slow;
-            stats->n_accepted = res.n_accepted;
-            stats->n_uncertain = res.n_uncertain;
-            stats->host_lower_ms = host_ms_a + res.host_ms;
-            stats->device_ms = res.device_ms;
-            stats->kernel_ms = res.kernel_ms;
+            stats->built = cache->compile_built;
+            stats->checks = cache->compile_built * (int64_t)V.n_sorted;
+            stats->executed_checks = ticket ? ticket->executed : 0;
+            stats->executed_token_bytes = ticket ? ticket->executed_bytes : 0;
+            stats->host_lower_ms = cache->host_lower_ms;
         }
         *out = new xg2_mask_cache{cache};
         return XG2_OK;
     });
 }
 void xg2_mask_cache_destroy(xg2_mask_cache* c) { delete c; }
+
+int32_t xg2_mask_cache_stats(xg2_mask_cache* c, xg2_compile_stats* stats) {
+    return guarded([&]() -> int32_t {
+        if (!c) return fail(XG2_EINVAL, "xg2_mask_cache_stats: null cache");
+        CacheImpl& C = *c->p;
+        finalize_cache(C);
+        if (C.failed) return cache_failed();
+        if (!stats) return XG2_OK;
+        std::memset(stats, 0, sizeof(*stats));
+        const BuildTicket* t = C.compile_ticket.get();
+        stats->positions = (int64_t)C.gram->g.positions.size();
+        stats->unique = (int64_t)C.planes.size();
+        stats->built = C.compile_built;
+        stats->checks = C.compile_built * (int64_t)C.vocab->n_sorted;
+        stats->host_lower_ms = C.host_lower_ms;
+        if (t) {
+            stats->executed_checks = t->executed; stats->executed_token_bytes = t->executed_bytes;
+            stats->slow_path = t->slow; stats->n_accepted = t->n_accepted; stats->n_uncertain = t->n_uncertain;
+            stats->device_ms = t->device_ms; stats->kernel_ms = t->kernel_ms;
+        }
+        return XG2_OK;
+    });
+}
 
 int32_t xg2_mask_cache_num_positions(const xg2_mask_cache* c, int32_t* out) {
     if (!c || !out) return fail(XG2_EINVAL, "xg2_mask_cache_num_positions: bad argument");
@@ -1446,6 +1610,10 @@ int32_t xg2_mask_cache_num_positions(const xg2_mask_cache* c, int32_t* out) {
 }
 int32_t xg2_mask_cache_jit_stats(const xg2_mask_cache* c, int32_t* n_built, int32_t* n_builds_in_fill, double* device_ms_in_fill) {
     if (!c) return fail(XG2_EINVAL, "xg2_mask_cache_jit_stats: null cache");
+    CacheImpl& C = *const_cast<CacheImpl*>(c->p.get());
+    try { finalize_cache(C); } catch (const std::exception& e) { return fail(XG2_EHIP, e.what()); }
+    for (auto& t : C.jit_tickets) C.jit_device_ms += t->device_ms;
+    C.jit_tickets.clear();
     if (n_built) *n_built = (int32_t)c->p->n_built;
     if (n_builds_in_fill) *n_builds_in_fill = (int32_t)c->p->jit_calls;
     if (device_ms_in_fill) *device_ms_in_fill = c->p->jit_device_ms;
@@ -1485,6 +1653,8 @@ int32_t xg2_mask_cache_get_planes(const xg2_mask_cache* c, int32_t k, int32_t* a
     return guarded([&]() -> int32_t {
         if (!c || k < 0 || (size_t)k >= c->p->planes.size()) return fail(XG2_EINVAL, "xg2_mask_cache_get_planes: bad argument");
         const uint32_t W = c->p->vocab->W;
+        finalize_cache(*const_cast<CacheImpl*>(c->p.get()));
+        if (c->p->failed) return cache_failed();
         const uint32_t* row = c->p->planes[(size_t)k].row;
         if (!row) return fail(XG2_EINVAL, "xg2_mask_cache_get_planes: this plane has not been built yet (cache compiled just in time)");
         HIP_CHECK(hipDeviceSynchronize());
@@ -1638,6 +1808,18 @@ int32_t fill_common(xg2_matcher* const* matchers, int32_t B, int32_t* bitmask_de
                 host_workers().run(parts, work);
                 if (failed) return fail(XG2_EINVAL, "xg2_fill_next_token_bitmask: preparing a matcher failed");
             }
+            // builds enqueued by earlier calls (compile, or a fill that built just in time) are looked at now: by this
+            // time they have finished, and a failed one must not pass
+            {
+                CacheImpl* seen = nullptr;
+                for (int32_t b = 0; b < B; ++b) {
+                    CacheImpl* C = matchers[b]->p->cache.get();
+                    if (C == seen) continue;
+                    seen = C;
+                    if (!C->tickets.empty() || !C->fresh_planes.empty()) finalize_cache(*C);
+                    if (C->failed) return cache_failed();
+                }
+            }
             std::map<CacheImpl*, std::vector<int32_t>> missing;
             for (int32_t b = 0; b < B; ++b) {
                 MatcherImpl& M = *matchers[b]->p;
@@ -1656,12 +1838,18 @@ int32_t fill_common(xg2_matcher* const* matchers, int32_t B, int32_t* bitmask_de
                                                       "(building allocates: use xg2_fill_next_token_bitmask for such caches)");
                 CacheImpl& C = *kv.first;
                 std::lock_guard<std::mutex> pool_lock(C.pool->mu);
-                std::lock_guard<std::mutex> slow_lock(slow().mu);
-                slow().ensure();
-                BuildResult res;
-                int32_t rc = build_planes(C, v, stream, false, slow().s, res);
+                std::lock_guard<std::mutex> slow_lock(build_slow().mu);
+                build_slow().ensure();
+                // on the library's own stream, beside whatever the caller's stream is doing; the caller's stream waits for
+                // it on the device, the host does not
+                std::shared_ptr<BuildTicket> ticket;
+                int32_t rc = build_planes(C, v, jit_stream(), false, build_slow().s, &ticket);
                 if (rc != XG2_OK) return rc;
-                if (res.built) { ++C.jit_calls; C.jit_device_ms += res.device_ms; }     // rows found in the pool cost no launch
+                if (ticket) {                                       // rows found in the pool cost no launch
+                    ++C.jit_calls;
+                    C.jit_tickets.push_back(ticket);
+                    HIP_CHECK(hipStreamWaitEvent(stream, ticket->staging->ev[4], 0));
+                }
             }
         }
 
@@ -1707,6 +1895,12 @@ int32_t fill_common(xg2_matcher* const* matchers, int32_t B, int32_t* bitmask_de
         size_t o_zero = align(o_tabs + tables.size() * sizeof(DevTables));      // overflow-list length and flag
         size_t total = align(o_zero + 4 * sizeof(uint32_t));
 
+        {
+            // on the device, after the latest build (the one this call issued, or one a compile call issued on another stream)
+            std::lock_guard<std::mutex> ck(build_chain().mu);
+            const std::shared_ptr<BuildTicket>& last = build_chain().last;
+            if (last && last->state == 0 && last->staging && last->stream != stream) HIP_CHECK(hipStreamWaitEvent(stream, last->staging->ev[4], 0));
+        }
         std::lock_guard<std::mutex> ws_lock(fill_ws().mu);
         std::lock_guard<std::mutex> slow_lock(slow().mu);
         auto pack = [&](uint8_t* host) {
@@ -1843,9 +2037,11 @@ int32_t xg2_fill_resolve_overflow(xg2_matcher* const* matchers, int32_t B, int32
 }
 
 int32_t xg2_debug_set_large_capacity(int32_t items, int32_t wait_entries) {
-    std::lock_guard<std::mutex> slow_lock(slow().mu);
-    slow().k_cap = items <= 0 ? kSlowK : std::min<uint32_t>((uint32_t)items, kSlowK);
-    slow().wm_cap = wait_entries <= 0 ? kSlowWM : std::min<uint32_t>((uint32_t)wait_entries, kSlowWM);
+    for (SlowImpl* si : {&slow(), &build_slow()}) {
+        std::lock_guard<std::mutex> slow_lock(si->mu);
+        si->k_cap = items <= 0 ? kSlowK : std::min<uint32_t>((uint32_t)items, kSlowK);
+        si->wm_cap = wait_entries <= 0 ? kSlowWM : std::min<uint32_t>((uint32_t)wait_entries, kSlowWM);
+    }
     return XG2_OK;
 }
 
