@@ -74,8 +74,8 @@ def main() -> int:
     ap.add_argument("--cross-grammar", type=int, default=0, metavar="N",
                     help="also compile the first N grammars of the cross-grammar workload (config 4; 256 = all) into one pool and "
                          "report planes built once versus positions, and checks/s (adds build launches of other sizes)")
-    ap.add_argument("--jit", action="store_true", help="also time 32 decode steps on a cache compiled just in time (adds small launches of "
-                                                       "the build and fill kernels, so per-kernel averages of a profile no longer match the main figures)")
+    ap.add_argument("--no-jit", action="store_true", help="skip the just-in-time leg (128 decode steps on a cache compiled just in time and on the "
+                                                          "fully built one: per-step fill latency median / P99 / max)")
     ap.add_argument("--build-only", action="store_true",
                     help="time cache builds of --config only (steps = builds; no decode, no oracle): the command the build kernel's profiles are taken with")
     ap.add_argument("--cpu-positions", type=int, default=4096, help="positions in the oracle's timed sample")
@@ -408,7 +408,7 @@ def main() -> int:
                                 "executed_checks": tot["executed"]}
         del keep, pool4
 
-    if args.jit:
+    if not args.no_jit:
         # per-step latency of fill (host + device, synchronised) along 128 decode steps of B fresh sentences: on a cache
         # compiled just in time (nothing pre-built) and, for reference, on the fully built one
         def step_latencies(c):
@@ -425,16 +425,22 @@ def main() -> int:
                 lat.append((time.perf_counter() - tj) * 1e3)
                 batch_.accept_tokens([t[stp] if stp < len(t) else -1 for t in tr])
             return sorted(lat)
-        jit_cache = xg.compile_grammar(vocab, ebnf, root, stream=stream, jit=True, jit_prebuild=0)
-        jlat = step_latencies(jit_cache)
-        flat = step_latencies(cache0)
-        jbuilt, jlaunches, jms = jit_cache.jit_stats()
         pct = lambda v, q: v[min(len(v) - 1, int(q * len(v)))]
-        out["jit"] = {"compile_device_ms": jit_cache.stats.device_ms, "planes_total": jit_cache.num_planes(), "planes_built_after_128_steps": jbuilt,
-                      "build_launches_in_fill": jlaunches, "build_device_ms_in_fill": jms,
-                      "fill_step_ms": {"median": pct(jlat, 0.5), "p99": pct(jlat, 0.99), "max": jlat[-1], "mean": mean(jlat)},
-                      "fill_step_ms_fully_built_cache": {"median": pct(flat, 0.5), "p99": pct(flat, 0.99), "max": flat[-1], "mean": mean(flat)}}
-        del jit_cache
+        flat = step_latencies(cache0)
+        out["jit"] = {"note": "fill-step latency (host call + device, synchronised) over 128 decode steps of %d fresh sentences, host matchers; "
+                              "K = planes built at compile time (the costliest first), the rest by the fill calls that reach them, on the library's own stream" % B,
+                      "fully_built_cache": {"fill_step_ms": {"mean": mean(flat), "median": pct(flat, 0.5), "p99": pct(flat, 0.99), "max": flat[-1]}},
+                      "K": {}}
+        for K in (0, 5, 10):
+            jit_cache = xg.compile_grammar(vocab, ebnf, root, stream=stream, jit=True, jit_prebuild=K)
+            compile_ms = jit_cache.stats.device_ms
+            compile_host_ms = jit_cache.stats.host_lower_ms
+            jlat = step_latencies(jit_cache)
+            jbuilt, jlaunches, jms = jit_cache.jit_stats()
+            out["jit"]["K"][str(K)] = {"compile_device_ms": compile_ms, "compile_host_ms": compile_host_ms, "planes_total": jit_cache.num_planes(),
+                                       "planes_built_after_128_steps": jbuilt, "build_launches_in_fill": jlaunches, "build_device_ms_in_fill": jms,
+                                       "fill_step_ms": {"mean": mean(jlat), "median": pct(jlat, 0.5), "p99": pct(jlat, 0.99), "max": jlat[-1]}}
+            del jit_cache
 
     if not args.no_cpu_baseline:
         import oracle

@@ -364,6 +364,60 @@ def test_jit_compilation_gives_the_same_masks(xg, index, prebuild, batch, steps,
     assert n2 > 0 and cache2.jit_stats()[1] == 0 and pool.stats()[0] == built
 
 
+def test_builds_in_flight_on_other_streams(xg):
+    """Section 3.5: compilation overlapped with decoding.  (a) A cache compiled on one stream and used at once by a fill
+    on another, with no host synchronisation in between: the library orders the two on the device.  (b) A cache compiled
+    just in time: 40 decode steps whose fill calls issue builds on the library's own stream, again without any host
+    synchronisation until the end; every step's masks were copied aside on the fill stream and are compared with the
+    oracle's afterwards."""
+    import torch
+    cfg, vocab, va = load(2)
+    ebnf, root = cfg.grammars[0]
+    orc = oracle.Oracle(ebnf, root)
+    dev = torch.device("cuda:0")
+    W, B, steps = vocab.words, 64, 40
+    xg.compile_grammar(vocab, ebnf, root, stream=_stream()).stats      # vocabulary on the device, allocations warm
+    side = torch.cuda.Stream()                                         # default priority
+    torch.cuda.synchronize()
+    # (a)
+    cache = xg.compile_grammar(vocab, ebnf, root, stream=side.cuda_stream)
+    m = [xg.Matcher(cache) for _ in range(4)]
+    bm = torch.zeros((4, W), dtype=torch.int32, device=dev)
+    xg.fill_next_token_bitmask(m, bm.data_ptr(), W, _stream())          # the build may still be running on `side`
+    torch.cuda.synchronize()
+    want0 = oracle.pack_bitmask(orc.mask(b"", va))
+    assert all(np.array_equal(row, want0) for row in bm.cpu().numpy())
+    assert cache.stats.built == cache.num_planes()
+    # (b)
+    lazy = xg.compile_grammar(vocab, ebnf, root, stream=_stream(), jit=True, jit_prebuild=0)
+    rng = random.Random(3535)
+    seg = gen.Segmenter(cfg.vocab)
+    traces = [seg.segment(cfg.sample_text(rng, 0), rng) for _ in range(B)]
+    matchers = [xg.Matcher(lazy) for _ in range(B)]
+    batch = xg.MatcherBatch(matchers)
+    bitmask = torch.zeros((B, W), dtype=torch.int32, device=dev)
+    kept = torch.zeros((steps, B, W), dtype=torch.int32, device=dev)
+    for step in range(steps):
+        xg.fill_next_token_bitmask(batch, bitmask.data_ptr(), W, _stream())
+        kept[step].copy_(bitmask, non_blocking=True)
+        ids = np.array([t[step] if step < len(t) else -1 for t in traces], dtype=np.int32)
+        assert not batch.accept_tokens(ids).any()
+    torch.cuda.synchronize()
+    got = kept.cpu().numpy()
+    built, launches, ms = lazy.jit_stats()
+    assert launches >= 5 and 0 < built < lazy.num_planes() and ms > 0
+    n = 0
+    for step in range(steps):
+        for b in range(step % 7, B, 7):
+            if step > len(traces[b]):
+                continue
+            hist = b"".join(cfg.vocab.tokens[t] for t in traces[b][:step])
+            want = oracle.pack_bitmask(orc.mask(hist, va))
+            assert np.array_equal(got[step, b], want), (step, b, diff_words(got[step, b], want, cfg.vocab.tokens))
+            n += 1
+    assert n > 300
+
+
 def test_config4_cross_grammar_pool(xg):
     """Reduced cross-grammar workload: planes are built once per distinct structure, later grammars reuse them,
     and what a reusing grammar sees equals what the oracle computes for that grammar alone."""
