@@ -75,13 +75,18 @@ typedef struct xg2_matcher xg2_matcher;
  * jit (default 0): 1 = just-in-time compilation (section 3.5): xg2_compile_grammar builds only the
  *   jit_prebuild planes with the largest estimated cost; every other plane is built by the first
  *   xg2_fill_next_token_bitmask call whose matchers reach it (looked up in the pool first), on that
- *   call's stream, before the masks are filled.  The masks are the same either way.             */
+ *   call's stream, before the masks are filled.  The masks are the same either way.
+ * partial_hits (default 1; with follow_filter and a pool): a plane whose structure (rule, state, referencing state)
+ *   the pool already holds under another follow language is not built from scratch (section 3.3, partial cache
+ *   hit): its accepted tokens are copied, and only the tokens that leave the rule early and die -- every plane
+ *   keeps them in a third row -- are run again, against this grammar's follow language.  Same planes either way. */
 typedef struct xg2_compile_opts {
     int32_t context_depth;
     int32_t merge_equivalent;
     int32_t follow_filter;
     int32_t jit;
     int32_t jit_prebuild;
+    int32_t partial_hits;
 } xg2_compile_opts;
 
 /* Counters filled by xg2_compile_grammar. */
@@ -89,7 +94,8 @@ typedef struct xg2_compile_stats {
     int64_t positions;        /* scannable (rule, state) positions of the grammar                 */
     int64_t unique;           /* distinct planes this grammar uses (after dedupe and merging)     */
     int64_t built;            /* planes computed by this call (pool misses)                       */
-    int64_t checks;           /* built * (number of checkable tokens): logical (plane, token)     */
+    int64_t partial_hits;     /* of those: derived from a plane of the same structure (section 3.3) */
+    int64_t checks;           /* (built - partial_hits) * (number of checkable tokens): logical (plane, token) pairs */
     int64_t executed_checks;  /* (plane, token) pairs a lane actually stepped through (not the
                                  tokens skipped by their first byte or taken from another plane)  */
     int64_t executed_token_bytes; /* summed token lengths over the executed pairs                     */

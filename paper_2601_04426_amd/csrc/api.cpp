@@ -346,6 +346,8 @@ struct BuildTicket {
     hipStream_t stream = nullptr;
     std::vector<uint32_t*> rows;                                // the rows being built, with their keys in the pool
     std::vector<PlaneKey> keys;
+    std::vector<uint32_t*> borrowed;                            // rows of other planes this build reads: kept from eviction until it is looked at
+    int64_t partial_hits = 0;                                   // planes derived from a plane of the same structure
     int64_t executed = 0, executed_bytes = 0;
     double host_ms = 0;
     int state = 0;                                              // 0 enqueued, 1 good, 2 failed
@@ -366,6 +368,9 @@ struct PoolImpl {
     std::vector<Entry> entries;
     std::unordered_multimap<uint64_t, int> by_hash;
     std::map<PlaneKey, uint32_t*> rows;
+    // per structure (the key without its follow signature), one row built under the follow filter: what a plane of the same
+    // structure under another follow language is derived from (section 3.3: partial cache hit)
+    std::map<std::array<int64_t, 4>, uint32_t*> by_structure;
     std::unordered_set<const uint32_t*> no_uncertain;      // rows whose uncertain plane is all zero (need not be read)
     // bounded-bisimulation classes of interned rules, in canonical state numbers: (entry, token-length budget) -> for
     // canonical state c, the canonical state of its representative
@@ -380,6 +385,8 @@ struct PoolImpl {
     std::vector<uint32_t*> free_rows;
     uint64_t clock = 0;
     int64_t n_evicted = 0;
+    struct WordsHash { size_t operator()(const std::vector<uint64_t>& v) const { uint64_t h = 0x9E3779B97F4A7C15ull; for (uint64_t w : v) h = hash_combine(h, w); return (size_t)h; } };
+    std::unordered_map<std::vector<uint64_t>, uint64_t, WordsHash> follow_nodes;    // exact interning of follow-language descriptions
     std::vector<void*> slabs;
     // memory to clear before the next build writes to it: freshly allocated slabs and rows taken from the free list.
     // The build enqueues the fills inside its timed region (skipped tokens rely on the zeros).
@@ -417,7 +424,12 @@ struct PoolImpl {
     }
     void forget(uint32_t* row) {                                 // the row's content is void: its memory can be reused
         auto it = meta.find(row);
-        if (it != meta.end()) { rows.erase(it->second.key); meta.erase(it); }
+        if (it != meta.end()) {
+            const PlaneKey& k = it->second.key;
+            auto bs = by_structure.find({k[0], k[1], k[2], k[3]});
+            if (bs != by_structure.end() && bs->second == row) by_structure.erase(bs);
+            rows.erase(k); meta.erase(it);
+        }
         no_uncertain.erase(row);
         free_rows.push_back(row);
         --n_rows;
@@ -462,7 +474,7 @@ struct PoolImpl {
 // ---- mask cache -----------------------------------------------------------------------------------------
 struct PlaneInfo {
     int32_t rule, state, parent_rule, parent_state;         // the representative it is built for
-    uint32_t* row;                                          // accepted row (uncertain at + W words); null until built
+    uint32_t* row;                                          // accepted row (uncertain at + W words, left early at + 2 W); null until built
     bool no_uncertain;
     PlaneKey key;                                           // identity in the pool
     uint32_t sid; int64_t waiter_sid;                       // start of the build: position, and the waiting parent state or -1
@@ -480,6 +492,7 @@ struct CacheImpl {
     std::vector<int32_t> fresh_planes;
     std::shared_ptr<BuildTicket> compile_ticket;
     bool failed = false;
+    bool partial_hits = true;                               // derive planes from planes of the same structure under another follow language
     std::vector<std::shared_ptr<BuildTicket>> jit_tickets;  // builds issued by fill calls whose device time has not been added up yet
     double host_lower_ms = 0;                               // EBNF -> tables and plan, of the compile call
     int64_t compile_built = 0;
@@ -696,9 +709,12 @@ void finalize_ticket(BuildTicket& T) {
         }
         const uint32_t n_acc = S.res[2 + 2 * k], n_unc = S.res[3 + 2 * k];
         if (n_unc == 0) pool.no_uncertain.insert(T.rows[k]);
+        if (T.keys[k][4] != 0) pool.by_structure.emplace(std::array<int64_t, 4>{T.keys[k][0], T.keys[k][1], T.keys[k][2], T.keys[k][3]}, T.rows[k]);
         T.n_accepted += n_acc; T.n_uncertain += n_unc;
     }
     T.state = failed ? 2 : 1;
+    for (uint32_t* b : T.borrowed) pool.release(b);
+    T.borrowed.clear();
     for (auto it = pool.pending.begin(); it != pool.pending.end(); ++it) if (it->get() == &T) { pool.pending.erase(it); break; }
     {
         std::lock_guard<std::mutex> ck(build_chain().mu);
@@ -746,7 +762,7 @@ int32_t build_planes(CacheImpl& cache, const std::vector<int32_t>& todo, hipStre
     PoolImpl& pool = *cache.pool;
     VocabImpl& V = *cache.vocab;
     const FlatTables& ft = cache.gram->ft;
-    const size_t row_bytes = (size_t)V.W * 2 * sizeof(uint32_t);
+    const size_t row_bytes = (size_t)V.W * 3 * sizeof(uint32_t);       // accepted, uncertain, left early
     std::vector<int32_t> build;                                 // plane indices to class now
     std::vector<uint32_t*> build_rows;
     // Until the planes are known to be built, the pool must not offer their rows to anyone: whatever goes wrong
@@ -766,6 +782,10 @@ int32_t build_planes(CacheImpl& cache, const std::vector<int32_t>& todo, hipStre
             }
         }
     } rollback{pool, cache, build, build_rows, stream};
+    struct ReleaseBorrowed {                                     // rows borrowed for a partial hit go back if the build is not enqueued
+        PoolImpl& pool; std::vector<uint32_t*>* rows = nullptr; bool armed = true;
+        ~ReleaseBorrowed() { if (armed && rows) for (uint32_t* r : *rows) pool.release(r); }
+    } release_borrowed{pool};
     for (size_t i = 0; i < todo.size(); ++i) {
         const int32_t k = todo[i];
         PlaneInfo& pi = cache.planes[(size_t)k];
@@ -799,17 +819,34 @@ int32_t build_planes(CacheImpl& cache, const std::vector<int32_t>& todo, hipStre
     // plan: closed start set and live first-byte ranges of every plane to build
     std::vector<uint32_t> ctx_items, ctx_wait, ctx_wait_off;
     std::vector<uint4> plane_ctx, ranges;
-    std::vector<CopyJob> copies;
+    std::vector<CopyJob> copies, structure_copies;
     std::vector<FirstByteCopyJob> fb_copies;
+    std::vector<uint64_t> derive_base(build.size(), 0);          // partial hits: address of the base plane's left-early row
+    std::vector<uint32_t*> borrowed;
+    release_borrowed.rows = &borrowed;
     int64_t executed = 0, executed_bytes = 0;
     EarleyChart chart(&ft);
     std::map<int32_t, size_t> building;                         // plane index -> position in build
     for (size_t k = 0; k < build.size(); ++k) building.emplace(build[k], k);
     for (size_t k = 0; k < build.size(); ++k) {
         const PlaneInfo& pi = cache.planes[(size_t)build[k]];
+        // Partial cache hit (section 3.3): the pool holds a plane of the same structure built under another follow language.
+        // Accepted tokens, and the tokens that leave the rule early and die, are the same; only which of the latter stay
+        // uncertain depends on what may follow: those are run again, in follow mode, and nothing else is.
+        if (cache.follow && cache.partial_hits && pi.key[4] != 0) {
+            auto bs = pool.by_structure.find({pi.key[0], pi.key[1], pi.key[2], pi.key[3]});
+            if (bs != pool.by_structure.end() && bs->second != build_rows[k]) {
+                uint32_t* base = bs->second;
+                pool.take(base, pi.key);                         // not to be evicted while this build reads it
+                borrowed.push_back(base);
+                structure_copies.push_back({build_rows[k], base, nullptr, 0});
+                derive_base[k] = (uint64_t)(uintptr_t)(base + 2 * (size_t)V.W);
+            }
+        }
+        const bool derived = derive_base[k] != 0;
         // short tokens from a plane that agrees on them, if that plane is there or is being built in this call
         uint32_t near_d = 0;
-        if (pi.near_plane >= 0 && pi.near_depth >= 1 && V.near_depths >= 1) {
+        if (!derived && pi.near_plane >= 0 && pi.near_depth >= 1 && V.near_depths >= 1) {
             const uint32_t* src = cache.planes[(size_t)pi.near_plane].row;
             if (!src) {
                 auto pr = pool.rows.find(cache.planes[(size_t)pi.near_plane].key);
@@ -824,7 +861,7 @@ int32_t build_planes(CacheImpl& cache, const std::vector<int32_t>& todo, hipStre
         }
         // or the tokens with most first bytes from the plane of the rule's start state, under the same conditions
         bool by_first_byte = false;
-        if (!near_d && pi.fb_plane >= 0) {
+        if (!derived && !near_d && pi.fb_plane >= 0) {
             const uint32_t* src = cache.planes[(size_t)pi.fb_plane].row;
             if (!src) {
                 auto pr = pool.rows.find(cache.planes[(size_t)pi.fb_plane].key);
@@ -841,7 +878,7 @@ int32_t build_planes(CacheImpl& cache, const std::vector<int32_t>& todo, hipStre
         }
         // or every token that cannot leave the plain states of the rule from the plane of the same state under another site
         const VocabImpl::ByteSetList* by_list = nullptr;
-        if (!near_d && !by_first_byte && pi.site_plane >= 0) {
+        if (!derived && !near_d && !by_first_byte && pi.site_plane >= 0) {
             const uint32_t* src = cache.planes[(size_t)pi.site_plane].row;
             if (!src) {
                 auto pr = pool.rows.find(cache.planes[(size_t)pi.site_plane].key);
@@ -907,6 +944,10 @@ int32_t build_planes(CacheImpl& cache, const std::vector<int32_t>& todo, hipStre
                 threads = kChunkThreads;
             }
         }
+        if (derived) {
+            ranges.push_back(make_uint4((uint32_t)k, 0u, V.W, kChunkDerive | kChunkHeavy));
+            continue;
+        }
         if (by_first_byte) for (int b = 0; b < 256; ++b) if ((pi.fb_same[(size_t)b >> 5] >> (b & 31)) & 1u) live[b] = false;
         for (int b = 0; b < 256;) {
             if (!live[b]) { ++b; continue; }
@@ -935,10 +976,12 @@ int32_t build_planes(CacheImpl& cache, const std::vector<int32_t>& todo, hipStre
     for (uint32_t pass_heavy : {kChunkHeavy, 0u})
         for (const uint4& r : ranges) {
             if ((r.w & kChunkHeavy) != pass_heavy) continue;
-            const uint32_t step = pass_heavy ? kHeavyChunk : kBuildChunk;
+            const bool derive = r.w & kChunkDerive;
+            const uint32_t step = derive ? kDeriveChunk : pass_heavy ? kHeavyChunk : kBuildChunk;
             const uint4& pc = plane_ctx[r.x];
-            const uint64_t row = (uint64_t)(uintptr_t)build_rows[r.x];
-            const uint4 second = make_uint4(ctx_items[pc.x], pc.y, (uint32_t)row, (uint32_t)(row >> 32));
+            const uint64_t row = derive ? derive_base[r.x] : (uint64_t)(uintptr_t)build_rows[r.x];
+            const uint4 second = derive ? make_uint4(0u, 0u, (uint32_t)row, (uint32_t)(row >> 32))
+                                        : make_uint4(ctx_items[pc.x], pc.y, (uint32_t)row, (uint32_t)(row >> 32));
             for (uint32_t lo = r.y; lo < r.z; lo += 32 * step) {
                 const uint32_t hi = std::min(r.z, lo + 32 * step);
                 range_a.push_back(make_uint4(r.x, lo, hi, r.w));
@@ -959,7 +1002,7 @@ int32_t build_planes(CacheImpl& cache, const std::vector<int32_t>& todo, hipStre
         o_trans = tab.add(ft.trans); o_cls = tab.add(ft.byte_class_words);
     }
     const size_t o_range_a = tab.add(range_a), o_range_b = tab.add(range_b), o_range_first = tab.add(range_first), o_pctx = tab.add(plane_ctx), o_items = tab.add(ctx_items), o_wait = tab.add(ctx_wait),
-                 o_wait_off = tab.add(ctx_wait_off), o_rows = tab.add(build_rows), o_copies = tab.add(copies), o_fb_copies = tab.add(fb_copies), o_zero = tab.add(zeros);
+                 o_wait_off = tab.add(ctx_wait_off), o_rows = tab.add(build_rows), o_copies = tab.add(copies), o_structure_copies = tab.add(structure_copies), o_fb_copies = tab.add(fb_copies), o_zero = tab.add(zeros);
     const size_t o_chunks = tab.reserve(n_chunks * 2 * sizeof(uint4));
     tab.stage(with_tables, SS);
     if (with_tables) cache.d_tables = tab.dev;                     // the cache owns the block from here on
@@ -1003,6 +1046,7 @@ int32_t build_planes(CacheImpl& cache, const std::vector<int32_t>& todo, hipStre
     if (!build.empty()) launch_build(cache.dt, V.dv, P, S, stream);
     HIP_CHECK(hipEventRecord(evk1, stream));
     if (!build.empty()) launch_build_slow(cache.dt, V.dv, P, S, stream);
+    launch_copy_structure(tab.at<const CopyJob>(o_structure_copies), (uint32_t)structure_copies.size(), V.W, stream);
     launch_copy_masked(tab.at<const CopyJob>(o_copies), (uint32_t)copies.size(), V.W, stream);
     launch_copy_first_byte(tab.at<const FirstByteCopyJob>(o_fb_copies), (uint32_t)fb_copies.size(), V.d_first_byte.p, V.W, stream);
     HIP_CHECK(hipEventRecord(ev1, stream));                              // every plane is written
@@ -1014,6 +1058,9 @@ int32_t build_planes(CacheImpl& cache, const std::vector<int32_t>& todo, hipStre
     // from here on the build is under way: the planes have their rows, the ticket says what became of them
     rollback.armed = false;
     ticket->rows = build_rows;
+    ticket->borrowed = borrowed;
+    release_borrowed.armed = false;
+    ticket->partial_hits = (int64_t)structure_copies.size();
     ticket->executed = executed; ticket->executed_bytes = executed_bytes;
     for (size_t k = 0; k < build.size(); ++k) {
         PlaneInfo& pi = cache.planes[(size_t)build[k]];
@@ -1269,12 +1316,14 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
         const bool merge = opts ? opts->merge_equivalent != 0 : true;
         const bool follow = opts ? opts->follow_filter != 0 : true;
         const int32_t jit = (opts && opts->jit) ? std::max(opts->jit_prebuild, 0) : -1;   // -1: build every plane now
+        const bool partial = opts ? opts->partial_hits != 0 : true;
         if (depth != 1 && depth != 2) return fail(XG2_EINVAL, "xg2_compile_grammar: context_depth must be 1 or 2");
         hipStream_t stream = (hipStream_t)hip_stream;
         auto t0 = std::chrono::steady_clock::now();
         auto cache = std::make_shared<CacheImpl>();
         cache->vocab = vocab->p;
         cache->context_depth = depth;
+        cache->partial_hits = partial;
         cache->gram = make_grammar(ebnf, len, root_rule);
         const Grammar& g = cache->gram->g;
         const FlatTables& ft = cache->gram->ft;
@@ -1362,7 +1411,16 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
         }
         FollowInfo follow_info;
         const int32_t budget = (int32_t)std::max<uint32_t>(V.max_len, 1);
-        if (follow) follow_info = follow_signatures(g, budget, &classes);
+        // follow signatures are numbers the pool hands out for exact descriptions of the bounded follow language (rules named
+        // by their pool entries): equal numbers, equal structures
+        const FollowInterner intern_follow = [&pool](const std::vector<uint64_t>& desc) -> uint64_t {
+            auto it = pool.follow_nodes.find(desc);
+            if (it != pool.follow_nodes.end()) return it->second;
+            const uint64_t id = ((uint64_t)pool.follow_nodes.size() + 1) << 1;      // even: the key sets bit 0, and 0 stays "unfiltered"
+            pool.follow_nodes.emplace(desc, id);
+            return id;
+        };
+        if (follow) follow_info = follow_signatures(g, budget, &classes, &ref_id, &intern_follow);
         // reference sites of every rule, one representative per class of the state the referencing rule continues in
         struct Site { int32_t q, waiter, x; };
         std::vector<std::vector<Site>> sites((size_t)R);            // all sites
@@ -1569,7 +1627,8 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
             stats->positions = (int64_t)g.positions.size();
             stats->unique = (int64_t)cache->planes.size();
             stats->built = cache->compile_built;
-            stats->checks = cache->compile_built * (int64_t)V.n_sorted;
+            stats->partial_hits = ticket ? ticket->partial_hits : 0;
+            stats->checks = (cache->compile_built - stats->partial_hits) * (int64_t)V.n_sorted;
             stats->executed_checks = ticket ? ticket->executed : 0;
             stats->executed_token_bytes = ticket ? ticket->executed_bytes : 0;
             stats->host_lower_ms = cache->host_lower_ms;
@@ -1592,7 +1651,8 @@ int32_t xg2_mask_cache_stats(xg2_mask_cache* c, xg2_compile_stats* stats) {
         stats->positions = (int64_t)C.gram->g.positions.size();
         stats->unique = (int64_t)C.planes.size();
         stats->built = C.compile_built;
-        stats->checks = C.compile_built * (int64_t)C.vocab->n_sorted;
+        stats->partial_hits = t ? t->partial_hits : 0;
+        stats->checks = (C.compile_built - stats->partial_hits) * (int64_t)C.vocab->n_sorted;
         stats->host_lower_ms = C.host_lower_ms;
         if (t) {
             stats->executed_checks = t->executed; stats->executed_token_bytes = t->executed_bytes;

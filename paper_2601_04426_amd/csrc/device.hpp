@@ -56,7 +56,7 @@ struct BuildPlan {
     const uint4* chunk; uint32_t n_chunks;                      // 2 * n_chunks uint4
     const uint4* plane_ctx;                                     // [n_planes]
     const uint32_t* ctx_items; const uint2* ctx_wait; const uint32_t* ctx_wait_off;
-    uint32_t* const* plane_ptr;                                 // [n_planes] accepted row; uncertain row at + W words
+    uint32_t* const* plane_ptr;                                 // [n_planes] accepted row; uncertain row at + W words, left-early row at + 2 W
     uint32_t follow_filter;                                     // drop uncertain tokens that no reference site can continue
     uint32_t large_lists, list_k, list_wm;                      // set by launch_build: long or short item lists; item and wait-entry capacity a lane
 };
@@ -77,13 +77,17 @@ constexpr uint32_t kSlowK = 256, kSlowWM = 1024, kSlowMaxLen = 1024;
 constexpr uint32_t kSlowSearchBudget = 1u << 20;     // list entries one token may compare against in the device-memory lists
 constexpr uint32_t kSlowSlots = 2 * kSlowK + 2 * kSlowWM + kSlowMaxLen + 1;
 
-constexpr uint32_t kChunkListed = 1u, kChunkHeavy = 2u, kChunkThreads = 4u;   // bits of chunk[c].w
+constexpr uint32_t kChunkListed = 1u, kChunkHeavy = 2u, kChunkThreads = 4u, kChunkDerive = 8u;   // bits of chunk[c].w
+constexpr uint32_t kDeriveChunk = 64;                        // mask words of a derive chunk: y and z are word indices there, and the second
+                                                             // half of the record holds the address of the base plane's third row
 constexpr uint32_t kNoThread = 0xFFFFFFFFu;                  // an empty slot of the thread walk (what the transition table holds for "no edge")
 
-// dst gets, for the tokens in mask (token ids, W words), the bits src holds: both rows of a plane at once
-// (accepted at [0, W), uncertain at [W, 2 W)).  The mask bits of dst must be clear before.
+// dst gets, for the tokens in mask (token ids, W words), the bits src holds: all three rows of a plane at once
+// (accepted at [0, W), uncertain at [W, 2 W), left early at [2 W, 3 W)).  The mask bits of dst must be clear before.
 struct CopyJob { uint32_t* dst; const uint32_t* src; const uint32_t* mask; uint64_t pad; };
 void launch_copy_masked(const CopyJob* jobs_dev, uint32_t n_jobs, uint32_t W, hipStream_t stream);
+// dst gets src's accepted row and left-early row whole (mask unused): what a plane derived from another one shares with it.
+void launch_copy_structure(const CopyJob* jobs_dev, uint32_t n_jobs, uint32_t W, hipStream_t stream);
 // The same with the mask given by first bytes: dst gets the bits src holds for the tokens whose first byte is in the
 // set `bytes` (256 bits).  first_byte_dev: first byte of every token id, padded to W * 32 entries.
 struct FirstByteCopyJob { uint32_t* dst; const uint32_t* src; uint32_t bytes[8]; };

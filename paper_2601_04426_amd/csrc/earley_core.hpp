@@ -25,7 +25,7 @@ constexpr uint32_t REF_BITS = 21;
 constexpr uint32_t ROOT_ORIGIN = (1u << (32 - REF_BITS)) - 1;
 constexpr uint32_t NO_TARGET = 0xFFFFFFFFu;          // "none" marker in registers; the tables mark a missing edge by DevTables::sink
 
-constexpr int RES_ALIVE = 1, RES_EARLY = 2, RES_OVERFLOW = 4;
+constexpr int RES_ALIVE = 1, RES_EARLY = 2, RES_OVERFLOW = 4, RES_LEFT_EARLY = 8 /* set by callers: left the outermost rule early, then died */;
 
 struct DevCtx {                      // closed item set to continue from, plus what older sets wait for
     const uint32_t* items; uint32_t n_items;

@@ -1254,8 +1254,19 @@ std::vector<int32_t> bounded_classes_rule(const Grammar& g, int32_t rule, int32_
     return rep_r;
 }
 
-FollowInfo follow_signatures(const Grammar& g, int32_t budget, const std::vector<std::vector<int32_t>>* rep) {
+FollowInfo follow_signatures(const Grammar& g, int32_t budget, const std::vector<std::vector<int32_t>>* rep,
+                             const std::vector<uint64_t>* ref_identity, const FollowInterner* intern) {
     const int R = (int)g.rules.size();
+    // A node of the unfolding is described by a list of words (constants, byte ranges, the values of its children).
+    // Without an interner its value is the hash of the list; with one it is the interner's number for exactly this
+    // list, so that equal values mean equal structures as long as the children's values do.
+    auto value_of = [&](std::vector<uint64_t>& desc) -> uint64_t {
+        if (intern) return (*intern)(desc);
+        uint64_t h = desc.empty() ? 0 : desc[0];
+        for (size_t k = 1; k < desc.size(); ++k) h = hash_combine(h, desc[k]);
+        return h;
+    };
+    auto rule_identity = [&](int rule) -> uint64_t { return ref_identity ? (*ref_identity)[(size_t)rule] : g.rules[(size_t)rule].hash; };
     const int32_t INF = 1 << 28;
     // shortest completion of every state, in bytes
     std::vector<std::vector<int32_t>> min_suf((size_t)R);
@@ -1304,30 +1315,33 @@ FollowInfo follow_signatures(const Grammar& g, int32_t budget, const std::vector
         if (unfold_have[(size_t)d][sid]) return unfold_memo[(size_t)d][sid];
         const RuleFsm& f = g.rules[(size_t)r];
         uint64_t h;
+        std::vector<uint64_t> desc;
         if (cyclic[sid]) {
-            h = hash_combine(0xC1C1ull, g_unshareable_salt.fetch_add(1));
+            desc = {0xC1C1ull, g_unshareable_salt.fetch_add(1)};
+            h = value_of(desc);
         } else {
-            h = hash_combine(0x51ull, f.is_final[(size_t)x]);
+            desc = {0x51ull, (uint64_t)f.is_final[(size_t)x]};
             {   // maximal runs of consecutive bytes with the same unfolding (edges are sorted and disjoint)
                 int run_lo = -1, run_hi = -1; uint64_t run_h = 0;
                 for (auto& e : f.bedges[(size_t)x]) {
                     const uint64_t u = unfold(d - 1, r, e.tgt);
                     if (run_lo >= 0 && (int)e.lo == run_hi + 1 && u == run_h) { run_hi = e.hi; continue; }
-                    if (run_lo >= 0) h = hash_combine(hash_combine(hash_combine(h, (uint64_t)run_lo), (uint64_t)run_hi), run_h);
+                    if (run_lo >= 0) { desc.push_back((uint64_t)run_lo); desc.push_back((uint64_t)run_hi); desc.push_back(run_h); }
                     run_lo = e.lo; run_hi = e.hi; run_h = u;
                 }
-                if (run_lo >= 0) h = hash_combine(hash_combine(hash_combine(h, (uint64_t)run_lo), (uint64_t)run_hi), run_h);
+                if (run_lo >= 0) { desc.push_back((uint64_t)run_lo); desc.push_back((uint64_t)run_hi); desc.push_back(run_h); }
             }
             if (!f.redges[(size_t)x].empty()) {
                 std::vector<std::pair<uint64_t, uint64_t>> refs;
                 for (auto& e : f.redges[(size_t)x]) {
                     const RuleFsm& c = g.rules[(size_t)e.rule];
                     int32_t left = c.nullable ? d : d - c.min_len;
-                    refs.emplace_back(c.hash, left >= 0 ? unfold(left, r, e.tgt) : 0x7777ull);
+                    refs.emplace_back(rule_identity(e.rule), left >= 0 ? unfold(left, r, e.tgt) : 0x7777ull);
                 }
                 std::sort(refs.begin(), refs.end());
-                for (auto& p : refs) h = hash_combine(hash_combine(hash_combine(h, 0xEFull), p.first), p.second);
+                for (auto& p : refs) { desc.push_back(0xEFull << 56); desc.push_back(p.first); desc.push_back(p.second); }
             }
+            h = value_of(desc);
         }
         unfold_memo[(size_t)d][sid] = h;
         unfold_have[(size_t)d][sid] = 1;
@@ -1348,20 +1362,27 @@ FollowInfo follow_signatures(const Grammar& g, int32_t budget, const std::vector
     std::function<uint64_t(int, int)> sig = [&](int rule, int d) -> uint64_t {
         const size_t key = (size_t)rule * ((size_t)budget + 1) + (size_t)d;
         if (memo_state[key] == 2) return memo[key];
-        if (memo_state[key] == 1) return hash_combine(0xCCCCull, g_unshareable_salt.fetch_add(1));   // cycle through rule ends
+        if (memo_state[key] == 1) {                                         // cycle through rule ends
+            std::vector<uint64_t> salt{0xCCCCull, g_unshareable_salt.fetch_add(1)};
+            return value_of(salt);
+        }
         memo_state[key] = 1;
         std::vector<uint64_t> parts;
         if (rule == g.root) parts.push_back(0xE0Full);                      // the input may end here
         for (const Site& st : sites[(size_t)rule]) {
             uint64_t h = unfold(d, st.q, st.x);
             int32_t left = d - min_suf[(size_t)st.q][(size_t)st.x];
-            if (left > 0 || (left == 0 && d > 0 && min_suf[(size_t)st.q][(size_t)st.x] == 0)) h = hash_combine(h, sig(st.q, left));
+            if (left > 0 || (left == 0 && d > 0 && min_suf[(size_t)st.q][(size_t)st.x] == 0)) {
+                std::vector<uint64_t> pair{0x5173ull, h, sig(st.q, left)};
+                h = value_of(pair);
+            }
             parts.push_back(h);
         }
         std::sort(parts.begin(), parts.end());
         parts.erase(std::unique(parts.begin(), parts.end()), parts.end());
-        uint64_t h = 0xF011ull;
-        for (uint64_t p : parts) h = hash_combine(h, p);
+        std::vector<uint64_t> desc{0xF011ull};
+        desc.insert(desc.end(), parts.begin(), parts.end());
+        uint64_t h = value_of(desc);
         memo_state[key] = 2;
         memo[key] = h;
         return h;

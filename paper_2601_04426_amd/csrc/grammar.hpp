@@ -3,6 +3,7 @@
 // ranges or references to other FSMs), plus the structural hashes of Algorithm 1 / Algorithm 2.
 #pragma once
 #include <cstdint>
+#include <functional>
 #include <stdexcept>
 #include <string>
 #include <vector>
@@ -85,7 +86,13 @@ struct FollowInfo {
 };
 // rep (optional): per rule and state, a state that no string of at most `budget` bytes tells apart from it; sites are then
 // taken at these representatives, which leaves the follow language as it is and the work independent of repetition bounds.
-FollowInfo follow_signatures(const Grammar& g, int32_t budget, const std::vector<std::vector<int32_t>>* rep = nullptr);
+// ref_identity (optional): per rule, a number that identical rules share and different ones do not (the pool's entry);
+// without it the rule's structural hash stands in.  intern (optional): gives every distinct description (a list of words)
+// a number of its own, the same for the same list as long as the interner lives; the signatures are then such numbers
+// and comparing them is exact, not merely probable.
+using FollowInterner = std::function<uint64_t(const std::vector<uint64_t>&)>;
+FollowInfo follow_signatures(const Grammar& g, int32_t budget, const std::vector<std::vector<int32_t>>* rep = nullptr,
+                             const std::vector<uint64_t>* ref_identity = nullptr, const FollowInterner* intern = nullptr);
 
 // Exact serialisation of one rule in Algorithm 1's canonical order; a reference to rule r is
 // written as ref_id[r].  Two rules with equal text and equal meaning of the ids are isomorphic.

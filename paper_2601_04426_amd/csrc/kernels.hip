@@ -170,6 +170,12 @@ __device__ __forceinline__ void store_class(uint32_t* row, uint32_t W, uint32_t 
 __device__ __forceinline__ void store_class(const BuildPlan& P, uint32_t p, uint32_t W, uint32_t id, int res) {
     store_class(P.plane_ptr[p], W, id, res);
 }
+// The third row of a plane: the tokens that left the outermost rule early and then died, whatever the follow filter
+// makes of them (with the filter off this is the uncertain row again).  It is what a plane of the same structure under
+// another follow language is derived from (section 3.3: partial cache hit).
+__device__ __forceinline__ void store_left_early(uint32_t* row, uint32_t W, uint32_t id) {
+    atomicOr(row + 2 * W + (id >> 5), 1u << (id & 31));
+}
 
 // A persistent grid of single-wave workgroups: workgroup g handles chunks g, g + grid, g + 2 grid, ...
 // (sorted ranks of one plane each; the host puts the long ones first), each in phases, so that the long
@@ -262,9 +268,31 @@ __global__ __launch_bounds__(64) XG2_BUILD_ATTR void k_build(DevTables T, DevVoc
         };
         // what phase 1 does with such a token: the plain run would end dead with the early mark, so it is not made
         auto died_early = [&](bool yes, uint32_t rank) {
-            if (yes && !P.follow_filter) { store_class(row, Vd.W, Vd.perm[rank], RES_EARLY); yes = false; }
+            if (yes) {
+                const uint32_t id = Vd.perm[rank];
+                store_left_early(row, Vd.W, id);
+                if (!P.follow_filter) { store_class(row, Vd.W, id, RES_EARLY); yes = false; }
+            }
             queue_follow(yes, rank);
         };
+        if (chunk.w & kChunkDerive) {
+            // partial cache hit: the plane's accepted row comes from a plane of the same structure built under another follow
+            // language (copied by another kernel); of its tokens that left early and died -- mask words chunk.y .. chunk.z of
+            // that plane's third row, one a lane -- those that this grammar's follow language can continue are uncertain here
+            const uint32_t* base_left = reinterpret_cast<const uint32_t*>(((uint64_t)chunk_b.w << 32) | chunk_b.z);
+            const uint32_t w = chunk.y + lane;
+            uint32_t bits = w < chunk.z ? base_left[w] : 0u;
+            while (__any(bits != 0)) {
+                uint32_t rank = 0xFFFFFFFFu;
+                if (bits) {
+                    const uint32_t bit = (uint32_t)__ffs(bits) - 1;
+                    bits &= bits - 1;
+                    rank = Vd.rank[w * 32 + bit];
+                }
+                queue_follow(rank < Vd.n_sorted, rank);
+            }
+            continue;
+        }
         if (walkable) {
             n_work = 0;
             for (uint32_t rank0 = chunk.y; rank0 < chunk.z; rank0 += 64) {
@@ -384,8 +412,13 @@ __global__ __launch_bounds__(64) XG2_BUILD_ATTR void k_build(DevTables T, DevVoc
                     if (over && wide) push_overflow(S, p, rank);     // the large-capacity kernel takes it
                     else if (!over) {
                         // leaves the rule early and dies: it stays uncertain only if some context can take the rest of the token
-                        again = P.follow_filter && !(res & RES_ALIVE) && (res & RES_EARLY);
-                        if (!again) store_class(row, Vd.W, Vd.perm[rank], res);
+                        const bool left_early = !(res & RES_ALIVE) && (res & RES_EARLY);
+                        again = P.follow_filter && left_early;
+                        if (left_early || !again) {
+                            const uint32_t id = Vd.perm[rank];
+                            if (left_early) store_left_early(row, Vd.W, id);
+                            if (!again) store_class(row, Vd.W, id, res);
+                        }
                     }
                 }
                 queue_follow(again, rank);
@@ -411,11 +444,12 @@ __device__ int classify_slow(const DevTables& T, const DevVocab& Vd, const Build
     st.reset();
     MemBytes tok{Vd.bytes + off};
     int res = scan_token<S, false, MemBytes>(T, T.byte_class_words, C, tok, n, st);
-    if (P.follow_filter && !(res & (RES_ALIVE | RES_OVERFLOW)) && (res & RES_EARLY)) {
+    if (!(res & (RES_ALIVE | RES_OVERFLOW)) && (res & RES_EARLY)) res |= RES_LEFT_EARLY;
+    if (P.follow_filter && (res & RES_LEFT_EARLY)) {
         st.reset();
         int res2 = scan_token<S, true, MemBytes>(T, T.byte_class_words, C, tok, n, st);
         if (res2 & RES_OVERFLOW) res = RES_OVERFLOW;
-        else if (!(res2 & RES_ALIVE)) res = 0;
+        else if (!(res2 & RES_ALIVE)) res = RES_LEFT_EARLY;
     }
     return res;
 }
@@ -438,7 +472,9 @@ __global__ __launch_bounds__(64) void k_build_slow(DevTables T, DevVocab Vd, Bui
         int res = S.k_cap >= (uint32_t)MidStore::K ? classify_slow(T, Vd, P, C, off, n, mid) : RES_OVERFLOW;   // (overflows at once if the token is too long for it)
         if (res & RES_OVERFLOW) res = classify_slow(T, Vd, P, C, off, n, st);
         if (res & RES_OVERFLOW) { atomicOr(S.count + 1, 2u); continue; }
-        store_class(P, p, Vd.W, Vd.perm[rank], res);
+        const uint32_t id = Vd.perm[rank];
+        if (res & RES_LEFT_EARLY) store_left_early(P.plane_ptr[p], Vd.W, id);
+        store_class(P, p, Vd.W, id, res);
     }
 }
 
@@ -451,7 +487,7 @@ __global__ __launch_bounds__(256) void k_expand_chunks(const uint4* range_a, con
     const uint32_t r = blockIdx.x * 256 + threadIdx.x;
     if (r >= n_ranges) return;
     const uint4 a = range_a[r], b = range_b[r];
-    const uint32_t step = (a.w & kChunkHeavy) ? kHeavyChunk : kBuildChunk;
+    const uint32_t step = (a.w & kChunkDerive) ? kDeriveChunk : (a.w & kChunkHeavy) ? kHeavyChunk : kBuildChunk;
     uint4* out = chunk + 2 * (size_t)first[r];
     for (uint32_t lo = a.y; lo < a.z; lo += step, out += 2) {
         out[0] = make_uint4(a.x, lo, min(a.z, lo + step), a.w);
@@ -467,6 +503,7 @@ __global__ __launch_bounds__(256) void k_copy_masked(const CopyJob* jobs, uint32
     if (!m) return;
     j.dst[w] |= j.src[w] & m;
     j.dst[W + w] |= j.src[W + w] & m;
+    j.dst[2 * W + w] |= j.src[2 * W + w] & m;
 }
 
 __global__ __launch_bounds__(256) void k_copy_first_byte(const FirstByteCopyJob* jobs, const uint8_t* first_byte, uint32_t W) {
@@ -478,8 +515,8 @@ __global__ __launch_bounds__(256) void k_copy_first_byte(const FirstByteCopyJob*
     if (w >= W) return;
     const uint32_t* src = j->src;
     uint32_t* dst = j->dst;
-    const uint32_t a = src[w], u = src[W + w];
-    uint32_t todo = a | u, m = 0;                                   // only the tokens the source has a bit for matter
+    const uint32_t a = src[w], u = src[W + w], e = src[2 * W + w];
+    uint32_t todo = a | u | e, m = 0;                               // only the tokens the source has a bit for matter
     while (todo) {
         const uint32_t bit = __ffs(todo) - 1;
         todo &= todo - 1;
@@ -488,6 +525,16 @@ __global__ __launch_bounds__(256) void k_copy_first_byte(const FirstByteCopyJob*
     }
     if (a & m) dst[w] |= a & m;
     if (u & m) dst[W + w] |= u & m;
+    if (e & m) dst[2 * W + w] |= e & m;
+}
+
+// Partial cache hit: the accepted row and the left-early row of a plane are those of the plane it is derived from.
+__global__ __launch_bounds__(256) void k_copy_structure(const CopyJob* jobs, uint32_t W) {
+    const CopyJob j = jobs[blockIdx.y];
+    const uint32_t w = blockIdx.x * 256 + threadIdx.x;
+    if (w >= W) return;
+    j.dst[w] = j.src[w];
+    j.dst[2 * W + w] = j.src[2 * W + w];
 }
 
 __global__ __launch_bounds__(256) void k_popcount(const uint32_t* const* plane_ptr, uint32_t n_pos, uint32_t W, uint32_t* counts) {
@@ -1006,6 +1053,13 @@ void launch_copy_masked(const CopyJob* jobs_dev, uint32_t n_jobs, uint32_t W, hi
     for (uint32_t first = 0; first < n_jobs; first += 65535) {      // grid.y limit
         const uint32_t n = std::min<uint32_t>(65535, n_jobs - first);
         hipLaunchKernelGGL(k_copy_masked, dim3((W + 255) / 256, n), dim3(256), 0, stream, jobs_dev + first, W);
+    }
+}
+
+void launch_copy_structure(const CopyJob* jobs_dev, uint32_t n_jobs, uint32_t W, hipStream_t stream) {
+    for (uint32_t first = 0; first < n_jobs; first += 65535) {      // grid.y limit
+        const uint32_t n = std::min<uint32_t>(65535, n_jobs - first);
+        hipLaunchKernelGGL(k_copy_structure, dim3((W + 255) / 256, n), dim3(256), 0, stream, jobs_dev + first, W);
     }
 }
 

@@ -530,11 +530,64 @@ def test_config4_full_size_planes_of_late_grammars(xg):
     assert n_planes > 20000
 
 
+def test_partial_cache_hits_on_a_differing_follow_language(xg):
+    """Section 3.3: grammars that share rules (a number, a quoted word, whitespace) but differ in what follows them.
+    Compiled into one pool, the later grammars find planes of the same structure under another follow language: a
+    partial hit, where only the tokens that leave the rule early and die are run again.  Every plane of every grammar
+    equals the oracle's classes for that grammar alone, and equals what a full build without partial hits gives; a
+    grammar with the same follow language as an earlier one is a perfect hit."""
+    cfg, vocab, va = load(1)
+    shared = 'num ::= "-"? [0-9]{1,6} ("." [0-9]{1,3})?\nword ::= "\\"" [a-z]{0,12} "\\""\nws ::= [ \t\n]*\nitem ::= ws (num | word) ws\n'
+    grammars = ['root ::= "[" item ("," item)* "]"\n' + shared,
+                'root ::= "{" item (";" item){0,5} "}" ws\n' + shared,
+                'root ::= "(" item (":" ws item)? ")"\n' + shared,
+                'root ::= "<" "[" item ("," item)* "]" ">"\nlist ::= "[" item ("," item)* "]"\n' + shared]
+    sentences = [b'[12,"ab", -3.5]', b'{1;"x" ;22} ', b'( "a" : 7)', b'<[1 ,2.25]>']
+    pool = xg.Pool()
+    partial = built = 0
+    for gi, ebnf in enumerate(grammars):
+        cache, orc = check_planes(xg, cfg, vocab, va, ebnf, "root", pool=pool, max_contexts=100000, seed=gi)   # every plane against the oracle
+        st = cache.stats
+        partial += st.partial_hits
+        built += st.built
+        if gi == 0:
+            assert st.partial_hits == 0 and st.built == st.unique
+        else:
+            assert st.partial_hits > 0 and st.checks == (st.built - st.partial_hits) * (cfg.vocab.size - 1)
+        # the same grammar built from scratch, no partial hits: identical planes
+        alone = xg.compile_grammar(vocab, ebnf, "root", stream=_stream(), partial_hits=False)
+        assert alone.stats.partial_hits == 0 and alone.num_planes() == cache.num_planes()
+        for k in range(cache.num_planes()):
+            assert cache.plane_info(k) == alone.plane_info(k)
+            a1, u1 = cache.get_planes(k)
+            a2, u2 = alone.get_planes(k)
+            assert np.array_equal(a1, a2) and np.array_equal(u1, u2), (gi, cache.plane_info(k))
+        # decode through the pooled cache, byte by byte along a sentence of this grammar
+        import torch
+        single = {bytes([t[0]]): i for i, t in enumerate(cfg.vocab.tokens) if len(t) == 1}
+        m = xg.Matcher(cache)
+        bm = torch.zeros((1, vocab.words), dtype=torch.int32, device="cuda:0")
+        sentence = sentences[gi]
+        for i in range(len(sentence) + 1):
+            xg.fill_next_token_bitmask([m], bm.data_ptr(), vocab.words, _stream())
+            torch.cuda.synchronize()
+            want = oracle.pack_bitmask(orc.mask(sentence[:i], va))
+            assert np.array_equal(bm.cpu().numpy()[0], want), (gi, sentence[:i], diff_words(bm.cpu().numpy()[0], want, cfg.vocab.tokens))
+            if i < len(sentence):
+                assert m.accept_token(single[sentence[i:i + 1]])
+        assert m.accept_token(cfg.vocab.eos_id)
+        del alone
+    assert partial >= 10 and partial < built
+    # the first grammar once more: every plane is in the pool (perfect hits)
+    again = xg.compile_grammar(vocab, grammars[0], "root", pool=pool, stream=_stream())
+    assert again.stats.built == 0 and again.stats.partial_hits == 0
+
+
 def test_pool_gives_up_unused_planes_when_full(xg):
     """A pool bounded by max_bytes: planes of destroyed caches are evicted (least recently used first) to make room,
     rebuilt when needed again, and always equal to the oracle's; a pool whose planes are all in use reports overflow."""
     cfg, vocab, va = load(1)
-    row_bytes = 2 * vocab.words * 4
+    row_bytes = 3 * vocab.words * 4                                 # a plane: accepted, uncertain and left-early row
     grammars = ['root ::= "[" [0-9]{1,3} ("," [0-9]{1,3})* "]"\n', 'root ::= "{" ws pair ws "}"\npair ::= "\\"" [a-z]+ "\\"" ws ":" ws [0-9]+\nws ::= " "*\n',
                 'root ::= ("a" | "b" x)+\nx ::= "c" x | "d"\n', 'root ::= t ("+" t)*\nt ::= [0-9]+ | "(" root ")"\n']
     sizes = []
