@@ -398,6 +398,7 @@ def main() -> int:
             s4 = c4.stats
             tot["positions"] += s4.positions; tot["planes_used"] += s4.unique; tot["planes_built"] += s4.built
             tot["device_ms"] += s4.device_ms; tot["host_ms"] += s4.host_lower_ms; tot["executed"] += s4.executed_checks
+            tot["partial_hits"] = tot.get("partial_hits", 0) + s4.partial_hits
             keep.append(c4)
         wall4 = time.perf_counter() - t4
         out["cross_grammar"] = {"grammars": len(keep), "vocab": cfg4.vocab.size, "positions": tot["positions"], "planes_used": tot["planes_used"],
@@ -405,7 +406,7 @@ def main() -> int:
                                 "device_ms": tot["device_ms"], "host_lower_ms": tot["host_ms"], "wall_s": wall4,
                                 "checks_per_s_device": tot["planes_built"] * n_tok4 / (tot["device_ms"] * 1e-3),
                                 "checks_per_s_served_device": tot["planes_used"] * n_tok4 / (tot["device_ms"] * 1e-3),
-                                "executed_checks": tot["executed"]}
+                                "executed_checks": tot["executed"], "partial_hits": tot.get("partial_hits", 0)}
         del keep, pool4
 
     if not args.no_jit:

@@ -387,6 +387,7 @@ struct PoolImpl {
     int64_t n_evicted = 0;
     struct WordsHash { size_t operator()(const std::vector<uint64_t>& v) const { uint64_t h = 0x9E3779B97F4A7C15ull; for (uint64_t w : v) h = hash_combine(h, w); return (size_t)h; } };
     std::unordered_map<std::vector<uint64_t>, uint64_t, WordsHash> follow_nodes;    // exact interning of follow-language descriptions
+    std::unordered_map<int, std::vector<uint64_t>> follow_unfold;   // per interned rule: value of (depth, canonical state), 0 = not known yet
     std::vector<void*> slabs;
     // memory to clear before the next build writes to it: freshly allocated slabs and rows taken from the free list.
     // The build enqueues the fills inside its timed region (skipped tokens rely on the zeros).
@@ -1420,7 +1421,15 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
             pool.follow_nodes.emplace(desc, id);
             return id;
         };
-        if (follow) follow_info = follow_signatures(g, budget, &classes, &ref_id, &intern_follow);
+        const FollowMemo follow_memo = [&](int rule, int state, int d) -> uint64_t* {
+            const RuleFsm& f = g.rules[(size_t)rule];
+            if (!f.shareable) return nullptr;
+            std::vector<uint64_t>& slots = pool.follow_unfold[entry[(size_t)rule]];
+            const size_t n = (size_t)f.n_states();
+            if (slots.size() != ((size_t)budget + 1) * n) slots.assign(((size_t)budget + 1) * n, 0);
+            return &slots[(size_t)d * n + (size_t)f.canon_id[(size_t)state]];
+        };
+        if (follow) follow_info = follow_signatures(g, budget, &classes, &ref_id, &intern_follow, &follow_memo);
         // reference sites of every rule, one representative per class of the state the referencing rule continues in
         struct Site { int32_t q, waiter, x; };
         std::vector<std::vector<Site>> sites((size_t)R);            // all sites

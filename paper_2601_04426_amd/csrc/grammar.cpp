@@ -1255,7 +1255,7 @@ std::vector<int32_t> bounded_classes_rule(const Grammar& g, int32_t rule, int32_
 }
 
 FollowInfo follow_signatures(const Grammar& g, int32_t budget, const std::vector<std::vector<int32_t>>* rep,
-                             const std::vector<uint64_t>* ref_identity, const FollowInterner* intern) {
+                             const std::vector<uint64_t>* ref_identity, const FollowInterner* intern, const FollowMemo* memo_of) {
     const int R = (int)g.rules.size();
     // A node of the unfolding is described by a list of words (constants, byte ranges, the values of its children).
     // Without an interner its value is the hash of the list; with one it is the interner's number for exactly this
@@ -1314,6 +1314,14 @@ FollowInfo follow_signatures(const Grammar& g, int32_t budget, const std::vector
         const size_t sid = (size_t)g.sid(r, x);
         if (unfold_have[(size_t)d][sid]) return unfold_memo[(size_t)d][sid];
         const RuleFsm& f = g.rules[(size_t)r];
+        // the unfolding of a state depends on its rule and the rules that one references, not on the grammar around it:
+        // an identical rule met before (in this grammar or an earlier one of the pool) has it ready
+        uint64_t* kept = memo_of ? (*memo_of)(r, x, d) : nullptr;
+        if (kept && *kept) {
+            unfold_memo[(size_t)d][sid] = *kept;
+            unfold_have[(size_t)d][sid] = 1;
+            return *kept;
+        }
         uint64_t h;
         std::vector<uint64_t> desc;
         if (cyclic[sid]) {
@@ -1345,6 +1353,7 @@ FollowInfo follow_signatures(const Grammar& g, int32_t budget, const std::vector
         }
         unfold_memo[(size_t)d][sid] = h;
         unfold_have[(size_t)d][sid] = 1;
+        if (kept) *kept = h;
         return h;
     };
     // reference sites of every rule

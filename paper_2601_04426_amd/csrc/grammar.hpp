@@ -91,8 +91,12 @@ struct FollowInfo {
 // a number of its own, the same for the same list as long as the interner lives; the signatures are then such numbers
 // and comparing them is exact, not merely probable.
 using FollowInterner = std::function<uint64_t(const std::vector<uint64_t>&)>;
+// memo_of (optional, with an interner): where the value of (rule, state, depth) is kept across calls, or null for rules
+// that are not shared; a slot holding 0 is empty.
+using FollowMemo = std::function<uint64_t*(int rule, int state, int depth)>;
 FollowInfo follow_signatures(const Grammar& g, int32_t budget, const std::vector<std::vector<int32_t>>* rep = nullptr,
-                             const std::vector<uint64_t>* ref_identity = nullptr, const FollowInterner* intern = nullptr);
+                             const std::vector<uint64_t>* ref_identity = nullptr, const FollowInterner* intern = nullptr,
+                             const FollowMemo* memo_of = nullptr);
 
 // Exact serialisation of one rule in Algorithm 1's canonical order; a reference to rule r is
 // written as ref_id[r].  Two rules with equal text and equal meaning of the ids are isomorphic.
