@@ -230,6 +230,76 @@ def test_follow_filtered_classes_match_enumeration(name, ebnf, rules, alphabet, 
         assert n_moved > 0                     # the filter does reject something on these grammars
 
 
+def _reach_languages(o, rules, N):
+    """{(rule, state): the enumerated strings that take the rule's automaton from its start state to the state}, every
+    rule symbol on the way replaced by that rule's enumerated sentences."""
+    index = o.low.index
+    L = languages(rules, N)
+    out = {}
+    for rule in o.low.reachable:
+        d = o.low.dfa[rule]
+        sym_lang = languages({"r": _placeholder(rules[rule], index)}, N)["r"]
+        reach = {q: set() for q in range(d.n)}
+        seen = set()
+        for s in sym_lang:
+            for k in range(len(s) + 1):
+                w = s[:k]
+                if w in seen:
+                    continue
+                seen.add(w)
+                q = d.start
+                cur = {b""}
+                for c in w:
+                    if c >= 0xF0:
+                        q = d.redges[q][c - 0xF0]
+                        nxt = L[o.order[c - 0xF0]]
+                    else:
+                        q = next(t for m, t in d.bedges[q] if (m >> c) & 1)
+                        nxt = {bytes([c])}
+                    cur = {x + y for x in cur for y in nxt if len(x) + len(y) <= N}
+                reach[q] |= cur
+        for q in range(d.n):
+            out[(rule, q)] = reach[q]
+    return out
+
+
+@pytest.mark.parametrize("name,ebnf,rules,alphabet,N", TINY, ids=[t[0] for t in TINY])
+def test_frontier_matches_enumeration(name, ebnf, rules, alphabet, N):
+    """The scannable frontier after a history h, by its definition: position (R, q) belongs to it iff q has a byte edge
+    and h = u.v where an instance of R can start after u (u is a left context of R: the empty string for the root rule,
+    else a left context of a referencing rule followed by a string that takes that rule to the referencing state) and v
+    takes R from its start state to q.  The grammars are reduced, so every such partial parse can be completed.  A
+    spurious position, or a missing one, in Oracle.frontier fails this."""
+    o = oracle.Oracle(ebnf)
+    reach = _reach_languages(o, rules, N)
+    H = 4 if len(alphabet) <= 3 else 3
+    ctx = {r: set() for r in o.low.reachable}
+    ctx[o.root].add(b"")
+    while True:
+        grew = False
+        for q_rule in o.low.reachable:
+            d = o.low.dfa[q_rule]
+            for q in range(d.n):
+                for r, x in d.redges[q].items():
+                    add = {u + v for u in ctx[q_rule] for v in reach[(q_rule, q)] if len(u) + len(v) <= H}
+                    if not add <= ctx[o.order[r]]:
+                        ctx[o.order[r]] |= add
+                        grew = True
+        if not grew:
+            break
+    P = prefixes(languages(rules, N)["root"])
+    n = 0
+    for h in all_strings(alphabet, H):
+        if h not in P:
+            continue
+        want = sorted((rule, q) for rule in o.low.reachable for q in range(o.low.dfa[rule].n)
+                      if o.low.dfa[rule].bedges[q]
+                      and any(h[:k] in ctx[rule] and h[k:] in reach[(rule, q)] for k in range(len(h) + 1)))
+        assert o.frontier(h) == want, (h, o.frontier(h), want)
+        n += 1
+    assert n >= 5
+
+
 def test_number_grammar_equals_python_regex():
     """A grammar without rule references is a regular expression: compare with `re`."""
     o = oracle.Oracle('root ::= "-"? ("0" | [1-9] [0-9]*) ("." [0-9]+)? ([eE] [+\\-]? [0-9]+)?\n')
