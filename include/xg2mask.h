@@ -218,7 +218,7 @@ int32_t xg2_fill_next_token_bitmask(xg2_matcher* const* matchers, int32_t B, int
  * builds, and therefore allocates, inside xg2_fill_next_token_bitmask only).  All calls on one GPU share the one array,
  * which keeps the previous call's contents (what must start at zero is cleared by the call itself): calls whose device work
  * overlaps on one GPU race, so keep them on one stream or order them with events.  Arguments, bitmask layout and errors are
- * otherwise those of xg2_fill_next_token_bitmask; xg2_fill_last_status and xg2_fill_last_recheck_words work after it (they
+ * otherwise those of xg2_fill_next_token_bitmask; xg2_fill_last_status and xg2_fill_last_recheck_tokens work after it (they
  * wait for the stream), xg2_fill_last_device_us does not (no events are recorded).                                          */
 int32_t xg2_fill_next_token_bitmask_noalloc(xg2_matcher* const* matchers, int32_t B, int32_t* bitmask_dev,
                                             int64_t row_stride_words, void* hip_stream);
@@ -249,10 +249,10 @@ int32_t xg2_fill_resolve_overflow(xg2_matcher* const* matchers, int32_t B, int32
 int32_t xg2_debug_set_large_capacity(int32_t items, int32_t wait_entries);
 
 /* Measurement and test aid: for each row of the latest fill call of this process (waits for its device work), the
- * number of mask words that held at least one candidate, i.e. a token that is uncertain somewhere in the row's
- * frontier and accepted nowhere in it, and therefore went through the full-context re-check (section 3.4, runtime
- * part).  words_host: host array; at most cap entries are written; *n_rows (nullable) receives the batch size.   */
-int32_t xg2_fill_last_recheck_words(int32_t* words_host, int32_t cap, int32_t* n_rows);
+ * number of candidate tokens, i.e. tokens that are uncertain in a plane of the row's frontier and therefore went through
+ * the full-context re-check (section 3.4, runtime part).  tokens_host: host array; at most cap entries are written;
+ * *n_rows (nullable) receives the batch size.                                                                        */
+int32_t xg2_fill_last_recheck_tokens(int32_t* tokens_host, int32_t cap, int32_t* n_rows);
 
 /* ---- matchers that live on the device (section 3.4 and the appendix on Earley parsing: the parser that traces the
  * output, one per sequence) ------------------------------------------------------------------------------------------

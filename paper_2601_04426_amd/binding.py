@@ -26,7 +26,7 @@ EXPORTS = [
     "xg2_mask_cache_plane_info", "xg2_mask_cache_find_plane", "xg2_mask_cache_get_planes", "xg2_matcher_create", "xg2_matcher_create_host", "xg2_matcher_destroy",
     "xg2_matcher_accept_token", "xg2_matcher_accept_tokens", "xg2_matcher_reset", "xg2_matcher_is_terminated", "xg2_matcher_frontier",
     "xg2_fill_next_token_bitmask", "xg2_fill_next_token_bitmask_noalloc", "xg2_fill_resolve_overflow", "xg2_debug_set_large_capacity",
-    "xg2_fill_last_device_us", "xg2_fill_last_status", "xg2_fill_last_recheck_words",
+    "xg2_fill_last_device_us", "xg2_fill_last_status", "xg2_fill_last_recheck_tokens",
     "xg2_apply_token_bitmask", "xg2_batch_create", "xg2_batch_destroy", "xg2_batch_assign", "xg2_batch_accept_tokens",
     "xg2_batch_fill_next_token_bitmask", "xg2_batch_row_info",
 ]
@@ -102,7 +102,7 @@ def _load() -> ctypes.CDLL:
     L.xg2_debug_set_large_capacity.argtypes = [i32, i32]
     L.xg2_fill_last_device_us.argtypes = [ctypes.POINTER(ctypes.c_float)]
     L.xg2_fill_last_status.argtypes = [ctypes.POINTER(i32), ctypes.POINTER(i32)]
-    L.xg2_fill_last_recheck_words.argtypes = [vp, i32, ctypes.POINTER(i32)]
+    L.xg2_fill_last_recheck_tokens.argtypes = [vp, i32, ctypes.POINTER(i32)]
     L.xg2_apply_token_bitmask.argtypes = [vp, i32, i32, i32, i64, vp, i64, vp]
     L.xg2_batch_create.argtypes = [vp, i32, pvp]
     L.xg2_batch_destroy.argtypes = [vp]
@@ -387,11 +387,11 @@ def fill_last_status() -> Tuple[int, bool]:
     return n.value, bool(over.value)
 
 
-def fill_last_recheck_words(batch: int) -> np.ndarray:
-    """Per row of the latest fill: how many mask words held a candidate for the full-context re-check."""
+def fill_last_recheck_tokens(batch: int) -> np.ndarray:
+    """Per row of the latest fill: how many candidate tokens went through the full-context re-check."""
     out = np.zeros(batch, dtype=np.int32)
     n = ctypes.c_int32(0)
-    _check(lib.xg2_fill_last_recheck_words(out.ctypes.data, batch, ctypes.byref(n)))
+    _check(lib.xg2_fill_last_recheck_tokens(out.ctypes.data, batch, ctypes.byref(n)))
     return out[:min(batch, n.value)]
 
 

@@ -102,12 +102,12 @@ __device__ int accept_token(const CacheDev& Cd, const uint32_t* cls_words, const
         };
         if (o == ROOT_ORIGIN || Cd.context_depth == 1) {
             // the root instance: leaving the rule leaves the grammar, so its uncertain tokens are never allowed
-            const uint64_t row = Cd.plain_row[sid];
+            const uint64_t row = tab(Cd.plain_row + sid);
             if (!row) return ACC_NO_PLANE;
             if (!add_plane(o == ROOT_ORIGIN ? (row | 1u) : row)) return ACC_OVERFLOW;
             continue;
         }
-        const uint32_t rule = T.state[sid].x;
+        const uint32_t rule = tab(&T.state[sid].x);
         uint32_t lo, hi;
         wait_range(o, lo, hi);
         bool any = false;
@@ -117,13 +117,14 @@ __device__ int accept_token(const CacheDev& Cd, const uint32_t* cls_words, const
             if (wr != rule) continue;
             const uint32_t key = wt & SID_MASK;
             // the state's planes are sorted by site (a state inside a long repetition is referenced from thousands of states)
-            uint32_t lo_j = Cd.pair_off[sid], hi_j = Cd.pair_off[sid + 1];
+            const uint32_t end_j = tab(Cd.pair_off + sid + 1);
+            uint32_t lo_j = tab(Cd.pair_off + sid), hi_j = end_j;
             while (lo_j < hi_j) {
                 const uint32_t mid = (lo_j + hi_j) >> 1;
-                if (Cd.pair_key[mid] < key) lo_j = mid + 1; else hi_j = mid;
+                if (tab(Cd.pair_key + mid) < key) lo_j = mid + 1; else hi_j = mid;
             }
-            if (lo_j >= Cd.pair_off[sid + 1] || Cd.pair_key[lo_j] != key) return ACC_NO_PLANE;
-            const uint64_t row = Cd.pair_row[lo_j];
+            if (lo_j >= end_j || tab(Cd.pair_key + lo_j) != key) return ACC_NO_PLANE;
+            const uint64_t row = tab(Cd.pair_row + lo_j);
             if (!row) return ACC_NO_PLANE;
             if (!add_plane(row)) return ACC_OVERFLOW;
             any = true;

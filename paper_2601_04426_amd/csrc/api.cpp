@@ -763,7 +763,7 @@ int32_t build_planes(CacheImpl& cache, const std::vector<int32_t>& todo, hipStre
     PoolImpl& pool = *cache.pool;
     VocabImpl& V = *cache.vocab;
     const FlatTables& ft = cache.gram->ft;
-    const size_t row_bytes = (size_t)V.W * 3 * sizeof(uint32_t);       // accepted, uncertain, left early
+    const size_t row_bytes = plane_words(V.W) * sizeof(uint32_t);      // accepted, uncertain, left early, list of uncertain tokens
     std::vector<int32_t> build;                                 // plane indices to class now
     std::vector<uint32_t*> build_rows;
     // Until the planes are known to be built, the pool must not offer their rows to anyone: whatever goes wrong
@@ -1051,7 +1051,7 @@ int32_t build_planes(CacheImpl& cache, const std::vector<int32_t>& todo, hipStre
     launch_copy_masked(tab.at<const CopyJob>(o_copies), (uint32_t)copies.size(), V.W, stream);
     launch_copy_first_byte(tab.at<const FirstByteCopyJob>(o_fb_copies), (uint32_t)fb_copies.size(), V.d_first_byte.p, V.W, stream);
     HIP_CHECK(hipEventRecord(ev1, stream));                              // every plane is written
-    if (!build.empty()) launch_popcount(d_rows_p, (uint32_t)build_rows.size(), V.W, d_counts, stream);   // statistics
+    if (!build.empty()) launch_plane_summary(d_rows_p, (uint32_t)build_rows.size(), V.W, d_counts, stream);   // statistics, lists of uncertain tokens
     HIP_CHECK(hipMemcpyAsync(SS.res, S.count, 2 * sizeof(uint32_t), hipMemcpyDeviceToHost, stream));
     if (!build_rows.empty()) HIP_CHECK(hipMemcpyAsync(SS.res + 2, d_counts, 2 * build_rows.size() * sizeof(uint32_t), hipMemcpyDeviceToHost, stream));
     HIP_CHECK(hipEventRecord(SS.ev[4], stream));
@@ -1142,6 +1142,7 @@ struct BatchImpl {
     DevBuf<FillRow> rows;
     DevBuf<uint64_t> front, slow_front;
     DevBuf<uint32_t> items, wait_off, slow_mem, flag_words;
+    int flag_turn = 0;                                      // which half of flag_words the next fill counts in
     DevBuf<uint2> wait;
     DevBuf<uint8_t> slow_map;
     DevBuf<CacheDev> caches_dev;
@@ -2140,14 +2141,14 @@ int32_t xg2_fill_last_status(int32_t* large_capacity_tokens, int32_t* overflowed
     });
 }
 
-int32_t xg2_fill_last_recheck_words(int32_t* words_host, int32_t cap, int32_t* n_rows) {
+int32_t xg2_fill_last_recheck_tokens(int32_t* tokens_host, int32_t cap, int32_t* n_rows) {
     return guarded([&]() -> int32_t {
-        if (cap < 0 || (cap > 0 && !words_host)) return fail(XG2_EINVAL, "xg2_fill_last_recheck_words: bad argument");
+        if (cap < 0 || (cap > 0 && !tokens_host)) return fail(XG2_EINVAL, "xg2_fill_last_recheck_tokens: bad argument");
         std::lock_guard<std::mutex> ws_lock(fill_ws().mu);
-        if (!fill_ws().any) return fail(XG2_EINVAL, "xg2_fill_last_recheck_words: no fill call yet");
+        if (!fill_ws().any) return fail(XG2_EINVAL, "xg2_fill_last_recheck_tokens: no fill call yet");
         fill_ws().wait_last();
         const int32_t n = std::min(cap, fill_ws().last_B);
-        if (n > 0) HIP_CHECK(hipMemcpy(words_host, fill_ws().last_counts, (size_t)n * sizeof(uint32_t), hipMemcpyDeviceToHost));
+        if (n > 0) HIP_CHECK(hipMemcpy(tokens_host, fill_ws().last_counts, (size_t)n * sizeof(uint32_t), hipMemcpyDeviceToHost));
         if (n_rows) *n_rows = fill_ws().last_B;
         return XG2_OK;
     });
@@ -2180,11 +2181,11 @@ int32_t xg2_batch_create(xg2_vocab* vocab, int32_t B, xg2_batch** out) {
         b->rows.alloc(n); b->front.alloc(n * BatchImpl::KF); b->slow_front.alloc(n * BatchImpl::KF);
         b->items.alloc(2 * n * BatchImpl::KI); b->wait.alloc(2 * n * BatchImpl::KW); b->wait_off.alloc(2 * n * (BatchImpl::KH + 1));
         b->slow_mem.alloc(n * kSlowSlots); b->slow_map.alloc(n * (BatchImpl::KH + kSlowMaxLen + 1));
-        b->flag_words.alloc(4);
+        b->flag_words.alloc(8);
         b->caches_dev.alloc(BatchImpl::kMaxCaches); b->tables_dev.alloc(BatchImpl::kMaxCaches);
         b->row_list.alloc(n);
         HIP_CHECK(hipMemset(b->rows.p, 0, n * sizeof(FillRow)));
-        HIP_CHECK(hipMemset(b->flag_words.p, 0, 4 * sizeof(uint32_t)));
+        HIP_CHECK(hipMemset(b->flag_words.p, 0, 8 * sizeof(uint32_t)));
         b->assigned.assign(n, 0);
         BatchDev& d = b->d;
         d.B = (uint32_t)B; d.KI = BatchImpl::KI; d.KH = BatchImpl::KH; d.KW = BatchImpl::KW; d.KF = BatchImpl::KF;
@@ -2268,8 +2269,10 @@ int32_t xg2_batch_fill_next_token_bitmask(xg2_batch* batch, int32_t* bitmask_dev
         F.tables = Bt.d.tables;
         F.eos_id = (uint32_t)V.eos;
         F.cand_words = fill_ws().cand_words.p; F.work_list = fill_ws().work_list.p; F.row_count = fill_ws().row_count.p;
-        F.zero_words = Bt.flag_words.p;                         // nothing is uploaded: the union kernel clears the overflow counter
-        S.count = Bt.flag_words.p;
+        // nothing is uploaded: two sets of counter words take turns, each call's last kernel clears the set of the next call
+        S.count = Bt.flag_words.p + 4 * Bt.flag_turn;
+        Bt.flag_turn ^= 1;
+        F.zero_words = Bt.flag_words.p + 4 * Bt.flag_turn;
         S.mark_rows = Bt.d.rows;                                // an undecided pair makes its slot unusable: the next accept says so
         HIP_CHECK(hipEventRecord(fill_ws().t_begin, stream));
         launch_fill(F, V.dv, bitmask_dev, row_stride_words, S, stream);

@@ -99,8 +99,14 @@ void launch_expand_chunks(const uint4* range_a_dev, const uint4* range_b_dev, co
                           uint4* chunk_dev, hipStream_t stream);
 void launch_build(const DevTables& T, const DevVocab& Vd, BuildPlan P, const SlowScratch& S, hipStream_t stream);
 void launch_build_slow(const DevTables& T, const DevVocab& Vd, const BuildPlan& P, const SlowScratch& S, hipStream_t stream);
-// counts_dev[2p], counts_dev[2p + 1] = set bits of the accepted and of the uncertain row of plane p
-void launch_popcount(const uint32_t* const* plane_ptr_dev, uint32_t n_pos, uint32_t W, uint32_t* counts_dev, hipStream_t stream);
+// A plane in device memory: three rows of W words (accepted, uncertain, left early) and behind them the list of its
+// uncertain tokens: word 0 = how many (kUncListDense if more than the list holds), then their token ids.
+constexpr uint32_t kUncListWords = 64;
+constexpr uint32_t kUncListDense = 0xFFFFFFFFu;
+constexpr size_t plane_words(uint32_t W) { return 3 * (size_t)W + kUncListWords; }
+// counts_dev[2p], counts_dev[2p + 1] = set bits of the accepted and of the uncertain row of plane p; also writes the
+// plane's list of uncertain tokens
+void launch_plane_summary(uint32_t* const* plane_ptr_dev, uint32_t n_pos, uint32_t W, uint32_t* counts_dev, hipStream_t stream);
 
 // One row of a fill batch.
 struct FillRow {
@@ -114,7 +120,7 @@ struct FillRow {
 };
 struct FillBatch {
     const FillRow* rows; uint32_t B;
-    const uint64_t* front_planes;        // device addresses of accepted rows (uncertain at + W words);
+    const uint64_t* front_planes;        // device addresses of accepted rows (uncertain at + W words, list of uncertain tokens at + 3 W);
                                          // bit 0 set: only the accepted row counts (root instance)
     const uint32_t* ctx_items; const uint2* ctx_wait; const uint32_t* ctx_wait_off;
     const DevTables* tables;
@@ -122,9 +128,9 @@ struct FillBatch {
     // re-check scratch: candidate bits of every mask word; per row, the indices of the non-zero ones and their count
     uint32_t* cand_words;                // [B * W]
     uint32_t* work_list;                 // [B * W], row b's list starts at b * W
-    uint32_t* row_count;                 // [B], written by the union kernel
-    uint32_t* zero_words;                // if not null: four words the union kernel clears (the overflow list's length and flag, where
-                                         // no upload brings them in as zeros)
+    uint32_t* row_count;                 // [B], written by the fill kernel: candidate tokens of the row
+    uint32_t* zero_words;                // if not null: four words the large-capacity kernel clears for the next call (the overflow
+                                         // list's length and flag, where no upload brings them in as zeros: two sets take turns)
 };
 void launch_fill(const FillBatch& F, const DevVocab& Vd, int32_t* bitmask_dev, int64_t row_stride_words,
                  const SlowScratch& S, hipStream_t stream);

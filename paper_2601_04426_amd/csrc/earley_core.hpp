@@ -58,6 +58,17 @@ struct MemBytes {
 // needs expanding again) and one wait entry {rule, target | origin} per rule edge involved.  The flags
 // travel with the state reference; memory is read only for expansions.
 constexpr uint32_t REF_MASK = (1u << REF_BITS) - 1;
+
+// A load from the grammar tables.  They always live in device memory; a kernel that got their addresses from memory
+// itself (a batch of rows with a cache each) cannot know that, and would pay for generic-address loads.
+template <class P>
+__device__ __forceinline__ P tab(const P* p) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    return *(const __attribute__((address_space(1))) P*)p;
+#else
+    return *p;
+#endif
+}
 constexpr uint32_t EXP_CURRENT = 1u << REF_BITS;
 
 // A list that is full, or a search bound that is used up, sets `full` and drops the entry; the caller looks at the flag
@@ -87,7 +98,7 @@ __device__ __forceinline__ void add_wait(S& st, uint32_t rule, uint32_t tgt, int
 // but scan, so if it has no edge for the byte that comes next it is left out (`la` = class of that byte, or NO_TARGET
 // after the token's last byte, where every item counts because only "is the set empty" is asked).
 __device__ __forceinline__ bool inert(const DevTables& T, uint32_t ref, uint32_t la) {
-    return la != NO_TARGET && (ref & (F_BYTE | F_REF | F_FINAL)) == F_BYTE && T.trans[(ref & SID_MASK) * T.n_classes + la] == T.sink;
+    return la != NO_TARGET && (ref & (F_BYTE | F_REF | F_FINAL)) == F_BYTE && tab(T.trans + (ref & SID_MASK) * T.n_classes + la) == T.sink;
 }
 
 template <class S>
@@ -97,17 +108,17 @@ __device__ __forceinline__ void enter(const DevTables& T, S& st, uint32_t ref, u
         if (!add_nxt(st, ref | (origin << REF_BITS), nn, full)) return;      // there already (or no room): nothing more to add
     }
     if (ref & F_REF) {
-        const uint4 d = T.state[ref & SID_MASK];
+        const uint4 d = tab(T.state + (ref & SID_MASK));
         const uint32_t* e = T.exp_list + d.y;
         for (uint32_t k = 0; k < d.z; ++k) {
-            const uint32_t w = e[k];
+            const uint32_t w = tab(e + k);
             if (inert(T, w, la)) continue;
             add_nxt(st, (w & REF_MASK) | (((w & EXP_CURRENT) ? set_idx : origin) << REF_BITS), nn, full);
         }
         e += d.z;
         for (uint32_t k = 0; k < d.w; ++k) {
-            const uint32_t w = e[2 * k + 1];
-            add_wait(st, e[2 * k], (w & REF_MASK) | (((w & EXP_CURRENT) ? set_idx : origin) << REF_BITS), nw, wbeg, full);
+            const uint32_t w = tab(e + 2 * k + 1);
+            add_wait(st, tab(e + 2 * k), (w & REF_MASK) | (((w & EXP_CURRENT) ? set_idx : origin) << REF_BITS), nw, wbeg, full);
         }
     }
 }
@@ -150,7 +161,7 @@ __device__ int scan_token(const DevTables& T, const uint32_t* cls_words, const D
         while (single && i < n) {
             const uint32_t b = tok.next();
             const uint32_t cls = (cls_words[b >> 2] >> ((b & 3) * 8)) & 0xFF;
-            const uint32_t tgt = T.trans[(one & SID_MASK) * T.n_classes + cls];
+            const uint32_t tgt = tab(T.trans + (one & SID_MASK) * T.n_classes + cls);
             if (tgt == T.sink) return res;                       // dead
             if (tgt & (F_REF | F_FINAL)) { pending = tgt; single = false; break; }   // this state predicts or completes
             one = tgt | (one & ~REF_MASK);
@@ -183,7 +194,7 @@ __device__ int scan_token(const DevTables& T, const uint32_t* cls_words, const D
                 if (!walked) {
                     const uint32_t it = st.get_cur(k);
                     if (!(it & F_BYTE)) continue;
-                    tgt = T.trans[(it & SID_MASK) * T.n_classes + cls];
+                    tgt = tab(T.trans + (it & SID_MASK) * T.n_classes + cls);
                     origin = it >> REF_BITS;
                 }
                 if (tgt != T.sink) enter(T, st, tgt, origin, set_idx, la, nn, nw, wbeg, full);
@@ -202,15 +213,15 @@ __device__ int scan_token(const DevTables& T, const uint32_t* cls_words, const D
                 root_now = true;
                 if (!FOLLOW) continue;
             }
-            const uint32_t rule = T.state[it & SID_MASK].x;
+            const uint32_t rule = tab(&T.state[it & SID_MASK].x);
             const bool local = !root_end && origin >= C.H;
             int lo, hi;
-            if (root_end) { lo = (int)T.site_off[rule]; hi = (int)T.site_off[rule + 1]; }
+            if (root_end) { lo = (int)tab(T.site_off + rule); hi = (int)tab(T.site_off + rule + 1); }
             else if (local) { lo = (int)st.get_wstart((int)(origin - C.H)); hi = (int)st.get_wstart((int)(origin - C.H) + 1); }
             else { lo = (int)C.wait_off[origin]; hi = (int)C.wait_off[origin + 1]; }
             for (int k = lo; k < hi; ++k) {
                 uint32_t wr, wt;
-                if (root_end) { wr = rule; wt = T.site_tgt[k] | (ROOT_ORIGIN << REF_BITS); }
+                if (root_end) { wr = rule; wt = tab(T.site_tgt + k) | (ROOT_ORIGIN << REF_BITS); }
                 else if (local) { wr = st.wait_rule(k); wt = st.wait_tgt(k); }
                 else { const uint2 w = C.wait[k]; wr = w.x; wt = w.y; }
                 if (wr == rule) enter(T, st, wt & REF_MASK, wt >> REF_BITS, set_idx, la, nn, nw, wbeg, full);

@@ -5,8 +5,10 @@
 //   k_copy_masked  short tokens of a plane taken from the plane of a state they cannot tell apart (section 3.6)
 //   k_copy_first_byte  tokens of a plane taken from the plane of a state that moves alike on their first byte
 //   k_upload       per-call plan and tables from pinned host memory
-//   k_fill_or      union of cached planes over the scannable frontier   (section 3.4, runtime part)
-//   k_recheck      re-check of uncertain tokens against the full Earley context, and its large-capacity twin
+//   k_plane_summary  per built plane: bit counts, and the short list of its uncertain tokens that the fill reads
+//   k_fill         union of cached planes over the scannable frontier and, beside it, the re-check of the uncertain
+//                  tokens against the full Earley context              (section 3.4, runtime part)
+//   k_recheck_slow the re-check with larger item sets, for the tokens that overflowed the short ones
 //   k_apply_*      logits of disallowed tokens := -infinity, in place    (section 2.1)
 // No MFMA: nothing here is a contraction.  All device writes are vector stores or LDS/L2 atomics.
 #include <algorithm>
@@ -24,21 +26,21 @@ namespace {
 using namespace core;
 
 // ---- per-lane item storage -------------------------------------------------------------------------
-// LDS: word (slot, lane) lives at slot * 64 + lane, so a wave touching one slot per lane hits every
-// bank once per 32 lanes whatever the slots are.
-template <int K_, int WM_>
+// LDS: word (slot, column) lives at slot * COLS + column (a lane's column is its place among the lanes at work), so a
+// wave touching one slot per lane hits every bank once per 32 lanes whatever the slots are.
+template <int K_, int WM_, int COLS_ = 64>
 struct LdsStore {
-    static constexpr int K = K_, WM = WM_, MAXLEN = 16, SLOTS = 2 * K_ + 2 * WM_;
+    static constexpr int K = K_, WM = WM_, MAXLEN = 16, COLS = COLS_, SLOTS = 2 * K_ + 2 * WM_;
     uint32_t* cur; uint32_t* nxt; uint32_t* wait;  // this lane's column of the two item lists and the wait list (two words an entry)
     unsigned long long ws_lo = 0, ws_hi = 0;        // wait-list length at the start of each new set, 8 bits each
-    __device__ void init(uint32_t* base) { cur = base; nxt = base + K * 64; wait = base + 2 * K * 64; }
-    __device__ uint32_t get_cur(int k) const { return cur[k * 64]; }
-    __device__ void set_cur(int k, uint32_t v) { cur[k * 64] = v; }
-    __device__ uint32_t get_nxt(int k) const { return nxt[k * 64]; }
-    __device__ void set_nxt(int k, uint32_t v) { nxt[k * 64] = v; }
-    __device__ uint32_t wait_rule(int k) const { return wait[k * 128]; }
-    __device__ uint32_t wait_tgt(int k) const { return wait[k * 128 + 64]; }
-    __device__ void set_wait(int k, uint32_t rule, uint32_t tgt) { wait[k * 128] = rule; wait[k * 128 + 64] = tgt; }
+    __device__ void init(uint32_t* base) { cur = base; nxt = base + K * COLS; wait = base + 2 * K * COLS; }
+    __device__ uint32_t get_cur(int k) const { return cur[k * COLS]; }
+    __device__ void set_cur(int k, uint32_t v) { cur[k * COLS] = v; }
+    __device__ uint32_t get_nxt(int k) const { return nxt[k * COLS]; }
+    __device__ void set_nxt(int k, uint32_t v) { nxt[k * COLS] = v; }
+    __device__ uint32_t wait_rule(int k) const { return wait[k * 2 * COLS]; }
+    __device__ uint32_t wait_tgt(int k) const { return wait[k * 2 * COLS + COLS]; }
+    __device__ void set_wait(int k, uint32_t rule, uint32_t tgt) { wait[k * 2 * COLS] = rule; wait[k * 2 * COLS + COLS] = tgt; }
     __device__ void swap() { uint32_t* t = cur; cur = nxt; nxt = t; }
     __device__ bool charge(int) { return true; }   // short lists: nothing to bound
     __device__ void reset() { ws_lo = 0; ws_hi = 0; }
@@ -537,34 +539,63 @@ __global__ __launch_bounds__(256) void k_copy_structure(const CopyJob* jobs, uin
     j.dst[2 * W + w] = j.src[2 * W + w];
 }
 
-__global__ __launch_bounds__(256) void k_popcount(const uint32_t* const* plane_ptr, uint32_t n_pos, uint32_t W, uint32_t* counts) {
+// Per plane: set bits of the accepted and of the uncertain row, and the plane's list of uncertain tokens behind its
+// three rows: word 0 = how many (kUncListDense if they do not fit), then their token ids in no particular order.
+__global__ __launch_bounds__(256) void k_plane_summary(uint32_t* const* plane_ptr, uint32_t n_pos, uint32_t W, uint32_t* counts) {
     __shared__ uint32_t part[2][4];
+    __shared__ uint32_t n_list;
     const uint32_t p = blockIdx.x;
     if (p >= n_pos) return;
-    const uint32_t* row = plane_ptr[p];
+    uint32_t* row = plane_ptr[p];
+    uint32_t* list = row + 3 * (size_t)W;
+    if (threadIdx.x == 0) n_list = 0;
+    __syncthreads();
     uint32_t a = 0, u = 0;
-    for (uint32_t w = threadIdx.x; w < W; w += blockDim.x) { a += __popc(row[w]); u += __popc(row[W + w]); }
+    for (uint32_t w = threadIdx.x; w < W; w += blockDim.x) {
+        const uint32_t aw = row[w], uw = row[W + w];
+        a += __popc(aw); u += __popc(uw);
+        uint32_t c = uw & ~aw;
+        if (c) {
+            uint32_t at = atomicAdd(&n_list, (uint32_t)__popc(c));
+            for (; c; c &= c - 1, ++at)
+                if (at < kUncListWords - 1) list[1 + at] = w * 32 + (uint32_t)__ffs(c) - 1;
+        }
+    }
     for (int s = 32; s > 0; s >>= 1) { a += __shfl_down(a, s); u += __shfl_down(u, s); }
     if ((threadIdx.x & 63) == 0) { part[0][threadIdx.x >> 6] = a; part[1][threadIdx.x >> 6] = u; }
     __syncthreads();
     if (threadIdx.x == 0) {
         counts[2 * p] = part[0][0] + part[0][1] + part[0][2] + part[0][3];
         counts[2 * p + 1] = part[1][0] + part[1][1] + part[1][2] + part[1][3];
+        list[0] = n_list <= kUncListWords - 1 ? n_list : kUncListDense;
     }
 }
 
 // ---- fill ------------------------------------------------------------------------------------------
-// k_fill_or: pure streaming.  Workgroup = one row; per mask word the OR of the accepted planes of the row's
-// frontier, plus the end-of-sequence bit; uncertain-and-not-accepted bits go to a scratch word and the
-// word's index to a global work list (one atomic per wave with candidates; the list can hold every word).
-// k_recheck: each wave takes 64 listed words, spreads their set bits densely over its lanes and runs the
-// Earley routine from the row's context; survivors are OR-ed into the bitmask.
-constexpr int FILL_THREADS = 256;
+// k_fill: one workgroup per row, in two teams of wavefronts that work side by side.
+//   The union team streams: per mask word the OR of the accepted rows of the row's frontier planes, plus the
+//   end-of-sequence bit, stored with 16-byte accesses.
+//   The re-check team takes the uncertain tokens of the frontier planes from the short list every plane carries behind
+//   its three rows (written by k_plane_summary), one token per lane, and runs the Earley routine from the row's full
+//   context; what survives is kept in LDS until the union is stored, and OR-ed in afterwards.
+// The two teams need nothing from each other until that point, so the latency of the re-check (a chain of dependent
+// table loads) hides behind the streaming and the other way round.  A token that another frontier plane accepts is in
+// the mask anyway and is not parsed: its lane looks the bit up in the accepted rows itself and does not wait for the union.
+// A row with a frontier plane whose uncertain tokens do not fit its list (or with more candidates than the LDS list
+// holds) takes the sequential way: the union team also reads the uncertain rows and lists the words with candidates,
+// the re-check team starts when the union is done.
+// Four wavefronts stream, two re-check with half of their lanes at work (measured: fewer lanes per wavefront, more
+// wavefronts or another split of the six gain nothing; a larger workgroup lowers the number of rows a compute unit holds).
+constexpr int FILL_OR_WAVES = 4, FILL_RECHECK_WAVES = 2;
+constexpr int FILL_RECHECK_LANES = 32;                               // lanes at work in a wavefront of the re-check team
+constexpr int FILL_COLS = FILL_RECHECK_WAVES * FILL_RECHECK_LANES;  // tokens the team parses at a time
+constexpr int FILL_OR_THREADS = 64 * FILL_OR_WAVES;
+constexpr int FILL_THREADS = 64 * (FILL_OR_WAVES + FILL_RECHECK_WAVES);
 constexpr int FILL_BLOCK = 5;                          // steps of the union whose loads are issued together
 constexpr int FILL_K = 8, FILL_WM = 12;
-constexpr int RECHECK_WAVES = 4;
-constexpr uint32_t RECHECK_CHUNK = 16;                    // listed words per wave per round (few, so that many waves share the work)
-using FillStore = LdsStore<FILL_K, FILL_WM>;
+constexpr uint32_t FILL_SPARSE_CAP = 512;              // candidates of a row that the side-by-side way handles
+constexpr uint32_t FILL_NONE = 0xFFFFFFFFu;
+using FillStore = LdsStore<FILL_K, FILL_WM, FILL_COLS>;
 
 __device__ __forceinline__ DevCtx row_ctx(const FillBatch& F, const FillRow& r) {
     DevCtx C;
@@ -578,7 +609,7 @@ __device__ __forceinline__ DevCtx row_ctx(const FillBatch& F, const FillRow& r) 
 
 // Candidate bits of one mask word of row b go to the scratch word; the word's index goes to the row's own
 // work list (one LDS atomic per wave with candidates: no atomics on device memory).
-__device__ __forceinline__ void list_candidates(const FillBatch& F, uint32_t* n_listed, uint32_t cand, uint32_t row_base, uint32_t w) {
+__device__ __forceinline__ void list_candidates(const FillBatch& F, uint32_t* n_listed, uint32_t* n_cand, uint32_t cand, uint32_t row_base, uint32_t w) {
     const unsigned long long has = __ballot(cand != 0);
     if (has) {
         const uint32_t lane = threadIdx.x & 63;
@@ -587,126 +618,187 @@ __device__ __forceinline__ void list_candidates(const FillBatch& F, uint32_t* n_
         if (lane == leader) base = atomicAdd(n_listed, (uint32_t)__popcll(has));
         base = __shfl(base, (int)leader);
         if (cand) {
+            atomicAdd(n_cand, (uint32_t)__popc(cand));
             F.cand_words[row_base + w] = cand;
             F.work_list[row_base + base + (uint32_t)__popcll(has & ((1ull << lane) - 1))] = w;
         }
     }
 }
 
-// One workgroup per row; a thread handles WORDS consecutive mask words per step (4: 16-byte loads and
-// stores, needs W % 4 == 0 and a 16-byte aligned bitmask row; 1: any layout).
+// One candidate token of row b against the row's full context.  A token the short lists cannot decide goes to the
+// large-capacity list and counts as rejected here.
+__device__ __forceinline__ bool recheck_token(const DevVocab& Vd, const SlowScratch& S, const DevTables& T, const uint32_t* cls_words, const DevCtx& C,
+                                              uint32_t b, uint32_t id, FillStore& st) {
+    const uint32_t rank = Vd.rank[id];
+    if (rank >= Vd.n_sorted) return false;
+    const int n = (int)(Vd.off[rank + 1] - Vd.off[rank]);
+    RegBytes tok;
+    tok.v = Vd.tok16[rank];
+    st.reset();
+    const int res = scan_token(T, cls_words, C, tok, n, st);
+    if (res & RES_OVERFLOW) { push_overflow(S, b, id); return false; }
+    return (res & RES_ALIVE) != 0;
+}
+
+// Entry with the smallest index whose inclusive prefix sum exceeds t (every lane of the wave calls this; incl is the
+// lanes' non-decreasing prefix, lane 63 holds the total).
+__device__ __forceinline__ uint32_t prefix_owner(uint32_t incl, uint32_t t) {
+    uint32_t lo = 0, hi = 63;
+#pragma unroll
+    for (int it = 0; it < 6; ++it) {
+        const uint32_t mid = (lo + hi) >> 1;
+        const uint32_t v = (uint32_t)__shfl((int)incl, (int)mid);
+        if (v > t) hi = mid; else lo = mid + 1;
+    }
+    return lo;
+}
+
+// A thread of the union team handles WORDS consecutive mask words per step (4: 16-byte loads and stores, needs
+// W % 4 == 0 and a 16-byte aligned bitmask row; 1: any layout).
 template <int WORDS>
-__global__ __launch_bounds__(FILL_THREADS) void k_fill_or(FillBatch F, DevVocab Vd, int32_t* bitmask, long long row_stride) {
-    __shared__ uint32_t n_listed;
-    const uint32_t b = blockIdx.x;
-    if (threadIdx.x == 0) n_listed = 0;
-    if (F.zero_words && b == 0 && threadIdx.x < 4) F.zero_words[threadIdx.x] = 0;
-    __syncthreads();
-    const uint32_t front_off = F.rows[b].front_off, front_n = F.rows[b].front_n, flags = F.rows[b].flags;
-    const uint32_t eos_word = F.eos_id >> 5, eos_bit = 1u << (F.eos_id & 31);
+__global__ __launch_bounds__(FILL_THREADS) void k_fill(FillBatch F, DevVocab Vd, int32_t* bitmask, long long row_stride, SlowScratch S) {
+    __shared__ uint32_t lds_store[FillStore::SLOTS * FILL_COLS];
+    __shared__ uint32_t sh_surv[FILL_SPARSE_CAP];
+    __shared__ uint32_t sh_cls[FILL_RECHECK_WAVES][64];               // byte classes of the row's grammar, a copy per wavefront of the re-check team
+    __shared__ uint32_t n_listed, n_cand;
+    const uint32_t b = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const FillRow r = F.rows[b];
+    const uint32_t front_off = r.front_off, front_n = r.front_n, flags = r.flags;
+    const bool live = !(flags & 2u);
+    if (threadIdx.x == 0) { n_listed = 0; n_cand = 0; }
+    // the plan, worked out by every wavefront for itself: lane k looks at frontier plane k
+    uint64_t addr = 1;
+    uint32_t n_unc = 0;
+    if (live && front_n <= 64 && lane < front_n) {
+        addr = F.front_planes[front_off + lane];
+        if (!(addr & 1)) n_unc = tab(reinterpret_cast<const uint32_t*>(addr) + 3 * (size_t)Vd.W);
+    }
+    uint32_t incl = n_unc == kUncListDense ? 0u : n_unc;
+    for (int d = 1; d < 64; d <<= 1) { const uint32_t up = (uint32_t)__shfl_up((int)incl, d); if ((int)lane >= d) incl += up; }
+    const uint32_t total = (uint32_t)__shfl((int)incl, 63);
+    const bool listed_way = live && front_n != 0 && (front_n > 64 || __any(n_unc == kUncListDense) || total > FILL_SPARSE_CAP);
     uint32_t* out = reinterpret_cast<uint32_t*>(bitmask) + (long long)b * row_stride;
-    const uint32_t n_steps = (Vd.W / WORDS + FILL_THREADS - 1) / FILL_THREADS;        // same for every thread: the ballots see whole waves
-    // FILL_BLOCK steps at a time: first every load of the block (plane after plane, so that a thread has several
-    // independent loads in flight), then the candidates and the stores
-    for (uint32_t step0 = 0; step0 < n_steps; step0 += FILL_BLOCK) {
-        uint32_t acc[FILL_BLOCK][WORDS], unc[FILL_BLOCK][WORDS];
+    FillStore st;
+    const uint32_t col = (wave - FILL_OR_WAVES) * FILL_RECHECK_LANES + lane;      // re-check team: this lane's place among the lanes at work
+    const bool at_work = wave >= FILL_OR_WAVES && lane < FILL_RECHECK_LANES;
+    if (at_work) st.init(lds_store + col);
+    __syncthreads();
+
+    if (wave < FILL_OR_WAVES) {
+        const uint32_t eos_word = F.eos_id >> 5, eos_bit = 1u << (F.eos_id & 31);
+        const uint32_t n_steps = (Vd.W / WORDS + FILL_OR_THREADS - 1) / FILL_OR_THREADS;   // same for every thread: the ballots see whole waves
+        // FILL_BLOCK steps at a time: first every load of the block (plane after plane, so that a thread has several
+        // independent loads in flight), then the candidates and the stores
+        for (uint32_t step0 = 0; step0 < n_steps; step0 += FILL_BLOCK) {
+            uint32_t acc[FILL_BLOCK][WORDS], unc[FILL_BLOCK][WORDS];
 #pragma unroll
-        for (int s = 0; s < FILL_BLOCK; ++s)
+            for (int s = 0; s < FILL_BLOCK; ++s)
 #pragma unroll
-            for (int c = 0; c < WORDS; ++c) { acc[s][c] = 0; unc[s][c] = 0; }
-        if (!(flags & 2u))
-            for (uint32_t k = 0; k < front_n; ++k) {
-                const uint64_t addr = F.front_planes[front_off + k];
-                const uint32_t* row = reinterpret_cast<const uint32_t*>(addr & ~(uint64_t)1);
-                const bool with_unc = !(addr & 1);
+                for (int c = 0; c < WORDS; ++c) { acc[s][c] = 0; unc[s][c] = 0; }
+            if (live)
+                for (uint32_t k = 0; k < front_n; ++k) {
+                    const uint64_t pa = F.front_planes[front_off + k];
+                    const uint32_t* row = reinterpret_cast<const uint32_t*>(pa & ~(uint64_t)1);
+                    const bool with_unc = listed_way && !(pa & 1);
 #pragma unroll
-                for (int s = 0; s < FILL_BLOCK; ++s) {
-                    const uint32_t v = (step0 + s) * FILL_THREADS + threadIdx.x;
-                    if (v >= Vd.W / WORDS) continue;
-                    if (WORDS == 4) {
-                        const uint4 a = reinterpret_cast<const uint4*>(row)[v];
-                        acc[s][0] |= a.x; acc[s][1 % WORDS] |= a.y; acc[s][2 % WORDS] |= a.z; acc[s][3 % WORDS] |= a.w;
-                        if (with_unc) {
-                            const uint4 u = reinterpret_cast<const uint4*>(row + Vd.W)[v];
-                            unc[s][0] |= u.x; unc[s][1 % WORDS] |= u.y; unc[s][2 % WORDS] |= u.z; unc[s][3 % WORDS] |= u.w;
+                    for (int s = 0; s < FILL_BLOCK; ++s) {
+                        const uint32_t v = (step0 + s) * FILL_OR_THREADS + threadIdx.x;
+                        if (v >= Vd.W / WORDS) continue;
+                        if (WORDS == 4) {
+                            const uint4 a = tab(reinterpret_cast<const uint4*>(row) + v);
+                            acc[s][0] |= a.x; acc[s][1 % WORDS] |= a.y; acc[s][2 % WORDS] |= a.z; acc[s][3 % WORDS] |= a.w;
+                            if (with_unc) {
+                                const uint4 u = tab(reinterpret_cast<const uint4*>(row + Vd.W) + v);
+                                unc[s][0] |= u.x; unc[s][1 % WORDS] |= u.y; unc[s][2 % WORDS] |= u.z; unc[s][3 % WORDS] |= u.w;
+                            }
+                        } else {
+                            acc[s][0] |= tab(row + v);
+                            if (with_unc) unc[s][0] |= tab(row + Vd.W + v);
                         }
-                    } else {
-                        acc[s][0] |= row[v];
-                        if (with_unc) unc[s][0] |= row[Vd.W + v];
                     }
                 }
-            }
 #pragma unroll
-        for (int s = 0; s < FILL_BLOCK; ++s) {
-            if (step0 + s >= n_steps) break;                        // same for every thread
-            const uint32_t v = (step0 + s) * FILL_THREADS + threadIdx.x;
-            const bool in_row = v < Vd.W / WORDS;
-            uint32_t cand[WORDS], any = 0;
+            for (int s = 0; s < FILL_BLOCK; ++s) {
+                if (step0 + s >= n_steps) break;                        // same for every thread
+                const uint32_t v = (step0 + s) * FILL_OR_THREADS + threadIdx.x;
+                const bool in_row = v < Vd.W / WORDS;
+                uint32_t cand[WORDS], any = 0;
 #pragma unroll
-            for (int c = 0; c < WORDS; ++c) {
-                cand[c] = in_row ? (unc[s][c] & ~acc[s][c]) : 0u;
-                any |= cand[c];
-                if ((flags & 3u) && eos_word == v * WORDS + c) acc[s][c] |= eos_bit;
-            }
-            if (__any(any != 0)) {                                  // candidates are few: most wavefronts have none
+                for (int c = 0; c < WORDS; ++c) {
+                    cand[c] = in_row ? (unc[s][c] & ~acc[s][c]) : 0u;
+                    any |= cand[c];
+                    if ((flags & 3u) && eos_word == v * WORDS + c) acc[s][c] |= eos_bit;
+                }
+                if (listed_way && __any(any != 0)) {                    // candidates are few: most wavefronts have none
 #pragma unroll
-                for (int c = 0; c < WORDS; ++c) list_candidates(F, &n_listed, cand[c], b * Vd.W, v * WORDS + c);
+                    for (int c = 0; c < WORDS; ++c) list_candidates(F, &n_listed, &n_cand, cand[c], b * Vd.W, v * WORDS + c);
+                }
+                if (in_row) {
+                    if (WORDS == 4) reinterpret_cast<uint4*>(out)[v] = make_uint4(acc[s][0], acc[s][1 % WORDS], acc[s][2 % WORDS], acc[s][3 % WORDS]);
+                    else out[v] = acc[s][0];
+                }
             }
-            if (in_row) {
-                if (WORDS == 4) reinterpret_cast<uint4*>(out)[v] = make_uint4(acc[s][0], acc[s][1 % WORDS], acc[s][2 % WORDS], acc[s][3 % WORDS]);
-                else out[v] = acc[s][0];
+        }
+    } else if (!listed_way && total != 0) {
+        // side by side with the union: candidate t is entry t - (tokens of the planes before) of its plane's list
+        const DevTables T = F.tables[r.tables_idx];
+        const DevCtx C = row_ctx(F, r);
+        sh_cls[wave - FILL_OR_WAVES][lane] = T.byte_class_words[lane];
+        __builtin_amdgcn_wave_barrier();                              // one wave: its LDS operations complete in order
+        for (uint32_t t0 = 0; t0 < total; t0 += FILL_COLS) {
+            const uint32_t t = t0 + col;
+            const bool mine = at_work && t < total;
+            const uint32_t k = prefix_owner(incl, t);
+            const uint32_t end_k = (uint32_t)__shfl((int)incl, (int)k), n_k = (uint32_t)__shfl((int)n_unc, (int)k);
+            const uint32_t a_lo = (uint32_t)__shfl((int)(uint32_t)addr, (int)k), a_hi = (uint32_t)__shfl((int)(uint32_t)(addr >> 32), (int)k);
+            uint32_t id = 0;
+            if (mine) id = tab(reinterpret_cast<const uint32_t*>(((uint64_t)a_hi << 32) | a_lo) + 3 * (size_t)Vd.W + 1 + (t - (end_k - n_k)));
+            // a token that a frontier plane accepts is in the mask already: no need to parse it
+            uint32_t accepted = 0;
+            for (uint32_t k2 = 0; k2 < front_n; ++k2) {
+                const uint32_t p_lo = (uint32_t)__shfl((int)(uint32_t)addr, (int)k2), p_hi = (uint32_t)__shfl((int)(uint32_t)(addr >> 32), (int)k2);
+                accepted |= tab(reinterpret_cast<const uint32_t*>((((uint64_t)p_hi << 32) | p_lo) & ~(uint64_t)1) + (id >> 5)) >> (id & 31);
             }
+            if (mine) sh_surv[t] = !(accepted & 1u) && recheck_token(Vd, S, T, sh_cls[wave - FILL_OR_WAVES], C, b, id, st) ? id : FILL_NONE;
         }
     }
     __syncthreads();
-    if (threadIdx.x == 0) F.row_count[b] = n_listed;                  // every row writes its count: nothing to clear beforehand
-}
 
-__global__ __launch_bounds__(64 * RECHECK_WAVES) void k_recheck(FillBatch F, DevVocab Vd, int32_t* bitmask, long long row_stride, SlowScratch S) {
-    __shared__ uint32_t lds_store[RECHECK_WAVES * FillStore::SLOTS * 64];
-    __shared__ uint32_t sh_prefix[RECHECK_WAVES][64], sh_cand[RECHECK_WAVES][64], sh_idx[RECHECK_WAVES][64];
-    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const uint32_t b = blockIdx.x;                                  // one workgroup per row
-    const uint32_t count = F.row_count[b];
-    if (count == 0) return;
-    const uint32_t* list = F.work_list + b * Vd.W;
+    if (!listed_way) {
+        for (uint32_t t = threadIdx.x; t < total; t += FILL_THREADS) {
+            const uint32_t id = sh_surv[t];
+            if (id != FILL_NONE) atomicOr(out + (id >> 5), 1u << (id & 31));
+        }
+        if (threadIdx.x == 0) F.row_count[b] = total;                   // every row writes its count: nothing to clear beforehand
+        return;
+    }
+    if (threadIdx.x == 0) F.row_count[b] = n_cand;
+    if (wave < FILL_OR_WAVES) return;
+    // the sequential way: each wave of the re-check team takes as many listed words at a time as it has lanes at work
+    // and spreads their set bits densely over those lanes
+    const uint32_t count = n_listed;
+    const uint32_t* wlist = F.work_list + b * Vd.W;
     const uint32_t* cands = F.cand_words + b * Vd.W;
-    FillStore st;
-    st.init(lds_store + wave * FillStore::SLOTS * 64 + lane);
-    for (uint32_t base = wave * RECHECK_CHUNK; base < count; base += RECHECK_WAVES * RECHECK_CHUNK) {
-        // RECHECK_CHUNK listed words, one per lane; inclusive prefix sum of their candidate counts
+    const DevTables T = F.tables[r.tables_idx];
+    const DevCtx C = row_ctx(F, r);
+    sh_cls[wave - FILL_OR_WAVES][lane] = T.byte_class_words[lane];
+    __builtin_amdgcn_wave_barrier();
+    for (uint32_t base = (wave - FILL_OR_WAVES) * FILL_RECHECK_LANES; base < count; base += FILL_COLS) {
         uint32_t idx = 0, cand = 0;
-        if (lane < RECHECK_CHUNK && base + lane < count) { idx = list[base + lane]; cand = cands[idx]; }
-        uint32_t incl = (uint32_t)__popc(cand);
-        for (int d = 1; d < 64; d <<= 1) { uint32_t up = __shfl_up(incl, d); if ((int)lane >= d) incl += up; }
-        __builtin_amdgcn_wave_barrier();                           // lanes of the previous round are done reading
-        sh_prefix[wave][lane] = incl; sh_cand[wave][lane] = cand; sh_idx[wave][lane] = idx;
-        __builtin_amdgcn_wave_barrier();                           // one wave: LDS operations complete in order
-        const uint32_t total = __shfl(incl, 63);
-        for (uint32_t t0 = 0; t0 < total; t0 += 64) {
+        if (lane < FILL_RECHECK_LANES && base + lane < count) { idx = wlist[base + lane]; cand = cands[idx]; }
+        uint32_t pre = (uint32_t)__popc(cand);
+        for (int d = 1; d < 64; d <<= 1) { const uint32_t up = (uint32_t)__shfl_up((int)pre, d); if ((int)lane >= d) pre += up; }
+        const uint32_t n_tok = (uint32_t)__shfl((int)pre, 63);
+        for (uint32_t t0 = 0; t0 < n_tok; t0 += FILL_RECHECK_LANES) {
             const uint32_t my = t0 + lane;
-            if (my < total) {
-                // entry j = first lane whose inclusive prefix exceeds `my`
-                uint32_t lo = 0, hi = 63;
-                while (lo < hi) { uint32_t mid = (lo + hi) >> 1; if (sh_prefix[wave][mid] > my) hi = mid; else lo = mid + 1; }
-                uint32_t c = sh_cand[wave][lo];
-                uint32_t k = my - (sh_prefix[wave][lo] - (uint32_t)__popc(c));
-                while (k--) c &= c - 1;                            // drop the k lowest set bits
+            const uint32_t j = prefix_owner(pre, my);
+            uint32_t c = (uint32_t)__shfl((int)cand, (int)j);
+            const uint32_t end_j = (uint32_t)__shfl((int)pre, (int)j), w = (uint32_t)__shfl((int)idx, (int)j);
+            if (lane < FILL_RECHECK_LANES && my < n_tok) {
+                uint32_t skip = my - (end_j - (uint32_t)__popc(c));
+                while (skip--) c &= c - 1;                             // drop the lowest set bits that other lanes take
                 const uint32_t bit = __ffs(c) - 1;
-                const uint32_t w = sh_idx[wave][lo];
-                const uint32_t id = w * 32 + bit;
-                const uint32_t rank = Vd.rank[id];
-                if (rank < Vd.n_sorted) {
-                    const FillRow r = F.rows[b];
-                    const int n = (int)(Vd.off[rank + 1] - Vd.off[rank]);
-                    RegBytes tok;
-                    tok.v = Vd.tok16[rank];
-                    st.reset();
-                    const DevTables T = F.tables[r.tables_idx];
-                    int res = scan_token(T, T.byte_class_words, row_ctx(F, r), tok, n, st);
-                    if (res & RES_OVERFLOW) push_overflow(S, b, id);
-                    else if (res & RES_ALIVE) atomicOr(reinterpret_cast<uint32_t*>(bitmask) + (long long)b * row_stride + w, 1u << bit);
-                }
+                if (recheck_token(Vd, S, T, sh_cls[wave - FILL_OR_WAVES], C, b, w * 32 + bit, st)) atomicOr(out + w, 1u << bit);
             }
         }
     }
@@ -715,6 +807,7 @@ __global__ __launch_bounds__(64 * RECHECK_WAVES) void k_recheck(FillBatch F, Dev
 __global__ __launch_bounds__(64) void k_recheck_slow(FillBatch F, DevVocab Vd, int32_t* bitmask, long long row_stride, SlowScratch S) {
     __shared__ uint32_t lds[MidStore::SLOTS * 64];
     const uint32_t gl = blockIdx.x * 64 + threadIdx.x;
+    if (F.zero_words && gl < 4) F.zero_words[gl] = 0;                   // the words the next call counts in
     uint32_t count = S.count[0];
     if (count > S.list_cap) count = S.list_cap;
     MidStore mid;
@@ -1070,19 +1163,17 @@ void launch_copy_first_byte(const FirstByteCopyJob* jobs_dev, uint32_t n_jobs, c
     }
 }
 
-void launch_popcount(const uint32_t* const* plane_ptr_dev, uint32_t n_pos, uint32_t W, uint32_t* counts_dev, hipStream_t stream) {
+void launch_plane_summary(uint32_t* const* plane_ptr_dev, uint32_t n_pos, uint32_t W, uint32_t* counts_dev, hipStream_t stream) {
     if (n_pos == 0) return;
-    hipLaunchKernelGGL(k_popcount, dim3(n_pos), dim3(256), 0, stream, plane_ptr_dev, n_pos, W, counts_dev);
+    hipLaunchKernelGGL(k_plane_summary, dim3(n_pos), dim3(256), 0, stream, plane_ptr_dev, n_pos, W, counts_dev);
 }
 
 void launch_fill(const FillBatch& F, const DevVocab& Vd, int32_t* bitmask_dev, int64_t row_stride_words,
                  const SlowScratch& S, hipStream_t stream) {
     if (F.B == 0) return;
     const bool wide = Vd.W % 4 == 0 && row_stride_words % 4 == 0 && ((uintptr_t)bitmask_dev & 15) == 0;   // plane rows are 16-byte aligned when W % 4 == 0
-    if (wide) hipLaunchKernelGGL(k_fill_or<4>, dim3(F.B), dim3(FILL_THREADS), 0, stream, F, Vd, bitmask_dev, (long long)row_stride_words);
-    else hipLaunchKernelGGL(k_fill_or<1>, dim3(F.B), dim3(FILL_THREADS), 0, stream, F, Vd, bitmask_dev, (long long)row_stride_words);
-    hipLaunchKernelGGL(k_recheck, dim3(F.B), dim3(64 * RECHECK_WAVES), 0, stream, F, Vd, bitmask_dev,
-                       (long long)row_stride_words, S);
+    if (wide) hipLaunchKernelGGL(k_fill<4>, dim3(F.B), dim3(FILL_THREADS), 0, stream, F, Vd, bitmask_dev, (long long)row_stride_words, S);
+    else hipLaunchKernelGGL(k_fill<1>, dim3(F.B), dim3(FILL_THREADS), 0, stream, F, Vd, bitmask_dev, (long long)row_stride_words, S);
 }
 
 void launch_recheck_slow(const FillBatch& F, const DevVocab& Vd, int32_t* bitmask_dev, int64_t row_stride_words,

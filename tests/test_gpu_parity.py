@@ -58,7 +58,8 @@ def check_planes(xg, cfg, vocab, va, ebnf, root, pool=None, depth=2, merge=True,
     return cache, orc
 
 
-def run_decode(xg, cfg, vocab, va, cache, orc, batch, steps, seed, check_every=1):
+def run_decode(xg, cfg, vocab, va, cache, orc, batch, steps, seed, check_every=1, candidates=None):
+    """candidates: a list that receives, every 16th step, the rows' numbers of re-checked tokens."""
     import torch
     dev = torch.device("cuda:0")
     W = vocab.words
@@ -74,6 +75,8 @@ def run_decode(xg, cfg, vocab, va, cache, orc, batch, steps, seed, check_every=1
         xg.fill_next_token_bitmask(matchers, bitmask.data_ptr(), W, _stream())
         torch.cuda.synchronize()
         got = bitmask.cpu().numpy()
+        if candidates is not None and step % 16 == 0:
+            candidates.extend(int(c) for c in xg.fill_last_recheck_tokens(batch))
         for b in range(batch):
             if (step * batch + b) % check_every == 0:
                 if matchers[b].is_terminated():
@@ -167,8 +170,11 @@ def test_config2_planes_and_decode(xg):
     cfg, vocab, va = load(2)
     ebnf, root = cfg.grammars[0]
     cache, orc = check_planes(xg, cfg, vocab, va, ebnf, root)
-    n = run_decode(xg, cfg, vocab, va, cache, orc, batch=cfg.batch, steps=cfg.steps, seed=22, check_every=1)
+    cand = []
+    n = run_decode(xg, cfg, vocab, va, cache, orc, batch=cfg.batch, steps=cfg.steps, seed=22, check_every=1, candidates=cand)
     assert n == 64 * 256
+    # rows whose few uncertain tokens come from the planes' short lists and are parsed beside the union
+    assert any(0 < c <= 64 for c in cand)
 
 
 def test_config3_tagdispatch_planes_and_decode(xg):
@@ -177,8 +183,11 @@ def test_config3_tagdispatch_planes_and_decode(xg):
     cfg, vocab, va = load(3)
     ebnf, root = cfg.grammars[0]
     cache, orc = check_planes(xg, cfg, vocab, va, ebnf, root)          # every plane x 128,256 tokens
-    n = run_decode(xg, cfg, vocab, va, cache, orc, batch=cfg.batch, steps=cfg.steps, seed=33, check_every=31)
+    cand = []
+    n = run_decode(xg, cfg, vocab, va, cache, orc, batch=cfg.batch, steps=cfg.steps, seed=33, check_every=31, candidates=cand)
     assert n >= 4200
+    # rows whose few uncertain tokens come from the planes' short lists and are parsed beside the union
+    assert any(0 < c <= 64 for c in cand), (min(cand), max(cand))
 
 
 def test_config5_depth1_unmerged_planes(xg):
@@ -243,7 +252,7 @@ def test_config5_decode_at_random_depths_batch_1024(xg):
             torch.cuda.synchronize()
             assert not xg.fill_last_status()[1]
             got = bitmask.cpu().numpy()
-            words = xg.fill_last_recheck_words(B)
+            words = xg.fill_last_recheck_tokens(B)
             nxt = np.array([traces[b][cursor[b]] for b in range(B)])
             assert ((got.view(np.uint32)[np.arange(B), nxt // 32] >> (nxt % 32).astype(np.uint32)) & 1).all(), "a trace's next token is not allowed"
             ints = [b for b in range(B) if in_int.search(hist[b][-64:])]
@@ -587,7 +596,7 @@ def test_pool_gives_up_unused_planes_when_full(xg):
     """A pool bounded by max_bytes: planes of destroyed caches are evicted (least recently used first) to make room,
     rebuilt when needed again, and always equal to the oracle's; a pool whose planes are all in use reports overflow."""
     cfg, vocab, va = load(1)
-    row_bytes = 3 * vocab.words * 4                                 # a plane: accepted, uncertain and left-early row
+    row_bytes = (3 * vocab.words + 64) * 4                          # a plane: accepted, uncertain and left-early row, list of uncertain tokens
     grammars = ['root ::= "[" [0-9]{1,3} ("," [0-9]{1,3})* "]"\n', 'root ::= "{" ws pair ws "}"\npair ::= "\\"" [a-z]+ "\\"" ws ":" ws [0-9]+\nws ::= " "*\n',
                 'root ::= ("a" | "b" x)+\nx ::= "c" x | "d"\n', 'root ::= t ("+" t)*\nt ::= [0-9]+ | "(" root ")"\n']
     sizes = []
@@ -765,6 +774,7 @@ def test_tricky_grammars_planes_and_masks(xg, case, depth, follow):
     cache, orc = check_planes(xg, Cfg, vocab, va, ebnf, "root", depth=depth, merge=True, follow=follow, max_contexts=100000)
     single = {bytes([b]): toks.index(bytes([b])) for b in alphabet}
     bm = torch.full((1, vocab.words), -1, dtype=torch.int32, device="cuda:0")
+    most = 0
     for sent in sentences:
         m = xg.Matcher(cache)
         for i in range(len(sent) + 1):
@@ -773,9 +783,14 @@ def test_tricky_grammars_planes_and_masks(xg, case, depth, follow):
             want = oracle.pack_bitmask(orc.mask(sent[:i], va))
             got = bm.cpu().numpy()[0]
             assert np.array_equal(got, want), (sent[:i], diff_words(got, want, toks))
+            most = max(most, int(xg.fill_last_recheck_tokens(1)[0]))
             if i < len(sent):
                 assert m.accept_token(single[sent[i:i + 1]])
         assert m.accept_token(0) and m.is_terminated()
+    if (case, depth) == (3, 1):
+        # a frontier plane with more uncertain tokens than its short list holds: the union finds the candidates and they
+        # are parsed after it (the other way of the fill kernel)
+        assert most > 64, most
 
 
 def test_nullable_and_final_rule_instances_under_sites(xg):
