@@ -28,18 +28,21 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
 
-# HBM traffic per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (KiB per dispatch, default workload and batch),
-# valid only for the kernel sources they were taken with.  The same counters read 303,884 KiB (FETCH_SIZE) and
-# 607,744 KiB (WRITE_SIZE) for a device-to-device copy of 607,744 KiB, hence the scale factors.
+# HBM traffic per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (counter values per dispatch, default workload and
+# batch; k_build_tagdispatch: the one build of the TagDispatch workload), valid only for the kernel sources they were taken
+# with.  The same counters read 303,890 (FETCH_SIZE) and 607,744 (WRITE_SIZE) for a device-to-device copy of 607,744 KiB,
+# hence the scale factors to KiB.  The summaries under profiles/ hold the commands and the full tables.
 PMC = {
-    "sources_sha256": "4082be428ec9ccc861382e0ba1bc6d14f8e4c37f54989ef74cc07c77d6de7059",
-    "fetch_scale": 2.0, "write_scale": 1.0,
-    "k_build": (10924.8, 3374.7),
-    "k_fill": (4114.0, 19167.8),
-    "k_apply_vec<8>": (98619.9, 303872.0),
-    # wave instructions of one k_build launch of the default workload (rocprofv3 --pmc SQ_INSTS_VALU, SQ_INSTS_SALU + SQ_INSTS_BRANCH)
-    "k_build_valu_instructions": 11400000.0, "k_build_scalar_and_branch_instructions": 20100000.0,
-    "k_apply_vec<4>": (182233.6, 605511.0),
+    "sources_sha256": "82861912951d10e2d7af5ce56c1fcbacb809a38a037e9fd5b58dd9c07846861a",
+    "fetch_scale": 2.00, "write_scale": 1.00,
+    "k_build": (11010.3, 4800.5),
+    "k_fill": (3307.9, 19192.2),
+    "k_apply_vec<8>": (97590.4, 303872.0),
+    "k_apply_vec<4>": (180437.9, 605533.3),
+    "k_build_tagdispatch": (144445.8, 689897.5),
+    # wave instructions of one k_build launch (rocprofv3 --pmc SQ_INSTS_VALU; SQ_INSTS_SALU + SQ_INSTS_SMEM + SQ_INSTS_BRANCH)
+    "k_build_valu_instructions": 12826031.0, "k_build_scalar_and_branch_instructions": 17314808.0,
+    "k_build_tagdispatch_valu_instructions": 842330509.0, "k_build_tagdispatch_scalar_and_branch_instructions": 1117415809.0,
 }
 KERNEL_SOURCES = ("csrc/kernels.hip", "csrc/earley_core.hpp", "csrc/device.hpp", "build.py")   # code and compiler flags
 
@@ -352,6 +355,15 @@ def main() -> int:
                                     "device_ms": s3.device_ms, "kernel_ms": s3.kernel_ms, "host_lower_ms": s3.host_lower_ms,
                                     "checks_per_s_device": int(s3.checks) / (s3.device_ms * 1e-3),
                                     "roofline": build_roofline(s3, s3.kernel_ms)}
+        counted3 = kernel_sources_sha256() == PMC["sources_sha256"]
+        if counted3:
+            f3, w3 = PMC["k_build_tagdispatch"]
+            out["build_tagdispatch"]["roofline"]["traffic"] = (f3 * PMC["fetch_scale"] + w3 * PMC["write_scale"]) * 1024.0
+        n3 = PMC["k_build_tagdispatch_valu_instructions"] if counted3 else None
+        out["build_tagdispatch"]["roofline_alu"] = {
+            "kernel": "k_build", "bound": "alu", "achieved": (n3 / (s3.kernel_ms * 1e-3)) if n3 else None, "peak": valu_peak,
+            "unit": "vector wave-instructions/s", "frac": (n3 / (s3.kernel_ms * 1e-3) / valu_peak) if n3 else None, "traffic": None,
+            "scalar_and_branch_instructions_per_launch": PMC["k_build_tagdispatch_scalar_and_branch_instructions"] if counted3 else None}
         del c3, vocab3
 
     if not args.no_host_matchers:
