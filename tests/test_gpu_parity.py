@@ -337,6 +337,75 @@ def test_plane_count_does_not_depend_on_repetition_bound(xg):
         hist += cfg.vocab.tokens[tid]
 
 
+def test_long_bounded_string_planes_and_masks_near_the_bound(xg):
+    """Section 3.6 on a character repetition: a string of up to 4,096 characters instead of 256 makes the rule's automaton
+    sixteen times as long and the mask cache no larger (the states far from the bound share one plane, the last sixteen
+    keep their own); masks at the start, deep inside, within a token's length of the bound and at the bound equal the
+    oracle's, for a matcher on the host and for one on the device."""
+    import torch
+    cfg, vocab, va = load(5)
+
+    def grammar(n):
+        return ('root ::= "{" ws "\\"k\\"" ws ":" ws str ws "}"\n'
+                'str ::= "\\"" [^"\\\\\\x00-\\x1F]{0,%d} "\\""\n'
+                'ws ::= [ \\n\\t]*\n' % n)
+    small = xg.compile_grammar(vocab, grammar(256), "root", stream=_stream())
+    ebnf = grammar(4096)
+    big = xg.compile_grammar(vocab, ebnf, "root", stream=_stream())
+    assert big.stats.positions > 10 * small.stats.positions
+    assert big.stats.unique == small.stats.unique and big.stats.built == small.stats.built
+    assert big.stats.executed_checks == small.stats.executed_checks
+    orc = oracle.Oracle(ebnf, "root")
+    rng = random.Random(40960)
+    seg = gen.Segmenter(cfg.vocab)
+    body = bytes(rng.choice(b"abcdefghij klmnop,.:{}[]0123456789") for _ in range(4096))
+    head = b'{"k":"'
+    ids = seg.segment(head, rng) + seg.segment(body, rng)
+    depth_after = []                                                # characters of the string after each token
+    n = -len(head)
+    for t in ids:
+        n += len(cfg.vocab.tokens[t])
+        depth_after.append(n)
+    assert depth_after[-1] == 4096
+    want_depths = [0, 7, 2000, 4079, 4080, 4081, 4088, 4093, 4095]
+    check_at = set()                                                # token counts whose string depth is the first at or after a wanted one
+    for d in want_depths:
+        check_at.add(next(i + 1 for i, a in enumerate(depth_after) if a >= d))
+    m = xg.Matcher(big)
+    db = xg.DeviceBatch(vocab, 1)
+    db.assign(big, stream=_stream())
+    ids_dev = torch.zeros(1, dtype=torch.int32, device="cuda:0")
+    st_dev = torch.zeros(1, dtype=torch.int32, device="cuda:0")
+    bm = torch.full((2, vocab.words), -1, dtype=torch.int32, device="cuda:0")
+    hist = b""
+    checked = []
+    for i, tid in enumerate(ids):
+        if i in check_at:
+            xg.fill_next_token_bitmask([m], bm.data_ptr(), vocab.words, _stream())
+            db.fill_next_token_bitmask(bm[1].data_ptr(), vocab.words, _stream())
+            torch.cuda.synchronize()
+            got = bm.cpu().numpy()
+            want = oracle.pack_bitmask(orc.mask(hist, va))
+            assert np.array_equal(got[0], want), (len(hist), hist[-20:], diff_words(got[0], want, cfg.vocab.tokens))
+            assert np.array_equal(got[1], want), ("device matcher", len(hist), diff_words(got[1], want, cfg.vocab.tokens))
+            checked.append(depth_after[i - 1] if i else -len(head))
+        assert m.accept_token(tid)
+        ids_dev.fill_(tid)
+        db.accept_tokens(ids_dev.data_ptr(), st_dev.data_ptr(), _stream())
+        hist += cfg.vocab.tokens[tid]
+    assert not st_dev.cpu().numpy().any()
+    # the string is full: only its closing quote may follow
+    xg.fill_next_token_bitmask([m], bm.data_ptr(), vocab.words, _stream())
+    db.fill_next_token_bitmask(bm[1].data_ptr(), vocab.words, _stream())
+    torch.cuda.synchronize()
+    got = bm.cpu().numpy()
+    want = oracle.pack_bitmask(orc.mask(hist, va))
+    assert np.array_equal(got[0], want) and np.array_equal(got[1], want)
+    allowed = [cfg.vocab.tokens[t] for t in range(vocab.size) if (int(want[t // 32]) >> (t % 32)) & 1]
+    assert allowed and all(a.startswith(b'"') for a in allowed)
+    assert len(checked) >= 6 and max(checked) >= 4080, checked
+
+
 @pytest.mark.parametrize("index,prebuild,batch,steps,every", [(1, 0, 4, 64, 1), (1, 7, 4, 64, 1), (2, 0, 64, 40, 5), (3, 16, 64, 24, 11)])
 def test_jit_compilation_gives_the_same_masks(xg, index, prebuild, batch, steps, every):
     """Section 3.5: nothing (or only the costliest planes) built at compile time, the rest by the fill calls that
