@@ -480,7 +480,8 @@ __global__ __launch_bounds__(64) void k_build_slow(DevTables T, DevVocab Vd, Bui
     }
 }
 
-// Set bits of the freshly built planes: counts[2p] = accepted, counts[2p + 1] = uncertain bits of plane p.
+// Copies n 16-byte words from pinned host memory (read through its device address) to device memory: the per-call plan,
+// tables and per-row records travel this way, without a trip through the copy engine.
 __global__ __launch_bounds__(256) void k_upload(uint4* dst, const uint4* src, size_t n) {
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) dst[i] = src[i];
 }
