@@ -87,6 +87,8 @@ typedef struct xg2_compile_opts {
     int32_t jit;
     int32_t jit_prebuild;
     int32_t partial_hits;
+    int32_t time_kernel;      /* measurement aid: also time the classification kernel alone (xg2_compile_stats.kernel_ms); the two
+                                 extra events sit between the kernels of the build and lengthen device_ms by a few microseconds */
 } xg2_compile_opts;
 
 /* Counters filled by xg2_compile_grammar. */
@@ -103,8 +105,8 @@ typedef struct xg2_compile_stats {
     int64_t n_accepted;       /* set bits over the built accepted planes                          */
     int64_t n_uncertain;      /* set bits over the built uncertain planes                         */
     double  host_lower_ms;    /* EBNF -> tables and work plan on the host                         */
-    double  device_ms;        /* first table upload -> last plane written (HIP events)            */
-    double  kernel_ms;        /* the classification kernel alone (HIP events around its launch)   */
+    double  device_ms;        /* first clear / table upload -> last plane written and summarised (HIP events) */
+    double  kernel_ms;        /* the classification kernel alone (HIP events around its launch); 0 unless time_kernel was set */
 } xg2_compile_stats;
 
 const char* xg2_last_error(void);

@@ -51,7 +51,7 @@ class CompileStats(ctypes.Structure):
 
 class CompileOpts(ctypes.Structure):
     _fields_ = [("context_depth", ctypes.c_int32), ("merge_equivalent", ctypes.c_int32), ("follow_filter", ctypes.c_int32),
-                ("jit", ctypes.c_int32), ("jit_prebuild", ctypes.c_int32), ("partial_hits", ctypes.c_int32)]
+                ("jit", ctypes.c_int32), ("jit_prebuild", ctypes.c_int32), ("partial_hits", ctypes.c_int32), ("time_kernel", ctypes.c_int32)]
 
 
 def _load() -> ctypes.CDLL:
@@ -243,11 +243,11 @@ class MaskCache:
 
 def compile_grammar(vocab: Vocab, ebnf: str, root: str = "root", pool: Optional[Pool] = None, stream: int = 0,
                     context_depth: int = 2, merge_equivalent: bool = True, follow_filter: bool = True,
-                    jit: bool = False, jit_prebuild: int = 0, partial_hits: bool = True) -> MaskCache:
+                    jit: bool = False, jit_prebuild: int = 0, partial_hits: bool = True, time_kernel: bool = False) -> MaskCache:
     data = ebnf.encode("utf-8")
     h = ctypes.c_void_p()
     stats = CompileStats()
-    opts = CompileOpts(context_depth, 1 if merge_equivalent else 0, 1 if follow_filter else 0, 1 if jit else 0, jit_prebuild, 1 if partial_hits else 0)
+    opts = CompileOpts(context_depth, 1 if merge_equivalent else 0, 1 if follow_filter else 0, 1 if jit else 0, jit_prebuild, 1 if partial_hits else 0, 1 if time_kernel else 0)
     _check(lib.xg2_compile_grammar(vocab.h, data, len(data), root.encode(), ctypes.byref(opts), pool.h if pool else None,
                                    ctypes.c_void_p(stream), ctypes.byref(h), ctypes.byref(stats)))
     return MaskCache(h, vocab, stats, pool)

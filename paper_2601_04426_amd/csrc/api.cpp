@@ -10,6 +10,7 @@
 #include <cstring>
 #include <deque>
 #include <map>
+#include <set>
 #include <memory>
 #include <mutex>
 #include <numeric>
@@ -353,6 +354,7 @@ struct BuildTicket {
     int state = 0;                                              // 0 enqueued, 1 good, 2 failed
     int64_t slow = 0, n_accepted = 0, n_uncertain = 0;
     float device_ms = 0.f, kernel_ms = 0.f;
+    bool timed_kernel = false;                                  // events were recorded around the classification kernel
     ~BuildTicket() { if (staging) { (void)hipEventSynchronize(staging->ev[4]); staging_pool().release(staging); } }
 };
 // Builds follow one another on the device whatever streams they were given: each waits for the event of the one before
@@ -494,6 +496,7 @@ struct CacheImpl {
     std::shared_ptr<BuildTicket> compile_ticket;
     bool failed = false;
     bool partial_hits = true;                               // derive planes from planes of the same structure under another follow language
+    bool time_kernel = false;                               // record events around the classification kernel (they cost a few microseconds of device time each)
     std::vector<std::shared_ptr<BuildTicket>> jit_tickets;  // builds issued by fill calls whose device time has not been added up yet
     double host_lower_ms = 0;                               // EBNF -> tables and plan, of the compile call
     int64_t compile_built = 0;
@@ -695,7 +698,7 @@ void finalize_ticket(BuildTicket& T) {
     bool failed = e != hipSuccess;
     if (!failed) {
         (void)hipEventElapsedTime(&T.device_ms, S.ev[0], S.ev[1]);
-        (void)hipEventElapsedTime(&T.kernel_ms, S.ev[2], S.ev[3]);
+        if (T.timed_kernel) (void)hipEventElapsedTime(&T.kernel_ms, S.ev[2], S.ev[3]);
         T.slow = S.res[0];
         failed = S.res[1] != 0;                                     // item sets exceeded even the large-capacity lists
     }
@@ -968,6 +971,29 @@ int32_t build_planes(CacheImpl& cache, const std::vector<int32_t>& todo, hipStre
             b = e + 1;
         }
     }
+    // The copies of derived planes and the per-plane summary go in one pass over the planes when no plane takes bits from
+    // a plane that itself takes bits in this build (the separate kernels order such chains: masked copies, then
+    // first-byte copies, then the summary).
+    std::vector<FinishJob> finish(build_rows.size(), FinishJob{});
+    bool finish_in_one = !build_rows.empty();
+    {
+        std::map<const uint32_t*, size_t> at;
+        for (size_t k = 0; k < build_rows.size(); ++k) at.emplace(build_rows[k], k);
+        std::set<const uint32_t*> takes;
+        for (const CopyJob& j : copies) takes.insert(j.dst);
+        for (const FirstByteCopyJob& j : fb_copies) takes.insert(j.dst);
+        for (const CopyJob& j : copies) {
+            FinishJob& f = finish[at.at(j.dst)];
+            if (f.m_src || takes.count(j.src)) finish_in_one = false;
+            f.m_src = j.src; f.m_mask = j.mask;
+        }
+        for (const FirstByteCopyJob& j : fb_copies) {
+            FinishJob& f = finish[at.at(j.dst)];
+            if (f.f_src || takes.count(j.src)) finish_in_one = false;
+            f.f_src = j.src;
+            for (int w = 0; w < 8; ++w) f.f_bytes[w] = j.bytes[w];
+        }
+    }
     // The chunk records are written on the device (k_expand_chunks) from the ranges: per range {plane, first rank, end
     // rank, flags}, the index of its first chunk and what the walk needs of its plane.  Chunks of the heavy ranges come
     // first, then the others, each group in plane order; a long range is cut so that one thread writes at most 32 chunks.
@@ -1003,7 +1029,7 @@ int32_t build_planes(CacheImpl& cache, const std::vector<int32_t>& todo, hipStre
         o_trans = tab.add(ft.trans); o_cls = tab.add(ft.byte_class_words);
     }
     const size_t o_range_a = tab.add(range_a), o_range_b = tab.add(range_b), o_range_first = tab.add(range_first), o_pctx = tab.add(plane_ctx), o_items = tab.add(ctx_items), o_wait = tab.add(ctx_wait),
-                 o_wait_off = tab.add(ctx_wait_off), o_rows = tab.add(build_rows), o_copies = tab.add(copies), o_structure_copies = tab.add(structure_copies), o_fb_copies = tab.add(fb_copies), o_zero = tab.add(zeros);
+                 o_wait_off = tab.add(ctx_wait_off), o_rows = tab.add(build_rows), o_copies = tab.add(copies), o_structure_copies = tab.add(structure_copies), o_fb_copies = tab.add(fb_copies), o_finish = tab.add(finish), o_zero = tab.add(zeros);
     const size_t o_chunks = tab.reserve(n_chunks * 2 * sizeof(uint4));
     tab.stage(with_tables, SS);
     if (with_tables) cache.d_tables = tab.dev;                     // the cache owns the block from here on
@@ -1019,8 +1045,31 @@ int32_t build_planes(CacheImpl& cache, const std::vector<int32_t>& todo, hipStre
         if (last && last->state == 0 && last->staging && last->stream != stream) HIP_CHECK(hipStreamWaitEvent(stream, last->staging->ev[4], 0));
     }
     HIP_CHECK(hipEventRecord(ev0, stream));
-    pool.flush_zero(stream);                                       // the rows start as zeros: tokens skipped by their first byte are never written
-    tab.copy(stream);
+    // The rows start as zeros (tokens skipped by their first byte are never written), the plan goes up and the chunk
+    // records are written: one launch when the upload is small enough for a copy kernel and the pool has few ranges to
+    // clear (a fresh slab, a few recycled rows), else one call each.
+    bool staged = false;
+    if (tab.total <= kUploadByKernelMax && pool.to_zero.size() <= kStageZeroRanges) {
+        StageZero Z{};
+        bool ok = true;
+        for (auto& z : pool.to_zero) {
+            if (z.second % 4) { ok = false; break; }
+            Z.p[Z.n] = static_cast<uint32_t*>(z.first); Z.words[Z.n] = z.second / 4; ++Z.n;
+        }
+        if (ok) {
+            void* mapped = nullptr;
+            HIP_CHECK(hipHostGetDevicePointer(&mapped, tab.host, 0));
+            const uint8_t* hm = static_cast<const uint8_t*>(mapped);
+            launch_stage(tab.dev, mapped, tab.total, Z, reinterpret_cast<const uint4*>(hm + o_range_a), reinterpret_cast<const uint4*>(hm + o_range_b),
+                         reinterpret_cast<const uint32_t*>(hm + o_range_first), (uint32_t)range_a.size(), tab.at<uint4>(o_chunks), stream);
+            pool.to_zero.clear();
+            staged = true;
+        }
+    }
+    if (!staged) {
+        pool.flush_zero(stream);
+        tab.copy(stream);
+    }
     if (with_tables) {
         cache.dt.state = tab.at<const uint4>(o_state);
         cache.dt.exp_list = tab.at<const uint32_t>(o_exp);
@@ -1041,17 +1090,23 @@ int32_t build_planes(CacheImpl& cache, const std::vector<int32_t>& todo, hipStre
     P.plane_ptr = tab.at<uint32_t*>(o_rows);
     P.follow_filter = cache.follow ? 1u : 0u;
     uint32_t* const* d_rows_p = tab.at<uint32_t*>(o_rows);
-    launch_expand_chunks(tab.at<const uint4>(o_range_a), tab.at<const uint4>(o_range_b), tab.at<const uint32_t>(o_range_first),
-                         (uint32_t)range_a.size(), tab.at<uint4>(o_chunks), stream);
-    HIP_CHECK(hipEventRecord(evk0, stream));
+    if (!staged)
+        launch_expand_chunks(tab.at<const uint4>(o_range_a), tab.at<const uint4>(o_range_b), tab.at<const uint32_t>(o_range_first),
+                             (uint32_t)range_a.size(), tab.at<uint4>(o_chunks), stream);
+    ticket->timed_kernel = cache.time_kernel;
+    if (cache.time_kernel) HIP_CHECK(hipEventRecord(evk0, stream));
     if (!build.empty()) launch_build(cache.dt, V.dv, P, S, stream);
-    HIP_CHECK(hipEventRecord(evk1, stream));
+    if (cache.time_kernel) HIP_CHECK(hipEventRecord(evk1, stream));
     if (!build.empty()) launch_build_slow(cache.dt, V.dv, P, S, stream);
     launch_copy_structure(tab.at<const CopyJob>(o_structure_copies), (uint32_t)structure_copies.size(), V.W, stream);
-    launch_copy_masked(tab.at<const CopyJob>(o_copies), (uint32_t)copies.size(), V.W, stream);
-    launch_copy_first_byte(tab.at<const FirstByteCopyJob>(o_fb_copies), (uint32_t)fb_copies.size(), V.d_first_byte.p, V.W, stream);
-    HIP_CHECK(hipEventRecord(ev1, stream));                              // every plane is written
-    if (!build.empty()) launch_plane_summary(d_rows_p, (uint32_t)build_rows.size(), V.W, d_counts, stream);   // statistics, lists of uncertain tokens
+    if (finish_in_one) {
+        launch_finish_planes(d_rows_p, tab.at<const FinishJob>(o_finish), (uint32_t)build_rows.size(), V.d_first_byte.p, V.W, d_counts, stream);
+    } else {
+        launch_copy_masked(tab.at<const CopyJob>(o_copies), (uint32_t)copies.size(), V.W, stream);
+        launch_copy_first_byte(tab.at<const FirstByteCopyJob>(o_fb_copies), (uint32_t)fb_copies.size(), V.d_first_byte.p, V.W, stream);
+        if (!build.empty()) launch_plane_summary(d_rows_p, (uint32_t)build_rows.size(), V.W, d_counts, stream);   // statistics, lists of uncertain tokens
+    }
+    HIP_CHECK(hipEventRecord(ev1, stream));                              // every plane is written, with its list of uncertain tokens
     HIP_CHECK(hipMemcpyAsync(SS.res, S.count, 2 * sizeof(uint32_t), hipMemcpyDeviceToHost, stream));
     if (!build_rows.empty()) HIP_CHECK(hipMemcpyAsync(SS.res + 2, d_counts, 2 * build_rows.size() * sizeof(uint32_t), hipMemcpyDeviceToHost, stream));
     HIP_CHECK(hipEventRecord(SS.ev[4], stream));
@@ -1326,6 +1381,7 @@ int32_t xg2_compile_grammar(xg2_vocab* vocab, const char* ebnf, size_t len, cons
         cache->vocab = vocab->p;
         cache->context_depth = depth;
         cache->partial_hits = partial;
+        cache->time_kernel = opts ? opts->time_kernel != 0 : false;
         cache->gram = make_grammar(ebnf, len, root_rule);
         const Grammar& g = cache->gram->g;
         const FlatTables& ft = cache->gram->ft;

@@ -97,12 +97,25 @@ void launch_copy_first_byte(const FirstByteCopyJob* jobs_dev, uint32_t n_jobs, c
 // kBuildChunk (kHeavyChunk with kChunkHeavy) ranks, records first[r], first[r] + 1, ..., each followed by range_b[r].
 void launch_expand_chunks(const uint4* range_a_dev, const uint4* range_b_dev, const uint32_t* first_dev, uint32_t n_ranges,
                           uint4* chunk_dev, hipStream_t stream);
+// One launch for what a build needs first: the copy of `bytes` (a multiple of 16) from pinned host memory (given by its
+// device address) to dst_dev, the clearing of up to kStageZeroRanges ranges of words, and the chunk records (as
+// launch_expand_chunks, but reading the ranges through the device addresses of their pinned host copies).
+constexpr uint32_t kStageZeroRanges = 8;
+struct StageZero { uint32_t* p[kStageZeroRanges]; uint64_t words[kStageZeroRanges]; uint32_t n; };
+void launch_stage(void* dst_dev, const void* src_host_mapped, size_t bytes, const StageZero& Z, const uint4* range_a_host_mapped,
+                  const uint4* range_b_host_mapped, const uint32_t* first_host_mapped, uint32_t n_ranges, uint4* chunk_dev, hipStream_t stream);
 void launch_build(const DevTables& T, const DevVocab& Vd, BuildPlan P, const SlowScratch& S, hipStream_t stream);
 void launch_build_slow(const DevTables& T, const DevVocab& Vd, const BuildPlan& P, const SlowScratch& S, hipStream_t stream);
+// What a freshly classed plane still lacks: the bits it takes from other planes (either kind, or none: null sources).
+// m_src under the token mask m_mask (all three rows, as launch_copy_masked); f_src for the tokens whose first byte is in
+// f_bytes (as launch_copy_first_byte).  The sources must not themselves be planes that take bits in the same launch.
+struct FinishJob { const uint32_t* m_src; const uint32_t* m_mask; const uint32_t* f_src; uint32_t f_bytes[8]; uint32_t pad[2]; };
+// One pass over every built plane: the copies above, then what launch_plane_summary does, on the words in registers.
+void launch_finish_planes(uint32_t* const* plane_ptr_dev, const FinishJob* jobs_dev, uint32_t n_pos, const uint8_t* first_byte_dev, uint32_t W,
+                          uint32_t* counts_dev, hipStream_t stream);
 // A plane in device memory: three rows of W words (accepted, uncertain, left early) and behind them the list of its
-// uncertain tokens: word 0 = how many (kUncListDense if more than the list holds), then their token ids.
+// uncertain tokens: word 0 = how many (the list holds them if that is at most kUncListWords - 1), then their token ids.
 constexpr uint32_t kUncListWords = 64;
-constexpr uint32_t kUncListDense = 0xFFFFFFFFu;
 constexpr size_t plane_words(uint32_t W) { return 3 * (size_t)W + kUncListWords; }
 // counts_dev[2p], counts_dev[2p + 1] = set bits of the accepted and of the uncertain row of plane p; also writes the
 // plane's list of uncertain tokens

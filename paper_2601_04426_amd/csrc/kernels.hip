@@ -5,7 +5,9 @@
 //   k_copy_masked  short tokens of a plane taken from the plane of a state they cannot tell apart (section 3.6)
 //   k_copy_first_byte  tokens of a plane taken from the plane of a state that moves alike on their first byte
 //   k_upload       per-call plan and tables from pinned host memory
+//   k_stage        the same for a build, together with the clearing of fresh rows and the chunk records
 //   k_plane_summary  per built plane: bit counts, and the short list of its uncertain tokens that the fill reads
+//   k_finish_planes  the copy kernels and the summary in one pass, when no derived plane leans on another derived one
 //   k_fill         union of cached planes over the scannable frontier and, beside it, the re-check of the uncertain
 //                  tokens against the full Earley context              (section 3.4, runtime part)
 //   k_recheck_slow the re-check with larger item sets, for the tokens that overflowed the short ones
@@ -486,15 +488,45 @@ __global__ __launch_bounds__(256) void k_upload(uint4* dst, const uint4* src, si
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) dst[i] = src[i];
 }
 
-__global__ __launch_bounds__(256) void k_expand_chunks(const uint4* range_a, const uint4* range_b, const uint32_t* first, uint32_t n_ranges, uint4* chunk) {
-    const uint32_t r = blockIdx.x * 256 + threadIdx.x;
-    if (r >= n_ranges) return;
+__device__ __forceinline__ void expand_range(const uint4* range_a, const uint4* range_b, const uint32_t* first, uint32_t r, uint4* chunk) {
     const uint4 a = range_a[r], b = range_b[r];
     const uint32_t step = (a.w & kChunkDerive) ? kDeriveChunk : (a.w & kChunkHeavy) ? kHeavyChunk : kBuildChunk;
     uint4* out = chunk + 2 * (size_t)first[r];
     for (uint32_t lo = a.y; lo < a.z; lo += step, out += 2) {
         out[0] = make_uint4(a.x, lo, min(a.z, lo + step), a.w);
         out[1] = b;
+    }
+}
+
+__global__ __launch_bounds__(256) void k_expand_chunks(const uint4* range_a, const uint4* range_b, const uint32_t* first, uint32_t n_ranges, uint4* chunk) {
+    const uint32_t r = blockIdx.x * 256 + threadIdx.x;
+    if (r < n_ranges) expand_range(range_a, range_b, first, r, chunk);
+}
+
+// Everything a build needs before its first kernel, in one launch of three independent parts: workgroups [0, nb_up) copy
+// the plan (and tables) from pinned host memory, the next nb_zero clear the rows that the pool hands out for the first
+// time, the rest write the chunk records, reading their ranges from the pinned host copy (not from the device copy that
+// the first part is still writing).
+__global__ __launch_bounds__(256) void k_stage(uint4* dst, const uint4* src, size_t n_up, uint32_t nb_up, StageZero Z, uint32_t nb_zero,
+                                               const uint4* range_a, const uint4* range_b, const uint32_t* first, uint32_t n_ranges, uint4* chunk) {
+    if (blockIdx.x < nb_up) {
+        for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n_up; i += (size_t)nb_up * 256) dst[i] = src[i];
+    } else if (blockIdx.x < nb_up + nb_zero) {
+        const size_t t = (size_t)(blockIdx.x - nb_up) * 256 + threadIdx.x, stride = (size_t)nb_zero * 256;
+        for (uint32_t k = 0; k < Z.n; ++k) {
+            uint32_t* p = Z.p[k];
+            const size_t words = Z.words[k];
+            if ((reinterpret_cast<uintptr_t>(p) & 15) == 0) {
+                uint4* p4 = reinterpret_cast<uint4*>(p);
+                for (size_t i = t; i < words / 4; i += stride) p4[i] = make_uint4(0, 0, 0, 0);
+                for (size_t i = (words & ~(size_t)3) + t; i < words; i += stride) p[i] = 0u;
+            } else {
+                for (size_t i = t; i < words; i += stride) p[i] = 0u;
+            }
+        }
+    } else {
+        const uint32_t r = (blockIdx.x - nb_up - nb_zero) * 256 + threadIdx.x;
+        if (r < n_ranges) expand_range(range_a, range_b, first, r, chunk);
     }
 }
 
@@ -541,7 +573,8 @@ __global__ __launch_bounds__(256) void k_copy_structure(const CopyJob* jobs, uin
 }
 
 // Per plane: set bits of the accepted and of the uncertain row, and the plane's list of uncertain tokens behind its
-// three rows: word 0 = how many (kUncListDense if they do not fit), then their token ids in no particular order.
+// three rows: word 0 = how many (the list holds them if that is at most kUncListWords - 1), then their token ids in no
+// particular order.
 __global__ __launch_bounds__(256) void k_plane_summary(uint32_t* const* plane_ptr, uint32_t n_pos, uint32_t W, uint32_t* counts) {
     __shared__ uint32_t part[2][4];
     __shared__ uint32_t n_list;
@@ -568,7 +601,77 @@ __global__ __launch_bounds__(256) void k_plane_summary(uint32_t* const* plane_pt
     if (threadIdx.x == 0) {
         counts[2 * p] = part[0][0] + part[0][1] + part[0][2] + part[0][3];
         counts[2 * p + 1] = part[1][0] + part[1][1] + part[1][2] + part[1][3];
-        list[0] = n_list <= kUncListWords - 1 ? n_list : kUncListDense;
+        list[0] = n_list;
+    }
+}
+
+// The copies of the derived planes and the summary in one pass: a plane's words are read once, completed from the
+// planes it takes bits from, written back where they changed, and counted and listed from the registers.  A workgroup
+// takes FINISH_WORDS words of one plane; the plane's counts and the length of its list are summed with one device atomic
+// per workgroup each (they start at zero: the counts arrive as zeros with the plan, the list with the cleared row).
+constexpr uint32_t FINISH_ITER = 4, FINISH_WORDS = 256 * FINISH_ITER;
+__global__ __launch_bounds__(256) void k_finish_planes(uint32_t* const* plane_ptr, const FinishJob* jobs, uint32_t n_pos, const uint8_t* first_byte,
+                                                       uint32_t W, uint32_t* counts) {
+    __shared__ uint32_t part[2][4];
+    __shared__ uint32_t n_list, list_base;
+    __shared__ uint32_t bytes[8];
+    const uint32_t p = blockIdx.y;
+    uint32_t* row = plane_ptr[p];
+    uint32_t* list = row + 3 * (size_t)W;
+    const FinishJob* job = jobs + p;
+    const uint32_t* m_src = job->m_src;
+    const uint32_t* m_mask = job->m_mask;
+    const uint32_t* f_src = job->f_src;
+    if (threadIdx.x == 0) n_list = 0;
+    if (threadIdx.x < 8) bytes[threadIdx.x] = job->f_bytes[threadIdx.x];
+    __syncthreads();
+    uint32_t na = 0, nu = 0, cand[FINISH_ITER], at[FINISH_ITER];
+#pragma unroll
+    for (uint32_t it = 0; it < FINISH_ITER; ++it) {
+        const uint32_t w = blockIdx.x * FINISH_WORDS + it * 256 + threadIdx.x;
+        cand[it] = 0; at[it] = 0;
+        if (w >= W) continue;
+        const uint32_t a0 = row[w], u0 = row[W + w], e0 = row[2 * W + w];
+        uint32_t a = a0, u = u0, e = e0;
+        if (m_src) {
+            const uint32_t m = m_mask[w];
+            if (m) { a |= m_src[w] & m; u |= m_src[W + w] & m; e |= m_src[2 * W + w] & m; }
+        }
+        if (f_src) {
+            const uint32_t sa = f_src[w], su = f_src[W + w], se = f_src[2 * W + w];
+            uint32_t todo = sa | su | se, m = 0;                    // only the tokens the source has a bit for matter
+            while (todo) {
+                const uint32_t bit = __ffs(todo) - 1;
+                todo &= todo - 1;
+                const uint32_t b = first_byte[w * 32 + bit];
+                m |= ((bytes[b >> 5] >> (b & 31)) & 1u) << bit;
+            }
+            a |= sa & m; u |= su & m; e |= se & m;
+        }
+        if (a != a0) row[w] = a;
+        if (u != u0) row[W + w] = u;
+        if (e != e0) row[2 * W + w] = e;
+        na += __popc(a); nu += __popc(u);
+        cand[it] = u & ~a;
+        if (cand[it]) at[it] = atomicAdd(&n_list, (uint32_t)__popc(cand[it]));
+    }
+    for (int s = 32; s > 0; s >>= 1) { na += __shfl_down(na, s); nu += __shfl_down(nu, s); }
+    if ((threadIdx.x & 63) == 0) { part[0][threadIdx.x >> 6] = na; part[1][threadIdx.x >> 6] = nu; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const uint32_t ta = part[0][0] + part[0][1] + part[0][2] + part[0][3], tu = part[1][0] + part[1][1] + part[1][2] + part[1][3];
+        if (ta) atomicAdd(counts + 2 * p, ta);
+        if (tu) atomicAdd(counts + 2 * p + 1, tu);
+        list_base = n_list ? atomicAdd(list, n_list) : 0u;           // word 0 of the list: how many uncertain tokens the plane has
+    }
+    __syncthreads();
+    if (n_list == 0) return;
+#pragma unroll
+    for (uint32_t it = 0; it < FINISH_ITER; ++it) {
+        const uint32_t w = blockIdx.x * FINISH_WORDS + it * 256 + threadIdx.x;
+        uint32_t k = list_base + at[it];
+        for (uint32_t c = cand[it]; c; c &= c - 1, ++k)
+            if (k < kUncListWords - 1) list[1 + k] = w * 32 + (uint32_t)__ffs(c) - 1;
     }
 }
 
@@ -674,10 +777,11 @@ __global__ __launch_bounds__(FILL_THREADS) void k_fill(FillBatch F, DevVocab Vd,
         addr = F.front_planes[front_off + lane];
         if (!(addr & 1)) n_unc = tab(reinterpret_cast<const uint32_t*>(addr) + 3 * (size_t)Vd.W);
     }
-    uint32_t incl = n_unc == kUncListDense ? 0u : n_unc;
+    const bool no_list = n_unc > kUncListWords - 1;                   // more uncertain tokens than the plane's list holds
+    uint32_t incl = no_list ? 0u : n_unc;
     for (int d = 1; d < 64; d <<= 1) { const uint32_t up = (uint32_t)__shfl_up((int)incl, d); if ((int)lane >= d) incl += up; }
     const uint32_t total = (uint32_t)__shfl((int)incl, 63);
-    const bool listed_way = live && front_n != 0 && (front_n > 64 || __any(n_unc == kUncListDense) || total > FILL_SPARSE_CAP);
+    const bool listed_way = live && front_n != 0 && (front_n > 64 || __any(no_list) || total > FILL_SPARSE_CAP);
     uint32_t* out = reinterpret_cast<uint32_t*>(bitmask) + (long long)b * row_stride;
     FillStore st;
     const uint32_t col = (wave - FILL_OR_WAVES) * FILL_RECHECK_LANES + lane;      // re-check team: this lane's place among the lanes at work
@@ -1090,6 +1194,19 @@ void launch_expand_chunks(const uint4* range_a_dev, const uint4* range_b_dev, co
     hipLaunchKernelGGL(k_expand_chunks, dim3((n_ranges + 255) / 256), dim3(256), 0, stream, range_a_dev, range_b_dev, first_dev, n_ranges, chunk_dev);
 }
 
+void launch_stage(void* dst_dev, const void* src_host_mapped, size_t bytes, const StageZero& Z, const uint4* range_a_host_mapped,
+                  const uint4* range_b_host_mapped, const uint32_t* first_host_mapped, uint32_t n_ranges, uint4* chunk_dev, hipStream_t stream) {
+    const size_t n = bytes / sizeof(uint4);
+    const uint32_t nb_up = (uint32_t)std::min<size_t>((n + 255) / 256, 2048);
+    size_t zero_words = 0;
+    for (uint32_t k = 0; k < Z.n; ++k) zero_words += Z.words[k];
+    const uint32_t nb_zero = (uint32_t)std::min<size_t>((zero_words / 4 + 255) / 256, 2048);
+    const uint32_t nb_exp = (n_ranges + 255) / 256;
+    if (nb_up + nb_zero + nb_exp == 0) return;
+    hipLaunchKernelGGL(k_stage, dim3(nb_up + nb_zero + nb_exp), dim3(256), 0, stream, static_cast<uint4*>(dst_dev), static_cast<const uint4*>(src_host_mapped), n,
+                       nb_up, Z, nb_zero, range_a_host_mapped, range_b_host_mapped, first_host_mapped, n_ranges, chunk_dev);
+}
+
 void launch_build(const DevTables& T, const DevVocab& Vd, BuildPlan P, const SlowScratch& S, hipStream_t stream) {
     if (P.n_chunks == 0) return;
     // Short item lists let a compute unit hold more workgroups, which is what hides the latency of the automaton
@@ -1167,6 +1284,15 @@ void launch_copy_first_byte(const FirstByteCopyJob* jobs_dev, uint32_t n_jobs, c
 void launch_plane_summary(uint32_t* const* plane_ptr_dev, uint32_t n_pos, uint32_t W, uint32_t* counts_dev, hipStream_t stream) {
     if (n_pos == 0) return;
     hipLaunchKernelGGL(k_plane_summary, dim3(n_pos), dim3(256), 0, stream, plane_ptr_dev, n_pos, W, counts_dev);
+}
+
+void launch_finish_planes(uint32_t* const* plane_ptr_dev, const FinishJob* jobs_dev, uint32_t n_pos, const uint8_t* first_byte_dev, uint32_t W,
+                          uint32_t* counts_dev, hipStream_t stream) {
+    for (uint32_t first = 0; first < n_pos; first += 65535) {       // grid.y limit
+        const uint32_t n = std::min<uint32_t>(65535, n_pos - first);
+        hipLaunchKernelGGL(k_finish_planes, dim3((W + FINISH_WORDS - 1) / FINISH_WORDS, n), dim3(256), 0, stream, plane_ptr_dev + first, jobs_dev + first, n,
+                           first_byte_dev, W, counts_dev + 2 * (size_t)first);
+    }
 }
 
 void launch_fill(const FillBatch& F, const DevVocab& Vd, int32_t* bitmask_dev, int64_t row_stride_words,
