@@ -246,6 +246,11 @@ int32_t xg2_fill_last_status(int32_t* large_capacity_tokens, int32_t* overflowed
 int32_t xg2_fill_resolve_overflow(xg2_matcher* const* matchers, int32_t B, int32_t* bitmask_dev, int64_t row_stride_words,
                                   int32_t* n_decided);
 
+/* Test aid: on = 0 makes the builds that follow use one launch per step (clearing of rows, upload, chunk records; copy
+ * kernels of derived planes, per-plane summary) also where the library would otherwise do them in one launch each; on = 1
+ * (the default) restores that.  The planes are the same either way.                                                    */
+int32_t xg2_debug_set_build_fusion(int32_t on);
+
 /* Test aid: lowers the capacities of the large-capacity item lists (256 items, 1024 wait entries; 0 = back to these) for
  * the build and fill calls that follow, so that the handling of their overflow can be exercised with small grammars.   */
 int32_t xg2_debug_set_large_capacity(int32_t items, int32_t wait_entries);

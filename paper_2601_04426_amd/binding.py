@@ -25,7 +25,7 @@ EXPORTS = [
     "xg2_compile_grammar", "xg2_mask_cache_destroy", "xg2_mask_cache_stats", "xg2_mask_cache_num_positions", "xg2_mask_cache_num_planes", "xg2_mask_cache_jit_stats",
     "xg2_mask_cache_plane_info", "xg2_mask_cache_find_plane", "xg2_mask_cache_get_planes", "xg2_matcher_create", "xg2_matcher_create_host", "xg2_matcher_destroy",
     "xg2_matcher_accept_token", "xg2_matcher_accept_tokens", "xg2_matcher_reset", "xg2_matcher_is_terminated", "xg2_matcher_frontier",
-    "xg2_fill_next_token_bitmask", "xg2_fill_next_token_bitmask_noalloc", "xg2_fill_resolve_overflow", "xg2_debug_set_large_capacity",
+    "xg2_fill_next_token_bitmask", "xg2_fill_next_token_bitmask_noalloc", "xg2_fill_resolve_overflow", "xg2_debug_set_large_capacity", "xg2_debug_set_build_fusion",
     "xg2_fill_last_device_us", "xg2_fill_last_status", "xg2_fill_last_recheck_tokens",
     "xg2_apply_token_bitmask", "xg2_batch_create", "xg2_batch_destroy", "xg2_batch_assign", "xg2_batch_accept_tokens",
     "xg2_batch_fill_next_token_bitmask", "xg2_batch_row_info",
@@ -100,6 +100,7 @@ def _load() -> ctypes.CDLL:
     L.xg2_fill_next_token_bitmask_noalloc.argtypes = [vp, i32, vp, i64, vp]
     L.xg2_fill_resolve_overflow.argtypes = [vp, i32, vp, i64, ctypes.POINTER(i32)]
     L.xg2_debug_set_large_capacity.argtypes = [i32, i32]
+    L.xg2_debug_set_build_fusion.argtypes = [i32]
     L.xg2_fill_last_device_us.argtypes = [ctypes.POINTER(ctypes.c_float)]
     L.xg2_fill_last_status.argtypes = [ctypes.POINTER(i32), ctypes.POINTER(i32)]
     L.xg2_fill_last_recheck_tokens.argtypes = [vp, i32, ctypes.POINTER(i32)]
@@ -374,6 +375,10 @@ def fill_resolve_overflow(matchers, bitmask_ptr: int, row_stride_words: int) -> 
     n = ctypes.c_int32(0)
     _check(lib.xg2_fill_resolve_overflow(arr, len(matchers), ctypes.c_void_p(bitmask_ptr), row_stride_words, ctypes.byref(n)))
     return n.value
+
+
+def debug_set_build_fusion(on: bool = True) -> None:
+    _check(lib.xg2_debug_set_build_fusion(1 if on else 0))
 
 
 def debug_set_large_capacity(items: int = 0, wait_entries: int = 0) -> None:

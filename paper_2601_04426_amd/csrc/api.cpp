@@ -108,6 +108,8 @@ struct StagingPool {
     void release(StagingSet* s) { std::lock_guard<std::mutex> lk(mu); s->in_use = false; }
 };
 StagingPool& staging_pool() { static StagingPool* s = new StagingPool(); return *s; }
+// test aid: off = a build uses one launch per step (clear, upload, chunk records; copy kernels, summary) even where one would do
+std::atomic<bool>& build_fusion() { static std::atomic<bool> on{true}; return on; }
 
 struct Packer {
     struct Seg { const void* src; size_t bytes, off; };
@@ -975,7 +977,7 @@ int32_t build_planes(CacheImpl& cache, const std::vector<int32_t>& todo, hipStre
     // a plane that itself takes bits in this build (the separate kernels order such chains: masked copies, then
     // first-byte copies, then the summary).
     std::vector<FinishJob> finish(build_rows.size(), FinishJob{});
-    bool finish_in_one = !build_rows.empty();
+    bool finish_in_one = !build_rows.empty() && build_fusion().load();
     {
         std::map<const uint32_t*, size_t> at;
         for (size_t k = 0; k < build_rows.size(); ++k) at.emplace(build_rows[k], k);
@@ -1049,7 +1051,7 @@ int32_t build_planes(CacheImpl& cache, const std::vector<int32_t>& todo, hipStre
     // records are written: one launch when the upload is small enough for a copy kernel and the pool has few ranges to
     // clear (a fresh slab, a few recycled rows), else one call each.
     bool staged = false;
-    if (tab.total <= kUploadByKernelMax && pool.to_zero.size() <= kStageZeroRanges) {
+    if (build_fusion().load() && tab.total <= kUploadByKernelMax && pool.to_zero.size() <= kStageZeroRanges) {
         StageZero Z{};
         bool ok = true;
         for (auto& z : pool.to_zero) {
@@ -2160,6 +2162,11 @@ int32_t xg2_fill_resolve_overflow(xg2_matcher* const* matchers, int32_t B, int32
         if (n_decided) *n_decided = n;
         return XG2_OK;
     });
+}
+
+int32_t xg2_debug_set_build_fusion(int32_t on) {
+    build_fusion().store(on != 0);
+    return XG2_OK;
 }
 
 int32_t xg2_debug_set_large_capacity(int32_t items, int32_t wait_entries) {

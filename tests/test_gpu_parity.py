@@ -190,6 +190,21 @@ def test_config3_tagdispatch_planes_and_decode(xg):
     assert any(0 < c <= 64 for c in cand), (min(cand), max(cand))
 
 
+@pytest.mark.parametrize("index", [1, 5])
+def test_planes_are_the_same_with_one_launch_per_build_step(xg, index):
+    """The build's fused launches (staging; copies of derived planes + summary) switched off: separate clear, upload,
+    chunk records, copy kernels and summary give the same planes (every plane against the oracle) and the same masks."""
+    cfg, vocab, va = load(index)
+    ebnf, root = cfg.grammars[0]
+    try:
+        xg.debug_set_build_fusion(False)
+        cache, orc = check_planes(xg, cfg, vocab, va, ebnf, root, max_contexts=300)
+        n = run_decode(xg, cfg, vocab, va, cache, orc, batch=8, steps=12, seed=5 + index, check_every=3)
+        assert n >= 30
+    finally:
+        xg.debug_set_build_fusion(True)
+
+
 def test_config5_depth1_unmerged_planes(xg):
     """One plane per position, nothing merged: the plain cache on the largest vocabulary, all 1,547 positions."""
     cfg, vocab, va = load(5)
