@@ -631,8 +631,8 @@ __global__ __launch_bounds__(256) void k_finish_planes(uint32_t* const* plane_pt
         const uint32_t w = blockIdx.x * FINISH_WORDS + it * 256 + threadIdx.x;
         cand[it] = 0; at[it] = 0;
         if (w >= W) continue;
-        const uint32_t a0 = row[w], u0 = row[W + w], e0 = row[2 * W + w];
-        uint32_t a = a0, u = u0, e = e0;
+        const uint32_t a0 = row[w], u0 = row[W + w];
+        uint32_t a = a0, u = u0, e = 0;                             // e: bits to add to the third row (it is not read for a plane that takes none)
         if (m_src) {
             const uint32_t m = m_mask[w];
             if (m) { a |= m_src[w] & m; u |= m_src[W + w] & m; e |= m_src[2 * W + w] & m; }
@@ -650,7 +650,7 @@ __global__ __launch_bounds__(256) void k_finish_planes(uint32_t* const* plane_pt
         }
         if (a != a0) row[w] = a;
         if (u != u0) row[W + w] = u;
-        if (e != e0) row[2 * W + w] = e;
+        if (e) { const uint32_t e0 = row[2 * W + w]; if (e & ~e0) row[2 * W + w] = e0 | e; }
         na += __popc(a); nu += __popc(u);
         cand[it] = u & ~a;
         if (cand[it]) at[it] = atomicAdd(&n_list, (uint32_t)__popc(cand[it]));
