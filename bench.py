@@ -33,13 +33,13 @@ HBM_PEAK_GBS = 8000.0
 # with.  The same counters read 303,890 (FETCH_SIZE) and 607,744 (WRITE_SIZE) for a device-to-device copy of 607,744 KiB,
 # hence the scale factors to KiB.  The summaries under profiles/ hold the commands and the full tables.
 PMC = {
-    "sources_sha256": "30fd1bacf9bce454ca05204ff283ca9b9344f43d07154bf852ed57d8957c2a2c",
+    "sources_sha256": "d63278a90bf7d4f70d6f120e6546cdbf90caf1643370c70e99ff645930181717",
     "fetch_scale": 2.00, "write_scale": 1.00,
-    "k_build": (11027.4, 4800.5),
-    "k_fill": (3316.3, 19191.9),
-    "k_apply_vec<8>": (97591.0, 303872.0),
-    "k_apply_vec<4>": (180438.4, 605533.3),
-    "k_build_tagdispatch": (144635.8, 689897.5),
+    "k_build": (11027.0, 4800.5),
+    "k_fill": (3315.7, 19190.7),
+    "k_apply_vec<8>": (97590.6, 303872.0),
+    "k_apply_vec<4>": (180437.3, 605533.3),
+    "k_build_tagdispatch": (144996.9, 689897.5),
     # wave instructions of one k_build launch (rocprofv3 --pmc SQ_INSTS_VALU; SQ_INSTS_SALU + SQ_INSTS_SMEM + SQ_INSTS_BRANCH)
     "k_build_valu_instructions": 12826031.0, "k_build_scalar_and_branch_instructions": 17314808.0,
     "k_build_tagdispatch_valu_instructions": 842330509.0, "k_build_tagdispatch_scalar_and_branch_instructions": 1117415809.0,
