@@ -112,22 +112,26 @@ struct GlobalStore {
 #define XG2_BUILD_K_SMALL 3
 #define XG2_BUILD_WM_SMALL 4
 #endif
+#ifndef XG2_BUILD_LEVELS
+#define XG2_BUILD_LEVELS 3
+#endif
+constexpr int BUILD_LEVELS = XG2_BUILD_LEVELS;        // 64, 32, 16, ... lanes at work with 1, 2, 4, ... times the capacity
 constexpr int BUILD_K_SMALL = XG2_BUILD_K_SMALL, BUILD_WM_SMALL = XG2_BUILD_WM_SMALL, BUILD_K_LARGE = 6, BUILD_WM_LARGE = 10;
 
 // The build kernel's item lists: the LDS layout above with capacities chosen at run time.  The lists are kept short
 // because their size bounds how many workgroups a compute unit holds, and the kernel lives on hiding the latency of
 // dependent table loads behind other wavefronts.  A token that outgrows them is run again with only the lower 32 lanes
 // at work, each with two lanes' worth of the same memory (word (slot, lane) at slot * 32 + lane): twice the capacity,
-// no more LDS.
+// no more LDS; one that outgrows those too, once more with 16 lanes and four times the capacity (BUILD_LEVELS).
 struct BuildStore {
     static constexpr int MAXLEN = 16;
     int K, WM, sh;                                  // capacities; log2 of the distance between a lane's consecutive slots
     uint32_t* cur; uint32_t* nxt; uint32_t* wait;
     unsigned long long ws_lo = 0, ws_hi = 0;        // wait-list length at the start of each new set, 8 bits each
-    // lds: the workgroup's (2 k + 2 wm) * 64 words for lists of k items and wm wait entries a lane; wide: lanes 0..31 only,
-    // double capacity
-    __device__ void init(uint32_t* lds, uint32_t lane, int k, int wm, bool wide) {
-        K = wide ? 2 * k : k; WM = wide ? 2 * wm : wm; sh = wide ? 5 : 6;
+    // lds: the workgroup's (2 k + 2 wm) * 64 words for lists of k items and wm wait entries a lane; level l: lanes
+    // 0 .. (64 >> l) - 1 only, 2^l times the capacity
+    __device__ void init(uint32_t* lds, uint32_t lane, int k, int wm, int level) {
+        K = k << level; WM = wm << level; sh = 6 - level;
         cur = lds + lane; nxt = lds + k * 64 + lane; wait = lds + 2 * k * 64 + lane;
     }
     __device__ uint32_t get_cur(int k) const { return cur[k << sh]; }
@@ -196,39 +200,44 @@ __device__ __forceinline__ void store_left_early(uint32_t* row, uint32_t W, uint
 __device__ __forceinline__ void follow_batch(const DevTables& T, const DevVocab& Vd, const BuildPlan& P, const SlowScratch& S,
                                           const uint32_t* cls_words, uint32_t* lds, uint32_t* f_plane, uint32_t* f_rank,
                                           uint32_t first, uint32_t count, uint32_t lane) {
-    // round 0: the batch, one token a lane; later rounds: the tokens that outgrew the lists, 32 at a time with twice the
-    // room (their entries have moved to the front of the batch's part of the queue, which has been read)
-    uint32_t n_over = 0;
-    for (uint32_t round = 0;; ++round) {
-        const bool wide = round > 0;
-        const uint32_t off = wide ? (round - 1) * 32 : 0, cnt = wide ? n_over : count;
-        if (off >= cnt) break;
-        BuildStore st;
-        st.init(lds, lane, (int)P.list_k, (int)P.list_wm, wide);
-        bool over = false;
-        uint32_t p = 0, rank = 0;
-        if (lane < (wide ? 32u : 64u) && off + lane < cnt) {
-            p = f_plane[first + off + lane]; rank = f_rank[first + off + lane];
-            const DevCtx C = position_ctx(P, p);
-            const int n = (int)(Vd.off[rank + 1] - Vd.off[rank]);
-            RegBytes tok;
-            tok.v = Vd.tok16[rank];
-            const int res = scan_token<BuildStore, true>(T, cls_words, C, tok, n, st);
-            over = res & RES_OVERFLOW;
-            if (over && wide) push_overflow(S, p, rank);            // the large-capacity kernel takes it
-            else if (res & RES_ALIVE) store_class(P, p, Vd.W, Vd.perm[rank], RES_EARLY);   // some context can take the rest: uncertain
-        }
-        if (!wide) {
-            const unsigned long long mo = __ballot(over);
-            n_over = (uint32_t)__popcll(mo);
-            if (!mo) break;
-            __syncthreads();
-            if (over) {
-                const uint32_t at = first + (uint32_t)__popcll(mo & ((1ull << lane) - 1));
-                f_plane[at] = p; f_rank[at] = rank;
+    // level 0: the batch, one token a lane; further levels: the tokens that outgrew the lists of the level before, half as
+    // many at a time with twice the room (their entries have moved to the front of the batch's part of the queue, which
+    // has been read)
+    uint32_t cnt = count;
+    for (int level = 0; level < BUILD_LEVELS && cnt; ++level) {
+        const uint32_t lanes = 64u >> level;
+        const bool last = level == BUILD_LEVELS - 1;
+        uint32_t n_next = 0;
+        for (uint32_t off = 0; off < cnt; off += lanes) {
+            BuildStore st;
+            st.init(lds, lane, (int)P.list_k, (int)P.list_wm, level);
+            bool over = false;
+            uint32_t p = 0, rank = 0;
+            if (lane < lanes && off + lane < cnt) {
+                p = f_plane[first + off + lane]; rank = f_rank[first + off + lane];
+                const DevCtx C = position_ctx(P, p);
+                const int n = (int)(Vd.off[rank + 1] - Vd.off[rank]);
+                RegBytes tok;
+                tok.v = Vd.tok16[rank];
+                const int res = scan_token<BuildStore, true>(T, cls_words, C, tok, n, st);
+                over = res & RES_OVERFLOW;
+                if (over && last) push_overflow(S, p, rank);        // the large-capacity kernel takes it
+                else if (res & RES_ALIVE) store_class(P, p, Vd.W, Vd.perm[rank], RES_EARLY);   // some context can take the rest: uncertain
             }
-            __syncthreads();
+            if (!last) {
+                const unsigned long long mo = __ballot(over);
+                if (mo) {
+                    __syncthreads();
+                    if (over) {
+                        const uint32_t at = first + n_next + (uint32_t)__popcll(mo & ((1ull << lane) - 1));
+                        f_plane[at] = p; f_rank[at] = rank;
+                    }
+                    __syncthreads();
+                    n_next += (uint32_t)__popcll(mo);
+                }
+            }
         }
+        cnt = n_next;
     }
 }
 
@@ -392,48 +401,52 @@ __global__ __launch_bounds__(64) XG2_BUILD_ATTR void k_build(DevTables T, DevVoc
         if (n_work == 0) continue;
         const DevCtx C = position_ctx(P, p);                        // only the recogniser needs the whole start set
         for (uint32_t base = 0; base < n_work; base += 64) {
-            // round 0: 64 tokens of the list, one a lane; later rounds: those of them that outgrew the item lists, 32 at a
-            // time with half the lanes and twice the room (their ranks go through the part of the deferred list that
-            // this batch has read)
-            uint32_t n_over = 0;
-            for (uint32_t round = 0;; ++round) {
-                const bool wide = round > 0;
-                const uint32_t off = wide ? (round - 1) * 32 : 0, cnt = wide ? n_over : min(64u, n_work - base);
-                if (off >= cnt) break;
-                BuildStore st;
-                st.init(lds, lane, (int)P.list_k, (int)P.list_wm, wide);
-                bool again = false, over = false;
-                uint32_t rank = 0, at = 0;                           // the token: sorted rank, and offset in the chunk
-                if (lane < (wide ? 32u : 64u) && off + lane < cnt) {
-                    const uint32_t idx = base + off + lane;
-                    at = (wide || walkable || threaded) ? deferred[idx] : idx;
-                    rank = listed ? Vd.long_rank[chunk.y + at] : chunk.y + at;
-                    const int n = (int)(Vd.off[rank + 1] - Vd.off[rank]);
-                    RegBytes tok;
-                    tok.v = Vd.tok16[rank];
-                    const int res = scan_token(T, cls_words, C, tok, n, st);
-                    over = res & RES_OVERFLOW;
-                    if (over && wide) push_overflow(S, p, rank);     // the large-capacity kernel takes it
-                    else if (!over) {
-                        // leaves the rule early and dies: it stays uncertain only if some context can take the rest of the token
-                        const bool left_early = !(res & RES_ALIVE) && (res & RES_EARLY);
-                        again = P.follow_filter && left_early;
-                        if (left_early || !again) {
-                            const uint32_t id = Vd.perm[rank];
-                            if (left_early) store_left_early(row, Vd.W, id);
-                            if (!again) store_class(row, Vd.W, id, res);
+            // level 0: 64 tokens of the list, one a lane; further levels: those of them that outgrew the item lists of the
+            // level before, half as many at a time with twice the room (their offsets go through the part of the deferred
+            // list that this batch has read)
+            uint32_t cnt = min(64u, n_work - base);
+            for (int level = 0; level < BUILD_LEVELS && cnt; ++level) {
+                const uint32_t lanes = 64u >> level;
+                const bool last = level == BUILD_LEVELS - 1;
+                uint32_t n_next = 0;
+                for (uint32_t off = 0; off < cnt; off += lanes) {
+                    BuildStore st;
+                    st.init(lds, lane, (int)P.list_k, (int)P.list_wm, level);
+                    bool again = false, over = false;
+                    uint32_t rank = 0, at = 0;                       // the token: sorted rank, and offset in the chunk
+                    if (lane < lanes && off + lane < cnt) {
+                        const uint32_t idx = base + off + lane;
+                        at = (level > 0 || walkable || threaded) ? deferred[idx] : idx;
+                        rank = listed ? Vd.long_rank[chunk.y + at] : chunk.y + at;
+                        const int n = (int)(Vd.off[rank + 1] - Vd.off[rank]);
+                        RegBytes tok;
+                        tok.v = Vd.tok16[rank];
+                        const int res = scan_token(T, cls_words, C, tok, n, st);
+                        over = res & RES_OVERFLOW;
+                        if (over && last) push_overflow(S, p, rank); // the large-capacity kernel takes it
+                        else if (!over) {
+                            // leaves the rule early and dies: it stays uncertain only if some context can take the rest of the token
+                            const bool left_early = !(res & RES_ALIVE) && (res & RES_EARLY);
+                            again = P.follow_filter && left_early;
+                            if (left_early || !again) {
+                                const uint32_t id = Vd.perm[rank];
+                                if (left_early) store_left_early(row, Vd.W, id);
+                                if (!again) store_class(row, Vd.W, id, res);
+                            }
+                        }
+                    }
+                    queue_follow(again, rank);
+                    if (!last) {
+                        const unsigned long long mo = __ballot(over);
+                        if (mo) {
+                            __syncthreads();
+                            if (over) deferred[base + n_next + (uint32_t)__popcll(mo & ((1ull << lane) - 1))] = (uint8_t)at;
+                            __syncthreads();
+                            n_next += (uint32_t)__popcll(mo);
                         }
                     }
                 }
-                queue_follow(again, rank);
-                if (!wide) {
-                    const unsigned long long mo = __ballot(over);
-                    n_over = (uint32_t)__popcll(mo);
-                    if (!mo) break;
-                    __syncthreads();
-                    if (over) deferred[base + (uint32_t)__popcll(mo & ((1ull << lane) - 1))] = (uint8_t)at;
-                    __syncthreads();
-                }
+                cnt = n_next;
             }
         }
     }
