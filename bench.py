@@ -33,16 +33,16 @@ HBM_PEAK_GBS = 8000.0
 # with.  The same counters read 303,890 (FETCH_SIZE) and 607,744 (WRITE_SIZE) for a device-to-device copy of 607,744 KiB,
 # hence the scale factors to KiB.  The summaries under profiles/ hold the commands and the full tables.
 PMC = {
-    "sources_sha256": "d63278a90bf7d4f70d6f120e6546cdbf90caf1643370c70e99ff645930181717",
+    "sources_sha256": "236e9418d43ccc896bf41a1fa618f043c5f6b0f15c010edf8f2233fc1ca770e9",
     "fetch_scale": 2.00, "write_scale": 1.00,
-    "k_build": (11027.0, 4800.5),
-    "k_fill": (3315.7, 19190.7),
-    "k_apply_vec<8>": (97590.6, 303872.0),
-    "k_apply_vec<4>": (180437.3, 605533.3),
-    "k_build_tagdispatch": (144996.9, 689897.5),
+    "k_build": (11030.4, 4800.5),
+    "k_fill": (3308.2, 19191.9),
+    "k_apply_vec<8>": (97590.3, 303872.0),
+    "k_apply_vec<4>": (180438.0, 605533.3),
+    "k_build_tagdispatch": (144657.9, 689897.5),
     # wave instructions of one k_build launch (rocprofv3 --pmc SQ_INSTS_VALU; SQ_INSTS_SALU + SQ_INSTS_SMEM + SQ_INSTS_BRANCH)
-    "k_build_valu_instructions": 12826031.0, "k_build_scalar_and_branch_instructions": 17314808.0,
-    "k_build_tagdispatch_valu_instructions": 842330509.0, "k_build_tagdispatch_scalar_and_branch_instructions": 1117415809.0,
+    "k_build_valu_instructions": 12898560.0, "k_build_scalar_and_branch_instructions": 17288610.0,
+    "k_build_tagdispatch_valu_instructions": 848041696.0, "k_build_tagdispatch_scalar_and_branch_instructions": 1115408341.0,
 }
 KERNEL_SOURCES = ("csrc/kernels.hip", "csrc/earley_core.hpp", "csrc/device.hpp", "build.py")   # code and compiler flags
 
